@@ -1,0 +1,286 @@
+"""Pins for the value side of the CPU oracle (Algorithm 1, Eq. 2-3, Phases 1-3, decoder phases 3-4).
+
+Each pin checks the oracle against something other than itself: Python's correctly rounded
+math.fsum, exact rational arithmetic, the paper's worked example, or a stated invariant.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import ref
+from tests.streamparse import exact_code, parse
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def golden(name):
+    out = {}
+    for line in open(os.path.join(GOLDEN, name)):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            k, v = line.split("=", 1)
+            out[k.strip()] = v.strip()
+    return out
+
+
+def f32(x):
+    return np.asarray(x, dtype=np.float32)
+
+
+def bits_to_f32(b):
+    return np.asarray(b, dtype=np.uint32).view(np.float32)
+
+
+# ----------------------------------------------------------------------------- abs-sum
+def wide_values(rng, n):
+    """float32 values whose exponents span the whole finite range, denormals and zeros included."""
+    e = rng.integers(0, 255, n).astype(np.uint32)
+    m = rng.integers(0, 1 << 23, n).astype(np.uint32)
+    s = rng.integers(0, 2, n).astype(np.uint32)
+    return ((s << 31) | (e << 23) | m).view(np.float32)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_abs_sum_equals_fsum_wide_exponents(seed):
+    rng = np.random.default_rng(seed)
+    v = wide_values(rng, 5000)
+    bad, s = ref.abs_sum(v)
+    assert not bad
+    assert s == math.fsum(abs(float(x)) for x in v)
+
+
+@pytest.mark.parametrize("lo,hi", [(0, 40), (100, 140), (230, 254), (0, 3)])
+def test_abs_sum_equals_fsum_narrow_windows(lo, hi):
+    rng = np.random.default_rng(lo)
+    n = 20000
+    e = rng.integers(lo, hi + 1, n).astype(np.uint32)
+    m = rng.integers(0, 1 << 23, n).astype(np.uint32)
+    v = ((e << 23) | m).view(np.float32)
+    bad, s = ref.abs_sum(v)
+    assert not bad and s == math.fsum(float(x) for x in v)
+
+
+def test_abs_sum_rounds_ties_to_even_and_sticky():
+    # 2^60 + 2^7 is exactly half an ulp (ulp of 2^60 in binary64 is 2^8): tie -> even -> 2^60.
+    assert ref.abs_sum(f32([2.0 ** 60, 2.0 ** 7]))[1] == 2.0 ** 60
+    # a sticky bit below the tie pushes it up
+    assert ref.abs_sum(f32([2.0 ** 60, 2.0 ** 7, 2.0 ** -20]))[1] == 2.0 ** 60 + 2.0 ** 8
+    # odd mantissa + tie rounds up to even
+    assert ref.abs_sum(f32([2.0 ** 60, 2.0 ** 8, 2.0 ** 7]))[1] == 2.0 ** 60 + 2.0 ** 9
+    # smallest denormal alone, and with a huge partner (lost to rounding, but only once)
+    tiny = np.uint32(1).view(np.float32)
+    assert ref.abs_sum(f32([tiny]))[1] == 2.0 ** -149
+    assert ref.abs_sum(f32([3.0e38, tiny]))[1] == float(np.float32(3.0e38))
+
+
+def test_abs_sum_order_independent_and_signs():
+    rng = np.random.default_rng(7)
+    v = wide_values(rng, 3000)
+    s0 = ref.abs_sum(v)[1]
+    for k in range(5):
+        assert ref.abs_sum(rng.permutation(v))[1] == s0
+    assert ref.abs_sum(-v)[1] == s0
+    assert ref.abs_sum(np.zeros(0, np.float32)) == (False, 0.0)
+    assert ref.abs_sum(f32([0.0, -0.0]))[1] == 0.0
+
+
+def test_abs_sum_many_equal_values_carry_chain():
+    # 2^20 copies of the largest finite float: exercises long carries; exact answer known.
+    big = np.float32(3.4028234663852886e38)
+    v = np.full(1 << 20, big, np.float32)
+    assert ref.abs_sum(v)[1] == float(big) * 2.0 ** 20
+
+
+@pytest.mark.parametrize("badval", [np.nan, np.inf, -np.inf])
+def test_abs_sum_flags_nonfinite(badval):
+    v = f32([1.0, 2.0, badval, 3.0])
+    assert ref.abs_sum(v)[0] is True
+    rc, st = ref.compress(np.arange(4), v, ref.params())
+    assert rc == ref.ERR_NONFINITE and st.size == 0
+
+
+# ----------------------------------------------------------------------------- tables
+@pytest.mark.parametrize("S,b,tau", [(100.25, 1.1, 128), (3.7e-4, 1.0371, 128), (1e30, 2.0, 128),
+                                     (2.0 ** -140, 1.5, 128), (12345.678, 16.0, 128), (1.0, 1.000001, 64),
+                                     (1e40, 1.5, 128)])
+def test_tables_against_exact_rationals(S, b, tau):
+    B, V = ref.tables(S, b, tau)
+    Sf, bf = Fraction(S), Fraction(b)
+    FLT_MAX = Fraction(float(np.finfo(np.float32).max))
+    for c in range(1, tau + 1):
+        t = Sf / bf ** c                       # the real-number boundary sum / b^c
+        Bc, Vc = bits_to_f32(B[c]), bits_to_f32(V[c])
+        if t > FLT_MAX * 2:
+            assert np.isinf(Bc)
+            continue
+        if t < Fraction(2.0 ** -149) / 4:
+            assert B[c] in (0, 1, 2)
+            continue
+        # the float64 recipe carries at most ~c+2 roundings of 2^-53 each
+        tol = Fraction(c + 3, 2 ** 52)
+        if np.isfinite(Bc):
+            up, dn = Fraction(float(Bc)), Fraction(float(bits_to_f32(max(int(B[c]) - 1, 0))))
+            assert up >= t * (1 - tol)           # boundary rounded up ...
+            assert dn <= t * (1 + tol)           # ... and to the very next float32
+        assert int(V[c]) in (int(B[c]), int(B[c]) - 1)   # nearest is the boundary or the float below
+        assert float(Vc) <= float(Bc)
+
+
+def test_tables_monotone_and_tau_e():
+    B, V = ref.tables(100.25, 1.1, 128)
+    assert np.all(np.diff(B[1:129].astype(np.int64)) < 0)      # strictly decreasing boundaries
+    assert np.all(np.diff(V[1:129].astype(np.int64)) < 0)
+    # Algorithm 1 line 2: tau_e = sum / b^tau
+    tau_e = float(bits_to_f32(B[128]))
+    assert tau_e == pytest.approx(100.25 / 1.1 ** 128, rel=1e-6)
+
+
+# ----------------------------------------------------------------------------- codes
+def codes_of(values, p):
+    keys = np.arange(len(values), dtype=np.uint32)
+    rc, st = ref.compress(keys, f32(values), p)
+    assert rc == ref.OK
+    info = parse(st)
+    return info
+
+
+def test_fig2_worked_example():
+    g = golden("fig2_logquant.txt")
+    b, D = float(g["base"]), int(g["D"])
+    # six values whose first reciprocal value is the paper's 6.1: v1 = 1, the rest add up to 5.1
+    v = f32([1.0, 1.7, -0.9, 0.5, 1.2, 0.8])
+    assert len(v) == D
+    S = ref.abs_sum(v)[1]
+    assert S / 1.0 == pytest.approx(float(g["R_first"]), rel=1e-6)
+    info = codes_of(v, ref.params(b, 128, 2, 1024))
+    assert info["d"] == D
+    assert (info["codes"][0] & 0x7F) + 1 == int(g["L_first"])
+    # and every other code is ceil(log_2(S/|v|)) too, sign in bit 7
+    for x, byte in zip(v, info["codes"]):
+        assert (byte & 0x7F) + 1 == max(1, math.ceil(math.log2(S / abs(float(x)))))
+        assert (byte >> 7) == (1 if x < 0 else 0)
+
+
+@pytest.mark.parametrize("seed,b,tau", [(0, 1.1, 128), (1, 1.05, 128), (2, 2.0, 40), (3, 1.3, 64),
+                                        (4, 1.0371, 128), (5, 16.0, 9)])
+def test_codes_match_exact_rational_log(seed, b, tau):
+    """Brute force: L = ceil(log_b(sum/|v|)) with exact rationals; kept iff L <= tau (Phase 3)."""
+    rng = np.random.default_rng(seed)
+    n = 300
+    v = (rng.laplace(0, 1, n) * np.exp(rng.uniform(-12, 0, n))).astype(np.float32)
+    S = ref.abs_sum(v)[1]
+    assert S == math.fsum(abs(float(x)) for x in v)
+    info = codes_of(v, ref.params(b, tau, 2, 1024))
+    got = dict(zip(info["keys"], info["codes"]))
+    checked = 0
+    for j, x in enumerate(v):
+        if x == 0:
+            assert j not in got
+            continue
+        c, margin = exact_code(abs(float(x)), S, b, limit=tau + 2)
+        if c is not None and margin < 1e-9:
+            continue                      # on a boundary to within float64 round-off: recipe decides
+        if c is None or c > tau:
+            assert j not in got, (j, x, c)
+        else:
+            assert j in got, (j, x, c)
+            assert (got[j] & 0x7F) + 1 == max(c, 1)
+            assert (got[j] >> 7) == (1 if x < 0 else 0)
+            checked += 1
+    assert checked > 20
+
+
+def test_codes_nonincreasing_in_magnitude_and_R_at_least_one():
+    rng = np.random.default_rng(11)
+    v = np.sort(np.abs(rng.laplace(0, 1e-3, 2000)).astype(np.float32))
+    info = codes_of(v, ref.params(1.08, 128, 2, 1024))
+    c = np.array([(x & 0x7F) + 1 for x in info["codes"]])
+    assert c.min() >= 1                                   # R >= 1  =>  L >= 0, stored >= 1
+    assert np.all(np.diff(c) <= 0)                        # bigger |v|  =>  smaller code
+    # survivors are exactly the top of the sorted order (order reversal, Phase 3)
+    assert info["keys"] == list(range(2000 - info["d"], 2000))
+
+
+def test_kept_set_is_threshold_test():
+    rng = np.random.default_rng(12)
+    v = rng.laplace(0, 1e-3, 5000).astype(np.float32)
+    b, tau = 1.07, 128
+    S = math.fsum(abs(float(x)) for x in v)
+    info = codes_of(v, ref.params(b, tau, 2, 1024))
+    thr = Fraction(S) / Fraction(b) ** tau
+    expect = [j for j, x in enumerate(v) if Fraction(abs(float(x))) >= thr * (1 + Fraction(1, 10 ** 9))]
+    maybe = [j for j, x in enumerate(v) if Fraction(abs(float(x))) >= thr * (1 - Fraction(1, 10 ** 9))]
+    assert set(expect) <= set(info["keys"]) <= set(maybe)
+
+
+def test_power_of_two_scaling_leaves_codes_unchanged():
+    rng = np.random.default_rng(13)
+    v = rng.laplace(0, 1e-3, 3000).astype(np.float32)
+    p = ref.params(1.09, 128, 2, 1024)
+    a = codes_of(v, p)
+    for k in (-20, 7, 30):
+        s = codes_of(v * np.float32(2.0 ** k), p)
+        assert s["codes"] == a["codes"] and s["keys"] == a["keys"]
+        assert s["S"] == a["S"] * 2.0 ** k
+
+
+def test_single_element_code_clamped_to_one():
+    info = codes_of([-0.37], ref.params(1.1, 128, 2, 1024))
+    assert info["d"] == 1 and info["codes"] == [0x80 | 0]   # L = 0 stored as code 1, negative
+
+
+def test_zero_and_empty_inputs():
+    p = ref.params()
+    rc, st = ref.compress(np.zeros(0, np.uint32), np.zeros(0, np.float32), p)
+    assert rc == ref.OK and st.size == 64 and parse(st)["d"] == 0
+    rc, st = ref.compress(np.arange(10), np.zeros(10, np.float32), p)
+    assert rc == ref.OK and st.size == 64 and parse(st)["n"] == 10
+    info = codes_of([0.0, 1.0, -0.0, 2.0], p)
+    assert info["keys"] == [1, 3]                          # zeros never survive
+
+
+# ----------------------------------------------------------------------------- decode
+@pytest.mark.parametrize("seed,b", [(0, 1.1), (1, 1.07), (2, 3.0)])
+def test_decode_underestimates_within_one_base_step(seed, b):
+    rng = np.random.default_rng(seed)
+    n = 4000
+    keys = np.sort(rng.choice(10 * n, n, replace=False)).astype(np.uint32)
+    v = rng.laplace(0, 1e-3, n).astype(np.float32)
+    p = ref.params(b, 128, 2, 256)
+    rc, st = ref.compress(keys, v, p)
+    assert rc == ref.OK
+    rc, k2, v2 = ref.decompress(st)
+    assert rc == ref.OK
+    info = parse(st)
+    assert list(k2) == info["keys"]
+    orig = v[np.searchsorted(keys, k2)]
+    assert np.all(np.sign(v2) == np.sign(orig))
+    a, o = np.abs(v2).astype(np.float64), np.abs(orig).astype(np.float64)
+    clamped = np.array([(c & 0x7F) == 0 for c in info["codes"]], dtype=bool)
+    assert info["d"] > 100
+    assert np.all(a <= o)                                   # never over-estimates
+    assert np.all((o / b < a * (1 + 2.0 ** -22)) | clamped)  # and by less than one base step
+    # decoded magnitude is sum / b^code
+    S = info["S"]
+    c = np.array([(x & 0x7F) + 1 for x in info["codes"]], dtype=np.float64)
+    assert np.allclose(a, S / b ** c, rtol=1e-6)
+
+
+def test_decoded_magnitude_stays_in_its_own_bucket():
+    """The decoded magnitude of code c lies between the boundaries of c+1 and c (at most one
+    float32 below its own boundary), so re-quantizing a decoded value moves it by at most one code."""
+    rng = np.random.default_rng(5)
+    v = rng.laplace(0, 1e-3, 3000).astype(np.float32)
+    b, tau = 1.1, 128
+    rc, st = ref.compress(np.arange(3000), v, ref.params(b, tau, 2, 1024))
+    info = parse(st)
+    rc, k2, v2 = ref.decompress(st)
+    B, V = ref.tables(info["S"], b, tau)
+    a = np.abs(v2).view(np.uint32)
+    for x, byte in zip(a, info["codes"]):
+        c = (byte & 0x7F) + 1
+        # the decoded magnitude lies in (B[c+1], B[c]]: one ulp below B[c] at most
+        assert x <= B[c] and (c == tau or x >= B[c + 1])
