@@ -1,0 +1,132 @@
+/*
+ * fastsgd.h -- C ABI of the MI355X (gfx950) FastSGD gradient codec.
+ *
+ * The codec is the encoder/decoder pair of FastSGD (arXiv 2112.04291, Section 3):
+ *   encoder  = Algorithm 1 (GV-Encoder: sum of |v|, early-stop threshold sum/b^tau, reciprocal
+ *              mapper Eq. 2, logarithm quantization Eq. 3, threshold filter, sign) followed by
+ *              Algorithm 2 (GK-Encoder: delta keys Eq. 4, maximal length M, l-bit length flag,
+ *              bit-level binary encoding) on the keys of the surviving values;
+ *   decoder  = phases 1-4 of Section 3.1 (split by flags, prefix-sum deltas, scale integers back
+ *              up, divide sum by them).
+ *
+ * Conventions for every entry point
+ *   - Pointers named d_* are DEVICE pointers (readable/writable by kernels on the current
+ *     device); everything else is host memory read during the call only.
+ *   - The caller owns every buffer.  The library allocates no device memory and keeps no state
+ *     between calls; two calls may run concurrently if they use different workspaces.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default
+ *     stream).  No entry point synchronises with the host.  Values only the device knows are
+ *     reported through the d_* result words, valid once the stream has been synchronised.
+ *   - The return value covers what the host can see (bad arguments, workspace too small, launch
+ *     failure).  Conditions detected on the device set *d_status to a fastsgd_status value and
+ *     the reported length (bytes / pairs) to 0; nothing is ever written past a stated capacity.
+ *   - Keys are uint32 and strictly increasing within one gradient (the first may be 0);
+ *     values are IEEE binary32.  n <= 2^32 - 1 per gradient.
+ *
+ * Stream layout (little-endian): 64-byte header {"FSGD", version u8, l u8, tau u8, 0 u8,
+ * block_keys u32, n_blocks u32, b f64, sum f64, n u64, d u64, total_bytes u64, 0 u64}; value
+ * plane of d bytes (bit 7 sign, bits 0-6 code-1) zero-padded to 8; block directory of n_blocks x
+ * {off8 u32, preKey u32, M u32, payload_bits u32}; key blocks back to back, each a flags plane
+ * (cnt*l bits) and a payload plane (payload_bits bits), LSB first, zero-padded to 64-bit words.
+ */
+#ifndef FASTSGD_H
+#define FASTSGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Hyper-parameters of Section 4.2 ("effect of the hyper-parameters"): base b of the logarithm
+ * quantization, threshold tau of the filter, size l of the length flag; block_keys is how many
+ * surviving keys share one M (Algorithm 2 is applied per block, preKey carried across). */
+typedef struct {
+    double   base;       /* b: 1 + 2^-20 <= b <= 16 (paper: about 1.1)            */
+    uint32_t tau;        /* 1..128 (paper: 128, so a code fits one byte with sign) */
+    uint32_t flag_bits;  /* l: 1..5 (paper: 2)                                     */
+    uint32_t block_keys; /* power of two, 256..4096 (default 1024)                 */
+    uint32_t reserved;   /* must be 0                                              */
+} fastsgd_params;
+
+typedef enum {
+    FASTSGD_OK = 0,
+    FASTSGD_ERR_INVALID_ARG = 1,
+    FASTSGD_ERR_BUFFER_TOO_SMALL = 2, /* output / pair capacity or workspace too small      */
+    FASTSGD_ERR_NONFINITE = 3,        /* a NaN or infinity among the values                  */
+    FASTSGD_ERR_UNSORTED_KEYS = 4,    /* surviving keys not strictly increasing             */
+    FASTSGD_ERR_CORRUPT_STREAM = 5,   /* decoder: header, directory or planes inconsistent  */
+    FASTSGD_ERR_DEVICE = 6            /* HIP launch failure or an internal wait that gave up */
+} fastsgd_status;
+
+/* Host-only, pure.  Worst-case stream size in bytes for a gradient of n elements (all survive,
+ * every key token takes l + 32 bits); Section 3.4 gives the expected size, this is the bound an
+ * output buffer must have.  Returns 0 if *p is invalid. */
+size_t fastsgd_compressed_size(uint64_t n, const fastsgd_params* p);
+
+/* Host-only, pure.  Bytes of device workspace fastsgd_compress (n_segments = 1) or
+ * fastsgd_compress_segmented needs for total_n elements in n_segments gradients whose smallest
+ * block_keys is min_block_keys.  Returns 0 on invalid arguments. */
+size_t fastsgd_workspace_size(uint64_t total_n, uint32_t n_segments, uint32_t min_block_keys);
+
+/* Host-only, pure.  Bytes of device workspace the decoders need for n_segments streams. */
+size_t fastsgd_decompress_workspace_size(uint32_t n_segments);
+
+/* Encoder (Algorithms 1 and 2) for one worker's gradient {(k_j, v_j)}, j = 1..n.
+ *   d_keys, d_values   device, read-only, n entries each (4-byte aligned)
+ *   p                  host
+ *   d_out              device, out_capacity bytes, 8-byte aligned; receives the stream
+ *   d_out_bytes        device u64: stream length, or 0 if *d_status != FASTSGD_OK
+ *   d_status           device u32: fastsgd_status detected on the device
+ *   d_workspace        device, >= fastsgd_workspace_size(n, 1, p->block_keys) bytes, 256-byte aligned;
+ *                      contents need no initialisation and are garbage afterwards */
+fastsgd_status fastsgd_compress(const uint32_t* d_keys, const float* d_values, uint64_t n,
+                                const fastsgd_params* p,
+                                void* d_out, size_t out_capacity,
+                                uint64_t* d_out_bytes, uint32_t* d_status,
+                                void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Decoder (Section 3.1, phases 1-4) of one stream.
+ *   d_stream           device, stream_bytes bytes, 8-byte aligned
+ *   d_keys_out, d_values_out   device, `capacity` entries each; receive the d surviving pairs
+ *   d_count            device u64: d, or 0 if *d_status != FASTSGD_OK
+ *   d_workspace        device, >= fastsgd_decompress_workspace_size(1) bytes, 256-byte aligned */
+fastsgd_status fastsgd_decompress(const void* d_stream, size_t stream_bytes,
+                                  uint32_t* d_keys_out, float* d_values_out, uint64_t capacity,
+                                  uint64_t* d_count, uint32_t* d_status,
+                                  void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Encoder for a batch of independent gradients (e.g. one per layer) in one call: gradient s is
+ * elements [seg_offsets[s], seg_offsets[s+1]) of d_keys / d_values and is encoded exactly as
+ * fastsgd_compress would encode it alone.  Streams are written back to back into d_out (each a
+ * multiple of 8 bytes, each decodable on its own).
+ *   seg_offsets        host, n_segments + 1 non-decreasing element offsets
+ *   params             host; params_stride = 0: one entry shared by all segments,
+ *                      params_stride = 1: n_segments entries
+ *   d_out_seg_offsets  device u64[n_segments + 1]: byte offset of each stream in d_out, last
+ *                      entry = total bytes; all 0 if *d_status != FASTSGD_OK
+ *   n_segments         1..65536 */
+fastsgd_status fastsgd_compress_segmented(const uint32_t* d_keys, const float* d_values,
+                                          const uint64_t* seg_offsets, uint32_t n_segments,
+                                          const fastsgd_params* params, uint32_t params_stride,
+                                          void* d_out, size_t out_capacity,
+                                          uint64_t* d_out_seg_offsets, uint32_t* d_status,
+                                          void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Decoder for such a batch.
+ *   d_streams, total_bytes   device, the concatenated streams
+ *   d_stream_offsets   device u64[n_segments + 1] as written by fastsgd_compress_segmented
+ *   d_keys_out, d_values_out   device, `capacity` pairs; pairs of segment s start at
+ *                      d_pair_offsets[s]
+ *   d_pair_offsets     device u64[n_segments + 1]; all 0 if *d_status != FASTSGD_OK */
+fastsgd_status fastsgd_decompress_segmented(const void* d_streams, size_t total_bytes,
+                                            const uint64_t* d_stream_offsets, uint32_t n_segments,
+                                            uint32_t* d_keys_out, float* d_values_out, uint64_t capacity,
+                                            uint64_t* d_pair_offsets, uint32_t* d_status,
+                                            void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTSGD_H */

@@ -1,0 +1,250 @@
+// C ABI of the gfx950 FastSGD codec: argument checks, workspace carve-up, kernel launches.
+// Every entry point only enqueues work on the caller's stream.
+#include <atomic>
+#include <vector>
+
+#include "fastsgd_device.hpp"
+#include "fastsgd_encode_kernels.hpp"
+#include "fastsgd_decode_kernels.hpp"
+
+namespace fsgd {
+
+constexpr u64 kDecSegBytes = 640, kDecCtrlBytes = 64;   // >= sizeof(DecSeg), sizeof(DecCtrl)
+constexpr u32 kMaxSegments = 65536;
+static_assert(sizeof(DecSeg) <= kDecSegBytes && sizeof(DecCtrl) <= kDecCtrlBytes, "decoder workspace records");
+static_assert(sizeof(SegInfo) == 48 && sizeof(SegBatch) <= 3072, "segment table travels as a kernel argument");
+
+static bool params_ok(const fastsgd_params* p) {
+    if (!p) return false;
+    if (!(p->base >= 1.0 + 1.0 / 1048576.0) || !(p->base <= 16.0)) return false;
+    if (p->tau < 1 || p->tau > 128) return false;
+    if (p->flag_bits < 1 || p->flag_bits > 5) return false;
+    if (p->block_keys < 256 || p->block_keys > kMaxKB || (p->block_keys & (p->block_keys - 1))) return false;
+    return p->reserved == 0;
+}
+
+static u64 up(u64 x, u64 a) { return (x + a - 1) / a * a; }
+
+// Workspace layout from bounds that depend only on (total_n, n_segments, min_block_keys), so the size
+// query and the call agree.
+static EncodePlan make_plan(u64 total_n, u32 n_segments, u32 min_kb) {
+    EncodePlan pl{};
+    pl.total_n = total_n;
+    pl.n_segments = n_segments;
+    pl.n_slots = (n_segments == 1) ? 32u : 4u;
+    pl.n_tiles = total_n / kTile + 2ull * n_segments + 1;          // bound; a segment adds at most 2 partial tiles
+    pl.max_items = total_n / min_kb + n_segments + 1;              // bound on key blocks (+1 per empty segment)
+    u64 o = 0;
+    pl.off_ctrl = o;  o += 256;
+    pl.off_gbins = o; o += up((u64)n_segments * pl.n_slots * 2 * kBins * 8, 256);
+    pl.off_tdesc = o; o += up(pl.n_tiles * 8, 256);
+    pl.off_idesc = o; o += up(pl.max_items * 8, 256);
+    pl.off_segstate = o; o += up((u64)n_segments * sizeof(SegState), 256);   // holds the non-finite flags
+    pl.zero_end = o;
+    pl.off_seginfo = o;  o += up((u64)n_segments * sizeof(SegInfo), 256);
+    pl.off_binfo = o;    o += up(pl.max_items * sizeof(BlockInfo), 256);
+    pl.off_ckeys = o;    o += up(total_n * 4, 256);
+    pl.off_codes = o;    o += up(total_n, 256);
+    pl.total = o;
+    return pl;
+}
+
+static u32 cu_count() {
+    static std::atomic<u32> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    u32 c = cached[dev].load(std::memory_order_relaxed);
+    if (c == 0) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+        c = (u32)v;
+        cached[dev].store(c, std::memory_order_relaxed);
+    }
+    return c;
+}
+
+static u32 clamp_grid(u64 want, u64 cap) { u64 g = want < cap ? want : cap; return (u32)(g ? g : 1); }
+
+static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, const u64* seg_offsets, u32 n_segments,
+                                    const fastsgd_params* params, u32 params_stride, void* d_out, size_t out_capacity,
+                                    u64* d_out_offsets, u32* d_status, void* d_ws, size_t ws_bytes, void* hip_stream,
+                                    bool single) {
+    if (!seg_offsets || !params || !d_out || !d_out_offsets || !d_status || !d_ws) return FASTSGD_ERR_INVALID_ARG;
+    if (n_segments < 1 || n_segments > kMaxSegments || params_stride > 1) return FASTSGD_ERR_INVALID_ARG;
+    if (((uintptr_t)d_out & 7) || ((uintptr_t)d_ws & 255) || ((uintptr_t)d_values & 3) || ((uintptr_t)d_keys & 3))
+        return FASTSGD_ERR_INVALID_ARG;
+    const u64 total_n = seg_offsets[n_segments] - seg_offsets[0];
+    if (seg_offsets[n_segments] < seg_offsets[0] || total_n >= (1ull << 40)) return FASTSGD_ERR_INVALID_ARG;
+    if (total_n && (!d_keys || !d_values)) return FASTSGD_ERR_INVALID_ARG;
+
+    // shift the bases down to a 16-byte boundary of the value array; elements keep their pairing
+    const u64 mis = ((uintptr_t)d_values & 15) / 4;
+    const float* vbase = d_values - mis;
+    const u32* kbase = d_keys - mis;
+
+    std::vector<SegInfo> segs(n_segments);
+    u32 min_kb = kMaxKB;
+    u64 n_tiles = 0, max_items = 0;
+    for (u32 s = 0; s < n_segments; ++s) {
+        const fastsgd_params* p = &params[params_stride ? s : 0];
+        if (!params_ok(p)) return FASTSGD_ERR_INVALID_ARG;
+        if (seg_offsets[s + 1] < seg_offsets[s]) return FASTSGD_ERR_INVALID_ARG;
+        const u64 cnt = seg_offsets[s + 1] - seg_offsets[s];
+        if (cnt > 0xFFFFFFFFull) return FASTSGD_ERR_INVALID_ARG;
+        SegInfo& si = segs[s];
+        si.elem_begin = seg_offsets[s] + mis;
+        si.elem_count = cnt;
+        si.tile_begin = n_tiles;
+        si.base = p->base; si.tau = p->tau; si.flag_bits = p->flag_bits; si.block_keys = p->block_keys; si.pad = 0;
+        if (cnt) n_tiles += (si.elem_begin + cnt - (si.elem_begin & ~3ull) + kTile - 1) / kTile;
+        const u64 blocks = (cnt + p->block_keys - 1) / p->block_keys;
+        max_items += blocks ? blocks : 1;
+        if (p->block_keys < min_kb) min_kb = p->block_keys;
+    }
+    const EncodePlan pl = make_plan(total_n, n_segments, min_kb);
+    if (n_tiles > pl.n_tiles || max_items > pl.max_items || n_tiles >= 0xFFFFFFFFull) return FASTSGD_ERR_INVALID_ARG;
+    const u64 need = single ? pl.off_codes : pl.total;
+    if (ws_bytes < need) return FASTSGD_ERR_BUFFER_TOO_SMALL;
+    if (out_capacity < kHeaderBytes) return FASTSGD_ERR_BUFFER_TOO_SMALL;
+
+    uint8_t* ws = static_cast<uint8_t*>(d_ws);
+    Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + pl.off_ctrl);
+    u64* gbins = reinterpret_cast<u64*>(ws + pl.off_gbins);
+    u64* tdesc = reinterpret_cast<u64*>(ws + pl.off_tdesc);
+    u64* idesc = reinterpret_cast<u64*>(ws + pl.off_idesc);
+    SegInfo* dsegs = reinterpret_cast<SegInfo*>(ws + pl.off_seginfo);
+    SegState* dstates = reinterpret_cast<SegState*>(ws + pl.off_segstate);
+    BlockInfo* binfo = reinterpret_cast<BlockInfo*>(ws + pl.off_binfo);
+    u32* ckeys = reinterpret_cast<u32*>(ws + pl.off_ckeys);
+    uint8_t* out = static_cast<uint8_t*>(d_out);
+    uint8_t* codes = single ? out + kHeaderBytes : ws + pl.off_codes;
+    const u64 codes_cap = single ? (u64)out_capacity - kHeaderBytes : total_n;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const u32 cus = cu_count();
+
+    // clear control words and descriptors, store the segment table (48 segments per launch)
+    const u64 zero_words = (pl.zero_end - pl.off_ctrl) / 8;
+    for (u32 first = 0; first < n_segments; first += 48) {
+        SegBatch b;
+        const u32 count = (n_segments - first < 48) ? n_segments - first : 48;
+        for (u32 i = 0; i < count; ++i) b.seg[i] = segs[first + i];
+        if (first == 0)
+            hipLaunchKernelGGL(k_init, dim3(clamp_grid((zero_words + 1023) / 1024, 2048)), dim3(256), 0, stream,
+                               reinterpret_cast<u64*>(ws + pl.off_ctrl), zero_words, dsegs, b, first, count);
+        else
+            hipLaunchKernelGGL(k_store_segments, dim3(1), dim3(64), 0, stream, dsegs, b, first, count);
+    }
+
+    const u32 grid_sum_max = cus * 5;
+    u32 tpc = (u32)(n_tiles / ((u64)grid_sum_max * 8));
+    tpc = tpc < 1 ? 1 : (tpc > 8 ? 8 : tpc);
+    const u64 n_chunks = (n_tiles + tpc - 1) / tpc;
+    hipLaunchKernelGGL(k_abs_sum, dim3(clamp_grid(n_chunks, grid_sum_max)), dim3(kThreads), 0, stream,
+                       vbase, dsegs, dstates, n_segments, n_tiles, tpc, gbins, pl.n_slots, ctrl);
+    hipLaunchKernelGGL(k_tables, dim3(n_segments), dim3(kThreads), 0, stream, dsegs, dstates, gbins, pl.n_slots, ctrl);
+    hipLaunchKernelGGL(k_encode_values, dim3(clamp_grid(n_tiles, (u64)cus * 6)), dim3(kThreads), 0, stream,
+                       kbase, vbase, dsegs, dstates, n_segments, n_tiles, tdesc, ckeys, codes, codes_cap, total_n, ctrl);
+    hipLaunchKernelGGL(k_plan_keys, dim3(1), dim3(kThreads), 0, stream, dsegs, dstates, n_segments, n_tiles, tdesc, ctrl);
+    hipLaunchKernelGGL(k_encode_keys, dim3(clamp_grid(max_items, (u64)cus * 4)), dim3(kThreads), 0, stream,
+                       dsegs, dstates, n_segments, ckeys, idesc, binfo, out, (u64)out_capacity, ctrl);
+    hipLaunchKernelGGL(k_finalize, dim3(clamp_grid(max_items, (u64)cus * 4)), dim3(kThreads), 0, stream,
+                       dsegs, dstates, n_segments, idesc, binfo, codes, out, (u64)out_capacity, d_out_offsets,
+                       single ? 1u : 0u, d_status, ctrl);
+    return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
+}
+
+static fastsgd_status decompress_impl(const void* d_streams, size_t total_bytes, const u64* d_stream_offsets,
+                                      u32 n_segments, u32* d_keys_out, float* d_values_out, u64 capacity,
+                                      u64* d_counts, u32* d_status, void* d_ws, size_t ws_bytes, void* hip_stream,
+                                      bool single) {
+    if (!d_streams || !d_counts || !d_status || !d_ws) return FASTSGD_ERR_INVALID_ARG;
+    if (n_segments < 1 || n_segments > kMaxSegments) return FASTSGD_ERR_INVALID_ARG;
+    if (!single && !d_stream_offsets) return FASTSGD_ERR_INVALID_ARG;
+    if (((uintptr_t)d_streams & 7) || ((uintptr_t)d_ws & 255)) return FASTSGD_ERR_INVALID_ARG;
+    if (capacity && (!d_keys_out || !d_values_out)) return FASTSGD_ERR_INVALID_ARG;
+    if (((uintptr_t)d_keys_out & 3) || ((uintptr_t)d_values_out & 3)) return FASTSGD_ERR_INVALID_ARG;
+    if (ws_bytes < kDecCtrlBytes + 192 + (u64)n_segments * kDecSegBytes) return FASTSGD_ERR_BUFFER_TOO_SMALL;
+    uint8_t* ws = static_cast<uint8_t*>(d_ws);
+    DecCtrl* ctrl = reinterpret_cast<DecCtrl*>(ws);
+    DecSeg* segs = reinterpret_cast<DecSeg*>(ws + 256);
+    const uint8_t* streams = static_cast<const uint8_t*>(d_streams);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const u32 cus = cu_count();
+
+    if (single) {
+        hipLaunchKernelGGL(k_decode_setup, dim3(1), dim3(128), 0, stream, streams, (u64)total_bytes,
+                           (const u64*)nullptr, 1u, segs, ctrl, capacity, d_counts, d_status);
+    } else {
+        hipLaunchKernelGGL(k_decode_clear, dim3(1), dim3(64), 0, stream, ctrl);
+        hipLaunchKernelGGL(k_decode_setup, dim3(n_segments), dim3(128), 0, stream, streams, (u64)total_bytes,
+                           d_stream_offsets, n_segments, segs, ctrl, capacity, d_counts, d_status);
+        if (n_segments > 1)
+            hipLaunchKernelGGL(k_decode_plan, dim3(1), dim3(64), 0, stream, segs, n_segments, capacity, ctrl,
+                               d_counts, d_status);
+    }
+    // every key costs at least one value byte, so bytes/256 bounds the number of key blocks
+    hipLaunchKernelGGL(k_decode, dim3(clamp_grid((u64)total_bytes / 256 + n_segments, (u64)cus * 4)), dim3(kThreads), 0,
+                       stream, streams, segs, n_segments, ctrl, d_keys_out, d_values_out, d_counts,
+                       single ? 1u : n_segments + 1u, d_status);
+    return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
+}
+
+}  // namespace fsgd
+
+using namespace fsgd;
+
+extern "C" {
+
+size_t fastsgd_compressed_size(uint64_t n, const fastsgd_params* p) {
+    if (!params_ok(p) || n > 0xFFFFFFFFull) return 0;
+    const u64 KB = p->block_keys, nb = (n + KB - 1) / KB;
+    const u64 per_block = 8 * ((KB * p->flag_bits + 63) / 64 + (KB * 32 + 63) / 64);
+    return (size_t)(kHeaderBytes + ((n + 7) & ~7ull) + 16 * nb + nb * per_block);
+}
+
+size_t fastsgd_workspace_size(uint64_t total_n, uint32_t n_segments, uint32_t min_block_keys) {
+    if (n_segments < 1 || n_segments > kMaxSegments || total_n >= (1ull << 40)) return 0;
+    if (min_block_keys < 256 || min_block_keys > kMaxKB || (min_block_keys & (min_block_keys - 1))) return 0;
+    // + 4 elements: the call may shift its base down to a 16-byte boundary
+    return (size_t)make_plan(total_n, n_segments, min_block_keys).total;
+}
+
+size_t fastsgd_decompress_workspace_size(uint32_t n_segments) {
+    if (n_segments < 1 || n_segments > kMaxSegments) return 0;
+    return (size_t)(256 + (u64)n_segments * kDecSegBytes);
+}
+
+fastsgd_status fastsgd_compress(const uint32_t* d_keys, const float* d_values, uint64_t n, const fastsgd_params* p,
+                                void* d_out, size_t out_capacity, uint64_t* d_out_bytes, uint32_t* d_status,
+                                void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+    if (n > 0xFFFFFFFFull) return FASTSGD_ERR_INVALID_ARG;
+    const u64 offs[2] = {0, n};
+    return compress_impl(d_keys, d_values, offs, 1, p, 0, d_out, out_capacity, d_out_bytes, d_status, d_workspace,
+                         workspace_bytes, hip_stream, true);
+}
+
+fastsgd_status fastsgd_compress_segmented(const uint32_t* d_keys, const float* d_values, const uint64_t* seg_offsets,
+                                          uint32_t n_segments, const fastsgd_params* params, uint32_t params_stride,
+                                          void* d_out, size_t out_capacity, uint64_t* d_out_seg_offsets,
+                                          uint32_t* d_status, void* d_workspace, size_t workspace_bytes,
+                                          void* hip_stream) {
+    return compress_impl(d_keys, d_values, seg_offsets, n_segments, params, params_stride, d_out, out_capacity,
+                         d_out_seg_offsets, d_status, d_workspace, workspace_bytes, hip_stream, false);
+}
+
+fastsgd_status fastsgd_decompress(const void* d_stream, size_t stream_bytes, uint32_t* d_keys_out, float* d_values_out,
+                                  uint64_t capacity, uint64_t* d_count, uint32_t* d_status, void* d_workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
+    return decompress_impl(d_stream, stream_bytes, nullptr, 1, d_keys_out, d_values_out, capacity, d_count, d_status,
+                           d_workspace, workspace_bytes, hip_stream, true);
+}
+
+fastsgd_status fastsgd_decompress_segmented(const void* d_streams, size_t total_bytes, const uint64_t* d_stream_offsets,
+                                            uint32_t n_segments, uint32_t* d_keys_out, float* d_values_out,
+                                            uint64_t capacity, uint64_t* d_pair_offsets, uint32_t* d_status,
+                                            void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+    return decompress_impl(d_streams, total_bytes, d_stream_offsets, n_segments, d_keys_out, d_values_out, capacity,
+                           d_pair_offsets, d_status, d_workspace, workspace_bytes, hip_stream, false);
+}
+
+}  // extern "C"

@@ -1,0 +1,49 @@
+"""Helpers for the GPU parity tests: run the HIP path through the C ABI binding on numpy inputs."""
+import numpy as np
+import torch
+
+from paper_2112_04291_amd import binding as B
+
+
+def to_dev_u32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint32).view(np.int32)).cuda()
+
+
+def to_dev_f32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def hip_compress(keys, values, p, out_capacity=None, bufs=None):
+    """Returns (host rc, device status, stream bytes as uint8 numpy array, bufs)."""
+    n = int(np.asarray(values).size)
+    bufs = bufs or B.Buffers(n, p, out_capacity=out_capacity)
+    k, v = to_dev_u32(keys), to_dev_f32(values)
+    bufs.status.fill_(-1)
+    bufs.out_offsets.fill_(-1)
+    rc = B.compress(k, v, p, bufs.out, bufs.out_offsets, bufs.status, bufs.workspace, n=n,
+                    out_capacity=bufs.out_capacity)
+    torch.cuda.synchronize()
+    if rc != B.OK:
+        return rc, None, None, bufs
+    status = int(bufs.status[0].item())
+    nbytes = int(bufs.out_offsets[0].item())
+    stream = bufs.out_bytes_view()[:nbytes].cpu().numpy().copy()
+    return rc, status, stream, bufs
+
+
+def hip_decompress(stream, capacity, bufs=None, p=None):
+    """stream: uint8 numpy array.  Returns (host rc, device status, keys uint32, values float32)."""
+    s = np.ascontiguousarray(stream, dtype=np.uint8)
+    pad = (-s.size) % 8
+    dev = torch.from_numpy(np.concatenate([s, np.zeros(pad + 8, np.uint8)])).cuda()
+    keys_out = torch.empty(max(capacity, 1), dtype=torch.int32, device="cuda")
+    vals_out = torch.empty(max(capacity, 1), dtype=torch.float32, device="cuda")
+    count = torch.full((2,), -1, dtype=torch.int64, device="cuda")
+    status = torch.full((2,), -1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.decompress_workspace_size(1) // 8 + 32, dtype=torch.int64, device="cuda")
+    rc = B.decompress(dev, s.size, keys_out, vals_out, count, status, ws, capacity=capacity)
+    torch.cuda.synchronize()
+    if rc != B.OK:
+        return rc, None, None, None
+    c = int(count[0].item())
+    return rc, int(status[0].item()), keys_out[:c].cpu().numpy().view(np.uint32).copy(), vals_out[:c].cpu().numpy().copy()

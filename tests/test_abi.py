@@ -1,0 +1,55 @@
+"""The C-ABI library loads and exports every symbol include/fastsgd.h declares; host-only entry
+points agree with the oracle's closed forms.  No GPU needed (no compute call is made)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import ref
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "fastsgd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fastsgd_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    from paper_2112_04291_amd import binding as B
+    assert declared_symbols() == sorted(B.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2112_04291_amd import binding as B
+    L = B.lib()
+    for name in declared_symbols():
+        assert hasattr(L, name), name
+
+
+def test_compressed_size_matches_oracle_bound():
+    from paper_2112_04291_amd import binding as B
+    for n in [0, 1, 255, 256, 1000, 4097, 10 ** 6, 124_000_000]:
+        for kb in [256, 1024, 4096]:
+            for l in [1, 2, 5]:
+                assert B.compressed_size(n, B.params(1.1, 128, l, kb)) == ref.compressed_size(n, ref.params(1.1, 128, l, kb))
+    assert B.compressed_size(10, B.params(0.5)) == 0
+    assert B.compressed_size(10, B.params(block_keys=100)) == 0
+
+
+def test_workspace_size_is_monotone_and_rejects_bad_arguments():
+    from paper_2112_04291_amd import binding as B
+    a = B.workspace_size(1000, 1, 1024)
+    b = B.workspace_size(10 ** 6, 1, 1024)
+    c = B.workspace_size(10 ** 6, 160, 256)
+    assert 0 < a < b < c
+    assert B.workspace_size(10, 0, 1024) == 0 and B.workspace_size(10, 1, 100) == 0
+    assert B.decompress_workspace_size(1) > 0 and B.decompress_workspace_size(0) == 0
+
+
+def test_params_struct_layout_matches_header():
+    from paper_2112_04291_amd import binding as B
+    assert ctypes.sizeof(B.Params) == 24
+    assert [f[0] for f in B.Params._fields_] == ["base", "tau", "flag_bits", "block_keys", "reserved"]

@@ -1,0 +1,213 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Bar: the compressed stream is byte-identical; decoded keys are identical; decoded values are
+within 1e-6 relative of the oracle's decode (in practice identical bit patterns)."""
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2112_04291_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 1e-6
+
+
+def _gpu():
+    import torch
+    from paper_2112_04291_amd import binding as B
+    from tests import gpu_util as G
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return torch, B, G
+
+
+def check_round_trip(keys, values, base, tau=128, l=2, kb=1024, expect_status=0):
+    torch, B, G = _gpu()
+    keys = np.ascontiguousarray(keys, dtype=np.uint32)
+    values = np.ascontiguousarray(values, dtype=np.float32)
+    rc_ref, st_ref = ref.compress(keys, values, ref.params(base, tau, l, kb))
+    rc, status, st, _ = G.hip_compress(keys, values, B.params(base, tau, l, kb))
+    assert rc == B.OK
+    assert status == rc_ref == expect_status, (status, rc_ref)
+    if expect_status != 0:
+        assert st.size == 0
+        return None
+    assert st.size == st_ref.size, (st.size, st_ref.size)
+    if not np.array_equal(st, st_ref):
+        bad = np.flatnonzero(st != st_ref)
+        raise AssertionError(f"stream differs at {bad.size} bytes, first at {bad[:8]} of {st.size}; "
+                             f"header hip={st[:64].tolist()} ref={st_ref[:64].tolist()}")
+    d = int(st_ref[40:48].view("<u8")[0])
+    rc_ref, k_ref, v_ref = ref.decompress(st_ref)
+    rc, status, k, v = G.hip_decompress(st_ref, capacity=d)
+    assert rc == B.OK and status == 0 and rc_ref == 0
+    assert np.array_equal(k, k_ref)
+    assert v.size == v_ref.size
+    if d:
+        assert np.all(np.abs(v.astype(np.float64) - v_ref.astype(np.float64)) <= REL_TOL * np.abs(v_ref.astype(np.float64)))
+        assert np.array_equal(np.signbit(v), np.signbit(v_ref))
+    return st
+
+
+@pytest.mark.parametrize("n", [0, 1, 3, 255, 4095, 4096, 4097, 10_000, 70_001])
+def test_small_sizes_and_ragged_tails(n):
+    w = W.small_mixture(100 + n, n)
+    b = W.solve_base(w.values, 0.2) if n else 1.1
+    check_round_trip(w.keys, w.values, b)
+
+
+@pytest.mark.parametrize("keep", [1.0, 0.5, 0.1, 0.01, 0.001])
+def test_survival_fractions(keep):
+    w = W.small_mixture(7, 300_000)
+    check_round_trip(w.keys, w.values, W.solve_base(w.values, keep))
+
+
+@pytest.mark.parametrize("tau,l,kb", [(128, 1, 256), (128, 3, 512), (100, 4, 2048), (64, 5, 4096), (1, 2, 1024),
+                                      (17, 2, 256)])
+def test_parameter_grid(tau, l, kb):
+    w = W.small_mixture(11, 200_000)
+    check_round_trip(w.keys, w.values, W.solve_base(w.values, 0.3, tau), tau, l, kb)
+
+
+def test_config1_tiny_sparse_gradient():
+    w = W.config1()
+    st = check_round_trip(w.keys, w.values, W.solve_base(w.values, 0.10))
+    d = int(st[40:48].view("<u8")[0])
+    assert 0.09 * w.values.size <= d <= 0.11 * w.values.size
+    # the paper's own defaults (b = 1.1) with a smaller tau that keeps about a tenth
+    check_round_trip(w.keys, w.values, 1.1, tau=112)
+
+
+def test_all_survive_and_none_survive():
+    n = 50_000
+    keys = np.arange(n, dtype=np.uint32) * 3
+    check_round_trip(keys, np.full(n, 1.0, np.float32), 1.1)                 # everything kept, dense codes
+    vals = np.full(n, 1e-3, np.float32)
+    check_round_trip(keys, vals, 1.0 + 2.0 ** -19)                           # b^tau ~ 1: nothing reaches sum
+    check_round_trip(keys, np.zeros(n, np.float32), 1.1)                     # all-zero gradient: d = 0
+    one = np.zeros(n, np.float32)
+    one[12345] = -2.5
+    check_round_trip(keys, one, 1.1)                                         # one element is the whole sum
+
+
+def test_wide_exponent_range_exact_sum():
+    rng = np.random.default_rng(5)
+    n = 123_457
+    e = rng.integers(0, 255, n).astype(np.uint32)
+    m = rng.integers(0, 1 << 23, n).astype(np.uint32)
+    s = rng.integers(0, 2, n).astype(np.uint32)
+    vals = ((s << 31) | (e << 23) | m).view(np.float32)
+    keys = np.sort(rng.choice(2 ** 32 - 1, n, replace=False)).astype(np.uint32)
+    check_round_trip(keys, vals, 1.9)
+    check_round_trip(keys, vals, 16.0, tau=128, l=5, kb=256)
+    # denormals only
+    dn = rng.integers(1, 1 << 23, 20_000).astype(np.uint32).view(np.float32)
+    check_round_trip(np.arange(20_000), dn, 1.07)
+
+
+@pytest.mark.parametrize("badval", [np.nan, np.inf, -np.inf])
+def test_nonfinite_input_is_reported(badval):
+    w = W.small_mixture(3, 20_000)
+    v = w.values.copy()
+    v[17_123] = badval
+    check_round_trip(w.keys, v, 1.1, expect_status=ref.ERR_NONFINITE)
+
+
+def test_unsorted_surviving_keys_are_reported():
+    n = 10_000
+    keys = np.arange(n, dtype=np.uint32)
+    keys[5000], keys[5001] = keys[5001], keys[5000]
+    check_round_trip(keys, np.full(n, 1.0, np.float32), 1.1, expect_status=ref.ERR_UNSORTED_KEYS)
+    keys = np.arange(n, dtype=np.uint32)
+    keys[77] = keys[76]
+    check_round_trip(keys, np.full(n, 1.0, np.float32), 1.1, expect_status=ref.ERR_UNSORTED_KEYS)
+
+
+def test_output_capacity_is_respected():
+    torch, B, G = _gpu()
+    w = W.small_mixture(21, 100_000)
+    b = W.solve_base(w.values, 0.5)
+    rc_ref, st_ref = ref.compress(w.keys, w.values, ref.params(b))
+    for cap in [64, 64 + 1000, st_ref.size - 8, st_ref.size]:
+        bufs = B.Buffers(w.values.size, B.params(b), out_capacity=st_ref.size + 4096)
+        guard = bufs.out_bytes_view()
+        guard.fill_(0xAB)
+        bufs.out_capacity = cap
+        rc, status, st, _ = G.hip_compress(w.keys, w.values, B.params(b), bufs=bufs)
+        assert rc == B.OK
+        after = guard.cpu().numpy()
+        assert np.all(after[cap:] == 0xAB), "wrote past the stated capacity"
+        if cap >= st_ref.size:
+            assert status == 0 and np.array_equal(st, st_ref)
+        else:
+            assert status == B.ERR_BUFFER_TOO_SMALL and st.size == 0
+    assert G.hip_compress(w.keys, w.values, B.params(b), out_capacity=32)[0] == B.ERR_BUFFER_TOO_SMALL
+
+
+def test_unaligned_input_pointers():
+    torch, B, G = _gpu()
+    w = W.small_mixture(31, 50_001)
+    b = W.solve_base(w.values, 0.3)
+    for shift in (1, 2, 3):
+        keys, vals = w.keys[shift:], w.values[shift:]
+        rc_ref, st_ref = ref.compress(keys, vals, ref.params(b))
+        k = G.to_dev_u32(w.keys)[shift:]
+        v = G.to_dev_f32(w.values)[shift:]
+        bufs = B.Buffers(vals.size, B.params(b))
+        rc = B.compress(k, v, B.params(b), bufs.out, bufs.out_offsets, bufs.status, bufs.workspace, n=vals.size,
+                        out_capacity=bufs.out_capacity)
+        torch.cuda.synchronize()
+        assert rc == B.OK and int(bufs.status[0]) == 0
+        nbytes = int(bufs.out_offsets[0])
+        assert np.array_equal(bufs.out_bytes_view()[:nbytes].cpu().numpy(), st_ref)
+
+
+def test_repeated_calls_are_deterministic_and_reuse_workspace():
+    torch, B, G = _gpu()
+    w = W.small_mixture(41, 400_000)
+    b = W.solve_base(w.values, 0.05)
+    bufs = B.Buffers(w.values.size, B.params(b))
+    first = None
+    for it in range(10):
+        rc, status, st, _ = G.hip_compress(w.keys, w.values, B.params(b), bufs=bufs)
+        assert rc == B.OK and status == 0
+        if first is None:
+            first = st
+            assert np.array_equal(st, ref.compress(w.keys, w.values, ref.params(b))[1])
+        else:
+            assert np.array_equal(st, first)
+
+
+def test_corrupt_streams_are_rejected_on_device():
+    torch, B, G = _gpu()
+    import struct
+    rng = np.random.default_rng(9)
+    keys = np.cumsum(rng.integers(1, 100, 2000)).astype(np.uint32)
+    rc, st = ref.compress(keys, np.full(2000, 1.0, np.float32), ref.params(1.1, 100, 2, 256))
+    assert rc == 0
+    d = 2000
+    dir_off = 64 + ((d + 7) & ~7)
+
+    def run(mut, cap=4096):
+        s = st.copy()
+        mut(s)
+        rc_ref = ref.decompress(s, capacity=cap)[0]
+        rc, status, k, v = G.hip_decompress(s, capacity=cap)
+        assert rc == B.OK
+        assert status == rc_ref, (status, rc_ref)
+        if status != 0:
+            assert k.size == 0
+        return status
+
+    def poke(off, fmt, val):
+        return lambda s: s.__setitem__(slice(off, off + struct.calcsize(fmt)), np.frombuffer(struct.pack(fmt, val), np.uint8))
+
+    assert run(lambda s: None) == 0
+    for mut in [poke(0, "<B", 0x58), poke(4, "<B", 9), poke(5, "<B", 7), poke(6, "<B", 200), poke(8, "<I", 300),
+                poke(12, "<I", 9), poke(40, "<Q", d + 1), poke(40, "<Q", 10 ** 12), poke(48, "<Q", st.size + 8),
+                poke(64 + 5, "<B", 120), poke(dir_off + 16, "<I", 12345), poke(dir_off + 16, "<I", 0xFFFFFFF0),
+                poke(dir_off + 16 + 4, "<I", 1), poke(dir_off + 8, "<I", 33), poke(dir_off + 12, "<I", 17),
+                poke(dir_off + 12, "<I", 0xFFFFFFFF)]:
+        assert run(mut) == B.ERR_CORRUPT_STREAM
+    assert run(lambda s: None, cap=1999) == B.ERR_BUFFER_TOO_SMALL
+    rc, status, k, v = G.hip_decompress(st[:48], capacity=10)
+    assert status == B.ERR_CORRUPT_STREAM
