@@ -100,9 +100,9 @@ k_decode_setup(const uint8_t* __restrict__ streams, u64 total_bytes, const u64* 
         if (ok) power_chain(base, tau, s_P);
     }
     __syncthreads();
-    if (s_ok && t >= 1 && t <= s_tau) {
+    if (s_ok && t < s_tau) {            // thread t owns code c = t + 1
         const double sum = s_sum;
-        ds->V[t - 1] = (sum > 0.0) ? f64_to_f32_bits(sum / s_P[t], false) : 0u;
+        ds->V[t] = (sum > 0.0) ? f64_to_f32_bits(sum / s_P[t + 1], false) : 0u;
     }
     if (n_segments == 1) {           // a single stream needs no separate planning launch
         __syncthreads();
