@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the FastSGD codec on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: for every keep fraction
+of the workload's sweep, fastsgd_compress followed by fastsgd_decompress of that stream, inputs
+resident in HBM.  Prints ONE JSON line (metric = input GB/s of the round trip, 8 bytes per element:
+4-byte key + 4-byte value, the paper's 64 bits per original pair, Section 3.4).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 24, help="elements of the workload the oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this codec is a single-GPU path (one worker's gradient); --gpus must be 1. "
+              "Nothing was run.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2112_04291_amd import binding as B
+    from paper_2112_04291_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    B.lib()
+
+    gen = {"c1": W.config1, "c2": W.config2, "c3": W.config3, "c4": W.config4}[args.workload]
+    t0 = time.time()
+    if args.scale != 1.0 and args.workload in ("c2", "c4"):
+        w = gen(n=int({"c2": 25_600_000, "c4": 124_000_000}[args.workload] * args.scale))
+    else:
+        w = gen()
+    keeps = w.meta["keep"]
+    bases = W.solve_bases(w.values, keeps)
+    n = int(w.values.size)
+    print(f"[bench] workload {w.name}: n={n} keeps={keeps} bases={bases} (generated in {time.time() - t0:.1f}s)",
+          file=sys.stderr, flush=True)
+
+    keys = torch.from_numpy(w.keys.view(np.int32)).cuda()
+    values = torch.from_numpy(w.values).cuda()
+    plist = [B.params(b) for b in bases]
+
+    # one output buffer per sweep point (sized from a first, untimed pass), shared workspace
+    probe = B.Buffers(n, plist[0])
+    points = []
+    for keep, p in zip(keeps, plist):
+        rc = B.compress(keys, values, p, probe.out, probe.out_offsets, probe.status, probe.workspace, n=n,
+                        out_capacity=probe.out_capacity)
+        torch.cuda.synchronize()
+        assert rc == B.OK and int(probe.status[0]) == B.OK, (rc, int(probe.status[0]))
+        nbytes = int(probe.out_offsets[0])
+        hdr = probe.out_bytes_view()[:64].cpu().numpy()
+        d = int(hdr[40:48].view("<u8")[0])
+        out = torch.empty(nbytes // 8 + 8, dtype=torch.int64, device="cuda")
+        points.append(dict(keep=keep, p=p, out=out, cap=nbytes, bytes=nbytes, d=d,
+                           keys_out=torch.empty(max(d, 1), dtype=torch.int32, device="cuda"),
+                           vals_out=torch.empty(max(d, 1), dtype=torch.float32, device="cuda")))
+    ws, dws = probe.workspace, probe.dec_workspace
+    obytes = torch.zeros(2, dtype=torch.int64, device="cuda")
+    count = torch.zeros(2, dtype=torch.int64, device="cuda")
+    status = torch.zeros(2, dtype=torch.int32, device="cuda")
+    del probe.out
+
+    def do_compress(pt):
+        rc = B.compress(keys, values, pt["p"], pt["out"], obytes, status, ws, n=n, out_capacity=pt["cap"])
+        assert rc == B.OK
+
+    def do_decompress(pt):
+        rc = B.decompress(pt["out"], pt["bytes"], pt["keys_out"], pt["vals_out"], count, status, dws, capacity=pt["d"])
+        assert rc == B.OK
+
+    def step():
+        for pt in points:
+            do_compress(pt)
+            do_decompress(pt)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert int(status[0]) == B.OK and int(count[0]) == points[-1]["d"]
+    ms_per_step = 1e3 * elapsed / args.steps
+    in_bytes_step = 8.0 * n * len(points)
+    value = in_bytes_step / (elapsed / args.steps) / 1e9
+
+    # per direction and per sweep point, event-timed on the launch stream
+    def timed(fn, pt, iters):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn(pt)
+        e0.record()
+        for _ in range(iters):
+            fn(pt)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    detail = []
+    kern_time = {}
+    kern_bytes = {}
+    for pt in points:
+        c_ms = timed(do_compress, pt, args.steps)
+        d_ms = timed(do_decompress, pt, args.steps)
+        rc, kc = B.profile_compress(keys, values, pt["p"], pt["out"], obytes, status, ws, args.steps, n=n,
+                                    out_capacity=pt["cap"])
+        assert rc == B.OK
+        rc, kd = B.profile_decompress(pt["out"], pt["bytes"], pt["keys_out"], pt["vals_out"], count, status, dws,
+                                      args.steps, capacity=pt["d"])
+        assert rc == B.OK
+        d, sb = pt["d"], pt["bytes"]
+        # algorithmic bytes per launch (what the method itself has to move)
+        alg = {
+            "abs_sum": 4.0 * n,                                  # every value once
+            "encode_values": 4.0 * n + 4.0 * d + d + 4.0 * d,    # values, keys of survivors, code bytes, compacted keys
+            "encode_keys": 4.0 * d + (sb - 64 - d),              # compacted keys in, directory + key blocks out
+            "decode": sb + 8.0 * d,                              # stream in, (key, value) pairs out
+        }
+        for k, v in {**kc, **{"decode": kd["decode"], "decode_setup": kd["setup"]}}.items():
+            kern_time[k] = kern_time.get(k, 0.0) + v
+        for k, v in alg.items():
+            kern_bytes[k] = kern_bytes.get(k, 0.0) + v
+        comp_alg = 8.0 * n + 13.0 * d + sb                       # two value passes + survivor traffic + stream
+        detail.append(dict(keep=pt["keep"], base=pt["p"].base, d=d, stream_bytes=sb, ratio=8.0 * n / sb,
+                           bits_per_key=8.0 * (sb - 64 - d) / max(d, 1),
+                           compress_ms=c_ms, decompress_ms=d_ms,
+                           compress_input_GBps=8.0 * n / c_ms / 1e6, decompress_input_GBps=8.0 * n / d_ms / 1e6,
+                           compress_elements_per_s=n / c_ms * 1e3,
+                           compress_hbm_frac=comp_alg / c_ms / 1e6 / HBM_PEAK_GBPS,
+                           decompress_hbm_frac=(sb + 8.0 * d) / d_ms / 1e6 / HBM_PEAK_GBPS,
+                           kernels_ms={**kc, **{"decode_" + k: v for k, v in kd.items()}}))
+
+    dominant = max(("abs_sum", "encode_values"), key=lambda k: kern_time[k])
+    kernels = {k: dict(ms_total=kern_time[k], achieved_GBps=kern_bytes[k] / kern_time[k] / 1e6,
+                       frac=kern_bytes[k] / kern_time[k] / 1e6 / HBM_PEAK_GBPS) for k in kern_bytes}
+    launches = len(points)
+    roofline = dict(bound="hbm", kernel="k_" + dominant,
+                    achieved=kern_bytes[dominant] / kern_time[dominant] / 1e6, peak=HBM_PEAK_GBPS, unit="GB/s",
+                    frac=kern_bytes[dominant] / kern_time[dominant] / 1e6 / HBM_PEAK_GBPS,
+                    traffic=None,
+                    avg_launch_ms=kern_time[dominant] / launches,
+                    algorithmic_bytes_per_launch=kern_bytes[dominant] / launches)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ref
+        m = min(args.cpu_sample, n)
+        sk, sv = w.keys[:m], w.values[:m]
+        sbases = W.solve_bases(sv, keeps)
+        t0 = time.perf_counter()
+        for b in sbases:
+            rc, st = ref.compress(sk, sv, ref.params(b))
+            assert rc == ref.OK
+            rc, k2, v2 = ref.decompress(st)
+            assert rc == ref.OK
+        cpu_s = time.perf_counter() - t0
+        cpu = dict(value=8.0 * m * len(sbases) / cpu_s / 1e9, unit="GB/s", cores=1, kind="oracle",
+                   sample=f"first {m} elements of {w.name}, all {len(sbases)} keep fractions, compress+decompress, "
+                          f"{cpu_s:.1f} s on one host core")
+
+    line = {
+        "metric": "compress & decompress input GB/s (% of HBM peak) on 1 MI355X; compression ratio",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 values, u32 keys; integer compares on IEEE bit patterns, f64 table", "data": "synthetic",
+        "config": {"workload": w.name, "n": n, "keep_fractions": keeps, "tau": 128, "flag_bits": 2,
+                   "block_keys": 1024, "step": "compress+decompress at every keep fraction"},
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "detail": detail,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

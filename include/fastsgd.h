@@ -126,6 +126,27 @@ fastsgd_status fastsgd_decompress_segmented(const void* d_streams, size_t total_
                                             uint64_t* d_pair_offsets, uint32_t* d_status,
                                             void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Measurement aids (Section 4.2 of the paper reports encoder and decoder time separately; these
+ * split each further, per kernel).  Same arguments and results as fastsgd_compress /
+ * fastsgd_decompress, run `iterations` (1..4096) times back to back with a HIP event recorded on
+ * hip_stream before the first and after every kernel; the call then WAITS for the stream and
+ * stores the average milliseconds per kernel in kernel_ms (host).  Kernel order, compress: clear,
+ * abs-sum, tables, encode-values, plan-keys, encode-keys, finalize; decompress: setup, decode.
+ * These two calls create and destroy HIP events; they are not meant for production paths. */
+#define FASTSGD_PROFILE_COMPRESS_KERNELS 7
+#define FASTSGD_PROFILE_DECOMPRESS_KERNELS 2
+fastsgd_status fastsgd_profile_compress(const uint32_t* d_keys, const float* d_values, uint64_t n,
+                                        const fastsgd_params* p,
+                                        void* d_out, size_t out_capacity,
+                                        uint64_t* d_out_bytes, uint32_t* d_status,
+                                        void* d_workspace, size_t workspace_bytes, void* hip_stream,
+                                        uint32_t iterations, float* kernel_ms);
+fastsgd_status fastsgd_profile_decompress(const void* d_stream, size_t stream_bytes,
+                                          uint32_t* d_keys_out, float* d_values_out, uint64_t capacity,
+                                          uint64_t* d_count, uint32_t* d_status,
+                                          void* d_workspace, size_t workspace_bytes, void* hip_stream,
+                                          uint32_t iterations, float* kernel_ms);
+
 #ifdef __cplusplus
 }
 #endif

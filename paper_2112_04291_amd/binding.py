@@ -16,7 +16,10 @@ OK, ERR_INVALID_ARG, ERR_BUFFER_TOO_SMALL, ERR_NONFINITE, ERR_UNSORTED_KEYS, ERR
 STATUS_NAMES = ["OK", "INVALID_ARG", "BUFFER_TOO_SMALL", "NONFINITE", "UNSORTED_KEYS", "CORRUPT_STREAM", "DEVICE"]
 
 EXPORTS = ["fastsgd_compressed_size", "fastsgd_workspace_size", "fastsgd_decompress_workspace_size",
-           "fastsgd_compress", "fastsgd_decompress", "fastsgd_compress_segmented", "fastsgd_decompress_segmented"]
+           "fastsgd_compress", "fastsgd_decompress", "fastsgd_compress_segmented", "fastsgd_decompress_segmented",
+           "fastsgd_profile_compress", "fastsgd_profile_decompress"]
+COMPRESS_KERNELS = ["clear", "abs_sum", "tables", "encode_values", "plan_keys", "encode_keys", "finalize"]
+DECOMPRESS_KERNELS = ["setup", "decode"]
 
 
 class Params(C.Structure):
@@ -56,6 +59,11 @@ def lib():
         L.fastsgd_compress_segmented.restype = C.c_int
         L.fastsgd_decompress_segmented.argtypes = [vp, sz, vp, u32, vp, vp, u64, vp, vp, vp, sz, vp]
         L.fastsgd_decompress_segmented.restype = C.c_int
+        fp = C.POINTER(C.c_float)
+        L.fastsgd_profile_compress.argtypes = [vp, vp, u64, PP, vp, sz, vp, vp, vp, sz, vp, u32, fp]
+        L.fastsgd_profile_compress.restype = C.c_int
+        L.fastsgd_profile_decompress.argtypes = [vp, sz, vp, vp, u64, vp, vp, vp, sz, vp, u32, fp]
+        L.fastsgd_profile_decompress.restype = C.c_int
         _lib = L
     return _lib
 
@@ -93,6 +101,27 @@ def decompress(stream, stream_bytes, keys_out, values_out, count, status, worksp
     capacity = keys_out.numel() if capacity is None else int(capacity)
     return lib().fastsgd_decompress(_p(stream), int(stream_bytes), _p(keys_out), _p(values_out), capacity, _p(count),
                                     _p(status), _p(workspace), workspace.numel() * workspace.element_size(), _stream())
+
+
+def profile_compress(keys, values, p, out, out_bytes, status, workspace, iterations, n=None, out_capacity=None):
+    """fastsgd_profile_compress: (host status, {kernel name: average ms}).  Waits for the stream."""
+    n = values.numel() if n is None else int(n)
+    cap = out.numel() * out.element_size() if out_capacity is None else int(out_capacity)
+    ms = (C.c_float * len(COMPRESS_KERNELS))()
+    rc = lib().fastsgd_profile_compress(_p(keys), _p(values), n, C.byref(p), _p(out), cap, _p(out_bytes), _p(status),
+                                        _p(workspace), workspace.numel() * workspace.element_size(), _stream(),
+                                        int(iterations), ms)
+    return rc, dict(zip(COMPRESS_KERNELS, [float(x) for x in ms]))
+
+
+def profile_decompress(stream, stream_bytes, keys_out, values_out, count, status, workspace, iterations, capacity=None):
+    """fastsgd_profile_decompress: (host status, {kernel name: average ms}).  Waits for the stream."""
+    capacity = keys_out.numel() if capacity is None else int(capacity)
+    ms = (C.c_float * len(DECOMPRESS_KERNELS))()
+    rc = lib().fastsgd_profile_decompress(_p(stream), int(stream_bytes), _p(keys_out), _p(values_out), capacity,
+                                          _p(count), _p(status), _p(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream(), int(iterations), ms)
+    return rc, dict(zip(DECOMPRESS_KERNELS, [float(x) for x in ms]))
 
 
 def _params_array(plist, n_segments):

@@ -63,12 +63,20 @@ static u32 cu_count() {
     return c;
 }
 
+// Optional per-kernel timing for the profiling entry points: events recorded on the launch stream
+// before the first kernel and after every kernel.
+struct Marks {
+    hipEvent_t* ev = nullptr;
+    u32 next = 0;
+    void mark(hipStream_t s) { if (ev) (void)hipEventRecord(ev[next++], s); }
+};
+
 static u32 clamp_grid(u64 want, u64 cap) { u64 g = want < cap ? want : cap; return (u32)(g ? g : 1); }
 
 static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, const u64* seg_offsets, u32 n_segments,
                                     const fastsgd_params* params, u32 params_stride, void* d_out, size_t out_capacity,
                                     u64* d_out_offsets, u32* d_status, void* d_ws, size_t ws_bytes, void* hip_stream,
-                                    bool single) {
+                                    bool single, Marks marks = Marks()) {
     if (!seg_offsets || !params || !d_out || !d_out_offsets || !d_status || !d_ws) return FASTSGD_ERR_INVALID_ARG;
     if (n_segments < 1 || n_segments > kMaxSegments || params_stride > 1) return FASTSGD_ERR_INVALID_ARG;
     if (((uintptr_t)d_out & 7) || ((uintptr_t)d_ws & 255) || ((uintptr_t)d_values & 3) || ((uintptr_t)d_keys & 3))
@@ -122,6 +130,7 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const u32 cus = cu_count();
 
+    marks.mark(stream);
     // clear control words and descriptors, store the segment table (48 segments per launch)
     const u64 zero_words = (pl.zero_end - pl.off_ctrl) / 8;
     for (u32 first = 0; first < n_segments; first += 48) {
@@ -134,6 +143,7 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
         else
             hipLaunchKernelGGL(k_store_segments, dim3(1), dim3(64), 0, stream, dsegs, b, first, count);
     }
+    marks.mark(stream);
 
     const u32 grid_sum_max = cus * 5;
     u32 tpc = (u32)(n_tiles / ((u64)grid_sum_max * 8));
@@ -141,22 +151,28 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     const u64 n_chunks = (n_tiles + tpc - 1) / tpc;
     hipLaunchKernelGGL(k_abs_sum, dim3(clamp_grid(n_chunks, grid_sum_max)), dim3(kThreads), 0, stream,
                        vbase, dsegs, dstates, n_segments, n_tiles, tpc, gbins, pl.n_slots, ctrl);
+    marks.mark(stream);
     hipLaunchKernelGGL(k_tables, dim3(n_segments), dim3(kThreads), 0, stream, dsegs, dstates, gbins, pl.n_slots, ctrl);
+    marks.mark(stream);
     hipLaunchKernelGGL(k_encode_values, dim3(clamp_grid(n_tiles, (u64)cus * 6)), dim3(kThreads), 0, stream,
                        kbase, vbase, dsegs, dstates, n_segments, n_tiles, tdesc, ckeys, codes, codes_cap, total_n, ctrl);
+    marks.mark(stream);
     hipLaunchKernelGGL(k_plan_keys, dim3(1), dim3(kThreads), 0, stream, dsegs, dstates, n_segments, n_tiles, tdesc, ctrl);
+    marks.mark(stream);
     hipLaunchKernelGGL(k_encode_keys, dim3(clamp_grid(max_items, (u64)cus * 4)), dim3(kThreads), 0, stream,
                        dsegs, dstates, n_segments, ckeys, idesc, binfo, out, (u64)out_capacity, ctrl);
+    marks.mark(stream);
     hipLaunchKernelGGL(k_finalize, dim3(clamp_grid(max_items, (u64)cus * 4)), dim3(kThreads), 0, stream,
                        dsegs, dstates, n_segments, idesc, binfo, codes, out, (u64)out_capacity, d_out_offsets,
                        single ? 1u : 0u, d_status, ctrl);
+    marks.mark(stream);
     return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
 }
 
 static fastsgd_status decompress_impl(const void* d_streams, size_t total_bytes, const u64* d_stream_offsets,
                                       u32 n_segments, u32* d_keys_out, float* d_values_out, u64 capacity,
                                       u64* d_counts, u32* d_status, void* d_ws, size_t ws_bytes, void* hip_stream,
-                                      bool single) {
+                                      bool single, Marks marks = Marks()) {
     if (!d_streams || !d_counts || !d_status || !d_ws) return FASTSGD_ERR_INVALID_ARG;
     if (n_segments < 1 || n_segments > kMaxSegments) return FASTSGD_ERR_INVALID_ARG;
     if (!single && !d_stream_offsets) return FASTSGD_ERR_INVALID_ARG;
@@ -171,6 +187,7 @@ static fastsgd_status decompress_impl(const void* d_streams, size_t total_bytes,
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const u32 cus = cu_count();
 
+    marks.mark(stream);
     if (single) {
         hipLaunchKernelGGL(k_decode_setup, dim3(1), dim3(128), 0, stream, streams, (u64)total_bytes,
                            (const u64*)nullptr, 1u, segs, ctrl, capacity, d_counts, d_status);
@@ -182,11 +199,41 @@ static fastsgd_status decompress_impl(const void* d_streams, size_t total_bytes,
             hipLaunchKernelGGL(k_decode_plan, dim3(1), dim3(64), 0, stream, segs, n_segments, capacity, ctrl,
                                d_counts, d_status);
     }
+    marks.mark(stream);
     // every key costs at least one value byte, so bytes/256 bounds the number of key blocks
     hipLaunchKernelGGL(k_decode, dim3(clamp_grid((u64)total_bytes / 256 + n_segments, (u64)cus * 4)), dim3(kThreads), 0,
                        stream, streams, segs, n_segments, ctrl, d_keys_out, d_values_out, d_counts,
                        single ? 1u : n_segments + 1u, d_status);
+    marks.mark(stream);
     return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
+}
+
+// Runs `call` `iterations` times with an event after every kernel and averages the gaps.
+template <class Call>
+static fastsgd_status profile_loop(u32 n_kernels, u32 iterations, float* kernel_ms, hipStream_t stream, Call call) {
+    if (!kernel_ms || iterations < 1 || iterations > 4096) return FASTSGD_ERR_INVALID_ARG;
+    const u32 per = n_kernels + 1;
+    std::vector<hipEvent_t> ev((size_t)per * iterations);
+    for (auto& e : ev)
+        if (hipEventCreate(&e) != hipSuccess) return FASTSGD_ERR_DEVICE;
+    fastsgd_status rc = FASTSGD_OK;
+    for (u32 it = 0; it < iterations && rc == FASTSGD_OK; ++it) {
+        Marks m;
+        m.ev = ev.data() + (size_t)it * per;
+        rc = call(m);
+    }
+    if (hipStreamSynchronize(stream) != hipSuccess) rc = FASTSGD_ERR_DEVICE;
+    for (u32 k = 0; k < n_kernels; ++k) kernel_ms[k] = 0.f;
+    if (rc == FASTSGD_OK) {
+        for (u32 it = 0; it < iterations; ++it)
+            for (u32 k = 0; k < n_kernels; ++k) {
+                float ms = 0.f;
+                (void)hipEventElapsedTime(&ms, ev[(size_t)it * per + k], ev[(size_t)it * per + k + 1]);
+                kernel_ms[k] += ms / (float)iterations;
+            }
+    }
+    for (auto& e : ev) (void)hipEventDestroy(e);
+    return rc;
 }
 
 }  // namespace fsgd
@@ -221,6 +268,32 @@ fastsgd_status fastsgd_compress(const uint32_t* d_keys, const float* d_values, u
     const u64 offs[2] = {0, n};
     return compress_impl(d_keys, d_values, offs, 1, p, 0, d_out, out_capacity, d_out_bytes, d_status, d_workspace,
                          workspace_bytes, hip_stream, true);
+}
+
+fastsgd_status fastsgd_profile_compress(const uint32_t* d_keys, const float* d_values, uint64_t n,
+                                        const fastsgd_params* p, void* d_out, size_t out_capacity,
+                                        uint64_t* d_out_bytes, uint32_t* d_status, void* d_workspace,
+                                        size_t workspace_bytes, void* hip_stream, uint32_t iterations,
+                                        float* kernel_ms) {
+    if (n > 0xFFFFFFFFull) return FASTSGD_ERR_INVALID_ARG;
+    const u64 offs[2] = {0, n};
+    return profile_loop(FASTSGD_PROFILE_COMPRESS_KERNELS, iterations, kernel_ms, static_cast<hipStream_t>(hip_stream),
+                        [&](Marks m) {
+                            return compress_impl(d_keys, d_values, offs, 1, p, 0, d_out, out_capacity, d_out_bytes,
+                                                 d_status, d_workspace, workspace_bytes, hip_stream, true, m);
+                        });
+}
+
+fastsgd_status fastsgd_profile_decompress(const void* d_stream, size_t stream_bytes, uint32_t* d_keys_out,
+                                          float* d_values_out, uint64_t capacity, uint64_t* d_count,
+                                          uint32_t* d_status, void* d_workspace, size_t workspace_bytes,
+                                          void* hip_stream, uint32_t iterations, float* kernel_ms) {
+    return profile_loop(FASTSGD_PROFILE_DECOMPRESS_KERNELS, iterations, kernel_ms,
+                        static_cast<hipStream_t>(hip_stream), [&](Marks m) {
+                            return decompress_impl(d_stream, stream_bytes, nullptr, 1, d_keys_out, d_values_out,
+                                                   capacity, d_count, d_status, d_workspace, workspace_bytes,
+                                                   hip_stream, true, m);
+                        });
 }
 
 fastsgd_status fastsgd_compress_segmented(const uint32_t* d_keys, const float* d_values, const uint64_t* seg_offsets,

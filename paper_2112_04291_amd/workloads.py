@@ -44,6 +44,21 @@ def solve_base(values: np.ndarray, keep_fraction: float, tau: int = TAU) -> floa
     return float(min(max(b, 1.0 + 2.0 ** -19), 16.0))
 
 
+def solve_bases(values: np.ndarray, keep_fractions, tau: int = TAU) -> List[float]:
+    """solve_base for several keep fractions with one partition of |values| (large arrays)."""
+    a = np.abs(values)                                   # float32: the order statistics are exact
+    n = a.size
+    s = float(a.sum(dtype=np.float64))
+    ks = [min(max(int(np.ceil(f * n)), 1), n) for f in keep_fractions]
+    part = np.partition(a, sorted(set(n - k for k in ks)))
+    out = []
+    for k in ks:
+        x = float(part[n - k])
+        b = (s / x) ** (1.0 / tau) * (1.0 + 1e-9) if x > 0.0 and s > 0.0 else 1.1
+        out.append(float(min(max(b, 1.0 + 2.0 ** -19), 16.0)))
+    return out
+
+
 def config1(seed: int = 1001, dim: int = 1_000_000, nnz: int = 100_000) -> Workload:
     """Tiny sparse gradient: uniform keys without replacement, Laplace(0, 1e-3) values."""
     rng = np.random.Generator(np.random.PCG64(seed))
