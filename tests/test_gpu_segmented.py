@@ -1,0 +1,88 @@
+"""GPU parity for the segmented batch (many independent gradients in one call) against the oracle."""
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2112_04291_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu():
+    import torch
+    from paper_2112_04291_amd import binding as B
+    from tests import gpu_util as G
+    assert torch.cuda.is_available()
+    return torch, B, G
+
+
+def check_segmented(keys, vals, offs, ref_plist, hip_plist):
+    torch, B, G = _gpu()
+    rc_ref, blob_ref, so_ref = ref.compress_segmented(keys, vals, offs, ref_plist)
+    assert rc_ref == ref.OK
+    rc, status, blob, so = G.hip_compress_segmented(keys, vals, offs, hip_plist)
+    assert rc == B.OK and status == 0, (rc, status)
+    assert np.array_equal(so, so_ref), (so[:8], so_ref[:8])
+    if not np.array_equal(blob, blob_ref):
+        bad = np.flatnonzero(blob != blob_ref)
+        seg = int(np.searchsorted(so_ref, bad[0], side="right") - 1)
+        raise AssertionError(f"{bad.size} bytes differ, first at {bad[0]} (segment {seg}, offset {bad[0] - int(so_ref[seg])})")
+    cap = int(sum(int(blob_ref[int(o) + 40:int(o) + 48].view("<u8")[0]) for o in so_ref[:-1]))
+    rc_ref, k_ref, v_ref, po_ref = ref.decompress_segmented(blob_ref, so_ref, cap)
+    rc, status, k, v, po = G.hip_decompress_segmented(blob_ref, so_ref, cap)
+    assert rc == B.OK and status == 0 and rc_ref == ref.OK
+    assert np.array_equal(po, po_ref) and np.array_equal(k, k_ref)
+    assert np.array_equal(v.view(np.uint32), v_ref.view(np.uint32))
+    # every stream of the batch is decodable on its own
+    nseg = len(so_ref) - 1
+    for i in sorted({0, nseg // 2, nseg - 1}):
+        a, b = int(so_ref[i]), int(so_ref[i + 1])
+        rc1, st1, k1, v1 = G.hip_decompress(blob_ref[a:b], capacity=int(po_ref[i + 1] - po_ref[i]))
+        assert rc1 == B.OK and st1 == 0
+        assert np.array_equal(k1, k_ref[int(po_ref[i]):int(po_ref[i + 1])])
+    return blob
+
+
+def test_small_batch_with_empty_and_tiny_segments():
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(21)
+    sizes = [0, 1, 700, 5000, 3, 0, 2500, 4096, 4097, 12289, 0]
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.uint64)
+    keys = np.concatenate([np.arange(s, dtype=np.uint32) for s in sizes])
+    vals = np.concatenate([rng.laplace(0, 10.0 ** -(i % 5 + 1), s) for i, s in enumerate(sizes)]).astype(np.float32)
+    args = [(1.04 + 0.01 * i, 128 - i, 1 + i % 3, 256 << (i % 3)) for i in range(len(sizes))]
+    check_segmented(keys, vals, offs, [ref.params(*a) for a in args], [B.params(*a) for a in args])
+    check_segmented(keys, vals, offs, ref.params(1.07), B.params(1.07))      # shared parameters
+
+
+def test_single_segment_batch_matches_plain_call():
+    torch, B, G = _gpu()
+    w = W.small_mixture(5, 100_000)
+    b = W.solve_base(w.values, 0.1)
+    blob = check_segmented(w.keys, w.values, np.array([0, w.values.size], np.uint64), ref.params(b), B.params(b))
+    rc, status, st, _ = G.hip_compress(w.keys, w.values, B.params(b))
+    assert np.array_equal(blob, st)
+
+
+def test_config5_scaled_down():
+    """160 tensors, log-uniform sizes, per-tensor Laplace scale, per-tensor base keeping about 1%."""
+    torch, B, G = _gpu()
+    w = W.config5(lo=256, hi=262_144, total_range=(3_500_000, 4_000_000))
+    offs = w.seg_offsets
+    bases = [W.solve_base(w.values[int(offs[i]):int(offs[i + 1])], 0.01) for i in range(len(offs) - 1)]
+    blob = check_segmented(w.keys, w.values, offs, [ref.params(b) for b in bases], [B.params(b) for b in bases])
+    ratio = 8.0 * w.values.size / blob.size
+    assert ratio > 50
+
+
+def test_batch_with_a_nonfinite_segment_fails_as_a_whole():
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(3)
+    sizes = [5000, 6000, 7000]
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.uint64)
+    keys = np.concatenate([np.arange(s, dtype=np.uint32) for s in sizes])
+    vals = rng.laplace(0, 1e-3, sum(sizes)).astype(np.float32)
+    vals[5000 + 17] = np.inf
+    rc, status, blob, so = G.hip_compress_segmented(keys, vals, offs, B.params(1.1))
+    assert rc == B.OK and status == B.ERR_NONFINITE and blob.size == 0 and np.all(so == 0)
+    assert ref.compress_segmented(keys, vals, offs, ref.params(1.1))[0] == ref.ERR_NONFINITE
