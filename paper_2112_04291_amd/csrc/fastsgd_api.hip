@@ -11,6 +11,7 @@ namespace fsgd {
 
 constexpr u64 kDecSegBytes = 640, kDecCtrlBytes = 64;   // >= sizeof(DecSeg), sizeof(DecCtrl)
 constexpr u32 kMaxSegments = 65536;
+constexpr u32 kMaxSumGrid = 2048;      // most workgroups the abs-sum pass of a single gradient is launched with
 static_assert(sizeof(DecSeg) <= kDecSegBytes && sizeof(DecCtrl) <= kDecCtrlBytes, "decoder workspace records");
 static_assert(sizeof(SegInfo) == 48 && sizeof(SegBatch) <= 3072, "segment table travels as a kernel argument");
 
@@ -31,16 +32,17 @@ static EncodePlan make_plan(u64 total_n, u32 n_segments, u32 min_kb) {
     EncodePlan pl{};
     pl.total_n = total_n;
     pl.n_segments = n_segments;
-    pl.n_slots = (n_segments == 1) ? 32u : 4u;
+    pl.n_slots = (n_segments == 1) ? kMaxSumGrid : 4u;           // abs-sum records per segment
     pl.n_tiles = total_n / kTile + 2ull * n_segments + 1;          // bound; a segment adds at most 2 partial tiles
     pl.max_items = total_n / min_kb + n_segments + 1;              // bound on key blocks (+1 per empty segment)
     u64 o = 0;
-    pl.off_ctrl = o;  o += 256;
-    pl.off_gbins = o; o += up((u64)n_segments * pl.n_slots * 2 * kBins * 8, 256);
+    pl.off_ctrl = o;  o += up(sizeof(Ctrl), 256);
     pl.off_tdesc = o; o += up(pl.n_tiles * 8, 256);
     pl.off_idesc = o; o += up(pl.max_items * 8, 256);
-    pl.off_segstate = o; o += up((u64)n_segments * sizeof(SegState), 256);   // holds the non-finite flags
-    pl.zero_end = o;
+    pl.off_segstate = o; o += up((u64)n_segments * sizeof(SegState), 256);
+    pl.zero_end = o;                                               // a single-gradient call clears up to here
+    pl.off_gbins = o; o += up((u64)n_segments * pl.n_slots * kBinWords * 8, 256);
+    pl.zero_end_batch = o;                                         // a batch also clears the abs-sum records
     pl.off_seginfo = o;  o += up((u64)n_segments * sizeof(SegInfo), 256);
     pl.off_binfo = o;    o += up(pl.max_items * sizeof(BlockInfo), 256);
     pl.off_ckeys = o;    o += up(total_n * 4, 256);
@@ -131,30 +133,37 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     const u32 cus = cu_count();
 
     marks.mark(stream);
-    // clear control words and descriptors, store the segment table (48 segments per launch)
-    const u64 zero_words = (pl.zero_end - pl.off_ctrl) / 8;
-    for (u32 first = 0; first < n_segments; first += 48) {
-        SegBatch b;
-        const u32 count = (n_segments - first < 48) ? n_segments - first : 48;
-        for (u32 i = 0; i < count; ++i) b.seg[i] = segs[first + i];
-        if (first == 0)
-            hipLaunchKernelGGL(k_init, dim3(clamp_grid((zero_words + 1023) / 1024, 2048)), dim3(256), 0, stream,
-                               reinterpret_cast<u64*>(ws + pl.off_ctrl), zero_words, dsegs, b, first, count);
-        else
-            hipLaunchKernelGGL(k_store_segments, dim3(1), dim3(64), 0, stream, dsegs, b, first, count);
+    const u64 zero_words = ((single ? pl.zero_end : pl.zero_end_batch) - pl.off_ctrl) / 8;
+    u64* zero_begin = reinterpret_cast<u64*>(ws + pl.off_ctrl);
+    if (!single) {
+        // clear control words, descriptors and abs-sum records; store the segment table (48 per launch)
+        for (u32 first = 0; first < n_segments; first += 48) {
+            SegBatch b;
+            const u32 count = (n_segments - first < 48) ? n_segments - first : 48;
+            for (u32 i = 0; i < count; ++i) b.seg[i] = segs[first + i];
+            if (first == 0)
+                hipLaunchKernelGGL(k_init, dim3(clamp_grid((zero_words + 1023) / 1024, 2048)), dim3(256), 0, stream,
+                                   zero_begin, zero_words, dsegs, b, first, count);
+            else
+                hipLaunchKernelGGL(k_store_segments, dim3(1), dim3(64), 0, stream, dsegs, b, first, count);
+        }
     }
     marks.mark(stream);
 
-    const u32 grid_sum_max = cus * 5;
-    u32 tpc = (u32)(n_tiles / ((u64)grid_sum_max * 8));
-    tpc = tpc < 1 ? 1 : (tpc > 8 ? 8 : tpc);
-    const u64 n_chunks = (n_tiles + tpc - 1) / tpc;
-    hipLaunchKernelGGL(k_abs_sum, dim3(clamp_grid(n_chunks, grid_sum_max)), dim3(kThreads), 0, stream,
-                       vbase, dsegs, dstates, n_segments, n_tiles, tpc, gbins, pl.n_slots, ctrl);
+    u32 sum_grid = cus * 4 < kMaxSumGrid ? cus * 4 : kMaxSumGrid;
+    sum_grid = clamp_grid(n_tiles, sum_grid);
+    if (single)
+        hipLaunchKernelGGL(k_abs_sum<true>, dim3(sum_grid), dim3(kThreads), 0, stream, vbase, dsegs, 1u, n_tiles,
+                           gbins, sum_grid, zero_begin, zero_words, segs[0], dsegs);
+    else
+        hipLaunchKernelGGL(k_abs_sum<false>, dim3(sum_grid), dim3(kThreads), 0, stream, vbase, dsegs, n_segments,
+                           n_tiles, gbins, pl.n_slots, zero_begin, (u64)0, segs[0], dsegs);
     marks.mark(stream);
-    hipLaunchKernelGGL(k_tables, dim3(n_segments), dim3(kThreads), 0, stream, dsegs, dstates, gbins, pl.n_slots, ctrl);
+    hipLaunchKernelGGL(k_tables, dim3(n_segments), dim3(kTableThreads), 0, stream, dsegs, dstates, gbins,
+                       single ? sum_grid : pl.n_slots, ctrl);
     marks.mark(stream);
-    hipLaunchKernelGGL(k_encode_values, dim3(clamp_grid(n_tiles, (u64)cus * 6)), dim3(kThreads), 0, stream,
+    hipLaunchKernelGGL(k_encode_values, dim3(clamp_grid((n_tiles + kTicketLanes - 1) / kTicketLanes, (u64)cus * 2)),
+                       dim3(kTicketLanes * kWave), 0, stream,
                        kbase, vbase, dsegs, dstates, n_segments, n_tiles, tdesc, ckeys, codes, codes_cap, total_n, ctrl);
     marks.mark(stream);
     hipLaunchKernelGGL(k_plan_keys, dim3(1), dim3(kThreads), 0, stream, dsegs, dstates, n_segments, n_tiles, tdesc, ctrl);

@@ -36,7 +36,7 @@ struct SegInfo {
 struct SegState {
     double sum;         // Algorithm 1 line 1
     u32 thr_bits;       // bit pattern of the early-stop threshold (Algorithm 1 line 2); 0xFFFFFFFF = keep nothing
-    u32 nonfinite;
+    u32 pad0;
     u64 rank_begin;     // global rank of the segment's first survivor
     u64 d;              // survivors
     u64 item_begin;     // first work item (key block) of the segment
@@ -49,18 +49,30 @@ struct SegState {
 // Per key block, filled by the key encoder, consumed by the finaliser.
 struct BlockInfo { u32 preKey, M, payload_bits, size8; };
 
+// A returning atomic on one address costs about 11 ns on this part and they serialise, so one ticket
+// counter per tile would cap a pass at ~90 M tiles/s.  Tiles are therefore dealt from kLanesOfTickets
+// counters on separate cache lines: counter c hands out tiles c, c + 8, c + 16, ...; wave c of every
+// workgroup draws from counter c.  Any resident workgroup owns a wave for every counter, so the lowest
+// unpublished tile is always either in work or about to be drawn by a wave that is not waiting:
+// the look-back cannot deadlock, whatever part of the grid is resident.
+constexpr u32 kTicketLanes = 8;
+constexpr u32 kTicketStride = 32;             // u32 words between counters (128 bytes)
+
 struct Ctrl {
-    u32 ticket_sum, ticket_val, ticket_key, pad0;
+    u32 ticket_val[kTicketLanes * kTicketStride];
+    u32 ticket_key[kTicketLanes * kTicketStride];
     u32 status;         // first device-detected fastsgd_status
-    u32 pad1;
+    u32 done_key;       // key-encoder work items finished
     u64 total_items;
     u64 total_d;
+    u64 pad[5];
 };
+static_assert(sizeof(Ctrl) == 2 * kTicketLanes * kTicketStride * 4 + 64, "control block layout");
 
 struct EncodePlan {     // host-computed carve-up of the workspace
     u64 n_tiles, max_items, total_n;
     u32 n_segments, n_slots;
-    u64 off_ctrl, off_gbins, off_tdesc, off_idesc, zero_end;   // [off_ctrl, zero_end) is cleared per call
+    u64 off_ctrl, off_gbins, off_tdesc, off_idesc, zero_end, zero_end_batch;   // [off_ctrl, zero_end*) is cleared per call
     u64 off_seginfo, off_segstate, off_binfo, off_ckeys, off_codes, total;
 };
 

@@ -68,10 +68,19 @@ __device__ __forceinline__ void load_tile(const float* __restrict__ values, cons
 // 64-bit integer.  Integer addition is associative, so any partition of the work gives the same
 // bins, and the sum can be rounded exactly once.  Every lane owns a private row of bins in shared
 // memory (one 64-bit add per element, no conflicts, no atomics between lanes); a workgroup folds
-// its lanes into (low-half sum, high-half sum) pairs and adds them to one of `n_slots` copies of
-// the segment's global bins.
-__device__ __forceinline__ void flush_bins(u64 (*bins)[kThreads], u64* gbins_seg, u32 n_slots, u32 maxa,
-                                           SegState* st) {
+// its lanes into (low-half sum, high-half sum) pairs.
+//
+// Records of kBinWords u64: words 2k, 2k+1 = low/high half sums of bin k, word 32 = non-finite flag.
+//   single gradient : every workgroup stores its one record at gbins[blockIdx.x] (plain stores, so
+//                     nothing has to be cleared beforehand), and the launch also clears the scan
+//                     descriptors and control words the later kernels rely on;
+//   batch           : a workgroup owns a contiguous run of tiles and adds a record to one of n_slots
+//                     copies of the segment's record each time it leaves a segment (atomics on
+//                     memory k_init cleared).
+constexpr u32 kBinWords = 2 * kBins + 2;
+
+template <bool SINGLE>
+__device__ __forceinline__ void flush_bins(u64 (*bins)[kThreads], u64* rec, u32 maxa) {
     __syncthreads();
     const u32 t = threadIdx.x;
     const u32 bin = t >> 4, part = t & 15u;          // 16 threads per bin, 16 lanes each
@@ -87,43 +96,77 @@ __device__ __forceinline__ void flush_bins(u64 (*bins)[kThreads], u64* gbins_seg
         lo += __shfl_xor((unsigned long long)lo, d, 16);
         hi += __shfl_xor((unsigned long long)hi, d, 16);
     }
-    if (part == 0) {
-        u64* g = gbins_seg + (u64)(blockIdx.x % n_slots) * (2 * kBins) + 2 * bin;
-        if (lo) atomicAdd((unsigned long long*)&g[0], (unsigned long long)lo);
-        if (hi) atomicAdd((unsigned long long*)&g[1], (unsigned long long)hi);
-    }
-    if (__any(maxa >= 0x7F800000u) && lane_id() == 0) atomicOr(&st->nonfinite, 1u);
-    __syncthreads();
+    const bool bad = __syncthreads_or(maxa >= 0x7F800000u);
+    if (SINGLE) {
+        if (part == 0) { rec[2 * bin] = lo; rec[2 * bin + 1] = hi; }
+        if (t == 0) { rec[2 * kBins] = bad ? 1u : 0u; rec[2 * kBins + 1] = 0; }
+    } else {
+        if (part == 0) {
+            if (lo) atomicAdd((unsigned long long*)&rec[2 * bin], (unsigned long long)lo);
+            if (hi) atomicAdd((unsigned long long*)&rec[2 * bin + 1], (unsigned long long)hi);
+        }
+        if (bad && t == 0) atomicOr((unsigned long long*)&rec[2 * kBins], 1ull);
 #pragma unroll
-    for (u32 b = 0; b < kBins; ++b) bins[b][t] = 0;
-    __syncthreads();
+        for (u32 b = 0; b < kBins; ++b) bins[b][t] = 0;
+        __syncthreads();
+    }
 }
 
+__device__ __forceinline__ void accumulate_tile(const u32 bits[4][4], u64 (*bins)[kThreads], u32& maxa) {
+    const u32 t = threadIdx.x;
+#pragma unroll
+    for (u32 r = 0; r < 4; ++r)
+#pragma unroll
+        for (u32 c = 0; c < 4; ++c) {
+            const u32 a = bits[r][c] & 0x7FFFFFFFu;
+            maxa = a > maxa ? a : maxa;
+            const u32 e = a >> 23;
+            const u32 e1 = e ? e : 1u;
+            const u32 m = a - ((e1 - 1u) << 23);          // significand with its leading one (none for denormals)
+            const u64 val = (u64)m << (e1 & 15u);
+            // a NaN/Inf lands in bin 15 as garbage; the record's flag makes the whole sum void
+            atomicAdd((unsigned long long*)&bins[e1 >> 4][t], (unsigned long long)val);
+        }
+}
+
+template <bool SINGLE>
 __global__ void __launch_bounds__(kThreads)
-k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, SegState* __restrict__ states,
-          u32 n_segments, u64 n_tiles, u32 tiles_per_chunk, u64* gbins, u32 n_slots, Ctrl* ctrl) {
+k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u32 n_segments, u64 n_tiles,
+          u64* gbins, u32 n_slots, u64* zero_begin, u64 zero_words, SegInfo single_seg, SegInfo* seg_store) {
     __shared__ u64 bins[kBins][kThreads];
-    __shared__ u32 s_chunk;
     const u32 t = threadIdx.x;
 #pragma unroll
     for (u32 b = 0; b < kBins; ++b) bins[b][t] = 0;
+    if (SINGLE) {
+        for (u64 i = (u64)blockIdx.x * kThreads + t; i < zero_words; i += (u64)gridDim.x * kThreads) zero_begin[i] = 0;
+        if (blockIdx.x == 0 && t == 0) seg_store[0] = single_seg;
+    }
     __syncthreads();
-
-    u32 cur_seg = 0xFFFFFFFFu, maxa = 0;
-    const u64 n_chunks = (n_tiles + tiles_per_chunk - 1) / tiles_per_chunk;
-    for (;;) {
-        if (t == 0) s_chunk = atomicAdd(&ctrl->ticket_sum, 1u);
-        __syncthreads();
-        const u64 chunk = s_chunk;
-        __syncthreads();
-        if (chunk >= n_chunks) break;
-        const u64 t_begin = chunk * tiles_per_chunk;
-        const u64 t_end = (t_begin + tiles_per_chunk < n_tiles) ? t_begin + tiles_per_chunk : n_tiles;
+    u32 maxa = 0;
+    const u64 G = gridDim.x;
+    const u64 per_wg = (n_tiles + G - 1) / G;
+    if (SINGLE) {
+        const TileGeom g0 = tile_geom(single_seg, 0);
+        for (u64 it = 0; it < per_wg; ++it) {
+            const u64 tile = it * G + blockIdx.x;             // neighbours in time are neighbours in memory
+            if (tile >= n_tiles) break;
+            TileGeom g = g0;
+            g.tile0 += tile * kTile;
+            g.full = (g.tile0 >= g.lo) && (g.tile0 + kTile <= g.hi);
+            u32 bits[4][4];
+            load_tile(values, g, bits);
+            accumulate_tile(bits, bins, maxa);
+        }
+        flush_bins<true>(bins, gbins + (u64)blockIdx.x * kBinWords, maxa);
+    } else {
+        u32 cur_seg = 0xFFFFFFFFu;
+        const u64 t_begin = blockIdx.x * per_wg;
+        const u64 t_end = (t_begin + per_wg < n_tiles) ? t_begin + per_wg : n_tiles;
         for (u64 tile = t_begin; tile < t_end; ++tile) {
-            const u32 seg = (n_segments == 1) ? 0u : find_segment(segs, n_segments, tile);
+            const u32 seg = find_segment(segs, n_segments, tile);
             if (seg != cur_seg) {
                 if (cur_seg != 0xFFFFFFFFu) {
-                    flush_bins(bins, gbins + (u64)cur_seg * n_slots * (2 * kBins), n_slots, maxa, &states[cur_seg]);
+                    flush_bins<false>(bins, gbins + ((u64)cur_seg * n_slots + blockIdx.x % n_slots) * kBinWords, maxa);
                     maxa = 0;
                 }
                 cur_seg = seg;
@@ -131,85 +174,105 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, Se
             const TileGeom g = tile_geom(segs[seg], tile);
             u32 bits[4][4];
             load_tile(values, g, bits);
-#pragma unroll
-            for (u32 r = 0; r < 4; ++r)
-#pragma unroll
-                for (u32 c = 0; c < 4; ++c) {
-                    const u32 a = bits[r][c] & 0x7FFFFFFFu;
-                    maxa = a > maxa ? a : maxa;
-                    const u32 e = a >> 23;
-                    const u32 m = (a & 0x7FFFFFu) | (e ? 0x800000u : 0u);
-                    const u32 e1 = e ? e : 1u;
-                    const u64 val = (u64)m << (e1 & 15u);
-                    if (e != 255u)     // NaN/Inf: reported through maxa, kept out of the bins
-                        atomicAdd((unsigned long long*)&bins[e1 >> 4][t], (unsigned long long)val);
-                }
+            accumulate_tile(bits, bins, maxa);
         }
+        if (cur_seg != 0xFFFFFFFFu)
+            flush_bins<false>(bins, gbins + ((u64)cur_seg * n_slots + blockIdx.x % n_slots) * kBinWords, maxa);
     }
-    if (cur_seg != 0xFFFFFFFFu)
-        flush_bins(bins, gbins + (u64)cur_seg * n_slots * (2 * kBins), n_slots, maxa, &states[cur_seg]);
 }
 
 // ---------------------------------------------------------------------------------------------
-// One workgroup (one wave) per segment: fold the bins into a wide integer counting units of 2^-150,
-// round once to binary64 (nearest, ties to even), then the boundary table.
-__global__ void __launch_bounds__(kThreads)
+// One workgroup per segment: add up the segment's records, fold the bins into a 384-bit integer
+// counting units of 2^-150, round once to binary64 (nearest, ties to even), then the boundary table.
+constexpr u32 kTableThreads = 1024;
+
+__device__ __forceinline__ void wide_add(u64 (&L)[6], u64 x, u32 bitpos) {   // bitpos is a compile-time constant after unrolling
+    const u32 i = bitpos >> 6, sh = bitpos & 63u;
+    u64 parts[2] = {x << sh, sh ? (x >> (64u - sh)) : 0ull};
+    u64 carry = 0;
+#pragma unroll
+    for (u32 j = 0; j < 6; ++j) {
+        if (j >= i) {
+            const u64 add = (j - i < 2) ? parts[j - i] : 0ull;
+            const u64 s1 = L[j] + add;
+            const u64 c1 = s1 < add ? 1ull : 0ull;
+            const u64 s2 = s1 + carry;
+            const u64 c2 = s2 < carry ? 1ull : 0ull;
+            L[j] = s2;
+            carry = c1 + c2;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kTableThreads)
 k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const u64* __restrict__ gbins,
          u32 n_slots, Ctrl* ctrl) {
-    __shared__ u64 s_part[2 * kBins];
-    __shared__ u32 s_limb[16];
+    __shared__ u64 s_part[kTableThreads / 64][64];
     __shared__ double s_P[129];
     __shared__ double s_sum;
     const u32 seg = blockIdx.x, t = threadIdx.x;
     const SegInfo info = segs[seg];
     SegState* st = &states[seg];
-    if (t < 2 * kBins) {
-        const u64* g = gbins + (u64)seg * n_slots * (2 * kBins);
-        u64 x = 0;
-        for (u32 s = 0; s < n_slots; ++s) x += g[(u64)s * (2 * kBins) + t];
-        s_part[t] = x;
-    }
-    if (t < 16) s_limb[t] = 0;
-    __syncthreads();
-    if (t == 0) {
-        // bin k holds lo + hi * 2^32 in units of 2^(16k - 150)
-        for (u32 k = 0; k < kBins; ++k)
-            for (u32 h = 0; h < 2; ++h) {
-                const u64 x = s_part[2 * k + h];
-                const u32 bitpos = 16u * k + 32u * h;
-                // add the two 32-bit halves of x, each shifted by bitpos % 32, at limb bitpos / 32
-                for (u32 half = 0; half < 2; ++half) {
-                    u64 piece = ((x >> (32 * half)) & 0xFFFFFFFFull) << (bitpos & 31u);
-                    u32 li = (bitpos >> 5) + half;
-                    while (piece) {
-                        u64 s = (u64)s_limb[li] + (piece & 0xFFFFFFFFull);
-                        s_limb[li] = (u32)s;
-                        piece = (piece >> 32) + (s >> 32);
-                        ++li;
-                    }
+    {
+        // thread (group, word) adds up word `word` of records group, group+16, ...; 64 loads in flight
+        const u32 word = t & 63u, group = t >> 6;
+        constexpr u32 kGroups = kTableThreads / 64;
+        u64 acc[4] = {0, 0, 0, 0};
+        if (word < kBinWords) {
+            const u64* g = gbins + (u64)seg * n_slots * kBinWords + word;
+            for (u32 base = group; base < n_slots; base += kGroups * 64) {
+#pragma unroll
+                for (u32 j = 0; j < 64; ++j) {
+                    const u32 sl = base + kGroups * j;
+                    if (sl < n_slots) acc[j & 3] += g[(u64)sl * kBinWords];
                 }
             }
-        int top = -1;
-        for (int li = 15; li >= 0; --li)
-            if (s_limb[li]) { top = li * 32 + 31 - __builtin_clz(s_limb[li]); break; }
+        }
+        s_part[group][word] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    }
+    __syncthreads();
+    if (t == 0) {
+        u64 rec[kBinWords];
+#pragma unroll
+        for (u32 w = 0; w < kBinWords; ++w) {
+            u64 x = 0;
+#pragma unroll
+            for (u32 g = 0; g < kTableThreads / 64; ++g) x += s_part[g][w];
+            rec[w] = x;
+        }
+        // bin k holds lo + hi * 2^32 in units of 2^(16k - 150)
+        u64 L[6] = {0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (u32 k = 0; k < kBins; ++k) {
+            wide_add(L, rec[2 * k], 16u * k);
+            wide_add(L, rec[2 * k + 1], 16u * k + 32u);
+        }
+        int hi_i = -1;
+#pragma unroll
+        for (int i = 0; i < 6; ++i) if (L[i]) hi_i = i;
         double sum = 0.0;
-        if (top >= 0) {
-            u64 q = 0;
-            const int lo = top - 52;
-            for (int b = top; b >= lo && b >= 0; --b) q = (q << 1) | ((s_limb[b >> 5] >> (b & 31)) & 1u);
-            if (lo > 0) {
-                const u32 guard = (s_limb[(lo - 1) >> 5] >> ((lo - 1) & 31)) & 1u;
-                u32 sticky = 0;
-                for (int b = lo - 2; b >= 0 && !sticky; --b) sticky = (s_limb[b >> 5] >> (b & 31)) & 1u;
-                if (guard && (sticky || (q & 1))) ++q;
-            } else {
-                q <<= (52 - top);            // fewer than 53 bits: exact, left-align the significand
+        if (hi_i >= 0) {
+            u64 hi = 0, lo = 0;
+            bool below = false;                       // any set bit in limbs under `lo`
+#pragma unroll
+            for (int i = 0; i < 6; ++i) {
+                if (i == hi_i) hi = L[i];
+                if (i + 1 == hi_i) lo = L[i];
+                if (i + 1 < hi_i && L[i]) below = true;
             }
-            // value = q * 2^(max(lo,0) - 150) with q in [2^52, 2^53]; q = 2^53 carries into the exponent
+            const u32 s = 63u - (u32)__builtin_clzll(hi);       // top bit inside its limb
+            const int top = hi_i * 64 + (int)s;
+            // 64-bit window whose most significant bit is the sum's leading one
+            const u64 W = (s == 63u) ? hi : ((hi << (63u - s)) | (lo >> (s + 1u)));
+            const bool lost = below || (s != 63u && (lo & ((1ull << (s + 1u)) - 1ull)) != 0);
+            u64 q = W >> 11;                                    // 53 significant bits
+            const bool guard = (W >> 10) & 1ull;
+            const bool sticky = (W & 0x3FFull) != 0 || lost;
+            if (guard && (sticky || (q & 1ull))) ++q;           // q = 2^53 carries into the exponent below
             const u64 bits = ((u64)(top - 150 + 1023) << 52) + (q - (1ull << 52));
             sum = __longlong_as_double((long long)bits);
         }
-        const bool bad = st->nonfinite != 0;
+        const bool bad = rec[2 * kBins] != 0;
         if (bad) set_status(ctrl, FASTSGD_ERR_NONFINITE);
         st->sum = bad ? 0.0 : sum;
         s_sum = bad ? 0.0 : sum;
@@ -226,110 +289,158 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Second pass over the values: keep |v| >= threshold (one unsigned compare on bit patterns), rank
-// the survivors in element order (wave scans inside the tile, decoupled look-back across tiles),
-// then -- densely over the survivors only -- find the code by binary search in the boundary table,
-// fetch the key, and write code byte and key at the survivor's global rank.
-__global__ void __launch_bounds__(kThreads)
+// Second pass over the values (Algorithm 1 lines 4-10).  Every WAVE works on its own tiles of 4096
+// elements and never waits for another wave of its workgroup, so memory latency of one wave hides
+// behind the arithmetic of the others:
+//   ticket -> 16 float4 loads per lane -> keep test |v| >= threshold (unsigned compare of bit
+//   patterns, 64 ballots) -> survivor count -> decoupled look-back gives the tile's first global rank
+//   -> survivors are staged in the wave's slice of shared memory at their rank inside the tile
+//   (ballot + mbcnt) -> densely over the staged survivors only: code by binary search in the boundary
+//   table, key fetch, code byte and key written at the global rank.
+// Lane `lane` holds, for row r = 0..15, elements tile0 + r*256 + lane*4 + {0..3}.
+constexpr u32 kRows = kTile / 256;       // 16 float4 rows per wave tile
+constexpr u32 kStage = 1024;             // staged survivors per wave and round (4 rows can never exceed it)
+
+// |v| >= threshold as a float compare with the |x| source modifier: for non-negative finite floats
+// (denormals are preserved in this build) it orders exactly like the unsigned compare of the bit
+// patterns, and a NaN threshold (bit pattern 0xFFFFFFFF = keep nothing) compares false.
+__device__ __forceinline__ bool keeps(u32 value_bits, float threshold) {
+    return __builtin_fabsf(__uint_as_float(value_bits)) >= threshold;
+}
+
+__device__ __forceinline__ u32 lanes_below(u64 mask) {
+    return __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
+}
+
+__global__ void __launch_bounds__(kTicketLanes * kWave) __attribute__((amdgpu_waves_per_eu(4, 8)))
 k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                 const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
                 u64 n_tiles, u64* tdesc, u32* __restrict__ ckeys, uint8_t* __restrict__ codes,
                 u64 codes_capacity, u64 ckeys_capacity, Ctrl* ctrl) {
-    __shared__ u32 s_B[128];
-    __shared__ u32 s_val[kTile];
-    __shared__ uint16_t s_idx[kTile];
-    __shared__ u32 s_wtot[kWaves];
-    __shared__ u64 s_base;
-    __shared__ u32 s_tile;
-    const u32 t = threadIdx.x, lane = lane_id(), w = wave_id();
+    __shared__ u32 s_Ball[kTicketLanes][128];
+    __shared__ u32 s_valall[kTicketLanes][kStage];
+    __shared__ uint16_t s_idxall[kTicketLanes][kStage];
+    const u32 lane = lane_id();
+    const u32 w = (u32)__builtin_amdgcn_readfirstlane((int)wave_id());   // tell the compiler it is wave-uniform
+    u32* s_B = s_Ball[w];
+    u32* s_val = s_valall[w];
+    uint16_t* s_idx = s_idxall[w];
     u32 cur_seg = 0xFFFFFFFFu, thr = 0xFFFFFFFFu, tau = 1;
 
     for (;;) {
-        if (t == 0) s_tile = atomicAdd(&ctrl->ticket_val, 1u);
-        __syncthreads();
-        const u64 tile = s_tile;
+        u32 ticket = 0;
+        if (lane == 0) ticket = atomicAdd(&ctrl->ticket_val[w * kTicketStride], 1u);
+        const u64 tile = (u64)(u32)__builtin_amdgcn_readfirstlane((int)ticket) * kTicketLanes + w;
         if (tile >= n_tiles) break;
         const u32 seg = (n_segments == 1) ? 0u : find_segment(segs, n_segments, tile);
         if (seg != cur_seg) {
             cur_seg = seg;
             thr = states[seg].thr_bits;
             tau = segs[seg].tau;
-            if (t < 128) s_B[t] = states[seg].B[t];
+            s_B[lane] = states[seg].B[lane];
+            s_B[lane + 64] = states[seg].B[lane + 64];
         }
         const TileGeom g = tile_geom(segs[seg], tile);
-        u32 bits[4][4];
-        load_tile(values, g, bits);
-
-        u32 kb[4], cnt[4];
+        const float* tvals = values + g.tile0;
+        u32 bits[kRows][4];
+        if (g.full) {
+            const uint4* src = reinterpret_cast<const uint4*>(tvals) + lane;
 #pragma unroll
-        for (u32 r = 0; r < 4; ++r) {
-            u32 m = 0;
+            for (u32 r = 0; r < kRows; ++r) {
+                const uint4 q = src[r * 64u];
+                bits[r][0] = q.x; bits[r][1] = q.y; bits[r][2] = q.z; bits[r][3] = q.w;
+            }
+        } else {
+            // slots [lo_off, hi_off) of the tile belong to the segment; others read a clamped (valid)
+            // address and are replaced by zero, which never survives
+            const u32 lo_off = g.lo > g.tile0 ? (u32)(g.lo - g.tile0) : 0u;
+            const u32 hi_off = g.hi - g.tile0 < kTile ? (u32)(g.hi - g.tile0) : kTile;
 #pragma unroll
-            for (u32 c = 0; c < 4; ++c) m |= ((bits[r][c] & 0x7FFFFFFFu) >= thr ? 1u : 0u) << c;
-            kb[r] = m;
-            cnt[r] = __popc(m);
-        }
-        // wave-level ranks: two packed 16-bit scans cover the four rows
-        const u32 p01 = cnt[0] | (cnt[1] << 16), p23 = cnt[2] | (cnt[3] << 16);
-        const u32 i01 = wave_incl_scan(p01), i23 = wave_incl_scan(p23);
-        const u32 t01 = __shfl(i01, 63, 64), t23 = __shfl(i23, 63, 64);
-        u32 rowbase[4], excl[4];
-        rowbase[0] = 0;
-        rowbase[1] = t01 & 0xFFFFu;
-        rowbase[2] = rowbase[1] + (t01 >> 16);
-        rowbase[3] = rowbase[2] + (t23 & 0xFFFFu);
-        const u32 wave_total = rowbase[3] + (t23 >> 16);
-        excl[0] = (i01 & 0xFFFFu) - cnt[0];
-        excl[1] = (i01 >> 16) - cnt[1];
-        excl[2] = (i23 & 0xFFFFu) - cnt[2];
-        excl[3] = (i23 >> 16) - cnt[3];
-        if (lane == 0) s_wtot[w] = wave_total;
-        __syncthreads();
-        u32 wave_base = 0, tile_total = 0;
+            for (u32 r = 0; r < kRows; ++r) {
 #pragma unroll
-        for (u32 k = 0; k < kWaves; ++k) {
-            const u32 x = s_wtot[k];
-            if (k < w) wave_base += x;
-            tile_total += x;
-        }
-        if (w == 0) {
-            u32 gave_up = 0;
-            const u64 base = lookback_exclusive(tdesc, tile, tile_total, &gave_up);
-            if (lane == 0) {
-                s_base = base;
-                if (gave_up) set_status(ctrl, FASTSGD_ERR_DEVICE);
+                for (u32 c = 0; c < 4; ++c) {
+                    const u32 off = r * 256u + lane * 4u + c;
+                    const u32 cl = off < lo_off ? lo_off : (off >= hi_off ? hi_off - 1u : off);
+                    const u32 x = __float_as_uint(tvals[cl]);
+                    bits[r][c] = (cl == off) ? x : 0u;
+                }
+                __builtin_amdgcn_sched_barrier(0);      // rare path: keep its address arithmetic row-local
             }
         }
-        // stage survivors (value bits + slot in the tile) at their rank inside the tile
+        // survivors of the tile: per-lane count, then one wave reduction
+        const float thr_f = __uint_as_float(thr);
+        u32 mine = 0;
 #pragma unroll
-        for (u32 r = 0; r < 4; ++r) {
-            u32 pos = wave_base + rowbase[r] + excl[r];
+        for (u32 r = 0; r < kRows; ++r)
+#pragma unroll
+            for (u32 c = 0; c < 4; ++c) mine += keeps(bits[r][c], thr_f) ? 1u : 0u;
+#pragma unroll
+        for (u32 d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d, 64);
+        const u32 total = (u32)__builtin_amdgcn_readfirstlane((int)mine);
+        u32 gave_up = 0;
+        const u64 base = lookback_exclusive(tdesc, tile, total, &gave_up);
+        if (gave_up && lane == 0) set_status(ctrl, FASTSGD_ERR_DEVICE);
+        if (total == 0) continue;
+
+        const u32* tkeys = keys + g.tile0;
+        // one row: stage its survivors behind `staged` earlier ones; returns the new count
+        float thr_s = thr_f;
+        asm volatile("" : "+s"(thr_s));     // an opaque copy: the compare masks of the count pass stay dead
+        auto stage_row = [&](const u32 (&row)[4], u32 r, u32 staged) -> u32 {
+            u64 m[4];
+            u32 below = 0, rowcnt = 0;
+#pragma unroll
+            for (u32 c = 0; c < 4; ++c) {
+                m[c] = __ballot(keeps(row[c], thr_s));
+                below += lanes_below(m[c]);
+                rowcnt += (u32)__popcll(m[c]);
+            }
+            u32 pos = staged + below;
 #pragma unroll
             for (u32 c = 0; c < 4; ++c)
-                if (kb[r] >> c & 1u) {
-                    s_val[pos] = bits[r][c];
-                    s_idx[pos] = (uint16_t)(w * 1024u + r * 256u + lane * 4u + c);
+                if (keeps(row[c], thr_s)) {
+                    s_val[pos] = row[c];
+                    s_idx[pos] = (uint16_t)(r * 256u + lane * 4u + c);
                     ++pos;
                 }
-        }
-        __syncthreads();
-        const u64 base = s_base;
-        for (u32 j = t; j < tile_total; j += kThreads) {
-            const u32 vb = s_val[j];
-            const u32 a = vb & 0x7FFFFFFFu;
-            // smallest code c in [1, tau] with a >= B[c]  (B non-increasing, a >= B[tau])
-            u32 lo = 1, hi = tau;
-            while (lo < hi) {
-                const u32 mid = (lo + hi) >> 1;
-                if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
+            return staged + rowcnt;
+        };
+        // the staged survivors [0, cnt) have global ranks base + rank_off + j
+        auto write_staged = [&](u32 cnt, u32 rank_off) {
+            __builtin_amdgcn_wave_barrier();
+            for (u32 j = lane; j < cnt; j += 64u) {
+                const u32 vb = s_val[j];
+                const u32 a = vb & 0x7FFFFFFFu;
+                // smallest code c in [1, tau] with a >= B[c]  (B non-increasing, a >= B[tau])
+                u32 lo = 1, hi = tau;
+                while (lo < hi) {
+                    const u32 mid = (lo + hi) >> 1;
+                    if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
+                }
+                const u32 key = tkeys[s_idx[j]];
+                const u64 rank = base + rank_off + j;
+                if (rank < codes_capacity) codes[rank] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
+                else set_status(ctrl, FASTSGD_ERR_BUFFER_TOO_SMALL);
+                if (rank < ckeys_capacity) ckeys[rank] = key;
             }
-            const u32 key = keys[g.tile0 + s_idx[j]];
-            const u64 rank = base + j;
-            if (rank < codes_capacity) codes[rank] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
-            else set_status(ctrl, FASTSGD_ERR_BUFFER_TOO_SMALL);
-            if (rank < ckeys_capacity) ckeys[rank] = key;
+            __builtin_amdgcn_wave_barrier();
+        };
+        if (total <= kStage) {
+            u32 staged = 0;
+#pragma unroll
+            for (u32 r = 0; r < kRows; ++r) staged = stage_row(bits[r], r, staged);
+            write_staged(total, 0);
+        } else {
+            u32 done = 0;
+#pragma unroll
+            for (u32 q = 0; q < kRows / 4; ++q) {
+                u32 staged = 0;
+#pragma unroll
+                for (u32 rr = 0; rr < 4; ++rr) staged = stage_row(bits[4 * q + rr], 4 * q + rr, staged);
+                write_staged(staged, done);
+                done += staged;
+            }
         }
-        __syncthreads();
     }
 }
 
@@ -404,7 +515,7 @@ k_encode_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ sta
     const u64 total_items = ctrl->total_items;
 
     for (;;) {
-        if (t == 0) s_item_lo = atomicAdd(&ctrl->ticket_key, 1u);   // items < 2^32
+        if (t == 0) s_item_lo = atomicAdd(&ctrl->ticket_key[0], 1u);   // items < 2^32
         __syncthreads();
         const u64 item = s_item_lo;
         if (item >= total_items) break;
