@@ -133,15 +133,16 @@ def main():
         # algorithmic bytes per launch (what the method itself has to move)
         alg = {
             "abs_sum": 4.0 * n,                                  # every value once
-            "encode_values": 4.0 * n + 4.0 * d + d + 4.0 * d,    # values, keys of survivors, code bytes, compacted keys
-            "encode_keys": 4.0 * d + (sb - 64 - d),              # compacted keys in, directory + key blocks out
+            "encode_values": 4.0 * n + 4.0 * d + 5.0 * d,        # values; keys of survivors; key + code byte to scratch
+            "measure_keys": 4.0 * d,                             # surviving keys
+            "pack_keys": 5.0 * d + (sb - 64),                    # surviving keys and code bytes in, stream out
             "decode": sb + 8.0 * d,                              # stream in, (key, value) pairs out
         }
         for k, v in {**kc, **{"decode": kd["decode"], "decode_setup": kd["setup"]}}.items():
             kern_time[k] = kern_time.get(k, 0.0) + v
         for k, v in alg.items():
             kern_bytes[k] = kern_bytes.get(k, 0.0) + v
-        comp_alg = 8.0 * n + 13.0 * d + sb                       # two value passes + survivor traffic + stream
+        comp_alg = 8.0 * n + 18.0 * d + sb                       # two value passes + survivor traffic + stream
         detail.append(dict(keep=pt["keep"], base=pt["p"].base, d=d, stream_bytes=sb, ratio=8.0 * n / sb,
                            bits_per_key=8.0 * (sb - 64 - d) / max(d, 1),
                            compress_ms=c_ms, decompress_ms=d_ms,

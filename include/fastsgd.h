@@ -131,9 +131,9 @@ fastsgd_status fastsgd_decompress_segmented(const void* d_streams, size_t total_
  * fastsgd_decompress, run `iterations` (1..4096) times back to back with a HIP event recorded on
  * hip_stream before the first and after every kernel; the call then WAITS for the stream and
  * stores the average milliseconds per kernel in kernel_ms (host).  Kernel order, compress: clear,
- * abs-sum, tables, encode-values, plan-keys, encode-keys, finalize; decompress: setup, decode.
+ * abs-sum, tables, encode-values, plan-keys, measure-keys, scan-items, pack-keys; decompress: setup, decode.
  * These two calls create and destroy HIP events; they are not meant for production paths. */
-#define FASTSGD_PROFILE_COMPRESS_KERNELS 7
+#define FASTSGD_PROFILE_COMPRESS_KERNELS 8
 #define FASTSGD_PROFILE_DECOMPRESS_KERNELS 2
 fastsgd_status fastsgd_profile_compress(const uint32_t* d_keys, const float* d_values, uint64_t n,
                                         const fastsgd_params* p,

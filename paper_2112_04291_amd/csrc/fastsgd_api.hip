@@ -35,18 +35,22 @@ static EncodePlan make_plan(u64 total_n, u32 n_segments, u32 min_kb) {
     pl.n_slots = (n_segments == 1) ? kMaxSumGrid : 4u;           // abs-sum records per segment
     pl.n_tiles = total_n / kTile + 2ull * n_segments + 1;          // bound; a segment adds at most 2 partial tiles
     pl.max_items = total_n / min_kb + n_segments + 1;              // bound on key blocks (+1 per empty segment)
+    const u64 slots = pl.n_tiles * kTile;                          // scratch entries: every tile owns 4096
     u64 o = 0;
     pl.off_ctrl = o;  o += up(sizeof(Ctrl), 256);
-    pl.off_tdesc = o; o += up(pl.n_tiles * 8, 256);
-    pl.off_idesc = o; o += up(pl.max_items * 8, 256);
-    pl.off_segstate = o; o += up((u64)n_segments * sizeof(SegState), 256);
     pl.zero_end = o;                                               // a single-gradient call clears up to here
     pl.off_gbins = o; o += up((u64)n_segments * pl.n_slots * kBinWords * 8, 256);
     pl.zero_end_batch = o;                                         // a batch also clears the abs-sum records
-    pl.off_seginfo = o;  o += up((u64)n_segments * sizeof(SegInfo), 256);
+    pl.off_tcount = o;   o += up(pl.n_tiles * 4, 256);
+    pl.off_tprefix = o;  o += up(pl.n_tiles * 8, 256);
+    pl.off_btile = o;    o += up((pl.max_items + 1) * 4, 256);
+    pl.off_bprev = o;    o += up((pl.max_items + 1) * 4, 256);
     pl.off_binfo = o;    o += up(pl.max_items * sizeof(BlockInfo), 256);
-    pl.off_ckeys = o;    o += up(total_n * 4, 256);
-    pl.off_codes = o;    o += up(total_n, 256);
+    pl.off_ioff = o;     o += up(pl.max_items * 8, 256);
+    pl.off_seginfo = o;  o += up((u64)n_segments * sizeof(SegInfo), 256);
+    pl.off_segstate = o; o += up((u64)n_segments * sizeof(SegState), 256);
+    pl.off_skeys = o;    o += up(slots * 4, 256);
+    pl.off_scodes = o;   o += up(slots, 256);
     pl.total = o;
     return pl;
 }
@@ -113,22 +117,23 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     }
     const EncodePlan pl = make_plan(total_n, n_segments, min_kb);
     if (n_tiles > pl.n_tiles || max_items > pl.max_items || n_tiles >= 0xFFFFFFFFull) return FASTSGD_ERR_INVALID_ARG;
-    const u64 need = single ? pl.off_codes : pl.total;
-    if (ws_bytes < need) return FASTSGD_ERR_BUFFER_TOO_SMALL;
+    if (ws_bytes < pl.total) return FASTSGD_ERR_BUFFER_TOO_SMALL;
     if (out_capacity < kHeaderBytes) return FASTSGD_ERR_BUFFER_TOO_SMALL;
 
     uint8_t* ws = static_cast<uint8_t*>(d_ws);
     Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + pl.off_ctrl);
     u64* gbins = reinterpret_cast<u64*>(ws + pl.off_gbins);
-    u64* tdesc = reinterpret_cast<u64*>(ws + pl.off_tdesc);
-    u64* idesc = reinterpret_cast<u64*>(ws + pl.off_idesc);
+    u32* tcount = reinterpret_cast<u32*>(ws + pl.off_tcount);
+    u64* tprefix = reinterpret_cast<u64*>(ws + pl.off_tprefix);
+    u32* btile = reinterpret_cast<u32*>(ws + pl.off_btile);
+    u32* bprev = reinterpret_cast<u32*>(ws + pl.off_bprev);
+    BlockInfo* binfo = reinterpret_cast<BlockInfo*>(ws + pl.off_binfo);
+    u64* ioff = reinterpret_cast<u64*>(ws + pl.off_ioff);
     SegInfo* dsegs = reinterpret_cast<SegInfo*>(ws + pl.off_seginfo);
     SegState* dstates = reinterpret_cast<SegState*>(ws + pl.off_segstate);
-    BlockInfo* binfo = reinterpret_cast<BlockInfo*>(ws + pl.off_binfo);
-    u32* ckeys = reinterpret_cast<u32*>(ws + pl.off_ckeys);
+    u32* skeys = reinterpret_cast<u32*>(ws + pl.off_skeys);
+    uint8_t* scodes = ws + pl.off_scodes;
     uint8_t* out = static_cast<uint8_t*>(d_out);
-    uint8_t* codes = single ? out + kHeaderBytes : ws + pl.off_codes;
-    const u64 codes_cap = single ? (u64)out_capacity - kHeaderBytes : total_n;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const u32 cus = cu_count();
 
@@ -162,17 +167,22 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     hipLaunchKernelGGL(k_tables, dim3(n_segments), dim3(kTableThreads), 0, stream, dsegs, dstates, gbins,
                        single ? sum_grid : pl.n_slots, ctrl);
     marks.mark(stream);
-    hipLaunchKernelGGL(k_encode_values, dim3(clamp_grid((n_tiles + kTicketLanes - 1) / kTicketLanes, (u64)cus * 2)),
-                       dim3(kTicketLanes * kWave), 0, stream,
-                       kbase, vbase, dsegs, dstates, n_segments, n_tiles, tdesc, ckeys, codes, codes_cap, total_n, ctrl);
+    hipLaunchKernelGGL(k_encode_values, dim3(clamp_grid((n_tiles + kValWaves - 1) / kValWaves, (u64)cus * 4)),
+                       dim3(kValWaves * kWave), 0, stream, kbase, vbase, dsegs, dstates, n_segments, n_tiles, tcount,
+                       skeys, scodes);
     marks.mark(stream);
-    hipLaunchKernelGGL(k_plan_keys, dim3(1), dim3(kThreads), 0, stream, dsegs, dstates, n_segments, n_tiles, tdesc, ctrl);
+    hipLaunchKernelGGL(k_plan_keys, dim3(1), dim3(kPlanThreads), 0, stream, dsegs, dstates, n_segments, n_tiles,
+                       tcount, tprefix, btile, bprev, ctrl);
     marks.mark(stream);
-    hipLaunchKernelGGL(k_encode_keys, dim3(clamp_grid(max_items, (u64)cus * 4)), dim3(kThreads), 0, stream,
-                       dsegs, dstates, n_segments, ckeys, idesc, binfo, out, (u64)out_capacity, ctrl);
+    const u32 key_grid = clamp_grid(max_items, (u64)cus * 8);
+    hipLaunchKernelGGL(k_measure_keys, dim3(key_grid), dim3(kThreads), 0, stream, dsegs, dstates, n_segments, n_tiles,
+                       tprefix, btile, bprev, skeys, binfo, ctrl);
     marks.mark(stream);
-    hipLaunchKernelGGL(k_finalize, dim3(clamp_grid(max_items, (u64)cus * 4)), dim3(kThreads), 0, stream,
-                       dsegs, dstates, n_segments, idesc, binfo, codes, out, (u64)out_capacity, d_out_offsets,
+    hipLaunchKernelGGL(k_scan_items, dim3(1), dim3(kPlanThreads), 0, stream, dsegs, dstates, n_segments, binfo, ioff,
+                       ctrl);
+    marks.mark(stream);
+    hipLaunchKernelGGL(k_pack_keys, dim3(key_grid), dim3(kThreads), 0, stream, dsegs, dstates, n_segments, n_tiles,
+                       tprefix, btile, bprev, skeys, scodes, binfo, ioff, out, (u64)out_capacity, d_out_offsets,
                        single ? 1u : 0u, d_status, ctrl);
     marks.mark(stream);
     return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;

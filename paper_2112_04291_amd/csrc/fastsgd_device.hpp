@@ -1,5 +1,5 @@
 // Shared device-side definitions of the gfx950 FastSGD codec: workspace records, wave64 helpers,
-// the decoupled look-back scan, exact float64 -> float32 conversions on bit patterns.
+// exact float64 -> float32 conversions on bit patterns.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -21,7 +21,6 @@ constexpr u32 kMagic = 0x44475346u;           // "FSGD"
 constexpr u32 kVersion = 1;
 constexpr u32 kBins = 16;                     // exponent bins of the exact abs-sum (16 exponents each)
 constexpr u32 kMaxKB = 4096;
-constexpr u32 kSpinLimit = 1u << 20;          // bounded wait of the look-back scan
 
 // Host-built description of one gradient (segment) of a call.
 struct SegInfo {
@@ -49,31 +48,21 @@ struct SegState {
 // Per key block, filled by the key encoder, consumed by the finaliser.
 struct BlockInfo { u32 preKey, M, payload_bits, size8; };
 
-// A returning atomic on one address costs about 11 ns on this part and they serialise, so one ticket
-// counter per tile would cap a pass at ~90 M tiles/s.  Tiles are therefore dealt from kLanesOfTickets
-// counters on separate cache lines: counter c hands out tiles c, c + 8, c + 16, ...; wave c of every
-// workgroup draws from counter c.  Any resident workgroup owns a wave for every counter, so the lowest
-// unpublished tile is always either in work or about to be drawn by a wave that is not waiting:
-// the look-back cannot deadlock, whatever part of the grid is resident.
-constexpr u32 kTicketLanes = 8;
-constexpr u32 kTicketStride = 32;             // u32 words between counters (128 bytes)
-
 struct Ctrl {
-    u32 ticket_val[kTicketLanes * kTicketStride];
-    u32 ticket_key[kTicketLanes * kTicketStride];
     u32 status;         // first device-detected fastsgd_status
-    u32 done_key;       // key-encoder work items finished
-    u64 total_items;
-    u64 total_d;
+    u32 pad0;
+    u64 total_items;    // work items of the key encoder
+    u64 total_d;        // survivors of the whole call
     u64 pad[5];
 };
-static_assert(sizeof(Ctrl) == 2 * kTicketLanes * kTicketStride * 4 + 64, "control block layout");
+static_assert(sizeof(Ctrl) == 64, "control block layout");
 
 struct EncodePlan {     // host-computed carve-up of the workspace
     u64 n_tiles, max_items, total_n;
     u32 n_segments, n_slots;
-    u64 off_ctrl, off_gbins, off_tdesc, off_idesc, zero_end, zero_end_batch;   // [off_ctrl, zero_end*) is cleared per call
-    u64 off_seginfo, off_segstate, off_binfo, off_ckeys, off_codes, total;
+    u64 off_ctrl, off_gbins, zero_end, zero_end_batch;    // [off_ctrl, zero_end*) is cleared per call
+    u64 off_tcount, off_tprefix, off_btile, off_bprev, off_binfo, off_ioff;
+    u64 off_seginfo, off_segstate, off_skeys, off_scodes, total;
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -123,54 +112,6 @@ __device__ __forceinline__ u32 block_excl_scan(u32 x, u32* scratch, u32* total) 
     __syncthreads();
     *total = tot;
     return base + incl - x;
-}
-
-// ---------------------------------------------------------------------------------------------
-// Decoupled look-back over descriptors {status:2, value:62}.  Items are numbered by a ticket taken
-// when a workgroup starts on them, so every predecessor of a waiting item is already running and
-// publishes its aggregate without waiting on anyone.  Called by all 64 lanes of ONE wave; returns
-// the exclusive prefix of item `idx` to every lane.  The wait is bounded: on giving up *gave_up is
-// set (the caller reports FASTSGD_ERR_DEVICE) and a prefix is still published, so no successor
-// can wait forever.
-constexpr u64 kDescAgg = 1ull << 62, kDescPrefix = 2ull << 62, kDescMask = (1ull << 62) - 1;
-
-__device__ __forceinline__ u64 desc_load(const u64* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void desc_store(u64* p, u64 v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-__device__ __forceinline__ u64 lookback_exclusive(u64* desc, u64 idx, u64 aggregate, u32* gave_up) {
-    const u32 lane = lane_id();
-    if (idx == 0) {
-        if (lane == 0) desc_store(&desc[0], kDescPrefix | aggregate);
-        return 0;
-    }
-    if (lane == 0) desc_store(&desc[idx], kDescAgg | aggregate);
-    u64 excl = 0;
-    i64 top = (i64)idx - 1;
-    u32 spins = 0;
-    for (;;) {
-        i64 j = top - (i64)lane;
-        u64 w = (j >= 0) ? desc_load(&desc[j]) : kDescPrefix;      // virtual prefix 0 before item 0
-        u32 st = (u32)(w >> 62);
-        u64 none = __ballot(st == 0);
-        u64 pref = __ballot(st == 2);
-        u32 first_none = none ? (u32)__builtin_ctzll(none) : 64u;
-        u32 first_pref = pref ? (u32)__builtin_ctzll(pref) : 64u;
-        if (first_none < first_pref) {                             // a needed descriptor is not there yet
-            if (++spins > kSpinLimit) { *gave_up = 1; break; }
-            __builtin_amdgcn_s_sleep(2);
-            continue;
-        }
-        u32 last = first_pref < 64u ? first_pref : 63u;
-        excl += wave_sum64(lane <= last ? (w & kDescMask) : 0ull);
-        if (first_pref < 64u) break;
-        top -= 64;
-    }
-    if (lane == 0) desc_store(&desc[idx], kDescPrefix | ((excl + aggregate) & kDescMask));
-    return excl;
 }
 
 // ---------------------------------------------------------------------------------------------

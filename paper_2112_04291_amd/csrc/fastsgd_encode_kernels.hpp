@@ -4,9 +4,10 @@
 //   k_abs_sum        Algorithm 1 line 1: exact sum of |v| per segment (integer accumulation)
 //   k_tables         Algorithm 1 line 2 + Eq. 3 as a boundary table sum / b^c, c = 1..tau
 //   k_encode_values  Algorithm 1 lines 4-10: threshold test, code, sign, compaction of survivors
-//   k_plan_keys      per segment: survivors d, key blocks, work-item numbering
-//   k_encode_keys    Algorithm 2 per key block: deltas, M, length flags, bit packing
-//   k_finalize       directory, headers, (segmented) value planes, lengths and status
+//   k_plan_keys      tile counts -> global ranks; per segment: survivors d, key blocks, work items
+//   k_measure_keys   Algorithm 2, first loop, per key block: deltas, maxDelta -> M, size of the block
+//   k_scan_items     byte offsets of the key blocks
+//   k_pack_keys      Algorithm 2, second loop: length flags, bit packing; directory, headers, value planes
 #pragma once
 #include "fastsgd_device.hpp"
 
@@ -289,17 +290,21 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Second pass over the values (Algorithm 1 lines 4-10).  Every WAVE works on its own tiles of 4096
-// elements and never waits for another wave of its workgroup, so memory latency of one wave hides
-// behind the arithmetic of the others:
-//   ticket -> 16 float4 loads per lane -> keep test |v| >= threshold (unsigned compare of bit
-//   patterns, 64 ballots) -> survivor count -> decoupled look-back gives the tile's first global rank
-//   -> survivors are staged in the wave's slice of shared memory at their rank inside the tile
-//   (ballot + mbcnt) -> densely over the staged survivors only: code by binary search in the boundary
-//   table, key fetch, code byte and key written at the global rank.
+// Second pass over the values (Algorithm 1 lines 4-10).  A pure streaming pass: no tile depends on
+// another.  Every WAVE walks its own tiles of 4096 elements (tile = wave + k * waves):
+//   16 float4 loads per lane -> keep test |v| >= threshold -> survivors staged in the wave's slice of
+//   shared memory at their rank inside the tile (ballot + mbcnt) -> densely over the staged survivors
+//   only: code by binary search in the boundary table, key fetch -> code byte and key written to the
+//   TILE'S OWN SLOT of the scratch arrays (entry tile*4096 + rank in tile) -> survivor count of the tile.
+// Global ranks are fixed afterwards by a scan over the 4-byte tile counts (k_plan_keys); the key
+// encoder gathers through that scan.  This keeps look-back chains and ticket counters -- dependent
+// memory round trips that cost microseconds each while the memory system is saturated -- out of the
+// one kernel that has to run at memory speed.
 // Lane `lane` holds, for row r = 0..15, elements tile0 + r*256 + lane*4 + {0..3}.
 constexpr u32 kRows = kTile / 256;       // 16 float4 rows per wave tile
 constexpr u32 kStage = 1024;             // staged survivors per wave and round (4 rows can never exceed it)
+constexpr u32 kValWaves = 4;             // waves per workgroup of the value encoder (they never synchronise)
+constexpr u32 kGather = 8;               // key fetches a lane keeps in flight
 
 // |v| >= threshold as a float compare with the |x| source modifier: for non-negative finite floats
 // (denormals are preserved in this build) it orders exactly like the unsigned compare of the bit
@@ -312,60 +317,93 @@ __device__ __forceinline__ u32 lanes_below(u64 mask) {
     return __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
 }
 
-__global__ void __launch_bounds__(kTicketLanes * kWave) __attribute__((amdgpu_waves_per_eu(4, 8)))
+struct WaveTile {        // wave-uniform description of the tile a wave holds
+    u64 tile;            // tile number (>= n_tiles: none)
+    u64 tile0;           // element index of its first slot
+    u32 seg;
+    u32 lo_off, hi_off;  // slots [lo_off, hi_off) belong to the segment
+};
+
+__device__ __forceinline__ WaveTile describe_tile(const SegInfo* segs, u32 n_segments, u64 n_tiles, u64 tile) {
+    WaveTile wt;
+    wt.tile = tile; wt.tile0 = 0; wt.seg = 0; wt.lo_off = 0; wt.hi_off = 0;
+    if (tile < n_tiles) {
+        wt.seg = (n_segments == 1) ? 0u : find_segment(segs, n_segments, tile);
+        const TileGeom g = tile_geom(segs[wt.seg], tile);
+        wt.tile0 = g.tile0;
+        wt.lo_off = g.lo > g.tile0 ? (u32)(g.lo - g.tile0) : 0u;
+        wt.hi_off = g.hi - g.tile0 < kTile ? (u32)(g.hi - g.tile0) : kTile;
+    }
+    return wt;
+}
+
+__device__ __forceinline__ bool is_full(const WaveTile& wt) { return wt.lo_off == 0 && wt.hi_off == kTile; }
+
+// A tile that lies wholly inside its segment: 16 coalesced float4 loads per lane.
+__device__ __forceinline__ void load_full_tile(const float* __restrict__ values, const WaveTile& wt, u32 lane,
+                                               u32 (&bits)[kRows][4]) {
+    const uint4* src = reinterpret_cast<const uint4*>(values + wt.tile0) + lane;
+#pragma unroll
+    for (u32 r = 0; r < kRows; ++r) {
+        const uint4 q = src[r * 64u];
+        bits[r][0] = q.x; bits[r][1] = q.y; bits[r][2] = q.z; bits[r][3] = q.w;
+    }
+}
+
+// A tile cut by a segment boundary (at most two per segment): slots outside the segment become zero,
+// which never survives.  Goes through the wave's staging buffer in rolled loops so that this rare path
+// costs no registers; the buffer must be free when it is called.
+__device__ __forceinline__ void load_partial_tile(const float* __restrict__ values, const WaveTile& wt, u32 lane,
+                                                  u32* stage, u32 (&bits)[kRows][4]) {
+    const float* tvals = values + wt.tile0;
+#pragma unroll
+    for (u32 q = 0; q < kRows / 4; ++q) {
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll 1
+        for (u32 i = 0; i < 16; ++i) {
+            const u32 off = q * 1024u + i * 64u + lane;
+            stage[i * 64u + lane] = (off >= wt.lo_off && off < wt.hi_off) ? __float_as_uint(tvals[off]) : 0u;
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (u32 rr = 0; rr < 4; ++rr)
+#pragma unroll
+            for (u32 c = 0; c < 4; ++c) bits[4 * q + rr][c] = stage[rr * 256u + lane * 4u + c];
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// The loop is software-pipelined: once a tile's survivors sit in shared memory its registers are free,
+// so the loads of the next tile are issued BEFORE the key fetches and stores of this one, and both
+// waits collapse into one memory round trip per tile.
+__global__ void __launch_bounds__(kValWaves * kWave) __attribute__((amdgpu_waves_per_eu(4, 8)))
 k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                 const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
-                u64 n_tiles, u64* tdesc, u32* __restrict__ ckeys, uint8_t* __restrict__ codes,
-                u64 codes_capacity, u64 ckeys_capacity, Ctrl* ctrl) {
-    __shared__ u32 s_Ball[kTicketLanes][128];
-    __shared__ u32 s_valall[kTicketLanes][kStage];
-    __shared__ uint16_t s_idxall[kTicketLanes][kStage];
+                u64 n_tiles, u32* __restrict__ tcount, u32* __restrict__ skeys, uint8_t* __restrict__ scodes) {
+    __shared__ u32 s_Ball[kValWaves][128];
+    __shared__ u32 s_valall[kValWaves][kStage];
+    __shared__ uint16_t s_idxall[kValWaves][kStage];
     const u32 lane = lane_id();
     const u32 w = (u32)__builtin_amdgcn_readfirstlane((int)wave_id());   // tell the compiler it is wave-uniform
     u32* s_B = s_Ball[w];
     u32* s_val = s_valall[w];
     uint16_t* s_idx = s_idxall[w];
+    const u64 stride = (u64)gridDim.x * kValWaves;
     u32 cur_seg = 0xFFFFFFFFu, thr = 0xFFFFFFFFu, tau = 1;
 
+    u32 bits[kRows][4];
+    WaveTile cur = describe_tile(segs, n_segments, n_tiles, (u64)blockIdx.x * kValWaves + w);
+    if (cur.tile >= n_tiles) return;
+    if (is_full(cur)) load_full_tile(values, cur, lane, bits);
+    else load_partial_tile(values, cur, lane, s_val, bits);
+
     for (;;) {
-        u32 ticket = 0;
-        if (lane == 0) ticket = atomicAdd(&ctrl->ticket_val[w * kTicketStride], 1u);
-        const u64 tile = (u64)(u32)__builtin_amdgcn_readfirstlane((int)ticket) * kTicketLanes + w;
-        if (tile >= n_tiles) break;
-        const u32 seg = (n_segments == 1) ? 0u : find_segment(segs, n_segments, tile);
-        if (seg != cur_seg) {
-            cur_seg = seg;
-            thr = states[seg].thr_bits;
-            tau = segs[seg].tau;
-            s_B[lane] = states[seg].B[lane];
-            s_B[lane + 64] = states[seg].B[lane + 64];
-        }
-        const TileGeom g = tile_geom(segs[seg], tile);
-        const float* tvals = values + g.tile0;
-        u32 bits[kRows][4];
-        if (g.full) {
-            const uint4* src = reinterpret_cast<const uint4*>(tvals) + lane;
-#pragma unroll
-            for (u32 r = 0; r < kRows; ++r) {
-                const uint4 q = src[r * 64u];
-                bits[r][0] = q.x; bits[r][1] = q.y; bits[r][2] = q.z; bits[r][3] = q.w;
-            }
-        } else {
-            // slots [lo_off, hi_off) of the tile belong to the segment; others read a clamped (valid)
-            // address and are replaced by zero, which never survives
-            const u32 lo_off = g.lo > g.tile0 ? (u32)(g.lo - g.tile0) : 0u;
-            const u32 hi_off = g.hi - g.tile0 < kTile ? (u32)(g.hi - g.tile0) : kTile;
-#pragma unroll
-            for (u32 r = 0; r < kRows; ++r) {
-#pragma unroll
-                for (u32 c = 0; c < 4; ++c) {
-                    const u32 off = r * 256u + lane * 4u + c;
-                    const u32 cl = off < lo_off ? lo_off : (off >= hi_off ? hi_off - 1u : off);
-                    const u32 x = __float_as_uint(tvals[cl]);
-                    bits[r][c] = (cl == off) ? x : 0u;
-                }
-                __builtin_amdgcn_sched_barrier(0);      // rare path: keep its address arithmetic row-local
-            }
+        if (cur.seg != cur_seg) {
+            cur_seg = cur.seg;
+            thr = states[cur_seg].thr_bits;
+            tau = segs[cur_seg].tau;
+            s_B[lane] = states[cur_seg].B[lane];
+            s_B[lane + 64] = states[cur_seg].B[lane + 64];
         }
         // survivors of the tile: per-lane count, then one wave reduction
         const float thr_f = __uint_as_float(thr);
@@ -377,15 +415,10 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
 #pragma unroll
         for (u32 d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d, 64);
         const u32 total = (u32)__builtin_amdgcn_readfirstlane((int)mine);
-        u32 gave_up = 0;
-        const u64 base = lookback_exclusive(tdesc, tile, total, &gave_up);
-        if (gave_up && lane == 0) set_status(ctrl, FASTSGD_ERR_DEVICE);
-        if (total == 0) continue;
 
-        const u32* tkeys = keys + g.tile0;
-        // one row: stage its survivors behind `staged` earlier ones; returns the new count
         float thr_s = thr_f;
         asm volatile("" : "+s"(thr_s));     // an opaque copy: the compare masks of the count pass stay dead
+        // one row: stage its survivors behind `staged` earlier ones; returns the new count
         auto stage_row = [&](const u32 (&row)[4], u32 r, u32 staged) -> u32 {
             u64 m[4];
             u32 below = 0, rowcnt = 0;
@@ -405,64 +438,141 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                 }
             return staged + rowcnt;
         };
-        // the staged survivors [0, cnt) have global ranks base + rank_off + j
-        auto write_staged = [&](u32 cnt, u32 rank_off) {
+        // staged survivors [0, cnt) of tile `wt` go to entries slot0 + j of the tile's slot
+        auto write_staged = [&](const WaveTile& wt, u32 cnt, u64 slot0) {
+            const u32* tkeys = keys + wt.tile0;
             __builtin_amdgcn_wave_barrier();
-            for (u32 j = lane; j < cnt; j += 64u) {
-                const u32 vb = s_val[j];
-                const u32 a = vb & 0x7FFFFFFFu;
-                // smallest code c in [1, tau] with a >= B[c]  (B non-increasing, a >= B[tau])
-                u32 lo = 1, hi = tau;
-                while (lo < hi) {
-                    const u32 mid = (lo + hi) >> 1;
-                    if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
+            for (u32 j0 = 0; j0 < cnt; j0 += 64u * kGather) {
+                u32 key[kGather];
+#pragma unroll
+                for (u32 k = 0; k < kGather; ++k) {               // all key fetches of the chunk first
+                    const u32 j = j0 + k * 64u + lane;
+                    key[k] = (j < cnt) ? tkeys[s_idx[j]] : 0u;
                 }
-                const u32 key = tkeys[s_idx[j]];
-                const u64 rank = base + rank_off + j;
-                if (rank < codes_capacity) codes[rank] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
-                else set_status(ctrl, FASTSGD_ERR_BUFFER_TOO_SMALL);
-                if (rank < ckeys_capacity) ckeys[rank] = key;
+#pragma unroll
+                for (u32 k = 0; k < kGather; ++k) {
+                    const u32 j = j0 + k * 64u + lane;
+                    if (j < cnt) {
+                        const u32 vb = s_val[j];
+                        const u32 a = vb & 0x7FFFFFFFu;
+                        // smallest code c in [1, tau] with a >= B[c]  (B non-increasing, a >= B[tau])
+                        u32 lo = 1, hi = tau;
+                        while (lo < hi) {
+                            const u32 mid = (lo + hi) >> 1;
+                            if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
+                        }
+                        scodes[slot0 + j] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
+                        skeys[slot0 + j] = key[k];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);            // one search at a time: keeps registers low
+                }
             }
             __builtin_amdgcn_wave_barrier();
         };
-        if (total <= kStage) {
-            u32 staged = 0;
-#pragma unroll
-            for (u32 r = 0; r < kRows; ++r) staged = stage_row(bits[r], r, staged);
-            write_staged(total, 0);
-        } else {
-            u32 done = 0;
-#pragma unroll
-            for (u32 q = 0; q < kRows / 4; ++q) {
+
+        const WaveTile done = cur;
+        const u64 slot0 = done.tile * kTile;
+        const bool fits = total <= kStage;
+        if (fits) {
+            if (total) {
                 u32 staged = 0;
 #pragma unroll
-                for (u32 rr = 0; rr < 4; ++rr) staged = stage_row(bits[4 * q + rr], 4 * q + rr, staged);
-                write_staged(staged, done);
-                done += staged;
+                for (u32 r = 0; r < kRows; ++r) staged = stage_row(bits[r], r, staged);
+            }
+        } else {
+            // more than a quarter of the tile survives (far from the sparse regime this codec is for):
+            // no staging, every lane codes and writes its own survivors
+            const u32* tkeys = keys + done.tile0;
+            u32 emitted = 0;
+#pragma unroll
+            for (u32 r = 0; r < kRows; ++r) {
+                u64 m[4];
+                u32 below = 0, rowcnt = 0;
+#pragma unroll
+                for (u32 c = 0; c < 4; ++c) {
+                    m[c] = __ballot(keeps(bits[r][c], thr_s));
+                    below += lanes_below(m[c]);
+                    rowcnt += (u32)__popcll(m[c]);
+                }
+                u32 pos = emitted + below;
+#pragma unroll
+                for (u32 c = 0; c < 4; ++c)
+                    if (keeps(bits[r][c], thr_s)) {
+                        const u32 vb = bits[r][c], a = vb & 0x7FFFFFFFu;
+                        u32 lo = 1, hi = tau;
+                        while (lo < hi) {
+                            const u32 mid = (lo + hi) >> 1;
+                            if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
+                        }
+                        scodes[slot0 + pos] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
+                        skeys[slot0 + pos] = tkeys[r * 256u + lane * 4u + c];
+                        ++pos;
+                    }
+                emitted += rowcnt;
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+        // the registers are free: start on the next tile before finishing this one
+        cur = describe_tile(segs, n_segments, n_tiles, done.tile + stride);
+        const bool early = cur.tile < n_tiles && is_full(cur);
+        if (early) load_full_tile(values, cur, lane, bits);
+        if (fits && total) write_staged(done, total, slot0);
+        if (lane == 0) tcount[done.tile] = total;
+        if (cur.tile < n_tiles && !early) load_partial_tile(values, cur, lane, s_val, bits);
+        if (cur.tile >= n_tiles) break;
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// After the value pass every tile descriptor holds an inclusive prefix, so a segment's survivors are
-// the difference of two of them.  Work items: one per key block, and one for a segment without any.
-__global__ void __launch_bounds__(kThreads)
+// One workgroup turns the tile counts into global ranks and plans the key encoder:
+//   A  inclusive scan of the tile counts -> tprefix
+//   B  per segment: first rank, survivors d, key blocks, work-item numbering (one item per key block,
+//      and one for a segment without any)
+//   C  for every key block the tile that holds its first key and the tile that holds the key before it
+constexpr u32 kPlanThreads = 1024;
+
+__global__ void __launch_bounds__(kPlanThreads)
 k_plan_keys(const SegInfo* __restrict__ segs, SegState* __restrict__ states, u32 n_segments, u64 n_tiles,
-            const u64* __restrict__ tdesc, Ctrl* ctrl) {
-    __shared__ u32 s_scan[kWaves + 1];
+            const u32* __restrict__ tcount, u64* __restrict__ tprefix, u32* __restrict__ block_tile,
+            u32* __restrict__ block_prev_tile, Ctrl* ctrl) {
+    __shared__ u64 s_wave[kPlanThreads / 64];
     __shared__ u64 s_carry;
-    const u32 t = threadIdx.x;
+    const u32 t = threadIdx.x, lane = lane_id(), w = wave_id();
+    constexpr u32 kW = kPlanThreads / 64;
+
+    auto block_scan = [&](u64 x, u64* total) -> u64 {       // exclusive scan over the workgroup
+        const u64 incl = wave_incl_scan64(x);
+        if (lane == 63) s_wave[w] = incl;
+        __syncthreads();
+        u64 base = 0, tot = 0;
+        for (u32 k = 0; k < kW; ++k) { const u64 v = s_wave[k]; if (k < w) base += v; tot += v; }
+        __syncthreads();
+        *total = tot;
+        return base + incl - x;
+    };
+
+    // A: every thread owns a run of consecutive tiles
+    const u64 per = (n_tiles + kPlanThreads - 1) / kPlanThreads;
+    const u64 a = (u64)t * per < n_tiles ? (u64)t * per : n_tiles;
+    const u64 b = a + per < n_tiles ? a + per : n_tiles;
+    u64 mine = 0;
+    for (u64 i = a; i < b; ++i) mine += tcount[i];
+    u64 total_d;
+    u64 run = block_scan(mine, &total_d);
+    for (u64 i = a; i < b; ++i) { run += tcount[i]; tprefix[i] = run; }
+    __syncthreads();
+
+    // B
     if (t == 0) s_carry = 0;
     __syncthreads();
-    for (u32 s0 = 0; s0 < n_segments; s0 += kThreads) {
+    for (u32 s0 = 0; s0 < n_segments; s0 += kPlanThreads) {
         const u32 s = s0 + t;
-        u32 items = 0;
+        u64 items = 0;
         if (s < n_segments) {
             const u64 tb = segs[s].tile_begin;
             const u64 te = (s + 1 < n_segments) ? segs[s + 1].tile_begin : n_tiles;
-            const u64 rb = tb ? (tdesc[tb - 1] & kDescMask) : 0;
-            const u64 re = te ? (tdesc[te - 1] & kDescMask) : 0;
+            const u64 rb = tb ? tprefix[tb - 1] : 0;
+            const u64 re = te ? tprefix[te - 1] : 0;
             const u64 d = re - rb;
             const u32 KB = segs[s].block_keys;
             const u32 nb = (u32)((d + KB - 1) / KB);
@@ -471,16 +581,27 @@ k_plan_keys(const SegInfo* __restrict__ segs, SegState* __restrict__ states, u32
             states[s].nb = nb;
             items = nb ? nb : 1u;
         }
-        u32 total;
-        const u32 ex = block_excl_scan(items, s_scan, &total);
+        u64 total;
+        const u64 ex = block_scan(items, &total);
         if (s < n_segments) states[s].item_begin = s_carry + ex;
         __syncthreads();
         if (t == 0) s_carry += total;
         __syncthreads();
     }
-    if (t == 0) {
-        ctrl->total_items = s_carry;
-        ctrl->total_d = n_tiles ? (tdesc[n_tiles - 1] & kDescMask) : 0;
+    if (t == 0) { ctrl->total_items = s_carry; ctrl->total_d = total_d; }
+
+    // C: tile i holds the segment-relative ranks [lo, hi); it owns block starts b*KB in that range
+    // (block_tile) and the ranks b*KB - 1 in that range (block_prev_tile)
+    for (u64 i = t; i < n_tiles; i += kPlanThreads) {
+        const u32 s = (n_segments == 1) ? 0u : find_segment(segs, n_segments, i);
+        const u64 rb = states[s].rank_begin, ib = states[s].item_begin;
+        const u64 KB = segs[s].block_keys;
+        const u64 lo = (i ? tprefix[i - 1] : 0) - rb, hi = tprefix[i] - rb;
+        if (hi > lo) {
+            for (u64 blk = (lo + KB - 1) / KB; blk * KB < hi; ++blk) block_tile[ib + blk] = (u32)i;
+            const u64 nb = states[s].nb;
+            for (u64 blk = (lo + KB) / KB; blk * KB - 1 < hi && blk < nb; ++blk) block_prev_tile[ib + blk] = (u32)i;
+        }
     }
 }
 
@@ -496,61 +617,101 @@ __device__ __forceinline__ u32 find_item_segment(const SegState* states, u32 n_s
 __device__ __forceinline__ u64 align8(u64 x) { return (x + 7) & ~7ull; }
 
 // ---------------------------------------------------------------------------------------------
-// Algorithm 2 on one block of surviving keys per work item.  The block's planes are assembled in
-// shared memory (zeroed, then OR-ed in at scanned bit offsets) and written out as 64-bit words at the
-// byte offset a second look-back scan assigns.  The first item of a segment also accounts for the
-// segment's header, value plane and directory in that scan.
+// Algorithm 2 on one block of surviving keys per work item, in two launches with a scan between:
+//   k_measure_keys  first loop of Algorithm 2 (deltas, maxDelta -> M) and the size of the block's planes
+//   k_scan_items    byte offset of every block (exclusive scan over the items)
+//   k_pack_keys     second loop (length flags, bit packing), directory entry, header, value plane
+// Both key kernels fetch a block's keys through the tile scan: rank r lives in the tile T with
+// tprefix[T-1] <= r < tprefix[T], at entry T*4096 + (r - tprefix[T-1]) of the scratch arrays.
+struct BlockGeom {
+    u32 seg, blk, cnt, KB, l, nb;
+    u64 d, first, grank;       // survivors of the segment; rank of the block's first key in the segment / globally
+};
+
+__device__ __forceinline__ BlockGeom block_geom(const SegInfo* segs, const SegState* states, u32 n_segments, u64 item) {
+    BlockGeom g;
+    g.seg = (n_segments == 1) ? 0u : find_item_segment(states, n_segments, item);
+    const SegState* st = &states[g.seg];
+    g.KB = segs[g.seg].block_keys; g.l = segs[g.seg].flag_bits;
+    g.d = st->d; g.nb = st->nb;
+    g.blk = (u32)(item - st->item_begin);
+    g.first = (u64)g.blk * g.KB;
+    g.cnt = g.nb ? (u32)((g.d - g.first < g.KB) ? g.d - g.first : g.KB) : 0u;
+    g.grank = st->rank_begin + g.first;
+    return g;
+}
+
+constexpr u32 kSlice = 1024;     // tile prefixes staged per round of the gather
+
+// Fills s_keys[1 + i] (and, if codes_dst is given, codes_dst[i]) for the block's keys i = 0..cnt-1 and
+// s_keys[0] with the key before the block (0 for a segment's first block).  All threads call it.
+__device__ __forceinline__ void gather_block(const BlockGeom& g, u64 item, u64 n_tiles,
+                                             const u64* __restrict__ tprefix, const u32* __restrict__ block_tile,
+                                             const u32* __restrict__ block_prev_tile,
+                                             const u32* __restrict__ skeys, const uint8_t* __restrict__ scodes,
+                                             u32* s_keys, u64* s_pre, uint8_t* codes_dst) {
+    const u32 t = threadIdx.x;
+    if (g.cnt == 0) { if (t == 0) s_keys[0] = 0; __syncthreads(); return; }
+    if (t == 0) {
+        u32 pk = 0;
+        if (g.first != 0) {
+            const u64 T = block_prev_tile[item], r = g.grank - 1;
+            pk = skeys[T * kTile + (r - (T ? tprefix[T - 1] : 0))];
+        }
+        s_keys[0] = pk;
+    }
+    const u64 r_end = g.grank + g.cnt;
+    u64 T0 = block_tile[item];
+    u32 len = 32;                 // a dense block spans a few tiles; a sparse one gets full slices afterwards
+    for (;;) {
+        // entry j = prefix BEFORE tile T0 + j, j = 0..len
+        for (u32 j = t; j <= len; j += kThreads) {
+            const u64 T = T0 + j;
+            s_pre[j] = (T == 0) ? 0 : (T - 1 < n_tiles ? tprefix[T - 1] : ~0ull);
+        }
+        __syncthreads();
+        const u64 covered = s_pre[len];                       // ranks below this are inside the slice
+        for (u32 i = t; i < g.cnt; i += kThreads) {
+            const u64 r = g.grank + i;
+            if (r >= s_pre[0] && r < covered) {
+                u32 lo = 0, hi = len - 1;                     // largest j with s_pre[j] <= r
+                while (lo < hi) {
+                    const u32 mid = (lo + hi + 1) >> 1;
+                    if (s_pre[mid] <= r) lo = mid; else hi = mid - 1;
+                }
+                const u64 e = (T0 + lo) * kTile + (r - s_pre[lo]);
+                s_keys[1 + i] = skeys[e];
+                if (codes_dst) codes_dst[i] = scodes[e];
+            }
+        }
+        __syncthreads();
+        if (covered >= r_end) break;
+        T0 += len;
+        len = kSlice;
+    }
+}
+
 __global__ void __launch_bounds__(kThreads)
-k_encode_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
-              const u32* __restrict__ ckeys, u64* idesc, BlockInfo* __restrict__ binfo,
-              uint8_t* __restrict__ out, u64 out_capacity, Ctrl* ctrl) {
+k_measure_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments, u64 n_tiles,
+               const u64* __restrict__ tprefix, const u32* __restrict__ block_tile,
+               const u32* __restrict__ block_prev_tile, const u32* __restrict__ skeys,
+               BlockInfo* __restrict__ binfo, Ctrl* ctrl) {
     __shared__ u32 s_keys[kMaxKB + 1];
-    __shared__ u32 s_flags[kMaxKB * 5 / 32 + 2];
-    __shared__ u32 s_pay[kMaxKB + 2];
-    __shared__ u32 s_scan[kWaves + 1];
-    __shared__ u32 s_red[kWaves];
-    __shared__ u64 s_base;
-    __shared__ u32 s_item_lo;
+    __shared__ u64 s_pre[kSlice + 1];
+    __shared__ u32 s_red[kWaves], s_bits[kWaves];
     const u32 t = threadIdx.x, lane = lane_id(), w = wave_id();
     const u64 total_items = ctrl->total_items;
-
-    for (;;) {
-        if (t == 0) s_item_lo = atomicAdd(&ctrl->ticket_key[0], 1u);   // items < 2^32
-        __syncthreads();
-        const u64 item = s_item_lo;
-        if (item >= total_items) break;
-        const u32 seg = (n_segments == 1) ? 0u : find_item_segment(states, n_segments, item);
-        const SegState* st = &states[seg];
-        const u32 KB = segs[seg].block_keys, l = segs[seg].flag_bits;
-        const u64 d = st->d;
-        const u32 nb = st->nb;
-        const u32 blk = (u32)(item - st->item_begin);
-        const u64 first = (u64)blk * KB;                      // rank inside the segment
-        const u32 cnt = nb ? (u32)((d - first < KB) ? d - first : KB) : 0u;
-        const u64 grank = st->rank_begin + first;             // global rank of the block's first key
-        const u32 per = KB / kThreads;                        // keys per thread: 1..16
-
-        // keys of the block, preceded by preKey
-        for (u32 i = t; i < cnt; i += kThreads) s_keys[i + 1] = ckeys[grank + i];
-        if (t == 0) s_keys[0] = (first == 0) ? 0u : ckeys[grank - 1];
-        for (u32 i = t; i < sizeof(s_flags) / 4; i += kThreads) s_flags[i] = 0;
-        for (u32 i = t; i < sizeof(s_pay) / 4; i += kThreads) s_pay[i] = 0;
-        __syncthreads();
-
+    for (u64 item = blockIdx.x; item < total_items; item += gridDim.x) {
+        const BlockGeom g = block_geom(segs, states, n_segments, item);
+        gather_block(g, item, n_tiles, tprefix, block_tile, block_prev_tile, skeys, nullptr, s_keys, s_pre, nullptr);
         // first loop of Algorithm 2: deltas and their maximum
-        u32 delta[16];
         u32 mx = 0;
         bool unsorted = false;
-#pragma unroll
-        for (u32 k = 0; k < 16; ++k) {
-            const u32 i = t * per + k;
-            delta[k] = 0;
-            if (k < per && i < cnt) {
-                const u32 prev = s_keys[i], cur = s_keys[i + 1];
-                delta[k] = cur - prev;
-                unsorted |= (cur < prev) || (cur == prev && (first + i) != 0);
-                mx = delta[k] > mx ? delta[k] : mx;
-            }
+        for (u32 i = t; i < g.cnt; i += kThreads) {
+            const u32 prev = s_keys[i], cur = s_keys[i + 1];
+            unsorted |= (cur < prev) || (cur == prev && (g.first + i) != 0);
+            const u32 dk = cur - prev;
+            mx = dk > mx ? dk : mx;
         }
         mx = wave_max(mx);
         if (lane == 0) s_red[w] = mx;
@@ -561,14 +722,146 @@ k_encode_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ sta
         for (u32 k = 1; k < kWaves; ++k) mx = s_red[k] > mx ? s_red[k] : mx;
         u32 M = 32u - __clz(mx);      // __clz(0) = 32
         if (M < 1) M = 1;
+        // payload bits: every key takes the length of the smallest level that holds its delta
+        u32 bits = 0;
+        for (u32 i = t; i < g.cnt; i += kThreads) {
+            const u32 need = 32u - __clz(s_keys[i + 1] - s_keys[i]);
+            const u32 level = need ? (((need - 1u) << g.l) / M + 1u) : 1u;
+            bits += (level * M + (1u << g.l) - 1u) >> g.l;
+        }
+#pragma unroll
+        for (u32 d = 32; d >= 1; d >>= 1) bits += __shfl_xor(bits, d, 64);
+        if (lane == 0) s_bits[w] = bits;
+        __syncthreads();
+        if (t == 0) {
+            u32 pb = 0;
+#pragma unroll
+            for (u32 k = 0; k < kWaves; ++k) pb += s_bits[k];
+            BlockInfo bi;
+            bi.preKey = s_keys[0]; bi.M = M; bi.payload_bits = pb;
+            bi.size8 = ((g.cnt * g.l + 63u) >> 6) + ((pb + 63u) >> 6);
+            binfo[item] = bi;
+        }
+        __syncthreads();
+    }
+}
 
-        // second loop: level (smallest length that holds the delta) and its length
-        u32 len[16], lvl[16], mybits = 0;
+// Inclusive scan over the work items of the bytes each adds to the output: its key block, plus -- for
+// the first item of a segment -- the segment's header, value plane and directory.
+__global__ void __launch_bounds__(kPlanThreads)
+k_scan_items(const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
+             const BlockInfo* __restrict__ binfo, u64* __restrict__ ioff, const Ctrl* ctrl) {
+    __shared__ u64 s_wave[kPlanThreads / 64];
+    const u32 t = threadIdx.x, lane = lane_id(), w = wave_id();
+    constexpr u32 kW = kPlanThreads / 64;
+    const u64 n = ctrl->total_items;
+    const u64 per = (n + kPlanThreads - 1) / kPlanThreads;
+    const u64 a = (u64)t * per < n ? (u64)t * per : n;
+    const u64 b = a + per < n ? a + per : n;
+    auto bytes_of = [&](u64 item) -> u64 {
+        const u32 s = (n_segments == 1) ? 0u : find_item_segment(states, n_segments, item);
+        u64 x = 8ull * binfo[item].size8;
+        if (item == states[s].item_begin) x += kHeaderBytes + align8(states[s].d) + 16ull * states[s].nb;
+        return x;
+    };
+    u64 mine = 0;
+    for (u64 i = a; i < b; ++i) mine += bytes_of(i);
+    const u64 incl = wave_incl_scan64(mine);
+    if (lane == 63) s_wave[w] = incl;
+    __syncthreads();
+    u64 run = incl - mine;
+    for (u32 k = 0; k < kW; ++k) if (k < w) run += s_wave[k];
+    for (u64 i = a; i < b; ++i) { run += bytes_of(i); ioff[i] = run; }
+}
+
+__global__ void __launch_bounds__(kThreads)
+k_pack_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments, u64 n_tiles,
+            const u64* __restrict__ tprefix, const u32* __restrict__ block_tile,
+            const u32* __restrict__ block_prev_tile, const u32* __restrict__ skeys,
+            const uint8_t* __restrict__ scodes, const BlockInfo* __restrict__ binfo, const u64* __restrict__ ioff,
+            uint8_t* __restrict__ out, u64 out_capacity, u64* out_offsets, u32 single, u32* out_status,
+            const Ctrl* ctrl) {
+    __shared__ u32 s_keys[kMaxKB + 1];
+    __shared__ u64 s_pre[kSlice + 1];
+    __shared__ u32 s_flags[kMaxKB * 5 / 32 + 2];
+    __shared__ u32 s_pay[kMaxKB + 2];
+    __shared__ u32 s_scan[kWaves + 1];
+    __shared__ uint8_t s_codes[kMaxKB];
+    const u32 t = threadIdx.x;
+    const u64 total_items = ctrl->total_items;
+    const u64 total_bytes = total_items ? ioff[total_items - 1] : 0;
+    u32 status = ctrl->status;
+    if (status == 0 && total_bytes > out_capacity) status = FASTSGD_ERR_BUFFER_TOO_SMALL;
+    const bool ok = (status == 0);
+
+    if (blockIdx.x == 0) {          // lengths and status of the whole call
+        if (single) {
+            if (t == 0) out_offsets[0] = ok ? total_bytes : 0;
+        } else {
+            for (u32 s = t; s <= n_segments; s += kThreads) {
+                u64 off = 0;
+                if (ok) {
+                    if (s == n_segments) off = total_bytes;
+                    else { const u64 ib = states[s].item_begin; off = ib ? ioff[ib - 1] : 0; }
+                }
+                out_offsets[s] = off;
+            }
+        }
+        if (t == 0) *out_status = status;
+    }
+    if (!ok) return;                // nothing is written into a buffer that cannot hold the result
+
+    for (u64 item = blockIdx.x; item < total_items; item += gridDim.x) {
+        const BlockGeom g = block_geom(segs, states, n_segments, item);
+        const SegInfo info = segs[g.seg];
+        const u64 ib = states[g.seg].item_begin;
+        const u64 sbeg = ib ? ioff[ib - 1] : 0;                        // stream start of the segment
+        const u64 send = ioff[ib + (g.nb ? g.nb : 1u) - 1];            // and its end
+        const u64 dir_off = sbeg + kHeaderBytes + align8(g.d);
+        const u64 blocks_off = dir_off + 16ull * g.nb;
+        if (g.blk == 0) {
+            if (t == 0) {
+                u64* h = reinterpret_cast<u64*>(out + sbeg);
+                h[0] = (u64)kMagic | ((u64)kVersion << 32) | ((u64)info.flag_bits << 40) | ((u64)info.tau << 48);
+                h[1] = (u64)info.block_keys | ((u64)g.nb << 32);
+                h[2] = (u64)__double_as_longlong(info.base);
+                h[3] = (u64)__double_as_longlong(states[g.seg].sum);
+                h[4] = info.elem_count;
+                h[5] = g.d;
+                h[6] = send - sbeg;
+                h[7] = 0;
+            }
+            // zero padding between the value plane and the directory
+            if (t < 8 && g.d + t < align8(g.d)) out[sbeg + kHeaderBytes + g.d + t] = 0;
+        }
+        if (g.cnt == 0) continue;                                      // a segment without survivors
+        const BlockInfo bi = binfo[item];
+        const u32 M = bi.M, l = g.l, cnt = g.cnt;
+        const u32 fwords = (cnt * l + 63u) >> 6, pwords = (bi.payload_bits + 63u) >> 6;
+        const u64 start = ioff[item] - 8ull * bi.size8;                // this block's planes
+        if (t == 0) {
+            u64* e = reinterpret_cast<u64*>(out + dir_off + 16ull * g.blk);
+            e[0] = (u64)(u32)((start - blocks_off) >> 3) | ((u64)bi.preKey << 32);
+            e[1] = (u64)M | ((u64)bi.payload_bits << 32);
+        }
+        for (u32 i = t; i < 2 * fwords + 2; i += kThreads) s_flags[i] = 0;
+        for (u32 i = t; i < 2 * pwords + 2; i += kThreads) s_pay[i] = 0;
+        gather_block(g, item, n_tiles, tprefix, block_tile, block_prev_tile, skeys, scodes, s_keys, s_pre, s_codes);
+
+        // value plane of the block's survivors
+        {
+            uint8_t* vdst = out + sbeg + kHeaderBytes + g.first;
+            for (u32 i = t; i < cnt; i += kThreads) vdst[i] = s_codes[i];
+        }
+        // second loop of Algorithm 2: thread t owns keys [t*per, (t+1)*per)
+        const u32 per = g.KB / kThreads;
+        u32 len[16], lvl[16], delta[16], mybits = 0;
 #pragma unroll
         for (u32 k = 0; k < 16; ++k) {
             const u32 i = t * per + k;
-            len[k] = 0; lvl[k] = 0;
+            len[k] = 0; lvl[k] = 0; delta[k] = 0;
             if (k < per && i < cnt) {
+                delta[k] = s_keys[i + 1] - s_keys[i];
                 const u32 need = 32u - __clz(delta[k]);
                 const u32 level = need ? (((need - 1u) << l) / M + 1u) : 1u;
                 lvl[k] = level - 1u;
@@ -592,112 +885,11 @@ k_encode_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ sta
                 bitpos += len[k];
             }
         }
-        const u32 fwords = (cnt * l + 63u) >> 6, pwords = (payload_bits + 63u) >> 6;   // 64-bit words
-        const u32 size8 = fwords + pwords;
-        const u64 fixed = (blk == 0) ? (kHeaderBytes + align8(d) + 16ull * nb) : 0ull;
-        if (w == 0) {
-            u32 gave_up = 0;
-            const u64 base = lookback_exclusive(idesc, item, 8ull * size8 + fixed, &gave_up);
-            if (lane == 0) {
-                s_base = base;
-                if (gave_up) set_status(ctrl, FASTSGD_ERR_DEVICE);
-                BlockInfo bi;
-                bi.preKey = s_keys[0]; bi.M = M; bi.payload_bits = payload_bits; bi.size8 = size8;
-                binfo[item] = bi;
-            }
-        }
         __syncthreads();
-        const u64 start = s_base + fixed;                     // byte offset of this block's planes
-        if (start + 8ull * size8 <= out_capacity) {
-            u64* dst = reinterpret_cast<u64*>(out + start);
-            for (u32 i = t; i < fwords; i += kThreads)
-                dst[i] = (u64)s_flags[2 * i] | ((u64)s_flags[2 * i + 1] << 32);
-            for (u32 i = t; i < pwords; i += kThreads)
-                dst[fwords + i] = (u64)s_pay[2 * i] | ((u64)s_pay[2 * i + 1] << 32);
-        } else if (t == 0) {
-            set_status(ctrl, FASTSGD_ERR_BUFFER_TOO_SMALL);
-        }
+        u64* dst = reinterpret_cast<u64*>(out + start);
+        for (u32 i = t; i < fwords; i += kThreads) dst[i] = (u64)s_flags[2 * i] | ((u64)s_flags[2 * i + 1] << 32);
+        for (u32 i = t; i < pwords; i += kThreads) dst[fwords + i] = (u64)s_pay[2 * i] | ((u64)s_pay[2 * i + 1] << 32);
         __syncthreads();
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Everything that needs the resolved byte offsets: directory entries, headers, value planes of a
-// segmented call (the single-gradient call wrote them in place), lengths and status.
-__global__ void __launch_bounds__(kThreads)
-k_finalize(const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
-           const u64* __restrict__ idesc, const BlockInfo* __restrict__ binfo,
-           const uint8_t* __restrict__ codes_scratch, uint8_t* __restrict__ out, u64 out_capacity,
-           u64* out_offsets /* n_segments+1, or a single length if single */, u32 single,
-           u32* out_status, Ctrl* ctrl) {
-    const u32 t = threadIdx.x;
-    const u64 total_items = ctrl->total_items;
-    const u64 total_bytes = total_items ? (idesc[total_items - 1] & kDescMask) : 0;
-    u32 status = ctrl->status;
-    if (status == 0 && total_bytes > out_capacity) status = FASTSGD_ERR_BUFFER_TOO_SMALL;
-    const bool ok = (status == 0);
-
-    for (u64 item = blockIdx.x; item < total_items; item += gridDim.x) {
-        const u32 seg = (n_segments == 1) ? 0u : find_item_segment(states, n_segments, item);
-        const SegState* st = &states[seg];
-        const SegInfo info = segs[seg];
-        const u64 ib = st->item_begin;
-        const u64 sbeg = ib ? (idesc[ib - 1] & kDescMask) : 0;            // stream start of the segment
-        const u64 d = st->d;
-        const u32 nb = st->nb;
-        const u32 blk = (u32)(item - ib);
-        const u64 dir_off = sbeg + kHeaderBytes + align8(d);
-        const u64 blocks_off = dir_off + 16ull * nb;
-        const u64 incl = idesc[item] & kDescMask;
-        const u64 send = idesc[ib + (nb ? nb : 1u) - 1] & kDescMask;      // stream end
-        if (!ok) continue;
-        if (nb) {
-            const BlockInfo bi = binfo[item];
-            const u64 start = incl - 8ull * bi.size8;
-            if (t == 0) {
-                u64* e = reinterpret_cast<u64*>(out + dir_off + 16ull * blk);
-                e[0] = (u64)(u32)((start - blocks_off) >> 3) | ((u64)bi.preKey << 32);
-                e[1] = (u64)bi.M | ((u64)bi.payload_bits << 32);
-            }
-            if (!single) {
-                const u32 KB = info.block_keys;
-                const u64 first = (u64)blk * KB;
-                const u32 cnt = (u32)((d - first < KB) ? d - first : KB);
-                const uint8_t* src = codes_scratch + st->rank_begin + first;
-                uint8_t* dst = out + sbeg + kHeaderBytes + first;
-                for (u32 i = t; i < cnt; i += kThreads) dst[i] = src[i];
-            }
-        }
-        if (blk == 0) {
-            if (t == 0) {
-                u64* h = reinterpret_cast<u64*>(out + sbeg);
-                h[0] = (u64)kMagic | ((u64)kVersion << 32) | ((u64)info.flag_bits << 40) | ((u64)info.tau << 48);
-                h[1] = (u64)info.block_keys | ((u64)nb << 32);
-                h[2] = (u64)__double_as_longlong(info.base);
-                h[3] = (u64)__double_as_longlong(st->sum);
-                h[4] = info.elem_count;
-                h[5] = d;
-                h[6] = send - sbeg;
-                h[7] = 0;
-            }
-            // zero padding between the value plane and the directory
-            if (t < 8 && d + t < align8(d)) out[sbeg + kHeaderBytes + d + t] = 0;
-        }
-    }
-    if (blockIdx.x == 0) {
-        if (single) {
-            if (t == 0) out_offsets[0] = ok ? total_bytes : 0;
-        } else {
-            for (u32 s = t; s <= n_segments; s += kThreads) {
-                u64 off = 0;
-                if (ok) {
-                    if (s == n_segments) off = total_bytes;
-                    else { const u64 ib = states[s].item_begin; off = ib ? (idesc[ib - 1] & kDescMask) : 0; }
-                }
-                out_offsets[s] = off;
-            }
-        }
-        if (t == 0) *out_status = status;
     }
 }
 
