@@ -21,7 +21,7 @@
  *     failure).  Conditions detected on the device set *d_status to a fastsgd_status value and
  *     the reported length (bytes / pairs) to 0; nothing is ever written past a stated capacity.
  *   - Keys are uint32 and strictly increasing within one gradient (the first may be 0);
- *     values are IEEE binary32.  n <= 2^32 - 1 per gradient.
+ *     values are IEEE binary32.  n <= 2^32 - 1024 per gradient.
  *
  * Stream layout (little-endian): 64-byte header {"FSGD", version u8, l u8, tau u8, 0 u8,
  * block_keys u32, n_blocks u32, b f64, sum f64, n u64, d u64, total_bytes u64, 0 u64}; value
@@ -130,10 +130,10 @@ fastsgd_status fastsgd_decompress_segmented(const void* d_streams, size_t total_
  * split each further, per kernel).  Same arguments and results as fastsgd_compress /
  * fastsgd_decompress, run `iterations` (1..4096) times back to back with a HIP event recorded on
  * hip_stream before the first and after every kernel; the call then WAITS for the stream and
- * stores the average milliseconds per kernel in kernel_ms (host).  Kernel order, compress: clear,
- * abs-sum, tables, encode-values, plan-keys, measure-keys, scan-items, pack-keys; decompress: setup, decode.
+ * stores the average milliseconds per kernel in kernel_ms (host).  Kernel order, compress:
+ * abs-sum, tables, encode-values, measure-keys, pack-keys; decompress: setup, decode.
  * These two calls create and destroy HIP events; they are not meant for production paths. */
-#define FASTSGD_PROFILE_COMPRESS_KERNELS 8
+#define FASTSGD_PROFILE_COMPRESS_KERNELS 5
 #define FASTSGD_PROFILE_DECOMPRESS_KERNELS 2
 fastsgd_status fastsgd_profile_compress(const uint32_t* d_keys, const float* d_values, uint64_t n,
                                         const fastsgd_params* p,

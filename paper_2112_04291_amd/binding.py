@@ -18,8 +18,7 @@ STATUS_NAMES = ["OK", "INVALID_ARG", "BUFFER_TOO_SMALL", "NONFINITE", "UNSORTED_
 EXPORTS = ["fastsgd_compressed_size", "fastsgd_workspace_size", "fastsgd_decompress_workspace_size",
            "fastsgd_compress", "fastsgd_decompress", "fastsgd_compress_segmented", "fastsgd_decompress_segmented",
            "fastsgd_profile_compress", "fastsgd_profile_decompress"]
-COMPRESS_KERNELS = ["clear", "abs_sum", "tables", "encode_values", "plan_keys", "measure_keys", "scan_items",
-                    "pack_keys"]
+COMPRESS_KERNELS = ["abs_sum", "tables", "encode_values", "measure_keys", "pack_keys"]
 DECOMPRESS_KERNELS = ["setup", "decode"]
 
 

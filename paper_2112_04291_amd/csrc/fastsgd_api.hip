@@ -11,6 +11,7 @@ namespace fsgd {
 
 constexpr u64 kDecSegBytes = 640, kDecCtrlBytes = 64;   // >= sizeof(DecSeg), sizeof(DecCtrl)
 constexpr u32 kMaxSegments = 65536;
+constexpr u64 kMaxElems = 0xFFFFFFFFull - 1023;   // per gradient: scratch offsets inside a segment stay below 2^32
 constexpr u32 kMaxSumGrid = 2048;      // most workgroups the abs-sum pass of a single gradient is launched with
 static_assert(sizeof(DecSeg) <= kDecSegBytes && sizeof(DecCtrl) <= kDecCtrlBytes, "decoder workspace records");
 static_assert(sizeof(SegInfo) == 48 && sizeof(SegBatch) <= 3072, "segment table travels as a kernel argument");
@@ -33,24 +34,22 @@ static EncodePlan make_plan(u64 total_n, u32 n_segments, u32 min_kb) {
     pl.total_n = total_n;
     pl.n_segments = n_segments;
     pl.n_slots = (n_segments == 1) ? kMaxSumGrid : 4u;           // abs-sum records per segment
-    pl.n_tiles = total_n / kTile + 2ull * n_segments + 1;          // bound; a segment adds at most 2 partial tiles
+    pl.max_chunks = (u64)kChunkTarget + n_segments;                // a segment adds at most one short chunk
     pl.max_items = total_n / min_kb + n_segments + 1;              // bound on key blocks (+1 per empty segment)
-    const u64 slots = pl.n_tiles * kTile;                          // scratch entries: every tile owns 4096
+    pl.max_slots = total_n + 4ull * n_segments + 8;                // scratch entries: element index + 4 per segment
     u64 o = 0;
     pl.off_ctrl = o;  o += up(sizeof(Ctrl), 256);
+    pl.off_segd = o;  o += up((u64)n_segments * 8, 256);
+    pl.off_gsum = o;  o += up((u64)(kMaxGroups + 1) * 8, 256);
     pl.zero_end = o;                                               // a single-gradient call clears up to here
     pl.off_gbins = o; o += up((u64)n_segments * pl.n_slots * kBinWords * 8, 256);
     pl.zero_end_batch = o;                                         // a batch also clears the abs-sum records
-    pl.off_tcount = o;   o += up(pl.n_tiles * 4, 256);
-    pl.off_tprefix = o;  o += up(pl.n_tiles * 8, 256);
-    pl.off_btile = o;    o += up((pl.max_items + 1) * 4, 256);
-    pl.off_bprev = o;    o += up((pl.max_items + 1) * 4, 256);
+    pl.off_ccount = o;   o += up(pl.max_chunks * 4, 256);
     pl.off_binfo = o;    o += up(pl.max_items * sizeof(BlockInfo), 256);
-    pl.off_ioff = o;     o += up(pl.max_items * 8, 256);
     pl.off_seginfo = o;  o += up((u64)n_segments * sizeof(SegInfo), 256);
     pl.off_segstate = o; o += up((u64)n_segments * sizeof(SegState), 256);
-    pl.off_skeys = o;    o += up(slots * 4, 256);
-    pl.off_scodes = o;   o += up(slots, 256);
+    pl.off_skeys = o;    o += up(pl.max_slots * 4, 256);
+    pl.off_scodes = o;   o += up(pl.max_slots, 256);
     pl.total = o;
     return pl;
 }
@@ -87,48 +86,67 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     if (n_segments < 1 || n_segments > kMaxSegments || params_stride > 1) return FASTSGD_ERR_INVALID_ARG;
     if (((uintptr_t)d_out & 7) || ((uintptr_t)d_ws & 255) || ((uintptr_t)d_values & 3) || ((uintptr_t)d_keys & 3))
         return FASTSGD_ERR_INVALID_ARG;
-    const u64 total_n = seg_offsets[n_segments] - seg_offsets[0];
-    if (seg_offsets[n_segments] < seg_offsets[0] || total_n >= (1ull << 40)) return FASTSGD_ERR_INVALID_ARG;
+    const u64 first_elem = seg_offsets[0];
+    const u64 total_n = seg_offsets[n_segments] - first_elem;
+    if (seg_offsets[n_segments] < first_elem || total_n >= (1ull << 40)) return FASTSGD_ERR_INVALID_ARG;
     if (total_n && (!d_keys || !d_values)) return FASTSGD_ERR_INVALID_ARG;
 
-    // shift the bases down to a 16-byte boundary of the value array; elements keep their pairing
-    const u64 mis = ((uintptr_t)d_values & 15) / 4;
-    const float* vbase = d_values - mis;
-    const u32* kbase = d_keys - mis;
+    // elements are counted from the 16-byte boundary at or below the first one; keys keep their pairing
+    const u64 mis = total_n ? ((uintptr_t)(d_values + first_elem) & 15) / 4 : 0;
+    const float* vbase = d_values + first_elem - mis;
+    const u32* kbase = d_keys + first_elem - mis;
 
     std::vector<SegInfo> segs(n_segments);
     u32 min_kb = kMaxKB;
-    u64 n_tiles = 0, max_items = 0;
+    u64 n_tiles = 0, max_items = 0, total_rows = 0;
     for (u32 s = 0; s < n_segments; ++s) {
         const fastsgd_params* p = &params[params_stride ? s : 0];
         if (!params_ok(p)) return FASTSGD_ERR_INVALID_ARG;
         if (seg_offsets[s + 1] < seg_offsets[s]) return FASTSGD_ERR_INVALID_ARG;
         const u64 cnt = seg_offsets[s + 1] - seg_offsets[s];
-        if (cnt > 0xFFFFFFFFull) return FASTSGD_ERR_INVALID_ARG;
+        if (cnt > kMaxElems) return FASTSGD_ERR_INVALID_ARG;
         SegInfo& si = segs[s];
-        si.elem_begin = seg_offsets[s] + mis;
+        si.elem_begin = seg_offsets[s] - first_elem + mis;
         si.elem_count = cnt;
-        si.tile_begin = n_tiles;
         si.base = p->base; si.tau = p->tau; si.flag_bits = p->flag_bits; si.block_keys = p->block_keys; si.pad = 0;
-        if (cnt) n_tiles += (si.elem_begin + cnt - (si.elem_begin & ~3ull) + kTile - 1) / kTile;
+        if (n_tiles >= 0xFFFFFFFFull) return FASTSGD_ERR_INVALID_ARG;
+        si.tile_begin = (u32)n_tiles;
+        const u64 span = cnt ? si.elem_begin + cnt - (si.elem_begin & ~3ull) : 0;   // from the aligned start
+        n_tiles += (span + kTile - 1) / kTile;
+        total_rows += (span + kRow - 1) / kRow;
         const u64 blocks = (cnt + p->block_keys - 1) / p->block_keys;
         max_items += blocks ? blocks : 1;
         if (p->block_keys < min_kb) min_kb = p->block_keys;
     }
+    // chunks of R rows, about kChunkTarget of them, never shorter than one tile
+    u64 R64 = (total_rows + kChunkTarget - 1) / kChunkTarget;
+    if (R64 < kTileRows) R64 = kTileRows;
+    u64 n_chunks = 0;
+    for (u32 s = 0; s < n_segments; ++s) {
+        SegInfo& si = segs[s];
+        const u64 span = si.elem_count ? si.elem_begin + si.elem_count - (si.elem_begin & ~3ull) : 0;
+        const u64 rows = (span + kRow - 1) / kRow;
+        si.chunk_begin = (u32)n_chunks;
+        const u64 c = (rows + R64 - 1) / R64;
+        if (c > kMaxSegChunks) return FASTSGD_ERR_INVALID_ARG;     // cannot happen: R64 >= total_rows / kChunkTarget
+        n_chunks += c;
+    }
     const EncodePlan pl = make_plan(total_n, n_segments, min_kb);
-    if (n_tiles > pl.n_tiles || max_items > pl.max_items || n_tiles >= 0xFFFFFFFFull) return FASTSGD_ERR_INVALID_ARG;
+    if (n_chunks > pl.max_chunks || max_items > pl.max_items || n_tiles >= 0xFFFFFFFFull || R64 > 0xFFFFFFull)
+        return FASTSGD_ERR_INVALID_ARG;
     if (ws_bytes < pl.total) return FASTSGD_ERR_BUFFER_TOO_SMALL;
     if (out_capacity < kHeaderBytes) return FASTSGD_ERR_BUFFER_TOO_SMALL;
+    const u32 R = (u32)R64;
+    u32 g_shift = 6;                                               // key blocks per group of the size sums
+    while ((pl.max_items >> g_shift) + 1 > kMaxGroups) ++g_shift;
 
     uint8_t* ws = static_cast<uint8_t*>(d_ws);
     Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + pl.off_ctrl);
+    unsigned long long* segd = reinterpret_cast<unsigned long long*>(ws + pl.off_segd);
+    unsigned long long* gsum = reinterpret_cast<unsigned long long*>(ws + pl.off_gsum);
     u64* gbins = reinterpret_cast<u64*>(ws + pl.off_gbins);
-    u32* tcount = reinterpret_cast<u32*>(ws + pl.off_tcount);
-    u64* tprefix = reinterpret_cast<u64*>(ws + pl.off_tprefix);
-    u32* btile = reinterpret_cast<u32*>(ws + pl.off_btile);
-    u32* bprev = reinterpret_cast<u32*>(ws + pl.off_bprev);
+    u32* ccount = reinterpret_cast<u32*>(ws + pl.off_ccount);
     BlockInfo* binfo = reinterpret_cast<BlockInfo*>(ws + pl.off_binfo);
-    u64* ioff = reinterpret_cast<u64*>(ws + pl.off_ioff);
     SegInfo* dsegs = reinterpret_cast<SegInfo*>(ws + pl.off_seginfo);
     SegState* dstates = reinterpret_cast<SegState*>(ws + pl.off_segstate);
     u32* skeys = reinterpret_cast<u32*>(ws + pl.off_skeys);
@@ -141,7 +159,7 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     const u64 zero_words = ((single ? pl.zero_end : pl.zero_end_batch) - pl.off_ctrl) / 8;
     u64* zero_begin = reinterpret_cast<u64*>(ws + pl.off_ctrl);
     if (!single) {
-        // clear control words, descriptors and abs-sum records; store the segment table (48 per launch)
+        // clear control words, counters and abs-sum records; store the segment table (48 per launch)
         for (u32 first = 0; first < n_segments; first += 48) {
             SegBatch b;
             const u32 count = (n_segments - first < 48) ? n_segments - first : 48;
@@ -153,7 +171,6 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
                 hipLaunchKernelGGL(k_store_segments, dim3(1), dim3(64), 0, stream, dsegs, b, first, count);
         }
     }
-    marks.mark(stream);
 
     u32 sum_grid = cus * 4 < kMaxSumGrid ? cus * 4 : kMaxSumGrid;
     sum_grid = clamp_grid(n_tiles, sum_grid);
@@ -167,23 +184,21 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     hipLaunchKernelGGL(k_tables, dim3(n_segments), dim3(kTableThreads), 0, stream, dsegs, dstates, gbins,
                        single ? sum_grid : pl.n_slots, ctrl);
     marks.mark(stream);
-    hipLaunchKernelGGL(k_encode_values, dim3(clamp_grid((n_tiles + kValWaves - 1) / kValWaves, (u64)cus * 4)),
-                       dim3(kValWaves * kWave), 0, stream, kbase, vbase, dsegs, dstates, n_segments, n_tiles, tcount,
-                       skeys, scodes);
+    if (n_chunks)
+        hipLaunchKernelGGL(k_encode_values, dim3((u32)((n_chunks + kValWaves - 1) / kValWaves)),
+                           dim3(kValWaves * kWave), 0, stream, kbase, vbase, dsegs, dstates, n_segments, (u32)n_chunks,
+                           R, ccount, segd, skeys, scodes);
     marks.mark(stream);
-    hipLaunchKernelGGL(k_plan_keys, dim3(1), dim3(kPlanThreads), 0, stream, dsegs, dstates, n_segments, n_tiles,
-                       tcount, tprefix, btile, bprev, ctrl);
+    if (!single)
+        hipLaunchKernelGGL(k_plan_segments, dim3(1), dim3(kPlanThreads), 0, stream, dsegs, dstates, n_segments, segd,
+                           ctrl);
+    const u64 max_units = (max_items + kWaves - 1) / kWaves + n_segments;
+    hipLaunchKernelGGL(k_measure_keys, dim3(clamp_grid(max_units, (u64)cus * 8)), dim3(kThreads), 0, stream, dsegs,
+                       dstates, n_segments, R, ccount, segd, skeys, binfo, gsum, g_shift, ctrl);
     marks.mark(stream);
-    const u32 key_grid = clamp_grid(max_items, (u64)cus * 8);
-    hipLaunchKernelGGL(k_measure_keys, dim3(key_grid), dim3(kThreads), 0, stream, dsegs, dstates, n_segments, n_tiles,
-                       tprefix, btile, bprev, skeys, binfo, ctrl);
-    marks.mark(stream);
-    hipLaunchKernelGGL(k_scan_items, dim3(1), dim3(kPlanThreads), 0, stream, dsegs, dstates, n_segments, binfo, ioff,
-                       ctrl);
-    marks.mark(stream);
-    hipLaunchKernelGGL(k_pack_keys, dim3(key_grid), dim3(kThreads), 0, stream, dsegs, dstates, n_segments, n_tiles,
-                       tprefix, btile, bprev, skeys, scodes, binfo, ioff, out, (u64)out_capacity, d_out_offsets,
-                       single ? 1u : 0u, d_status, ctrl);
+    hipLaunchKernelGGL(k_pack_keys, dim3(clamp_grid(max_units, (u64)cus * 3)), dim3(kThreads), 0, stream, dsegs,
+                       dstates, n_segments, R, ccount, segd, skeys, scodes, binfo, gsum, g_shift, out,
+                       (u64)out_capacity, d_out_offsets, single ? 1u : 0u, d_status, ctrl);
     marks.mark(stream);
     return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
 }
@@ -262,7 +277,7 @@ using namespace fsgd;
 extern "C" {
 
 size_t fastsgd_compressed_size(uint64_t n, const fastsgd_params* p) {
-    if (!params_ok(p) || n > 0xFFFFFFFFull) return 0;
+    if (!params_ok(p) || n > kMaxElems) return 0;
     const u64 KB = p->block_keys, nb = (n + KB - 1) / KB;
     const u64 per_block = 8 * ((KB * p->flag_bits + 63) / 64 + (KB * 32 + 63) / 64);
     return (size_t)(kHeaderBytes + ((n + 7) & ~7ull) + 16 * nb + nb * per_block);
@@ -283,7 +298,7 @@ size_t fastsgd_decompress_workspace_size(uint32_t n_segments) {
 fastsgd_status fastsgd_compress(const uint32_t* d_keys, const float* d_values, uint64_t n, const fastsgd_params* p,
                                 void* d_out, size_t out_capacity, uint64_t* d_out_bytes, uint32_t* d_status,
                                 void* d_workspace, size_t workspace_bytes, void* hip_stream) {
-    if (n > 0xFFFFFFFFull) return FASTSGD_ERR_INVALID_ARG;
+    if (n > kMaxElems) return FASTSGD_ERR_INVALID_ARG;
     const u64 offs[2] = {0, n};
     return compress_impl(d_keys, d_values, offs, 1, p, 0, d_out, out_capacity, d_out_bytes, d_status, d_workspace,
                          workspace_bytes, hip_stream, true);
@@ -294,7 +309,7 @@ fastsgd_status fastsgd_profile_compress(const uint32_t* d_keys, const float* d_v
                                         uint64_t* d_out_bytes, uint32_t* d_status, void* d_workspace,
                                         size_t workspace_bytes, void* hip_stream, uint32_t iterations,
                                         float* kernel_ms) {
-    if (n > 0xFFFFFFFFull) return FASTSGD_ERR_INVALID_ARG;
+    if (n > kMaxElems) return FASTSGD_ERR_INVALID_ARG;
     const u64 offs[2] = {0, n};
     return profile_loop(FASTSGD_PROFILE_COMPRESS_KERNELS, iterations, kernel_ms, static_cast<hipStream_t>(hip_stream),
                         [&](Marks m) {

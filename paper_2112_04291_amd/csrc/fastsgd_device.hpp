@@ -13,61 +13,72 @@ typedef uint64_t u64;
 typedef int64_t i64;
 
 constexpr u32 kWave = 64;
-constexpr u32 kThreads = 256;                 // workgroup size of every streaming kernel
+constexpr u32 kThreads = 256;                 // workgroup size of the streaming kernels
 constexpr u32 kWaves = kThreads / kWave;
-constexpr u32 kTile = 4096;                   // elements per tile: 4 float4 per thread
+constexpr u32 kRow = 256;                     // elements of one row: a float4 per lane of a wave
+constexpr u32 kTileRows = 16;                 // rows a wave holds in registers at a time
+constexpr u32 kTile = kRow * kTileRows;       // 4096 elements
 constexpr u32 kHeaderBytes = 64;
 constexpr u32 kMagic = 0x44475346u;           // "FSGD"
 constexpr u32 kVersion = 1;
 constexpr u32 kBins = 16;                     // exponent bins of the exact abs-sum (16 exponents each)
 constexpr u32 kMaxKB = 4096;
+constexpr u32 kChunkTarget = 4096;            // chunks a call's elements are cut into (one per wave of the value pass)
+constexpr u32 kMaxSegChunks = kChunkTarget;   // no segment has more chunks than this
+constexpr u32 kMaxGroups = 2048;              // groups of key blocks whose sizes are added up by atomics
+constexpr u32 kSub = 1024;                    // keys of a key block a wave handles at a time (16 rows of 64)
 
 // Host-built description of one gradient (segment) of a call.
 struct SegInfo {
     u64 elem_begin;     // first element, counted from the 16-byte-aligned base of the arrays
     u64 elem_count;
-    u64 tile_begin;     // first tile of this segment in the call's tile numbering
     double base;
+    u32 tile_begin;     // first tile of the segment in the abs-sum pass
+    u32 chunk_begin;    // first chunk of the segment in the value pass
     u32 tau, flag_bits, block_keys, pad;
 };
+static_assert(sizeof(SegInfo) == 48, "segment record layout");
 
 // Device-computed state of one segment.
 struct SegState {
     double sum;         // Algorithm 1 line 1
     u32 thr_bits;       // bit pattern of the early-stop threshold (Algorithm 1 line 2); 0xFFFFFFFF = keep nothing
-    u32 pad0;
-    u64 rank_begin;     // global rank of the segment's first survivor
+    u32 nb;             // key blocks (batch calls; a single gradient derives it from the survivor count)
     u64 d;              // survivors
     u64 item_begin;     // first work item (key block) of the segment
-    u64 stream_begin;   // byte offset of the segment's stream in the output
-    u32 nb;             // key blocks
-    u32 pad[3];
+    u64 unit_begin;     // first work unit (kWaves key blocks of one segment) of the segment
+    u64 pad;
     u32 B[128];         // B[c-1] = bit pattern of the boundary of code c
 };
 
-// Per key block, filled by the key encoder, consumed by the finaliser.
-struct BlockInfo { u32 preKey, M, payload_bits, size8; };
+// Per key block (work item), filled by k_measure_keys, consumed by k_pack_keys.
+//   span8: 8-byte words the item adds to the output: its two planes and, for the first item of a
+//   segment, the segment's header, value plane and directory.
+struct BlockInfo { u32 preKey, M, payload_bits, span8; };
 
 struct Ctrl {
     u32 status;         // first device-detected fastsgd_status
     u32 pad0;
-    u64 total_items;    // work items of the key encoder
-    u64 total_d;        // survivors of the whole call
+    u64 total_items;    // batch calls: work items / units of the key encoder
+    u64 total_units;
     u64 pad[5];
 };
 static_assert(sizeof(Ctrl) == 64, "control block layout");
 
 struct EncodePlan {     // host-computed carve-up of the workspace
-    u64 n_tiles, max_items, total_n;
+    u64 max_chunks, max_items, total_n, max_slots;
     u32 n_segments, n_slots;
-    u64 off_ctrl, off_gbins, zero_end, zero_end_batch;    // [off_ctrl, zero_end*) is cleared per call
-    u64 off_tcount, off_tprefix, off_btile, off_bprev, off_binfo, off_ioff;
-    u64 off_seginfo, off_segstate, off_skeys, off_scodes, total;
+    u64 off_ctrl, off_segd, off_gsum, zero_end, off_gbins, zero_end_batch;   // [off_ctrl, zero_end*) is cleared per call
+    u64 off_ccount, off_binfo, off_seginfo, off_segstate, off_skeys, off_scodes, total;
 };
 
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ u32 lane_id() { return threadIdx.x & 63u; }
 __device__ __forceinline__ u32 wave_id() { return threadIdx.x >> 6; }
+__device__ __forceinline__ u32 uniform(u32 x) { return (u32)__builtin_amdgcn_readfirstlane((int)x); }
+__device__ __forceinline__ u64 uniform64(u64 x) {
+    return (u64)uniform((u32)x) | ((u64)uniform((u32)(x >> 32)) << 32);
+}
 
 __device__ __forceinline__ u32 wave_incl_scan(u32 x) {
 #pragma unroll
@@ -83,6 +94,11 @@ __device__ __forceinline__ u64 wave_incl_scan64(u64 x) {
         u64 y = __shfl_up((unsigned long long)x, d, 64);
         if (lane_id() >= d) x += y;
     }
+    return x;
+}
+__device__ __forceinline__ u32 wave_sum(u32 x) {
+#pragma unroll
+    for (u32 d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, 64);
     return x;
 }
 __device__ __forceinline__ u64 wave_sum64(u64 x) {
@@ -106,6 +122,21 @@ __device__ __forceinline__ u32 block_excl_scan(u32 x, u32* scratch, u32* total) 
 #pragma unroll
     for (u32 w = 0; w < kWaves; ++w) {
         u32 t = scratch[w];
+        if (w < wave_id()) base += t;
+        tot += t;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + incl - x;
+}
+__device__ __forceinline__ u64 block_excl_scan64(u64 x, u64* scratch, u64* total) {
+    u64 incl = wave_incl_scan64(x);
+    if (lane_id() == 63) scratch[wave_id()] = incl;
+    __syncthreads();
+    u64 base = 0, tot = 0;
+#pragma unroll
+    for (u32 w = 0; w < kWaves; ++w) {
+        u64 t = scratch[w];
         if (w < wave_id()) base += t;
         tot += t;
     }
@@ -144,15 +175,37 @@ __device__ __forceinline__ void power_chain(double base, u32 tau, double* P) {
     for (u32 c = 1; c <= tau; ++c) { p = p * base; P[c] = p; }
 }
 
-__device__ __forceinline__ u32 find_segment(const SegInfo* segs, u32 n_segments, u64 tile) {
-    u32 lo = 0, hi = n_segments;            // last segment with tile_begin <= tile that is not empty of tiles
+// Last segment whose first tile is <= tile (segments without tiles share their successor's value).
+__device__ __forceinline__ u32 find_tile_segment(const SegInfo* segs, u32 n_segments, u32 tile) {
+    u32 lo = 0, hi = n_segments;
     while (hi - lo > 1) {
         u32 mid = (lo + hi) >> 1;
         if (segs[mid].tile_begin <= tile) lo = mid; else hi = mid;
     }
     return lo;
 }
+__device__ __forceinline__ u32 find_chunk_segment(const SegInfo* segs, u32 n_segments, u32 chunk) {
+    u32 lo = 0, hi = n_segments;
+    while (hi - lo > 1) {
+        u32 mid = (lo + hi) >> 1;
+        if (segs[mid].chunk_begin <= chunk) lo = mid; else hi = mid;
+    }
+    return lo;
+}
 
 __device__ __forceinline__ void set_status(Ctrl* ctrl, u32 code) { atomicCAS(&ctrl->status, 0u, code); }
+
+__device__ __forceinline__ u64 align8(u64 x) { return (x + 7) & ~7ull; }
+
+// Level lengths of Algorithm 2's length flag for a block with maximal length M and l flag bits:
+// level i (1..2^l) holds ceil(i*M / 2^l) bits; a delta of `need` significant bits takes the
+// smallest level that holds it, i = floor((need-1) * 2^l / M) + 1 (level 1 for need = 0).
+// The division is by the block's M (<= 32) of a number below 1024, done as a multiplication by
+// ceil(2^16 / M), which is exact in that range.
+__device__ __forceinline__ u32 level_magic(u32 M) { return (65536u + M - 1u) / M; }
+__device__ __forceinline__ u32 level_of(u32 need, u32 l, u32 magic) {
+    return need ? ((((need - 1u) << l) * magic) >> 16) + 1u : 1u;
+}
+__device__ __forceinline__ u32 level_len(u32 level, u32 M, u32 l) { return (level * M + (1u << l) - 1u) >> l; }
 
 }  // namespace fsgd

@@ -1,12 +1,11 @@
 // Encoder kernels of the gfx950 FastSGD codec (Algorithms 1 and 2 of arXiv 2112.04291).
 //
-//   k_init           clears the per-call control words and scan descriptors, stores the segment table
+//   k_init           batch calls: clears the per-call control words, stores the segment table
 //   k_abs_sum        Algorithm 1 line 1: exact sum of |v| per segment (integer accumulation)
 //   k_tables         Algorithm 1 line 2 + Eq. 3 as a boundary table sum / b^c, c = 1..tau
 //   k_encode_values  Algorithm 1 lines 4-10: threshold test, code, sign, compaction of survivors
-//   k_plan_keys      tile counts -> global ranks; per segment: survivors d, key blocks, work items
+//   k_plan_segments  batch calls: per segment survivors d, key blocks, work-item numbering
 //   k_measure_keys   Algorithm 2, first loop, per key block: deltas, maxDelta -> M, size of the block
-//   k_scan_items     byte offsets of the key blocks
 //   k_pack_keys      Algorithm 2, second loop: length flags, bit packing; directory, headers, value planes
 #pragma once
 #include "fastsgd_device.hpp"
@@ -28,9 +27,9 @@ __global__ void k_store_segments(SegInfo* segs, SegBatch batch, u32 first, u32 c
 }
 
 // ---------------------------------------------------------------------------------------------
-// Tile geometry shared by the two passes over the values.  A segment's tiles start at its first
-// element rounded down to a multiple of 4 (so float4 loads stay aligned); thread (wave w, lane)
-// holds, for r = 0..3, the four elements  tile0 + w*1024 + r*256 + lane*4 + {0,1,2,3}.
+// Tile geometry of the abs-sum pass.  A segment's tiles start at its first element rounded down to
+// a multiple of 4 (so float4 loads stay aligned); thread (wave w, lane) holds, for r = 0..3, the
+// four elements  tile0 + w*1024 + r*256 + lane*4 + {0,1,2,3}.
 struct TileGeom {
     u64 tile0;      // element index of the tile's first slot
     u64 lo, hi;     // valid element range [lo, hi) of the segment
@@ -73,8 +72,8 @@ __device__ __forceinline__ void load_tile(const float* __restrict__ values, cons
 //
 // Records of kBinWords u64: words 2k, 2k+1 = low/high half sums of bin k, word 32 = non-finite flag.
 //   single gradient : every workgroup stores its one record at gbins[blockIdx.x] (plain stores, so
-//                     nothing has to be cleared beforehand), and the launch also clears the scan
-//                     descriptors and control words the later kernels rely on;
+//                     nothing has to be cleared beforehand), and the launch also clears the control
+//                     words and counters the later kernels rely on;
 //   batch           : a workgroup owns a contiguous run of tiles and adds a record to one of n_slots
 //                     copies of the segment's record each time it leaves a segment (atomics on
 //                     memory k_init cleared).
@@ -164,7 +163,7 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
         const u64 t_begin = blockIdx.x * per_wg;
         const u64 t_end = (t_begin + per_wg < n_tiles) ? t_begin + per_wg : n_tiles;
         for (u64 tile = t_begin; tile < t_end; ++tile) {
-            const u32 seg = find_segment(segs, n_segments, tile);
+            const u32 seg = find_tile_segment(segs, n_segments, (u32)tile);
             if (seg != cur_seg) {
                 if (cur_seg != 0xFFFFFFFFu) {
                     flush_bins<false>(bins, gbins + ((u64)cur_seg * n_slots + blockIdx.x % n_slots) * kBinWords, maxa);
@@ -185,35 +184,25 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
 // ---------------------------------------------------------------------------------------------
 // One workgroup per segment: add up the segment's records, fold the bins into a 384-bit integer
 // counting units of 2^-150, round once to binary64 (nearest, ties to even), then the boundary table.
+// The fold runs on 32-bit digits: bin word w (a sum below 2^60 at bit position 16*(w/2) + 32*(w%2))
+// is split over three digits and added by shared-memory atomics; one thread then propagates the
+// carries.  A second wave walks the power chain b^c meanwhile.
 constexpr u32 kTableThreads = 1024;
-
-__device__ __forceinline__ void wide_add(u64 (&L)[6], u64 x, u32 bitpos) {   // bitpos is a compile-time constant after unrolling
-    const u32 i = bitpos >> 6, sh = bitpos & 63u;
-    u64 parts[2] = {x << sh, sh ? (x >> (64u - sh)) : 0ull};
-    u64 carry = 0;
-#pragma unroll
-    for (u32 j = 0; j < 6; ++j) {
-        if (j >= i) {
-            const u64 add = (j - i < 2) ? parts[j - i] : 0ull;
-            const u64 s1 = L[j] + add;
-            const u64 c1 = s1 < add ? 1ull : 0ull;
-            const u64 s2 = s1 + carry;
-            const u64 c2 = s2 < carry ? 1ull : 0ull;
-            L[j] = s2;
-            carry = c1 + c2;
-        }
-    }
-}
+constexpr u32 kDigits = 12;
 
 __global__ void __launch_bounds__(kTableThreads)
 k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const u64* __restrict__ gbins,
          u32 n_slots, Ctrl* ctrl) {
     __shared__ u64 s_part[kTableThreads / 64][64];
+    __shared__ unsigned long long s_dig[kDigits];
     __shared__ double s_P[129];
     __shared__ double s_sum;
+    __shared__ u32 s_bad;
     const u32 seg = blockIdx.x, t = threadIdx.x;
     const SegInfo info = segs[seg];
     SegState* st = &states[seg];
+    if (t < kDigits) s_dig[t] = 0;
+    if (t == 0) s_bad = 0;
     {
         // thread (group, word) adds up word `word` of records group, group+16, ...; 64 loads in flight
         const u32 word = t & 63u, group = t >> 6;
@@ -232,21 +221,32 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
         s_part[group][word] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
     }
     __syncthreads();
-    if (t == 0) {
-        u64 rec[kBinWords];
+    if (t == 64) power_chain(info.base, info.tau, s_P);
+    if (t < kBinWords) {
+        u64 x = 0;
 #pragma unroll
-        for (u32 w = 0; w < kBinWords; ++w) {
-            u64 x = 0;
-#pragma unroll
-            for (u32 g = 0; g < kTableThreads / 64; ++g) x += s_part[g][w];
-            rec[w] = x;
+        for (u32 g = 0; g < kTableThreads / 64; ++g) x += s_part[g][t];
+        if (t < 2 * kBins) {
+            const u32 bitpos = 16u * (t >> 1) + 32u * (t & 1u);
+            const u32 q = bitpos >> 5, sh = bitpos & 31u;         // sh is 0 or 16
+            const u64 lo = x << sh, hi = sh ? (x >> (64u - sh)) : 0ull;
+            if (lo & 0xFFFFFFFFull) atomicAdd(&s_dig[q], (unsigned long long)(lo & 0xFFFFFFFFull));
+            if (lo >> 32) atomicAdd(&s_dig[q + 1], (unsigned long long)(lo >> 32));
+            if (hi) atomicAdd(&s_dig[q + 2], (unsigned long long)hi);
+        } else if (t == 2 * kBins && x != 0) {
+            s_bad = 1;
         }
-        // bin k holds lo + hi * 2^32 in units of 2^(16k - 150)
-        u64 L[6] = {0, 0, 0, 0, 0, 0};
+    }
+    __syncthreads();
+    if (t == 0) {
+        u64 L[6];
+        u64 carry = 0;
 #pragma unroll
-        for (u32 k = 0; k < kBins; ++k) {
-            wide_add(L, rec[2 * k], 16u * k);
-            wide_add(L, rec[2 * k + 1], 16u * k + 32u);
+        for (u32 i = 0; i < kDigits; i += 2) {
+            const u64 v0 = s_dig[i] + carry;
+            const u64 v1 = s_dig[i + 1] + (v0 >> 32);
+            carry = v1 >> 32;
+            L[i >> 1] = (v0 & 0xFFFFFFFFull) | (v1 << 32);
         }
         int hi_i = -1;
 #pragma unroll
@@ -273,11 +273,10 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
             const u64 bits = ((u64)(top - 150 + 1023) << 52) + (q - (1ull << 52));
             sum = __longlong_as_double((long long)bits);
         }
-        const bool bad = rec[2 * kBins] != 0;
+        const bool bad = s_bad != 0;
         if (bad) set_status(ctrl, FASTSGD_ERR_NONFINITE);
         st->sum = bad ? 0.0 : sum;
         s_sum = bad ? 0.0 : sum;
-        power_chain(info.base, info.tau, s_P);
     }
     __syncthreads();
     const double sum = s_sum;
@@ -290,18 +289,17 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Second pass over the values (Algorithm 1 lines 4-10).  A pure streaming pass: no tile depends on
-// another.  Every WAVE walks its own tiles of 4096 elements (tile = wave + k * waves):
+// Second pass over the values (Algorithm 1 lines 4-10).  A pure streaming pass: no wave depends on
+// another.  The elements of a call are cut into chunks of R rows (a row = 256 elements, a float4 per
+// lane); every WAVE owns one chunk and walks it in tiles of 16 rows:
 //   16 float4 loads per lane -> keep test |v| >= threshold -> survivors staged in the wave's slice of
 //   shared memory at their rank inside the tile (ballot + mbcnt) -> densely over the staged survivors
-//   only: code by binary search in the boundary table, key fetch -> code byte and key written to the
-//   TILE'S OWN SLOT of the scratch arrays (entry tile*4096 + rank in tile) -> survivor count of the tile.
-// Global ranks are fixed afterwards by a scan over the 4-byte tile counts (k_plan_keys); the key
-// encoder gathers through that scan.  This keeps look-back chains and ticket counters -- dependent
-// memory round trips that cost microseconds each while the memory system is saturated -- out of the
-// one kernel that has to run at memory speed.
-// Lane `lane` holds, for row r = 0..15, elements tile0 + r*256 + lane*4 + {0..3}.
-constexpr u32 kRows = kTile / 256;       // 16 float4 rows per wave tile
+//   only: code by binary search in the boundary table, key fetch -> code byte and key appended to the
+//   CHUNK'S OWN SLOT of the scratch arrays (the chunk's first element index + rank in the chunk).
+// The chunk's survivor count goes to ccount[chunk] and is added to the segment's total.  Global ranks
+// are never materialised: the key encoder scans the (at most 4096) chunk counts of a segment in
+// shared memory and gathers through that scan.
+// Lane `lane` holds, for row r = 0..15 of a tile, elements tile0 + r*256 + lane*4 + {0..3}.
 constexpr u32 kStage = 1024;             // staged survivors per wave and round (4 rows can never exceed it)
 constexpr u32 kValWaves = 4;             // waves per workgroup of the value encoder (they never synchronise)
 constexpr u32 kGather = 8;               // key fetches a lane keeps in flight
@@ -317,52 +315,70 @@ __device__ __forceinline__ u32 lanes_below(u64 mask) {
     return __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
 }
 
-struct WaveTile {        // wave-uniform description of the tile a wave holds
-    u64 tile;            // tile number (>= n_tiles: none)
-    u64 tile0;           // element index of its first slot
-    u32 seg;
-    u32 lo_off, hi_off;  // slots [lo_off, hi_off) belong to the segment
+struct Chunk {           // wave-uniform description of the chunk a wave owns
+    u32 seg, nrows;
+    u64 e0;              // element index of the chunk's first slot
+    u64 slot0;           // scratch entry of the chunk's first survivor
+    u64 lo, hi;          // valid elements [lo, hi) of the segment
 };
 
-__device__ __forceinline__ WaveTile describe_tile(const SegInfo* segs, u32 n_segments, u64 n_tiles, u64 tile) {
-    WaveTile wt;
-    wt.tile = tile; wt.tile0 = 0; wt.seg = 0; wt.lo_off = 0; wt.hi_off = 0;
-    if (tile < n_tiles) {
-        wt.seg = (n_segments == 1) ? 0u : find_segment(segs, n_segments, tile);
-        const TileGeom g = tile_geom(segs[wt.seg], tile);
-        wt.tile0 = g.tile0;
-        wt.lo_off = g.lo > g.tile0 ? (u32)(g.lo - g.tile0) : 0u;
-        wt.hi_off = g.hi - g.tile0 < kTile ? (u32)(g.hi - g.tile0) : kTile;
-    }
-    return wt;
+// Rows of a segment, counted from its first element rounded down to a multiple of 4.
+__device__ __forceinline__ u64 segment_rows(const SegInfo& s) {
+    return (s.elem_begin + s.elem_count - (s.elem_begin & ~3ull) + kRow - 1) / kRow;
+}
+// Scratch entry of the first slot of a segment's chunk j.  Segment s is shifted by 4*s entries so
+// that the rounding-down of its first element can never reach into its predecessor's entries.
+__device__ __forceinline__ u64 chunk_slot0(const SegInfo& s, u32 seg, u32 j, u32 R) {
+    return (s.elem_begin & ~3ull) + (u64)j * R * kRow + 4ull * seg;
 }
 
-__device__ __forceinline__ bool is_full(const WaveTile& wt) { return wt.lo_off == 0 && wt.hi_off == kTile; }
+__device__ __forceinline__ Chunk chunk_geom(const SegInfo* __restrict__ segs, u32 n_segments, u32 chunk, u32 R) {
+    Chunk c;
+    c.seg = (n_segments == 1) ? 0u : find_chunk_segment(segs, n_segments, chunk);
+    const SegInfo s = segs[c.seg];
+    const u32 j = chunk - s.chunk_begin;
+    const u64 rows = segment_rows(s), r0 = (u64)j * R;
+    c.nrows = (u32)(rows - r0 < R ? rows - r0 : R);
+    c.e0 = (s.elem_begin & ~3ull) + r0 * kRow;
+    c.slot0 = chunk_slot0(s, c.seg, j, R);
+    c.lo = s.elem_begin;
+    c.hi = s.elem_begin + s.elem_count;
+    return c;
+}
 
-// A tile that lies wholly inside its segment: 16 coalesced float4 loads per lane.
-__device__ __forceinline__ void load_full_tile(const float* __restrict__ values, const WaveTile& wt, u32 lane,
-                                               u32 (&bits)[kRows][4]) {
-    const uint4* src = reinterpret_cast<const uint4*>(values + wt.tile0) + lane;
+// Rows [0, rows) of the tile at element te, all inside the segment: coalesced float4 loads.
+__device__ __forceinline__ void load_rows(const float* __restrict__ values, u64 te, u32 rows, u32 lane,
+                                          u32 (&bits)[kTileRows][4]) {
+    const uint4* src = reinterpret_cast<const uint4*>(values + te) + lane;
+    if (rows == kTileRows) {
 #pragma unroll
-    for (u32 r = 0; r < kRows; ++r) {
-        const uint4 q = src[r * 64u];
-        bits[r][0] = q.x; bits[r][1] = q.y; bits[r][2] = q.z; bits[r][3] = q.w;
+        for (u32 r = 0; r < kTileRows; ++r) {
+            const uint4 q = src[r * 64u];
+            bits[r][0] = q.x; bits[r][1] = q.y; bits[r][2] = q.z; bits[r][3] = q.w;
+        }
+    } else {
+#pragma unroll
+        for (u32 r = 0; r < kTileRows; ++r) {
+            uint4 q = make_uint4(0u, 0u, 0u, 0u);
+            if (r < rows) q = src[r * 64u];
+            bits[r][0] = q.x; bits[r][1] = q.y; bits[r][2] = q.z; bits[r][3] = q.w;
+        }
     }
 }
 
-// A tile cut by a segment boundary (at most two per segment): slots outside the segment become zero,
-// which never survives.  Goes through the wave's staging buffer in rolled loops so that this rare path
-// costs no registers; the buffer must be free when it is called.
-__device__ __forceinline__ void load_partial_tile(const float* __restrict__ values, const WaveTile& wt, u32 lane,
-                                                  u32* stage, u32 (&bits)[kRows][4]) {
-    const float* tvals = values + wt.tile0;
+// A tile cut by a segment boundary (at most two per segment): slots outside [lo_off, hi_off) become
+// zero, which never survives.  Goes through the wave's staging buffer in rolled loops so that this
+// rare path costs no registers; the buffer must be free when it is called.
+__device__ __forceinline__ void load_ragged(const float* __restrict__ values, u64 te, u32 lo_off, u32 hi_off,
+                                            u32 lane, u32* stage, u32 (&bits)[kTileRows][4]) {
+    const float* tvals = values + te;
 #pragma unroll
-    for (u32 q = 0; q < kRows / 4; ++q) {
+    for (u32 q = 0; q < kTileRows / 4; ++q) {
         __builtin_amdgcn_wave_barrier();
 #pragma unroll 1
         for (u32 i = 0; i < 16; ++i) {
             const u32 off = q * 1024u + i * 64u + lane;
-            stage[i * 64u + lane] = (off >= wt.lo_off && off < wt.hi_off) ? __float_as_uint(tvals[off]) : 0u;
+            stage[i * 64u + lane] = (off >= lo_off && off < hi_off) ? __float_as_uint(tvals[off]) : 0u;
         }
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -379,42 +395,55 @@ __device__ __forceinline__ void load_partial_tile(const float* __restrict__ valu
 __global__ void __launch_bounds__(kValWaves * kWave) __attribute__((amdgpu_waves_per_eu(4, 8)))
 k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                 const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
-                u64 n_tiles, u32* __restrict__ tcount, u32* __restrict__ skeys, uint8_t* __restrict__ scodes) {
+                u32 n_chunks, u32 R, u32* __restrict__ ccount, unsigned long long* __restrict__ segd,
+                u32* __restrict__ skeys, uint8_t* __restrict__ scodes) {
     __shared__ u32 s_Ball[kValWaves][128];
     __shared__ u32 s_valall[kValWaves][kStage];
     __shared__ uint16_t s_idxall[kValWaves][kStage];
     const u32 lane = lane_id();
-    const u32 w = (u32)__builtin_amdgcn_readfirstlane((int)wave_id());   // tell the compiler it is wave-uniform
+    const u32 w = uniform(wave_id());
     u32* s_B = s_Ball[w];
     u32* s_val = s_valall[w];
     uint16_t* s_idx = s_idxall[w];
-    const u64 stride = (u64)gridDim.x * kValWaves;
-    u32 cur_seg = 0xFFFFFFFFu, thr = 0xFFFFFFFFu, tau = 1;
+    const u32 chunk = blockIdx.x * kValWaves + w;
+    if (chunk >= n_chunks) return;
+    const Chunk ck = chunk_geom(segs, n_segments, chunk, R);
+    const u32 thr = states[ck.seg].thr_bits;
+    const u32 tau = segs[ck.seg].tau;
+    s_B[lane] = states[ck.seg].B[lane];
+    s_B[lane + 64] = states[ck.seg].B[lane + 64];
+    const u32 ntiles = (ck.nrows + kTileRows - 1) / kTileRows;
 
-    u32 bits[kRows][4];
-    WaveTile cur = describe_tile(segs, n_segments, n_tiles, (u64)blockIdx.x * kValWaves + w);
-    if (cur.tile >= n_tiles) return;
-    if (is_full(cur)) load_full_tile(values, cur, lane, bits);
-    else load_partial_tile(values, cur, lane, s_val, bits);
+    // rows of tile t and whether all of them lie inside the segment
+    auto tile_rows = [&](u32 t) -> u32 { return ck.nrows - t * kTileRows < kTileRows ? ck.nrows - t * kTileRows : kTileRows; };
+    auto tile_interior = [&](u32 t) -> bool {
+        const u64 te = ck.e0 + (u64)t * kTile;
+        return te >= ck.lo && te + (u64)tile_rows(t) * kRow <= ck.hi;
+    };
+    auto tile_ragged_load = [&](u32 t, u32 (&b)[kTileRows][4]) {
+        const u64 te = ck.e0 + (u64)t * kTile;
+        const u32 lo_off = ck.lo > te ? (u32)(ck.lo - te) : 0u;
+        u64 hi_off = ck.hi - te;
+        const u64 cap = (u64)tile_rows(t) * kRow;
+        if (hi_off > cap) hi_off = cap;
+        load_ragged(values, te, lo_off, (u32)hi_off, lane, s_val, b);
+    };
 
-    for (;;) {
-        if (cur.seg != cur_seg) {
-            cur_seg = cur.seg;
-            thr = states[cur_seg].thr_bits;
-            tau = segs[cur_seg].tau;
-            s_B[lane] = states[cur_seg].B[lane];
-            s_B[lane + 64] = states[cur_seg].B[lane + 64];
-        }
+    u32 bits[kTileRows][4];
+    if (tile_interior(0)) load_rows(values, ck.e0, tile_rows(0), lane, bits);
+    else tile_ragged_load(0, bits);
+
+    const float thr_f = __uint_as_float(thr);
+    u32 cbase = 0;                           // survivors of the chunk so far
+    for (u32 t = 0; t < ntiles; ++t) {
+        const u64 te = ck.e0 + (u64)t * kTile;
         // survivors of the tile: per-lane count, then one wave reduction
-        const float thr_f = __uint_as_float(thr);
         u32 mine = 0;
 #pragma unroll
-        for (u32 r = 0; r < kRows; ++r)
+        for (u32 r = 0; r < kTileRows; ++r)
 #pragma unroll
             for (u32 c = 0; c < 4; ++c) mine += keeps(bits[r][c], thr_f) ? 1u : 0u;
-#pragma unroll
-        for (u32 d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d, 64);
-        const u32 total = (u32)__builtin_amdgcn_readfirstlane((int)mine);
+        const u32 total = uniform(wave_sum(mine));
 
         float thr_s = thr_f;
         asm volatile("" : "+s"(thr_s));     // an opaque copy: the compare masks of the count pass stay dead
@@ -438,9 +467,9 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                 }
             return staged + rowcnt;
         };
-        // staged survivors [0, cnt) of tile `wt` go to entries slot0 + j of the tile's slot
-        auto write_staged = [&](const WaveTile& wt, u32 cnt, u64 slot0) {
-            const u32* tkeys = keys + wt.tile0;
+        // staged survivors [0, cnt) of the tile go to scratch entries slot + j
+        auto write_staged = [&](u32 cnt, u64 slot) {
+            const u32* tkeys = keys + te;
             __builtin_amdgcn_wave_barrier();
             for (u32 j0 = 0; j0 < cnt; j0 += 64u * kGather) {
                 u32 key[kGather];
@@ -461,8 +490,8 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                             const u32 mid = (lo + hi) >> 1;
                             if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
                         }
-                        scodes[slot0 + j] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
-                        skeys[slot0 + j] = key[k];
+                        scodes[slot + j] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
+                        skeys[slot + j] = key[k];
                     }
                     __builtin_amdgcn_sched_barrier(0);            // one search at a time: keeps registers low
                 }
@@ -470,22 +499,21 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
             __builtin_amdgcn_wave_barrier();
         };
 
-        const WaveTile done = cur;
-        const u64 slot0 = done.tile * kTile;
+        const u64 slot = ck.slot0 + cbase;
         const bool fits = total <= kStage;
         if (fits) {
             if (total) {
                 u32 staged = 0;
 #pragma unroll
-                for (u32 r = 0; r < kRows; ++r) staged = stage_row(bits[r], r, staged);
+                for (u32 r = 0; r < kTileRows; ++r) staged = stage_row(bits[r], r, staged);
             }
         } else {
             // more than a quarter of the tile survives (far from the sparse regime this codec is for):
             // no staging, every lane codes and writes its own survivors
-            const u32* tkeys = keys + done.tile0;
+            const u32* tkeys = keys + te;
             u32 emitted = 0;
 #pragma unroll
-            for (u32 r = 0; r < kRows; ++r) {
+            for (u32 r = 0; r < kTileRows; ++r) {
                 u64 m[4];
                 u32 below = 0, rowcnt = 0;
 #pragma unroll
@@ -504,8 +532,8 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                             const u32 mid = (lo + hi) >> 1;
                             if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
                         }
-                        scodes[slot0 + pos] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
-                        skeys[slot0 + pos] = tkeys[r * 256u + lane * 4u + c];
+                        scodes[slot + pos] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
+                        skeys[slot + pos] = tkeys[r * 256u + lane * 4u + c];
                         ++pos;
                     }
                 emitted += rowcnt;
@@ -513,383 +541,499 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
             }
         }
         // the registers are free: start on the next tile before finishing this one
-        cur = describe_tile(segs, n_segments, n_tiles, done.tile + stride);
-        const bool early = cur.tile < n_tiles && is_full(cur);
-        if (early) load_full_tile(values, cur, lane, bits);
-        if (fits && total) write_staged(done, total, slot0);
-        if (lane == 0) tcount[done.tile] = total;
-        if (cur.tile < n_tiles && !early) load_partial_tile(values, cur, lane, s_val, bits);
-        if (cur.tile >= n_tiles) break;
+        const bool more = t + 1 < ntiles;
+        const bool early = more && tile_interior(t + 1);
+        if (early) load_rows(values, te + kTile, tile_rows(t + 1), lane, bits);
+        if (fits && total) write_staged(total, slot);
+        if (more && !early) tile_ragged_load(t + 1, bits);
+        cbase += total;
+    }
+    if (lane == 0) {
+        ccount[chunk] = cbase;
+        if (cbase) atomicAdd(&segd[ck.seg], (unsigned long long)cbase);
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// One workgroup turns the tile counts into global ranks and plans the key encoder:
-//   A  inclusive scan of the tile counts -> tprefix
-//   B  per segment: first rank, survivors d, key blocks, work-item numbering (one item per key block,
-//      and one for a segment without any)
-//   C  for every key block the tile that holds its first key and the tile that holds the key before it
+// Batch calls: one workgroup numbers the key encoder's work.  A work item is one key block (a segment
+// without survivors still has one item, which carries its header); a work unit is kWaves consecutive
+// items of one segment, the share of one workgroup iteration.
 constexpr u32 kPlanThreads = 1024;
 
 __global__ void __launch_bounds__(kPlanThreads)
-k_plan_keys(const SegInfo* __restrict__ segs, SegState* __restrict__ states, u32 n_segments, u64 n_tiles,
-            const u32* __restrict__ tcount, u64* __restrict__ tprefix, u32* __restrict__ block_tile,
-            u32* __restrict__ block_prev_tile, Ctrl* ctrl) {
-    __shared__ u64 s_wave[kPlanThreads / 64];
-    __shared__ u64 s_carry;
+k_plan_segments(const SegInfo* __restrict__ segs, SegState* __restrict__ states, u32 n_segments,
+                const unsigned long long* __restrict__ segd, Ctrl* ctrl) {
+    __shared__ u64 s_wave[2][kPlanThreads / 64];
+    __shared__ u64 s_carry[2];
     const u32 t = threadIdx.x, lane = lane_id(), w = wave_id();
     constexpr u32 kW = kPlanThreads / 64;
-
-    auto block_scan = [&](u64 x, u64* total) -> u64 {       // exclusive scan over the workgroup
-        const u64 incl = wave_incl_scan64(x);
-        if (lane == 63) s_wave[w] = incl;
-        __syncthreads();
-        u64 base = 0, tot = 0;
-        for (u32 k = 0; k < kW; ++k) { const u64 v = s_wave[k]; if (k < w) base += v; tot += v; }
-        __syncthreads();
-        *total = tot;
-        return base + incl - x;
-    };
-
-    // A: every thread owns a run of consecutive tiles
-    const u64 per = (n_tiles + kPlanThreads - 1) / kPlanThreads;
-    const u64 a = (u64)t * per < n_tiles ? (u64)t * per : n_tiles;
-    const u64 b = a + per < n_tiles ? a + per : n_tiles;
-    u64 mine = 0;
-    for (u64 i = a; i < b; ++i) mine += tcount[i];
-    u64 total_d;
-    u64 run = block_scan(mine, &total_d);
-    for (u64 i = a; i < b; ++i) { run += tcount[i]; tprefix[i] = run; }
-    __syncthreads();
-
-    // B
-    if (t == 0) s_carry = 0;
+    if (t < 2) s_carry[t] = 0;
     __syncthreads();
     for (u32 s0 = 0; s0 < n_segments; s0 += kPlanThreads) {
         const u32 s = s0 + t;
-        u64 items = 0;
+        u64 items = 0, units = 0, d = 0;
+        u32 nb = 0;
         if (s < n_segments) {
-            const u64 tb = segs[s].tile_begin;
-            const u64 te = (s + 1 < n_segments) ? segs[s + 1].tile_begin : n_tiles;
-            const u64 rb = tb ? tprefix[tb - 1] : 0;
-            const u64 re = te ? tprefix[te - 1] : 0;
-            const u64 d = re - rb;
+            d = segd[s];
             const u32 KB = segs[s].block_keys;
-            const u32 nb = (u32)((d + KB - 1) / KB);
-            states[s].rank_begin = rb;
+            nb = (u32)((d + KB - 1) / KB);
+            items = nb ? nb : 1u;
+            units = (items + kWaves - 1) / kWaves;
+        }
+        const u64 ii = wave_incl_scan64(items), iu = wave_incl_scan64(units);
+        if (lane == 63) { s_wave[0][w] = ii; s_wave[1][w] = iu; }
+        __syncthreads();
+        u64 bi = s_carry[0], bu = s_carry[1], ti = 0, tu = 0;
+        for (u32 k = 0; k < kW; ++k) {
+            const u64 a = s_wave[0][k], b = s_wave[1][k];
+            if (k < w) { bi += a; bu += b; }
+            ti += a; tu += b;
+        }
+        if (s < n_segments) {
             states[s].d = d;
             states[s].nb = nb;
-            items = nb ? nb : 1u;
+            states[s].item_begin = bi + ii - items;
+            states[s].unit_begin = bu + iu - units;
         }
-        u64 total;
-        const u64 ex = block_scan(items, &total);
-        if (s < n_segments) states[s].item_begin = s_carry + ex;
         __syncthreads();
-        if (t == 0) s_carry += total;
+        if (t == 0) { s_carry[0] += ti; s_carry[1] += tu; }
         __syncthreads();
     }
-    if (t == 0) { ctrl->total_items = s_carry; ctrl->total_d = total_d; }
-
-    // C: tile i holds the segment-relative ranks [lo, hi); it owns block starts b*KB in that range
-    // (block_tile) and the ranks b*KB - 1 in that range (block_prev_tile)
-    for (u64 i = t; i < n_tiles; i += kPlanThreads) {
-        const u32 s = (n_segments == 1) ? 0u : find_segment(segs, n_segments, i);
-        const u64 rb = states[s].rank_begin, ib = states[s].item_begin;
-        const u64 KB = segs[s].block_keys;
-        const u64 lo = (i ? tprefix[i - 1] : 0) - rb, hi = tprefix[i] - rb;
-        if (hi > lo) {
-            for (u64 blk = (lo + KB - 1) / KB; blk * KB < hi; ++blk) block_tile[ib + blk] = (u32)i;
-            const u64 nb = states[s].nb;
-            for (u64 blk = (lo + KB) / KB; blk * KB - 1 < hi && blk < nb; ++blk) block_prev_tile[ib + blk] = (u32)i;
-        }
-    }
+    if (t == 0) { ctrl->total_items = s_carry[0]; ctrl->total_units = s_carry[1]; }
 }
 
-__device__ __forceinline__ u32 find_item_segment(const SegState* states, u32 n_segments, u64 item) {
+// ---------------------------------------------------------------------------------------------
+// Algorithm 2 on one block of surviving keys per WAVE, in two launches:
+//   k_measure_keys  first loop of Algorithm 2 (deltas, maxDelta -> M), the size of the block's planes,
+//                   and the sum of those sizes per group of 2^g_shift blocks (atomics);
+//   k_pack_keys     byte offset of the block (scan of the group sums in shared memory + the sizes of
+//                   the blocks before it in its group), second loop (length flags, bit packing),
+//                   directory entry, header, value plane.
+// Both fetch a block's keys through the scan of the segment's chunk counts: rank r of the segment lives
+// in the chunk j with P[j] <= r < P[j+1], at entry chunk_slot0(j) + (r - P[j]) of the scratch arrays.
+// A wave takes the block 1024 keys at a time; lane `lane` holds, for row k = 0..15, key 64*k + lane.
+struct KeyUnit {        // workgroup-uniform
+    u32 seg, KB, l, nb, blk0, cb, nch;
+    u64 d, item_begin;
+};
+
+__device__ __forceinline__ u32 find_unit_segment(const SegState* states, u32 n_segments, u64 unit) {
     u32 lo = 0, hi = n_segments;
     while (hi - lo > 1) {
         u32 mid = (lo + hi) >> 1;
-        if (states[mid].item_begin <= item) lo = mid; else hi = mid;
+        if (states[mid].unit_begin <= unit) lo = mid; else hi = mid;
     }
     return lo;
 }
 
-__device__ __forceinline__ u64 align8(u64 x) { return (x + 7) & ~7ull; }
+__device__ __forceinline__ KeyUnit key_unit(const SegInfo* __restrict__ segs, const SegState* __restrict__ states,
+                                            u32 n_segments, u32 R, const unsigned long long* __restrict__ segd,
+                                            u64 unit) {
+    KeyUnit ku;
+    if (n_segments == 1) {
+        ku.seg = 0;
+        ku.KB = segs[0].block_keys;
+        ku.d = segd[0];
+        ku.nb = (u32)((ku.d + ku.KB - 1) / ku.KB);
+        ku.item_begin = 0;
+        ku.blk0 = (u32)unit * kWaves;
+    } else {
+        ku.seg = find_unit_segment(states, n_segments, unit);
+        ku.KB = segs[ku.seg].block_keys;
+        ku.d = states[ku.seg].d;
+        ku.nb = states[ku.seg].nb;
+        ku.item_begin = states[ku.seg].item_begin;
+        ku.blk0 = (u32)(unit - states[ku.seg].unit_begin) * kWaves;
+    }
+    ku.l = segs[ku.seg].flag_bits;
+    ku.cb = segs[ku.seg].chunk_begin;
+    ku.nch = segs[ku.seg].elem_count ? (u32)((segment_rows(segs[ku.seg]) + R - 1) / R) : 0u;
+    return ku;
+}
 
-// ---------------------------------------------------------------------------------------------
-// Algorithm 2 on one block of surviving keys per work item, in two launches with a scan between:
-//   k_measure_keys  first loop of Algorithm 2 (deltas, maxDelta -> M) and the size of the block's planes
-//   k_scan_items    byte offset of every block (exclusive scan over the items)
-//   k_pack_keys     second loop (length flags, bit packing), directory entry, header, value plane
-// Both key kernels fetch a block's keys through the tile scan: rank r lives in the tile T with
-// tprefix[T-1] <= r < tprefix[T], at entry T*4096 + (r - tprefix[T-1]) of the scratch arrays.
-struct BlockGeom {
-    u32 seg, blk, cnt, KB, l, nb;
-    u64 d, first, grank;       // survivors of the segment; rank of the block's first key in the segment / globally
+// In-place exclusive scan of arr[0..n) in shared memory by the whole workgroup, arr[n] = total;
+// n <= PER * kThreads.  Starts and ends with a barrier.
+template <typename T, u32 PER>
+__device__ __forceinline__ void lds_excl_scan(T* arr, u32 n, T* scratch) {
+    const u32 t = threadIdx.x;
+    __syncthreads();
+    T v[PER], sum = 0;
+#pragma unroll
+    for (u32 k = 0; k < PER; ++k) {
+        const u32 j = t * PER + k;
+        v[k] = j < n ? arr[j] : (T)0;
+        sum += v[k];
+    }
+    // wave scan + workgroup combine
+    T incl;
+    if constexpr (sizeof(T) == 8) incl = wave_incl_scan64(sum); else incl = wave_incl_scan(sum);
+    if (lane_id() == 63) scratch[wave_id()] = incl;
+    __syncthreads();
+    T base = 0, tot = 0;
+#pragma unroll
+    for (u32 w = 0; w < kWaves; ++w) {
+        const T x = scratch[w];
+        if (w < wave_id()) base += x;
+        tot += x;
+    }
+    T run = base + incl - sum;
+#pragma unroll
+    for (u32 k = 0; k < PER; ++k) {
+        const u32 j = t * PER + k;
+        if (j < n) arr[j] = run;
+        run += v[k];
+    }
+    if (t == 0) arr[n] = tot;
+    __syncthreads();
+}
+
+// P[j] = survivors of the segment in its chunks before j, j = 0..nch.
+__device__ __forceinline__ void build_prefix(const u32* __restrict__ ccount, u32 cb, u32 nch, u32* P, u32* scratch) {
+    __syncthreads();
+    for (u32 j = threadIdx.x; j < nch; j += kThreads) P[j] = ccount[cb + j];
+    lds_excl_scan<u32, kMaxSegChunks / kThreads>(P, nch, scratch);
+}
+
+// Largest j in [lo, hi] with P[j] <= r.
+__device__ __forceinline__ u32 find_chunk(const u32* P, u32 lo, u32 hi, u32 r) {
+    while (lo < hi) {
+        const u32 mid = (lo + hi + 1) >> 1;
+        if (P[mid] <= r) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+struct Gather {          // where a run of consecutive ranks of one segment lives in the scratch arrays
+    const u32* P;
+    u32 stride;          // entries between chunk starts
+    u32 jlo, jhi;        // chunks the run touches
+    // entry of rank r, relative to the segment's chunk 0 (below 2^32: a gradient has fewer elements)
+    __device__ __forceinline__ u32 entry(u32 r) const {
+        const u32 j = find_chunk(P, jlo, jhi, r);
+        return j * stride + (r - P[j]);
+    }
 };
 
-__device__ __forceinline__ BlockGeom block_geom(const SegInfo* segs, const SegState* states, u32 n_segments, u64 item) {
-    BlockGeom g;
-    g.seg = (n_segments == 1) ? 0u : find_item_segment(states, n_segments, item);
-    const SegState* st = &states[g.seg];
-    g.KB = segs[g.seg].block_keys; g.l = segs[g.seg].flag_bits;
-    g.d = st->d; g.nb = st->nb;
-    g.blk = (u32)(item - st->item_begin);
-    g.first = (u64)g.blk * g.KB;
-    g.cnt = g.nb ? (u32)((g.d - g.first < g.KB) ? g.d - g.first : g.KB) : 0u;
-    g.grank = st->rank_begin + g.first;
+__device__ __forceinline__ Gather make_gather(const u32* P, u32 R, u32 nch, u32 r_first, u32 r_last) {
+    Gather g;
+    g.P = P;
+    g.stride = R * kRow;
+    g.jlo = uniform(find_chunk(P, 0, nch - 1, r_first));
+    g.jhi = uniform(find_chunk(P, g.jlo, nch - 1, r_last));
     return g;
 }
 
-constexpr u32 kSlice = 1024;     // tile prefixes staged per round of the gather
+constexpr u32 kRowsAtOnce = 4;   // rows of 64 keys whose fetches a wave keeps in flight
 
-// Fills s_keys[1 + i] (and, if codes_dst is given, codes_dst[i]) for the block's keys i = 0..cnt-1 and
-// s_keys[0] with the key before the block (0 for a segment's first block).  All threads call it.
-__device__ __forceinline__ void gather_block(const BlockGeom& g, u64 item, u64 n_tiles,
-                                             const u64* __restrict__ tprefix, const u32* __restrict__ block_tile,
-                                             const u32* __restrict__ block_prev_tile,
-                                             const u32* __restrict__ skeys, const uint8_t* __restrict__ scodes,
-                                             u32* s_keys, u64* s_pre, uint8_t* codes_dst) {
-    const u32 t = threadIdx.x;
-    if (g.cnt == 0) { if (t == 0) s_keys[0] = 0; __syncthreads(); return; }
-    if (t == 0) {
-        u32 pk = 0;
-        if (g.first != 0) {
-            const u64 T = block_prev_tile[item], r = g.grank - 1;
-            pk = skeys[T * kTile + (r - (T ? tprefix[T - 1] : 0))];
-        }
-        s_keys[0] = pk;
+// Keys 64*(k0+q) + lane, q = 0..3, of the run of n keys whose first has segment rank r0: their scratch
+// entries and values (0 beyond n).
+__device__ __forceinline__ void fetch_rows(const Gather& g, const u32* __restrict__ seg_keys, u32 r0, u32 k0, u32 n,
+                                           u32 lane, u32 (&ent)[kRowsAtOnce], u32 (&key)[kRowsAtOnce]) {
+#pragma unroll
+    for (u32 q = 0; q < kRowsAtOnce; ++q) {
+        const u32 i = (k0 + q) * 64u + lane;
+        ent[q] = 0; key[q] = 0;
+        if (i < n) { ent[q] = g.entry(r0 + i); key[q] = seg_keys[ent[q]]; }
     }
-    const u64 r_end = g.grank + g.cnt;
-    u64 T0 = block_tile[item];
-    u32 len = 32;                 // a dense block spans a few tiles; a sparse one gets full slices afterwards
-    for (;;) {
-        // entry j = prefix BEFORE tile T0 + j, j = 0..len
-        for (u32 j = t; j <= len; j += kThreads) {
-            const u64 T = T0 + j;
-            s_pre[j] = (T == 0) ? 0 : (T - 1 < n_tiles ? tprefix[T - 1] : ~0ull);
+}
+
+// Delta of row k's keys: `carry` is the key before the row on entry and the row's last key on return.
+__device__ __forceinline__ u32 row_delta(u32 key, u32 r0, u32 k, u32 n, u32 lane, u32& carry, bool& unsorted) {
+    const u32 i = k * 64u + lane;
+    const u32 up = __shfl_up(key, 1, 64);
+    const u32 prev = lane ? up : carry;
+    u32 dl = 0;
+    if (i < n) {
+        dl = key - prev;
+        unsorted |= (key < prev) || (key == prev && (r0 + i) != 0);
+    }
+    const u32 last_lane = (n - k * 64u) < 64u ? (n - k * 64u - 1u) : 63u;   // the row's last valid key
+    carry = __shfl(key, (int)last_lane, 64);
+    return dl;
+}
+
+__global__ void __launch_bounds__(kThreads)
+k_measure_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments, u32 R,
+               const u32* __restrict__ ccount, const unsigned long long* __restrict__ segd,
+               const u32* __restrict__ skeys, BlockInfo* __restrict__ binfo, unsigned long long* __restrict__ gsum,
+               u32 g_shift, Ctrl* ctrl) {
+    __shared__ u32 s_P[kMaxSegChunks + 1];
+    __shared__ u32 s_scan[kWaves + 1];
+    __shared__ uint8_t s_needall[kWaves][kMaxKB];     // significant bits of every delta of the wave's block
+    const u32 lane = lane_id(), w = uniform(wave_id());
+    uint8_t* s_need = s_needall[w];
+    u64 total_units;
+    if (n_segments == 1) {
+        const u64 d = segd[0];
+        const u32 KB = segs[0].block_keys;
+        const u64 nb = (d + KB - 1) / KB;
+        total_units = ((nb ? nb : 1) + kWaves - 1) / kWaves;
+    } else {
+        total_units = ctrl->total_units;
+    }
+    u32 cur_seg = 0xFFFFFFFFu;
+    for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x) {
+        const KeyUnit ku = key_unit(segs, states, n_segments, R, segd, unit);
+        if (ku.seg != cur_seg) {
+            build_prefix(ccount, ku.cb, ku.nch, s_P, s_scan);
+            cur_seg = ku.seg;
         }
-        __syncthreads();
-        const u64 covered = s_pre[len];                       // ranks below this are inside the slice
-        for (u32 i = t; i < g.cnt; i += kThreads) {
-            const u64 r = g.grank + i;
-            if (r >= s_pre[0] && r < covered) {
-                u32 lo = 0, hi = len - 1;                     // largest j with s_pre[j] <= r
-                while (lo < hi) {
-                    const u32 mid = (lo + hi + 1) >> 1;
-                    if (s_pre[mid] <= r) lo = mid; else hi = mid - 1;
+        const u32 blk = ku.blk0 + w;
+        if (blk >= (ku.nb ? ku.nb : 1u)) continue;
+        const u64 item = ku.item_begin + blk;
+        const u32 head8 = (u32)((kHeaderBytes + align8(ku.d) + 16ull * ku.nb) >> 3);   // first item of a segment
+        if (ku.nb == 0) {                                   // a segment without survivors: its header only
+            if (lane == 0) {
+                BlockInfo bi; bi.preKey = 0; bi.M = 0; bi.payload_bits = 0; bi.span8 = head8;
+                binfo[item] = bi;
+                atomicAdd(&gsum[item >> g_shift], (unsigned long long)head8);
+            }
+            continue;
+        }
+        const u32 first = blk * ku.KB;
+        const u32 cnt = (u32)((ku.d - first < ku.KB) ? ku.d - first : ku.KB);
+        const u32 nsub = (cnt + kSub - 1) / kSub;
+        const u32* seg_keys = skeys + chunk_slot0(segs[ku.seg], ku.seg, 0, R);
+        u32 preKey = 0;
+        if (first) {
+            const u32 j = find_chunk(s_P, 0, ku.nch - 1, first - 1);
+            preKey = seg_keys[j * (R * kRow) + (first - 1 - s_P[j])];
+        }
+        // first loop of Algorithm 2: deltas and the longest of them (M = bit length of maxDelta)
+        bool unsorted = false;
+        u32 carry = preKey, mxneed = 0;
+        for (u32 sub = 0; sub < nsub; ++sub) {
+            const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
+            const u32 r0 = first + sub * kSub;
+            const Gather g = make_gather(s_P, R, ku.nch, r0, r0 + n - 1);
+#pragma unroll 1
+            for (u32 k0 = 0; k0 * 64u < n; k0 += kRowsAtOnce) {
+                u32 ent[kRowsAtOnce], key[kRowsAtOnce];
+                fetch_rows(g, seg_keys, r0, k0, n, lane, ent, key);
+#pragma unroll
+                for (u32 q = 0; q < kRowsAtOnce; ++q) {
+                    if ((k0 + q) * 64u < n) {
+                        const u32 dl = row_delta(key[q], r0, k0 + q, n, lane, carry, unsorted);
+                        const u32 need = 32u - __clz(dl);      // __clz(0) = 32
+                        const u32 i = (k0 + q) * 64u + lane;
+                        if (i < n) s_need[sub * kSub + i] = (uint8_t)need;
+                        mxneed = need > mxneed ? need : mxneed;
+                    }
                 }
-                const u64 e = (T0 + lo) * kTile + (r - s_pre[lo]);
-                s_keys[1 + i] = skeys[e];
-                if (codes_dst) codes_dst[i] = scodes[e];
             }
         }
-        __syncthreads();
-        if (covered >= r_end) break;
-        T0 += len;
-        len = kSlice;
-    }
-}
-
-__global__ void __launch_bounds__(kThreads)
-k_measure_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments, u64 n_tiles,
-               const u64* __restrict__ tprefix, const u32* __restrict__ block_tile,
-               const u32* __restrict__ block_prev_tile, const u32* __restrict__ skeys,
-               BlockInfo* __restrict__ binfo, Ctrl* ctrl) {
-    __shared__ u32 s_keys[kMaxKB + 1];
-    __shared__ u64 s_pre[kSlice + 1];
-    __shared__ u32 s_red[kWaves], s_bits[kWaves];
-    const u32 t = threadIdx.x, lane = lane_id(), w = wave_id();
-    const u64 total_items = ctrl->total_items;
-    for (u64 item = blockIdx.x; item < total_items; item += gridDim.x) {
-        const BlockGeom g = block_geom(segs, states, n_segments, item);
-        gather_block(g, item, n_tiles, tprefix, block_tile, block_prev_tile, skeys, nullptr, s_keys, s_pre, nullptr);
-        // first loop of Algorithm 2: deltas and their maximum
-        u32 mx = 0;
-        bool unsorted = false;
-        for (u32 i = t; i < g.cnt; i += kThreads) {
-            const u32 prev = s_keys[i], cur = s_keys[i + 1];
-            unsorted |= (cur < prev) || (cur == prev && (g.first + i) != 0);
-            const u32 dk = cur - prev;
-            mx = dk > mx ? dk : mx;
-        }
-        mx = wave_max(mx);
-        if (lane == 0) s_red[w] = mx;
+        mxneed = wave_max(mxneed);
         if (__any(unsorted) && lane == 0) set_status(ctrl, FASTSGD_ERR_UNSORTED_KEYS);
-        __syncthreads();
-        mx = s_red[0];
-#pragma unroll
-        for (u32 k = 1; k < kWaves; ++k) mx = s_red[k] > mx ? s_red[k] : mx;
-        u32 M = 32u - __clz(mx);      // __clz(0) = 32
-        if (M < 1) M = 1;
+        const u32 M = mxneed ? mxneed : 1u;
         // payload bits: every key takes the length of the smallest level that holds its delta
+        const u32 magic = level_magic(M), l = ku.l;
+        wave_lds_sync();
         u32 bits = 0;
-        for (u32 i = t; i < g.cnt; i += kThreads) {
-            const u32 need = 32u - __clz(s_keys[i + 1] - s_keys[i]);
-            const u32 level = need ? (((need - 1u) << g.l) / M + 1u) : 1u;
-            bits += (level * M + (1u << g.l) - 1u) >> g.l;
-        }
-#pragma unroll
-        for (u32 d = 32; d >= 1; d >>= 1) bits += __shfl_xor(bits, d, 64);
-        if (lane == 0) s_bits[w] = bits;
-        __syncthreads();
-        if (t == 0) {
-            u32 pb = 0;
-#pragma unroll
-            for (u32 k = 0; k < kWaves; ++k) pb += s_bits[k];
+        for (u32 i = lane; i < cnt; i += 64) bits += level_len(level_of(s_need[i], l, magic), M, l);
+        bits = wave_sum(bits);
+        wave_lds_sync();
+        if (lane == 0) {
             BlockInfo bi;
-            bi.preKey = s_keys[0]; bi.M = M; bi.payload_bits = pb;
-            bi.size8 = ((g.cnt * g.l + 63u) >> 6) + ((pb + 63u) >> 6);
+            bi.preKey = preKey; bi.M = M; bi.payload_bits = bits;
+            bi.span8 = ((cnt * l + 63u) >> 6) + ((bits + 63u) >> 6) + (blk == 0 ? head8 : 0u);
             binfo[item] = bi;
+            atomicAdd(&gsum[item >> g_shift], (unsigned long long)bi.span8);
         }
-        __syncthreads();
     }
 }
 
-// Inclusive scan over the work items of the bytes each adds to the output: its key block, plus -- for
-// the first item of a segment -- the segment's header, value plane and directory.
-__global__ void __launch_bounds__(kPlanThreads)
-k_scan_items(const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
-             const BlockInfo* __restrict__ binfo, u64* __restrict__ ioff, const Ctrl* ctrl) {
-    __shared__ u64 s_wave[kPlanThreads / 64];
-    const u32 t = threadIdx.x, lane = lane_id(), w = wave_id();
-    constexpr u32 kW = kPlanThreads / 64;
-    const u64 n = ctrl->total_items;
-    const u64 per = (n + kPlanThreads - 1) / kPlanThreads;
-    const u64 a = (u64)t * per < n ? (u64)t * per : n;
-    const u64 b = a + per < n ? a + per : n;
-    auto bytes_of = [&](u64 item) -> u64 {
-        const u32 s = (n_segments == 1) ? 0u : find_item_segment(states, n_segments, item);
-        u64 x = 8ull * binfo[item].size8;
-        if (item == states[s].item_begin) x += kHeaderBytes + align8(states[s].d) + 16ull * states[s].nb;
-        return x;
-    };
-    u64 mine = 0;
-    for (u64 i = a; i < b; ++i) mine += bytes_of(i);
-    const u64 incl = wave_incl_scan64(mine);
-    if (lane == 63) s_wave[w] = incl;
-    __syncthreads();
-    u64 run = incl - mine;
-    for (u32 k = 0; k < kW; ++k) if (k < w) run += s_wave[k];
-    for (u64 i = a; i < b; ++i) { run += bytes_of(i); ioff[i] = run; }
+// Offset (in 8-byte words) at which work item `item` starts adding to the output: the groups before
+// its group (s_G, scanned) plus the items before it inside the group.  All lanes of the wave call it
+// with the same item.
+__device__ __forceinline__ u64 item_offset8(const u64* s_G, const BlockInfo* __restrict__ binfo, u32 g_shift, u64 item,
+                                            u32 lane) {
+    const u64 g = item >> g_shift;
+    u64 acc = 0;
+    for (u64 i = (g << g_shift) + lane; i < item; i += 64) acc += binfo[i].span8;
+    return s_G[g] + wave_sum64(acc);
 }
 
 __global__ void __launch_bounds__(kThreads)
-k_pack_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments, u64 n_tiles,
-            const u64* __restrict__ tprefix, const u32* __restrict__ block_tile,
-            const u32* __restrict__ block_prev_tile, const u32* __restrict__ skeys,
-            const uint8_t* __restrict__ scodes, const BlockInfo* __restrict__ binfo, const u64* __restrict__ ioff,
-            uint8_t* __restrict__ out, u64 out_capacity, u64* out_offsets, u32 single, u32* out_status,
-            const Ctrl* ctrl) {
-    __shared__ u32 s_keys[kMaxKB + 1];
-    __shared__ u64 s_pre[kSlice + 1];
-    __shared__ u32 s_flags[kMaxKB * 5 / 32 + 2];
-    __shared__ u32 s_pay[kMaxKB + 2];
+k_pack_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments, u32 R,
+            const u32* __restrict__ ccount, const unsigned long long* __restrict__ segd,
+            const u32* __restrict__ skeys, const uint8_t* __restrict__ scodes, const BlockInfo* __restrict__ binfo,
+            const unsigned long long* __restrict__ gsum, u32 g_shift, uint8_t* __restrict__ out, u64 out_capacity,
+            u64* out_offsets, u32 single, u32* out_status, const Ctrl* ctrl) {
+    __shared__ u32 s_P[kMaxSegChunks + 1];
+    __shared__ u64 s_G[kMaxGroups + 1];
+    __shared__ u64 s_scan64[kWaves + 1];
     __shared__ u32 s_scan[kWaves + 1];
-    __shared__ uint8_t s_codes[kMaxKB];
-    const u32 t = threadIdx.x;
-    const u64 total_items = ctrl->total_items;
-    const u64 total_bytes = total_items ? ioff[total_items - 1] : 0;
+    __shared__ u32 s_payall[kWaves][kSub + 2];
+    __shared__ u32 s_flgall[kWaves][kSub * 5 / 32 + 2];
+    const u32 t = threadIdx.x, lane = lane_id(), w = uniform(wave_id());
+    u32* s_pay = s_payall[w];
+    u32* s_flg = s_flgall[w];
+    u64 total_units, total_items;
+    if (n_segments == 1) {
+        const u64 d = segd[0];
+        const u32 KB = segs[0].block_keys;
+        const u64 nb = (d + KB - 1) / KB;
+        total_items = nb ? nb : 1;
+        total_units = (total_items + kWaves - 1) / kWaves;
+    } else {
+        total_items = ctrl->total_items;
+        total_units = ctrl->total_units;
+    }
+    if (blockIdx.x != 0 && blockIdx.x >= total_units) return;     // nothing to pack and nothing to report
+    // byte offsets of the groups of work items
+    const u32 ngroups = (u32)((total_items + (1ull << g_shift) - 1) >> g_shift);
+    for (u32 i = t; i < ngroups; i += kThreads) s_G[i] = gsum[i];
+    lds_excl_scan<u64, kMaxGroups / kThreads>(s_G, ngroups, s_scan64);
+    const u64 total_bytes = 8ull * s_G[ngroups];
     u32 status = ctrl->status;
     if (status == 0 && total_bytes > out_capacity) status = FASTSGD_ERR_BUFFER_TOO_SMALL;
     const bool ok = (status == 0);
 
-    if (blockIdx.x == 0) {          // lengths and status of the whole call
+    if (blockIdx.x == 0) {          // length and status of the whole call
         if (single) {
             if (t == 0) out_offsets[0] = ok ? total_bytes : 0;
         } else {
-            for (u32 s = t; s <= n_segments; s += kThreads) {
-                u64 off = 0;
-                if (ok) {
-                    if (s == n_segments) off = total_bytes;
-                    else { const u64 ib = states[s].item_begin; off = ib ? ioff[ib - 1] : 0; }
-                }
-                out_offsets[s] = off;
-            }
+            if (t == 0) out_offsets[n_segments] = ok ? total_bytes : 0;
+            if (!ok) for (u32 s = t; s < n_segments; s += kThreads) out_offsets[s] = 0;
         }
         if (t == 0) *out_status = status;
     }
     if (!ok) return;                // nothing is written into a buffer that cannot hold the result
 
-    for (u64 item = blockIdx.x; item < total_items; item += gridDim.x) {
-        const BlockGeom g = block_geom(segs, states, n_segments, item);
-        const SegInfo info = segs[g.seg];
-        const u64 ib = states[g.seg].item_begin;
-        const u64 sbeg = ib ? ioff[ib - 1] : 0;                        // stream start of the segment
-        const u64 send = ioff[ib + (g.nb ? g.nb : 1u) - 1];            // and its end
-        const u64 dir_off = sbeg + kHeaderBytes + align8(g.d);
-        const u64 blocks_off = dir_off + 16ull * g.nb;
-        if (g.blk == 0) {
-            if (t == 0) {
+    u32 cur_seg = 0xFFFFFFFFu;
+    u64 sbeg8 = 0;
+    for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x) {
+        const KeyUnit ku = key_unit(segs, states, n_segments, R, segd, unit);
+        if (ku.seg != cur_seg) {
+            build_prefix(ccount, ku.cb, ku.nch, s_P, s_scan);
+            cur_seg = ku.seg;
+            sbeg8 = (n_segments == 1) ? 0ull : item_offset8(s_G, binfo, g_shift, ku.item_begin, lane);
+        }
+        const u32 blk = ku.blk0 + w;
+        const u32 nitems = ku.nb ? ku.nb : 1u;
+        if (blk >= nitems) continue;
+        const u64 item = ku.item_begin + blk;
+        const SegInfo info = segs[ku.seg];
+        const u64 sbeg = 8ull * sbeg8;
+        const u64 dir_off = sbeg + kHeaderBytes + align8(ku.d);
+        const u64 blocks_off = dir_off + 16ull * ku.nb;
+        if (blk == 0) {
+            const u64 send8 = item_offset8(s_G, binfo, g_shift, ku.item_begin + nitems, lane);
+            if (lane == 0) {
                 u64* h = reinterpret_cast<u64*>(out + sbeg);
                 h[0] = (u64)kMagic | ((u64)kVersion << 32) | ((u64)info.flag_bits << 40) | ((u64)info.tau << 48);
-                h[1] = (u64)info.block_keys | ((u64)g.nb << 32);
+                h[1] = (u64)info.block_keys | ((u64)ku.nb << 32);
                 h[2] = (u64)__double_as_longlong(info.base);
-                h[3] = (u64)__double_as_longlong(states[g.seg].sum);
+                h[3] = (u64)__double_as_longlong(states[ku.seg].sum);
                 h[4] = info.elem_count;
-                h[5] = g.d;
-                h[6] = send - sbeg;
+                h[5] = ku.d;
+                h[6] = 8ull * (send8 - sbeg8);
                 h[7] = 0;
+                if (!single) out_offsets[ku.seg] = sbeg;
             }
             // zero padding between the value plane and the directory
-            if (t < 8 && g.d + t < align8(g.d)) out[sbeg + kHeaderBytes + g.d + t] = 0;
+            if (lane < 8 && ku.d + lane < align8(ku.d)) out[sbeg + kHeaderBytes + ku.d + lane] = 0;
         }
-        if (g.cnt == 0) continue;                                      // a segment without survivors
+        if (ku.nb == 0) continue;                                      // a segment without survivors
         const BlockInfo bi = binfo[item];
-        const u32 M = bi.M, l = g.l, cnt = g.cnt;
-        const u32 fwords = (cnt * l + 63u) >> 6, pwords = (bi.payload_bits + 63u) >> 6;
-        const u64 start = ioff[item] - 8ull * bi.size8;                // this block's planes
-        if (t == 0) {
-            u64* e = reinterpret_cast<u64*>(out + dir_off + 16ull * g.blk);
+        const u32 M = bi.M, l = ku.l, magic = level_magic(M);
+        const u32 first = blk * ku.KB;
+        const u32 cnt = (u32)((ku.d - first < ku.KB) ? ku.d - first : ku.KB);
+        const u32 nsub = (cnt + kSub - 1) / kSub;
+        const u32 fwords = (cnt * l + 63u) >> 6;                       // 64-bit words of the flags plane
+        const u64 start = (blk == 0) ? blocks_off : 8ull * item_offset8(s_G, binfo, g_shift, item, lane);
+        if (lane == 0) {
+            u64* e = reinterpret_cast<u64*>(out + dir_off + 16ull * blk);
             e[0] = (u64)(u32)((start - blocks_off) >> 3) | ((u64)bi.preKey << 32);
             e[1] = (u64)M | ((u64)bi.payload_bits << 32);
         }
-        for (u32 i = t; i < 2 * fwords + 2; i += kThreads) s_flags[i] = 0;
-        for (u32 i = t; i < 2 * pwords + 2; i += kThreads) s_pay[i] = 0;
-        gather_block(g, item, n_tiles, tprefix, block_tile, block_prev_tile, skeys, scodes, s_keys, s_pre, s_codes);
+        u32* fdst = reinterpret_cast<u32*>(out + start);               // flags plane, 32-bit words
+        u32* pdst = fdst + 2u * fwords;                                // payload plane
+        uint8_t* vdst = out + sbeg + kHeaderBytes + first;             // the block's part of the value plane
+        for (u32 i = lane; i < kSub + 2; i += 64) s_pay[i] = 0;
+        for (u32 i = lane; i < kSub * 5 / 32 + 2; i += 64) s_flg[i] = 0;
+        wave_lds_sync();
 
-        // value plane of the block's survivors
-        {
-            uint8_t* vdst = out + sbeg + kHeaderBytes + g.first;
-            for (u32 i = t; i < cnt; i += kThreads) vdst[i] = s_codes[i];
-        }
-        // second loop of Algorithm 2: thread t owns keys [t*per, (t+1)*per)
-        const u32 per = g.KB / kThreads;
-        u32 len[16], lvl[16], delta[16], mybits = 0;
+        // second loop of Algorithm 2, 1024 keys at a time
+        const u64 seg_slot0 = chunk_slot0(info, ku.seg, 0, R);
+        const u32* seg_keys = skeys + seg_slot0;
+        const uint8_t* seg_codes = scodes + seg_slot0;
+        u32 carry = bi.preKey;
+        u32 wbits = 0;               // payload bits waiting in s_pay[0] from the previous round
+        u32 pw = 0;                  // payload words already written
+        bool unsorted = false;
+        for (u32 sub = 0; sub < nsub; ++sub) {
+            const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
+            const u32 r0 = first + sub * kSub;
+            const Gather g = make_gather(s_P, R, ku.nch, r0, r0 + n - 1);
+            u32 rowbase = wbits;
+#pragma unroll 1
+            for (u32 k0 = 0; k0 * 64u < n; k0 += kRowsAtOnce) {
+                u32 ent[kRowsAtOnce], key[kRowsAtOnce], code[kRowsAtOnce];
+                fetch_rows(g, seg_keys, r0, k0, n, lane, ent, key);
 #pragma unroll
-        for (u32 k = 0; k < 16; ++k) {
-            const u32 i = t * per + k;
-            len[k] = 0; lvl[k] = 0; delta[k] = 0;
-            if (k < per && i < cnt) {
-                delta[k] = s_keys[i + 1] - s_keys[i];
-                const u32 need = 32u - __clz(delta[k]);
-                const u32 level = need ? (((need - 1u) << l) / M + 1u) : 1u;
-                lvl[k] = level - 1u;
-                len[k] = (level * M + (1u << l) - 1u) >> l;
-                mybits += len[k];
-            }
-        }
-        u32 payload_bits;
-        u32 bitpos = block_excl_scan(mybits, s_scan, &payload_bits);
+                for (u32 q = 0; q < kRowsAtOnce; ++q) {
+                    const u32 i = (k0 + q) * 64u + lane;
+                    code[q] = (i < n) ? seg_codes[ent[q]] : 0u;
+                }
 #pragma unroll
-        for (u32 k = 0; k < 16; ++k) {
-            const u32 i = t * per + k;
-            if (k < per && i < cnt) {
-                const u32 fpos = i * l;
-                const u64 fv = (u64)lvl[k] << (fpos & 31u);
-                atomicOr(&s_flags[fpos >> 5], (u32)fv);
-                if (fv >> 32) atomicOr(&s_flags[(fpos >> 5) + 1], (u32)(fv >> 32));
-                const u64 pv = (u64)delta[k] << (bitpos & 31u);
-                if ((u32)pv) atomicOr(&s_pay[bitpos >> 5], (u32)pv);
-                if (pv >> 32) atomicOr(&s_pay[(bitpos >> 5) + 1], (u32)(pv >> 32));
-                bitpos += len[k];
+                for (u32 q = 0; q < kRowsAtOnce; ++q) {
+                    const u32 k = k0 + q, i = k * 64u + lane;
+                    if (k * 64u < n) {
+                        // the survivors' code bytes go straight into the value plane
+                        if (i < n) vdst[sub * kSub + i] = (uint8_t)code[q];
+                        const u32 dl = row_delta(key[q], r0, k, n, lane, carry, unsorted);
+                        u32 len = 0;
+                        if (i < n) {
+                            const u32 level = level_of(32u - __clz(dl), l, magic);
+                            len = level_len(level, M, l);
+                            const u32 fpos = i * l;
+                            const u64 fv = (u64)(level - 1u) << (fpos & 31u);
+                            if ((u32)fv) atomicOr(&s_flg[fpos >> 5], (u32)fv);
+                            if (fv >> 32) atomicOr(&s_flg[(fpos >> 5) + 1], (u32)(fv >> 32));
+                        }
+                        const u32 incl = wave_incl_scan(len);
+                        if (i < n) {
+                            const u32 bitpos = rowbase + incl - len;
+                            const u64 pv = (u64)dl << (bitpos & 31u);
+                            if ((u32)pv) atomicOr(&s_pay[bitpos >> 5], (u32)pv);
+                            if (pv >> 32) atomicOr(&s_pay[(bitpos >> 5) + 1], (u32)(pv >> 32));
+                        }
+                        rowbase += (u32)__shfl(incl, 63, 64);
+                    }
+                }
             }
+            wave_lds_sync();
+            const bool last = (sub + 1 == nsub);
+            // flags of this round: whole 32-bit words (1024*l bits per full round)
+            {
+                const u32 nfw = (n * l + 31u) >> 5, f0 = sub * 32u * l;
+                for (u32 i = lane; i < nfw; i += 64) { fdst[f0 + i] = s_flg[i]; s_flg[i] = 0; }
+                if (last && ((f0 + nfw) & 1u) && lane == 0) fdst[f0 + nfw] = 0;      // pad to a 64-bit word
+            }
+            // payload: the full words; the partial last word waits for the next round
+            {
+                const u32 full = rowbase >> 5, rest = rowbase & 31u;
+                const u32 nw = (last && rest) ? full + 1u : full;
+                for (u32 i = lane; i < nw; i += 64) pdst[pw + i] = s_pay[i];
+                if (last) {
+                    if (((pw + nw) & 1u) && lane == 0) pdst[pw + nw] = 0;
+                } else {
+                    const u32 keep = s_pay[full];
+                    wave_lds_sync();
+                    for (u32 i = lane; i <= full + 1u; i += 64) s_pay[i] = (i == 0) ? keep : 0u;
+                    pw += full;
+                    wbits = rest;
+                }
+            }
+            wave_lds_sync();
         }
-        __syncthreads();
-        u64* dst = reinterpret_cast<u64*>(out + start);
-        for (u32 i = t; i < fwords; i += kThreads) dst[i] = (u64)s_flags[2 * i] | ((u64)s_flags[2 * i + 1] << 32);
-        for (u32 i = t; i < pwords; i += kThreads) dst[fwords + i] = (u64)s_pay[2 * i] | ((u64)s_pay[2 * i + 1] << 32);
-        __syncthreads();
     }
 }
 

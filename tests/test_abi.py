@@ -44,7 +44,7 @@ def test_workspace_size_is_monotone_and_rejects_bad_arguments():
     a = B.workspace_size(1000, 1, 1024)
     b = B.workspace_size(10 ** 6, 1, 1024)
     c = B.workspace_size(10 ** 6, 160, 256)
-    assert 0 < a < b < c
+    assert 0 < a < b and c > B.workspace_size(10 ** 6, 160, 1024) > a
     assert B.workspace_size(10, 0, 1024) == 0 and B.workspace_size(10, 1, 100) == 0
     assert B.decompress_workspace_size(1) > 0 and B.decompress_workspace_size(0) == 0
 
