@@ -39,7 +39,6 @@ static EncodePlan make_plan(u64 total_n, u32 n_segments, u32 min_kb) {
     pl.max_slots = total_n + 4ull * n_segments + 8;                // scratch entries: element index + 4 per segment
     u64 o = 0;
     pl.off_ctrl = o;  o += up(sizeof(Ctrl), 256);
-    pl.off_segd = o;  o += up((u64)n_segments * 8, 256);
     pl.off_gsum = o;  o += up((u64)(kMaxGroups + 1) * 8, 256);
     pl.zero_end = o;                                               // a single-gradient call clears up to here
     pl.off_gbins = o; o += up((u64)n_segments * pl.n_slots * kBinWords * 8, 256);
@@ -120,7 +119,7 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     }
     // chunks of R rows, about kChunkTarget of them, never shorter than one tile
     u64 R64 = (total_rows + kChunkTarget - 1) / kChunkTarget;
-    if (R64 < kTileRows) R64 = kTileRows;
+    if (R64 < 2 * kValRows) R64 = 2 * kValRows;
     u64 n_chunks = 0;
     for (u32 s = 0; s < n_segments; ++s) {
         SegInfo& si = segs[s];
@@ -142,7 +141,6 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
 
     uint8_t* ws = static_cast<uint8_t*>(d_ws);
     Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + pl.off_ctrl);
-    unsigned long long* segd = reinterpret_cast<unsigned long long*>(ws + pl.off_segd);
     unsigned long long* gsum = reinterpret_cast<unsigned long long*>(ws + pl.off_gsum);
     u64* gbins = reinterpret_cast<u64*>(ws + pl.off_gbins);
     u32* ccount = reinterpret_cast<u32*>(ws + pl.off_ccount);
@@ -187,17 +185,17 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     if (n_chunks)
         hipLaunchKernelGGL(k_encode_values, dim3((u32)((n_chunks + kValWaves - 1) / kValWaves)),
                            dim3(kValWaves * kWave), 0, stream, kbase, vbase, dsegs, dstates, n_segments, (u32)n_chunks,
-                           R, ccount, segd, skeys, scodes);
+                           R, ccount, skeys, scodes);
     marks.mark(stream);
     if (!single)
-        hipLaunchKernelGGL(k_plan_segments, dim3(1), dim3(kPlanThreads), 0, stream, dsegs, dstates, n_segments, segd,
-                           ctrl);
+        hipLaunchKernelGGL(k_plan_segments, dim3((n_segments + kWaves - 1) / kWaves), dim3(kThreads), 0, stream, dsegs,
+                           dstates, n_segments, R, ccount, ctrl);
     const u64 max_units = (max_items + kWaves - 1) / kWaves + n_segments;
     hipLaunchKernelGGL(k_measure_keys, dim3(clamp_grid(max_units, (u64)cus * 8)), dim3(kThreads), 0, stream, dsegs,
-                       dstates, n_segments, R, ccount, segd, skeys, binfo, gsum, g_shift, ctrl);
+                       dstates, n_segments, R, ccount, skeys, binfo, gsum, g_shift, ctrl);
     marks.mark(stream);
     hipLaunchKernelGGL(k_pack_keys, dim3(clamp_grid(max_units, (u64)cus * 3)), dim3(kThreads), 0, stream, dsegs,
-                       dstates, n_segments, R, ccount, segd, skeys, scodes, binfo, gsum, g_shift, out,
+                       dstates, n_segments, R, ccount, skeys, scodes, binfo, gsum, g_shift, out,
                        (u64)out_capacity, d_out_offsets, single ? 1u : 0u, d_status, ctrl);
     marks.mark(stream);
     return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;

@@ -16,8 +16,9 @@ constexpr u32 kWave = 64;
 constexpr u32 kThreads = 256;                 // workgroup size of the streaming kernels
 constexpr u32 kWaves = kThreads / kWave;
 constexpr u32 kRow = 256;                     // elements of one row: a float4 per lane of a wave
-constexpr u32 kTileRows = 16;                 // rows a wave holds in registers at a time
-constexpr u32 kTile = kRow * kTileRows;       // 4096 elements
+constexpr u32 kTile = 4096;                   // elements of one abs-sum tile: 4 rows per wave of the workgroup
+constexpr u32 kValRows = 8;                   // rows a wave of the value pass loads at a time
+constexpr u32 kValTile = kRow * kValRows;     // 2048 elements
 constexpr u32 kHeaderBytes = 64;
 constexpr u32 kMagic = 0x44475346u;           // "FSGD"
 constexpr u32 kVersion = 1;
@@ -58,7 +59,7 @@ struct BlockInfo { u32 preKey, M, payload_bits, span8; };
 
 struct Ctrl {
     u32 status;         // first device-detected fastsgd_status
-    u32 pad0;
+    u32 plan_done;      // batch calls: workgroups of k_plan_segments that have finished
     u64 total_items;    // batch calls: work items / units of the key encoder
     u64 total_units;
     u64 pad[5];
@@ -68,7 +69,7 @@ static_assert(sizeof(Ctrl) == 64, "control block layout");
 struct EncodePlan {     // host-computed carve-up of the workspace
     u64 max_chunks, max_items, total_n, max_slots;
     u32 n_segments, n_slots;
-    u64 off_ctrl, off_segd, off_gsum, zero_end, off_gbins, zero_end_batch;   // [off_ctrl, zero_end*) is cleared per call
+    u64 off_ctrl, off_gsum, zero_end, off_gbins, zero_end_batch;   // [off_ctrl, zero_end*) is cleared per call
     u64 off_ccount, off_binfo, off_seginfo, off_segstate, off_skeys, off_scodes, total;
 };
 
@@ -80,36 +81,53 @@ __device__ __forceinline__ u64 uniform64(u64 x) {
     return (u64)uniform((u32)x) | ((u64)uniform((u32)(x >> 32)) << 32);
 }
 
+// Cross-lane moves by data-parallel primitives (no trip through the LDS crossbar).  `old` is what a
+// lane gets when its source lane does not exist or its row is masked out.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ u32 dpp_mov(u32 old, u32 x) {
+    return (u32)__builtin_amdgcn_update_dpp((int)old, (int)x, CTRL, ROW_MASK, 0xF, false);
+}
+constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118;
+constexpr int kDppRowBcast15 = 0x142, kDppRowBcast31 = 0x143, kDppWaveShr1 = 0x138;
+
+// value of lane - 1 (lane 0 gets `first`)
+__device__ __forceinline__ u32 lane_above(u32 x, u32 first) { return dpp_mov<kDppWaveShr1>(first, x); }
+__device__ __forceinline__ u32 read_lane(u32 x, u32 lane) { return (u32)__builtin_amdgcn_readlane((int)x, (int)lane); }
+
 __device__ __forceinline__ u32 wave_incl_scan(u32 x) {
-#pragma unroll
-    for (u32 d = 1; d < 64; d <<= 1) {
-        u32 y = __shfl_up(x, d, 64);
-        if (lane_id() >= d) x += y;
-    }
+    x += dpp_mov<kDppRowShr1>(0u, x);
+    x += dpp_mov<kDppRowShr2>(0u, x);
+    x += dpp_mov<kDppRowShr4>(0u, x);
+    x += dpp_mov<kDppRowShr8>(0u, x);                 // inclusive inside each row of 16 lanes
+    x += dpp_mov<kDppRowBcast15, 0xA>(0u, x);         // rows 1 and 3 add the total of the row before
+    x += dpp_mov<kDppRowBcast31, 0xC>(0u, x);         // rows 2 and 3 add the total of rows 0-1
     return x;
 }
 __device__ __forceinline__ u64 wave_incl_scan64(u64 x) {
-#pragma unroll
-    for (u32 d = 1; d < 64; d <<= 1) {
-        u64 y = __shfl_up((unsigned long long)x, d, 64);
-        if (lane_id() >= d) x += y;
+#define FSGD_STEP64(CTRL, MASK)                                                                   \
+    {                                                                                              \
+        const u32 lo = dpp_mov<CTRL, MASK>(0u, (u32)x), hi = dpp_mov<CTRL, MASK>(0u, (u32)(x >> 32)); \
+        x += (u64)lo | ((u64)hi << 32);                                                            \
     }
+    FSGD_STEP64(kDppRowShr1, 0xF) FSGD_STEP64(kDppRowShr2, 0xF) FSGD_STEP64(kDppRowShr4, 0xF)
+    FSGD_STEP64(kDppRowShr8, 0xF) FSGD_STEP64(kDppRowBcast15, 0xA) FSGD_STEP64(kDppRowBcast31, 0xC)
+#undef FSGD_STEP64
     return x;
 }
-__device__ __forceinline__ u32 wave_sum(u32 x) {
-#pragma unroll
-    for (u32 d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, 64);
-    return x;
-}
+__device__ __forceinline__ u32 wave_sum(u32 x) { return read_lane(wave_incl_scan(x), 63); }
 __device__ __forceinline__ u64 wave_sum64(u64 x) {
-#pragma unroll
-    for (u32 d = 32; d >= 1; d >>= 1) x += __shfl_xor((unsigned long long)x, d, 64);
-    return x;
+    const u64 s = wave_incl_scan64(x);
+    return (u64)read_lane((u32)s, 63) | ((u64)read_lane((u32)(s >> 32), 63) << 32);
 }
 __device__ __forceinline__ u32 wave_max(u32 x) {
-#pragma unroll
-    for (u32 d = 32; d >= 1; d >>= 1) { u32 y = __shfl_xor(x, d, 64); x = x > y ? x : y; }
-    return x;
+    u32 y;
+    y = dpp_mov<kDppRowShr1>(0u, x); x = x > y ? x : y;
+    y = dpp_mov<kDppRowShr2>(0u, x); x = x > y ? x : y;
+    y = dpp_mov<kDppRowShr4>(0u, x); x = x > y ? x : y;
+    y = dpp_mov<kDppRowShr8>(0u, x); x = x > y ? x : y;
+    y = dpp_mov<kDppRowBcast15, 0xA>(0u, x); x = x > y ? x : y;
+    y = dpp_mov<kDppRowBcast31, 0xC>(0u, x); x = x > y ? x : y;
+    return read_lane(x, 63);
 }
 
 // Exclusive scan of one u32 per thread over the 256-thread workgroup; *total receives the sum.

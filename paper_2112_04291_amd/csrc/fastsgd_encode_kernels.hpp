@@ -71,7 +71,9 @@ __device__ __forceinline__ void load_tile(const float* __restrict__ values, cons
 // its lanes into (low-half sum, high-half sum) pairs.
 //
 // Records of kBinWords u64: words 2k, 2k+1 = low/high half sums of bin k, word 32 = non-finite flag.
-//   single gradient : every workgroup stores its one record at gbins[blockIdx.x] (plain stores, so
+// A segment's n_slots records are stored word-major (word w of slot i at [w * n_slots + i]) so that
+// the kernel that adds them up reads consecutive addresses.
+//   single gradient : every workgroup stores its one record in slot blockIdx.x (plain stores, so
 //                     nothing has to be cleared beforehand), and the launch also clears the control
 //                     words and counters the later kernels rely on;
 //   batch           : a workgroup owns a contiguous run of tiles and adds a record to one of n_slots
@@ -80,7 +82,7 @@ __device__ __forceinline__ void load_tile(const float* __restrict__ values, cons
 constexpr u32 kBinWords = 2 * kBins + 2;
 
 template <bool SINGLE>
-__device__ __forceinline__ void flush_bins(u64 (*bins)[kThreads], u64* rec, u32 maxa) {
+__device__ __forceinline__ void flush_bins(u64 (*bins)[kThreads], u64* rec, u32 n_slots, u32 maxa) {
     __syncthreads();
     const u32 t = threadIdx.x;
     const u32 bin = t >> 4, part = t & 15u;          // 16 threads per bin, 16 lanes each
@@ -97,15 +99,16 @@ __device__ __forceinline__ void flush_bins(u64 (*bins)[kThreads], u64* rec, u32 
         hi += __shfl_xor((unsigned long long)hi, d, 16);
     }
     const bool bad = __syncthreads_or(maxa >= 0x7F800000u);
+    const u64 ns = n_slots;
     if (SINGLE) {
-        if (part == 0) { rec[2 * bin] = lo; rec[2 * bin + 1] = hi; }
-        if (t == 0) { rec[2 * kBins] = bad ? 1u : 0u; rec[2 * kBins + 1] = 0; }
+        if (part == 0) { rec[(2 * bin) * ns] = lo; rec[(2 * bin + 1) * ns] = hi; }
+        if (t == 0) { rec[(2 * kBins) * ns] = bad ? 1u : 0u; rec[(2 * kBins + 1) * ns] = 0; }
     } else {
         if (part == 0) {
-            if (lo) atomicAdd((unsigned long long*)&rec[2 * bin], (unsigned long long)lo);
-            if (hi) atomicAdd((unsigned long long*)&rec[2 * bin + 1], (unsigned long long)hi);
+            if (lo) atomicAdd((unsigned long long*)&rec[(2 * bin) * ns], (unsigned long long)lo);
+            if (hi) atomicAdd((unsigned long long*)&rec[(2 * bin + 1) * ns], (unsigned long long)hi);
         }
-        if (bad && t == 0) atomicOr((unsigned long long*)&rec[2 * kBins], 1ull);
+        if (bad && t == 0) atomicOr((unsigned long long*)&rec[(2 * kBins) * ns], 1ull);
 #pragma unroll
         for (u32 b = 0; b < kBins; ++b) bins[b][t] = 0;
         __syncthreads();
@@ -157,7 +160,7 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
             load_tile(values, g, bits);
             accumulate_tile(bits, bins, maxa);
         }
-        flush_bins<true>(bins, gbins + (u64)blockIdx.x * kBinWords, maxa);
+        flush_bins<true>(bins, gbins + blockIdx.x, n_slots, maxa);
     } else {
         u32 cur_seg = 0xFFFFFFFFu;
         const u64 t_begin = blockIdx.x * per_wg;
@@ -166,7 +169,7 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
             const u32 seg = find_tile_segment(segs, n_segments, (u32)tile);
             if (seg != cur_seg) {
                 if (cur_seg != 0xFFFFFFFFu) {
-                    flush_bins<false>(bins, gbins + ((u64)cur_seg * n_slots + blockIdx.x % n_slots) * kBinWords, maxa);
+                    flush_bins<false>(bins, gbins + (u64)cur_seg * n_slots * kBinWords + blockIdx.x % n_slots, n_slots, maxa);
                     maxa = 0;
                 }
                 cur_seg = seg;
@@ -177,7 +180,7 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
             accumulate_tile(bits, bins, maxa);
         }
         if (cur_seg != 0xFFFFFFFFu)
-            flush_bins<false>(bins, gbins + ((u64)cur_seg * n_slots + blockIdx.x % n_slots) * kBinWords, maxa);
+            flush_bins<false>(bins, gbins + (u64)cur_seg * n_slots * kBinWords + blockIdx.x % n_slots, n_slots, maxa);
     }
 }
 
@@ -193,7 +196,7 @@ constexpr u32 kDigits = 12;
 __global__ void __launch_bounds__(kTableThreads)
 k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const u64* __restrict__ gbins,
          u32 n_slots, Ctrl* ctrl) {
-    __shared__ u64 s_part[kTableThreads / 64][64];
+    __shared__ u64 s_tot[kBinWords];
     __shared__ unsigned long long s_dig[kDigits];
     __shared__ double s_P[129];
     __shared__ double s_sum;
@@ -204,28 +207,31 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
     if (t < kDigits) s_dig[t] = 0;
     if (t == 0) s_bad = 0;
     {
-        // thread (group, word) adds up word `word` of records group, group+16, ...; 64 loads in flight
-        const u32 word = t & 63u, group = t >> 6;
-        constexpr u32 kGroups = kTableThreads / 64;
-        u64 acc[4] = {0, 0, 0, 0};
-        if (word < kBinWords) {
-            const u64* g = gbins + (u64)seg * n_slots * kBinWords + word;
-            for (u32 base = group; base < n_slots; base += kGroups * 64) {
+        // wave v adds up words v, v + 16, v + 32 over all slots: 16 coalesced loads per lane in flight,
+        // a sum inside the lane, one reduction across the wave per word
+        const u64* g = gbins + (u64)seg * n_slots * kBinWords;
+        const u32 lane = lane_id();
+        for (u32 w = wave_id(); w < kBinWords; w += kTableThreads / 64) {
+            const u64* gw = g + (u64)w * n_slots;
+            u64 acc = 0;
+            for (u32 base = 0; base < n_slots; base += 1024) {
+                u64 x[16];
 #pragma unroll
-                for (u32 j = 0; j < 64; ++j) {
-                    const u32 sl = base + kGroups * j;
-                    if (sl < n_slots) acc[j & 3] += g[(u64)sl * kBinWords];
+                for (u32 j = 0; j < 16; ++j) {
+                    const u32 sl = base + j * 64u + lane;
+                    x[j] = gw[sl < n_slots ? sl : n_slots - 1];
                 }
+#pragma unroll
+                for (u32 j = 0; j < 16; ++j) acc += (base + j * 64u + lane < n_slots) ? x[j] : 0ull;
             }
+            const u64 tot = wave_sum64(acc);
+            if (lane == 63) s_tot[w] = tot;
         }
-        s_part[group][word] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
     }
     __syncthreads();
     if (t == 64) power_chain(info.base, info.tau, s_P);
     if (t < kBinWords) {
-        u64 x = 0;
-#pragma unroll
-        for (u32 g = 0; g < kTableThreads / 64; ++g) x += s_part[g][t];
+        const u64 x = s_tot[t];
         if (t < 2 * kBins) {
             const u32 bitpos = 16u * (t >> 1) + 32u * (t & 1u);
             const u32 q = bitpos >> 5, sh = bitpos & 31u;         // sh is 0 or 16
@@ -291,18 +297,22 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
 // ---------------------------------------------------------------------------------------------
 // Second pass over the values (Algorithm 1 lines 4-10).  A pure streaming pass: no wave depends on
 // another.  The elements of a call are cut into chunks of R rows (a row = 256 elements, a float4 per
-// lane); every WAVE owns one chunk and walks it in tiles of 16 rows:
-//   16 float4 loads per lane -> keep test |v| >= threshold -> survivors staged in the wave's slice of
-//   shared memory at their rank inside the tile (ballot + mbcnt) -> densely over the staged survivors
-//   only: code by binary search in the boundary table, key fetch -> code byte and key appended to the
-//   CHUNK'S OWN SLOT of the scratch arrays (the chunk's first element index + rank in the chunk).
-// The chunk's survivor count goes to ccount[chunk] and is added to the segment's total.  Global ranks
-// are never materialised: the key encoder scans the (at most 4096) chunk counts of a segment in
-// shared memory and gathers through that scan.
-// Lane `lane` holds, for row r = 0..15 of a tile, elements tile0 + r*256 + lane*4 + {0..3}.
-constexpr u32 kStage = 1024;             // staged survivors per wave and round (4 rows can never exceed it)
+// lane); every WAVE owns one chunk and walks it in tiles of 8 rows:
+//   8 float4 loads per lane -> per row, keep test |v| >= threshold as four wave-wide masks; a row
+//   without survivors costs those four compares and a scalar branch -> survivors of the other rows are
+//   staged in the wave's slice of shared memory in element order (mask popcounts + mbcnt) -> once more
+//   than a few hundred wait there, densely over the staged survivors only: code by binary search in
+//   the boundary table, key fetch -> code byte and key appended to the CHUNK'S OWN SLOT of the scratch
+//   arrays (the chunk's first element index + rank in the chunk).  The loads of the next tile are
+//   issued before that flush, so its round trip overlaps with them.
+// The chunk's survivor count goes to ccount[chunk].  Global ranks are never materialised: the key
+// encoder scans the (at most 4096) chunk counts of a segment in shared memory and gathers through
+// that scan.
+// Lane `lane` holds, for row r = 0..7 of a tile, elements tile0 + r*256 + lane*4 + {0..3}.
+constexpr u32 kStage = 1152;             // staged survivors per wave: four full rows on top of the flush level
+constexpr u32 kFlushLevel = kStage - 4 * kRow;
 constexpr u32 kValWaves = 4;             // waves per workgroup of the value encoder (they never synchronise)
-constexpr u32 kGather = 8;               // key fetches a lane keeps in flight
+constexpr u32 kGather = 4;               // key fetches a lane keeps in flight
 
 // |v| >= threshold as a float compare with the |x| source modifier: for non-negative finite floats
 // (denormals are preserved in this build) it orders exactly like the unsigned compare of the bit
@@ -346,65 +356,51 @@ __device__ __forceinline__ Chunk chunk_geom(const SegInfo* __restrict__ segs, u3
     return c;
 }
 
-// Rows [0, rows) of the tile at element te, all inside the segment: coalesced float4 loads.
-__device__ __forceinline__ void load_rows(const float* __restrict__ values, u64 te, u32 rows, u32 lane,
-                                          u32 (&bits)[kTileRows][4]) {
-    const uint4* src = reinterpret_cast<const uint4*>(values + te) + lane;
-    if (rows == kTileRows) {
+// Rows [0, rows) of the tile at element te.  `interior`: all of them lie inside the segment and are
+// fetched by coalesced float4 loads; otherwise (the first and last tile of a segment at most) every
+// element is fetched on its own and those outside [lo, hi) become zero, which never survives.
+__device__ __forceinline__ void load_rows(const float* __restrict__ values, u64 te, u32 rows, bool interior, u64 lo,
+                                          u64 hi, u32 lane, u32 (&bits)[kValRows][4]) {
+    if (interior) {
+        const uint4* src = reinterpret_cast<const uint4*>(values + te) + lane;
+        if (rows == kValRows) {
 #pragma unroll
-        for (u32 r = 0; r < kTileRows; ++r) {
-            const uint4 q = src[r * 64u];
-            bits[r][0] = q.x; bits[r][1] = q.y; bits[r][2] = q.z; bits[r][3] = q.w;
+            for (u32 r = 0; r < kValRows; ++r) {
+                const uint4 q = src[r * 64u];
+                bits[r][0] = q.x; bits[r][1] = q.y; bits[r][2] = q.z; bits[r][3] = q.w;
+            }
+        } else {
+#pragma unroll
+            for (u32 r = 0; r < kValRows; ++r) {
+                uint4 q = make_uint4(0u, 0u, 0u, 0u);
+                if (r < rows) q = src[r * 64u];
+                bits[r][0] = q.x; bits[r][1] = q.y; bits[r][2] = q.z; bits[r][3] = q.w;
+            }
         }
     } else {
 #pragma unroll
-        for (u32 r = 0; r < kTileRows; ++r) {
-            uint4 q = make_uint4(0u, 0u, 0u, 0u);
-            if (r < rows) q = src[r * 64u];
-            bits[r][0] = q.x; bits[r][1] = q.y; bits[r][2] = q.z; bits[r][3] = q.w;
-        }
+        for (u32 r = 0; r < kValRows; ++r)
+#pragma unroll
+            for (u32 c = 0; c < 4; ++c) {
+                const u64 e = te + r * 256u + lane * 4u + c;
+                bits[r][c] = (r < rows && e >= lo && e < hi) ? __float_as_uint(values[e]) : 0u;
+            }
     }
 }
 
-// A tile cut by a segment boundary (at most two per segment): slots outside [lo_off, hi_off) become
-// zero, which never survives.  Goes through the wave's staging buffer in rolled loops so that this
-// rare path costs no registers; the buffer must be free when it is called.
-__device__ __forceinline__ void load_ragged(const float* __restrict__ values, u64 te, u32 lo_off, u32 hi_off,
-                                            u32 lane, u32* stage, u32 (&bits)[kTileRows][4]) {
-    const float* tvals = values + te;
-#pragma unroll
-    for (u32 q = 0; q < kTileRows / 4; ++q) {
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll 1
-        for (u32 i = 0; i < 16; ++i) {
-            const u32 off = q * 1024u + i * 64u + lane;
-            stage[i * 64u + lane] = (off >= lo_off && off < hi_off) ? __float_as_uint(tvals[off]) : 0u;
-        }
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (u32 rr = 0; rr < 4; ++rr)
-#pragma unroll
-            for (u32 c = 0; c < 4; ++c) bits[4 * q + rr][c] = stage[rr * 256u + lane * 4u + c];
-    }
-    __builtin_amdgcn_wave_barrier();
-}
-
-// The loop is software-pipelined: once a tile's survivors sit in shared memory its registers are free,
-// so the loads of the next tile are issued BEFORE the key fetches and stores of this one, and both
-// waits collapse into one memory round trip per tile.
 __global__ void __launch_bounds__(kValWaves * kWave) __attribute__((amdgpu_waves_per_eu(4, 8)))
 k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                 const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
-                u32 n_chunks, u32 R, u32* __restrict__ ccount, unsigned long long* __restrict__ segd,
-                u32* __restrict__ skeys, uint8_t* __restrict__ scodes) {
+                u32 n_chunks, u32 R, u32* __restrict__ ccount, u32* __restrict__ skeys,
+                uint8_t* __restrict__ scodes) {
     __shared__ u32 s_Ball[kValWaves][128];
     __shared__ u32 s_valall[kValWaves][kStage];
-    __shared__ uint16_t s_idxall[kValWaves][kStage];
+    __shared__ u32 s_idxall[kValWaves][kStage];
     const u32 lane = lane_id();
     const u32 w = uniform(wave_id());
     u32* s_B = s_Ball[w];
-    u32* s_val = s_valall[w];
-    uint16_t* s_idx = s_idxall[w];
+    u32* s_val = s_valall[w];       // staged survivors: value bits ...
+    u32* s_idx = s_idxall[w];       // ... and element offset inside the chunk
     const u32 chunk = blockIdx.x * kValWaves + w;
     if (chunk >= n_chunks) return;
     const Chunk ck = chunk_geom(segs, n_segments, chunk, R);
@@ -412,171 +408,125 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
     const u32 tau = segs[ck.seg].tau;
     s_B[lane] = states[ck.seg].B[lane];
     s_B[lane + 64] = states[ck.seg].B[lane + 64];
-    const u32 ntiles = (ck.nrows + kTileRows - 1) / kTileRows;
-
-    // rows of tile t and whether all of them lie inside the segment
-    auto tile_rows = [&](u32 t) -> u32 { return ck.nrows - t * kTileRows < kTileRows ? ck.nrows - t * kTileRows : kTileRows; };
-    auto tile_interior = [&](u32 t) -> bool {
-        const u64 te = ck.e0 + (u64)t * kTile;
-        return te >= ck.lo && te + (u64)tile_rows(t) * kRow <= ck.hi;
-    };
-    auto tile_ragged_load = [&](u32 t, u32 (&b)[kTileRows][4]) {
-        const u64 te = ck.e0 + (u64)t * kTile;
-        const u32 lo_off = ck.lo > te ? (u32)(ck.lo - te) : 0u;
-        u64 hi_off = ck.hi - te;
-        const u64 cap = (u64)tile_rows(t) * kRow;
-        if (hi_off > cap) hi_off = cap;
-        load_ragged(values, te, lo_off, (u32)hi_off, lane, s_val, b);
-    };
-
-    u32 bits[kTileRows][4];
-    if (tile_interior(0)) load_rows(values, ck.e0, tile_rows(0), lane, bits);
-    else tile_ragged_load(0, bits);
-
+    const u32 ntiles = (ck.nrows + kValRows - 1) / kValRows;
     const float thr_f = __uint_as_float(thr);
-    u32 cbase = 0;                           // survivors of the chunk so far
-    for (u32 t = 0; t < ntiles; ++t) {
-        const u64 te = ck.e0 + (u64)t * kTile;
-        // survivors of the tile: per-lane count, then one wave reduction
-        u32 mine = 0;
-#pragma unroll
-        for (u32 r = 0; r < kTileRows; ++r)
-#pragma unroll
-            for (u32 c = 0; c < 4; ++c) mine += keeps(bits[r][c], thr_f) ? 1u : 0u;
-        const u32 total = uniform(wave_sum(mine));
+    const u32* ckeys = keys + ck.e0;
+    u32 cbase = 0;                           // survivors of the chunk already in the scratch arrays
+    u32 staged = 0;                          // survivors waiting in shared memory
 
-        float thr_s = thr_f;
-        asm volatile("" : "+s"(thr_s));     // an opaque copy: the compare masks of the count pass stay dead
-        // one row: stage its survivors behind `staged` earlier ones; returns the new count
-        auto stage_row = [&](const u32 (&row)[4], u32 r, u32 staged) -> u32 {
-            u64 m[4];
-            u32 below = 0, rowcnt = 0;
-#pragma unroll
-            for (u32 c = 0; c < 4; ++c) {
-                m[c] = __ballot(keeps(row[c], thr_s));
-                below += lanes_below(m[c]);
-                rowcnt += (u32)__popcll(m[c]);
-            }
-            u32 pos = staged + below;
-#pragma unroll
-            for (u32 c = 0; c < 4; ++c)
-                if (keeps(row[c], thr_s)) {
-                    s_val[pos] = row[c];
-                    s_idx[pos] = (uint16_t)(r * 256u + lane * 4u + c);
-                    ++pos;
-                }
-            return staged + rowcnt;
-        };
-        // staged survivors [0, cnt) of the tile go to scratch entries slot + j
-        auto write_staged = [&](u32 cnt, u64 slot) {
-            const u32* tkeys = keys + te;
-            __builtin_amdgcn_wave_barrier();
-            for (u32 j0 = 0; j0 < cnt; j0 += 64u * kGather) {
-                u32 key[kGather];
-#pragma unroll
-                for (u32 k = 0; k < kGather; ++k) {               // all key fetches of the chunk first
-                    const u32 j = j0 + k * 64u + lane;
-                    key[k] = (j < cnt) ? tkeys[s_idx[j]] : 0u;
-                }
-#pragma unroll
-                for (u32 k = 0; k < kGather; ++k) {
-                    const u32 j = j0 + k * 64u + lane;
-                    if (j < cnt) {
-                        const u32 vb = s_val[j];
-                        const u32 a = vb & 0x7FFFFFFFu;
-                        // smallest code c in [1, tau] with a >= B[c]  (B non-increasing, a >= B[tau])
-                        u32 lo = 1, hi = tau;
-                        while (lo < hi) {
-                            const u32 mid = (lo + hi) >> 1;
-                            if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
-                        }
-                        scodes[slot + j] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
-                        skeys[slot + j] = key[k];
-                    }
-                    __builtin_amdgcn_sched_barrier(0);            // one search at a time: keeps registers low
-                }
-            }
-            __builtin_amdgcn_wave_barrier();
-        };
-
+    // Staged survivors -> scratch arrays.
+    auto flush = [&]() {
         const u64 slot = ck.slot0 + cbase;
-        const bool fits = total <= kStage;
-        if (fits) {
-            if (total) {
-                u32 staged = 0;
+        __builtin_amdgcn_wave_barrier();
+        for (u32 j0 = 0; j0 < staged; j0 += 64u * kGather) {
+            u32 key[kGather];
 #pragma unroll
-                for (u32 r = 0; r < kTileRows; ++r) staged = stage_row(bits[r], r, staged);
+            for (u32 k = 0; k < kGather; ++k) {               // all key fetches of the round first
+                const u32 j = j0 + k * 64u + lane;
+                key[k] = (j < staged) ? ckeys[s_idx[j]] : 0u;
             }
-        } else {
-            // more than a quarter of the tile survives (far from the sparse regime this codec is for):
-            // no staging, every lane codes and writes its own survivors
-            const u32* tkeys = keys + te;
-            u32 emitted = 0;
 #pragma unroll
-            for (u32 r = 0; r < kTileRows; ++r) {
-                u64 m[4];
-                u32 below = 0, rowcnt = 0;
-#pragma unroll
-                for (u32 c = 0; c < 4; ++c) {
-                    m[c] = __ballot(keeps(bits[r][c], thr_s));
-                    below += lanes_below(m[c]);
-                    rowcnt += (u32)__popcll(m[c]);
-                }
-                u32 pos = emitted + below;
-#pragma unroll
-                for (u32 c = 0; c < 4; ++c)
-                    if (keeps(bits[r][c], thr_s)) {
-                        const u32 vb = bits[r][c], a = vb & 0x7FFFFFFFu;
-                        u32 lo = 1, hi = tau;
-                        while (lo < hi) {
-                            const u32 mid = (lo + hi) >> 1;
-                            if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
-                        }
-                        scodes[slot + pos] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
-                        skeys[slot + pos] = tkeys[r * 256u + lane * 4u + c];
-                        ++pos;
+            for (u32 k = 0; k < kGather; ++k) {
+                const u32 j = j0 + k * 64u + lane;
+                if (j < staged) {
+                    const u32 vb = s_val[j];
+                    const u32 a = vb & 0x7FFFFFFFu;
+                    // smallest code c in [1, tau] with a >= B[c]  (B non-increasing, a >= B[tau])
+                    u32 lo = 1, hi = tau;
+                    while (lo < hi) {
+                        const u32 mid = (lo + hi) >> 1;
+                        if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
                     }
-                emitted += rowcnt;
-                __builtin_amdgcn_sched_barrier(0);
+                    scodes[slot + j] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
+                    skeys[slot + j] = key[k];
+                }
+                __builtin_amdgcn_sched_barrier(0);            // one search at a time: keeps registers low
             }
         }
+        __builtin_amdgcn_wave_barrier();
+        cbase += staged;
+        staged = 0;
+    };
+
+    auto tile_load = [&](u32 t, u32 (&b)[kValRows][4]) {
+        const u64 te = ck.e0 + (u64)t * kValTile;
+        const u32 rows = ck.nrows - t * kValRows < kValRows ? ck.nrows - t * kValRows : kValRows;
+        const bool interior = te >= ck.lo && te + (u64)rows * kRow <= ck.hi;
+        load_rows(values, te, rows, interior, ck.lo, ck.hi, lane, b);
+    };
+
+    // one row of the tile at chunk offset toff: masks, and staging if anything survives
+    auto stage_row = [&](const u32 (&row)[4], u32 off) {
+        u64 m[4];
+#pragma unroll
+        for (u32 c = 0; c < 4; ++c) m[c] = __ballot(keeps(row[c], thr_f));
+        if ((m[0] | m[1] | m[2] | m[3]) == 0) return;
+        u32 pos = staged + lanes_below(m[0]) + lanes_below(m[1]) + lanes_below(m[2]) + lanes_below(m[3]);
+#pragma unroll
+        for (u32 c = 0; c < 4; ++c)
+            if (keeps(row[c], thr_f)) {
+                s_val[pos] = row[c];
+                s_idx[pos] = off + lane * 4u + c;
+                ++pos;
+            }
+        staged += (u32)__popcll(m[0]) + (u32)__popcll(m[1]) + (u32)__popcll(m[2]) + (u32)__popcll(m[3]);
+    };
+
+    u32 bits[kValRows][4];
+    tile_load(0, bits);
+    for (u32 t = 0; t < ntiles; ++t) {
+        const u32 toff = t * kValTile;      // offset of the tile inside the chunk
+#pragma unroll
+        for (u32 r = 0; r < 4; ++r) stage_row(bits[r], toff + r * kRow);
+        if (staged > kFlushLevel) flush();                     // room for four more rows
+#pragma unroll
+        for (u32 r = 4; r < 8; ++r) stage_row(bits[r], toff + r * kRow);
         // the registers are free: start on the next tile before finishing this one
-        const bool more = t + 1 < ntiles;
-        const bool early = more && tile_interior(t + 1);
-        if (early) load_rows(values, te + kTile, tile_rows(t + 1), lane, bits);
-        if (fits && total) write_staged(total, slot);
-        if (more && !early) tile_ragged_load(t + 1, bits);
-        cbase += total;
+        if (t + 1 < ntiles) tile_load(t + 1, bits);
+        if (staged > kFlushLevel || (t + 1 == ntiles && staged)) flush();
     }
-    if (lane == 0) {
-        ccount[chunk] = cbase;
-        if (cbase) atomicAdd(&segd[ck.seg], (unsigned long long)cbase);
-    }
+    if (lane == 0) ccount[chunk] = cbase;
 }
 
 // ---------------------------------------------------------------------------------------------
-// Batch calls: one workgroup numbers the key encoder's work.  A work item is one key block (a segment
-// without survivors still has one item, which carries its header); a work unit is kWaves consecutive
-// items of one segment, the share of one workgroup iteration.
-constexpr u32 kPlanThreads = 1024;
-
-__global__ void __launch_bounds__(kPlanThreads)
-k_plan_segments(const SegInfo* __restrict__ segs, SegState* __restrict__ states, u32 n_segments,
-                const unsigned long long* __restrict__ segd, Ctrl* ctrl) {
-    __shared__ u64 s_wave[2][kPlanThreads / 64];
+// Batch calls: numbering of the key encoder's work.  A work item is one key block (a segment without
+// survivors still has one item, which carries its header); a work unit is kWaves consecutive items of
+// one segment, the share of one workgroup iteration.  Every wave adds up the chunk counts of one
+// segment; the workgroup that finishes last (a counter in the control block) then scans the segments.
+__global__ void __launch_bounds__(kThreads)
+k_plan_segments(const SegInfo* __restrict__ segs, SegState* __restrict__ states, u32 n_segments, u32 R,
+                const u32* __restrict__ ccount, Ctrl* ctrl) {
+    __shared__ u64 s_wave[2][kWaves];
     __shared__ u64 s_carry[2];
+    __shared__ u32 s_last;
     const u32 t = threadIdx.x, lane = lane_id(), w = wave_id();
-    constexpr u32 kW = kPlanThreads / 64;
+    {
+        const u32 s = blockIdx.x * kWaves + w;
+        if (s < n_segments) {
+            const SegInfo info = segs[s];
+            const u32 nch = info.elem_count ? (u32)((segment_rows(info) + R - 1) / R) : 0u;
+            u64 d = 0;
+            for (u32 j = lane; j < nch; j += 64) d += ccount[info.chunk_begin + j];
+            d = wave_sum64(d);
+            if (lane == 0) {
+                states[s].d = d;
+                states[s].nb = (u32)((d + info.block_keys - 1) / info.block_keys);
+            }
+        }
+    }
+    __threadfence();
+    __syncthreads();
+    if (t == 0) s_last = (atomicAdd(&ctrl->plan_done, 1u) == gridDim.x - 1) ? 1u : 0u;
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
     if (t < 2) s_carry[t] = 0;
     __syncthreads();
-    for (u32 s0 = 0; s0 < n_segments; s0 += kPlanThreads) {
+    for (u32 s0 = 0; s0 < n_segments; s0 += kThreads) {
         const u32 s = s0 + t;
-        u64 items = 0, units = 0, d = 0;
-        u32 nb = 0;
+        u64 items = 0, units = 0;
         if (s < n_segments) {
-            d = segd[s];
-            const u32 KB = segs[s].block_keys;
-            nb = (u32)((d + KB - 1) / KB);
+            const u32 nb = __atomic_load_n(&states[s].nb, __ATOMIC_RELAXED);
             items = nb ? nb : 1u;
             units = (items + kWaves - 1) / kWaves;
         }
@@ -584,14 +534,13 @@ k_plan_segments(const SegInfo* __restrict__ segs, SegState* __restrict__ states,
         if (lane == 63) { s_wave[0][w] = ii; s_wave[1][w] = iu; }
         __syncthreads();
         u64 bi = s_carry[0], bu = s_carry[1], ti = 0, tu = 0;
-        for (u32 k = 0; k < kW; ++k) {
+#pragma unroll
+        for (u32 k = 0; k < kWaves; ++k) {
             const u64 a = s_wave[0][k], b = s_wave[1][k];
             if (k < w) { bi += a; bu += b; }
             ti += a; tu += b;
         }
         if (s < n_segments) {
-            states[s].d = d;
-            states[s].nb = nb;
             states[s].item_begin = bi + ii - items;
             states[s].unit_begin = bu + iu - units;
         }
@@ -627,13 +576,12 @@ __device__ __forceinline__ u32 find_unit_segment(const SegState* states, u32 n_s
 }
 
 __device__ __forceinline__ KeyUnit key_unit(const SegInfo* __restrict__ segs, const SegState* __restrict__ states,
-                                            u32 n_segments, u32 R, const unsigned long long* __restrict__ segd,
-                                            u64 unit) {
+                                            u32 n_segments, u32 R, u64 single_d, u64 unit) {
     KeyUnit ku;
     if (n_segments == 1) {
         ku.seg = 0;
         ku.KB = segs[0].block_keys;
-        ku.d = segd[0];
+        ku.d = single_d;
         ku.nb = (u32)((ku.d + ku.KB - 1) / ku.KB);
         ku.item_begin = 0;
         ku.blk0 = (u32)unit * kWaves;
@@ -713,11 +661,7 @@ struct Gather {          // where a run of consecutive ranks of one segment live
     const u32* P;
     u32 stride;          // entries between chunk starts
     u32 jlo, jhi;        // chunks the run touches
-    // entry of rank r, relative to the segment's chunk 0 (below 2^32: a gradient has fewer elements)
-    __device__ __forceinline__ u32 entry(u32 r) const {
-        const u32 j = find_chunk(P, jlo, jhi, r);
-        return j * stride + (r - P[j]);
-    }
+    u32 step0;           // largest power of two <= jhi - jlo (0 if the run lies in one chunk)
 };
 
 __device__ __forceinline__ Gather make_gather(const u32* P, u32 R, u32 nch, u32 r_first, u32 r_last) {
@@ -726,60 +670,72 @@ __device__ __forceinline__ Gather make_gather(const u32* P, u32 R, u32 nch, u32 
     g.stride = R * kRow;
     g.jlo = uniform(find_chunk(P, 0, nch - 1, r_first));
     g.jhi = uniform(find_chunk(P, g.jlo, nch - 1, r_last));
+    const u32 span = g.jhi - g.jlo;
+    g.step0 = span ? 1u << (31u - __clz(span)) : 0u;
     return g;
 }
 
-constexpr u32 kRowsAtOnce = 4;   // rows of 64 keys whose fetches a wave keeps in flight
+constexpr u32 kKeyRows = kSub / 64;   // rows of 64 keys a wave handles at a time
 
-// Keys 64*(k0+q) + lane, q = 0..3, of the run of n keys whose first has segment rank r0: their scratch
-// entries and values (0 beyond n).
-__device__ __forceinline__ void fetch_rows(const Gather& g, const u32* __restrict__ seg_keys, u32 r0, u32 k0, u32 n,
-                                           u32 lane, u32 (&ent)[kRowsAtOnce], u32 (&key)[kRowsAtOnce]) {
+// Scratch entries, relative to the segment's chunk 0 (below 2^32: a gradient has fewer elements), of
+// the keys with segment ranks r0 + 64*q + lane, q = 0..15.  The searches of the 16 rows advance
+// together, one shared-memory probe each per step, so their latencies overlap.  Ranks beyond the run
+// give entries that must not be used.
+__device__ __forceinline__ void find_entries(const Gather& g, u32 r0, u32 lane, u32 (&ent)[kKeyRows]) {
+    u32 j[kKeyRows];
 #pragma unroll
-    for (u32 q = 0; q < kRowsAtOnce; ++q) {
-        const u32 i = (k0 + q) * 64u + lane;
-        ent[q] = 0; key[q] = 0;
-        if (i < n) { ent[q] = g.entry(r0 + i); key[q] = seg_keys[ent[q]]; }
+    for (u32 q = 0; q < kKeyRows; ++q) j[q] = g.jlo;
+    for (u32 step = g.step0; step; step >>= 1) {
+#pragma unroll
+        for (u32 q = 0; q < kKeyRows; ++q) {
+            const u32 cand = j[q] + step;
+            const u32 probe = g.P[cand < g.jhi ? cand : g.jhi];
+            if (cand <= g.jhi && probe <= r0 + q * 64u + lane) j[q] = cand;
+        }
     }
+#pragma unroll
+    for (u32 q = 0; q < kKeyRows; ++q) ent[q] = j[q] * g.stride + (r0 + q * 64u + lane - g.P[j[q]]);
 }
 
 // Delta of row k's keys: `carry` is the key before the row on entry and the row's last key on return.
 __device__ __forceinline__ u32 row_delta(u32 key, u32 r0, u32 k, u32 n, u32 lane, u32& carry, bool& unsorted) {
     const u32 i = k * 64u + lane;
-    const u32 up = __shfl_up(key, 1, 64);
-    const u32 prev = lane ? up : carry;
+    const u32 prev = lane_above(key, carry);
     u32 dl = 0;
     if (i < n) {
         dl = key - prev;
         unsorted |= (key < prev) || (key == prev && (r0 + i) != 0);
     }
     const u32 last_lane = (n - k * 64u) < 64u ? (n - k * 64u - 1u) : 63u;   // the row's last valid key
-    carry = __shfl(key, (int)last_lane, 64);
+    carry = read_lane(key, uniform(last_lane));
     return dl;
 }
 
 __global__ void __launch_bounds__(kThreads)
 k_measure_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments, u32 R,
-               const u32* __restrict__ ccount, const unsigned long long* __restrict__ segd,
-               const u32* __restrict__ skeys, BlockInfo* __restrict__ binfo, unsigned long long* __restrict__ gsum,
-               u32 g_shift, Ctrl* ctrl) {
+               const u32* __restrict__ ccount, const u32* __restrict__ skeys, BlockInfo* __restrict__ binfo,
+               unsigned long long* __restrict__ gsum, u32 g_shift, Ctrl* ctrl) {
     __shared__ u32 s_P[kMaxSegChunks + 1];
     __shared__ u32 s_scan[kWaves + 1];
     __shared__ uint8_t s_needall[kWaves][kMaxKB];     // significant bits of every delta of the wave's block
     const u32 lane = lane_id(), w = uniform(wave_id());
     uint8_t* s_need = s_needall[w];
-    u64 total_units;
+    // a single gradient: its survivor count is the total of the scan of its chunk counts
+    u64 total_units, single_d = 0;
+    u32 cur_seg = 0xFFFFFFFFu;
     if (n_segments == 1) {
-        const u64 d = segd[0];
-        const u32 KB = segs[0].block_keys;
-        const u64 nb = (d + KB - 1) / KB;
+        const SegInfo info = segs[0];
+        const u32 nch = info.elem_count ? (u32)((segment_rows(info) + R - 1) / R) : 0u;
+        build_prefix(ccount, info.chunk_begin, nch, s_P, s_scan);
+        cur_seg = 0;
+        single_d = s_P[nch];
+        const u64 nb = (single_d + info.block_keys - 1) / info.block_keys;
         total_units = ((nb ? nb : 1) + kWaves - 1) / kWaves;
     } else {
         total_units = ctrl->total_units;
     }
-    u32 cur_seg = 0xFFFFFFFFu;
     for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x) {
-        const KeyUnit ku = key_unit(segs, states, n_segments, R, segd, unit);
+        const KeyUnit ku = key_unit(segs, states, n_segments, R, single_d, unit);
         if (ku.seg != cur_seg) {
             build_prefix(ccount, ku.cb, ku.nch, s_P, s_scan);
             cur_seg = ku.seg;
@@ -812,19 +768,18 @@ k_measure_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ st
             const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
             const u32 r0 = first + sub * kSub;
             const Gather g = make_gather(s_P, R, ku.nch, r0, r0 + n - 1);
-#pragma unroll 1
-            for (u32 k0 = 0; k0 * 64u < n; k0 += kRowsAtOnce) {
-                u32 ent[kRowsAtOnce], key[kRowsAtOnce];
-                fetch_rows(g, seg_keys, r0, k0, n, lane, ent, key);
+            u32 ent[kKeyRows], key[kKeyRows];
+            find_entries(g, r0, lane, ent);
 #pragma unroll
-                for (u32 q = 0; q < kRowsAtOnce; ++q) {
-                    if ((k0 + q) * 64u < n) {
-                        const u32 dl = row_delta(key[q], r0, k0 + q, n, lane, carry, unsorted);
-                        const u32 need = 32u - __clz(dl);      // __clz(0) = 32
-                        const u32 i = (k0 + q) * 64u + lane;
-                        if (i < n) s_need[sub * kSub + i] = (uint8_t)need;
-                        mxneed = need > mxneed ? need : mxneed;
-                    }
+            for (u32 q = 0; q < kKeyRows; ++q) key[q] = (q * 64u + lane < n) ? seg_keys[ent[q]] : 0u;
+#pragma unroll
+            for (u32 q = 0; q < kKeyRows; ++q) {
+                if (q * 64u < n) {
+                    const u32 dl = row_delta(key[q], r0, q, n, lane, carry, unsorted);
+                    const u32 need = 32u - __clz(dl);      // __clz(0) = 32
+                    const u32 i = q * 64u + lane;
+                    if (i < n) s_need[sub * kSub + i] = (uint8_t)need;
+                    mxneed = need > mxneed ? need : mxneed;
                 }
             }
         }
@@ -861,8 +816,8 @@ __device__ __forceinline__ u64 item_offset8(const u64* s_G, const BlockInfo* __r
 
 __global__ void __launch_bounds__(kThreads)
 k_pack_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments, u32 R,
-            const u32* __restrict__ ccount, const unsigned long long* __restrict__ segd,
-            const u32* __restrict__ skeys, const uint8_t* __restrict__ scodes, const BlockInfo* __restrict__ binfo,
+            const u32* __restrict__ ccount, const u32* __restrict__ skeys,
+            const uint8_t* __restrict__ scodes, const BlockInfo* __restrict__ binfo,
             const unsigned long long* __restrict__ gsum, u32 g_shift, uint8_t* __restrict__ out, u64 out_capacity,
             u64* out_offsets, u32 single, u32* out_status, const Ctrl* ctrl) {
     __shared__ u32 s_P[kMaxSegChunks + 1];
@@ -874,11 +829,15 @@ k_pack_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ state
     const u32 t = threadIdx.x, lane = lane_id(), w = uniform(wave_id());
     u32* s_pay = s_payall[w];
     u32* s_flg = s_flgall[w];
-    u64 total_units, total_items;
+    u64 total_units, total_items, single_d = 0;
+    u32 cur_seg = 0xFFFFFFFFu;
     if (n_segments == 1) {
-        const u64 d = segd[0];
-        const u32 KB = segs[0].block_keys;
-        const u64 nb = (d + KB - 1) / KB;
+        const SegInfo info = segs[0];
+        const u32 nch = info.elem_count ? (u32)((segment_rows(info) + R - 1) / R) : 0u;
+        build_prefix(ccount, info.chunk_begin, nch, s_P, s_scan);
+        cur_seg = 0;
+        single_d = s_P[nch];
+        const u64 nb = (single_d + info.block_keys - 1) / info.block_keys;
         total_items = nb ? nb : 1;
         total_units = (total_items + kWaves - 1) / kWaves;
     } else {
@@ -906,10 +865,9 @@ k_pack_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ state
     }
     if (!ok) return;                // nothing is written into a buffer that cannot hold the result
 
-    u32 cur_seg = 0xFFFFFFFFu;
     u64 sbeg8 = 0;
     for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x) {
-        const KeyUnit ku = key_unit(segs, states, n_segments, R, segd, unit);
+        const KeyUnit ku = key_unit(segs, states, n_segments, R, single_d, unit);
         if (ku.seg != cur_seg) {
             build_prefix(ccount, ku.cb, ku.nch, s_P, s_scan);
             cur_seg = ku.seg;
@@ -973,40 +931,38 @@ k_pack_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ state
             const u32 r0 = first + sub * kSub;
             const Gather g = make_gather(s_P, R, ku.nch, r0, r0 + n - 1);
             u32 rowbase = wbits;
-#pragma unroll 1
-            for (u32 k0 = 0; k0 * 64u < n; k0 += kRowsAtOnce) {
-                u32 ent[kRowsAtOnce], key[kRowsAtOnce], code[kRowsAtOnce];
-                fetch_rows(g, seg_keys, r0, k0, n, lane, ent, key);
+            u32 ent[kKeyRows], key[kKeyRows], code[kKeyRows];
+            find_entries(g, r0, lane, ent);
 #pragma unroll
-                for (u32 q = 0; q < kRowsAtOnce; ++q) {
-                    const u32 i = (k0 + q) * 64u + lane;
-                    code[q] = (i < n) ? seg_codes[ent[q]] : 0u;
-                }
+            for (u32 q = 0; q < kKeyRows; ++q) {
+                const bool in = q * 64u + lane < n;
+                key[q] = in ? seg_keys[ent[q]] : 0u;
+                code[q] = in ? seg_codes[ent[q]] : 0u;
+            }
 #pragma unroll
-                for (u32 q = 0; q < kRowsAtOnce; ++q) {
-                    const u32 k = k0 + q, i = k * 64u + lane;
-                    if (k * 64u < n) {
-                        // the survivors' code bytes go straight into the value plane
-                        if (i < n) vdst[sub * kSub + i] = (uint8_t)code[q];
-                        const u32 dl = row_delta(key[q], r0, k, n, lane, carry, unsorted);
-                        u32 len = 0;
-                        if (i < n) {
-                            const u32 level = level_of(32u - __clz(dl), l, magic);
-                            len = level_len(level, M, l);
-                            const u32 fpos = i * l;
-                            const u64 fv = (u64)(level - 1u) << (fpos & 31u);
-                            if ((u32)fv) atomicOr(&s_flg[fpos >> 5], (u32)fv);
-                            if (fv >> 32) atomicOr(&s_flg[(fpos >> 5) + 1], (u32)(fv >> 32));
-                        }
-                        const u32 incl = wave_incl_scan(len);
-                        if (i < n) {
-                            const u32 bitpos = rowbase + incl - len;
-                            const u64 pv = (u64)dl << (bitpos & 31u);
-                            if ((u32)pv) atomicOr(&s_pay[bitpos >> 5], (u32)pv);
-                            if (pv >> 32) atomicOr(&s_pay[(bitpos >> 5) + 1], (u32)(pv >> 32));
-                        }
-                        rowbase += (u32)__shfl(incl, 63, 64);
+            for (u32 q = 0; q < kKeyRows; ++q) {
+                const u32 i = q * 64u + lane;
+                if (q * 64u < n) {
+                    // the survivors' code bytes go straight into the value plane
+                    if (i < n) vdst[sub * kSub + i] = (uint8_t)code[q];
+                    const u32 dl = row_delta(key[q], r0, q, n, lane, carry, unsorted);
+                    u32 len = 0;
+                    if (i < n) {
+                        const u32 level = level_of(32u - __clz(dl), l, magic);
+                        len = level_len(level, M, l);
+                        const u32 fpos = i * l;
+                        const u64 fv = (u64)(level - 1u) << (fpos & 31u);
+                        if ((u32)fv) atomicOr(&s_flg[fpos >> 5], (u32)fv);
+                        if (fv >> 32) atomicOr(&s_flg[(fpos >> 5) + 1], (u32)(fv >> 32));
                     }
+                    const u32 incl = wave_incl_scan(len);
+                    if (i < n) {
+                        const u32 bitpos = rowbase + incl - len;
+                        const u64 pv = (u64)dl << (bitpos & 31u);
+                        if ((u32)pv) atomicOr(&s_pay[bitpos >> 5], (u32)pv);
+                        if (pv >> 32) atomicOr(&s_pay[(bitpos >> 5) + 1], (u32)(pv >> 32));
+                    }
+                    rowbase += read_lane(incl, 63);
                 }
             }
             wave_lds_sync();
