@@ -191,10 +191,10 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
         hipLaunchKernelGGL(k_plan_segments, dim3((n_segments + kWaves - 1) / kWaves), dim3(kThreads), 0, stream, dsegs,
                            dstates, n_segments, R, ccount, ctrl);
     const u64 max_units = (max_items + kWaves - 1) / kWaves + n_segments;
-    hipLaunchKernelGGL(k_measure_keys, dim3(clamp_grid(max_units, (u64)cus * 8)), dim3(kThreads), 0, stream, dsegs,
+    hipLaunchKernelGGL(k_measure_keys, dim3(clamp_grid(max_units, (u64)cus * 3)), dim3(kThreads), 0, stream, segs[0], dsegs,
                        dstates, n_segments, R, ccount, skeys, binfo, gsum, g_shift, ctrl);
     marks.mark(stream);
-    hipLaunchKernelGGL(k_pack_keys, dim3(clamp_grid(max_units, (u64)cus * 3)), dim3(kThreads), 0, stream, dsegs,
+    hipLaunchKernelGGL(k_pack_keys, dim3(clamp_grid(max_units, (u64)cus * 3)), dim3(kThreads), 0, stream, segs[0], dsegs,
                        dstates, n_segments, R, ccount, skeys, scodes, binfo, gsum, g_shift, out,
                        (u64)out_capacity, d_out_offsets, single ? 1u : 0u, d_status, ctrl);
     marks.mark(stream);

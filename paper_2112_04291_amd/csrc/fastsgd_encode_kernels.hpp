@@ -575,27 +575,35 @@ __device__ __forceinline__ u32 find_unit_segment(const SegState* states, u32 n_s
     return lo;
 }
 
-__device__ __forceinline__ KeyUnit key_unit(const SegInfo* __restrict__ segs, const SegState* __restrict__ states,
-                                            u32 n_segments, u32 R, u64 single_d, u64 unit) {
+__device__ __forceinline__ u32 segment_chunks(const SegInfo& s, u32 R) {
+    return s.elem_count ? (u32)((segment_rows(s) + R - 1) / R) : 0u;
+}
+
+// `seg0` is the segment record of a single-gradient call (a kernel argument, so no load is needed).
+__device__ __forceinline__ KeyUnit key_unit(const SegInfo& seg0, const SegInfo* __restrict__ segs,
+                                            const SegState* __restrict__ states, u32 n_segments, u32 R,
+                                            u64 single_d, u64 unit, SegInfo* info_out) {
     KeyUnit ku;
     if (n_segments == 1) {
+        *info_out = seg0;
         ku.seg = 0;
-        ku.KB = segs[0].block_keys;
+        ku.KB = seg0.block_keys;
         ku.d = single_d;
         ku.nb = (u32)((ku.d + ku.KB - 1) / ku.KB);
         ku.item_begin = 0;
         ku.blk0 = (u32)unit * kWaves;
     } else {
         ku.seg = find_unit_segment(states, n_segments, unit);
-        ku.KB = segs[ku.seg].block_keys;
+        *info_out = segs[ku.seg];
+        ku.KB = info_out->block_keys;
         ku.d = states[ku.seg].d;
         ku.nb = states[ku.seg].nb;
         ku.item_begin = states[ku.seg].item_begin;
         ku.blk0 = (u32)(unit - states[ku.seg].unit_begin) * kWaves;
     }
-    ku.l = segs[ku.seg].flag_bits;
-    ku.cb = segs[ku.seg].chunk_begin;
-    ku.nch = segs[ku.seg].elem_count ? (u32)((segment_rows(segs[ku.seg]) + R - 1) / R) : 0u;
+    ku.l = info_out->flag_bits;
+    ku.cb = info_out->chunk_begin;
+    ku.nch = segment_chunks(*info_out, R);
     return ku;
 }
 
@@ -635,20 +643,43 @@ __device__ __forceinline__ void lds_excl_scan(T* arr, u32 n, T* scratch) {
     __syncthreads();
 }
 
-// P[j] = survivors of the segment in its chunks before j, j = 0..nch.
+// P[j] = survivors of the segment in its chunks before j, j = 0..nch.  Every thread fetches 16
+// consecutive chunk counts straight from memory (no condition on the loads, so all are in flight at
+// once), the workgroup scans the 256 sums, and the prefixes go to shared memory.
 __device__ __forceinline__ void build_prefix(const u32* __restrict__ ccount, u32 cb, u32 nch, u32* P, u32* scratch) {
+    constexpr u32 PER = kMaxSegChunks / kThreads;
+    const u32 t = threadIdx.x;
+    __syncthreads();                                   // earlier readers of P are done
+    u32 v[PER], sum = 0;
+#pragma unroll
+    for (u32 k = 0; k < PER; ++k) {
+        const u32 j = t * PER + k;
+        const u32 x = ccount[cb + (j < nch ? j : 0u)];
+        v[k] = (j < nch) ? x : 0u;
+    }
+#pragma unroll
+    for (u32 k = 0; k < PER; ++k) sum += v[k];
+    u32 total;
+    u32 run = block_excl_scan(sum, scratch, &total);
+#pragma unroll
+    for (u32 k = 0; k < PER; ++k) {
+        const u32 j = t * PER + k;
+        if (j < nch) P[j] = run;
+        run += v[k];
+    }
+    if (t == 0) P[nch] = total;
     __syncthreads();
-    for (u32 j = threadIdx.x; j < nch; j += kThreads) P[j] = ccount[cb + j];
-    lds_excl_scan<u32, kMaxSegChunks / kThreads>(P, nch, scratch);
 }
 
-// Largest j in [lo, hi] with P[j] <= r.
-__device__ __forceinline__ u32 find_chunk(const u32* P, u32 lo, u32 hi, u32 r) {
-    while (lo < hi) {
-        const u32 mid = (lo + hi + 1) >> 1;
-        if (P[mid] <= r) lo = mid; else hi = mid - 1;
-    }
-    return lo;
+// Largest j in [0, nch) with P[j] <= r, for a rank r that is the same in all lanes (P[0] = 0 <= r):
+// the wave probes 64 entries at a time, so two shared-memory round trips cover 4096 chunks.
+__device__ __forceinline__ u32 find_chunk_wave(const u32* P, u32 nch, u32 r, u32 lane) {
+    const u32 i1 = lane * 64u;
+    const bool p1 = i1 < nch && P[i1 < nch ? i1 : 0u] <= r;
+    const u32 c = (u32)__popcll(__ballot(p1)) - 1u;
+    const u32 i2 = c * 64u + lane;
+    const bool p2 = i2 < nch && P[i2 < nch ? i2 : 0u] <= r;
+    return c * 64u + (u32)__popcll(__ballot(p2)) - 1u;
 }
 
 __device__ __forceinline__ void wave_lds_sync() {
@@ -657,44 +688,54 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-struct Gather {          // where a run of consecutive ranks of one segment lives in the scratch arrays
-    const u32* P;
-    u32 stride;          // entries between chunk starts
-    u32 jlo, jhi;        // chunks the run touches
-    u32 step0;           // largest power of two <= jhi - jlo (0 if the run lies in one chunk)
-};
-
-__device__ __forceinline__ Gather make_gather(const u32* P, u32 R, u32 nch, u32 r_first, u32 r_last) {
-    Gather g;
-    g.P = P;
-    g.stride = R * kRow;
-    g.jlo = uniform(find_chunk(P, 0, nch - 1, r_first));
-    g.jhi = uniform(find_chunk(P, g.jlo, nch - 1, r_last));
-    const u32 span = g.jhi - g.jlo;
-    g.step0 = span ? 1u << (31u - __clz(span)) : 0u;
-    return g;
+__device__ __forceinline__ u32 wave_incl_scan_max(u32 x) {
+    u32 y;
+    y = dpp_mov<kDppRowShr1>(0u, x); x = x > y ? x : y;
+    y = dpp_mov<kDppRowShr2>(0u, x); x = x > y ? x : y;
+    y = dpp_mov<kDppRowShr4>(0u, x); x = x > y ? x : y;
+    y = dpp_mov<kDppRowShr8>(0u, x); x = x > y ? x : y;
+    y = dpp_mov<kDppRowBcast15, 0xA>(0u, x); x = x > y ? x : y;
+    y = dpp_mov<kDppRowBcast31, 0xC>(0u, x); x = x > y ? x : y;
+    return x;
 }
 
 constexpr u32 kKeyRows = kSub / 64;   // rows of 64 keys a wave handles at a time
 
 // Scratch entries, relative to the segment's chunk 0 (below 2^32: a gradient has fewer elements), of
-// the keys with segment ranks r0 + 64*q + lane, q = 0..15.  The searches of the 16 rows advance
-// together, one shared-memory probe each per step, so their latencies overlap.  Ranks beyond the run
-// give entries that must not be used.
-__device__ __forceinline__ void find_entries(const Gather& g, u32 r0, u32 lane, u32 (&ent)[kKeyRows]) {
-    u32 j[kKeyRows];
+// the n <= 1024 keys with segment ranks r0 + 64*q + lane, q = 0..15 (entries beyond n must not be
+// used).  jlo / jhi are the chunks of the first / last of these ranks.  If the run crosses chunks,
+// every chunk that starts inside it leaves its number at its first rank in `mark` (1024 words of the
+// wave's shared memory, clobbered), and a running maximum spreads the numbers over the ranks.
+__device__ __forceinline__ void find_entries(const u32* P, u32 stride, u32 jlo, u32 jhi, u32 r0, u32 n, u32 lane,
+                                             u32* mark, u32 (&ent)[kKeyRows]) {
+    if (jlo == jhi) {
+        const u32 base = jlo * stride - P[jlo];
 #pragma unroll
-    for (u32 q = 0; q < kKeyRows; ++q) j[q] = g.jlo;
-    for (u32 step = g.step0; step; step >>= 1) {
-#pragma unroll
-        for (u32 q = 0; q < kKeyRows; ++q) {
-            const u32 cand = j[q] + step;
-            const u32 probe = g.P[cand < g.jhi ? cand : g.jhi];
-            if (cand <= g.jhi && probe <= r0 + q * 64u + lane) j[q] = cand;
-        }
+        for (u32 q = 0; q < kKeyRows; ++q) ent[q] = base + r0 + q * 64u + lane;
+        return;
     }
 #pragma unroll
-    for (u32 q = 0; q < kKeyRows; ++q) ent[q] = j[q] * g.stride + (r0 + q * 64u + lane - g.P[j[q]]);
+    for (u32 q = 0; q < kKeyRows; ++q) mark[q * 64u + lane] = 0;
+    wave_lds_sync();
+    for (u32 j = jlo + 1u + lane; j <= jhi; j += 64u) atomicMax(&mark[P[j] - r0], j);   // r0 < P[j] <= r0 + n - 1
+    wave_lds_sync();
+    u32 m[kKeyRows];
+#pragma unroll
+    for (u32 q = 0; q < kKeyRows; ++q) m[q] = mark[q * 64u + lane];
+    u32 carry = jlo;
+#pragma unroll
+    for (u32 q = 0; q < kKeyRows; ++q) {
+        u32 j = wave_incl_scan_max(m[q]);
+        j = j > carry ? j : carry;
+        carry = read_lane(j, 63);
+        m[q] = j;
+    }
+#pragma unroll
+    for (u32 q = 0; q < kKeyRows; ++q) {
+        const u32 j = (q * 64u < n) ? m[q] : jlo;
+        ent[q] = j * stride + (r0 + q * 64u + lane - P[j]);
+    }
+    wave_lds_sync();
 }
 
 // Delta of row k's keys: `carry` is the key before the row on entry and the row's last key on return.
@@ -712,30 +753,32 @@ __device__ __forceinline__ u32 row_delta(u32 key, u32 r0, u32 k, u32 n, u32 lane
 }
 
 __global__ void __launch_bounds__(kThreads)
-k_measure_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments, u32 R,
-               const u32* __restrict__ ccount, const u32* __restrict__ skeys, BlockInfo* __restrict__ binfo,
+k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
+               u32 R, const u32* __restrict__ ccount, const u32* __restrict__ skeys, BlockInfo* __restrict__ binfo,
                unsigned long long* __restrict__ gsum, u32 g_shift, Ctrl* ctrl) {
     __shared__ u32 s_P[kMaxSegChunks + 1];
     __shared__ u32 s_scan[kWaves + 1];
+    __shared__ u32 s_markall[kWaves][kSub];
     __shared__ uint8_t s_needall[kWaves][kMaxKB];     // significant bits of every delta of the wave's block
     const u32 lane = lane_id(), w = uniform(wave_id());
     uint8_t* s_need = s_needall[w];
+    u32* s_mark = s_markall[w];
     // a single gradient: its survivor count is the total of the scan of its chunk counts
     u64 total_units, single_d = 0;
     u32 cur_seg = 0xFFFFFFFFu;
     if (n_segments == 1) {
-        const SegInfo info = segs[0];
-        const u32 nch = info.elem_count ? (u32)((segment_rows(info) + R - 1) / R) : 0u;
-        build_prefix(ccount, info.chunk_begin, nch, s_P, s_scan);
+        const u32 nch = segment_chunks(seg0, R);
+        build_prefix(ccount, seg0.chunk_begin, nch, s_P, s_scan);
         cur_seg = 0;
         single_d = s_P[nch];
-        const u64 nb = (single_d + info.block_keys - 1) / info.block_keys;
+        const u64 nb = (single_d + seg0.block_keys - 1) / seg0.block_keys;
         total_units = ((nb ? nb : 1) + kWaves - 1) / kWaves;
     } else {
         total_units = ctrl->total_units;
     }
     for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x) {
-        const KeyUnit ku = key_unit(segs, states, n_segments, R, single_d, unit);
+        SegInfo info;
+        const KeyUnit ku = key_unit(seg0, segs, states, n_segments, R, single_d, unit, &info);
         if (ku.seg != cur_seg) {
             build_prefix(ccount, ku.cb, ku.nch, s_P, s_scan);
             cur_seg = ku.seg;
@@ -752,26 +795,28 @@ k_measure_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ st
             }
             continue;
         }
-        const u32 first = blk * ku.KB;
-        const u32 cnt = (u32)((ku.d - first < ku.KB) ? ku.d - first : ku.KB);
+        const u32 first = uniform(blk * ku.KB);
+        const u32 cnt = uniform((u32)((ku.d - first < ku.KB) ? ku.d - first : ku.KB));
         const u32 nsub = (cnt + kSub - 1) / kSub;
-        const u32* seg_keys = skeys + chunk_slot0(segs[ku.seg], ku.seg, 0, R);
+        const u32 stride = R * kRow;
+        const u32* seg_keys = skeys + chunk_slot0(info, ku.seg, 0, R);
+        // chunk of the key before the block (its own first key for the segment's first block)
+        u32 jnext = uniform(find_chunk_wave(s_P, ku.nch, first ? first - 1 : 0u, lane));
         u32 preKey = 0;
-        if (first) {
-            const u32 j = find_chunk(s_P, 0, ku.nch - 1, first - 1);
-            preKey = seg_keys[j * (R * kRow) + (first - 1 - s_P[j])];
-        }
+        if (first) preKey = seg_keys[jnext * stride + (first - 1 - s_P[jnext])];
         // first loop of Algorithm 2: deltas and the longest of them (M = bit length of maxDelta)
         bool unsorted = false;
-        u32 carry = preKey, mxneed = 0;
+        u32 carry = 0, mxneed = 0;
         for (u32 sub = 0; sub < nsub; ++sub) {
             const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
             const u32 r0 = first + sub * kSub;
-            const Gather g = make_gather(s_P, R, ku.nch, r0, r0 + n - 1);
+            const u32 jlo = uniform(find_chunk_wave(s_P, ku.nch, r0, lane));
+            const u32 jhi = uniform(find_chunk_wave(s_P, ku.nch, r0 + n - 1, lane));
             u32 ent[kKeyRows], key[kKeyRows];
-            find_entries(g, r0, lane, ent);
+            find_entries(s_P, stride, jlo, jhi, r0, n, lane, s_mark, ent);
 #pragma unroll
             for (u32 q = 0; q < kKeyRows; ++q) key[q] = (q * 64u + lane < n) ? seg_keys[ent[q]] : 0u;
+            if (sub == 0) carry = preKey;                   // (its fetch was in flight until here)
 #pragma unroll
             for (u32 q = 0; q < kKeyRows; ++q) {
                 if (q * 64u < n) {
@@ -815,8 +860,8 @@ __device__ __forceinline__ u64 item_offset8(const u64* s_G, const BlockInfo* __r
 }
 
 __global__ void __launch_bounds__(kThreads)
-k_pack_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments, u32 R,
-            const u32* __restrict__ ccount, const u32* __restrict__ skeys,
+k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
+            u32 R, const u32* __restrict__ ccount, const u32* __restrict__ skeys,
             const uint8_t* __restrict__ scodes, const BlockInfo* __restrict__ binfo,
             const unsigned long long* __restrict__ gsum, u32 g_shift, uint8_t* __restrict__ out, u64 out_capacity,
             u64* out_offsets, u32 single, u32* out_status, const Ctrl* ctrl) {
@@ -832,12 +877,11 @@ k_pack_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ state
     u64 total_units, total_items, single_d = 0;
     u32 cur_seg = 0xFFFFFFFFu;
     if (n_segments == 1) {
-        const SegInfo info = segs[0];
-        const u32 nch = info.elem_count ? (u32)((segment_rows(info) + R - 1) / R) : 0u;
-        build_prefix(ccount, info.chunk_begin, nch, s_P, s_scan);
+        const u32 nch = segment_chunks(seg0, R);
+        build_prefix(ccount, seg0.chunk_begin, nch, s_P, s_scan);
         cur_seg = 0;
         single_d = s_P[nch];
-        const u64 nb = (single_d + info.block_keys - 1) / info.block_keys;
+        const u64 nb = (single_d + seg0.block_keys - 1) / seg0.block_keys;
         total_items = nb ? nb : 1;
         total_units = (total_items + kWaves - 1) / kWaves;
     } else {
@@ -865,9 +909,11 @@ k_pack_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ state
     }
     if (!ok) return;                // nothing is written into a buffer that cannot hold the result
 
+    for (u32 i = lane; i < kSub * 5 / 32 + 2; i += 64) s_flg[i] = 0;
     u64 sbeg8 = 0;
     for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x) {
-        const KeyUnit ku = key_unit(segs, states, n_segments, R, single_d, unit);
+        SegInfo info;
+        const KeyUnit ku = key_unit(seg0, segs, states, n_segments, R, single_d, unit, &info);
         if (ku.seg != cur_seg) {
             build_prefix(ccount, ku.cb, ku.nch, s_P, s_scan);
             cur_seg = ku.seg;
@@ -877,7 +923,6 @@ k_pack_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ state
         const u32 nitems = ku.nb ? ku.nb : 1u;
         if (blk >= nitems) continue;
         const u64 item = ku.item_begin + blk;
-        const SegInfo info = segs[ku.seg];
         const u64 sbeg = 8ull * sbeg8;
         const u64 dir_off = sbeg + kHeaderBytes + align8(ku.d);
         const u64 blocks_off = dir_off + 16ull * ku.nb;
@@ -900,9 +945,9 @@ k_pack_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ state
         }
         if (ku.nb == 0) continue;                                      // a segment without survivors
         const BlockInfo bi = binfo[item];
-        const u32 M = bi.M, l = ku.l, magic = level_magic(M);
-        const u32 first = blk * ku.KB;
-        const u32 cnt = (u32)((ku.d - first < ku.KB) ? ku.d - first : ku.KB);
+        const u32 M = uniform(bi.M), l = ku.l, magic = level_magic(M);
+        const u32 first = uniform(blk * ku.KB);
+        const u32 cnt = uniform((u32)((ku.d - first < ku.KB) ? ku.d - first : ku.KB));
         const u32 nsub = (cnt + kSub - 1) / kSub;
         const u32 fwords = (cnt * l + 63u) >> 6;                       // 64-bit words of the flags plane
         const u64 start = (blk == 0) ? blocks_off : 8ull * item_offset8(s_G, binfo, g_shift, item, lane);
@@ -914,31 +959,34 @@ k_pack_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ state
         u32* fdst = reinterpret_cast<u32*>(out + start);               // flags plane, 32-bit words
         u32* pdst = fdst + 2u * fwords;                                // payload plane
         uint8_t* vdst = out + sbeg + kHeaderBytes + first;             // the block's part of the value plane
-        for (u32 i = lane; i < kSub + 2; i += 64) s_pay[i] = 0;
-        for (u32 i = lane; i < kSub * 5 / 32 + 2; i += 64) s_flg[i] = 0;
-        wave_lds_sync();
 
         // second loop of Algorithm 2, 1024 keys at a time
+        const u32 stride = R * kRow;
         const u64 seg_slot0 = chunk_slot0(info, ku.seg, 0, R);
         const u32* seg_keys = skeys + seg_slot0;
         const uint8_t* seg_codes = scodes + seg_slot0;
-        u32 carry = bi.preKey;
-        u32 wbits = 0;               // payload bits waiting in s_pay[0] from the previous round
+        u32 carry = uniform(bi.preKey);
+        u32 wbits = 0;               // payload bits of this block waiting in `wword` from the previous round
+        u32 wword = 0;
         u32 pw = 0;                  // payload words already written
         bool unsorted = false;
         for (u32 sub = 0; sub < nsub; ++sub) {
             const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
             const u32 r0 = first + sub * kSub;
-            const Gather g = make_gather(s_P, R, ku.nch, r0, r0 + n - 1);
-            u32 rowbase = wbits;
+            const u32 jlo = uniform(find_chunk_wave(s_P, ku.nch, r0, lane));
+            const u32 jhi = uniform(find_chunk_wave(s_P, ku.nch, r0 + n - 1, lane));
             u32 ent[kKeyRows], key[kKeyRows], code[kKeyRows];
-            find_entries(g, r0, lane, ent);
+            find_entries(s_P, stride, jlo, jhi, r0, n, lane, s_pay, ent);     // borrows the payload window
 #pragma unroll
             for (u32 q = 0; q < kKeyRows; ++q) {
                 const bool in = q * 64u + lane < n;
                 key[q] = in ? seg_keys[ent[q]] : 0u;
                 code[q] = in ? seg_codes[ent[q]] : 0u;
             }
+            // the payload window: word 0 carries the bits left over from the previous round
+            for (u32 i = lane; i < kSub + 2; i += 64) s_pay[i] = (i == 0) ? wword : 0u;
+            wave_lds_sync();
+            u32 rowbase = wbits;
 #pragma unroll
             for (u32 q = 0; q < kKeyRows; ++q) {
                 const u32 i = q * 64u + lane;
@@ -981,9 +1029,7 @@ k_pack_keys(const SegInfo* __restrict__ segs, const SegState* __restrict__ state
                 if (last) {
                     if (((pw + nw) & 1u) && lane == 0) pdst[pw + nw] = 0;
                 } else {
-                    const u32 keep = s_pay[full];
-                    wave_lds_sync();
-                    for (u32 i = lane; i <= full + 1u; i += 64) s_pay[i] = (i == 0) ? keep : 0u;
+                    wword = uniform(s_pay[full]);
                     pw += full;
                     wbits = rest;
                 }
