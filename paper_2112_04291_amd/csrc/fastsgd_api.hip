@@ -233,7 +233,7 @@ static fastsgd_status decompress_impl(const void* d_streams, size_t total_bytes,
     }
     marks.mark(stream);
     // every key costs at least one value byte, so bytes/256 bounds the number of key blocks
-    hipLaunchKernelGGL(k_decode, dim3(clamp_grid((u64)total_bytes / 256 + n_segments, (u64)cus * 4)), dim3(kThreads), 0,
+    hipLaunchKernelGGL(k_decode, dim3(clamp_grid(((u64)total_bytes / 256 + n_segments + kWaves - 1) / kWaves, (u64)cus * 7)), dim3(kThreads), 0,
                        stream, streams, segs, n_segments, ctrl, d_keys_out, d_values_out, d_counts,
                        single ? 1u : n_segments + 1u, d_status);
     marks.mark(stream);

@@ -128,126 +128,132 @@ __device__ __forceinline__ u32 find_dec_segment(const DecSeg* segs, u32 n_segmen
     return lo;
 }
 
+// One key block per WAVE, 1024 keys at a time; lane `lane` holds, for row q = 0..15, key 64*q + lane.
+// Per round the wave fetches the round's flag words, the payload words the round can reach (its start
+// is known from the rounds before, its end is bounded by M bits per key) and the code bytes in one
+// go, parks flags and payload in its slice of shared memory, and then per row: flag -> level ->
+// length, a scan of the lengths -> bit offsets, a 64-bit window at that offset -> delta, a scan of the
+// deltas on top of the key before the row -> keys (phase 2), code byte -> magnitude table -> value
+// (phases 3-4).  The waves of a workgroup never synchronise.
 __global__ void __launch_bounds__(kThreads)
 k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u32 n_segments, DecCtrl* ctrl,
          u32* __restrict__ keys_out, float* __restrict__ values_out, u64* out_counts, u32 n_counts,
          u32* out_status) {
-    __shared__ u32 s_flags[kMaxKB * 5 / 32 + 2];
-    __shared__ u32 s_pay[kMaxKB + 2];
-    __shared__ u32 s_V[128];
-    __shared__ u32 s_scan[kWaves + 1];
-    __shared__ u64 s_scan64[kWaves];
-    __shared__ u32 s_bad;
-    const u32 t = threadIdx.x, lane = lane_id(), w = wave_id();
+    __shared__ u32 s_payall[kWaves][kSub + 2];
+    __shared__ u32 s_flgall[kWaves][kSub * 5 / 32 + 2];
+    __shared__ u32 s_Vall[kWaves][128];
+    const u32 lane = lane_id(), w = uniform(wave_id());
+    u32* s_pay = s_payall[w];
+    u32* s_flg = s_flgall[w];
+    u32* s_V = s_Vall[w];
     const u64 total_items = ctrl->total_items;
     u32 cur_seg = 0xFFFFFFFFu;
 
-    for (u64 item = blockIdx.x; item < total_items; item += gridDim.x) {
-        const u32 seg = (n_segments == 1) ? 0u : find_dec_segment(segs, n_segments, item);
+    for (u64 item = (u64)blockIdx.x * kWaves + w; item < total_items; item += (u64)gridDim.x * kWaves) {
+        const u32 seg = (n_segments == 1) ? 0u : uniform(find_dec_segment(segs, n_segments, item));
         const DecSeg* ds = &segs[seg];
-        const u32 KB = ds->KB, l = ds->l, tau = ds->tau, nb = ds->nb;
+        const u32 KB = uniform(ds->KB), l = uniform(ds->l), tau = uniform(ds->tau), nb = uniform(ds->nb);
         const u64 d = ds->d;
-        const u32 blk = (u32)(item - ds->item_begin);
-        const u64 first = (u64)blk * KB;
-        const u32 cnt = (u32)((d - first < KB) ? d - first : KB);
-        const u32 per = KB / kThreads;
+        const u32 blk = uniform((u32)(item - ds->item_begin));
+        const u32 first = blk * KB;
+        const u32 cnt = uniform((u32)((d - first < KB) ? d - first : KB));
+        const u32 nsub = (cnt + kSub - 1) / kSub;
         if (seg != cur_seg) {
-            __syncthreads();
-            if (t < 128) s_V[t] = ds->V[t];
+            wave_lds_sync();
+            s_V[lane] = ds->V[lane];
+            s_V[lane + 64] = ds->V[lane + 64];
             cur_seg = seg;
+            wave_lds_sync();
         }
-        if (t == 0) s_bad = 0;
-
-        // directory entry, checked against its neighbour
+        // directory entry of the block and of the next one, checked against each other
         const u32* dir = reinterpret_cast<const u32*>(streams + ds->dir_off + 16ull * blk);
-        const u32 off8 = dir[0], preKey = dir[1], M = dir[2], pbits = dir[3];
-        const u64 next_off8 = (blk + 1 < nb) ? (u64)dir[4] : ds->total_words;
+        const bool has_next = blk + 1 < nb;
+        const u32 dword = (lane < 4 || (lane < 8 && has_next)) ? dir[lane] : 0u;
+        const u32 off8 = read_lane(dword, 0), preKey = read_lane(dword, 1), M = read_lane(dword, 2);
+        const u32 pbits = read_lane(dword, 3), next_off8_dir = read_lane(dword, 4), next_pre = read_lane(dword, 5);
+        const u64 total_words = ds->total_words;
+        const u64 next_off8 = has_next ? (u64)next_off8_dir : total_words;
         const u32 fwords = (cnt * l + 63u) >> 6, pwords = (pbits + 63u) >> 6;
         bool bad = (M < 1 || M > 32) || (pbits > cnt * 32u) || ((u64)off8 + fwords + pwords != next_off8) ||
-                   ((u64)off8 + fwords + pwords > ds->total_words) || (blk == 0 && (off8 != 0 || preKey != 0));
-        __syncthreads();
+                   ((u64)off8 + fwords + pwords > total_words) || (blk == 0 && (off8 != 0 || preKey != 0));
         if (!bad) {
-            const u64* src = reinterpret_cast<const u64*>(streams + ds->blocks_off + 8ull * off8);
-            for (u32 i = t; i < fwords; i += kThreads) {
-                const u64 x = src[i];
-                s_flags[2 * i] = (u32)x; s_flags[2 * i + 1] = (u32)(x >> 32);
-            }
-            for (u32 i = t; i < pwords; i += kThreads) {
-                const u64 x = src[fwords + i];
-                s_pay[2 * i] = (u32)x; s_pay[2 * i + 1] = (u32)(x >> 32);
-            }
-            if (t < 2) { s_flags[2 * fwords + t] = 0; s_pay[2 * pwords + t] = 0; }   // window reads run one word over
-        }
-        __syncthreads();
-
-        // phase 1: lengths from the flags, bit offsets by a scan
-        u32 len[16], mybits = 0;
+            const u32* fsrc = reinterpret_cast<const u32*>(streams + ds->blocks_off + 8ull * off8);   // flags plane
+            const u32* psrc = fsrc + 2u * fwords;                                                    // payload plane
+            const u32 pw_total = 2u * pwords;
+            const uint8_t* codes = streams + ds->stream_begin + kHeaderBytes + first;
+            const u64 out0 = ds->pair_begin + first;
+            u32 pbit = 0;                  // payload bits consumed by the rounds before
+            u32 carry = preKey;            // key before the row in hand
+            bool wrapped = false, badcode = false;
+            for (u32 sub = 0; sub < nsub; ++sub) {
+                const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
+                const u32 nfw = (n * l + 31u) >> 5, f0 = sub * 32u * l;
+                const u32 pw0 = pbit >> 5, wbits = pbit & 31u;
+                u32 npw = ((wbits + n * M + 31u) >> 5) + 1u;           // words this round can reach (+1: windows)
+                if (npw > kSub + 2) npw = kSub + 2;
+                // all fetches of the round first
+                u32 fw[3], pwd[17], code[kKeyRows];
 #pragma unroll
-        for (u32 k = 0; k < 16; ++k) {
-            const u32 i = t * per + k;
-            len[k] = 0;
-            if (!bad && k < per && i < cnt) {
-                const u32 fpos = i * l;
-                const u64 win = (u64)s_flags[fpos >> 5] | ((u64)s_flags[(fpos >> 5) + 1] << 32);
-                const u32 level = ((u32)(win >> (fpos & 31u)) & ((1u << l) - 1u)) + 1u;
-                len[k] = (level * M + (1u << l) - 1u) >> l;
-                mybits += len[k];
-            }
-        }
-        u32 total_bits;
-        u32 bitpos = block_excl_scan(mybits, s_scan, &total_bits);
-        bad = bad || (total_bits != pbits);
-
-        // deltas and their running sum inside the thread
-        u64 run = 0;
-        u64 local[16];
+                for (u32 k = 0; k < 3; ++k) { const u32 i = k * 64u + lane; fw[k] = fsrc[f0 + (i < nfw ? i : 0u)]; }
 #pragma unroll
-        for (u32 k = 0; k < 16; ++k) {
-            const u32 i = t * per + k;
-            local[k] = 0;
-            if (!bad && k < per && i < cnt) {
-                const u64 win = (u64)s_pay[bitpos >> 5] | ((u64)s_pay[(bitpos >> 5) + 1] << 32);
-                const u32 mask = len[k] >= 32u ? 0xFFFFFFFFu : ((1u << len[k]) - 1u);
-                run += (u32)(win >> (bitpos & 31u)) & mask;
-                local[k] = run;
-                bitpos += len[k];
-            }
-        }
-        // phase 2: prefix sum across the workgroup, plus preKey
-        const u64 incl = wave_incl_scan64(run);
-        if (lane == 63) s_scan64[w] = incl;
-        __syncthreads();
-        u64 before = preKey, block_sum = 0;
-#pragma unroll
-        for (u32 k = 0; k < kWaves; ++k) {
-            if (k < w) before += s_scan64[k];
-            block_sum += s_scan64[k];
-        }
-        before += incl - run;
-        const u64 last_key = (u64)preKey + block_sum;
-        bad = bad || (last_key > 0xFFFFFFFFull) || (blk + 1 < nb && (u32)last_key != dir[5]);
-
-        // phases 3-4 and the writes
-        const u64 out0 = ds->pair_begin + first;
-        const uint8_t* codes = streams + ds->stream_begin + kHeaderBytes + first;
-        bool badcode = false;
-#pragma unroll
-        for (u32 k = 0; k < 16; ++k) {
-            const u32 i = t * per + k;
-            if (!bad && k < per && i < cnt) {
-                const u32 byte = codes[i];
-                const u32 c = (byte & 0x7Fu) + 1u;
-                if (c > tau) badcode = true;
-                else {
-                    keys_out[out0 + i] = (u32)(before + local[k]);
-                    values_out[out0 + i] = __uint_as_float(s_V[c - 1] | ((byte >> 7) << 31));
+                for (u32 k = 0; k < 17; ++k) {
+                    const u32 i = k * 64u + lane;
+                    pwd[k] = (k * 64u < npw && pw_total) ? psrc[(pw0 + i < pw_total) ? pw0 + i : pw_total - 1u] : 0u;
                 }
+#pragma unroll
+                for (u32 q = 0; q < kKeyRows; ++q) code[q] = (q * 64u + lane < n) ? codes[sub * kSub + q * 64u + lane] : 0u;
+#pragma unroll
+                for (u32 k = 0; k < 3; ++k) { const u32 i = k * 64u + lane; if (i < nfw + 1u) s_flg[i] = (i < nfw) ? fw[k] : 0u; }
+#pragma unroll
+                for (u32 k = 0; k < 17; ++k) {
+                    const u32 i = k * 64u + lane;
+                    if (k * 64u < npw && i < npw) s_pay[i] = (pw0 + i < pw_total) ? pwd[k] : 0u;
+                }
+                wave_lds_sync();
+                u32 rowbase = wbits;
+#pragma unroll
+                for (u32 q = 0; q < kKeyRows; ++q) {
+                    const u32 i = q * 64u + lane;
+                    if (q * 64u < n) {
+                        u32 len = 0;
+                        if (i < n) {
+                            const u32 fpos = i * l;
+                            const u64 win = (u64)s_flg[fpos >> 5] | ((u64)s_flg[(fpos >> 5) + 1] << 32);
+                            const u32 level = ((u32)(win >> (fpos & 31u)) & ((1u << l) - 1u)) + 1u;
+                            len = level_len(level, M, l);
+                        }
+                        const u32 incl = wave_incl_scan(len);
+                        u32 delta = 0;
+                        if (i < n) {
+                            const u32 bitpos = rowbase + incl - len;
+                            const u64 win = (u64)s_pay[bitpos >> 5] | ((u64)s_pay[(bitpos >> 5) + 1] << 32);
+                            const u32 mask = len >= 32u ? 0xFFFFFFFFu : ((1u << len) - 1u);
+                            delta = (u32)(win >> (bitpos & 31u)) & mask;
+                        }
+                        rowbase += read_lane(incl, 63);
+                        const u32 key = carry + wave_incl_scan(delta);          // modulo 2^32 ...
+                        const u32 prev = lane_above(key, carry);
+                        if (i < n) {
+                            wrapped |= key < prev;                              // ... so a wrap shows as a step down
+                            const u32 byte = code[q];
+                            const u32 c = (byte & 0x7Fu) + 1u;
+                            if (c > tau) badcode = true;
+                            else {
+                                keys_out[out0 + sub * kSub + i] = key;
+                                values_out[out0 + sub * kSub + i] = __uint_as_float(s_V[c - 1] | ((byte >> 7) << 31));
+                            }
+                        }
+                        const u32 last_lane = (n - q * 64u) < 64u ? (n - q * 64u - 1u) : 63u;
+                        carry = read_lane(key, uniform(last_lane));
+                    }
+                }
+                pbit = rowbase - wbits + pbit;
+                if (pbit > pbits) { bad = true; break; }        // the lengths overrun the payload plane
+                wave_lds_sync();
             }
+            bad = bad || (pbit != pbits) || __any(wrapped) || __any(badcode) || (has_next && carry != next_pre);
         }
-        if (bad || badcode) s_bad = 1;
-        __syncthreads();
-        if (s_bad && t == 0) dec_fail(ctrl, FASTSGD_ERR_CORRUPT_STREAM, out_status, out_counts, n_counts);
-        __syncthreads();
+        if (bad && lane == 0) dec_fail(ctrl, FASTSGD_ERR_CORRUPT_STREAM, out_status, out_counts, n_counts);
     }
 }
 
