@@ -37,12 +37,14 @@ static EncodePlan make_plan(u64 total_n, u32 n_segments, u32 min_kb) {
     pl.max_chunks = (u64)kChunkTarget + n_segments;                // a segment adds at most one short chunk
     pl.max_items = total_n / min_kb + n_segments + 1;              // bound on key blocks (+1 per empty segment)
     pl.max_slots = total_n + 4ull * n_segments + 8;                // scratch entries: element index + 4 per segment
+    pl.max_rows = total_n / kRow + 2ull * n_segments + 2;           // a segment adds at most two partial rows
     u64 o = 0;
     pl.off_ctrl = o;  o += up(sizeof(Ctrl), 256);
     pl.off_gsum = o;  o += up((u64)(kMaxGroups + 1) * 8, 256);
     pl.zero_end = o;                                               // a single-gradient call clears up to here
     pl.off_gbins = o; o += up((u64)n_segments * pl.n_slots * kBinWords * 8, 256);
     pl.zero_end_batch = o;                                         // a batch also clears the abs-sum records
+    pl.off_rowmax = o;   o += up(pl.max_rows * 4, 256);
     pl.off_ccount = o;   o += up(pl.max_chunks * 4, 256);
     pl.off_binfo = o;    o += up(pl.max_items * sizeof(BlockInfo), 256);
     pl.off_seginfo = o;  o += up((u64)n_segments * sizeof(SegInfo), 256);
@@ -107,11 +109,12 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
         SegInfo& si = segs[s];
         si.elem_begin = seg_offsets[s] - first_elem + mis;
         si.elem_count = cnt;
-        si.base = p->base; si.tau = p->tau; si.flag_bits = p->flag_bits; si.block_keys = p->block_keys; si.pad = 0;
+        si.base = p->base; si.tau = p->tau; si.flag_bits = p->flag_bits; si.block_keys = p->block_keys;
         if (n_tiles >= 0xFFFFFFFFull) return FASTSGD_ERR_INVALID_ARG;
         si.tile_begin = (u32)n_tiles;
         const u64 span = cnt ? si.elem_begin + cnt - (si.elem_begin & ~3ull) : 0;   // from the aligned start
         n_tiles += (span + kTile - 1) / kTile;
+        si.row_begin = (u32)total_rows;
         total_rows += (span + kRow - 1) / kRow;
         const u64 blocks = (cnt + p->block_keys - 1) / p->block_keys;
         max_items += blocks ? blocks : 1;
@@ -131,6 +134,7 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
         n_chunks += c;
     }
     const EncodePlan pl = make_plan(total_n, n_segments, min_kb);
+    if (total_rows > pl.max_rows || total_rows >= 0xFFFFFFFFull) return FASTSGD_ERR_INVALID_ARG;
     if (n_chunks > pl.max_chunks || max_items > pl.max_items || n_tiles >= 0xFFFFFFFFull || R64 > 0xFFFFFFull)
         return FASTSGD_ERR_INVALID_ARG;
     if (ws_bytes < pl.total) return FASTSGD_ERR_BUFFER_TOO_SMALL;
@@ -143,6 +147,7 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + pl.off_ctrl);
     unsigned long long* gsum = reinterpret_cast<unsigned long long*>(ws + pl.off_gsum);
     u64* gbins = reinterpret_cast<u64*>(ws + pl.off_gbins);
+    u32* rowmax = reinterpret_cast<u32*>(ws + pl.off_rowmax);
     u32* ccount = reinterpret_cast<u32*>(ws + pl.off_ccount);
     BlockInfo* binfo = reinterpret_cast<BlockInfo*>(ws + pl.off_binfo);
     SegInfo* dsegs = reinterpret_cast<SegInfo*>(ws + pl.off_seginfo);
@@ -174,10 +179,10 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     sum_grid = clamp_grid(n_tiles, sum_grid);
     if (single)
         hipLaunchKernelGGL(k_abs_sum<true>, dim3(sum_grid), dim3(kThreads), 0, stream, vbase, dsegs, 1u, n_tiles,
-                           gbins, sum_grid, zero_begin, zero_words, segs[0], dsegs);
+                           gbins, sum_grid, zero_begin, zero_words, segs[0], dsegs, rowmax);
     else
         hipLaunchKernelGGL(k_abs_sum<false>, dim3(sum_grid), dim3(kThreads), 0, stream, vbase, dsegs, n_segments,
-                           n_tiles, gbins, pl.n_slots, zero_begin, (u64)0, segs[0], dsegs);
+                           n_tiles, gbins, pl.n_slots, zero_begin, (u64)0, segs[0], dsegs, rowmax);
     marks.mark(stream);
     hipLaunchKernelGGL(k_tables, dim3(n_segments), dim3(kTableThreads), 0, stream, dsegs, dstates, gbins,
                        single ? sum_grid : pl.n_slots, ctrl);
@@ -185,7 +190,7 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     if (n_chunks)
         hipLaunchKernelGGL(k_encode_values, dim3((u32)((n_chunks + kValWaves - 1) / kValWaves)),
                            dim3(kValWaves * kWave), 0, stream, kbase, vbase, dsegs, dstates, n_segments, (u32)n_chunks,
-                           R, ccount, skeys, scodes);
+                           R, rowmax, ccount, skeys, scodes);
     marks.mark(stream);
     if (!single)
         hipLaunchKernelGGL(k_plan_segments, dim3((n_segments + kWaves - 1) / kWaves), dim3(kThreads), 0, stream, dsegs,

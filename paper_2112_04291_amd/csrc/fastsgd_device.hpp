@@ -36,7 +36,8 @@ struct SegInfo {
     double base;
     u32 tile_begin;     // first tile of the segment in the abs-sum pass
     u32 chunk_begin;    // first chunk of the segment in the value pass
-    u32 tau, flag_bits, block_keys, pad;
+    u32 tau, flag_bits, block_keys;
+    u32 row_begin;      // first row of the segment in the call's row numbering (row maxima)
 };
 static_assert(sizeof(SegInfo) == 48, "segment record layout");
 
@@ -67,10 +68,10 @@ struct Ctrl {
 static_assert(sizeof(Ctrl) == 64, "control block layout");
 
 struct EncodePlan {     // host-computed carve-up of the workspace
-    u64 max_chunks, max_items, total_n, max_slots;
+    u64 max_chunks, max_items, total_n, max_slots, max_rows;
     u32 n_segments, n_slots;
     u64 off_ctrl, off_gsum, zero_end, off_gbins, zero_end_batch;   // [off_ctrl, zero_end*) is cleared per call
-    u64 off_ccount, off_binfo, off_seginfo, off_segstate, off_skeys, off_scodes, total;
+    u64 off_rowmax, off_ccount, off_binfo, off_seginfo, off_segstate, off_skeys, off_scodes, total;
 };
 
 // ---------------------------------------------------------------------------------------------

@@ -26,6 +26,11 @@ __global__ void k_store_segments(SegInfo* segs, SegBatch batch, u32 first, u32 c
     if (threadIdx.x < count) segs[first + threadIdx.x] = batch.seg[threadIdx.x];
 }
 
+// Rows (of 256 elements) of a segment, counted from its first element rounded down to a multiple of 4.
+__device__ __forceinline__ u64 segment_rows(const SegInfo& s) {
+    return s.elem_count ? (s.elem_begin + s.elem_count - (s.elem_begin & ~3ull) + kRow - 1) / kRow : 0ull;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Tile geometry of the abs-sum pass.  A segment's tiles start at its first element rounded down to
 // a multiple of 4 (so float4 loads stay aligned); thread (wave w, lane) holds, for r = 0..3, the
@@ -115,14 +120,27 @@ __device__ __forceinline__ void flush_bins(u64 (*bins)[kThreads], u64* rec, u32 
     }
 }
 
-__device__ __forceinline__ void accumulate_tile(const u32 bits[4][4], u64 (*bins)[kThreads], u32& maxa) {
+// Also stores, for each of the wave's four rows of the tile that exist (row index below row_end), the
+// largest |v| of the row as a bit pattern: the second pass skips every row whose maximum is below the
+// threshold.  rowmax points at the entry of the tile's first row; trow0 is that row's index.
+__device__ __forceinline__ void accumulate_tile(const u32 bits[4][4], u64 (*bins)[kThreads], u32& maxa,
+                                                u32* __restrict__ rowmax, u64 trow0, u64 row_end) {
     const u32 t = threadIdx.x;
+#pragma unroll
+    for (u32 r = 0; r < 4; ++r) {
+        u32 m = bits[r][0] & 0x7FFFFFFFu;
+#pragma unroll
+        for (u32 c = 1; c < 4; ++c) { const u32 a = bits[r][c] & 0x7FFFFFFFu; m = a > m ? a : m; }
+        m = wave_max(m);
+        const u32 wr = wave_id() * 4u + r;
+        if (lane_id() == 0 && trow0 + wr < row_end) rowmax[wr] = m;
+        maxa = m > maxa ? m : maxa;
+    }
 #pragma unroll
     for (u32 r = 0; r < 4; ++r)
 #pragma unroll
         for (u32 c = 0; c < 4; ++c) {
             const u32 a = bits[r][c] & 0x7FFFFFFFu;
-            maxa = a > maxa ? a : maxa;
             const u32 e = a >> 23;
             const u32 e1 = e ? e : 1u;
             const u32 m = a - ((e1 - 1u) << 23);          // significand with its leading one (none for denormals)
@@ -135,7 +153,8 @@ __device__ __forceinline__ void accumulate_tile(const u32 bits[4][4], u64 (*bins
 template <bool SINGLE>
 __global__ void __launch_bounds__(kThreads)
 k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u32 n_segments, u64 n_tiles,
-          u64* gbins, u32 n_slots, u64* zero_begin, u64 zero_words, SegInfo single_seg, SegInfo* seg_store) {
+          u64* gbins, u32 n_slots, u64* zero_begin, u64 zero_words, SegInfo single_seg, SegInfo* seg_store,
+          u32* __restrict__ rowmax) {
     __shared__ u64 bins[kBins][kThreads];
     const u32 t = threadIdx.x;
 #pragma unroll
@@ -150,6 +169,7 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
     const u64 per_wg = (n_tiles + G - 1) / G;
     if (SINGLE) {
         const TileGeom g0 = tile_geom(single_seg, 0);
+        const u64 row_end = segment_rows(single_seg);
         for (u64 it = 0; it < per_wg; ++it) {
             const u64 tile = it * G + blockIdx.x;             // neighbours in time are neighbours in memory
             if (tile >= n_tiles) break;
@@ -158,7 +178,7 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
             g.full = (g.tile0 >= g.lo) && (g.tile0 + kTile <= g.hi);
             u32 bits[4][4];
             load_tile(values, g, bits);
-            accumulate_tile(bits, bins, maxa);
+            accumulate_tile(bits, bins, maxa, rowmax + tile * (kTile / kRow), tile * (kTile / kRow), row_end);
         }
         flush_bins<true>(bins, gbins + blockIdx.x, n_slots, maxa);
     } else {
@@ -174,10 +194,12 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
                 }
                 cur_seg = seg;
             }
-            const TileGeom g = tile_geom(segs[seg], tile);
+            const SegInfo info = segs[seg];
+            const TileGeom g = tile_geom(info, tile);
             u32 bits[4][4];
             load_tile(values, g, bits);
-            accumulate_tile(bits, bins, maxa);
+            const u64 trow0 = (tile - info.tile_begin) * (kTile / kRow);
+            accumulate_tile(bits, bins, maxa, rowmax + info.row_begin + trow0, trow0, segment_rows(info));
         }
         if (cur_seg != 0xFFFFFFFFu)
             flush_bins<false>(bins, gbins + (u64)cur_seg * n_slots * kBinWords + blockIdx.x % n_slots, n_slots, maxa);
@@ -295,20 +317,21 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Second pass over the values (Algorithm 1 lines 4-10).  A pure streaming pass: no wave depends on
-// another.  The elements of a call are cut into chunks of R rows (a row = 256 elements, a float4 per
-// lane); every WAVE owns one chunk and walks it in tiles of 8 rows:
-//   8 float4 loads per lane -> per row, keep test |v| >= threshold as four wave-wide masks; a row
-//   without survivors costs those four compares and a scalar branch -> survivors of the other rows are
-//   staged in the wave's slice of shared memory in element order (mask popcounts + mbcnt) -> once more
-//   than a few hundred wait there, densely over the staged survivors only: code by binary search in
-//   the boundary table, key fetch -> code byte and key appended to the CHUNK'S OWN SLOT of the scratch
-//   arrays (the chunk's first element index + rank in the chunk).  The loads of the next tile are
-//   issued before that flush, so its round trip overlaps with them.
+// Second pass over the values (Algorithm 1 lines 4-10).  No wave depends on another.  The elements of
+// a call are cut into chunks of R rows (a row = 256 elements, a float4 per lane); every WAVE owns one
+// chunk:
+//   the row maxima the first pass left behind tell which rows can hold a survivor at all (the
+//   early-stop test of Algorithm 1 line 5 applied to a whole row); only those rows are read, eight at
+//   a time -> per row, keep test |v| >= threshold as four wave-wide masks -> survivors are staged in
+//   the wave's slice of shared memory in element order (mask popcounts + mbcnt) -> once more than a
+//   few hundred wait there, densely over the staged survivors only: code by binary search in the
+//   boundary table, key fetch -> code byte and key appended to the CHUNK'S OWN SLOT of the scratch
+//   arrays (the chunk's first element index + rank in the chunk).  The loads of the next eight rows
+//   are issued before that flush, so its round trip overlaps with them.
 // The chunk's survivor count goes to ccount[chunk].  Global ranks are never materialised: the key
 // encoder scans the (at most 4096) chunk counts of a segment in shared memory and gathers through
 // that scan.
-// Lane `lane` holds, for row r = 0..7 of a tile, elements tile0 + r*256 + lane*4 + {0..3}.
+// Lane `lane` holds elements row*256 + lane*4 + {0..3} of each row in hand.
 constexpr u32 kStage = 1152;             // staged survivors per wave: four full rows on top of the flush level
 constexpr u32 kFlushLevel = kStage - 4 * kRow;
 constexpr u32 kValWaves = 4;             // waves per workgroup of the value encoder (they never synchronise)
@@ -327,15 +350,12 @@ __device__ __forceinline__ u32 lanes_below(u64 mask) {
 
 struct Chunk {           // wave-uniform description of the chunk a wave owns
     u32 seg, nrows;
+    u32 row0;            // index of the chunk's first row in the call's row numbering
     u64 e0;              // element index of the chunk's first slot
     u64 slot0;           // scratch entry of the chunk's first survivor
     u64 lo, hi;          // valid elements [lo, hi) of the segment
 };
 
-// Rows of a segment, counted from its first element rounded down to a multiple of 4.
-__device__ __forceinline__ u64 segment_rows(const SegInfo& s) {
-    return (s.elem_begin + s.elem_count - (s.elem_begin & ~3ull) + kRow - 1) / kRow;
-}
 // Scratch entry of the first slot of a segment's chunk j.  Segment s is shifted by 4*s entries so
 // that the rounding-down of its first element can never reach into its predecessor's entries.
 __device__ __forceinline__ u64 chunk_slot0(const SegInfo& s, u32 seg, u32 j, u32 R) {
@@ -349,6 +369,7 @@ __device__ __forceinline__ Chunk chunk_geom(const SegInfo* __restrict__ segs, u3
     const u32 j = chunk - s.chunk_begin;
     const u64 rows = segment_rows(s), r0 = (u64)j * R;
     c.nrows = (u32)(rows - r0 < R ? rows - r0 : R);
+    c.row0 = s.row_begin + (u32)r0;
     c.e0 = (s.elem_begin & ~3ull) + r0 * kRow;
     c.slot0 = chunk_slot0(s, c.seg, j, R);
     c.lo = s.elem_begin;
@@ -356,43 +377,11 @@ __device__ __forceinline__ Chunk chunk_geom(const SegInfo* __restrict__ segs, u3
     return c;
 }
 
-// Rows [0, rows) of the tile at element te.  `interior`: all of them lie inside the segment and are
-// fetched by coalesced float4 loads; otherwise (the first and last tile of a segment at most) every
-// element is fetched on its own and those outside [lo, hi) become zero, which never survives.
-__device__ __forceinline__ void load_rows(const float* __restrict__ values, u64 te, u32 rows, bool interior, u64 lo,
-                                          u64 hi, u32 lane, u32 (&bits)[kValRows][4]) {
-    if (interior) {
-        const uint4* src = reinterpret_cast<const uint4*>(values + te) + lane;
-        if (rows == kValRows) {
-#pragma unroll
-            for (u32 r = 0; r < kValRows; ++r) {
-                const uint4 q = src[r * 64u];
-                bits[r][0] = q.x; bits[r][1] = q.y; bits[r][2] = q.z; bits[r][3] = q.w;
-            }
-        } else {
-#pragma unroll
-            for (u32 r = 0; r < kValRows; ++r) {
-                uint4 q = make_uint4(0u, 0u, 0u, 0u);
-                if (r < rows) q = src[r * 64u];
-                bits[r][0] = q.x; bits[r][1] = q.y; bits[r][2] = q.z; bits[r][3] = q.w;
-            }
-        }
-    } else {
-#pragma unroll
-        for (u32 r = 0; r < kValRows; ++r)
-#pragma unroll
-            for (u32 c = 0; c < 4; ++c) {
-                const u64 e = te + r * 256u + lane * 4u + c;
-                bits[r][c] = (r < rows && e >= lo && e < hi) ? __float_as_uint(values[e]) : 0u;
-            }
-    }
-}
-
 __global__ void __launch_bounds__(kValWaves * kWave) __attribute__((amdgpu_waves_per_eu(4, 8)))
 k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                 const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
-                u32 n_chunks, u32 R, u32* __restrict__ ccount, u32* __restrict__ skeys,
-                uint8_t* __restrict__ scodes) {
+                u32 n_chunks, u32 R, const u32* __restrict__ rowmax, u32* __restrict__ ccount,
+                u32* __restrict__ skeys, uint8_t* __restrict__ scodes) {
     __shared__ u32 s_Ball[kValWaves][128];
     __shared__ u32 s_valall[kValWaves][kStage];
     __shared__ u32 s_idxall[kValWaves][kStage];
@@ -404,13 +393,14 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
     const u32 chunk = blockIdx.x * kValWaves + w;
     if (chunk >= n_chunks) return;
     const Chunk ck = chunk_geom(segs, n_segments, chunk, R);
-    const u32 thr = states[ck.seg].thr_bits;
+    const u32 thr = uniform(states[ck.seg].thr_bits);
     const u32 tau = segs[ck.seg].tau;
     s_B[lane] = states[ck.seg].B[lane];
     s_B[lane + 64] = states[ck.seg].B[lane + 64];
-    const u32 ntiles = (ck.nrows + kValRows - 1) / kValRows;
     const float thr_f = __uint_as_float(thr);
     const u32* ckeys = keys + ck.e0;
+    const float* cvals = values + ck.e0;
+    const u32* crmax = rowmax + ck.row0;
     u32 cbase = 0;                           // survivors of the chunk already in the scratch arrays
     u32 staged = 0;                          // survivors waiting in shared memory
 
@@ -448,14 +438,23 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
         staged = 0;
     };
 
-    auto tile_load = [&](u32 t, u32 (&b)[kValRows][4]) {
-        const u64 te = ck.e0 + (u64)t * kValTile;
-        const u32 rows = ck.nrows - t * kValRows < kValRows ? ck.nrows - t * kValRows : kValRows;
-        const bool interior = te >= ck.lo && te + (u64)rows * kRow <= ck.hi;
-        load_rows(values, te, rows, interior, ck.lo, ck.hi, lane, b);
+    // Row r of the chunk.  Rows cut by the segment's ends (its first and last row at most) are fetched
+    // element by element and the elements outside [lo, hi) become zero, which never survives.
+    auto load_row = [&](u32 r, u32 (&row)[4]) {
+        const u64 e = ck.e0 + (u64)r * kRow;
+        if (e >= ck.lo && e + kRow <= ck.hi) {
+            const uint4 q = reinterpret_cast<const uint4*>(cvals + (u64)r * kRow)[lane];
+            row[0] = q.x; row[1] = q.y; row[2] = q.z; row[3] = q.w;
+        } else {
+#pragma unroll
+            for (u32 c = 0; c < 4; ++c) {
+                const u64 ee = e + lane * 4u + c;
+                row[c] = (ee >= ck.lo && ee < ck.hi) ? __float_as_uint(values[ee]) : 0u;
+            }
+        }
     };
 
-    // one row of the tile at chunk offset toff: masks, and staging if anything survives
+    // one row: masks, and staging if anything survives
     auto stage_row = [&](const u32 (&row)[4], u32 off) {
         u64 m[4];
 #pragma unroll
@@ -472,19 +471,51 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
         staged += (u32)__popcll(m[0]) + (u32)__popcll(m[1]) + (u32)__popcll(m[2]) + (u32)__popcll(m[3]);
     };
 
-    u32 bits[kValRows][4];
-    tile_load(0, bits);
-    for (u32 t = 0; t < ntiles; ++t) {
-        const u32 toff = t * kValTile;      // offset of the tile inside the chunk
+    for (u32 g0 = 0; g0 < ck.nrows; g0 += 256u) {
+        // which of the next 256 rows can hold a survivor (unsigned compare of bit patterns: the same
+        // order as the float compare, and no row passes the keep-nothing threshold)
+        u64 mask[4];
 #pragma unroll
-        for (u32 r = 0; r < 4; ++r) stage_row(bits[r], toff + r * kRow);
-        if (staged > kFlushLevel) flush();                     // room for four more rows
+        for (u32 k = 0; k < 4; ++k) {
+            const u32 rr = g0 + k * 64u + lane;
+            const u32 x = crmax[rr < ck.nrows ? rr : ck.nrows - 1u];
+            mask[k] = __ballot(rr < ck.nrows && x >= thr);
+        }
+        // the next (up to) eight such rows, in ascending order
+        auto take = [&](u32 (&rows)[kValRows]) -> u32 {
+            u32 cnt = 0;
 #pragma unroll
-        for (u32 r = 4; r < 8; ++r) stage_row(bits[r], toff + r * kRow);
-        // the registers are free: start on the next tile before finishing this one
-        if (t + 1 < ntiles) tile_load(t + 1, bits);
-        if (staged > kFlushLevel || (t + 1 == ntiles && staged)) flush();
+            for (u32 slot = 0; slot < kValRows; ++slot) {
+                rows[slot] = 0;
+#pragma unroll
+                for (u32 k = 0; k < 4; ++k) {
+                    if (cnt == slot && mask[k]) {
+                        rows[slot] = g0 + k * 64u + (u32)__builtin_ctzll(mask[k]);
+                        mask[k] &= mask[k] - 1ull;
+                        cnt = slot + 1u;
+                    }
+                }
+            }
+            return cnt;
+        };
+        u32 bits[kValRows][4], rows[kValRows];
+        u32 nr = take(rows);
+#pragma unroll
+        for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_row(rows[slot], bits[slot]);
+        while (nr) {
+#pragma unroll
+            for (u32 slot = 0; slot < 4; ++slot) if (slot < nr) stage_row(bits[slot], rows[slot] * kRow);
+            if (staged > kFlushLevel) flush();                     // room for four more rows
+#pragma unroll
+            for (u32 slot = 4; slot < 8; ++slot) if (slot < nr) stage_row(bits[slot], rows[slot] * kRow);
+            // the registers are free: start on the next rows before finishing these
+            nr = take(rows);
+#pragma unroll
+            for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_row(rows[slot], bits[slot]);
+            if (staged > kFlushLevel) flush();
+        }
     }
+    if (staged) flush();
     if (lane == 0) ccount[chunk] = cbase;
 }
 
