@@ -9,6 +9,7 @@ resident in HBM.  Prints ONE JSON line (metric = input GB/s of the round trip, 8
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -17,6 +18,34 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bench_c4_hbm_traffic.md")
+
+
+def threshold_bits(total, base, tau):
+    """Bit pattern of the early-stop threshold sum / b^tau (Algorithm 1 line 2) the way the codec
+    evaluates it: the power by repeated float64 multiplication, the quotient rounded up to float32.
+    Only used to count, for the byte accounting, the rows the value pass has to read."""
+    import numpy as np
+    p = 1.0
+    for _ in range(tau):
+        p = p * base
+    t = total / p
+    f = np.float32(t)
+    if float(f) < t:
+        f = np.nextafter(f, np.float32(np.inf))
+    return int(np.array([f], np.float32).view(np.uint32)[0])
+
+
+def committed_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary, or None."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            m = re.match(r"\|\s*(\w+)\s*\|.*\|\s*([0-9.eE+]+)\s*\|\s*$", line)
+            if m and m.group(1) == kernel:
+                return float(m.group(2))
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -27,7 +56,10 @@ def main():
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 24, help="elements of the workload the oracle is timed on")
+    ap.add_argument("--cpu-sample", type=int, default=0, help="elements the oracle is timed on (0 = the whole workload)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run one plain device copy of the value array (a dispatch of known HBM traffic, "
+                         "the reference the rocprofv3 counter runs are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this codec is a single-GPU path (one worker's gradient); --gpus must be 1. "
@@ -59,6 +91,12 @@ def main():
     values = torch.from_numpy(w.values).cuda()
     plist = [B.params(b) for b in bases]
 
+    if args.calibrate:
+        ref_copy = torch.empty_like(values)
+        ref_copy.copy_(values)          # n*4 bytes read + n*4 bytes written
+        torch.cuda.synchronize()
+        del ref_copy
+
     # one output buffer per sweep point (sized from a first, untimed pass), shared workspace
     probe = B.Buffers(n, plist[0])
     points = []
@@ -70,8 +108,9 @@ def main():
         nbytes = int(probe.out_offsets[0])
         hdr = probe.out_bytes_view()[:64].cpu().numpy()
         d = int(hdr[40:48].view("<u8")[0])
+        total = float(hdr[24:32].view("<f8")[0])
         out = torch.empty(nbytes // 8 + 8, dtype=torch.int64, device="cuda")
-        points.append(dict(keep=keep, p=p, out=out, cap=nbytes, bytes=nbytes, d=d,
+        points.append(dict(keep=keep, p=p, out=out, cap=nbytes, bytes=nbytes, d=d, sum=total,
                            keys_out=torch.empty(max(d, 1), dtype=torch.int32, device="cuda"),
                            vals_out=torch.empty(max(d, 1), dtype=torch.float32, device="cuda")))
     ws, dws = probe.workspace, probe.dec_workspace
@@ -79,6 +118,17 @@ def main():
     count = torch.zeros(2, dtype=torch.int64, device="cuda")
     status = torch.zeros(2, dtype=torch.int32, device="cuda")
     del probe.out
+
+    # rows of 256 elements that hold at least one survivor: what the value pass has to read
+    rows = (n + 255) // 256
+    pad = rows * 256 - n
+    absbits = values.abs().view(torch.int32)
+    if pad:
+        absbits = torch.cat([absbits, torch.zeros(pad, dtype=torch.int32, device="cuda")])
+    rowmax = absbits.view(rows, 256).max(dim=1).values
+    for pt in points:
+        pt["rows_active"] = int((rowmax >= threshold_bits(pt["sum"], pt["p"].base, pt["p"].tau)).sum())
+    del absbits, rowmax
 
     def do_compress(pt):
         rc = B.compress(keys, values, pt["p"], pt["out"], obytes, status, ws, n=n, out_capacity=pt["cap"])
@@ -129,11 +179,12 @@ def main():
         rc, kd = B.profile_decompress(pt["out"], pt["bytes"], pt["keys_out"], pt["vals_out"], count, status, dws,
                                       args.steps, capacity=pt["d"])
         assert rc == B.OK
-        d, sb = pt["d"], pt["bytes"]
-        # algorithmic bytes per launch (what the method itself has to move)
+        d, sb, ra = pt["d"], pt["bytes"], pt["rows_active"]
+        # algorithmic bytes per launch: what each kernel's method has to move
         alg = {
-            "abs_sum": 4.0 * n,                                  # every value once
-            "encode_values": 4.0 * n + 4.0 * d + 5.0 * d,        # values; keys of survivors; key + code byte to scratch
+            "abs_sum": 4.0 * n + 4.0 * rows,                     # every value once; one maximum per row out
+            "encode_values": 4.0 * rows + 1024.0 * ra + 4.0 * d + 5.0 * d,   # row maxima; rows with a survivor;
+                                                                 # keys of survivors; key + code byte to scratch
             "measure_keys": 4.0 * d,                             # surviving keys
             "pack_keys": 5.0 * d + (sb - 64),                    # surviving keys and code bytes in, stream out
             "decode": sb + 8.0 * d,                              # stream in, (key, value) pairs out
@@ -144,7 +195,7 @@ def main():
             kern_bytes[k] = kern_bytes.get(k, 0.0) + v
         comp_alg = 8.0 * n + 18.0 * d + sb                       # two value passes + survivor traffic + stream
         detail.append(dict(keep=pt["keep"], base=pt["p"].base, d=d, stream_bytes=sb, ratio=8.0 * n / sb,
-                           bits_per_key=8.0 * (sb - 64 - d) / max(d, 1),
+                           bits_per_key=8.0 * (sb - 64 - d) / max(d, 1), rows_with_survivors=ra, rows=rows,
                            compress_ms=c_ms, decompress_ms=d_ms,
                            compress_input_GBps=8.0 * n / c_ms / 1e6, decompress_input_GBps=8.0 * n / d_ms / 1e6,
                            compress_elements_per_s=n / c_ms * 1e3,
@@ -159,16 +210,18 @@ def main():
     roofline = dict(bound="hbm", kernel="k_" + dominant,
                     achieved=kern_bytes[dominant] / kern_time[dominant] / 1e6, peak=HBM_PEAK_GBPS, unit="GB/s",
                     frac=kern_bytes[dominant] / kern_time[dominant] / 1e6 / HBM_PEAK_GBPS,
-                    traffic=None,
+                    traffic=committed_traffic("k_" + dominant),
+                    traffic_source="profiles/bench_c4_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
+                                   "separate runs of this command, scaled by a plain copy; bytes per launch)",
                     avg_launch_ms=kern_time[dominant] / launches,
                     algorithmic_bytes_per_launch=kern_bytes[dominant] / launches)
 
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import ref
-        m = min(args.cpu_sample, n)
+        m = n if args.cpu_sample <= 0 else min(args.cpu_sample, n)
         sk, sv = w.keys[:m], w.values[:m]
-        sbases = W.solve_bases(sv, keeps)
+        sbases = bases if m == n else W.solve_bases(sv, keeps)
         t0 = time.perf_counter()
         for b in sbases:
             rc, st = ref.compress(sk, sv, ref.params(b))
@@ -177,16 +230,17 @@ def main():
             assert rc == ref.OK
         cpu_s = time.perf_counter() - t0
         cpu = dict(value=8.0 * m * len(sbases) / cpu_s / 1e9, unit="GB/s", cores=1, kind="oracle",
-                   sample=f"first {m} elements of {w.name}, all {len(sbases)} keep fractions, compress+decompress, "
-                          f"{cpu_s:.1f} s on one host core")
+                   sample=f"{'all' if m == n else 'first'} {m} elements of {w.name}, all {len(sbases)} keep "
+                          f"fractions, compress+decompress once, {cpu_s:.1f} s on one host core")
 
     line = {
         "metric": "compress & decompress input GB/s (% of HBM peak) on 1 MI355X; compression ratio",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 values, u32 keys; integer compares on IEEE bit patterns, f64 table", "data": "synthetic",
+        "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "n": n, "keep_fractions": keeps, "tau": 128, "flag_bits": 2,
-                   "block_keys": 1024, "step": "compress+decompress at every keep fraction"},
+                   "block_keys": 1024, "step": "compress+decompress at every keep fraction",
+                   "arithmetic": "f32 values and u32 keys compared as IEEE bit patterns; f64 boundary table"},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "detail": detail,
     }
     print(json.dumps(line))

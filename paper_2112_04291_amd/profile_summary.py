@@ -1,0 +1,92 @@
+"""Turns rocprofv3 CSV output of `bench.py` runs into the short summaries kept under profiles/.
+
+    python3 -m paper_2112_04291_amd.profile_summary trace   <dir> <out.md> "<command>"
+    python3 -m paper_2112_04291_amd.profile_summary traffic <fetch dir> <write dir> <out.md> <n_values> "<command>"
+
+`trace`   : <dir> holds the output of `rocprofv3 --kernel-trace --stats --output-format csv`.
+`traffic` : the two directories hold `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of
+            `bench.py --calibrate`, whose first large dispatch is a plain device copy of the value
+            array (n_values * 4 bytes read and as many written).  Both counters report KiB per
+            dispatch; each is scaled by (known KiB of the copy) / (what the counter read for it).
+"""
+import collections
+import csv
+import glob
+import sys
+
+
+def _rows(d, suffix):
+    files = glob.glob(d + "/**/*" + suffix, recursive=True)
+    if not files:
+        raise SystemExit(f"no *{suffix} under {d}")
+    return list(csv.DictReader(open(files[0])))
+
+
+def _short(name):
+    name = name.split("(")[0].replace("void ", "").replace("fsgd::", "")
+    return name.split("<")[0] if name.startswith("k_") else name[:60]
+
+
+def trace(d, out, command):
+    rows = _rows(d, "kernel_trace.csv")
+    st = collections.defaultdict(list)
+    meta = {}
+    for r in rows:
+        k = _short(r["Kernel_Name"])
+        st[k].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+        meta[k] = (r.get("VGPR_Count", ""), r.get("LDS_Block_Size", ""), r.get("Grid_Size_X", r.get("Grid_Size", "")),
+                   r.get("Workgroup_Size_X", r.get("Workgroup_Size", "")))
+    tot = sum(sum(v) for v in st.values())
+    with open(out, "w") as f:
+        f.write(f"# rocprofv3 kernel trace of the benchmark (config 4, 124M elements, four keep fractions)\n\n")
+        f.write(f"Command: `{command}`\n\n")
+        f.write("Durations in microseconds, begin to end of each dispatch.\n\n")
+        f.write("| kernel | calls | avg us | min us | max us | % of GPU time | VGPRs | LDS bytes | grid | workgroup |\n")
+        f.write("|---|---|---|---|---|---|---|---|---|---|\n")
+        for k, v in sorted(st.items(), key=lambda kv: -sum(kv[1])):
+            m = meta[k]
+            f.write(f"| {k} | {len(v)} | {sum(v) / len(v) / 1e3:.1f} | {min(v) / 1e3:.1f} | {max(v) / 1e3:.1f} | "
+                    f"{100.0 * sum(v) / tot:.1f} | {m[0]} | {m[1]} | {m[2]} | {m[3]} |\n")
+
+
+def _counter(d, name):
+    per = collections.defaultdict(list)
+    for r in _rows(d, "counter_collection.csv"):
+        if r["Counter_Name"] == name:
+            per[_short(r["Kernel_Name"])].append(float(r["Counter_Value"]))
+    return per
+
+
+def traffic(dfetch, dwrite, out, n_values, command):
+    known_kib = n_values * 4.0 / 1024.0
+    fetch, write = _counter(dfetch, "FETCH_SIZE"), _counter(dwrite, "WRITE_SIZE")
+
+    def calib(per):
+        best = max(((max(v), k) for k, v in per.items() if not k.startswith("k_")), default=(0.0, ""))
+        return known_kib / best[0] if best[0] > 0 else float("nan"), best
+    ff, fb = calib(fetch)
+    wf, wb = calib(write)
+    with open(out, "w") as f:
+        f.write("# HBM traffic per launch of the benchmark's kernels (config 4, four keep fractions)\n\n")
+        f.write(f"Commands: `{command.replace('COUNTER', 'FETCH_SIZE')}` and the same with `WRITE_SIZE`.\n\n")
+        f.write(f"Calibration: the plain device copy of the value array ({n_values} x 4 bytes = {known_kib:.0f} KiB "
+                f"each way) read FETCH_SIZE = {fb[0]:.0f} and WRITE_SIZE = {wb[0]:.0f} (dispatch `{fb[1]}`), so "
+                f"the counters are scaled by {ff:.4f} and {wf:.4f}.  Averages over all launches of a kernel in "
+                f"the run (all four keep fractions); the last column is the scaled fetch + write in bytes.\n\n")
+        f.write("| kernel | launches | FETCH_SIZE KiB avg | WRITE_SIZE KiB avg | HBM bytes per launch |\n")
+        f.write("|---|---|---|---|---|\n")
+        for k in sorted(set(fetch) | set(write)):
+            if not k.startswith("k_"):
+                continue
+            fv, wv = fetch.get(k, [0.0]), write.get(k, [0.0])
+            fa, wa = sum(fv) / len(fv), sum(wv) / len(wv)
+            f.write(f"| {k} | {len(fv)} | {fa:.1f} | {wa:.1f} | {(fa * ff + wa * wf) * 1024.0:.4e} |\n")
+
+
+if __name__ == "__main__":
+    if len(sys.argv) >= 5 and sys.argv[1] == "trace":
+        trace(sys.argv[2], sys.argv[3], sys.argv[4])
+    elif len(sys.argv) >= 7 and sys.argv[1] == "traffic":
+        traffic(sys.argv[2], sys.argv[3], sys.argv[4], int(sys.argv[5]), sys.argv[6])
+    else:
+        raise SystemExit(__doc__)
