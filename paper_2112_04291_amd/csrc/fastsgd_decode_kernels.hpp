@@ -128,19 +128,157 @@ __device__ __forceinline__ u32 find_dec_segment(const DecSeg* segs, u32 n_segmen
     return lo;
 }
 
-// One key block per WAVE, 1024 keys at a time; lane `lane` holds, for row q = 0..15, key 64*q + lane.
-// Per round the wave fetches the round's flag words, the payload words the round can reach (its start
-// is known from the rounds before, its end is bounded by M bits per key) and the code bytes in one
-// go, parks flags and payload in its slice of shared memory, and then per row: flag -> level ->
-// length, a scan of the lengths -> bit offsets, a 64-bit window at that offset -> delta, a scan of the
-// deltas on top of the key before the row -> keys (phase 2), code byte -> magnitude table -> value
-// (phases 3-4).  The waves of a workgroup never synchronise.
+// One key block per WAVE, 1024 keys at a time, each lane owning 16 CONSECUTIVE keys of the round, so
+// that the running sums inside a lane are plain additions and only one scan across the wave is needed
+// for the lengths and one for the deltas:
+//   the round's flag words, the payload words it can reach (its start is known from the rounds before,
+//   its end is bounded by M bits per key) and the lane's 16 code bytes are fetched in one go; flags and
+//   payload are parked in the wave's slice of shared memory -> per key: flag -> level -> length;
+//   lengths summed up inside the lane, scanned across the wave -> bit offsets; a 64-bit window at that
+//   offset -> delta; deltas summed up inside the lane, scanned across the wave on top of the key before
+//   the round -> keys (phase 2); code byte -> magnitude table -> value (phases 3-4).  Keys and values
+//   go through shared memory once more so that the stores to the output arrays are coalesced.
+// The waves of a workgroup never synchronise.
+constexpr u32 kLaneKeys = kSub / 64;     // 16 consecutive keys per lane and round
+
+// FULL: the round has all 1024 keys (no key-index tests).  Returns false if the stream is corrupt.
+template <bool FULL>
+__device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round, const u32* __restrict__ psrc,
+                                             u32 pw_total, const uint8_t* __restrict__ codes_round, u32 n, u32 l,
+                                             u32 M, u32 tau, u32 pbits, u32& pbit, u32& carry, u32 lane, u32* s_pay,
+                                             u32* s_flg, const u32* s_V, u32* __restrict__ keys_dst,
+                                             float* __restrict__ values_dst) {
+    const u32 nfw = (n * l + 31u) >> 5;
+    const u32 pw0 = pbit >> 5, wbits = pbit & 31u;
+    u32 npw = ((wbits + n * M + 31u) >> 5) + 1u;           // words this round can reach (+1: windows)
+    if (npw > kSub + 2) npw = kSub + 2;
+    // all fetches of the round first
+    u32 fw[3], pwd[17];
+#pragma unroll
+    for (u32 k = 0; k < 3; ++k) { const u32 i = k * 64u + lane; fw[k] = fsrc_round[i < nfw ? i : 0u]; }
+#pragma unroll
+    for (u32 k = 0; k < 17; ++k) {
+        const u32 i = k * 64u + lane;
+        pwd[k] = (k * 64u < npw && pw_total) ? psrc[(pw0 + i < pw_total) ? pw0 + i : pw_total - 1u] : 0u;
+    }
+    u32 cw[4];                                             // the lane's 16 code bytes
+    if (FULL) {
+        const uint2* c2 = reinterpret_cast<const uint2*>(codes_round) + 2u * lane;   // 8-byte aligned
+        const uint2 a = c2[0], b = c2[1];
+        cw[0] = a.x; cw[1] = a.y; cw[2] = b.x; cw[3] = b.y;
+    } else {
+#pragma unroll
+        for (u32 j = 0; j < 4; ++j) {
+            u32 x = 0;
+#pragma unroll
+            for (u32 bb = 0; bb < 4; ++bb) {
+                const u32 i = lane * kLaneKeys + j * 4u + bb;
+                if (i < n) x |= (u32)codes_round[i] << (8u * bb);
+            }
+            cw[j] = x;
+        }
+    }
+#pragma unroll
+    for (u32 k = 0; k < 3; ++k) { const u32 i = k * 64u + lane; if (i < nfw + 3u) s_flg[i] = (i < nfw) ? fw[k] : 0u; }
+#pragma unroll
+    for (u32 k = 0; k < 17; ++k) {
+        const u32 i = k * 64u + lane;
+        if (k * 64u < npw && i < npw) s_pay[i] = (pw0 + i < pw_total) ? pwd[k] : 0u;
+    }
+    wave_lds_sync();
+
+    // flags -> lengths: 8 flags at a time out of a 64-bit window of the lane's flag bits
+    const u32 lmask = (1u << l) - 1u, lenc = M + lmask;     // length = (flag * M + M + 2^l - 1) >> l
+    u32 len[kLaneKeys];
+#pragma unroll
+    for (u32 half = 0; half < 2; ++half) {
+        const u32 fb = (lane * kLaneKeys + half * 8u) * l, wi = fb >> 5;
+        const u32 w0 = s_flg[wi], w1 = s_flg[wi + 1], w2 = s_flg[wi + 2];
+        u64 fwin = (u64)__builtin_amdgcn_alignbit(w1, w0, fb & 31u) |
+                   ((u64)__builtin_amdgcn_alignbit(w2, w1, fb & 31u) << 32);
+#pragma unroll
+        for (u32 k = 0; k < 8; ++k) {
+            const u32 flag = (u32)fwin & lmask;
+            fwin >>= l;
+            u32 ln = (flag * M + lenc) >> l;
+            if (!FULL && lane * kLaneKeys + half * 8u + k >= n) ln = 0;
+            len[half * 8u + k] = ln;
+        }
+    }
+    u32 lanebits = 0;
+#pragma unroll
+    for (u32 k = 0; k < kLaneKeys; ++k) lanebits += len[k];
+    const u32 incl = wave_incl_scan(lanebits);
+    const u32 roundbits = read_lane(incl, 63);
+    if (pbit + roundbits > pbits) return false;             // the lengths overrun the payload plane
+    // deltas and their running sum inside the lane
+    u32 bp = wbits + incl - lanebits;
+    u32 kp[kLaneKeys];
+    u32 acc = 0;
+    bool ovf = false;
+#pragma unroll
+    for (u32 k = 0; k < kLaneKeys; ++k) {
+        const u32 wa = bp >> 5;
+        const u32 x = __builtin_amdgcn_alignbit(s_pay[wa + 1], s_pay[wa], bp & 31u);
+        u32 dl = x & (0xFFFFFFFFu >> ((32u - len[k]) & 31u));
+        if (!FULL && len[k] == 0) dl = 0;                   // (a real key has a length of at least 1)
+        bp += len[k];
+        const u32 nx = acc + dl;
+        ovf |= nx < acc;
+        acc = nx;
+        kp[k] = acc;
+    }
+    const u64 incl64 = wave_incl_scan64((u64)acc);
+    const u64 kbase = (u64)carry + incl64 - acc;            // key before the lane's first key
+    ovf |= (kbase >> 32) != 0 && (FULL || lane * kLaneKeys < n);
+#pragma unroll
+    for (u32 k = 0; k < kLaneKeys; ++k) {
+        const u32 key = (u32)kbase + kp[k];
+        ovf |= key < (u32)kbase && (FULL || lane * kLaneKeys + k < n);
+        kp[k] = key;
+    }
+    // values: code byte -> magnitude, sign on top
+    bool badcode = false;
+    u32 vb[kLaneKeys];
+#pragma unroll
+    for (u32 k = 0; k < kLaneKeys; ++k) {
+        const u32 byte = (cw[k >> 2] >> (8u * (k & 3u))) & 0xFFu;
+        const u32 c = byte & 0x7Fu;                         // code - 1
+        badcode |= c >= tau && (FULL || lane * kLaneKeys + k < n);
+        vb[k] = s_V[c] | ((byte >> 7) << 31);
+    }
+    // through shared memory to the output arrays: lane-major in, row-major out
+    wave_lds_sync();
+    uint4* t4 = reinterpret_cast<uint4*>(s_pay) + lane * 4u;
+#pragma unroll
+    for (u32 j = 0; j < 4; ++j) t4[j] = make_uint4(kp[4 * j], kp[4 * j + 1], kp[4 * j + 2], kp[4 * j + 3]);
+    wave_lds_sync();
+#pragma unroll
+    for (u32 q = 0; q < kLaneKeys; ++q) {
+        const u32 i = q * 64u + lane;
+        if (FULL || i < n) keys_dst[i] = s_pay[i];
+    }
+    carry = s_pay[n - 1];                                    // last key of the round (same in all lanes)
+    wave_lds_sync();
+#pragma unroll
+    for (u32 j = 0; j < 4; ++j) t4[j] = make_uint4(vb[4 * j], vb[4 * j + 1], vb[4 * j + 2], vb[4 * j + 3]);
+    wave_lds_sync();
+#pragma unroll
+    for (u32 q = 0; q < kLaneKeys; ++q) {
+        const u32 i = q * 64u + lane;
+        if (FULL || i < n) values_dst[i] = __uint_as_float(s_pay[i]);
+    }
+    wave_lds_sync();
+    pbit += roundbits;
+    return !(__any(ovf) || __any(badcode));
+}
+
 __global__ void __launch_bounds__(kThreads)
 k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u32 n_segments, DecCtrl* ctrl,
          u32* __restrict__ keys_out, float* __restrict__ values_out, u64* out_counts, u32 n_counts,
          u32* out_status) {
-    __shared__ u32 s_payall[kWaves][kSub + 2];
-    __shared__ u32 s_flgall[kWaves][kSub * 5 / 32 + 2];
+    __shared__ __attribute__((aligned(16))) u32 s_payall[kWaves][kSub + 4];
+    __shared__ u32 s_flgall[kWaves][kSub * 5 / 32 + 4];
     __shared__ u32 s_Vall[kWaves][128];
     const u32 lane = lane_id(), w = uniform(wave_id());
     u32* s_pay = s_payall[w];
@@ -177,81 +315,26 @@ k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u
         bool bad = (M < 1 || M > 32) || (pbits > cnt * 32u) || ((u64)off8 + fwords + pwords != next_off8) ||
                    ((u64)off8 + fwords + pwords > total_words) || (blk == 0 && (off8 != 0 || preKey != 0));
         if (!bad) {
-            const u32* fsrc = reinterpret_cast<const u32*>(streams + ds->blocks_off + 8ull * off8);   // flags plane
-            const u32* psrc = fsrc + 2u * fwords;                                                    // payload plane
+            const u32* fsrc = reinterpret_cast<const u32*>(streams + uniform64(ds->blocks_off + 8ull * off8));   // flags plane
+            const u32* psrc = fsrc + 2u * fwords;                                                              // payload plane
             const u32 pw_total = 2u * pwords;
-            const uint8_t* codes = streams + ds->stream_begin + kHeaderBytes + first;
-            const u64 out0 = ds->pair_begin + first;
+            const uint8_t* codes = streams + uniform64(ds->stream_begin + kHeaderBytes + first);
+            const u64 out0 = uniform64(ds->pair_begin + first);
             u32 pbit = 0;                  // payload bits consumed by the rounds before
-            u32 carry = preKey;            // key before the row in hand
-            bool wrapped = false, badcode = false;
-            for (u32 sub = 0; sub < nsub; ++sub) {
+            u32 carry = preKey;            // key before the round in hand
+            bool ok = true;
+            for (u32 sub = 0; sub < nsub && ok; ++sub) {
                 const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
-                const u32 nfw = (n * l + 31u) >> 5, f0 = sub * 32u * l;
-                const u32 pw0 = pbit >> 5, wbits = pbit & 31u;
-                u32 npw = ((wbits + n * M + 31u) >> 5) + 1u;           // words this round can reach (+1: windows)
-                if (npw > kSub + 2) npw = kSub + 2;
-                // all fetches of the round first
-                u32 fw[3], pwd[17], code[kKeyRows];
-#pragma unroll
-                for (u32 k = 0; k < 3; ++k) { const u32 i = k * 64u + lane; fw[k] = fsrc[f0 + (i < nfw ? i : 0u)]; }
-#pragma unroll
-                for (u32 k = 0; k < 17; ++k) {
-                    const u32 i = k * 64u + lane;
-                    pwd[k] = (k * 64u < npw && pw_total) ? psrc[(pw0 + i < pw_total) ? pw0 + i : pw_total - 1u] : 0u;
-                }
-#pragma unroll
-                for (u32 q = 0; q < kKeyRows; ++q) code[q] = (q * 64u + lane < n) ? codes[sub * kSub + q * 64u + lane] : 0u;
-#pragma unroll
-                for (u32 k = 0; k < 3; ++k) { const u32 i = k * 64u + lane; if (i < nfw + 1u) s_flg[i] = (i < nfw) ? fw[k] : 0u; }
-#pragma unroll
-                for (u32 k = 0; k < 17; ++k) {
-                    const u32 i = k * 64u + lane;
-                    if (k * 64u < npw && i < npw) s_pay[i] = (pw0 + i < pw_total) ? pwd[k] : 0u;
-                }
-                wave_lds_sync();
-                u32 rowbase = wbits;
-#pragma unroll
-                for (u32 q = 0; q < kKeyRows; ++q) {
-                    const u32 i = q * 64u + lane;
-                    if (q * 64u < n) {
-                        u32 len = 0;
-                        if (i < n) {
-                            const u32 fpos = i * l;
-                            const u64 win = (u64)s_flg[fpos >> 5] | ((u64)s_flg[(fpos >> 5) + 1] << 32);
-                            const u32 level = ((u32)(win >> (fpos & 31u)) & ((1u << l) - 1u)) + 1u;
-                            len = level_len(level, M, l);
-                        }
-                        const u32 incl = wave_incl_scan(len);
-                        u32 delta = 0;
-                        if (i < n) {
-                            const u32 bitpos = rowbase + incl - len;
-                            const u64 win = (u64)s_pay[bitpos >> 5] | ((u64)s_pay[(bitpos >> 5) + 1] << 32);
-                            const u32 mask = len >= 32u ? 0xFFFFFFFFu : ((1u << len) - 1u);
-                            delta = (u32)(win >> (bitpos & 31u)) & mask;
-                        }
-                        rowbase += read_lane(incl, 63);
-                        const u32 key = carry + wave_incl_scan(delta);          // modulo 2^32 ...
-                        const u32 prev = lane_above(key, carry);
-                        if (i < n) {
-                            wrapped |= key < prev;                              // ... so a wrap shows as a step down
-                            const u32 byte = code[q];
-                            const u32 c = (byte & 0x7Fu) + 1u;
-                            if (c > tau) badcode = true;
-                            else {
-                                keys_out[out0 + sub * kSub + i] = key;
-                                values_out[out0 + sub * kSub + i] = __uint_as_float(s_V[c - 1] | ((byte >> 7) << 31));
-                            }
-                        }
-                        const u32 last_lane = (n - q * 64u) < 64u ? (n - q * 64u - 1u) : 63u;
-                        carry = read_lane(key, uniform(last_lane));
-                    }
-                }
-                pbit = rowbase - wbits + pbit;
-                if (pbit > pbits) { bad = true; break; }        // the lengths overrun the payload plane
-                wave_lds_sync();
+                if (n == kSub)
+                    ok = decode_round<true>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * kSub, n, l, M, tau, pbits,
+                                            pbit, carry, lane, s_pay, s_flg, s_V, keys_out + out0 + sub * kSub,
+                                            values_out + out0 + sub * kSub);
+                else
+                    ok = decode_round<false>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * kSub, n, l, M, tau, pbits,
+                                             pbit, carry, lane, s_pay, s_flg, s_V, keys_out + out0 + sub * kSub,
+                                             values_out + out0 + sub * kSub);
             }
-            bad = bad || (pbit != pbits) || __any(wrapped) || __any(badcode) || (has_next && carry != next_pre);
+            bad = !ok || (pbit != pbits) || (has_next && carry != next_pre);
         }
         if (bad && lane == 0) dec_fail(ctrl, FASTSGD_ERR_CORRUPT_STREAM, out_status, out_counts, n_counts);
     }
