@@ -139,7 +139,6 @@ __device__ __forceinline__ u32 find_dec_segment(const DecSeg* segs, u32 n_segmen
 //   the round -> keys (phase 2); code byte -> magnitude table -> value (phases 3-4).  Keys and values
 //   go through shared memory once more so that the stores to the output arrays are coalesced.
 // The waves of a workgroup never synchronise.
-constexpr u32 kLaneKeys = kSub / 64;     // 16 consecutive keys per lane and round
 
 // FULL: the round has all 1024 keys (no key-index tests).  Returns false if the stream is corrupt.
 template <bool FULL>

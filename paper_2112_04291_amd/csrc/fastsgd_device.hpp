@@ -28,6 +28,7 @@ constexpr u32 kChunkTarget = 4096;            // chunks a call's elements are cu
 constexpr u32 kMaxSegChunks = kChunkTarget;   // no segment has more chunks than this
 constexpr u32 kMaxGroups = 2048;              // groups of key blocks whose sizes are added up by atomics
 constexpr u32 kSub = 1024;                    // keys of a key block a wave handles at a time (16 rows of 64)
+constexpr u32 kLaneKeys = kSub / 64;          // ... 16 consecutive keys per lane
 
 // Host-built description of one gradient (segment) of a call.
 struct SegInfo {

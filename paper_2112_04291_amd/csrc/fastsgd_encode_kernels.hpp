@@ -769,18 +769,57 @@ __device__ __forceinline__ void find_entries(const u32* P, u32 stride, u32 jlo, 
     wave_lds_sync();
 }
 
-// Delta of row k's keys: `carry` is the key before the row on entry and the row's last key on return.
-__device__ __forceinline__ u32 row_delta(u32 key, u32 r0, u32 k, u32 n, u32 lane, u32& carry, bool& unsorted) {
-    const u32 i = k * 64u + lane;
-    const u32 prev = lane_above(key, carry);
-    u32 dl = 0;
-    if (i < n) {
-        dl = key - prev;
-        unsorted |= (key < prev) || (key == prev && (r0 + i) != 0);
+// Keys r0 .. r0 + n - 1 of a segment (n <= 1024), fetched row-wise (row q, lane: key 64*q + lane, so the
+// fetches are coalesced wherever the ranks are contiguous in the scratch array) and handed to the lanes
+// 16 CONSECUTIVE keys each through `buf` (1024 words of the wave's shared memory, 16-byte aligned,
+// clobbered): kb[k] = key 16*lane + k (0 beyond n).  ent[q] keeps the scratch entry of key 64*q + lane.
+__device__ __forceinline__ void gather_blocked(const u32* P, u32 nch, u32 stride, const u32* __restrict__ seg_keys,
+                                               u32 r0, u32 n, u32 lane, u32* buf, u32 (&ent)[kKeyRows],
+                                               u32 (&kb)[kLaneKeys]) {
+    const u32 jlo = uniform(find_chunk_wave(P, nch, r0, lane));
+    const u32 jhi = uniform(find_chunk_wave(P, nch, r0 + n - 1, lane));
+    find_entries(P, stride, jlo, jhi, r0, n, lane, buf, ent);
+    u32 key[kKeyRows];
+#pragma unroll
+    for (u32 q = 0; q < kKeyRows; ++q) key[q] = (q * 64u + lane < n) ? seg_keys[ent[q]] : 0u;
+#pragma unroll
+    for (u32 q = 0; q < kKeyRows; ++q) buf[q * 64u + lane] = key[q];
+    wave_lds_sync();
+    const uint4* b4 = reinterpret_cast<const uint4*>(buf) + lane * 4u;
+#pragma unroll
+    for (u32 j = 0; j < 4; ++j) {
+        const uint4 x = b4[j];
+        kb[4 * j] = x.x; kb[4 * j + 1] = x.y; kb[4 * j + 2] = x.z; kb[4 * j + 3] = x.w;
     }
-    const u32 last_lane = (n - k * 64u) < 64u ? (n - k * 64u - 1u) : 63u;   // the row's last valid key
-    carry = read_lane(key, uniform(last_lane));
-    return dl;
+    wave_lds_sync();
+}
+
+// Deltas of the lane's 16 keys (Eq. 4): dl[k] = kb[k] - key before it; `carry` is the key before the
+// round on entry and the round's last key on return.  Keys that do not increase set bits in `unsorted`
+// (the very first key of a segment may be 0, i.e. equal to its imaginary predecessor).
+template <bool FULL>
+__device__ __forceinline__ void lane_deltas(const u32 (&kb)[kLaneKeys], u32 r0, u32 n, u32 lane, u32& carry,
+                                            u32 (&dl)[kLaneKeys], u64& unsorted) {
+    // last valid key of the lane: for lanes that end beyond n, the round's last key
+    const u32 nl = FULL ? kLaneKeys : (lane * kLaneKeys >= n ? 0u : (n - lane * kLaneKeys < kLaneKeys ? n - lane * kLaneKeys : kLaneKeys));
+    u32 lastkey = kb[kLaneKeys - 1];
+    if (!FULL) {
+        lastkey = 0;
+#pragma unroll
+        for (u32 k = 0; k < kLaneKeys; ++k) if (k < nl) lastkey = kb[k];
+    }
+    u32 prev = lane_above(lastkey, carry);
+#pragma unroll
+    for (u32 k = 0; k < kLaneKeys; ++k) {
+        const bool valid = FULL || k < nl;
+        dl[k] = valid ? kb[k] - prev : 0u;
+        u64 m = __ballot(valid && kb[k] <= prev);
+        if (k == 0 && r0 == 0) m &= ~1ull;                    // rank 0 of the segment
+        unsorted |= m;
+        if (valid) prev = kb[k];
+    }
+    const u32 last_lane = (n - 1u) / kLaneKeys;
+    carry = read_lane(lastkey, uniform(last_lane));
 }
 
 __global__ void __launch_bounds__(kThreads)
@@ -789,11 +828,11 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
                unsigned long long* __restrict__ gsum, u32 g_shift, Ctrl* ctrl) {
     __shared__ u32 s_P[kMaxSegChunks + 1];
     __shared__ u32 s_scan[kWaves + 1];
-    __shared__ u32 s_markall[kWaves][kSub];
-    __shared__ uint8_t s_needall[kWaves][kMaxKB];     // significant bits of every delta of the wave's block
+    __shared__ __attribute__((aligned(16))) u32 s_bufall[kWaves][kSub];
+    __shared__ __attribute__((aligned(16))) uint8_t s_needall[kWaves][kMaxKB];   // significant bits of every delta of the block
     const u32 lane = lane_id(), w = uniform(wave_id());
     uint8_t* s_need = s_needall[w];
-    u32* s_mark = s_markall[w];
+    u32* s_buf = s_bufall[w];
     // a single gradient: its survivor count is the total of the scan of its chunk counts
     u64 total_units, single_d = 0;
     u32 cur_seg = 0xFFFFFFFFu;
@@ -831,36 +870,39 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
         const u32 nsub = (cnt + kSub - 1) / kSub;
         const u32 stride = R * kRow;
         const u32* seg_keys = skeys + chunk_slot0(info, ku.seg, 0, R);
-        // chunk of the key before the block (its own first key for the segment's first block)
-        u32 jnext = uniform(find_chunk_wave(s_P, ku.nch, first ? first - 1 : 0u, lane));
+        // the key before the block (none for the segment's first block)
         u32 preKey = 0;
-        if (first) preKey = seg_keys[jnext * stride + (first - 1 - s_P[jnext])];
+        if (first) {
+            const u32 jp = uniform(find_chunk_wave(s_P, ku.nch, first - 1, lane));
+            preKey = seg_keys[jp * stride + (first - 1 - s_P[jp])];
+        }
         // first loop of Algorithm 2: deltas and the longest of them (M = bit length of maxDelta)
-        bool unsorted = false;
+        u64 unsorted = 0;
         u32 carry = 0, mxneed = 0;
         for (u32 sub = 0; sub < nsub; ++sub) {
             const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
             const u32 r0 = first + sub * kSub;
-            const u32 jlo = uniform(find_chunk_wave(s_P, ku.nch, r0, lane));
-            const u32 jhi = uniform(find_chunk_wave(s_P, ku.nch, r0 + n - 1, lane));
-            u32 ent[kKeyRows], key[kKeyRows];
-            find_entries(s_P, stride, jlo, jhi, r0, n, lane, s_mark, ent);
+            u32 ent[kKeyRows], kb[kLaneKeys], dl[kLaneKeys];
+            gather_blocked(s_P, ku.nch, stride, seg_keys, r0, n, lane, s_buf, ent, kb);
+            if (sub == 0) carry = uniform(preKey);              // (its fetch was in flight until here)
+            if (n == kSub) lane_deltas<true>(kb, r0, n, lane, carry, dl, unsorted);
+            else lane_deltas<false>(kb, r0, n, lane, carry, dl, unsorted);
+            u32 packed[4];
 #pragma unroll
-            for (u32 q = 0; q < kKeyRows; ++q) key[q] = (q * 64u + lane < n) ? seg_keys[ent[q]] : 0u;
-            if (sub == 0) carry = preKey;                   // (its fetch was in flight until here)
+            for (u32 j = 0; j < 4; ++j) {
+                u32 x = 0;
 #pragma unroll
-            for (u32 q = 0; q < kKeyRows; ++q) {
-                if (q * 64u < n) {
-                    const u32 dl = row_delta(key[q], r0, q, n, lane, carry, unsorted);
-                    const u32 need = 32u - __clz(dl);      // __clz(0) = 32
-                    const u32 i = q * 64u + lane;
-                    if (i < n) s_need[sub * kSub + i] = (uint8_t)need;
+                for (u32 bb = 0; bb < 4; ++bb) {
+                    const u32 need = 32u - __clz(dl[4 * j + bb]);      // __clz(0) = 32
                     mxneed = need > mxneed ? need : mxneed;
+                    x |= need << (8u * bb);
                 }
+                packed[j] = x;
             }
+            reinterpret_cast<uint4*>(s_need + sub * kSub)[lane] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
         }
         mxneed = wave_max(mxneed);
-        if (__any(unsorted) && lane == 0) set_status(ctrl, FASTSGD_ERR_UNSORTED_KEYS);
+        if (unsorted && lane == 0) set_status(ctrl, FASTSGD_ERR_UNSORTED_KEYS);
         const u32 M = mxneed ? mxneed : 1u;
         // payload bits: every key takes the length of the smallest level that holds its delta
         const u32 magic = level_magic(M), l = ku.l;
@@ -900,11 +942,13 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
     __shared__ u64 s_G[kMaxGroups + 1];
     __shared__ u64 s_scan64[kWaves + 1];
     __shared__ u32 s_scan[kWaves + 1];
-    __shared__ u32 s_payall[kWaves][kSub + 2];
+    __shared__ __attribute__((aligned(16))) u32 s_payall[kWaves][kSub + 4];
     __shared__ u32 s_flgall[kWaves][kSub * 5 / 32 + 2];
+    __shared__ u32 s_lutall[kWaves][33];
     const u32 t = threadIdx.x, lane = lane_id(), w = uniform(wave_id());
     u32* s_pay = s_payall[w];
     u32* s_flg = s_flgall[w];
+    u32* s_lut = s_lutall[w];
     u64 total_units, total_items, single_d = 0;
     u32 cur_seg = 0xFFFFFFFFu;
     if (n_segments == 1) {
@@ -991,58 +1035,69 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
         u32* pdst = fdst + 2u * fwords;                                // payload plane
         uint8_t* vdst = out + sbeg + kHeaderBytes + first;             // the block's part of the value plane
 
-        // second loop of Algorithm 2, 1024 keys at a time
+        // second loop of Algorithm 2, 1024 keys at a time, 16 consecutive keys per lane
         const u32 stride = R * kRow;
         const u64 seg_slot0 = chunk_slot0(info, ku.seg, 0, R);
         const u32* seg_keys = skeys + seg_slot0;
         const uint8_t* seg_codes = scodes + seg_slot0;
+        // level and length by significant bits of the delta: lut[need] = (level - 1) | length << 8
+        if (lane <= 32) {
+            const u32 level = level_of(lane, l, magic);
+            s_lut[lane] = (level - 1u) | (level_len(level, M, l) << 8);
+        }
         u32 carry = uniform(bi.preKey);
         u32 wbits = 0;               // payload bits of this block waiting in `wword` from the previous round
         u32 wword = 0;
         u32 pw = 0;                  // payload words already written
-        bool unsorted = false;
+        u64 unsorted = 0;
+        uint8_t* s_flgb = reinterpret_cast<uint8_t*>(s_flg);
         for (u32 sub = 0; sub < nsub; ++sub) {
             const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
             const u32 r0 = first + sub * kSub;
-            const u32 jlo = uniform(find_chunk_wave(s_P, ku.nch, r0, lane));
-            const u32 jhi = uniform(find_chunk_wave(s_P, ku.nch, r0 + n - 1, lane));
-            u32 ent[kKeyRows], key[kKeyRows], code[kKeyRows];
-            find_entries(s_P, stride, jlo, jhi, r0, n, lane, s_pay, ent);     // borrows the payload window
+            u32 ent[kKeyRows], kb[kLaneKeys], dl[kLaneKeys], code[kKeyRows];
+            gather_blocked(s_P, ku.nch, stride, seg_keys, r0, n, lane, s_pay, ent, kb);    // borrows the payload window
 #pragma unroll
-            for (u32 q = 0; q < kKeyRows; ++q) {
-                const bool in = q * 64u + lane < n;
-                key[q] = in ? seg_keys[ent[q]] : 0u;
-                code[q] = in ? seg_codes[ent[q]] : 0u;
-            }
+            for (u32 q = 0; q < kKeyRows; ++q) code[q] = (q * 64u + lane < n) ? seg_codes[ent[q]] : 0u;
             // the payload window: word 0 carries the bits left over from the previous round
             for (u32 i = lane; i < kSub + 2; i += 64) s_pay[i] = (i == 0) ? wword : 0u;
+            if (n == kSub) lane_deltas<true>(kb, r0, n, lane, carry, dl, unsorted);
+            else lane_deltas<false>(kb, r0, n, lane, carry, dl, unsorted);
+            // levels, lengths; the lane's 16 flags as a string of 16*l bits
+            u32 len[kLaneKeys];
+            u64 fstr[2] = {0, 0};
+            u32 lanebits = 0;
+#pragma unroll
+            for (u32 k = 0; k < kLaneKeys; ++k) {
+                const u32 e = s_lut[32u - __clz(dl[k])];
+                const bool valid = lane * kLaneKeys + k < n;
+                len[k] = valid ? e >> 8 : 0u;
+                fstr[k >> 3] |= (u64)(valid ? e & 0xFFu : 0u) << ((k & 7u) * l);
+                lanebits += len[k];
+            }
+            // 8 flags are l bytes: the lane's two halves go to bytes (2*lane + half) * l of the plane
+#pragma unroll
+            for (u32 half = 0; half < 2; ++half)
+#pragma unroll
+                for (u32 bb = 0; bb < 5; ++bb)
+                    if (bb < l) s_flgb[(2u * lane + half) * l + bb] = (uint8_t)(fstr[half] >> (8u * bb));
             wave_lds_sync();
-            u32 rowbase = wbits;
+            const u32 incl = wave_incl_scan(lanebits);
+            u32 bp = wbits + incl - lanebits;
+#pragma unroll
+            for (u32 k = 0; k < kLaneKeys; ++k) {
+                const u64 pv = (u64)dl[k] << (bp & 31u);
+                if (len[k]) {
+                    atomicOr(&s_pay[bp >> 5], (u32)pv);
+                    atomicOr(&s_pay[(bp >> 5) + 1], (u32)(pv >> 32));
+                }
+                bp += len[k];
+            }
+            const u32 roundend = wbits + read_lane(incl, 63);
+            // the survivors' code bytes go straight into the value plane
 #pragma unroll
             for (u32 q = 0; q < kKeyRows; ++q) {
                 const u32 i = q * 64u + lane;
-                if (q * 64u < n) {
-                    // the survivors' code bytes go straight into the value plane
-                    if (i < n) vdst[sub * kSub + i] = (uint8_t)code[q];
-                    const u32 dl = row_delta(key[q], r0, q, n, lane, carry, unsorted);
-                    u32 len = 0;
-                    if (i < n) {
-                        const u32 level = level_of(32u - __clz(dl), l, magic);
-                        len = level_len(level, M, l);
-                        const u32 fpos = i * l;
-                        const u64 fv = (u64)(level - 1u) << (fpos & 31u);
-                        if ((u32)fv) atomicOr(&s_flg[fpos >> 5], (u32)fv);
-                        if (fv >> 32) atomicOr(&s_flg[(fpos >> 5) + 1], (u32)(fv >> 32));
-                    }
-                    const u32 incl = wave_incl_scan(len);
-                    if (i < n) {
-                        const u32 bitpos = rowbase + incl - len;
-                        const u64 pv = (u64)dl << (bitpos & 31u);
-                        if ((u32)pv) atomicOr(&s_pay[bitpos >> 5], (u32)pv);
-                        if (pv >> 32) atomicOr(&s_pay[(bitpos >> 5) + 1], (u32)(pv >> 32));
-                    }
-                    rowbase += read_lane(incl, 63);
-                }
+                if (i < n) vdst[sub * kSub + i] = (uint8_t)code[q];
             }
             wave_lds_sync();
             const bool last = (sub + 1 == nsub);
@@ -1054,7 +1109,7 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
             }
             // payload: the full words; the partial last word waits for the next round
             {
-                const u32 full = rowbase >> 5, rest = rowbase & 31u;
+                const u32 full = roundend >> 5, rest = roundend & 31u;
                 const u32 nw = (last && rest) ? full + 1u : full;
                 for (u32 i = lane; i < nw; i += 64) pdst[pw + i] = s_pay[i];
                 if (last) {
