@@ -98,7 +98,7 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     const u32* kbase = d_keys + first_elem - mis;
 
     std::vector<SegInfo> segs(n_segments);
-    u32 min_kb = kMaxKB;
+    u32 min_kb = kMaxKB, max_kb = 0;
     u64 n_tiles = 0, max_items = 0, total_rows = 0;
     for (u32 s = 0; s < n_segments; ++s) {
         const fastsgd_params* p = &params[params_stride ? s : 0];
@@ -119,6 +119,7 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
         const u64 blocks = (cnt + p->block_keys - 1) / p->block_keys;
         max_items += blocks ? blocks : 1;
         if (p->block_keys < min_kb) min_kb = p->block_keys;
+        if (p->block_keys > max_kb) max_kb = p->block_keys;
     }
     // chunks of R rows, about kChunkTarget of them, never shorter than one tile
     u64 R64 = (total_rows + kChunkTarget - 1) / kChunkTarget;
@@ -196,8 +197,12 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
         hipLaunchKernelGGL(k_plan_segments, dim3((n_segments + kWaves - 1) / kWaves), dim3(kThreads), 0, stream, dsegs,
                            dstates, n_segments, R, ccount, ctrl);
     const u64 max_units = (max_items + kWaves - 1) / kWaves + n_segments;
-    hipLaunchKernelGGL(k_measure_keys, dim3(clamp_grid(max_units, (u64)cus * 3)), dim3(kThreads), 0, stream, segs[0], dsegs,
-                       dstates, n_segments, R, ccount, skeys, binfo, gsum, g_shift, ctrl);
+    if (max_kb > kSub)
+        hipLaunchKernelGGL(k_measure_keys<true>, dim3(clamp_grid(max_units, (u64)cus * 3)), dim3(kThreads), 0, stream,
+                           segs[0], dsegs, dstates, n_segments, R, ccount, skeys, binfo, gsum, g_shift, ctrl);
+    else
+        hipLaunchKernelGGL(k_measure_keys<false>, dim3(clamp_grid(max_units, (u64)cus * 4)), dim3(kThreads), 0, stream,
+                           segs[0], dsegs, dstates, n_segments, R, ccount, skeys, binfo, gsum, g_shift, ctrl);
     marks.mark(stream);
     hipLaunchKernelGGL(k_pack_keys, dim3(clamp_grid(max_units, (u64)cus * 3)), dim3(kThreads), 0, stream, segs[0], dsegs,
                        dstates, n_segments, R, ccount, skeys, scodes, binfo, gsum, g_shift, out,

@@ -822,6 +822,9 @@ __device__ __forceinline__ void lane_deltas(const u32 (&kb)[kLaneKeys], u32 r0, 
     carry = read_lane(lastkey, uniform(last_lane));
 }
 
+// BIG: some segment of the call has key blocks of more than 1024 keys, whose deltas' bit lengths then
+// wait in shared memory for the block's M; otherwise they stay in registers.
+template <bool BIG>
 __global__ void __launch_bounds__(kThreads)
 k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
                u32 R, const u32* __restrict__ ccount, const u32* __restrict__ skeys, BlockInfo* __restrict__ binfo,
@@ -829,10 +832,12 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
     __shared__ u32 s_P[kMaxSegChunks + 1];
     __shared__ u32 s_scan[kWaves + 1];
     __shared__ __attribute__((aligned(16))) u32 s_bufall[kWaves][kSub];
-    __shared__ __attribute__((aligned(16))) uint8_t s_needall[kWaves][kMaxKB];   // significant bits of every delta of the block
+    __shared__ __attribute__((aligned(16))) uint8_t s_needall[kWaves][BIG ? kMaxKB : 16];   // bit lengths of a big block's deltas
+    __shared__ u32 s_lutall[kWaves][33];
     const u32 lane = lane_id(), w = uniform(wave_id());
     uint8_t* s_need = s_needall[w];
     u32* s_buf = s_bufall[w];
+    u32* s_lut = s_lutall[w];
     // a single gradient: its survivor count is the total of the scan of its chunk counts
     u64 total_units, single_d = 0;
     u32 cur_seg = 0xFFFFFFFFu;
@@ -879,6 +884,7 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
         // first loop of Algorithm 2: deltas and the longest of them (M = bit length of maxDelta)
         u64 unsorted = 0;
         u32 carry = 0, mxneed = 0;
+        u32 packed[4] = {0, 0, 0, 0};
         for (u32 sub = 0; sub < nsub; ++sub) {
             const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
             const u32 r0 = first + sub * kSub;
@@ -887,7 +893,6 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
             if (sub == 0) carry = uniform(preKey);              // (its fetch was in flight until here)
             if (n == kSub) lane_deltas<true>(kb, r0, n, lane, carry, dl, unsorted);
             else lane_deltas<false>(kb, r0, n, lane, carry, dl, unsorted);
-            u32 packed[4];
 #pragma unroll
             for (u32 j = 0; j < 4; ++j) {
                 u32 x = 0;
@@ -899,16 +904,24 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
                 }
                 packed[j] = x;
             }
-            reinterpret_cast<uint4*>(s_need + sub * kSub)[lane] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+            if (BIG) reinterpret_cast<uint4*>(s_need + sub * kSub)[lane] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
         }
         mxneed = wave_max(mxneed);
         if (unsorted && lane == 0) set_status(ctrl, FASTSGD_ERR_UNSORTED_KEYS);
         const u32 M = mxneed ? mxneed : 1u;
         // payload bits: every key takes the length of the smallest level that holds its delta
         const u32 magic = level_magic(M), l = ku.l;
+        if (lane <= 32) s_lut[lane] = level_len(level_of(lane, l, magic), M, l);     // length by bit length
         wave_lds_sync();
         u32 bits = 0;
-        for (u32 i = lane; i < cnt; i += 64) bits += level_len(level_of(s_need[i], l, magic), M, l);
+        if (BIG) {
+            for (u32 i = lane; i < cnt; i += 64) bits += s_lut[s_need[i]];
+        } else {
+            // one round: the bit lengths are still in registers (keys beyond cnt have none)
+#pragma unroll
+            for (u32 k = 0; k < kLaneKeys; ++k)
+                if (lane * kLaneKeys + k < cnt) bits += s_lut[(packed[k >> 2] >> (8u * (k & 3u))) & 0xFFu];
+        }
         bits = wave_sum(bits);
         wave_lds_sync();
         if (lane == 0) {
