@@ -238,7 +238,7 @@ static fastsgd_status decompress_impl(const void* d_streams, size_t total_bytes,
         hipLaunchKernelGGL(k_decode_setup, dim3(n_segments), dim3(128), 0, stream, streams, (u64)total_bytes,
                            d_stream_offsets, n_segments, segs, ctrl, capacity, d_counts, d_status);
         if (n_segments > 1)
-            hipLaunchKernelGGL(k_decode_plan, dim3(1), dim3(64), 0, stream, segs, n_segments, capacity, ctrl,
+            hipLaunchKernelGGL(k_decode_plan, dim3(1), dim3(kThreads), 0, stream, segs, n_segments, capacity, ctrl,
                                d_counts, d_status);
     }
     marks.mark(stream);

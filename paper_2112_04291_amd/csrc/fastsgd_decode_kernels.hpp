@@ -114,18 +114,54 @@ __global__ void k_decode_clear(DecCtrl* ctrl) {
     if (threadIdx.x == 0 && blockIdx.x == 0) { ctrl->status = 0; ctrl->total_items = 0; ctrl->total_pairs = 0; }
 }
 
-__global__ void k_decode_plan(DecSeg* segs, u32 n_segments, u64 capacity, DecCtrl* ctrl, u64* out_counts,
-                              u32* out_status) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) plan_streams(segs, n_segments, capacity, ctrl, out_counts, 0, out_status);
+// Batch: pair offsets and work-item numbering over the streams, one workgroup scanning 256 streams
+// at a time.
+__global__ void __launch_bounds__(kThreads)
+k_decode_plan(DecSeg* segs, u32 n_segments, u64 capacity, DecCtrl* ctrl, u64* out_counts, u32* out_status) {
+    __shared__ u64 s_wave[2][kWaves];
+    __shared__ u64 s_carry[2];
+    const u32 t = threadIdx.x, lane = lane_id(), w = wave_id();
+    if (t < 2) s_carry[t] = 0;
+    __syncthreads();
+    for (u32 s0 = 0; s0 < n_segments; s0 += kThreads) {
+        const u32 s = s0 + t;
+        const u64 d = s < n_segments ? segs[s].d : 0, nb = s < n_segments ? segs[s].nb : 0;
+        const u64 id = wave_incl_scan64(d), ib = wave_incl_scan64(nb);
+        if (lane == 63) { s_wave[0][w] = id; s_wave[1][w] = ib; }
+        __syncthreads();
+        u64 bd = s_carry[0], bb = s_carry[1], td = 0, tb = 0;
+#pragma unroll
+        for (u32 k = 0; k < kWaves; ++k) {
+            const u64 a = s_wave[0][k], b = s_wave[1][k];
+            if (k < w) { bd += a; bb += b; }
+            td += a; tb += b;
+        }
+        if (s < n_segments) {
+            segs[s].pair_begin = bd + id - d;
+            segs[s].item_begin = bb + ib - nb;
+        }
+        __syncthreads();
+        if (t == 0) { s_carry[0] += td; s_carry[1] += tb; }
+        __syncthreads();
+    }
+    const u64 pairs = s_carry[0], items = s_carry[1];
+    u32 status = ctrl->status;
+    __syncthreads();
+    bool ok = (status == 0);
+    if (ok && pairs > capacity) { status = FASTSGD_ERR_BUFFER_TOO_SMALL; ok = false; }
+    for (u32 s = t; s < n_segments; s += kThreads) out_counts[s] = ok ? segs[s].pair_begin : 0;
+    if (t == 0) {
+        ctrl->status = status;
+        ctrl->total_items = ok ? items : 0;
+        ctrl->total_pairs = ok ? pairs : 0;
+        out_counts[n_segments] = ok ? pairs : 0;
+        *out_status = status;
+    }
 }
 
+// Stream that work item `item` belongs to: the last one whose first item is not beyond it.
 __device__ __forceinline__ u32 find_dec_segment(const DecSeg* segs, u32 n_segments, u64 item) {
-    u32 lo = 0, hi = n_segments;
-    while (hi - lo > 1) {
-        u32 mid = (lo + hi) >> 1;
-        if (segs[mid].item_begin <= item) lo = mid; else hi = mid;
-    }
-    return lo;
+    return wave_upper_index(n_segments, item, [&](u32 i) { return segs[i].item_begin; });
 }
 
 // One key block per WAVE, 1024 keys at a time, each lane owning 16 CONSECUTIVE keys of the round, so

@@ -195,22 +195,30 @@ __device__ __forceinline__ void power_chain(double base, u32 tau, double* P) {
     for (u32 c = 1; c <= tau; ++c) { p = p * base; P[c] = p; }
 }
 
-// Last segment whose first tile is <= tile (segments without tiles share their successor's value).
-__device__ __forceinline__ u32 find_tile_segment(const SegInfo* segs, u32 n_segments, u32 tile) {
-    u32 lo = 0, hi = n_segments;
+// Largest index i in [0, n) with value(i) <= x, for a non-decreasing value() with value(0) <= x and an
+// x that is the same in all lanes: the wave probes 64 evenly spaced entries per round, so 4096
+// entries take two memory round trips instead of twelve.
+template <class Value>
+__device__ __forceinline__ u32 wave_upper_index(u32 n, u64 x, Value value) {
+    u32 lo = 0, hi = n;
     while (hi - lo > 1) {
-        u32 mid = (lo + hi) >> 1;
-        if (segs[mid].tile_begin <= tile) lo = mid; else hi = mid;
+        const u32 step = (hi - lo + 63u) / 64u;
+        const u32 idx = lo + lane_id() * step;
+        const bool p = idx < hi && value(idx) <= x;
+        const u32 c = (u32)__popcll(__ballot(p));          // >= 1: lane 0 probes lo
+        lo = uniform(lo + (c - 1u) * step);
+        hi = lo + step < hi ? lo + step : hi;
     }
     return lo;
 }
+
+// Last segment whose first tile / chunk is <= the given one (segments without any share their
+// successor's value).
+__device__ __forceinline__ u32 find_tile_segment(const SegInfo* segs, u32 n_segments, u32 tile) {
+    return wave_upper_index(n_segments, tile, [&](u32 i) { return segs[i].tile_begin; });
+}
 __device__ __forceinline__ u32 find_chunk_segment(const SegInfo* segs, u32 n_segments, u32 chunk) {
-    u32 lo = 0, hi = n_segments;
-    while (hi - lo > 1) {
-        u32 mid = (lo + hi) >> 1;
-        if (segs[mid].chunk_begin <= chunk) lo = mid; else hi = mid;
-    }
-    return lo;
+    return wave_upper_index(n_segments, chunk, [&](u32 i) { return segs[i].chunk_begin; });
 }
 
 __device__ __forceinline__ void set_status(Ctrl* ctrl, u32 code) { atomicCAS(&ctrl->status, 0u, code); }

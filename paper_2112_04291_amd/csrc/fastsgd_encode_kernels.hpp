@@ -598,12 +598,7 @@ struct KeyUnit {        // workgroup-uniform
 };
 
 __device__ __forceinline__ u32 find_unit_segment(const SegState* states, u32 n_segments, u64 unit) {
-    u32 lo = 0, hi = n_segments;
-    while (hi - lo > 1) {
-        u32 mid = (lo + hi) >> 1;
-        if (states[mid].unit_begin <= unit) lo = mid; else hi = mid;
-    }
-    return lo;
+    return wave_upper_index(n_segments, unit, [&](u32 i) { return states[i].unit_begin; });
 }
 
 __device__ __forceinline__ u32 segment_chunks(const SegInfo& s, u32 R) {
