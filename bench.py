@@ -58,8 +58,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="elements the oracle is timed on (0 = the whole workload)")
     ap.add_argument("--calibrate", action="store_true",
-                    help="also run one plain device copy of the value array (a dispatch of known HBM traffic, "
-                         "the reference the rocprofv3 counter runs are scaled by)")
+                    help="also run, before anything else, one plain elementwise kernel over the value array "
+                         "(out = -in: n*4 bytes read, n*4 bytes written), the dispatch of known HBM traffic the "
+                         "rocprofv3 counter runs are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this codec is a single-GPU path (one worker's gradient); --gpus must be 1. "
@@ -93,7 +94,7 @@ def main():
 
     if args.calibrate:
         ref_copy = torch.empty_like(values)
-        ref_copy.copy_(values)          # n*4 bytes read + n*4 bytes written
+        torch.neg(values, out=ref_copy)          # n*4 bytes read + n*4 bytes written
         torch.cuda.synchronize()
         del ref_copy
 

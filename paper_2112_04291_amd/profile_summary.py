@@ -5,9 +5,10 @@
 
 `trace`   : <dir> holds the output of `rocprofv3 --kernel-trace --stats --output-format csv`.
 `traffic` : the two directories hold `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of
-            `bench.py --calibrate`, whose first large dispatch is a plain device copy of the value
-            array (n_values * 4 bytes read and as many written).  Both counters report KiB per
-            dispatch; each is scaled by (known KiB of the copy) / (what the counter read for it).
+            `bench.py --calibrate`, whose first large dispatch is a plain elementwise kernel over the
+            value array (out = -in: n_values * 4 bytes read and as many written).  Both counters report
+            KiB per dispatch; each is scaled by (known KiB of that kernel) / (what the counter read
+            for it).
 """
 import collections
 import csv
@@ -50,27 +51,31 @@ def trace(d, out, command):
 
 
 def _counter(d, name):
+    """({kernel: [value per dispatch]}, (value, kernel) of the calibration dispatch: the first one, in
+    dispatch order, that is not one of the library's kernels and moved a large amount)."""
     per = collections.defaultdict(list)
-    for r in _rows(d, "counter_collection.csv"):
-        if r["Counter_Name"] == name:
-            per[_short(r["Kernel_Name"])].append(float(r["Counter_Value"]))
-    return per
+    rows = [r for r in _rows(d, "counter_collection.csv") if r["Counter_Name"] == name]
+    rows.sort(key=lambda r: int(r["Dispatch_Id"]))
+    first = None
+    for r in rows:
+        k, v = _short(r["Kernel_Name"]), float(r["Counter_Value"])
+        per[k].append(v)
+        if first is None and not k.startswith("k_") and v > 100000.0:
+            first = (v, k)
+    return per, first or (0.0, "")
 
 
 def traffic(dfetch, dwrite, out, n_values, command):
     known_kib = n_values * 4.0 / 1024.0
-    fetch, write = _counter(dfetch, "FETCH_SIZE"), _counter(dwrite, "WRITE_SIZE")
-
-    def calib(per):
-        best = max(((max(v), k) for k, v in per.items() if not k.startswith("k_")), default=(0.0, ""))
-        return known_kib / best[0] if best[0] > 0 else float("nan"), best
-    ff, fb = calib(fetch)
-    wf, wb = calib(write)
+    (fetch, fb), (write, wb) = _counter(dfetch, "FETCH_SIZE"), _counter(dwrite, "WRITE_SIZE")
+    ff = known_kib / fb[0] if fb[0] > 0 else float("nan")
+    wf = known_kib / wb[0] if wb[0] > 0 else float("nan")
     with open(out, "w") as f:
         f.write("# HBM traffic per launch of the benchmark's kernels (config 4, four keep fractions)\n\n")
         f.write(f"Commands: `{command.replace('COUNTER', 'FETCH_SIZE')}` and the same with `WRITE_SIZE`.\n\n")
-        f.write(f"Calibration: the plain device copy of the value array ({n_values} x 4 bytes = {known_kib:.0f} KiB "
-                f"each way) read FETCH_SIZE = {fb[0]:.0f} and WRITE_SIZE = {wb[0]:.0f} (dispatch `{fb[1]}`), so "
+        f.write(f"Calibration: the plain elementwise kernel over the value array ({n_values} x 4 bytes = "
+                f"{known_kib:.0f} KiB each way) read FETCH_SIZE = {fb[0]:.0f} and WRITE_SIZE = {wb[0]:.0f} "
+                f"(dispatch `{fb[1]}`), so "
                 f"the counters are scaled by {ff:.4f} and {wf:.4f}.  Averages over all launches of a kernel in "
                 f"the run (all four keep fractions); the last column is the scaled fetch + write in bytes.\n\n")
         f.write("| kernel | launches | FETCH_SIZE KiB avg | WRITE_SIZE KiB avg | HBM bytes per launch |\n")
