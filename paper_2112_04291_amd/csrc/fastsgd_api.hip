@@ -44,7 +44,7 @@ static EncodePlan make_plan(u64 total_n, u32 n_segments, u32 min_kb) {
     pl.zero_end = o;                                               // a single-gradient call clears up to here
     pl.off_gbins = o; o += up((u64)n_segments * pl.n_slots * kBinWords * 8, 256);
     pl.zero_end_batch = o;                                         // a batch also clears the abs-sum records
-    pl.off_rowmax = o;   o += up(pl.max_rows * 4, 256);
+    pl.off_rowmax = o;   o += up(pl.max_rows * 8, 256);               // four 16-bit quarter-row bounds per row
     pl.off_ccount = o;   o += up(pl.max_chunks * 4, 256);
     pl.off_binfo = o;    o += up(pl.max_items * sizeof(BlockInfo), 256);
     pl.off_seginfo = o;  o += up((u64)n_segments * sizeof(SegInfo), 256);
@@ -148,7 +148,7 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + pl.off_ctrl);
     unsigned long long* gsum = reinterpret_cast<unsigned long long*>(ws + pl.off_gsum);
     u64* gbins = reinterpret_cast<u64*>(ws + pl.off_gbins);
-    u32* rowmax = reinterpret_cast<u32*>(ws + pl.off_rowmax);
+    uint16_t* rowmax = reinterpret_cast<uint16_t*>(ws + pl.off_rowmax);
     u32* ccount = reinterpret_cast<u32*>(ws + pl.off_ccount);
     BlockInfo* binfo = reinterpret_cast<BlockInfo*>(ws + pl.off_binfo);
     SegInfo* dsegs = reinterpret_cast<SegInfo*>(ws + pl.off_seginfo);

@@ -121,20 +121,27 @@ __device__ __forceinline__ void flush_bins(u64 (*bins)[kThreads], u64* rec, u32 
 }
 
 // Also stores, for each of the wave's four rows of the tile that exist (row index below row_end), the
-// largest |v| of the row as a bit pattern: the second pass skips every row whose maximum is below the
-// threshold.  rowmax points at the entry of the tile's first row; trow0 is that row's index.
+// largest |v| of each quarter row (64 values: the float4s of 16 neighbouring lanes): the upper 16 bits
+// of its bit pattern, rounded up, so that the stored bound is never below the true maximum.  The
+// second pass skips every quarter row whose bound is below the threshold.  rowmax points at the four
+// entries of the tile's first row; trow0 is that row's index.
 __device__ __forceinline__ void accumulate_tile(const u32 bits[4][4], u64 (*bins)[kThreads], u32& maxa,
-                                                u32* __restrict__ rowmax, u64 trow0, u64 row_end) {
+                                                uint16_t* __restrict__ rowmax, u64 trow0, u64 row_end) {
     const u32 t = threadIdx.x;
 #pragma unroll
     for (u32 r = 0; r < 4; ++r) {
         u32 m = bits[r][0] & 0x7FFFFFFFu;
 #pragma unroll
         for (u32 c = 1; c < 4; ++c) { const u32 a = bits[r][c] & 0x7FFFFFFFu; m = a > m ? a : m; }
-        m = wave_max(m);
-        const u32 wr = wave_id() * 4u + r;
-        if (lane_id() == 0 && trow0 + wr < row_end) rowmax[wr] = m;
         maxa = m > maxa ? m : maxa;
+        u32 y;                                              // maximum over the 16 lanes up to this one
+        y = dpp_mov<kDppRowShr1>(0u, m); m = m > y ? m : y;
+        y = dpp_mov<kDppRowShr2>(0u, m); m = m > y ? m : y;
+        y = dpp_mov<kDppRowShr4>(0u, m); m = m > y ? m : y;
+        y = dpp_mov<kDppRowShr8>(0u, m); m = m > y ? m : y;
+        const u32 wr = wave_id() * 4u + r;
+        if ((lane_id() & 15u) == 15u && trow0 + wr < row_end)
+            rowmax[wr * 4u + (lane_id() >> 4)] = (uint16_t)((m + 0xFFFFu) >> 16);   // m < 2^31: no overflow
     }
 #pragma unroll
     for (u32 r = 0; r < 4; ++r)
@@ -154,7 +161,7 @@ template <bool SINGLE>
 __global__ void __launch_bounds__(kThreads)
 k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u32 n_segments, u64 n_tiles,
           u64* gbins, u32 n_slots, u64* zero_begin, u64 zero_words, SegInfo single_seg, SegInfo* seg_store,
-          u32* __restrict__ rowmax) {
+          uint16_t* __restrict__ rowmax) {
     __shared__ u64 bins[kBins][kThreads];
     const u32 t = threadIdx.x;
 #pragma unroll
@@ -178,7 +185,7 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
             g.full = (g.tile0 >= g.lo) && (g.tile0 + kTile <= g.hi);
             u32 bits[4][4];
             load_tile(values, g, bits);
-            accumulate_tile(bits, bins, maxa, rowmax + tile * (kTile / kRow), tile * (kTile / kRow), row_end);
+            accumulate_tile(bits, bins, maxa, rowmax + tile * (4u * kTile / kRow), tile * (kTile / kRow), row_end);
         }
         flush_bins<true>(bins, gbins + blockIdx.x, n_slots, maxa);
     } else {
@@ -199,7 +206,7 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
             u32 bits[4][4];
             load_tile(values, g, bits);
             const u64 trow0 = (tile - info.tile_begin) * (kTile / kRow);
-            accumulate_tile(bits, bins, maxa, rowmax + info.row_begin + trow0, trow0, segment_rows(info));
+            accumulate_tile(bits, bins, maxa, rowmax + 4ull * (info.row_begin + trow0), trow0, segment_rows(info));
         }
         if (cur_seg != 0xFFFFFFFFu)
             flush_bins<false>(bins, gbins + (u64)cur_seg * n_slots * kBinWords + blockIdx.x % n_slots, n_slots, maxa);
@@ -380,7 +387,7 @@ __device__ __forceinline__ Chunk chunk_geom(const SegInfo* __restrict__ segs, u3
 __global__ void __launch_bounds__(kValWaves * kWave) __attribute__((amdgpu_waves_per_eu(4, 8)))
 k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                 const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
-                u32 n_chunks, u32 R, const u32* __restrict__ rowmax, u32* __restrict__ ccount,
+                u32 n_chunks, u32 R, const uint16_t* __restrict__ rowmax, u32* __restrict__ ccount,
                 u32* __restrict__ skeys, uint8_t* __restrict__ scodes) {
     __shared__ u32 s_Ball[kValWaves][128];
     __shared__ u32 s_valall[kValWaves][kStage];
@@ -400,7 +407,7 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
     const float thr_f = __uint_as_float(thr);
     const u32* ckeys = keys + ck.e0;
     const float* cvals = values + ck.e0;
-    const u32* crmax = rowmax + ck.row0;
+    const uint2* crmax = reinterpret_cast<const uint2*>(rowmax) + ck.row0;     // four quarter-row bounds per row, 16 bits each
     u32 cbase = 0;                           // survivors of the chunk already in the scratch arrays
     u32 staged = 0;                          // survivors waiting in shared memory
 
@@ -440,10 +447,13 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
 
     // Row r of the chunk.  Rows cut by the segment's ends (its first and last row at most) are fetched
     // element by element and the elements outside [lo, hi) become zero, which never survives.
-    auto load_row = [&](u32 r, u32 (&row)[4]) {
+    // `quarters`: bit k set = the row's quarter k (lanes 16k .. 16k+15) can hold a survivor; the others
+    // are not read and count as zero.
+    auto load_row = [&](u32 r, u32 quarters, u32 (&row)[4]) {
         const u64 e = ck.e0 + (u64)r * kRow;
         if (e >= ck.lo && e + kRow <= ck.hi) {
-            const uint4 q = reinterpret_cast<const uint4*>(cvals + (u64)r * kRow)[lane];
+            uint4 q = make_uint4(0u, 0u, 0u, 0u);
+            if ((quarters >> (lane >> 4)) & 1u) q = reinterpret_cast<const uint4*>(cvals + (u64)r * kRow)[lane];
             row[0] = q.x; row[1] = q.y; row[2] = q.z; row[3] = q.w;
         } else {
 #pragma unroll
@@ -472,25 +482,33 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
     };
 
     for (u32 g0 = 0; g0 < ck.nrows; g0 += 256u) {
-        // which of the next 256 rows can hold a survivor (unsigned compare of bit patterns: the same
-        // order as the float compare, and no row passes the keep-nothing threshold)
+        // which quarters of the next 256 rows can hold a survivor (unsigned compare of bit patterns: the
+        // same order as the float compare, and nothing passes the keep-nothing threshold): lane j keeps
+        // the four bits of rows g0 + 64*k + j, k = 0..3; a row is read if any of its bits is set
         u64 mask[4];
+        u32 qbits[4];
 #pragma unroll
         for (u32 k = 0; k < 4; ++k) {
             const u32 rr = g0 + k * 64u + lane;
-            const u32 x = crmax[rr < ck.nrows ? rr : ck.nrows - 1u];
-            mask[k] = __ballot(rr < ck.nrows && x >= thr);
+            const uint2 x = crmax[rr < ck.nrows ? rr : ck.nrows - 1u];
+            u32 qb = ((x.x << 16) >= thr ? 1u : 0u) | ((x.x & 0xFFFF0000u) >= thr ? 2u : 0u) |
+                     ((x.y << 16) >= thr ? 4u : 0u) | ((x.y & 0xFFFF0000u) >= thr ? 8u : 0u);
+            if (rr >= ck.nrows) qb = 0;
+            qbits[k] = qb;
+            mask[k] = __ballot(qb != 0);
         }
-        // the next (up to) eight such rows, in ascending order
-        auto take = [&](u32 (&rows)[kValRows]) -> u32 {
+        // the next (up to) eight such rows, in ascending order, with their quarter bits
+        auto take = [&](u32 (&rows)[kValRows], u32 (&quarters)[kValRows]) -> u32 {
             u32 cnt = 0;
 #pragma unroll
             for (u32 slot = 0; slot < kValRows; ++slot) {
-                rows[slot] = 0;
+                rows[slot] = 0; quarters[slot] = 0;
 #pragma unroll
                 for (u32 k = 0; k < 4; ++k) {
                     if (cnt == slot && mask[k]) {
-                        rows[slot] = g0 + k * 64u + (u32)__builtin_ctzll(mask[k]);
+                        const u32 b = (u32)__builtin_ctzll(mask[k]);
+                        rows[slot] = g0 + k * 64u + b;
+                        quarters[slot] = read_lane(qbits[k], b);
                         mask[k] &= mask[k] - 1ull;
                         cnt = slot + 1u;
                     }
@@ -498,10 +516,10 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
             }
             return cnt;
         };
-        u32 bits[kValRows][4], rows[kValRows];
-        u32 nr = take(rows);
+        u32 bits[kValRows][4], rows[kValRows], quarters[kValRows];
+        u32 nr = take(rows, quarters);
 #pragma unroll
-        for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_row(rows[slot], bits[slot]);
+        for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_row(rows[slot], quarters[slot], bits[slot]);
         while (nr) {
 #pragma unroll
             for (u32 slot = 0; slot < 4; ++slot) if (slot < nr) stage_row(bits[slot], rows[slot] * kRow);
@@ -509,9 +527,9 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
 #pragma unroll
             for (u32 slot = 4; slot < 8; ++slot) if (slot < nr) stage_row(bits[slot], rows[slot] * kRow);
             // the registers are free: start on the next rows before finishing these
-            nr = take(rows);
+            nr = take(rows, quarters);
 #pragma unroll
-            for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_row(rows[slot], bits[slot]);
+            for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_row(rows[slot], quarters[slot], bits[slot]);
             if (staged > kFlushLevel) flush();
         }
     }
