@@ -211,3 +211,46 @@ def test_corrupt_streams_are_rejected_on_device():
     assert run(lambda s: None, cap=1999) == B.ERR_BUFFER_TOO_SMALL
     rc, status, k, v = G.hip_decompress(st[:48], capacity=10)
     assert status == B.ERR_CORRUPT_STREAM
+
+
+def test_values_on_bucket_boundaries_and_quarter_row_bounds():
+    """Elements exactly on, one ulp below and one ulp above every boundary (exact powers of two by
+    construction), scattered so that many quarter rows hold a single borderline element: the row-skip
+    bounds and the boundary table must agree with the oracle to the last bit."""
+    from tests.test_oracle_values import boundary_gradient
+    keys, vals, codes, kept = boundary_gradient(10)
+    st = check_round_trip(keys, vals, 2.0, tau=10, l=2, kb=256)
+    d = int(st[40:48].view("<u8")[0])
+    assert d == int(kept.sum())
+    # sparse variant: the borderline elements far apart, everything else far below the threshold
+    rng = np.random.default_rng(8)
+    n = 600_000
+    v = np.zeros(n, np.float32)
+    pos = np.sort(rng.choice(n, vals.size, replace=False))
+    v[pos] = vals
+    check_round_trip(np.arange(n, dtype=np.uint32), v, 2.0, tau=10, l=3, kb=1024)
+
+
+def test_workspace_and_buffers_reused_across_sizes():
+    """The same workspace serves a large call, then a small one, then an empty one, then a large one
+    again: nothing of an earlier call may leak into a later one."""
+    torch, B, G = _gpu()
+    big = W.small_mixture(51, 700_000)
+    small = W.small_mixture(52, 3_000)
+    p_big = B.params(W.solve_base(big.values, 0.2))
+    bufs = B.Buffers(big.values.size, p_big)
+    for w, keep in ((big, 0.2), (small, 0.5), (W.small_mixture(53, 0), 0.5), (big, 0.01), (small, 1.0)):
+        b = W.solve_base(w.values, keep) if w.values.size else 1.1
+        rc_ref, st_ref = ref.compress(w.keys, w.values, ref.params(b))
+        rc, status, st, _ = G.hip_compress(w.keys, w.values, B.params(b), bufs=bufs)
+        assert rc == B.OK and status == rc_ref == 0
+        assert np.array_equal(st, st_ref)
+
+
+def test_many_rounds_per_block_and_mixed_block_sizes():
+    """Blocks of 2048 and 4096 keys take several rounds of 1024 per wave; dense keys, all survive."""
+    n = 50_000
+    keys = np.cumsum(np.random.default_rng(4).integers(1, 70_000, n)).astype(np.uint32)
+    vals = np.full(n, 0.25, np.float32)
+    for kb, l in ((2048, 1), (4096, 5), (4096, 2)):
+        check_round_trip(keys, vals, 1.2, tau=128, l=l, kb=kb)

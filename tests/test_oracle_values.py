@@ -284,3 +284,64 @@ def test_decoded_magnitude_stays_in_its_own_bucket():
         c = (byte & 0x7F) + 1
         # the decoded magnitude lies in (B[c+1], B[c]]: one ulp below B[c] at most
         assert x <= B[c] and (c == tau or x >= B[c + 1])
+
+
+def boundary_gradient(tau=10, reps=8):
+    """Values whose sum is exactly 2^20 with base 2, so that every boundary sum / 2^c is a power of two
+    (Eq. 3 evaluated without rounding): elements sit exactly on boundaries, one ulp below and one ulp
+    above them.  Returns (keys, values, expected codes, kept mask)."""
+    f = np.float32
+    vals, codes = [], []
+    for c in range(tau - 3, tau + 3):                 # boundaries 2^(20-c); c > tau lies below the threshold
+        t = f(2.0 ** (20 - c))
+        below, above = np.nextafter(t, f(0)), np.nextafter(t, f(np.inf))
+        for x, cx in ((t, c), (above, c), (below, c + 1)):
+            for s in (1.0, -1.0):
+                vals += [f(s) * x] * reps
+                codes += [cx] * reps
+    vals = np.array(vals, np.float32)
+    codes = np.array(codes)
+    # pad with small exact values so that the exact sum of |v| is 2^20 (all terms are multiples of 2^-20)
+    from fractions import Fraction
+    rest = Fraction(2 ** 20) - sum(Fraction(float(abs(x))) for x in vals)
+    assert rest > 0
+    filler = []
+    unit = Fraction(2 ** (20 - tau - 2))               # a quarter of the threshold 2^(20-tau): dropped
+    while rest > 0:
+        take = min(rest, unit)
+        # take is a multiple of 2^-33 at worst: split into exactly representable powers of two
+        num, den = take.numerator, take.denominator
+        bit = 1
+        while num:
+            if num & 1:
+                filler.append(float(Fraction(bit, den)))
+            num >>= 1
+            bit <<= 1
+        rest -= take
+    filler = np.array(filler, np.float32)
+    assert all(Fraction(float(x)) == Fraction(float(np.float64(x))) for x in filler[:4])
+    rng = np.random.default_rng(3)
+    allv = np.concatenate([vals, filler])
+    allc = np.concatenate([codes, np.full(filler.size, tau + 5)])
+    perm = rng.permutation(allv.size)
+    allv, allc = allv[perm], allc[perm]
+    return np.arange(allv.size, dtype=np.uint32) * 3, allv, allc, allc <= tau
+
+
+def test_values_exactly_on_below_and_above_bucket_boundaries():
+    """Closed form: with b = 2 and sum = 2^20 the boundary of code c is 2^(20-c) exactly, so the code of
+    |v| = 2^(20-c) is c, one ulp above it still c, one ulp below it c + 1; the filter keeps c <= tau."""
+    tau = 10
+    keys, vals, codes, kept = boundary_gradient(tau)
+    bad, S = ref.abs_sum(vals)
+    assert not bad and S == 2.0 ** 20
+    rc, st = ref.compress(keys, vals, ref.params(2.0, tau, 2, 256))
+    assert rc == ref.OK
+    d = int(st[40:48].view("<u8")[0])
+    assert d == int(kept.sum())
+    plane = st[64:64 + d]
+    assert np.array_equal((plane & 0x7F) + 1, codes[kept])
+    assert np.array_equal(plane >> 7, (vals[kept] < 0).astype(np.uint8))
+    rc, k, v = ref.decompress(st)
+    assert np.array_equal(k, keys[kept])
+    assert np.array_equal(np.abs(v), (2.0 ** (20 - codes[kept])).astype(np.float32))
