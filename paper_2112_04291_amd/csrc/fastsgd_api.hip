@@ -193,18 +193,17 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
                            dim3(kValWaves * kWave), 0, stream, kbase, vbase, dsegs, dstates, n_segments, (u32)n_chunks,
                            R, rowmax, ccount, skeys, scodes);
     marks.mark(stream);
-    if (!single)
-        hipLaunchKernelGGL(k_plan_segments, dim3((n_segments + kWaves - 1) / kWaves), dim3(kThreads), 0, stream, dsegs,
-                           dstates, n_segments, R, ccount, ctrl);
+    hipLaunchKernelGGL(k_plan_segments, dim3(n_segments), dim3(kThreads), 0, stream, dsegs, dstates, n_segments, R,
+                       ccount, ctrl);
     const u64 max_units = (max_items + kWaves - 1) / kWaves + n_segments;
     if (max_kb > kSub)
-        hipLaunchKernelGGL(k_measure_keys<true>, dim3(clamp_grid(max_units, (u64)cus * 3)), dim3(kThreads), 0, stream,
+        hipLaunchKernelGGL(k_measure_keys<true>, dim3(clamp_grid(max_units, (u64)cus * 4)), dim3(kThreads), 0, stream,
                            segs[0], dsegs, dstates, n_segments, R, ccount, skeys, binfo, gsum, g_shift, ctrl);
     else
-        hipLaunchKernelGGL(k_measure_keys<false>, dim3(clamp_grid(max_units, (u64)cus * 4)), dim3(kThreads), 0, stream,
+        hipLaunchKernelGGL(k_measure_keys<false>, dim3(clamp_grid(max_units, (u64)cus * 8)), dim3(kThreads), 0, stream,
                            segs[0], dsegs, dstates, n_segments, R, ccount, skeys, binfo, gsum, g_shift, ctrl);
     marks.mark(stream);
-    hipLaunchKernelGGL(k_pack_keys, dim3(clamp_grid(max_units, (u64)cus * 3)), dim3(kThreads), 0, stream, segs[0], dsegs,
+    hipLaunchKernelGGL(k_pack_keys, dim3(clamp_grid(max_units, (u64)cus * 4)), dim3(kThreads), 0, stream, segs[0], dsegs,
                        dstates, n_segments, R, ccount, skeys, scodes, binfo, gsum, g_shift, out,
                        (u64)out_capacity, d_out_offsets, single ? 1u : 0u, d_status, ctrl);
     marks.mark(stream);

@@ -538,31 +538,57 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
 }
 
 // ---------------------------------------------------------------------------------------------
-// Batch calls: numbering of the key encoder's work.  A work item is one key block (a segment without
+// One workgroup per segment turns the segment's chunk counts, in place, into their exclusive scan
+// P[j] = survivors of the segment in its chunks before j (the table through which the key encoder
+// finds rank r: chunk j with P[j] <= r < P[j+1]), and notes the segment's survivors d and key blocks.
+// Batch calls then number the key encoder's work: a work item is one key block (a segment without
 // survivors still has one item, which carries its header); a work unit is kWaves consecutive items of
-// one segment, the share of one workgroup iteration.  Every wave adds up the chunk counts of one
-// segment; the workgroup that finishes last (a counter in the control block) then scans the segments.
+// one segment, the share of one workgroup iteration; the workgroup that finishes last (a counter in
+// the control block) scans the segments.
 __global__ void __launch_bounds__(kThreads)
 k_plan_segments(const SegInfo* __restrict__ segs, SegState* __restrict__ states, u32 n_segments, u32 R,
-                const u32* __restrict__ ccount, Ctrl* ctrl) {
+                u32* __restrict__ ccount, Ctrl* ctrl) {
     __shared__ u64 s_wave[2][kWaves];
     __shared__ u64 s_carry[2];
+    __shared__ u32 s_scan[kWaves + 1];
     __shared__ u32 s_last;
     const u32 t = threadIdx.x, lane = lane_id(), w = wave_id();
     {
-        const u32 s = blockIdx.x * kWaves + w;
-        if (s < n_segments) {
-            const SegInfo info = segs[s];
-            const u32 nch = info.elem_count ? (u32)((segment_rows(info) + R - 1) / R) : 0u;
-            u64 d = 0;
-            for (u32 j = lane; j < nch; j += 64) d += ccount[info.chunk_begin + j];
-            d = wave_sum64(d);
-            if (lane == 0) {
-                states[s].d = d;
-                states[s].nb = (u32)((d + info.block_keys - 1) / info.block_keys);
+        constexpr u32 PER = kMaxSegChunks / kThreads;
+        const u32 seg = blockIdx.x;
+        const SegInfo info = segs[seg];
+        const u32 nch = info.elem_count ? (u32)((segment_rows(info) + R - 1) / R) : 0u;
+        u32* P = ccount + info.chunk_begin;
+        u32 v[PER], sum = 0;
+#pragma unroll
+        for (u32 k = 0; k < PER; ++k) {                 // no condition on the loads: all in flight at once
+            const u32 j = t * PER + k;
+            const u32 x = nch ? P[j < nch ? j : 0u] : 0u;
+            v[k] = (j < nch) ? x : 0u;
+        }
+#pragma unroll
+        for (u32 k = 0; k < PER; ++k) sum += v[k];
+        u32 total;
+        u32 run = block_excl_scan(sum, s_scan, &total);
+#pragma unroll
+        for (u32 k = 0; k < PER; ++k) {
+            const u32 j = t * PER + k;
+            if (j < nch) P[j] = run;
+            run += v[k];
+        }
+        if (t == 0) {
+            const u32 nb = (u32)(((u64)total + info.block_keys - 1) / info.block_keys);
+            states[seg].d = total;
+            states[seg].nb = nb;
+            if (gridDim.x == 1) {                       // a single gradient: nothing to number
+                states[seg].item_begin = 0;
+                states[seg].unit_begin = 0;
+                ctrl->total_items = nb ? nb : 1u;
+                ctrl->total_units = ((nb ? nb : 1u) + kWaves - 1) / kWaves;
             }
         }
     }
+    if (gridDim.x == 1) return;
     __threadfence();
     __syncthreads();
     if (t == 0) s_last = (atomicAdd(&ctrl->plan_done, 1u) == gridDim.x - 1) ? 1u : 0u;
@@ -607,8 +633,9 @@ k_plan_segments(const SegInfo* __restrict__ segs, SegState* __restrict__ states,
 //   k_pack_keys     byte offset of the block (scan of the group sums in shared memory + the sizes of
 //                   the blocks before it in its group), second loop (length flags, bit packing),
 //                   directory entry, header, value plane.
-// Both fetch a block's keys through the scan of the segment's chunk counts: rank r of the segment lives
-// in the chunk j with P[j] <= r < P[j+1], at entry chunk_slot0(j) + (r - P[j]) of the scratch arrays.
+// Both fetch a block's keys through the scan P of the segment's chunk counts (left in place of the
+// counts by k_plan_segments; 16 KB at most, so it stays in the L2): rank r of the segment lives in the
+// chunk j with P[j] <= r < P[j+1], at entry chunk_slot0(j) + (r - P[j]) of the scratch arrays.
 // A wave takes the block 1024 keys at a time; lane `lane` holds, for row k = 0..15, key 64*k + lane.
 struct KeyUnit {        // workgroup-uniform
     u32 seg, KB, l, nb, blk0, cb, nch;
@@ -626,14 +653,14 @@ __device__ __forceinline__ u32 segment_chunks(const SegInfo& s, u32 R) {
 // `seg0` is the segment record of a single-gradient call (a kernel argument, so no load is needed).
 __device__ __forceinline__ KeyUnit key_unit(const SegInfo& seg0, const SegInfo* __restrict__ segs,
                                             const SegState* __restrict__ states, u32 n_segments, u32 R,
-                                            u64 single_d, u64 unit, SegInfo* info_out) {
+                                            u64 unit, SegInfo* info_out) {
     KeyUnit ku;
     if (n_segments == 1) {
         *info_out = seg0;
         ku.seg = 0;
         ku.KB = seg0.block_keys;
-        ku.d = single_d;
-        ku.nb = (u32)((ku.d + ku.KB - 1) / ku.KB);
+        ku.d = states[0].d;
+        ku.nb = states[0].nb;
         ku.item_begin = 0;
         ku.blk0 = (u32)unit * kWaves;
     } else {
@@ -684,34 +711,6 @@ __device__ __forceinline__ void lds_excl_scan(T* arr, u32 n, T* scratch) {
         run += v[k];
     }
     if (t == 0) arr[n] = tot;
-    __syncthreads();
-}
-
-// P[j] = survivors of the segment in its chunks before j, j = 0..nch.  Every thread fetches 16
-// consecutive chunk counts straight from memory (no condition on the loads, so all are in flight at
-// once), the workgroup scans the 256 sums, and the prefixes go to shared memory.
-__device__ __forceinline__ void build_prefix(const u32* __restrict__ ccount, u32 cb, u32 nch, u32* P, u32* scratch) {
-    constexpr u32 PER = kMaxSegChunks / kThreads;
-    const u32 t = threadIdx.x;
-    __syncthreads();                                   // earlier readers of P are done
-    u32 v[PER], sum = 0;
-#pragma unroll
-    for (u32 k = 0; k < PER; ++k) {
-        const u32 j = t * PER + k;
-        const u32 x = ccount[cb + (j < nch ? j : 0u)];
-        v[k] = (j < nch) ? x : 0u;
-    }
-#pragma unroll
-    for (u32 k = 0; k < PER; ++k) sum += v[k];
-    u32 total;
-    u32 run = block_excl_scan(sum, scratch, &total);
-#pragma unroll
-    for (u32 k = 0; k < PER; ++k) {
-        const u32 j = t * PER + k;
-        if (j < nch) P[j] = run;
-        run += v[k];
-    }
-    if (t == 0) P[nch] = total;
     __syncthreads();
 }
 
@@ -842,8 +841,6 @@ __global__ void __launch_bounds__(kThreads)
 k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
                u32 R, const u32* __restrict__ ccount, const u32* __restrict__ skeys, BlockInfo* __restrict__ binfo,
                unsigned long long* __restrict__ gsum, u32 g_shift, Ctrl* ctrl) {
-    __shared__ u32 s_P[kMaxSegChunks + 1];
-    __shared__ u32 s_scan[kWaves + 1];
     __shared__ __attribute__((aligned(16))) u32 s_bufall[kWaves][kSub];
     __shared__ __attribute__((aligned(16))) uint8_t s_needall[kWaves][BIG ? kMaxKB : 16];   // bit lengths of a big block's deltas
     __shared__ u32 s_lutall[kWaves][33];
@@ -851,26 +848,11 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
     uint8_t* s_need = s_needall[w];
     u32* s_buf = s_bufall[w];
     u32* s_lut = s_lutall[w];
-    // a single gradient: its survivor count is the total of the scan of its chunk counts
-    u64 total_units, single_d = 0;
-    u32 cur_seg = 0xFFFFFFFFu;
-    if (n_segments == 1) {
-        const u32 nch = segment_chunks(seg0, R);
-        build_prefix(ccount, seg0.chunk_begin, nch, s_P, s_scan);
-        cur_seg = 0;
-        single_d = s_P[nch];
-        const u64 nb = (single_d + seg0.block_keys - 1) / seg0.block_keys;
-        total_units = ((nb ? nb : 1) + kWaves - 1) / kWaves;
-    } else {
-        total_units = ctrl->total_units;
-    }
+    const u64 total_units = ctrl->total_units;
     for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x) {
         SegInfo info;
-        const KeyUnit ku = key_unit(seg0, segs, states, n_segments, R, single_d, unit, &info);
-        if (ku.seg != cur_seg) {
-            build_prefix(ccount, ku.cb, ku.nch, s_P, s_scan);
-            cur_seg = ku.seg;
-        }
+        const KeyUnit ku = key_unit(seg0, segs, states, n_segments, R, unit, &info);
+        const u32* P = ccount + ku.cb;                      // the segment's chunk scan
         const u32 blk = ku.blk0 + w;
         if (blk >= (ku.nb ? ku.nb : 1u)) continue;
         const u64 item = ku.item_begin + blk;
@@ -891,8 +873,8 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
         // the key before the block (none for the segment's first block)
         u32 preKey = 0;
         if (first) {
-            const u32 jp = uniform(find_chunk_wave(s_P, ku.nch, first - 1, lane));
-            preKey = seg_keys[jp * stride + (first - 1 - s_P[jp])];
+            const u32 jp = uniform(find_chunk_wave(P, ku.nch, first - 1, lane));
+            preKey = seg_keys[jp * stride + (first - 1 - P[jp])];
         }
         // first loop of Algorithm 2: deltas and the longest of them (M = bit length of maxDelta)
         u64 unsorted = 0;
@@ -902,7 +884,7 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
             const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
             const u32 r0 = first + sub * kSub;
             u32 ent[kKeyRows], kb[kLaneKeys], dl[kLaneKeys];
-            gather_blocked(s_P, ku.nch, stride, seg_keys, r0, n, lane, s_buf, ent, kb);
+            gather_blocked(P, ku.nch, stride, seg_keys, r0, n, lane, s_buf, ent, kb);
             if (sub == 0) carry = uniform(preKey);              // (its fetch was in flight until here)
             if (n == kSub) lane_deltas<true>(kb, r0, n, lane, carry, dl, unsorted);
             else lane_deltas<false>(kb, r0, n, lane, carry, dl, unsorted);
@@ -964,10 +946,8 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
             const uint8_t* __restrict__ scodes, const BlockInfo* __restrict__ binfo,
             const unsigned long long* __restrict__ gsum, u32 g_shift, uint8_t* __restrict__ out, u64 out_capacity,
             u64* out_offsets, u32 single, u32* out_status, const Ctrl* ctrl) {
-    __shared__ u32 s_P[kMaxSegChunks + 1];
     __shared__ u64 s_G[kMaxGroups + 1];
     __shared__ u64 s_scan64[kWaves + 1];
-    __shared__ u32 s_scan[kWaves + 1];
     __shared__ __attribute__((aligned(16))) u32 s_payall[kWaves][kSub + 4];
     __shared__ u32 s_flgall[kWaves][kSub * 5 / 32 + 2];
     __shared__ u32 s_lutall[kWaves][33];
@@ -975,20 +955,7 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
     u32* s_pay = s_payall[w];
     u32* s_flg = s_flgall[w];
     u32* s_lut = s_lutall[w];
-    u64 total_units, total_items, single_d = 0;
-    u32 cur_seg = 0xFFFFFFFFu;
-    if (n_segments == 1) {
-        const u32 nch = segment_chunks(seg0, R);
-        build_prefix(ccount, seg0.chunk_begin, nch, s_P, s_scan);
-        cur_seg = 0;
-        single_d = s_P[nch];
-        const u64 nb = (single_d + seg0.block_keys - 1) / seg0.block_keys;
-        total_items = nb ? nb : 1;
-        total_units = (total_items + kWaves - 1) / kWaves;
-    } else {
-        total_items = ctrl->total_items;
-        total_units = ctrl->total_units;
-    }
+    const u64 total_items = ctrl->total_items, total_units = ctrl->total_units;
     if (blockIdx.x != 0 && blockIdx.x >= total_units) return;     // nothing to pack and nothing to report
     // byte offsets of the groups of work items
     const u32 ngroups = (u32)((total_items + (1ull << g_shift) - 1) >> g_shift);
@@ -1012,11 +979,12 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
 
     for (u32 i = lane; i < kSub * 5 / 32 + 2; i += 64) s_flg[i] = 0;
     u64 sbeg8 = 0;
+    u32 cur_seg = 0xFFFFFFFFu;
     for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x) {
         SegInfo info;
-        const KeyUnit ku = key_unit(seg0, segs, states, n_segments, R, single_d, unit, &info);
+        const KeyUnit ku = key_unit(seg0, segs, states, n_segments, R, unit, &info);
+        const u32* P = ccount + ku.cb;                      // the segment's chunk scan
         if (ku.seg != cur_seg) {
-            build_prefix(ccount, ku.cb, ku.nch, s_P, s_scan);
             cur_seg = ku.seg;
             sbeg8 = (n_segments == 1) ? 0ull : item_offset8(s_G, binfo, g_shift, ku.item_begin, lane);
         }
@@ -1081,7 +1049,7 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
             const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
             const u32 r0 = first + sub * kSub;
             u32 ent[kKeyRows], kb[kLaneKeys], dl[kLaneKeys], code[kKeyRows];
-            gather_blocked(s_P, ku.nch, stride, seg_keys, r0, n, lane, s_pay, ent, kb);    // borrows the payload window
+            gather_blocked(P, ku.nch, stride, seg_keys, r0, n, lane, s_pay, ent, kb);    // borrows the payload window
 #pragma unroll
             for (u32 q = 0; q < kKeyRows; ++q) code[q] = (q * 64u + lane < n) ? seg_codes[ent[q]] : 0u;
             // the payload window: word 0 carries the bits left over from the previous round
