@@ -254,3 +254,42 @@ def test_many_rounds_per_block_and_mixed_block_sizes():
     vals = np.full(n, 0.25, np.float32)
     for kb, l in ((2048, 1), (4096, 5), (4096, 2)):
         check_round_trip(keys, vals, 1.2, tau=128, l=l, kb=kb)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_shapes_and_parameters(seed):
+    """Seeded sweep over sizes (ragged tails of every kind), survival fractions, key gap structures and
+    codec parameters: stream bytes, keys and decoded values against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.choice([0, 1, 2, 63, 64, 65, 1023, 1025, 5000, 65_537, 200_003, 300_000]))
+    if seed % 3 == 0:
+        n = int(rng.integers(1, 400_000))
+    tau = int(rng.choice([1, 2, 7, 64, 100, 127, 128]))
+    l = int(rng.integers(1, 6))
+    kb = int(rng.choice([256, 512, 1024, 2048, 4096]))
+    keep = float(rng.choice([1.0, 0.9, 0.5, 0.1, 0.02, 0.001]))
+    scale = 10.0 ** rng.integers(-30, 20)
+    kind = seed % 4
+    if kind == 0:
+        vals = rng.laplace(0.0, scale, n)
+    elif kind == 1:
+        vals = rng.standard_normal(n) * scale * np.where(rng.random(n) < 0.05, 100.0, 1.0)
+    elif kind == 2:
+        vals = np.where(rng.random(n) < 0.3, 0.0, rng.standard_normal(n) * scale)     # many exact zeros
+    else:
+        vals = rng.choice(np.array([1.0, -1.0, 0.5, 3.0, 1e-3]), n) * scale             # many equal magnitudes
+    vals = vals.astype(np.float32)
+    gap_kind = seed % 5
+    if gap_kind == 0:
+        keys = np.arange(n, dtype=np.uint64)
+    elif gap_kind == 1:
+        keys = np.cumsum(rng.integers(1, 50, n)).astype(np.uint64)
+    elif gap_kind == 2:
+        keys = np.cumsum(rng.integers(1, max(2, (2 ** 32 - 2) // max(n, 1)), n)).astype(np.uint64)   # up to 2^32
+    elif gap_kind == 3:
+        keys = np.cumsum(np.where(rng.random(n) < 0.01, rng.integers(1, 5000, n), 1)).astype(np.uint64)
+    else:
+        keys = np.cumsum(2 ** rng.integers(0, 12, n)).astype(np.uint64)               # powers of two
+    assert n == 0 or keys[-1] < 2 ** 32
+    b = W.solve_base(vals, keep, tau) if n and np.any(vals != 0) else 1.1
+    check_round_trip(keys.astype(np.uint32), vals, b, tau, l, kb)
