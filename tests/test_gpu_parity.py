@@ -293,3 +293,29 @@ def test_random_shapes_and_parameters(seed):
     assert n == 0 or keys[-1] < 2 ** 32
     b = W.solve_base(vals, keep, tau) if n and np.any(vals != 0) else 1.1
     check_round_trip(keys.astype(np.uint32), vals, b, tau, l, kb)
+
+
+def test_random_bit_flips_in_a_stream_decode_like_the_oracle():
+    """Every single-bit corruption is either rejected by both decoders or decodes to the same pairs in
+    both (a flipped payload bit may still be a consistent stream)."""
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(77)
+    n = 3500
+    keys = np.cumsum(rng.integers(1, 3000, n)).astype(np.uint32)
+    vals = rng.laplace(0, 1.0, n).astype(np.float32)
+    rc, st = ref.compress(keys, vals, ref.params(W.solve_base(vals, 0.8), 128, 3, 1024))
+    assert rc == 0
+    d = int(st[40:48].view("<u8")[0])
+    assert d > 2100                                   # three blocks, the last one partial
+    positions = np.concatenate([rng.integers(0, 64 * 8, 12), rng.integers(64 * 8, st.size * 8, 84)])
+    for pos in positions:
+        s = st.copy()
+        s[int(pos) >> 3] ^= np.uint8(1 << (int(pos) & 7))
+        rc_ref, k_ref, v_ref = ref.decompress(s, capacity=d + 8)
+        rc, status, k, v = G.hip_decompress(s, capacity=d + 8)
+        assert rc == B.OK
+        assert status == rc_ref, (int(pos), status, rc_ref)
+        if status == 0:
+            assert np.array_equal(k, k_ref) and np.array_equal(v.view(np.uint32), v_ref.view(np.uint32)), int(pos)
+        else:
+            assert k.size == 0
