@@ -436,6 +436,46 @@ int fastsgd_ref_decompress_segmented(const uint8_t *streams, const uint64_t *str
 }
 
 /* ------------------------------------------------------------------------- *
+ * Decoder followed by the aggregation the decoded gradients are for (Section
+ * 2.1, Fig. 1: every worker's gradient is decoded and the gradients are added
+ * up before the model update): dense[k] += v for every decoded pair (k, v),
+ * stream after stream in the given order, every addition a binary32 addition.
+ * Reading: the paper does not say in which order or precision the workers'
+ * gradients are added; stream order and binary32 make the result reproducible
+ * (keys are unique inside a stream, so the order inside a stream is immaterial).
+ * A key >= dense_len is REF_ERR_BUFFER_TOO_SMALL.  On any error dense[] holds a
+ * partial sum.
+ * ------------------------------------------------------------------------- */
+int fastsgd_ref_decompress_accumulate(const uint8_t *streams, const uint64_t *stream_offsets,
+                                      uint32_t n_streams, float *dense, uint64_t dense_len,
+                                      uint64_t *count_out) {
+    if (count_out) *count_out = 0;
+    if (!streams || !stream_offsets || !count_out || (dense_len && !dense)) return REF_ERR_INVALID_ARG;
+    uint64_t total = 0;
+    for (uint32_t s = 0; s < n_streams; ++s) {
+        if (stream_offsets[s + 1] < stream_offsets[s]) return REF_ERR_INVALID_ARG;
+        const uint8_t *st = streams + stream_offsets[s];
+        uint64_t bytes = stream_offsets[s + 1] - stream_offsets[s];
+        uint64_t d = bytes >= REF_HEADER_BYTES ? get_u64(st + 40) : 0;
+        if (d > bytes) return REF_ERR_CORRUPT_STREAM;          /* every pair costs at least one byte */
+        uint32_t *k = (uint32_t *)malloc((d + 1) * sizeof(uint32_t));
+        float *v = (float *)malloc((d + 1) * sizeof(float));
+        if (!k || !v) { free(k); free(v); return REF_ERR_INVALID_ARG; }
+        uint64_t cnt = 0;
+        int rc = fastsgd_ref_decompress(st, bytes, k, v, d, &cnt);
+        for (uint64_t j = 0; rc == REF_OK && j < cnt; ++j) {
+            if (k[j] >= dense_len) rc = REF_ERR_BUFFER_TOO_SMALL;
+            else dense[k[j]] = dense[k[j]] + v[j];
+        }
+        free(k); free(v);
+        if (rc != REF_OK) return rc;
+        total += cnt;
+    }
+    *count_out = total;
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------- *
  * Debug view for the Fig. 3 worked example: Algorithm 2 literally (one global M,
  * no blocks), each token rendered the way the paper prints it: the flag as l
  * binary digits, then the delta as `len` binary digits, most significant first,

@@ -45,6 +45,8 @@ def lib():
         L.fastsgd_ref_compress_segmented.restype = C.c_int
         L.fastsgd_ref_decompress_segmented.argtypes = [vp, vp, u32, vp, vp, u64, vp]
         L.fastsgd_ref_decompress_segmented.restype = C.c_int
+        L.fastsgd_ref_decompress_accumulate.argtypes = [vp, vp, u32, vp, u64, C.POINTER(u64)]
+        L.fastsgd_ref_decompress_accumulate.restype = C.c_int
         L.fastsgd_ref_key_tokens_text.argtypes = [vp, u32, u32, C.c_char_p, u64]
         L.fastsgd_ref_key_tokens_text.restype = u32
         _lib = L
@@ -135,6 +137,17 @@ def decompress_segmented(streams, stream_offsets, capacity):
     rc = lib().fastsgd_ref_decompress_segmented(_ptr(s), _ptr(so), nseg, _ptr(keys), _ptr(vals),
                                                 int(capacity), _ptr(po))
     return rc, keys[:int(po[-1])].copy(), vals[:int(po[-1])].copy(), po
+
+
+def decompress_accumulate(streams, stream_offsets, dense):
+    """dense[k] += v for every pair of every stream, in stream order; dense (float32) is updated in
+    place.  Returns (status, pairs added)."""
+    s = np.ascontiguousarray(streams, dtype=np.uint8)
+    so = np.ascontiguousarray(stream_offsets, dtype=np.uint64)
+    assert dense.dtype == np.float32 and dense.flags.c_contiguous
+    cnt = C.c_uint64(0)
+    rc = lib().fastsgd_ref_decompress_accumulate(_ptr(s), _ptr(so), so.size - 1, _ptr(dense), dense.size, C.byref(cnt))
+    return rc, cnt.value
 
 
 def key_tokens_text(keys, flag_bits):
