@@ -126,6 +126,25 @@ fastsgd_status fastsgd_decompress_segmented(const void* d_streams, size_t total_
                                             uint64_t* d_pair_offsets, uint32_t* d_status,
                                             void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Decoder followed by the aggregation the decoded gradients are for (Section 2.1, Fig. 1: the
+ * workers' gradients are decoded and added up before the model update): for every pair (k, v)
+ * of every stream, d_dense[k] += v, a binary32 addition.  The streams are added one after the
+ * other in the given order (one decode launch per stream), keys are unique inside a stream, so
+ * the result does not depend on how the work is spread over the GPU.
+ *   d_streams, total_bytes   device, the concatenated streams of the workers, 8-byte aligned
+ *   d_stream_offsets   device u64[n_streams + 1]: byte offset of each stream, each a multiple of 8
+ *   d_dense, dense_len device float[dense_len], updated in place; a decoded key >= dense_len
+ *                      sets *d_status = FASTSGD_ERR_BUFFER_TOO_SMALL
+ *   d_count            device u64: pairs added, or 0 if *d_status != FASTSGD_OK (d_dense then
+ *                      holds an unspecified partial sum)
+ *   d_workspace        device, >= fastsgd_decompress_workspace_size(n_streams) bytes, 256-aligned
+ *   n_streams          1..65536 */
+fastsgd_status fastsgd_decompress_accumulate(const void* d_streams, size_t total_bytes,
+                                             const uint64_t* d_stream_offsets, uint32_t n_streams,
+                                             float* d_dense, uint64_t dense_len,
+                                             uint64_t* d_count, uint32_t* d_status,
+                                             void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Measurement aids (Section 4.2 of the paper reports encoder and decoder time separately; these
  * split each further, per kernel).  Same arguments and results as fastsgd_compress /
  * fastsgd_decompress, run `iterations` (1..4096) times back to back with a HIP event recorded on

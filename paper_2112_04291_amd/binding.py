@@ -17,6 +17,7 @@ STATUS_NAMES = ["OK", "INVALID_ARG", "BUFFER_TOO_SMALL", "NONFINITE", "UNSORTED_
 
 EXPORTS = ["fastsgd_compressed_size", "fastsgd_workspace_size", "fastsgd_decompress_workspace_size",
            "fastsgd_compress", "fastsgd_decompress", "fastsgd_compress_segmented", "fastsgd_decompress_segmented",
+           "fastsgd_decompress_accumulate",
            "fastsgd_profile_compress", "fastsgd_profile_decompress"]
 COMPRESS_KERNELS = ["abs_sum", "tables", "encode_values", "measure_keys", "pack_keys"]
 DECOMPRESS_KERNELS = ["setup", "decode"]
@@ -59,6 +60,8 @@ def lib():
         L.fastsgd_compress_segmented.restype = C.c_int
         L.fastsgd_decompress_segmented.argtypes = [vp, sz, vp, u32, vp, vp, u64, vp, vp, vp, sz, vp]
         L.fastsgd_decompress_segmented.restype = C.c_int
+        L.fastsgd_decompress_accumulate.argtypes = [vp, sz, vp, u32, vp, u64, vp, vp, vp, sz, vp]
+        L.fastsgd_decompress_accumulate.restype = C.c_int
         fp = C.POINTER(C.c_float)
         L.fastsgd_profile_compress.argtypes = [vp, vp, u64, PP, vp, sz, vp, vp, vp, sz, vp, u32, fp]
         L.fastsgd_profile_compress.restype = C.c_int
@@ -148,6 +151,13 @@ def decompress_segmented(streams, total_bytes, stream_offsets, n_segments, keys_
                                               _p(keys_out), _p(values_out), keys_out.numel(), _p(pair_offsets),
                                               _p(status), _p(workspace),
                                               workspace.numel() * workspace.element_size(), _stream())
+
+
+def decompress_accumulate(streams, total_bytes, stream_offsets, n_streams, dense, count, status, workspace):
+    """fastsgd_decompress_accumulate; stream_offsets is a device uint64 tensor, dense a device float32 tensor."""
+    return lib().fastsgd_decompress_accumulate(_p(streams), int(total_bytes), _p(stream_offsets), int(n_streams),
+                                               _p(dense), dense.numel(), _p(count), _p(status), _p(workspace),
+                                               workspace.numel() * workspace.element_size(), _stream())
 
 
 # ----------------------------------------------------------------------------------------------------

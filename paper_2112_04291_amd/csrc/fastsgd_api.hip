@@ -235,17 +235,47 @@ static fastsgd_status decompress_impl(const void* d_streams, size_t total_bytes,
     } else {
         hipLaunchKernelGGL(k_decode_clear, dim3(1), dim3(64), 0, stream, ctrl);
         hipLaunchKernelGGL(k_decode_setup, dim3(n_segments), dim3(128), 0, stream, streams, (u64)total_bytes,
-                           d_stream_offsets, n_segments, segs, ctrl, capacity, d_counts, d_status);
+                           d_stream_offsets, n_segments == 1 ? 1u : 0u, segs, ctrl, capacity, d_counts, d_status);
         if (n_segments > 1)
             hipLaunchKernelGGL(k_decode_plan, dim3(1), dim3(kThreads), 0, stream, segs, n_segments, capacity, ctrl,
-                               d_counts, d_status);
+                               d_counts, d_status, (u64*)nullptr);
     }
     marks.mark(stream);
     // every key costs at least one value byte, so bytes/256 bounds the number of key blocks
-    hipLaunchKernelGGL(k_decode, dim3(clamp_grid(((u64)total_bytes / 256 + n_segments + kWaves - 1) / kWaves, (u64)cus * 7)), dim3(kThreads), 0,
-                       stream, streams, segs, n_segments, ctrl, d_keys_out, d_values_out, d_counts,
-                       single ? 1u : n_segments + 1u, d_status);
+    hipLaunchKernelGGL(k_decode<false>, dim3(clamp_grid(((u64)total_bytes / 256 + n_segments + kWaves - 1) / kWaves, (u64)cus * 7)),
+                       dim3(kThreads), 0, stream, streams, segs, n_segments, ctrl, d_keys_out, d_values_out, d_counts,
+                       single ? 1u : n_segments + 1u, d_status, (float*)nullptr, (u64)0, 0u);
     marks.mark(stream);
+    return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
+}
+
+// Decode-and-aggregate: the streams are checked and planned like a batch, then one launch per stream
+// adds that stream's values into the dense array, so the additions happen stream after stream.
+static fastsgd_status accumulate_impl(const void* d_streams, size_t total_bytes, const u64* d_stream_offsets,
+                                      u32 n_streams, float* d_dense, u64 dense_len, u64* d_count, u32* d_status,
+                                      void* d_ws, size_t ws_bytes, void* hip_stream) {
+    if (!d_streams || !d_count || !d_status || !d_ws || !d_stream_offsets) return FASTSGD_ERR_INVALID_ARG;
+    if (n_streams < 1 || n_streams > kMaxSegments) return FASTSGD_ERR_INVALID_ARG;
+    if (((uintptr_t)d_streams & 7) || ((uintptr_t)d_ws & 255) || ((uintptr_t)d_dense & 3)) return FASTSGD_ERR_INVALID_ARG;
+    if (dense_len && !d_dense) return FASTSGD_ERR_INVALID_ARG;
+    const u64 off_counts = 256 + up((u64)n_streams * kDecSegBytes, 256);
+    if (ws_bytes < off_counts + ((u64)n_streams + 1) * 8) return FASTSGD_ERR_BUFFER_TOO_SMALL;
+    uint8_t* ws = static_cast<uint8_t*>(d_ws);
+    DecCtrl* ctrl = reinterpret_cast<DecCtrl*>(ws);
+    DecSeg* segs = reinterpret_cast<DecSeg*>(ws + 256);
+    u64* counts = reinterpret_cast<u64*>(ws + off_counts);
+    const uint8_t* streams = static_cast<const uint8_t*>(d_streams);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const u32 cus = cu_count();
+    hipLaunchKernelGGL(k_decode_clear, dim3(1), dim3(64), 0, stream, ctrl);
+    hipLaunchKernelGGL(k_decode_setup, dim3(n_streams), dim3(128), 0, stream, streams, (u64)total_bytes,
+                       d_stream_offsets, 0u, segs, ctrl, ~0ull, counts, d_status);
+    hipLaunchKernelGGL(k_decode_plan, dim3(1), dim3(kThreads), 0, stream, segs, n_streams, ~0ull, ctrl, counts, d_status,
+                       d_count);
+    const u32 grid = clamp_grid(((u64)total_bytes / 256 + 1 + kWaves - 1) / kWaves, (u64)cus * 7);
+    for (u32 s = 0; s < n_streams; ++s)
+        hipLaunchKernelGGL(k_decode<true>, dim3(grid), dim3(kThreads), 0, stream, streams, segs, n_streams, ctrl,
+                           (u32*)nullptr, (float*)nullptr, d_count, 1u, d_status, d_dense, dense_len, s);
     return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
 }
 
@@ -299,7 +329,15 @@ size_t fastsgd_workspace_size(uint64_t total_n, uint32_t n_segments, uint32_t mi
 
 size_t fastsgd_decompress_workspace_size(uint32_t n_segments) {
     if (n_segments < 1 || n_segments > kMaxSegments) return 0;
-    return (size_t)(256 + (u64)n_segments * kDecSegBytes);
+    return (size_t)(256 + up((u64)n_segments * kDecSegBytes, 256) + ((u64)n_segments + 1) * 8);
+}
+
+fastsgd_status fastsgd_decompress_accumulate(const void* d_streams, size_t total_bytes,
+                                             const uint64_t* d_stream_offsets, uint32_t n_streams, float* d_dense,
+                                             uint64_t dense_len, uint64_t* d_count, uint32_t* d_status,
+                                             void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+    return accumulate_impl(d_streams, total_bytes, d_stream_offsets, n_streams, d_dense, dense_len, d_count, d_status,
+                           d_workspace, workspace_bytes, hip_stream);
 }
 
 fastsgd_status fastsgd_compress(const uint32_t* d_keys, const float* d_values, uint64_t n, const fastsgd_params* p,

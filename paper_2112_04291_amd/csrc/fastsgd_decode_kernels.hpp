@@ -54,7 +54,7 @@ __device__ __forceinline__ void plan_streams(DecSeg* segs, u32 n_segments, u64 c
 
 __global__ void __launch_bounds__(128)
 k_decode_setup(const uint8_t* __restrict__ streams, u64 total_bytes, const u64* __restrict__ stream_offsets,
-               u32 n_segments, DecSeg* segs, DecCtrl* ctrl, u64 capacity, u64* out_counts, u32* out_status) {
+               u32 plan_inline, DecSeg* segs, DecCtrl* ctrl, u64 capacity, u64* out_counts, u32* out_status) {
     // launched with one workgroup per stream; for a batch k_decode_clear has reset ctrl beforehand
     __shared__ double s_P[129];
     __shared__ double s_sum;
@@ -62,7 +62,7 @@ k_decode_setup(const uint8_t* __restrict__ streams, u64 total_bytes, const u64* 
     const u32 seg = blockIdx.x, t = threadIdx.x;
     DecSeg* ds = &segs[seg];
     if (t == 0) {
-        if (n_segments == 1) ctrl->status = 0;
+        if (plan_inline) ctrl->status = 0;
         const u64 begin = stream_offsets ? stream_offsets[seg] : 0;
         const u64 end = stream_offsets ? stream_offsets[seg + 1] : total_bytes;
         bool ok = (begin <= end) && (end <= total_bytes) && ((begin & 7) == 0) && (end - begin >= kHeaderBytes);
@@ -104,7 +104,7 @@ k_decode_setup(const uint8_t* __restrict__ streams, u64 total_bytes, const u64* 
         const double sum = s_sum;
         ds->V[t] = (sum > 0.0) ? f64_to_f32_bits(sum / s_P[t + 1], false) : 0u;
     }
-    if (n_segments == 1) {           // a single stream needs no separate planning launch
+    if (plan_inline) {               // a single stream needs no separate planning launch
         __syncthreads();
         if (t == 0) plan_streams(segs, 1, capacity, ctrl, out_counts, stream_offsets == nullptr, out_status);
     }
@@ -117,7 +117,8 @@ __global__ void k_decode_clear(DecCtrl* ctrl) {
 // Batch: pair offsets and work-item numbering over the streams, one workgroup scanning 256 streams
 // at a time.
 __global__ void __launch_bounds__(kThreads)
-k_decode_plan(DecSeg* segs, u32 n_segments, u64 capacity, DecCtrl* ctrl, u64* out_counts, u32* out_status) {
+k_decode_plan(DecSeg* segs, u32 n_segments, u64 capacity, DecCtrl* ctrl, u64* out_counts, u32* out_status,
+              u64* total_out) {
     __shared__ u64 s_wave[2][kWaves];
     __shared__ u64 s_carry[2];
     const u32 t = threadIdx.x, lane = lane_id(), w = wave_id();
@@ -155,6 +156,7 @@ k_decode_plan(DecSeg* segs, u32 n_segments, u64 capacity, DecCtrl* ctrl, u64* ou
         ctrl->total_items = ok ? items : 0;
         ctrl->total_pairs = ok ? pairs : 0;
         out_counts[n_segments] = ok ? pairs : 0;
+        if (total_out) *total_out = ok ? pairs : 0;
         *out_status = status;
     }
 }
@@ -176,13 +178,16 @@ __device__ __forceinline__ u32 find_dec_segment(const DecSeg* segs, u32 n_segmen
 //   go through shared memory once more so that the stores to the output arrays are coalesced.
 // The waves of a workgroup never synchronise.
 
-// FULL: the round has all 1024 keys (no key-index tests).  Returns false if the stream is corrupt.
-template <bool FULL>
+// FULL: the round has all 1024 keys (no key-index tests).  ACCUM: instead of storing the pairs, add
+// every value to dense[key] (keys are unique inside a stream, so plain read-add-write is enough);
+// a key >= dense_len sets too_big.  Returns false if the stream is corrupt.
+template <bool FULL, bool ACCUM>
 __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round, const u32* __restrict__ psrc,
                                              u32 pw_total, const uint8_t* __restrict__ codes_round, u32 n, u32 l,
                                              u32 M, u32 tau, u32 pbits, u32& pbit, u32& carry, u32 lane, u32* s_pay,
                                              u32* s_flg, const u32* s_V, u32* __restrict__ keys_dst,
-                                             float* __restrict__ values_dst) {
+                                             float* __restrict__ values_dst, float* __restrict__ dense, u64 dense_len,
+                                             bool& too_big) {
     const u32 nfw = (n * l + 31u) >> 5;
     const u32 pw0 = pbit >> 5, wbits = pbit & 31u;
     u32 npw = ((wbits + n * M + 31u) >> 5) + 1u;           // words this round can reach (+1: windows)
@@ -282,6 +287,27 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         badcode |= c >= tau && (FULL || lane * kLaneKeys + k < n);
         vb[k] = s_V[c] | ((byte >> 7) << 31);
     }
+    if (ACCUM) {
+        bool big = false;
+#pragma unroll
+        for (u32 k = 0; k < kLaneKeys; ++k) {
+            if (FULL || lane * kLaneKeys + k < n) {
+                if (kp[k] < dense_len) dense[kp[k]] = dense[kp[k]] + __uint_as_float(vb[k]);
+                else big = true;
+            }
+        }
+        const u32 li = (n - 1u) & (kLaneKeys - 1u);             // the round's last key sits in lane (n-1)/16
+        u32 lastk = kp[kLaneKeys - 1];
+        if (!FULL) {
+#pragma unroll
+            for (u32 k = 0; k < kLaneKeys; ++k) if (k == li) lastk = kp[k];
+        }
+        carry = read_lane(lastk, uniform((n - 1u) / kLaneKeys));
+        wave_lds_sync();
+        pbit += roundbits;
+        too_big |= __any(big);
+        return !(__any(ovf) || __any(badcode));
+    }
     // through shared memory to the output arrays: lane-major in, row-major out
     wave_lds_sync();
     uint4* t4 = reinterpret_cast<uint4*>(s_pay) + lane * 4u;
@@ -308,10 +334,13 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
     return !(__any(ovf) || __any(badcode));
 }
 
+// ACCUM: the launch handles the key blocks of stream `only` alone and adds its values into `dense`
+// (one launch per stream, so that the additions happen stream after stream).
+template <bool ACCUM>
 __global__ void __launch_bounds__(kThreads)
 k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u32 n_segments, DecCtrl* ctrl,
          u32* __restrict__ keys_out, float* __restrict__ values_out, u64* out_counts, u32 n_counts,
-         u32* out_status) {
+         u32* out_status, float* __restrict__ dense, u64 dense_len, u32 only) {
     __shared__ __attribute__((aligned(16))) u32 s_payall[kWaves][kSub + 4];
     __shared__ u32 s_flgall[kWaves][kSub * 5 / 32 + 4];
     __shared__ u32 s_Vall[kWaves][128];
@@ -319,11 +348,12 @@ k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u
     u32* s_pay = s_payall[w];
     u32* s_flg = s_flgall[w];
     u32* s_V = s_Vall[w];
-    const u64 total_items = ctrl->total_items;
+    u64 item_lo = 0, item_hi = ctrl->total_items;
+    if (ACCUM && item_hi) { item_lo = segs[only].item_begin; item_hi = item_lo + segs[only].nb; }
     u32 cur_seg = 0xFFFFFFFFu;
 
-    for (u64 item = (u64)blockIdx.x * kWaves + w; item < total_items; item += (u64)gridDim.x * kWaves) {
-        const u32 seg = (n_segments == 1) ? 0u : uniform(find_dec_segment(segs, n_segments, item));
+    for (u64 item = item_lo + (u64)blockIdx.x * kWaves + w; item < item_hi; item += (u64)gridDim.x * kWaves) {
+        const u32 seg = ACCUM ? only : ((n_segments == 1) ? 0u : uniform(find_dec_segment(segs, n_segments, item)));
         const DecSeg* ds = &segs[seg];
         const u32 KB = uniform(ds->KB), l = uniform(ds->l), tau = uniform(ds->tau), nb = uniform(ds->nb);
         const u64 d = ds->d;
@@ -357,19 +387,23 @@ k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u
             const u64 out0 = uniform64(ds->pair_begin + first);
             u32 pbit = 0;                  // payload bits consumed by the rounds before
             u32 carry = preKey;            // key before the round in hand
-            bool ok = true;
+            bool ok = true, too_big = false;
             for (u32 sub = 0; sub < nsub && ok; ++sub) {
                 const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
+                u32* kd = ACCUM ? nullptr : keys_out + out0 + sub * kSub;
+                float* vd = ACCUM ? nullptr : values_out + out0 + sub * kSub;
                 if (n == kSub)
-                    ok = decode_round<true>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * kSub, n, l, M, tau, pbits,
-                                            pbit, carry, lane, s_pay, s_flg, s_V, keys_out + out0 + sub * kSub,
-                                            values_out + out0 + sub * kSub);
+                    ok = decode_round<true, ACCUM>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * kSub, n, l, M, tau,
+                                                   pbits, pbit, carry, lane, s_pay, s_flg, s_V, kd, vd, dense, dense_len,
+                                                   too_big);
                 else
-                    ok = decode_round<false>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * kSub, n, l, M, tau, pbits,
-                                             pbit, carry, lane, s_pay, s_flg, s_V, keys_out + out0 + sub * kSub,
-                                             values_out + out0 + sub * kSub);
+                    ok = decode_round<false, ACCUM>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * kSub, n, l, M, tau,
+                                                    pbits, pbit, carry, lane, s_pay, s_flg, s_V, kd, vd, dense, dense_len,
+                                                    too_big);
             }
             bad = !ok || (pbit != pbits) || (has_next && carry != next_pre);
+            if (!bad && too_big && lane == 0)
+                dec_fail(ctrl, FASTSGD_ERR_BUFFER_TOO_SMALL, out_status, out_counts, n_counts);
         }
         if (bad && lane == 0) dec_fail(ctrl, FASTSGD_ERR_CORRUPT_STREAM, out_status, out_counts, n_counts);
     }
