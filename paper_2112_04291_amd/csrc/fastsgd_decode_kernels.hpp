@@ -288,14 +288,21 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         vb[k] = s_V[c] | ((byte >> 7) << 31);
     }
     if (ACCUM) {
+        // all sixteen reads are issued before the first write: the keys of a valid stream are distinct,
+        // and a stream that is not valid leaves an unspecified sum anyway
         bool big = false;
+        float cur[kLaneKeys];
+        bool on[kLaneKeys];
 #pragma unroll
         for (u32 k = 0; k < kLaneKeys; ++k) {
-            if (FULL || lane * kLaneKeys + k < n) {
-                if (kp[k] < dense_len) dense[kp[k]] = dense[kp[k]] + __uint_as_float(vb[k]);
-                else big = true;
-            }
+            const bool have = FULL || lane * kLaneKeys + k < n;
+            on[k] = have && kp[k] < dense_len;
+            big |= have && !on[k];
+            cur[k] = on[k] ? dense[kp[k]] : 0.0f;
         }
+#pragma unroll
+        for (u32 k = 0; k < kLaneKeys; ++k)
+            if (on[k]) dense[kp[k]] = cur[k] + __uint_as_float(vb[k]);
         const u32 li = (n - 1u) & (kLaneKeys - 1u);             // the round's last key sits in lane (n-1)/16
         u32 lastk = kp[kLaneKeys - 1];
         if (!FULL) {
