@@ -476,6 +476,48 @@ int fastsgd_ref_decompress_accumulate(const uint8_t *streams, const uint64_t *st
 }
 
 /* ------------------------------------------------------------------------- *
+ * Decoder followed by the model update of Section 4.1 (Adam SGD), applied at
+ * the decoded keys only: for every decoded pair (k, g)
+ *     m[k]     = beta1 * m[k] + (1 - beta1) * g
+ *     v[k]     = beta2 * v[k] + (1 - beta2) * g * g
+ *     theta[k] = theta[k] - eta * m[k] / sqrt(v[k] + eps)
+ * with the new m[k], v[k] on the right of the third line.  Readings: the two
+ * equations of Section 4.1 are taken as printed, i.e. eps is under the square
+ * root and there is no bias correction; coordinates whose gradient did not
+ * survive the filter are not touched (their g is not known to the receiver).
+ * The three arrays hold binary32; the arithmetic here is binary64 on the stored
+ * values, each result rounded to binary32 when it is stored.
+ * A key >= dim is REF_ERR_BUFFER_TOO_SMALL (arrays then partly updated).
+ * ------------------------------------------------------------------------- */
+int fastsgd_ref_decompress_adam(const uint8_t *stream, uint64_t bytes, float *theta, float *m, float *v,
+                                uint64_t dim, double eta, double beta1, double beta2, double eps,
+                                uint64_t *count_out) {
+    if (count_out) *count_out = 0;
+    if (!stream || !count_out || (dim && (!theta || !m || !v))) return REF_ERR_INVALID_ARG;
+    uint64_t d = bytes >= REF_HEADER_BYTES ? get_u64(stream + 40) : 0;
+    if (d > bytes) return REF_ERR_CORRUPT_STREAM;              /* every pair costs at least one byte */
+    uint32_t *k = (uint32_t *)malloc((d + 1) * sizeof(uint32_t));
+    float *g = (float *)malloc((d + 1) * sizeof(float));
+    if (!k || !g) { free(k); free(g); return REF_ERR_INVALID_ARG; }
+    uint64_t cnt = 0;
+    int rc = fastsgd_ref_decompress(stream, bytes, k, g, d, &cnt);
+    for (uint64_t j = 0; rc == REF_OK && j < cnt; ++j) {
+        if (k[j] >= dim) { rc = REF_ERR_BUFFER_TOO_SMALL; break; }
+        const uint32_t i = k[j];
+        const double gj = (double)g[j];
+        const double mt = beta1 * (double)m[i] + (1.0 - beta1) * gj;
+        const double vt = beta2 * (double)v[i] + (1.0 - beta2) * gj * gj;
+        m[i] = (float)mt;
+        v[i] = (float)vt;
+        theta[i] = (float)((double)theta[i] - eta * (double)m[i] / sqrt((double)v[i] + eps));
+    }
+    free(k); free(g);
+    if (rc != REF_OK) return rc;
+    *count_out = cnt;
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------- *
  * Debug view for the Fig. 3 worked example: Algorithm 2 literally (one global M,
  * no blocks), each token rendered the way the paper prints it: the flag as l
  * binary digits, then the delta as `len` binary digits, most significant first,

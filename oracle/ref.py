@@ -47,6 +47,9 @@ def lib():
         L.fastsgd_ref_decompress_segmented.restype = C.c_int
         L.fastsgd_ref_decompress_accumulate.argtypes = [vp, vp, u32, vp, u64, C.POINTER(u64)]
         L.fastsgd_ref_decompress_accumulate.restype = C.c_int
+        L.fastsgd_ref_decompress_adam.argtypes = [vp, u64, vp, vp, vp, u64, C.c_double, C.c_double, C.c_double,
+                                                  C.c_double, C.POINTER(u64)]
+        L.fastsgd_ref_decompress_adam.restype = C.c_int
         L.fastsgd_ref_key_tokens_text.argtypes = [vp, u32, u32, C.c_char_p, u64]
         L.fastsgd_ref_key_tokens_text.restype = u32
         _lib = L
@@ -147,6 +150,18 @@ def decompress_accumulate(streams, stream_offsets, dense):
     assert dense.dtype == np.float32 and dense.flags.c_contiguous
     cnt = C.c_uint64(0)
     rc = lib().fastsgd_ref_decompress_accumulate(_ptr(s), _ptr(so), so.size - 1, _ptr(dense), dense.size, C.byref(cnt))
+    return rc, cnt.value
+
+
+def decompress_adam(stream, theta, m, v, eta, beta1=0.9, beta2=0.999, eps=1e-8):
+    """Adam step of Section 4.1 at the decoded keys of one stream; theta, m, v (float32) are updated in
+    place.  Returns (status, pairs applied)."""
+    s = np.ascontiguousarray(stream, dtype=np.uint8)
+    for a in (theta, m, v):
+        assert a.dtype == np.float32 and a.flags.c_contiguous and a.size == theta.size
+    cnt = C.c_uint64(0)
+    rc = lib().fastsgd_ref_decompress_adam(_ptr(s), s.size, _ptr(theta), _ptr(m), _ptr(v), theta.size, float(eta),
+                                           float(beta1), float(beta2), float(eps), C.byref(cnt))
     return rc, cnt.value
 
 
