@@ -145,6 +145,33 @@ fastsgd_status fastsgd_decompress_accumulate(const void* d_streams, size_t total
                                              uint64_t* d_count, uint32_t* d_status,
                                              void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Hyper-parameters of the Adam SGD update of Section 4.1 (paper: beta1 = 0.9, beta2 = 0.999,
+ * eps = 1e-8, eta tuned by grid search). */
+typedef struct {
+    double eta;    /* learning rate                 */
+    double beta1;  /* 0..1                          */
+    double beta2;  /* 0..1                          */
+    double eps;    /* >= 0, added under the root    */
+} fastsgd_adam;
+
+/* Decoder followed by the model update of Section 4.1 at the decoded keys: for every pair (k, g)
+ * of the stream,  m[k] = beta1 m[k] + (1 - beta1) g,  v[k] = beta2 v[k] + (1 - beta2) g^2,
+ * theta[k] -= eta m[k] / sqrt(v[k] + eps)  (the two equations as printed: eps under the root, no
+ * bias correction), in binary32.  Coordinates that are not in the stream are not touched.
+ *   d_stream, stream_bytes   device, 8-byte aligned: one stream (e.g. the re-encoded aggregate,
+ *                      or one worker's gradient)
+ *   d_theta, d_m, d_v  device float[dim], updated in place; a decoded key >= dim sets
+ *                      *d_status = FASTSGD_ERR_BUFFER_TOO_SMALL
+ *   h                  host
+ *   d_count            device u64: pairs applied, or 0 if *d_status != FASTSGD_OK (the arrays then
+ *                      hold an unspecified partial update)
+ *   d_workspace        device, >= fastsgd_decompress_workspace_size(1) bytes, 256-byte aligned */
+fastsgd_status fastsgd_decompress_adam(const void* d_stream, size_t stream_bytes,
+                                       float* d_theta, float* d_m, float* d_v, uint64_t dim,
+                                       const fastsgd_adam* h,
+                                       uint64_t* d_count, uint32_t* d_status,
+                                       void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Measurement aids (Section 4.2 of the paper reports encoder and decoder time separately; these
  * split each further, per kernel).  Same arguments and results as fastsgd_compress /
  * fastsgd_decompress, run `iterations` (1..4096) times back to back with a HIP event recorded on

@@ -17,7 +17,7 @@ STATUS_NAMES = ["OK", "INVALID_ARG", "BUFFER_TOO_SMALL", "NONFINITE", "UNSORTED_
 
 EXPORTS = ["fastsgd_compressed_size", "fastsgd_workspace_size", "fastsgd_decompress_workspace_size",
            "fastsgd_compress", "fastsgd_decompress", "fastsgd_compress_segmented", "fastsgd_decompress_segmented",
-           "fastsgd_decompress_accumulate",
+           "fastsgd_decompress_accumulate", "fastsgd_decompress_adam",
            "fastsgd_profile_compress", "fastsgd_profile_decompress"]
 COMPRESS_KERNELS = ["abs_sum", "tables", "encode_values", "measure_keys", "pack_keys"]
 DECOMPRESS_KERNELS = ["setup", "decode"]
@@ -27,6 +27,11 @@ class Params(C.Structure):
     """fastsgd_params"""
     _fields_ = [("base", C.c_double), ("tau", C.c_uint32), ("flag_bits", C.c_uint32),
                 ("block_keys", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class Adam(C.Structure):
+    """fastsgd_adam"""
+    _fields_ = [("eta", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double)]
 
 
 def params(base=1.1, tau=128, flag_bits=2, block_keys=1024):
@@ -62,6 +67,8 @@ def lib():
         L.fastsgd_decompress_segmented.restype = C.c_int
         L.fastsgd_decompress_accumulate.argtypes = [vp, sz, vp, u32, vp, u64, vp, vp, vp, sz, vp]
         L.fastsgd_decompress_accumulate.restype = C.c_int
+        L.fastsgd_decompress_adam.argtypes = [vp, sz, vp, vp, vp, u64, C.POINTER(Adam), vp, vp, vp, sz, vp]
+        L.fastsgd_decompress_adam.restype = C.c_int
         fp = C.POINTER(C.c_float)
         L.fastsgd_profile_compress.argtypes = [vp, vp, u64, PP, vp, sz, vp, vp, vp, sz, vp, u32, fp]
         L.fastsgd_profile_compress.restype = C.c_int
@@ -151,6 +158,14 @@ def decompress_segmented(streams, total_bytes, stream_offsets, n_segments, keys_
                                               _p(keys_out), _p(values_out), keys_out.numel(), _p(pair_offsets),
                                               _p(status), _p(workspace),
                                               workspace.numel() * workspace.element_size(), _stream())
+
+
+def decompress_adam(stream, stream_bytes, theta, m, v, eta, beta1, beta2, eps, count, status, workspace):
+    """fastsgd_decompress_adam; theta, m, v are device float32 tensors of one length."""
+    h = Adam(float(eta), float(beta1), float(beta2), float(eps))
+    return lib().fastsgd_decompress_adam(_p(stream), int(stream_bytes), _p(theta), _p(m), _p(v), theta.numel(),
+                                         C.byref(h), _p(count), _p(status), _p(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream())
 
 
 def decompress_accumulate(streams, total_bytes, stream_offsets, n_streams, dense, count, status, workspace):

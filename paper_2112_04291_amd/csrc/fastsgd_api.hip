@@ -242,9 +242,9 @@ static fastsgd_status decompress_impl(const void* d_streams, size_t total_bytes,
     }
     marks.mark(stream);
     // every key costs at least one value byte, so bytes/256 bounds the number of key blocks
-    hipLaunchKernelGGL(k_decode<false>, dim3(clamp_grid(((u64)total_bytes / 256 + n_segments + kWaves - 1) / kWaves, (u64)cus * 7)),
+    hipLaunchKernelGGL(k_decode<kStore>, dim3(clamp_grid(((u64)total_bytes / 256 + n_segments + kWaves - 1) / kWaves, (u64)cus * 7)),
                        dim3(kThreads), 0, stream, streams, segs, n_segments, ctrl, d_keys_out, d_values_out, d_counts,
-                       single ? 1u : n_segments + 1u, d_status, (float*)nullptr, (u64)0, 0u);
+                       single ? 1u : n_segments + 1u, d_status, (float*)nullptr, (u64)0, 0u, AdamArgs());
     marks.mark(stream);
     return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
 }
@@ -274,8 +274,42 @@ static fastsgd_status accumulate_impl(const void* d_streams, size_t total_bytes,
                        d_count);
     const u32 grid = clamp_grid(((u64)total_bytes / 256 + 1 + kWaves - 1) / kWaves, (u64)cus * 7);
     for (u32 s = 0; s < n_streams; ++s)
-        hipLaunchKernelGGL(k_decode<true>, dim3(grid), dim3(kThreads), 0, stream, streams, segs, n_streams, ctrl,
-                           (u32*)nullptr, (float*)nullptr, d_count, 1u, d_status, d_dense, dense_len, s);
+        hipLaunchKernelGGL(k_decode<kAccum>, dim3(grid), dim3(kThreads), 0, stream, streams, segs, n_streams, ctrl,
+                           (u32*)nullptr, (float*)nullptr, d_count, 1u, d_status, d_dense, dense_len, s, AdamArgs());
+    return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
+}
+
+// Decode-and-update: one stream, the Adam step of Section 4.1 at its keys.
+static fastsgd_status adam_impl(const void* d_stream, size_t stream_bytes, float* d_theta, float* d_m, float* d_v,
+                                u64 dim, const fastsgd_adam* h, u64* d_count, u32* d_status, void* d_ws,
+                                size_t ws_bytes, void* hip_stream) {
+    if (!d_stream || !d_count || !d_status || !d_ws || !h) return FASTSGD_ERR_INVALID_ARG;
+    if (((uintptr_t)d_stream & 7) || ((uintptr_t)d_ws & 255)) return FASTSGD_ERR_INVALID_ARG;
+    if (((uintptr_t)d_theta & 3) || ((uintptr_t)d_m & 3) || ((uintptr_t)d_v & 3)) return FASTSGD_ERR_INVALID_ARG;
+    if (dim && (!d_theta || !d_m || !d_v)) return FASTSGD_ERR_INVALID_ARG;
+    if (!(h->eta == h->eta) || !(h->beta1 >= 0.0 && h->beta1 <= 1.0) || !(h->beta2 >= 0.0 && h->beta2 <= 1.0) ||
+        !(h->eps >= 0.0))
+        return FASTSGD_ERR_INVALID_ARG;
+    if (ws_bytes < kDecCtrlBytes + 192 + kDecSegBytes) return FASTSGD_ERR_BUFFER_TOO_SMALL;
+    uint8_t* ws = static_cast<uint8_t*>(d_ws);
+    DecCtrl* ctrl = reinterpret_cast<DecCtrl*>(ws);
+    DecSeg* segs = reinterpret_cast<DecSeg*>(ws + 256);
+    const uint8_t* streams = static_cast<const uint8_t*>(d_stream);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    AdamArgs a;
+    a.m = d_m;
+    a.v = d_v;
+    a.eta = (float)h->eta;
+    a.beta1 = (float)h->beta1;
+    a.one_minus_beta1 = (float)(1.0 - h->beta1);
+    a.beta2 = (float)h->beta2;
+    a.one_minus_beta2 = (float)(1.0 - h->beta2);
+    a.eps = (float)h->eps;
+    hipLaunchKernelGGL(k_decode_setup, dim3(1), dim3(128), 0, stream, streams, (u64)stream_bytes, (const u64*)nullptr, 1u,
+                       segs, ctrl, ~0ull, d_count, d_status);
+    const u32 grid = clamp_grid(((u64)stream_bytes / 256 + 1 + kWaves - 1) / kWaves, (u64)cu_count() * 7);
+    hipLaunchKernelGGL(k_decode<kAdam>, dim3(grid), dim3(kThreads), 0, stream, streams, segs, 1u, ctrl, (u32*)nullptr,
+                       (float*)nullptr, d_count, 1u, d_status, d_theta, dim, 0u, a);
     return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
 }
 
@@ -338,6 +372,13 @@ fastsgd_status fastsgd_decompress_accumulate(const void* d_streams, size_t total
                                              void* d_workspace, size_t workspace_bytes, void* hip_stream) {
     return accumulate_impl(d_streams, total_bytes, d_stream_offsets, n_streams, d_dense, dense_len, d_count, d_status,
                            d_workspace, workspace_bytes, hip_stream);
+}
+
+fastsgd_status fastsgd_decompress_adam(const void* d_stream, size_t stream_bytes, float* d_theta, float* d_m, float* d_v,
+                                       uint64_t dim, const fastsgd_adam* h, uint64_t* d_count, uint32_t* d_status,
+                                       void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+    return adam_impl(d_stream, stream_bytes, d_theta, d_m, d_v, dim, h, d_count, d_status, d_workspace, workspace_bytes,
+                     hip_stream);
 }
 
 fastsgd_status fastsgd_compress(const uint32_t* d_keys, const float* d_values, uint64_t n, const fastsgd_params* p,

@@ -178,16 +178,27 @@ __device__ __forceinline__ u32 find_dec_segment(const DecSeg* segs, u32 n_segmen
 //   go through shared memory once more so that the stores to the output arrays are coalesced.
 // The waves of a workgroup never synchronise.
 
-// FULL: the round has all 1024 keys (no key-index tests).  ACCUM: instead of storing the pairs, add
-// every value to dense[key] (keys are unique inside a stream, so plain read-add-write is enough);
-// a key >= dense_len sets too_big.  Returns false if the stream is corrupt.
-template <bool FULL, bool ACCUM>
+// What a decode launch does with the pairs: store them, add every value to dense[key] (Section 2.1,
+// aggregation), or apply the Adam step of Section 4.1 at every key.
+enum : int { kStore = 0, kAccum = 1, kAdam = 2 };
+
+// Adam state and hyper-parameters (Section 4.1); theta is passed as the dense array.
+struct AdamArgs {
+    float* m;
+    float* v;
+    float eta, beta1, one_minus_beta1, beta2, one_minus_beta2, eps;
+};
+
+// FULL: the round has all 1024 keys (no key-index tests).  MODE kAccum / kAdam: instead of storing the
+// pairs, update the dense arrays at every key (keys are unique inside a stream, so plain
+// read-modify-write is enough); a key >= dense_len sets too_big.  Returns false if the stream is corrupt.
+template <bool FULL, int MODE>
 __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round, const u32* __restrict__ psrc,
                                              u32 pw_total, const uint8_t* __restrict__ codes_round, u32 n, u32 l,
                                              u32 M, u32 tau, u32 pbits, u32& pbit, u32& carry, u32 lane, u32* s_pay,
                                              u32* s_flg, const u32* s_V, u32* __restrict__ keys_dst,
                                              float* __restrict__ values_dst, float* __restrict__ dense, u64 dense_len,
-                                             bool& too_big) {
+                                             const AdamArgs& adam, bool& too_big) {
     const u32 nfw = (n * l + 31u) >> 5;
     const u32 pw0 = pbit >> 5, wbits = pbit & 31u;
     u32 npw = ((wbits + n * M + 31u) >> 5) + 1u;           // words this round can reach (+1: windows)
@@ -287,9 +298,9 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         badcode |= c >= tau && (FULL || lane * kLaneKeys + k < n);
         vb[k] = s_V[c] | ((byte >> 7) << 31);
     }
-    if (ACCUM) {
-        // all sixteen reads are issued before the first write: the keys of a valid stream are distinct,
-        // and a stream that is not valid leaves an unspecified sum anyway
+    if (MODE != kStore) {
+        // all reads of a lane's sixteen keys are issued before the first write: the keys of a valid
+        // stream are distinct, and a stream that is not valid leaves unspecified arrays anyway
         bool big = false;
         float cur[kLaneKeys];
         bool on[kLaneKeys];
@@ -300,9 +311,30 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
             big |= have && !on[k];
             cur[k] = on[k] ? dense[kp[k]] : 0.0f;
         }
+        if (MODE == kAccum) {
 #pragma unroll
-        for (u32 k = 0; k < kLaneKeys; ++k)
-            if (on[k]) dense[kp[k]] = cur[k] + __uint_as_float(vb[k]);
+            for (u32 k = 0; k < kLaneKeys; ++k)
+                if (on[k]) dense[kp[k]] = cur[k] + __uint_as_float(vb[k]);
+        } else {
+            // m = b1 m + (1 - b1) g;  v = b2 v + (1 - b2) g^2;  theta -= eta m / sqrt(v + eps)
+            float mo[kLaneKeys], vo[kLaneKeys];
+#pragma unroll
+            for (u32 k = 0; k < kLaneKeys; ++k) {
+                mo[k] = on[k] ? adam.m[kp[k]] : 0.0f;
+                vo[k] = on[k] ? adam.v[kp[k]] : 0.0f;
+            }
+#pragma unroll
+            for (u32 k = 0; k < kLaneKeys; ++k) {
+                if (on[k]) {
+                    const float g = __uint_as_float(vb[k]);
+                    const float mt = adam.beta1 * mo[k] + adam.one_minus_beta1 * g;
+                    const float vt = adam.beta2 * vo[k] + adam.one_minus_beta2 * g * g;
+                    adam.m[kp[k]] = mt;
+                    adam.v[kp[k]] = vt;
+                    dense[kp[k]] = cur[k] - adam.eta * mt / __fsqrt_rn(vt + adam.eps);
+                }
+            }
+        }
         const u32 li = (n - 1u) & (kLaneKeys - 1u);             // the round's last key sits in lane (n-1)/16
         u32 lastk = kp[kLaneKeys - 1];
         if (!FULL) {
@@ -341,13 +373,13 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
     return !(__any(ovf) || __any(badcode));
 }
 
-// ACCUM: the launch handles the key blocks of stream `only` alone and adds its values into `dense`
-// (one launch per stream, so that the additions happen stream after stream).
-template <bool ACCUM>
+// MODE kAccum / kAdam: the launch handles the key blocks of stream `only` alone and updates the dense
+// arrays (one launch per stream, so that the updates happen stream after stream).
+template <int MODE>
 __global__ void __launch_bounds__(kThreads)
 k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u32 n_segments, DecCtrl* ctrl,
          u32* __restrict__ keys_out, float* __restrict__ values_out, u64* out_counts, u32 n_counts,
-         u32* out_status, float* __restrict__ dense, u64 dense_len, u32 only) {
+         u32* out_status, float* __restrict__ dense, u64 dense_len, u32 only, AdamArgs adam) {
     __shared__ __attribute__((aligned(16))) u32 s_payall[kWaves][kSub + 4];
     __shared__ u32 s_flgall[kWaves][kSub * 5 / 32 + 4];
     __shared__ u32 s_Vall[kWaves][128];
@@ -356,11 +388,11 @@ k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u
     u32* s_flg = s_flgall[w];
     u32* s_V = s_Vall[w];
     u64 item_lo = 0, item_hi = ctrl->total_items;
-    if (ACCUM && item_hi) { item_lo = segs[only].item_begin; item_hi = item_lo + segs[only].nb; }
+    if (MODE != kStore && item_hi) { item_lo = segs[only].item_begin; item_hi = item_lo + segs[only].nb; }
     u32 cur_seg = 0xFFFFFFFFu;
 
     for (u64 item = item_lo + (u64)blockIdx.x * kWaves + w; item < item_hi; item += (u64)gridDim.x * kWaves) {
-        const u32 seg = ACCUM ? only : ((n_segments == 1) ? 0u : uniform(find_dec_segment(segs, n_segments, item)));
+        const u32 seg = MODE != kStore ? only : ((n_segments == 1) ? 0u : uniform(find_dec_segment(segs, n_segments, item)));
         const DecSeg* ds = &segs[seg];
         const u32 KB = uniform(ds->KB), l = uniform(ds->l), tau = uniform(ds->tau), nb = uniform(ds->nb);
         const u64 d = ds->d;
@@ -397,16 +429,16 @@ k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u
             bool ok = true, too_big = false;
             for (u32 sub = 0; sub < nsub && ok; ++sub) {
                 const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
-                u32* kd = ACCUM ? nullptr : keys_out + out0 + sub * kSub;
-                float* vd = ACCUM ? nullptr : values_out + out0 + sub * kSub;
+                u32* kd = MODE != kStore ? nullptr : keys_out + out0 + sub * kSub;
+                float* vd = MODE != kStore ? nullptr : values_out + out0 + sub * kSub;
                 if (n == kSub)
-                    ok = decode_round<true, ACCUM>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * kSub, n, l, M, tau,
+                    ok = decode_round<true, MODE>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * kSub, n, l, M, tau,
                                                    pbits, pbit, carry, lane, s_pay, s_flg, s_V, kd, vd, dense, dense_len,
-                                                   too_big);
+                                                   adam, too_big);
                 else
-                    ok = decode_round<false, ACCUM>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * kSub, n, l, M, tau,
+                    ok = decode_round<false, MODE>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * kSub, n, l, M, tau,
                                                     pbits, pbit, carry, lane, s_pay, s_flg, s_V, kd, vd, dense, dense_len,
-                                                    too_big);
+                                                    adam, too_big);
             }
             bad = !ok || (pbit != pbits) || (has_next && carry != next_pre);
             if (!bad && too_big && lane == 0)
