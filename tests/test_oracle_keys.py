@@ -222,3 +222,20 @@ def test_segmented_equals_independent_streams():
     # shared parameters
     rc, blob2, so2 = ref.compress_segmented(keys, vals, offs, plist[0])
     assert rc == ref.OK and parse(blob2[int(so2[3]):int(so2[4])])["tau"] == 128
+
+
+def test_bits_per_key_against_flag_size_has_an_interior_minimum():
+    # Table 6 (Section 4.2): on clustered keys the size per key first falls and then rises with l, smallest
+    # at l = 2.  Synthetic stand-in for the paper's dataset: Zipf(1.2) gaps, 10 % of the pairs survive.
+    from paper_2112_04291_amd import workloads as W
+    w = W.config3(nnz=200_000, dim=2_000_000)
+    b = W.solve_base(w.values, 0.1)
+    bits = []
+    for l in range(1, 6):
+        rc, st = ref.compress(w.keys, w.values, ref.params(b, 128, l, 1024))
+        assert rc == ref.OK
+        d = int(st[40:48].view("<u8")[0])
+        bits.append(8.0 * (st.size - 64 - ((d + 7) & ~7)) / d)
+    assert bits[1] == min(bits)
+    assert bits[0] > bits[1] < bits[2] < bits[3] < bits[4]
+    assert all(x < 32.0 for x in bits)
