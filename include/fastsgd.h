@@ -74,7 +74,9 @@ size_t fastsgd_workspace_size(uint64_t total_n, uint32_t n_segments, uint32_t mi
 size_t fastsgd_decompress_workspace_size(uint32_t n_segments);
 
 /* Encoder (Algorithms 1 and 2) for one worker's gradient {(k_j, v_j)}, j = 1..n.
- *   d_keys, d_values   device, read-only, n entries each (4-byte aligned)
+ *   d_keys, d_values   device, read-only, n entries each (4-byte aligned); d_keys may be NULL
+ *                      for a dense gradient, whose keys are then 0..n-1 (the stream is the one
+ *                      the explicit keys 0..n-1 give; the key array is never read)
  *   p                  host
  *   d_out              device, out_capacity bytes, 8-byte aligned; receives the stream
  *   d_out_bytes        device u64: stream length, or 0 if *d_status != FASTSGD_OK
@@ -99,7 +101,8 @@ fastsgd_status fastsgd_decompress(const void* d_stream, size_t stream_bytes,
 
 /* Encoder for a batch of independent gradients (e.g. one per layer) in one call: gradient s is
  * elements [seg_offsets[s], seg_offsets[s+1]) of d_keys / d_values and is encoded exactly as
- * fastsgd_compress would encode it alone.  Streams are written back to back into d_out (each a
+ * fastsgd_compress would encode it alone (d_keys NULL: every gradient has the keys 0..n_s-1).
+ * Streams are written back to back into d_out (each a
  * multiple of 8 bytes, each decodable on its own).
  *   seg_offsets        host, n_segments + 1 non-decreasing element offsets
  *   params             host; params_stride = 0: one entry shared by all segments,

@@ -90,12 +90,12 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     const u64 first_elem = seg_offsets[0];
     const u64 total_n = seg_offsets[n_segments] - first_elem;
     if (seg_offsets[n_segments] < first_elem || total_n >= (1ull << 40)) return FASTSGD_ERR_INVALID_ARG;
-    if (total_n && (!d_keys || !d_values)) return FASTSGD_ERR_INVALID_ARG;
+    if (total_n && !d_values) return FASTSGD_ERR_INVALID_ARG;
 
     // elements are counted from the 16-byte boundary at or below the first one; keys keep their pairing
     const u64 mis = total_n ? ((uintptr_t)(d_values + first_elem) & 15) / 4 : 0;
     const float* vbase = d_values + first_elem - mis;
-    const u32* kbase = d_keys + first_elem - mis;
+    const u32* kbase = d_keys ? d_keys + first_elem - mis : nullptr;     // no key array: keys are 0..n-1
 
     std::vector<SegInfo> segs(n_segments);
     u32 min_kb = kMaxKB, max_kb = 0;

@@ -406,6 +406,8 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
     s_B[lane + 64] = states[ck.seg].B[lane + 64];
     const float thr_f = __uint_as_float(thr);
     const u32* ckeys = keys + ck.e0;
+    const bool implicit = keys == nullptr;                 // dense gradient: the key is the index in the segment
+    const u32 key0 = (u32)(ck.e0 - ck.lo);                 // (wraps for the up to three slots before the segment)
     const float* cvals = values + ck.e0;
     const uint2* crmax = reinterpret_cast<const uint2*>(rowmax) + ck.row0;     // four quarter-row bounds per row, 16 bits each
     u32 cbase = 0;                           // survivors of the chunk already in the scratch arrays
@@ -420,7 +422,7 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
 #pragma unroll
             for (u32 k = 0; k < kGather; ++k) {               // all key fetches of the round first
                 const u32 j = j0 + k * 64u + lane;
-                key[k] = (j < staged) ? ckeys[s_idx[j]] : 0u;
+                key[k] = (j < staged) ? (implicit ? key0 + s_idx[j] : ckeys[s_idx[j]]) : 0u;
             }
 #pragma unroll
             for (u32 k = 0; k < kGather; ++k) {

@@ -17,7 +17,7 @@ def hip_compress(keys, values, p, out_capacity=None, bufs=None):
     """Returns (host rc, device status, stream bytes as uint8 numpy array, bufs)."""
     n = int(np.asarray(values).size)
     bufs = bufs or B.Buffers(n, p, out_capacity=out_capacity)
-    k, v = to_dev_u32(keys), to_dev_f32(values)
+    k, v = (None if keys is None else to_dev_u32(keys)), to_dev_f32(values)
     bufs.status.fill_(-1)
     bufs.out_offsets.fill_(-1)
     rc = B.compress(k, v, p, bufs.out, bufs.out_offsets, bufs.status, bufs.workspace, n=n,
@@ -60,7 +60,7 @@ def hip_compress_segmented(keys, values, seg_offsets, plist):
     ws = torch.empty(B.workspace_size(n, nseg, min_kb) // 8 + 32, dtype=torch.int64, device="cuda")
     offs = torch.full((nseg + 1,), -1, dtype=torch.int64, device="cuda")
     status = torch.full((2,), -1, dtype=torch.int32, device="cuda")
-    k, v = to_dev_u32(keys), to_dev_f32(values)
+    k, v = (None if keys is None else to_dev_u32(keys)), to_dev_f32(values)
     rc = B.compress_segmented(k, v, [int(x) for x in seg_offsets], plist, out, offs, status, ws)
     torch.cuda.synchronize()
     if rc != B.OK:

@@ -319,3 +319,17 @@ def test_random_bit_flips_in_a_stream_decode_like_the_oracle():
             assert np.array_equal(k, k_ref) and np.array_equal(v.view(np.uint32), v_ref.view(np.uint32)), int(pos)
         else:
             assert k.size == 0
+
+
+@pytest.mark.parametrize("n,keep", [(1, 1.0), (255, 0.5), (4097, 0.3), (300_001, 0.05), (2_000_003, 0.002)])
+def test_no_key_array_means_keys_are_the_indices(n, keep):
+    # a dense gradient handed over without keys encodes like the explicit keys 0..n-1
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(n)
+    vals = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    p = ref.params(W.solve_base(vals, keep), 128, 2, 1024)
+    rc_ref, want = ref.compress(np.arange(n, dtype=np.uint32), vals, p)
+    assert rc_ref == ref.OK
+    rc, status, got, _ = G.hip_compress(None, vals, B.params(p.base, 128, 2, 1024))
+    assert rc == B.OK and status == 0
+    assert np.array_equal(got, want)

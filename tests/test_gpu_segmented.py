@@ -86,3 +86,18 @@ def test_batch_with_a_nonfinite_segment_fails_as_a_whole():
     rc, status, blob, so = G.hip_compress_segmented(keys, vals, offs, B.params(1.1))
     assert rc == B.OK and status == B.ERR_NONFINITE and blob.size == 0 and np.all(so == 0)
     assert ref.compress_segmented(keys, vals, offs, ref.params(1.1))[0] == ref.ERR_NONFINITE
+
+
+def test_batch_without_key_array_uses_the_indices_inside_each_segment():
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(33)
+    sizes = [0, 1, 700, 5000, 3, 70_001, 4096, 4097, 250_003]
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.uint64)
+    keys = np.concatenate([np.arange(s, dtype=np.uint32) for s in sizes])
+    vals = np.concatenate([rng.laplace(0, 10.0 ** -(i % 4 + 1), s) for i, s in enumerate(sizes)]).astype(np.float32)
+    bases = [W.solve_base(vals[int(offs[i]):int(offs[i + 1])], 0.05) if sizes[i] > 100 else 1.1 for i in range(len(sizes))]
+    rc_ref, blob_ref, so_ref = ref.compress_segmented(keys, vals, offs, [ref.params(b) for b in bases])
+    assert rc_ref == ref.OK
+    rc, status, blob, so = G.hip_compress_segmented(None, vals, offs, [B.params(b) for b in bases])
+    assert rc == B.OK and status == 0
+    assert np.array_equal(so, so_ref) and np.array_equal(blob, blob_ref)
