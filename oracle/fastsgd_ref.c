@@ -194,15 +194,24 @@ static void put_u64(uint8_t *p, uint64_t x) { for (int k = 0; k < 8; ++k) p[k] =
 static uint32_t get_u32(const uint8_t *p) { uint32_t x = 0; for (int k = 0; k < 4; ++k) x |= (uint32_t)p[k] << (8 * k); return x; }
 static uint64_t get_u64(const uint8_t *p) { uint64_t x = 0; for (int k = 0; k < 8; ++k) x |= (uint64_t)p[k] << (8 * k); return x; }
 
-static uint64_t align8(uint64_t x) { return (x + 7) & ~(uint64_t)7; }
 static uint64_t words64(uint64_t bits) { return (bits + 63) / 64; }
+
+/* Section 3.2, after the threshold filter: the codes 1..tau need ceil(log2 tau) bits (stored as
+ * code-1), one more bit carries the sign: 8 bits for the recommended tau = 128. */
+static uint32_t code_width(uint32_t tau) {
+    uint32_t q = 0;
+    while (((uint32_t)1 << q) < tau) ++q;
+    return 1 + q;
+}
+/* bytes of the value plane of d survivors: d tokens of code_width bits, zero-padded to 8 bytes */
+static uint64_t value_plane_bytes(uint64_t d, uint32_t tau) { return 8 * words64(d * code_width(tau)); }
 
 /* Worst case: every element survives and every token takes l + 32 bits. */
 uint64_t fastsgd_ref_compressed_size(uint64_t n, const ref_params *p) {
     if (!params_ok(p)) return 0;
     uint64_t KB = p->block_keys, nb = (n + KB - 1) / KB;
     uint64_t per_block = 8 * (words64(KB * p->flag_bits) + words64(KB * 32));
-    return REF_HEADER_BYTES + align8(n) + 16 * nb + nb * per_block;
+    return REF_HEADER_BYTES + value_plane_bytes(n, p->tau) + 16 * nb + nb * per_block;
 }
 
 /* ------------------------------------------------------------------------- *
@@ -211,8 +220,10 @@ uint64_t fastsgd_ref_compressed_size(uint64_t n, const ref_params *p) {
  * Container (the paper fixes none; Reading): little-endian,
  *   [0,64)   header: magic, version u8, l u8, tau u8, 0 u8, block_keys u32,
  *            n_blocks u32, b f64, sum f64, n u64, d u64, total_bytes u64, 0 u64
- *   [64,64+d) value plane: one byte per survivor, bit7 = sign, bits0-6 = code-1
- *   zero padding to a multiple of 8
+ *   value plane: one token of w = 1 + ceil(log2 tau) bits per survivor (Section 3.2), token j at
+ *            bit j*w counted LSB first: low w-1 bits = code-1, top bit = sign; for tau in 65..128
+ *            that is one byte per survivor, bit7 = sign, bits0-6 = code-1
+ *   zero padding to a multiple of 8 bytes
  *   block directory: n_blocks x {off8 u32, preKey u32, M u32, payload_bits u32}
  *   key blocks, back to back, each a flags plane (cnt*l bits) and a payload
  *            plane (payload_bits bits), both zero-padded to 64-bit words.
@@ -242,30 +253,32 @@ int fastsgd_ref_compress(const uint32_t *keys, const float *values, uint64_t n,
     const uint32_t tau_e = B_bits[tau];
 
     /* lines 3-10: Result = codes of survivors, in key order */
+    const uint32_t w = code_width(tau);
     uint64_t d = 0;
     uint32_t *skeys = (uint32_t *)malloc((n ? n : 1) * sizeof(uint32_t));
-    if (!skeys) return REF_ERR_INVALID_ARG;
+    uint8_t *token = (uint8_t *)malloc(n ? n : 1);
+    if (!skeys || !token) { free(skeys); free(token); return REF_ERR_INVALID_ARG; }
     if (sum > 0.0) {
         for (uint64_t j = 0; j < n; ++j) {
             uint32_t bits = f32_bits(values[j]);
             uint32_t a = bits & 0x7FFFFFFFu;
             if (a >= tau_e) { /* |v_j| >= tau_e */
                 uint32_t c = code_of(a, B_bits, tau);
-                if (REF_HEADER_BYTES + d >= out_capacity) { free(skeys); return REF_ERR_BUFFER_TOO_SMALL; }
-                out[REF_HEADER_BYTES + d] = (uint8_t)((bits >> 31) << 7 | (c - 1));
+                token[d] = (uint8_t)((bits >> 31) << (w - 1) | (c - 1));
                 skeys[d] = keys[j];
                 ++d;
             }
         }
     }
+    uint64_t nb = (d + KB - 1) / KB;
+    uint64_t dir_off = REF_HEADER_BYTES + value_plane_bytes(d, tau);
+    uint64_t blocks_off = dir_off + 16 * nb;
+    if (blocks_off > out_capacity) { free(skeys); free(token); return REF_ERR_BUFFER_TOO_SMALL; }
+    memset(out + REF_HEADER_BYTES, 0, dir_off - REF_HEADER_BYTES);
+    for (uint64_t j = 0; j < d; ++j) put_bits(out + REF_HEADER_BYTES, j * w, token[j], w);
+    free(token);
 
     /* Algorithm 2 on the d surviving keys, block by block */
-    uint64_t nb = (d + KB - 1) / KB;
-    uint64_t dir_off = REF_HEADER_BYTES + align8(d);
-    uint64_t blocks_off = dir_off + 16 * nb;
-    if (blocks_off > out_capacity) { free(skeys); return REF_ERR_BUFFER_TOO_SMALL; }
-    memset(out + REF_HEADER_BYTES + d, 0, dir_off - (REF_HEADER_BYTES + d));
-
     uint64_t off8 = 0; /* running block offset in 8-byte units */
     uint32_t *delta = (uint32_t *)malloc(KB * sizeof(uint32_t));
     uint32_t preKey = 0;
@@ -339,7 +352,8 @@ int fastsgd_ref_decompress(const uint8_t *stream, uint64_t stream_bytes,
     if (!(sum >= 0.0) || isinf(sum)) return REF_ERR_CORRUPT_STREAM;
     if (n > 4294967296ull || d > n) return REF_ERR_CORRUPT_STREAM;
     if (nb != (d + KB - 1) / KB) return REF_ERR_CORRUPT_STREAM;
-    uint64_t dir_off = REF_HEADER_BYTES + align8(d), blocks_off = dir_off + 16 * nb;
+    const uint32_t w = code_width(tau);
+    uint64_t dir_off = REF_HEADER_BYTES + value_plane_bytes(d, tau), blocks_off = dir_off + 16 * nb;
     if (total > stream_bytes || total < blocks_off || (total & 7)) return REF_ERR_CORRUPT_STREAM;
     if (d > capacity) return REF_ERR_BUFFER_TOO_SMALL;
     if (d && (!keys_out || !values_out)) return REF_ERR_INVALID_ARG;
@@ -349,10 +363,10 @@ int fastsgd_ref_decompress(const uint8_t *stream, uint64_t stream_bytes,
 
     /* phases 3-4 */
     for (uint64_t j = 0; j < d; ++j) {
-        uint8_t byte = stream[REF_HEADER_BYTES + j];
-        uint32_t c = (uint32_t)(byte & 0x7F) + 1;
+        uint32_t token = get_bits(stream + REF_HEADER_BYTES, j * w, w);
+        uint32_t c = (token & (((uint32_t)1 << (w - 1)) - 1)) + 1;
         if (c > tau) return REF_ERR_CORRUPT_STREAM;
-        values_out[j] = bits_f32(V_bits[c] | (uint32_t)(byte >> 7) << 31);
+        values_out[j] = bits_f32(V_bits[c] | (token >> (w - 1)) << 31);
     }
 
     /* phases 1-2 */
@@ -457,7 +471,7 @@ int fastsgd_ref_decompress_accumulate(const uint8_t *streams, const uint64_t *st
         const uint8_t *st = streams + stream_offsets[s];
         uint64_t bytes = stream_offsets[s + 1] - stream_offsets[s];
         uint64_t d = bytes >= REF_HEADER_BYTES ? get_u64(st + 40) : 0;
-        if (d > bytes) return REF_ERR_CORRUPT_STREAM;          /* every pair costs at least one byte */
+        if (d > 8 * bytes) return REF_ERR_CORRUPT_STREAM;      /* every pair costs more than one bit */
         uint32_t *k = (uint32_t *)malloc((d + 1) * sizeof(uint32_t));
         float *v = (float *)malloc((d + 1) * sizeof(float));
         if (!k || !v) { free(k); free(v); return REF_ERR_INVALID_ARG; }
@@ -495,7 +509,7 @@ int fastsgd_ref_decompress_adam(const uint8_t *stream, uint64_t bytes, float *th
     if (count_out) *count_out = 0;
     if (!stream || !count_out || (dim && (!theta || !m || !v))) return REF_ERR_INVALID_ARG;
     uint64_t d = bytes >= REF_HEADER_BYTES ? get_u64(stream + 40) : 0;
-    if (d > bytes) return REF_ERR_CORRUPT_STREAM;              /* every pair costs at least one byte */
+    if (d > 8 * bytes) return REF_ERR_CORRUPT_STREAM;          /* every pair costs more than one bit */
     uint32_t *k = (uint32_t *)malloc((d + 1) * sizeof(uint32_t));
     float *g = (float *)malloc((d + 1) * sizeof(float));
     if (!k || !g) { free(k); free(g); return REF_ERR_INVALID_ARG; }

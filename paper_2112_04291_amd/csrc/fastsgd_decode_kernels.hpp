@@ -376,7 +376,7 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
 // MODE kAccum / kAdam: the launch handles the key blocks of stream `only` alone and updates the dense
 // arrays (one launch per stream, so that the updates happen stream after stream).
 template <int MODE>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(MODE == kStore ? 4 : 2, 8)))
 k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u32 n_segments, DecCtrl* ctrl,
          u32* __restrict__ keys_out, float* __restrict__ values_out, u64* out_counts, u32 n_counts,
          u32* out_status, float* __restrict__ dense, u64 dense_len, u32 only, AdamArgs adam) {

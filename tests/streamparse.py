@@ -32,9 +32,14 @@ def parse(stream):
     assert magic == b"FSGD" and version == 1 and zero == 0 and rsv == 0
     assert total == len(s), (total, len(s))
     assert nb == -(-d // KB)
-    codes = list(s[64:64 + d])
-    dir_off = 64 + ((d + 7) & ~7)
-    assert all(b == 0 for b in s[64 + d:dir_off]), "value-plane padding must be zero"
+    # value plane: d tokens of w = 1 + ceil(log2 tau) bits, low bits code-1, top bit the sign; reported
+    # as sign << 7 | code-1 whatever w is
+    w = 1 + (tau - 1).bit_length()
+    dir_off = 64 + 8 * (-(-(d * w) // 64))
+    plane = s[64:dir_off]
+    toks = [_bits(plane, j * w, w) for j in range(d)]
+    codes = [((t >> (w - 1)) << 7) | (t & ((1 << (w - 1)) - 1)) for t in toks]
+    assert _bits(plane, d * w, 8 * len(plane) - d * w) == 0, "value-plane padding must be zero"
     blocks_off = dir_off + 16 * nb
     keys, tokens, off_expect = [], [], 0
     last = 0
@@ -63,7 +68,7 @@ def parse(stream):
         last = key
         off_expect = off8 + fwords + pwords
     assert blocks_off + 8 * off_expect == total
-    return dict(l=l, tau=tau, KB=KB, nb=nb, base=base, S=S, n=n, d=d, total=total,
+    return dict(l=l, tau=tau, KB=KB, nb=nb, w=w, base=base, S=S, n=n, d=d, total=total,
                 codes=codes, keys=keys, tokens=tokens)
 
 

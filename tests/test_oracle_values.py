@@ -339,9 +339,60 @@ def test_values_exactly_on_below_and_above_bucket_boundaries():
     assert rc == ref.OK
     d = int(st[40:48].view("<u8")[0])
     assert d == int(kept.sum())
-    plane = st[64:64 + d]
+    plane = np.array(parse(st)["codes"], np.uint8)     # sign << 7 | code-1 (tau = 10: stored in 5 bits each)
     assert np.array_equal((plane & 0x7F) + 1, codes[kept])
     assert np.array_equal(plane >> 7, (vals[kept] < 0).astype(np.uint8))
     rc, k, v = ref.decompress(st)
     assert np.array_equal(k, keys[kept])
     assert np.array_equal(np.abs(v), (2.0 ** (20 - codes[kept])).astype(np.float32))
+
+
+@pytest.mark.parametrize("tau", [1, 2, 3, 5, 16, 32, 33, 64, 65, 100, 127])
+def test_codes_take_one_plus_ceil_log2_tau_bits(tau):
+    """Section 3.2: after the filter a code needs ceil(log2 tau) bits, plus the sign.  The code of a value
+    does not depend on tau (only the filter does), so the tokens of a tau < 128 stream must spell the
+    codes <= tau of the one-byte-per-code stream of tau = 128, in order, in narrower fields."""
+    import math
+    rng = np.random.default_rng(tau)
+    n = {1: 12, 2: 150, 3: 2000}.get(tau, 5000 + tau)       # few values for tiny tau: b <= 16 must reach them
+    keys = np.sort(rng.choice(10 * n, n, replace=False)).astype(np.uint32)
+    vals = rng.laplace(0.0, 1e-3, n).astype(np.float32)
+    S = float(np.abs(vals.astype(np.float64)).sum())
+    base = min(16.0, max(1.01, (S / float(np.median(np.abs(vals)))) ** (1.0 / tau)))   # about half survive
+    rc, wide = ref.compress(keys, vals, ref.params(base, 128, 2, 256))
+    assert rc == ref.OK
+    rc, st = ref.compress(keys, vals, ref.params(base, tau, 2, 256))
+    assert rc == ref.OK
+    a, b = parse(wide), parse(st)
+    w = 1 + (0 if tau == 1 else math.ceil(math.log2(tau)))
+    assert b["w"] == w and a["w"] == 8
+    keep = [i for i, c in enumerate(a["codes"]) if (c & 0x7F) + 1 <= tau]
+    assert b["d"] == len(keep) and b["d"] > 0
+    assert b["codes"] == [a["codes"][i] for i in keep]
+    assert b["keys"] == [a["keys"][i] for i in keep]
+    # size: header, d tokens of w bits padded to 8 bytes, directory, key blocks
+    plane = 8 * math.ceil(b["d"] * w / 64)
+    key_bytes = sum(8 * (math.ceil(min(256, b["d"] - 256 * i) * 2 / 64)) for i in range(b["nb"]))
+    pay = st.size - 64 - plane - 16 * b["nb"] - key_bytes
+    assert pay >= 0 and pay % 8 == 0
+    # decoding gives the values of the wide stream at the kept positions
+    rc, k1, v1 = ref.decompress(wide)
+    rc2, k2, v2 = ref.decompress(st)
+    assert rc == ref.OK and rc2 == ref.OK
+    assert np.array_equal(k2, k1[keep]) and np.array_equal(v2.view(np.uint32), v1[keep].view(np.uint32))
+
+
+def test_packed_codes_beyond_tau_are_rejected():
+    # tau = 5: 4-bit tokens, code-1 in 3 bits can say 5..7, which no encoder writes
+    rng = np.random.default_rng(1)
+    n = 3000
+    keys = np.arange(n, dtype=np.uint32)
+    vals = rng.laplace(0.0, 1e-3, n).astype(np.float32)
+    rc, st = ref.compress(keys, vals, ref.params(4.0, 5, 2, 256))
+    assert rc == ref.OK and parse(st)["d"] > 10
+    bad = st.copy()
+    bad[64] = (bad[64] & 0xF0) | 0x07          # token 0: sign 0, code-1 = 7
+    assert ref.decompress(bad)[0] == ref.ERR_CORRUPT_STREAM
+    bad[64] = (st[64] & 0xF0) | 0x04           # code-1 = 4 is code 5 = tau: fine
+    rc, k, v = ref.decompress(bad)
+    assert rc == ref.OK
