@@ -241,8 +241,8 @@ static fastsgd_status decompress_impl(const void* d_streams, size_t total_bytes,
                                d_counts, d_status, (u64*)nullptr);
     }
     marks.mark(stream);
-    // every key costs at least one value byte, so bytes/256 bounds the number of key blocks
-    hipLaunchKernelGGL(k_decode<kStore>, dim3(clamp_grid(((u64)total_bytes / 256 + n_segments + kWaves - 1) / kWaves, (u64)cus * 7)),
+    // every key costs at least three bits, so bytes/96 bounds the number of key blocks
+    hipLaunchKernelGGL(k_decode<kStore>, dim3(clamp_grid(((u64)total_bytes / 96 + n_segments + kWaves - 1) / kWaves, (u64)cus * 7)),
                        dim3(kThreads), 0, stream, streams, segs, n_segments, ctrl, d_keys_out, d_values_out, d_counts,
                        single ? 1u : n_segments + 1u, d_status, (float*)nullptr, (u64)0, 0u, AdamArgs());
     marks.mark(stream);
@@ -272,7 +272,7 @@ static fastsgd_status accumulate_impl(const void* d_streams, size_t total_bytes,
                        d_stream_offsets, 0u, segs, ctrl, ~0ull, counts, d_status);
     hipLaunchKernelGGL(k_decode_plan, dim3(1), dim3(kThreads), 0, stream, segs, n_streams, ~0ull, ctrl, counts, d_status,
                        d_count);
-    const u32 grid = clamp_grid(((u64)total_bytes / 256 + 1 + kWaves - 1) / kWaves, (u64)cus * 7);
+    const u32 grid = clamp_grid(((u64)total_bytes / 96 + 1 + kWaves - 1) / kWaves, (u64)cus * 7);
     for (u32 s = 0; s < n_streams; ++s)
         hipLaunchKernelGGL(k_decode<kAccum>, dim3(grid), dim3(kThreads), 0, stream, streams, segs, n_streams, ctrl,
                            (u32*)nullptr, (float*)nullptr, d_count, 1u, d_status, d_dense, dense_len, s, AdamArgs());
@@ -307,7 +307,7 @@ static fastsgd_status adam_impl(const void* d_stream, size_t stream_bytes, float
     a.eps = (float)h->eps;
     hipLaunchKernelGGL(k_decode_setup, dim3(1), dim3(128), 0, stream, streams, (u64)stream_bytes, (const u64*)nullptr, 1u,
                        segs, ctrl, ~0ull, d_count, d_status);
-    const u32 grid = clamp_grid(((u64)stream_bytes / 256 + 1 + kWaves - 1) / kWaves, (u64)cu_count() * 7);
+    const u32 grid = clamp_grid(((u64)stream_bytes / 96 + 1 + kWaves - 1) / kWaves, (u64)cu_count() * 7);
     hipLaunchKernelGGL(k_decode<kAdam>, dim3(grid), dim3(kThreads), 0, stream, streams, segs, 1u, ctrl, (u32*)nullptr,
                        (float*)nullptr, d_count, 1u, d_status, d_theta, dim, 0u, a);
     return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
@@ -351,7 +351,9 @@ size_t fastsgd_compressed_size(uint64_t n, const fastsgd_params* p) {
     if (!params_ok(p) || n > kMaxElems) return 0;
     const u64 KB = p->block_keys, nb = (n + KB - 1) / KB;
     const u64 per_block = 8 * ((KB * p->flag_bits + 63) / 64 + (KB * 32 + 63) / 64);
-    return (size_t)(kHeaderBytes + ((n + 7) & ~7ull) + 16 * nb + nb * per_block);
+    u32 width = 1;                                       // 1 + ceil(log2 tau) bits per value token
+    while ((1u << (width - 1)) < p->tau) ++width;
+    return (size_t)(kHeaderBytes + 8 * ((n * width + 63) / 64) + 16 * nb + nb * per_block);
 }
 
 size_t fastsgd_workspace_size(uint64_t total_n, uint32_t n_segments, uint32_t min_block_keys) {

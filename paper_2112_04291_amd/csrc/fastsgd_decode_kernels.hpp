@@ -85,7 +85,7 @@ k_decode_setup(const uint8_t* __restrict__ streams, u64 total_bytes, const u64* 
             ok = ok && n <= 4294967296ull && d <= n;
             if (ok) {
                 ok = (u64)nb == (d + KB - 1) / KB;
-                dir_off = kHeaderBytes + ((d + 7) & ~7ull);
+                dir_off = kHeaderBytes + value_plane_bytes(d, code_width(tau));
                 blocks_off = dir_off + 16ull * nb;
                 ok = ok && total <= end - begin && total >= blocks_off && (total & 7) == 0;
                 total_words = ok ? (total - blocks_off) >> 3 : 0;
@@ -195,8 +195,8 @@ struct AdamArgs {
 template <bool FULL, int MODE>
 __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round, const u32* __restrict__ psrc,
                                              u32 pw_total, const uint8_t* __restrict__ codes_round, u32 n, u32 l,
-                                             u32 M, u32 tau, u32 pbits, u32& pbit, u32& carry, u32 lane, u32* s_pay,
-                                             u32* s_flg, const u32* s_V, u32* __restrict__ keys_dst,
+                                             u32 M, u32 tau, u32 cwid, u32 pbits, u32& pbit, u32& carry, u32 lane,
+                                             u32* s_pay, u32* s_flg, u32* s_cod, const u32* s_V, u32* __restrict__ keys_dst,
                                              float* __restrict__ values_dst, float* __restrict__ dense, u64 dense_len,
                                              const AdamArgs& adam, bool& too_big) {
     const u32 nfw = (n * l + 31u) >> 5;
@@ -213,7 +213,9 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         pwd[k] = (k * 64u < npw && pw_total) ? psrc[(pw0 + i < pw_total) ? pw0 + i : pw_total - 1u] : 0u;
     }
     u32 cw[4];                                             // the lane's 16 code bytes
-    if (FULL) {
+    if (cwid != 8) {
+        // narrower tokens are widened further down, once the other fetches are parked
+    } else if (FULL) {
         const uint2* c2 = reinterpret_cast<const uint2*>(codes_round) + 2u * lane;   // 8-byte aligned
         const uint2 a = c2[0], b = c2[1];
         cw[0] = a.x; cw[1] = a.y; cw[2] = b.x; cw[3] = b.y;
@@ -237,6 +239,29 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         if (k * 64u < npw && i < npw) s_pay[i] = (pw0 + i < pw_total) ? pwd[k] : 0u;
     }
     wave_lds_sync();
+    if (cwid != 8) {
+        // token i of the round sits at bit i * cwid of the round's words; each is widened to the byte
+        // form (sign in bit 7, code-1 below) through shared memory
+        const u32* cwords = reinterpret_cast<const u32*>(codes_round);
+        uint8_t* s_codb = reinterpret_cast<uint8_t*>(s_cod + kCodeWords);
+        const u32 ncw = (n * cwid + 31u) >> 5;
+        for (u32 i = lane; i < ncw + 1u; i += 64) s_cod[i] = (i < ncw) ? cwords[i] : 0u;
+        wave_lds_sync();
+        const u32 tmask = (1u << cwid) - 1u, cmask = tmask >> 1;
+#pragma unroll 1
+        for (u32 i = lane; i < kSub; i += 64) {
+            u32 byte = 0;
+            if (i < n) {
+                const u32 pos = i * cwid, wa = pos >> 5;
+                const u32 tok = __builtin_amdgcn_alignbit(s_cod[wa + 1u], s_cod[wa], pos & 31u) & tmask;
+                byte = ((tok >> (cwid - 1u)) << 7) | (tok & cmask);
+            }
+            s_codb[i] = (uint8_t)byte;
+        }
+        wave_lds_sync();
+        const uint4 q = reinterpret_cast<const uint4*>(s_codb)[lane];
+        cw[0] = q.x; cw[1] = q.y; cw[2] = q.z; cw[3] = q.w;
+    }
 
     // flags -> lengths: 8 flags at a time out of a 64-bit window of the lane's flag bits
     const u32 lmask = (1u << l) - 1u, lenc = M + lmask;     // length = (flag * M + M + 2^l - 1) >> l
@@ -383,10 +408,12 @@ k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u
     __shared__ __attribute__((aligned(16))) u32 s_payall[kWaves][kSub + 4];
     __shared__ u32 s_flgall[kWaves][kSub * 5 / 32 + 4];
     __shared__ u32 s_Vall[kWaves][128];
+    __shared__ __attribute__((aligned(16))) u32 s_codall[kWaves][2 * kCodeWords];   // token words, then widened bytes
     const u32 lane = lane_id(), w = uniform(wave_id());
     u32* s_pay = s_payall[w];
     u32* s_flg = s_flgall[w];
     u32* s_V = s_Vall[w];
+    u32* s_cod = s_codall[w];
     u64 item_lo = 0, item_hi = ctrl->total_items;
     if (MODE != kStore && item_hi) { item_lo = segs[only].item_begin; item_hi = item_lo + segs[only].nb; }
     u32 cur_seg = 0xFFFFFFFFu;
@@ -422,7 +449,8 @@ k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u
             const u32* fsrc = reinterpret_cast<const u32*>(streams + uniform64(ds->blocks_off + 8ull * off8));   // flags plane
             const u32* psrc = fsrc + 2u * fwords;                                                              // payload plane
             const u32 pw_total = 2u * pwords;
-            const uint8_t* codes = streams + uniform64(ds->stream_begin + kHeaderBytes + first);
+            const u32 cwid = uniform(code_width(tau));                 // bits of a value token
+            const uint8_t* codes = streams + uniform64(ds->stream_begin + kHeaderBytes + (u64)(first >> 3) * cwid);
             const u64 out0 = uniform64(ds->pair_begin + first);
             u32 pbit = 0;                  // payload bits consumed by the rounds before
             u32 carry = preKey;            // key before the round in hand
@@ -432,12 +460,12 @@ k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u
                 u32* kd = MODE != kStore ? nullptr : keys_out + out0 + sub * kSub;
                 float* vd = MODE != kStore ? nullptr : values_out + out0 + sub * kSub;
                 if (n == kSub)
-                    ok = decode_round<true, MODE>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * kSub, n, l, M, tau,
-                                                   pbits, pbit, carry, lane, s_pay, s_flg, s_V, kd, vd, dense, dense_len,
+                    ok = decode_round<true, MODE>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * (kSub / 8u) * cwid, n, l, M,
+                                                   tau, cwid, pbits, pbit, carry, lane, s_pay, s_flg, s_cod, s_V, kd, vd, dense, dense_len,
                                                    adam, too_big);
                 else
-                    ok = decode_round<false, MODE>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * kSub, n, l, M, tau,
-                                                    pbits, pbit, carry, lane, s_pay, s_flg, s_V, kd, vd, dense, dense_len,
+                    ok = decode_round<false, MODE>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * (kSub / 8u) * cwid, n, l, M,
+                                                    tau, cwid, pbits, pbit, carry, lane, s_pay, s_flg, s_cod, s_V, kd, vd, dense, dense_len,
                                                     adam, too_big);
             }
             bad = !ok || (pbit != pbits) || (has_next && carry != next_pre);

@@ -225,6 +225,13 @@ __device__ __forceinline__ void set_status(Ctrl* ctrl, u32 code) { atomicCAS(&ct
 
 __device__ __forceinline__ u64 align8(u64 x) { return (x + 7) & ~7ull; }
 
+// Section 3.2: after the filter a code (stored as code-1) takes ceil(log2 tau) bits, one more for the
+// sign; 8 bits for tau in 65..128.
+__device__ __forceinline__ u32 code_width(u32 tau) { return 1u + (32u - (u32)__clz((int)(tau - 1u))); }
+// Bytes of the value plane: d tokens of `width` bits, zero-padded to 64-bit words.
+__device__ __forceinline__ u64 value_plane_bytes(u64 d, u32 width) { return 8ull * ((d * width + 63ull) >> 6); }
+constexpr u32 kCodeWords = 32u * 8u;   // 32-bit words of 1024 tokens of at most 8 bits
+
 // Level lengths of Algorithm 2's length flag for a block with maximal length M and l flag bits:
 // level i (1..2^l) holds ceil(i*M / 2^l) bits; a delta of `need` significant bits takes the
 // smallest level that holds it, i = floor((need-1) * 2^l / M) + 1 (level 1 for need = 0).

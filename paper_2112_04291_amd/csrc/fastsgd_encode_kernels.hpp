@@ -858,7 +858,7 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
         const u32 blk = ku.blk0 + w;
         if (blk >= (ku.nb ? ku.nb : 1u)) continue;
         const u64 item = ku.item_begin + blk;
-        const u32 head8 = (u32)((kHeaderBytes + align8(ku.d) + 16ull * ku.nb) >> 3);   // first item of a segment
+        const u32 head8 = (u32)((kHeaderBytes + value_plane_bytes(ku.d, code_width(info.tau)) + 16ull * ku.nb) >> 3);   // first item of a segment
         if (ku.nb == 0) {                                   // a segment without survivors: its header only
             if (lane == 0) {
                 BlockInfo bi; bi.preKey = 0; bi.M = 0; bi.payload_bits = 0; bi.span8 = head8;
@@ -995,7 +995,8 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
         if (blk >= nitems) continue;
         const u64 item = ku.item_begin + blk;
         const u64 sbeg = 8ull * sbeg8;
-        const u64 dir_off = sbeg + kHeaderBytes + align8(ku.d);
+        const u32 cwid = uniform(code_width(info.tau));               // bits of a value token
+        const u64 dir_off = sbeg + kHeaderBytes + value_plane_bytes(ku.d, cwid);
         const u64 blocks_off = dir_off + 16ull * ku.nb;
         if (blk == 0) {
             const u64 send8 = item_offset8(s_G, binfo, g_shift, ku.item_begin + nitems, lane);
@@ -1012,7 +1013,13 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
                 if (!single) out_offsets[ku.seg] = sbeg;
             }
             // zero padding between the value plane and the directory
-            if (lane < 8 && ku.d + lane < align8(ku.d)) out[sbeg + kHeaderBytes + ku.d + lane] = 0;
+            if (cwid == 8) {
+                if (lane < 8 && ku.d + lane < align8(ku.d)) out[sbeg + kHeaderBytes + ku.d + lane] = 0;
+            } else {
+                // the last block writes whole 32-bit words; an odd number of them leaves one word of padding
+                const u64 dw = (ku.d * cwid + 31ull) >> 5;
+                if (lane == 0 && (dw & 1ull)) reinterpret_cast<u32*>(out + sbeg + kHeaderBytes)[dw] = 0;
+            }
         }
         if (ku.nb == 0) continue;                                      // a segment without survivors
         const BlockInfo bi = binfo[item];
@@ -1029,7 +1036,8 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
         }
         u32* fdst = reinterpret_cast<u32*>(out + start);               // flags plane, 32-bit words
         u32* pdst = fdst + 2u * fwords;                                // payload plane
-        uint8_t* vdst = out + sbeg + kHeaderBytes + first;             // the block's part of the value plane
+        uint8_t* vdst = out + sbeg + kHeaderBytes + first;             // the block's part of the value plane (bytes)
+        u32* vdst32 = reinterpret_cast<u32*>(out + sbeg + kHeaderBytes) + (first >> 5) * cwid;   // (narrower tokens)
 
         // second loop of Algorithm 2, 1024 keys at a time, 16 consecutive keys per lane
         const u32 stride = R * kRow;
@@ -1054,6 +1062,36 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
             gather_blocked(P, ku.nch, stride, seg_keys, r0, n, lane, s_pay, ent, kb);    // borrows the payload window
 #pragma unroll
             for (u32 q = 0; q < kKeyRows; ++q) code[q] = (q * 64u + lane < n) ? seg_codes[ent[q]] : 0u;
+            if (cwid == 8) {
+                // the survivors' code bytes go straight into the value plane
+#pragma unroll
+                for (u32 q = 0; q < kKeyRows; ++q) {
+                    const u32 i = q * 64u + lane;
+                    if (i < n) vdst[sub * kSub + i] = (uint8_t)code[q];
+                }
+            } else {
+                // tokens of cwid bits (sign on top of code-1), token i of the round at bit i * cwid:
+                // assembled in the (still unused) payload window, stored as whole words
+                uint8_t* s_b = reinterpret_cast<uint8_t*>(s_pay);        // the round's code bytes
+                u32* s_t = s_pay + kSub / 4;                             // the token words
+                const u32 nw = (n * cwid + 31u) >> 5;
+#pragma unroll
+                for (u32 q = 0; q < kKeyRows; ++q) s_b[q * 64u + lane] = (uint8_t)code[q];
+                for (u32 i = lane; i < nw + 1u; i += 64) s_t[i] = 0;
+                wave_lds_sync();
+#pragma unroll 1
+                for (u32 i = lane; i < n; i += 64) {
+                    const u32 b = s_b[i];
+                    const u32 tok = ((b >> 7) << (cwid - 1u)) | (b & 0x7Fu);
+                    const u32 bit = i * cwid;
+                    const u64 pv = (u64)tok << (bit & 31u);
+                    atomicOr(&s_t[bit >> 5], (u32)pv);
+                    if ((u32)(pv >> 32)) atomicOr(&s_t[(bit >> 5) + 1u], (u32)(pv >> 32));
+                }
+                wave_lds_sync();
+                for (u32 i = lane; i < nw; i += 64) vdst32[sub * 32u * cwid + i] = s_t[i];
+                wave_lds_sync();
+            }
             // the payload window: word 0 carries the bits left over from the previous round
             for (u32 i = lane; i < kSub + 2; i += 64) s_pay[i] = (i == 0) ? wword : 0u;
             if (n == kSub) lane_deltas<true>(kb, r0, n, lane, carry, dl, unsorted);
@@ -1089,12 +1127,6 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
                 bp += len[k];
             }
             const u32 roundend = wbits + read_lane(incl, 63);
-            // the survivors' code bytes go straight into the value plane
-#pragma unroll
-            for (u32 q = 0; q < kKeyRows; ++q) {
-                const u32 i = q * 64u + lane;
-                if (i < n) vdst[sub * kSub + i] = (uint8_t)code[q];
-            }
             wave_lds_sync();
             const bool last = (sub + 1 == nsub);
             // flags of this round: whole 32-bit words (1024*l bits per full round)

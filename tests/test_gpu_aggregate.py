@@ -53,3 +53,25 @@ def test_aggregate_errors_match_oracle():
     assert ref.decompress_accumulate(bad, offs, np.zeros(top + 1, np.float32))[0] == ref.ERR_CORRUPT_STREAM
     rc, status, cnt, _ = hip_accumulate(bad, offs, np.zeros(top + 1, np.float32))
     assert rc == B.OK and status == B.ERR_CORRUPT_STREAM and cnt == 0
+
+
+def test_aggregate_of_streams_with_narrow_tokens():
+    from paper_2112_04291_amd import binding as B
+    from paper_2112_04291_amd import workloads as W
+    rng = np.random.default_rng(8)
+    dim, blobs, offs = 300_000, [], [0]
+    for tau in (16, 128, 5):
+        keys = np.sort(rng.choice(dim, 60_000, replace=False)).astype(np.uint32)
+        vals = rng.laplace(0.0, 1e-3, keys.size).astype(np.float32)
+        vals[::5000] *= np.float32(1e3)
+        rc, st = ref.compress(keys, vals, ref.params(W.solve_base(vals, 0.4, tau), tau, 2, 512))
+        assert rc == ref.OK
+        blobs.append(st)
+        offs.append(offs[-1] + st.size)
+    blob, offs = np.concatenate(blobs), np.array(offs, np.uint64)
+    want = np.zeros(dim, np.float32)
+    rc_ref, cnt_ref = ref.decompress_accumulate(blob, offs, want)
+    assert rc_ref == ref.OK and cnt_ref > 100
+    rc, status, cnt, got = hip_accumulate(blob, offs, np.zeros(dim, np.float32))
+    assert rc == B.OK and status == 0 and cnt == cnt_ref
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))

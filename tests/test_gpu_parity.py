@@ -333,3 +333,16 @@ def test_no_key_array_means_keys_are_the_indices(n, keep):
     rc, status, got, _ = G.hip_compress(None, vals, B.params(p.base, 128, 2, 1024))
     assert rc == B.OK and status == 0
     assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("tau", [1, 2, 3, 5, 16, 33, 64])
+@pytest.mark.parametrize("n,kb", [(700, 256), (150_001, 1024), (400_003, 4096)])
+def test_narrow_value_tokens(tau, n, kb):
+    # tau <= 64: value tokens of 1 + ceil(log2 tau) < 8 bits (Section 3.2), bit-packed; sizes span
+    # several blocks, rounds of 1024 inside a block, and ragged tails
+    rng = np.random.default_rng(tau * 1000 + kb)
+    keys = np.sort(rng.choice(4 * n, n, replace=False)).astype(np.uint32)
+    vals = rng.laplace(0.0, 1e-3, n).astype(np.float32)
+    vals[::n // 10] *= np.float32(1e4)           # a few dominant values: something survives even for tau = 1
+    st = check_round_trip(keys, vals, W.solve_base(vals, 0.6, tau), tau, 2, kb)
+    assert int(st[40:48].view("<u8")[0]) >= 1

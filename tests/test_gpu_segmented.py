@@ -101,3 +101,21 @@ def test_batch_without_key_array_uses_the_indices_inside_each_segment():
     rc, status, blob, so = G.hip_compress_segmented(None, vals, offs, [B.params(b) for b in bases])
     assert rc == B.OK and status == 0
     assert np.array_equal(so, so_ref) and np.array_equal(blob, blob_ref)
+
+
+def test_batch_with_mixed_token_widths():
+    # segments with tau from 1 to 128 in one call: value tokens of 1 to 8 bits side by side
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(44)
+    taus = [128, 64, 5, 1, 33, 16, 2, 100, 3]
+    sizes = [5000, 70_001, 4097, 300, 12289, 250_003, 1, 0, 9000]
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.uint64)
+    keys = np.concatenate([np.arange(s, dtype=np.uint32) for s in sizes])
+    vals = np.concatenate([rng.laplace(0, 1e-3, s) for s in sizes]).astype(np.float32)
+    args = []
+    for i, (tau, s) in enumerate(zip(taus, sizes)):
+        seg = vals[int(offs[i]):int(offs[i + 1])]
+        if s > 20:
+            seg[::max(s // 7, 1)] *= np.float32(3e3)
+        args.append((W.solve_base(seg, 0.4, tau) if s > 20 else 1.3, tau, 1 + i % 4, 256 << (i % 4)))
+    check_segmented(keys, vals, offs, [ref.params(*a) for a in args], [B.params(*a) for a in args])
