@@ -203,15 +203,19 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
     const u32 pw0 = pbit >> 5, wbits = pbit & 31u;
     u32 npw = ((wbits + n * M + 31u) >> 5) + 1u;           // words this round can reach (+1: windows)
     if (npw > kSub + 2) npw = kSub + 2;
-    // all fetches of the round first
+    // all fetches of the round first; flags and payload through buffer descriptors that end with the
+    // words the round may use, so that lanes beyond them read 0 without a test
     u32 fw[3], pwd[17];
+    const u32 pw_left = pw_total > pw0 ? pw_total - pw0 : 0u;
+    const __amdgpu_buffer_rsrc_t frs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u32*>(fsrc_round), 0, (int)uniform(nfw * 4u), kBufferWord3);
+    const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u32*>(psrc + uniform(pw0)), 0, (int)uniform((pw_left < npw ? pw_left : npw) * 4u), kBufferWord3);
 #pragma unroll
-    for (u32 k = 0; k < 3; ++k) { const u32 i = k * 64u + lane; fw[k] = fsrc_round[i < nfw ? i : 0u]; }
+    for (u32 k = 0; k < 3; ++k) fw[k] = __builtin_amdgcn_raw_buffer_load_b32(frs, (int)(lane * 4u + k * 256u), 0, 0);
 #pragma unroll
-    for (u32 k = 0; k < 17; ++k) {
-        const u32 i = k * 64u + lane;
-        pwd[k] = (k * 64u < npw && pw_total) ? psrc[(pw0 + i < pw_total) ? pw0 + i : pw_total - 1u] : 0u;
-    }
+    for (u32 k = 0; k < 17; ++k)
+        pwd[k] = (k * 64u < npw) ? __builtin_amdgcn_raw_buffer_load_b32(prs, (int)(lane * 4u + k * 256u), 0, 0) : 0u;
     u32 cw[4];                                             // the lane's 16 code bytes
     if (cwid != 8) {
         // narrower tokens are widened further down, once the other fetches are parked
@@ -232,12 +236,10 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         }
     }
 #pragma unroll
-    for (u32 k = 0; k < 3; ++k) { const u32 i = k * 64u + lane; if (i < nfw + 3u) s_flg[i] = (i < nfw) ? fw[k] : 0u; }
+    for (u32 k = 0; k < 3; ++k) s_flg[k * 64u + lane] = fw[k];                     // (zeros behind the round's flags)
 #pragma unroll
-    for (u32 k = 0; k < 17; ++k) {
-        const u32 i = k * 64u + lane;
-        if (k * 64u < npw && i < npw) s_pay[i] = (pw0 + i < pw_total) ? pwd[k] : 0u;
-    }
+    for (u32 k = 0; k < 17; ++k)
+        if (k * 64u < npw) s_pay[k * 64u + lane] = pwd[k];                         // (zeros behind the payload)
     wave_lds_sync();
     if (cwid != 8) {
         // token i of the round sits at bit i * cwid of the round's words; each is widened to the byte
@@ -276,7 +278,7 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         for (u32 k = 0; k < 8; ++k) {
             const u32 flag = (u32)fwin & lmask;
             fwin >>= l;
-            u32 ln = (flag * M + lenc) >> l;
+            u32 ln = (__umul24(flag, M) + lenc) >> l;
             if (!FULL && lane * kLaneKeys + half * 8u + k >= n) ln = 0;
             len[half * 8u + k] = ln;
         }
@@ -292,6 +294,8 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
     u32 kp[kLaneKeys];
     u32 acc = 0;
     bool ovf = false;
+    // (sixteen deltas of at most 27 bits cannot wrap a lane's running sum)
+    const bool wrap_possible = M > 27u;
 #pragma unroll
     for (u32 k = 0; k < kLaneKeys; ++k) {
         const u32 wa = bp >> 5;
@@ -300,29 +304,26 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         if (!FULL && len[k] == 0) dl = 0;                   // (a real key has a length of at least 1)
         bp += len[k];
         const u32 nx = acc + dl;
-        ovf |= nx < acc;
+        if (wrap_possible) ovf |= nx < acc;
         acc = nx;
         kp[k] = acc;
     }
     const u64 incl64 = wave_incl_scan64((u64)acc);
     const u64 kbase = (u64)carry + incl64 - acc;            // key before the lane's first key
-    ovf |= (kbase >> 32) != 0 && (FULL || lane * kLaneKeys < n);
+    // the lane's keys do not decrease, so the last one tells whether any of them leaves 32 bits
+    ovf |= ((kbase + acc) >> 32) != 0 && (FULL || lane * kLaneKeys < n);
 #pragma unroll
-    for (u32 k = 0; k < kLaneKeys; ++k) {
-        const u32 key = (u32)kbase + kp[k];
-        ovf |= key < (u32)kbase && (FULL || lane * kLaneKeys + k < n);
-        kp[k] = key;
-    }
-    // values: code byte -> magnitude, sign on top
-    bool badcode = false;
+    for (u32 k = 0; k < kLaneKeys; ++k) kp[k] = (u32)kbase + kp[k];
+    // values: the code byte (sign in bit 7) indexes a table of signed values; a code >= tau shows as a
+    // carry into bit 7 of (code-1) + (128 - tau), tested four bytes at a time
+    const u32 over = (128u - tau) * 0x01010101u;
+    u32 badbits = 0;
+#pragma unroll
+    for (u32 j = 0; j < 4; ++j) badbits |= ((cw[j] & 0x7F7F7F7Fu) + over) & 0x80808080u;
+    const bool badcode = badbits != 0;                      // (bytes beyond n are 0: code 1, never beyond tau)
     u32 vb[kLaneKeys];
 #pragma unroll
-    for (u32 k = 0; k < kLaneKeys; ++k) {
-        const u32 byte = (cw[k >> 2] >> (8u * (k & 3u))) & 0xFFu;
-        const u32 c = byte & 0x7Fu;                         // code - 1
-        badcode |= c >= tau && (FULL || lane * kLaneKeys + k < n);
-        vb[k] = s_V[c] | ((byte >> 7) << 31);
-    }
+    for (u32 k = 0; k < kLaneKeys; ++k) vb[k] = s_V[(cw[k >> 2] >> (8u * (k & 3u))) & 0xFFu];
     if (MODE != kStore) {
         // all reads of a lane's sixteen keys are issued before the first write: the keys of a valid
         // stream are distinct, and a stream that is not valid leaves unspecified arrays anyway
@@ -405,9 +406,9 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(M
 k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u32 n_segments, DecCtrl* ctrl,
          u32* __restrict__ keys_out, float* __restrict__ values_out, u64* out_counts, u32 n_counts,
          u32* out_status, float* __restrict__ dense, u64 dense_len, u32 only, AdamArgs adam) {
-    __shared__ __attribute__((aligned(16))) u32 s_payall[kWaves][kSub + 4];
-    __shared__ u32 s_flgall[kWaves][kSub * 5 / 32 + 4];
-    __shared__ u32 s_Vall[kWaves][128];
+    __shared__ __attribute__((aligned(16))) u32 s_payall[kWaves][17 * 64];     // payload window, whole rows of 64 words
+    __shared__ u32 s_flgall[kWaves][3 * 64];                                    // flags of a round (160 words at most)
+    __shared__ u32 s_Vall[kWaves][256];                                         // value by code byte (bit 7: sign)
     __shared__ __attribute__((aligned(16))) u32 s_codall[kWaves][2 * kCodeWords];   // token words, then widened bytes
     const u32 lane = lane_id(), w = uniform(wave_id());
     u32* s_pay = s_payall[w];
@@ -429,8 +430,11 @@ k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u
         const u32 nsub = (cnt + kSub - 1) / kSub;
         if (seg != cur_seg) {
             wave_lds_sync();
-            s_V[lane] = ds->V[lane];
-            s_V[lane + 64] = ds->V[lane + 64];
+            const u32 m0 = ds->V[lane], m1 = ds->V[lane + 64];      // magnitudes; the upper half of the table: negative
+            s_V[lane] = m0;
+            s_V[lane + 64] = m1;
+            s_V[lane + 128] = m0 | 0x80000000u;
+            s_V[lane + 192] = m1 | 0x80000000u;
             cur_seg = seg;
             wave_lds_sync();
         }

@@ -230,6 +230,7 @@ __device__ __forceinline__ u64 align8(u64 x) { return (x + 7) & ~7ull; }
 __device__ __forceinline__ u32 code_width(u32 tau) { return 1u + (32u - (u32)__clz((int)(tau - 1u))); }
 // Bytes of the value plane: d tokens of `width` bits, zero-padded to 64-bit words.
 __device__ __forceinline__ u64 value_plane_bytes(u64 d, u32 width) { return 8ull * ((d * width + 63ull) >> 6); }
+constexpr int kBufferWord3 = 0x00020000;   // fourth word of a gfx9 raw buffer descriptor: 32-bit data format
 constexpr u32 kCodeWords = 32u * 8u;   // 32-bit words of 1024 tokens of at most 8 bits
 
 // Level lengths of Algorithm 2's length flag for a block with maximal length M and l flag bits:
