@@ -716,21 +716,30 @@ __device__ __forceinline__ void lds_excl_scan(T* arr, u32 n, T* scratch) {
     __syncthreads();
 }
 
-// Largest j in [0, nch) with P[j] <= r, for a rank r that is the same in all lanes (P[0] = 0 <= r):
-// the wave probes 64 entries at a time, so two shared-memory round trips cover 4096 chunks.
-__device__ __forceinline__ u32 find_chunk_wave(const u32* P, u32 nch, u32 r, u32 lane) {
-    const u32 i1 = lane * 64u;
-    const bool p1 = i1 < nch && P[i1 < nch ? i1 : 0u] <= r;
-    const u32 c = (u32)__popcll(__ballot(p1)) - 1u;
+// Largest j in [0, nch) with P[j] <= r, for a rank r that is the same in all lanes (P[0] = 0 <= r); *pj
+// receives P[j].  `coarse` is the wave's copy of every 64th entry of P in shared memory (load_coarse), so
+// one memory round trip suffices: the wave reads the 64 entries behind the last coarse hit.
+__device__ __forceinline__ u32 find_chunk_wave(const u32* P, const u32* coarse, u32 nch, u32 r, u32 lane, u32* pj) {
+    const u32 c = (u32)__popcll(__ballot(coarse[lane] <= r)) - 1u;
     const u32 i2 = c * 64u + lane;
-    const bool p2 = i2 < nch && P[i2 < nch ? i2 : 0u] <= r;
-    return c * 64u + (u32)__popcll(__ballot(p2)) - 1u;
+    const u32 v = i2 < nch ? P[i2] : 0xFFFFFFFFu;
+    const u32 c2 = (u32)__popcll(__ballot(v <= r)) - 1u;
+    *pj = read_lane(v, uniform(c2));
+    return c * 64u + c2;
 }
 
 __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Every 64th entry of the chunk scan P of a segment (0xFFFFFFFF beyond its nch chunks) into 64 words of
+// the wave's shared memory.
+__device__ __forceinline__ void load_coarse(const u32* P, u32 nch, u32 lane, u32* coarse) {
+    wave_lds_sync();
+    coarse[lane] = lane * 64u < nch ? P[lane * 64u] : 0xFFFFFFFFu;
+    wave_lds_sync();
 }
 
 __device__ __forceinline__ u32 wave_incl_scan_max(u32 x) {
@@ -751,10 +760,10 @@ constexpr u32 kKeyRows = kSub / 64;   // rows of 64 keys a wave handles at a tim
 // used).  jlo / jhi are the chunks of the first / last of these ranks.  If the run crosses chunks,
 // every chunk that starts inside it leaves its number at its first rank in `mark` (1024 words of the
 // wave's shared memory, clobbered), and a running maximum spreads the numbers over the ranks.
-__device__ __forceinline__ void find_entries(const u32* P, u32 stride, u32 jlo, u32 jhi, u32 r0, u32 n, u32 lane,
-                                             u32* mark, u32 (&ent)[kKeyRows]) {
+__device__ __forceinline__ void find_entries(const u32* P, u32 stride, u32 jlo, u32 pjlo, u32 jhi, u32 r0, u32 n,
+                                             u32 lane, u32* mark, u32 (&ent)[kKeyRows]) {
     if (jlo == jhi) {
-        const u32 base = jlo * stride - P[jlo];
+        const u32 base = jlo * stride - pjlo;               // pjlo = P[jlo]
 #pragma unroll
         for (u32 q = 0; q < kKeyRows; ++q) ent[q] = base + r0 + q * 64u + lane;
         return;
@@ -787,12 +796,13 @@ __device__ __forceinline__ void find_entries(const u32* P, u32 stride, u32 jlo, 
 // fetches are coalesced wherever the ranks are contiguous in the scratch array) and handed to the lanes
 // 16 CONSECUTIVE keys each through `buf` (1024 words of the wave's shared memory, 16-byte aligned,
 // clobbered): kb[k] = key 16*lane + k (0 beyond n).  ent[q] keeps the scratch entry of key 64*q + lane.
-__device__ __forceinline__ void gather_blocked(const u32* P, u32 nch, u32 stride, const u32* __restrict__ seg_keys,
-                                               u32 r0, u32 n, u32 lane, u32* buf, u32 (&ent)[kKeyRows],
-                                               u32 (&kb)[kLaneKeys]) {
-    const u32 jlo = uniform(find_chunk_wave(P, nch, r0, lane));
-    const u32 jhi = uniform(find_chunk_wave(P, nch, r0 + n - 1, lane));
-    find_entries(P, stride, jlo, jhi, r0, n, lane, buf, ent);
+__device__ __forceinline__ void gather_blocked(const u32* P, const u32* coarse, u32 nch, u32 stride,
+                                               const u32* __restrict__ seg_keys, u32 r0, u32 n, u32 lane, u32* buf,
+                                               u32 (&ent)[kKeyRows], u32 (&kb)[kLaneKeys]) {
+    u32 pjlo, pjhi;
+    const u32 jlo = uniform(find_chunk_wave(P, coarse, nch, r0, lane, &pjlo));
+    const u32 jhi = uniform(find_chunk_wave(P, coarse, nch, r0 + n - 1, lane, &pjhi));
+    find_entries(P, stride, jlo, pjlo, jhi, r0, n, lane, buf, ent);
     u32 key[kKeyRows];
 #pragma unroll
     for (u32 q = 0; q < kKeyRows; ++q) key[q] = (q * 64u + lane < n) ? seg_keys[ent[q]] : 0u;
@@ -846,17 +856,21 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
     __shared__ __attribute__((aligned(16))) u32 s_bufall[kWaves][kSub];
     __shared__ __attribute__((aligned(16))) uint8_t s_needall[kWaves][BIG ? kMaxKB : 16];   // bit lengths of a big block's deltas
     __shared__ u32 s_lutall[kWaves][33];
+    __shared__ u32 s_coarseall[kWaves][64];
     const u32 lane = lane_id(), w = uniform(wave_id());
     uint8_t* s_need = s_needall[w];
     u32* s_buf = s_bufall[w];
     u32* s_lut = s_lutall[w];
+    u32* s_coarse = s_coarseall[w];
     const u64 total_units = ctrl->total_units;
+    u32 coarse_seg = 0xFFFFFFFFu;                           // segment whose scan s_coarse samples
     for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x) {
         SegInfo info;
         const KeyUnit ku = key_unit(seg0, segs, states, n_segments, R, unit, &info);
         const u32* P = ccount + ku.cb;                      // the segment's chunk scan
         const u32 blk = ku.blk0 + w;
         if (blk >= (ku.nb ? ku.nb : 1u)) continue;
+        if (ku.seg != coarse_seg && ku.nb) { load_coarse(P, ku.nch, lane, s_coarse); coarse_seg = ku.seg; }
         const u64 item = ku.item_begin + blk;
         const u32 head8 = (u32)((kHeaderBytes + value_plane_bytes(ku.d, code_width(info.tau)) + 16ull * ku.nb) >> 3);   // first item of a segment
         if (ku.nb == 0) {                                   // a segment without survivors: its header only
@@ -875,8 +889,9 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
         // the key before the block (none for the segment's first block)
         u32 preKey = 0;
         if (first) {
-            const u32 jp = uniform(find_chunk_wave(P, ku.nch, first - 1, lane));
-            preKey = seg_keys[jp * stride + (first - 1 - P[jp])];
+            u32 pjp;
+            const u32 jp = uniform(find_chunk_wave(P, s_coarse, ku.nch, first - 1, lane, &pjp));
+            preKey = seg_keys[jp * stride + (first - 1 - pjp)];
         }
         // first loop of Algorithm 2: deltas and the longest of them (M = bit length of maxDelta)
         u64 unsorted = 0;
@@ -886,7 +901,7 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
             const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
             const u32 r0 = first + sub * kSub;
             u32 ent[kKeyRows], kb[kLaneKeys], dl[kLaneKeys];
-            gather_blocked(P, ku.nch, stride, seg_keys, r0, n, lane, s_buf, ent, kb);
+            gather_blocked(P, s_coarse, ku.nch, stride, seg_keys, r0, n, lane, s_buf, ent, kb);
             if (sub == 0) carry = uniform(preKey);              // (its fetch was in flight until here)
             if (n == kSub) lane_deltas<true>(kb, r0, n, lane, carry, dl, unsorted);
             else lane_deltas<false>(kb, r0, n, lane, carry, dl, unsorted);
@@ -953,10 +968,13 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
     __shared__ __attribute__((aligned(16))) u32 s_payall[kWaves][kSub + 4];
     __shared__ u32 s_flgall[kWaves][kSub * 5 / 32 + 2];
     __shared__ u32 s_lutall[kWaves][33];
+    __shared__ u32 s_coarseall[kWaves][64];
     const u32 t = threadIdx.x, lane = lane_id(), w = uniform(wave_id());
     u32* s_pay = s_payall[w];
     u32* s_flg = s_flgall[w];
     u32* s_lut = s_lutall[w];
+    u32* s_coarse = s_coarseall[w];
+    u32 coarse_seg = 0xFFFFFFFFu;                           // segment whose scan s_coarse samples
     const u64 total_items = ctrl->total_items, total_units = ctrl->total_units;
     if (blockIdx.x != 0 && blockIdx.x >= total_units) return;     // nothing to pack and nothing to report
     // byte offsets of the groups of work items
@@ -1022,6 +1040,7 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
             }
         }
         if (ku.nb == 0) continue;                                      // a segment without survivors
+        if (ku.seg != coarse_seg) { load_coarse(P, ku.nch, lane, s_coarse); coarse_seg = ku.seg; }
         const BlockInfo bi = binfo[item];
         const u32 M = uniform(bi.M), l = ku.l, magic = level_magic(M);
         const u32 first = uniform(blk * ku.KB);
@@ -1059,7 +1078,7 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
             const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
             const u32 r0 = first + sub * kSub;
             u32 ent[kKeyRows], kb[kLaneKeys], dl[kLaneKeys], code[kKeyRows];
-            gather_blocked(P, ku.nch, stride, seg_keys, r0, n, lane, s_pay, ent, kb);    // borrows the payload window
+            gather_blocked(P, s_coarse, ku.nch, stride, seg_keys, r0, n, lane, s_pay, ent, kb);    // borrows the payload window
 #pragma unroll
             for (u32 q = 0; q < kKeyRows; ++q) code[q] = (q * 64u + lane < n) ? seg_codes[ent[q]] : 0u;
             if (cwid == 8) {
