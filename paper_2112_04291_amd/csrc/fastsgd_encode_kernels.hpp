@@ -653,16 +653,17 @@ __device__ __forceinline__ u32 segment_chunks(const SegInfo& s, u32 R) {
 }
 
 // `seg0` is the segment record of a single-gradient call (a kernel argument, so no load is needed).
+// d0 / nb0: survivors and key blocks of segment 0, read once per kernel.
 __device__ __forceinline__ KeyUnit key_unit(const SegInfo& seg0, const SegInfo* __restrict__ segs,
                                             const SegState* __restrict__ states, u32 n_segments, u32 R,
-                                            u64 unit, SegInfo* info_out) {
+                                            u64 unit, u64 d0, u32 nb0, SegInfo* info_out) {
     KeyUnit ku;
     if (n_segments == 1) {
         *info_out = seg0;
         ku.seg = 0;
         ku.KB = seg0.block_keys;
-        ku.d = states[0].d;
-        ku.nb = states[0].nb;
+        ku.d = d0;
+        ku.nb = nb0;
         ku.item_begin = 0;
         ku.blk0 = (u32)unit * kWaves;
     } else {
@@ -734,6 +735,26 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// The same for three ranks at once (ra <= rb <= rc), with the three fetches in flight together.
+__device__ __forceinline__ void find_chunks3(const u32* P, const u32* coarse, u32 nch, u32 ra, u32 rb, u32 rc, u32 lane,
+                                             u32 (&j)[3], u32 (&pj)[3]) {
+    const u32 cv = coarse[lane];
+    const u32 r[3] = {ra, rb, rc};
+    u32 c[3], v[3];
+#pragma unroll
+    for (u32 k = 0; k < 3; ++k) {
+        c[k] = (u32)__popcll(__ballot(cv <= r[k])) - 1u;
+        const u32 i2 = c[k] * 64u + lane;
+        v[k] = i2 < nch ? P[i2] : 0xFFFFFFFFu;
+    }
+#pragma unroll
+    for (u32 k = 0; k < 3; ++k) {
+        const u32 c2 = (u32)__popcll(__ballot(v[k] <= r[k])) - 1u;
+        pj[k] = read_lane(v[k], uniform(c2));
+        j[k] = uniform(c[k] * 64u + c2);
+    }
+}
+
 // Every 64th entry of the chunk scan P of a segment (0xFFFFFFFF beyond its nch chunks) into 64 words of
 // the wave's shared memory.
 __device__ __forceinline__ void load_coarse(const u32* P, u32 nch, u32 lane, u32* coarse) {
@@ -798,10 +819,14 @@ __device__ __forceinline__ void find_entries(const u32* P, u32 stride, u32 jlo, 
 // clobbered): kb[k] = key 16*lane + k (0 beyond n).  ent[q] keeps the scratch entry of key 64*q + lane.
 __device__ __forceinline__ void gather_blocked(const u32* P, const u32* coarse, u32 nch, u32 stride,
                                                const u32* __restrict__ seg_keys, u32 r0, u32 n, u32 lane, u32* buf,
-                                               u32 (&ent)[kKeyRows], u32 (&kb)[kLaneKeys]) {
-    u32 pjlo, pjhi;
-    const u32 jlo = uniform(find_chunk_wave(P, coarse, nch, r0, lane, &pjlo));
-    const u32 jhi = uniform(find_chunk_wave(P, coarse, nch, r0 + n - 1, lane, &pjhi));
+                                               u32 (&ent)[kKeyRows], u32 (&kb)[kLaneKeys], u32* prekey) {
+    // chunks of the key before the run (if there is one and the caller wants it), of its first and of its last key
+    u32 j[3], pj[3];
+    const bool want_pre = prekey != nullptr && r0 != 0;
+    find_chunks3(P, coarse, nch, want_pre ? r0 - 1u : r0, r0, r0 + n - 1u, lane, j, pj);
+    u32 pre = 0;
+    if (want_pre) pre = seg_keys[j[0] * stride + (r0 - 1u - pj[0])];
+    const u32 jlo = j[1], pjlo = pj[1], jhi = j[2];
     find_entries(P, stride, jlo, pjlo, jhi, r0, n, lane, buf, ent);
     u32 key[kKeyRows];
 #pragma unroll
@@ -816,6 +841,7 @@ __device__ __forceinline__ void gather_blocked(const u32* P, const u32* coarse, 
         kb[4 * j] = x.x; kb[4 * j + 1] = x.y; kb[4 * j + 2] = x.z; kb[4 * j + 3] = x.w;
     }
     wave_lds_sync();
+    if (prekey) *prekey = uniform(pre);
 }
 
 // Deltas of the lane's 16 keys (Eq. 4): dl[k] = kb[k] - key before it; `carry` is the key before the
@@ -864,9 +890,11 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
     u32* s_coarse = s_coarseall[w];
     const u64 total_units = ctrl->total_units;
     u32 coarse_seg = 0xFFFFFFFFu;                           // segment whose scan s_coarse samples
+    const u64 d0 = states[0].d;
+    const u32 nb0 = states[0].nb;
     for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x) {
         SegInfo info;
-        const KeyUnit ku = key_unit(seg0, segs, states, n_segments, R, unit, &info);
+        const KeyUnit ku = key_unit(seg0, segs, states, n_segments, R, unit, d0, nb0, &info);
         const u32* P = ccount + ku.cb;                      // the segment's chunk scan
         const u32 blk = ku.blk0 + w;
         if (blk >= (ku.nb ? ku.nb : 1u)) continue;
@@ -886,13 +914,7 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
         const u32 nsub = (cnt + kSub - 1) / kSub;
         const u32 stride = R * kRow;
         const u32* seg_keys = skeys + chunk_slot0(info, ku.seg, 0, R);
-        // the key before the block (none for the segment's first block)
-        u32 preKey = 0;
-        if (first) {
-            u32 pjp;
-            const u32 jp = uniform(find_chunk_wave(P, s_coarse, ku.nch, first - 1, lane, &pjp));
-            preKey = seg_keys[jp * stride + (first - 1 - pjp)];
-        }
+        u32 preKey = 0;                                     // the key before the block (none for the segment's first block)
         // first loop of Algorithm 2: deltas and the longest of them (M = bit length of maxDelta)
         u64 unsorted = 0;
         u32 carry = 0, mxneed = 0;
@@ -901,8 +923,8 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
             const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
             const u32 r0 = first + sub * kSub;
             u32 ent[kKeyRows], kb[kLaneKeys], dl[kLaneKeys];
-            gather_blocked(P, s_coarse, ku.nch, stride, seg_keys, r0, n, lane, s_buf, ent, kb);
-            if (sub == 0) carry = uniform(preKey);              // (its fetch was in flight until here)
+            gather_blocked(P, s_coarse, ku.nch, stride, seg_keys, r0, n, lane, s_buf, ent, kb, sub == 0 ? &preKey : nullptr);
+            if (sub == 0) carry = preKey;
             if (n == kSub) lane_deltas<true>(kb, r0, n, lane, carry, dl, unsorted);
             else lane_deltas<false>(kb, r0, n, lane, carry, dl, unsorted);
 #pragma unroll
@@ -1000,9 +1022,11 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
     for (u32 i = lane; i < kSub * 5 / 32 + 2; i += 64) s_flg[i] = 0;
     u64 sbeg8 = 0;
     u32 cur_seg = 0xFFFFFFFFu;
+    const u64 d0 = states[0].d;
+    const u32 nb0 = states[0].nb;
     for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x) {
         SegInfo info;
-        const KeyUnit ku = key_unit(seg0, segs, states, n_segments, R, unit, &info);
+        const KeyUnit ku = key_unit(seg0, segs, states, n_segments, R, unit, d0, nb0, &info);
         const u32* P = ccount + ku.cb;                      // the segment's chunk scan
         if (ku.seg != cur_seg) {
             cur_seg = ku.seg;
@@ -1078,7 +1102,7 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
             const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
             const u32 r0 = first + sub * kSub;
             u32 ent[kKeyRows], kb[kLaneKeys], dl[kLaneKeys], code[kKeyRows];
-            gather_blocked(P, s_coarse, ku.nch, stride, seg_keys, r0, n, lane, s_pay, ent, kb);    // borrows the payload window
+            gather_blocked(P, s_coarse, ku.nch, stride, seg_keys, r0, n, lane, s_pay, ent, kb, nullptr);    // borrows the payload window
 #pragma unroll
             for (u32 q = 0; q < kKeyRows; ++q) code[q] = (q * 64u + lane < n) ? seg_codes[ent[q]] : 0u;
             if (cwid == 8) {
