@@ -382,18 +382,20 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         too_big |= __any(big);
         return !(__any(ovf) || __any(badcode));
     }
-    // through shared memory to the output arrays: lane-major in, row-major out
+    // through shared memory to the output arrays: lane-major in, row-major out.  A lane's 16 words sit
+    // 20 words apart (word i at i + 4 * (i / 16)), which spreads the 16-byte writes over all banks.
     wave_lds_sync();
-    uint4* t4 = reinterpret_cast<uint4*>(s_pay) + lane * 4u;
+    uint4* t4 = reinterpret_cast<uint4*>(s_pay) + lane * 5u;
+    const u32 rowpos = lane + 4u * (lane >> 4);            // position of word 64 * q + lane: rowpos + 80 * q
 #pragma unroll
     for (u32 j = 0; j < 4; ++j) t4[j] = make_uint4(kp[4 * j], kp[4 * j + 1], kp[4 * j + 2], kp[4 * j + 3]);
     wave_lds_sync();
 #pragma unroll
     for (u32 q = 0; q < kLaneKeys; ++q) {
         const u32 i = q * 64u + lane;
-        if (FULL || i < n) keys_dst[i] = s_pay[i];
+        if (FULL || i < n) keys_dst[i] = s_pay[rowpos + 80u * q];
     }
-    carry = s_pay[n - 1];                                    // last key of the round (same in all lanes)
+    carry = s_pay[(n - 1u) + 4u * ((n - 1u) >> 4)];          // last key of the round (same in all lanes)
     wave_lds_sync();
 #pragma unroll
     for (u32 j = 0; j < 4; ++j) t4[j] = make_uint4(vb[4 * j], vb[4 * j + 1], vb[4 * j + 2], vb[4 * j + 3]);
@@ -401,7 +403,7 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
 #pragma unroll
     for (u32 q = 0; q < kLaneKeys; ++q) {
         const u32 i = q * 64u + lane;
-        if (FULL || i < n) values_dst[i] = __uint_as_float(s_pay[i]);
+        if (FULL || i < n) values_dst[i] = __uint_as_float(s_pay[rowpos + 80u * q]);
     }
     wave_lds_sync();
     pbit += roundbits;
@@ -415,7 +417,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(M
 k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u32 n_segments, DecCtrl* ctrl,
          u32* __restrict__ keys_out, float* __restrict__ values_out, u64* out_counts, u32 n_counts,
          u32* out_status, float* __restrict__ dense, u64 dense_len, u32 only, AdamArgs adam) {
-    __shared__ __attribute__((aligned(16))) u32 s_payall[kWaves][17 * 64];     // payload window, whole rows of 64 words
+    __shared__ __attribute__((aligned(16))) u32 s_payall[kWaves][20 * 64];     // payload window (17 rows of 64 words); output staging (1280 words)
     __shared__ u32 s_flgall[kWaves][3 * 64];                                    // flags of a round (160 words at most)
     __shared__ u32 s_Vall[kWaves][256];                                         // value by code byte (bit 7: sign)
     __shared__ __attribute__((aligned(16))) u32 s_codall[kWaves][2 * kCodeWords];   // token words, then widened bytes
