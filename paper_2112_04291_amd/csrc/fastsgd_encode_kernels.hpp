@@ -339,8 +339,8 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
 // encoder scans the (at most 4096) chunk counts of a segment in shared memory and gathers through
 // that scan.
 // Lane `lane` holds elements row*256 + lane*4 + {0..3} of each row in hand.
-constexpr u32 kStage = 1152;             // staged survivors per wave: four full rows on top of the flush level
-constexpr u32 kFlushLevel = kStage - 4 * kRow;
+constexpr u32 kStage = 1216;             // staged survivors per wave: two full rows on top of the flush level
+constexpr u32 kFlushLevel = kStage - 2 * kRow;
 constexpr u32 kValWaves = 4;             // waves per workgroup of the value encoder (they never synchronise)
 constexpr u32 kGather = 4;               // key fetches a lane keeps in flight
 
@@ -524,15 +524,17 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
         for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_row(rows[slot], quarters[slot], bits[slot]);
         while (nr) {
 #pragma unroll
-            for (u32 slot = 0; slot < 4; ++slot) if (slot < nr) stage_row(bits[slot], rows[slot] * kRow);
-            if (staged > kFlushLevel) flush();                     // room for four more rows
+            for (u32 pair = 0; pair < kValRows / 2; ++pair) {
 #pragma unroll
-            for (u32 slot = 4; slot < 8; ++slot) if (slot < nr) stage_row(bits[slot], rows[slot] * kRow);
-            // the registers are free: start on the next rows before finishing these
-            nr = take(rows, quarters);
+                for (u32 slot = 2 * pair; slot < 2 * pair + 2; ++slot) if (slot < nr) stage_row(bits[slot], rows[slot] * kRow);
+                if (pair + 1 == kValRows / 2) {
+                    // the registers are free: start on the next rows before finishing these
+                    nr = take(rows, quarters);
 #pragma unroll
-            for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_row(rows[slot], quarters[slot], bits[slot]);
-            if (staged > kFlushLevel) flush();
+                    for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_row(rows[slot], quarters[slot], bits[slot]);
+                }
+                if (staged > kFlushLevel) flush();                 // room for two more rows
+            }
         }
     }
     if (staged) flush();
