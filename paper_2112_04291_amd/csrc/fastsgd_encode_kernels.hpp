@@ -4,7 +4,7 @@
 //   k_abs_sum        Algorithm 1 line 1: exact sum of |v| per segment (integer accumulation)
 //   k_tables         Algorithm 1 line 2 + Eq. 3 as a boundary table sum / b^c, c = 1..tau
 //   k_encode_values  Algorithm 1 lines 4-10: threshold test, code, sign, compaction of survivors
-//   k_plan_segments  batch calls: per segment survivors d, key blocks, work-item numbering
+//   k_plan_segments  per segment: scan of the chunk counts, survivors d, key blocks; batch calls: work-item numbering
 //   k_measure_keys   Algorithm 2, first loop, per key block: deltas, maxDelta -> M, size of the block
 //   k_pack_keys      Algorithm 2, second loop: length flags, bit packing; directory, headers, value planes
 #pragma once
@@ -330,13 +330,13 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
 //   the row maxima the first pass left behind tell which rows can hold a survivor at all (the
 //   early-stop test of Algorithm 1 line 5 applied to a whole row); only those rows are read, eight at
 //   a time -> per row, keep test |v| >= threshold as four wave-wide masks -> survivors are staged in
-//   the wave's slice of shared memory in element order (mask popcounts + mbcnt) -> once more than a
-//   few hundred wait there, densely over the staged survivors only: code by binary search in the
+//   the wave's slice of shared memory in element order (mask popcounts + mbcnt) -> once more than
+//   seven hundred wait there, densely over the staged survivors only: code by binary search in the
 //   boundary table, key fetch -> code byte and key appended to the CHUNK'S OWN SLOT of the scratch
 //   arrays (the chunk's first element index + rank in the chunk).  The loads of the next eight rows
 //   are issued before that flush, so its round trip overlaps with them.
-// The chunk's survivor count goes to ccount[chunk].  Global ranks are never materialised: the key
-// encoder scans the (at most 4096) chunk counts of a segment in shared memory and gathers through
+// The chunk's survivor count goes to ccount[chunk].  Global ranks are never materialised: k_plan_segments
+// turns the (at most 4096) chunk counts of a segment into their scan and the key encoder gathers through
 // that scan.
 // Lane `lane` holds elements row*256 + lane*4 + {0..3} of each row in hand.
 constexpr u32 kStage = 1216;             // staged survivors per wave: two full rows on top of the flush level
