@@ -70,3 +70,64 @@ def test_config5_segmented_60m():
     assert rc == B.OK and status == 0
     assert np.array_equal(po, po_ref) and np.array_equal(k, k_ref)
     assert np.array_equal(v.view(np.uint32), v_ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("n", [(1 << 31) + 12345, (1 << 32) - 1024])
+def test_gradients_beyond_2_to_the_31_and_at_the_size_limit(n):
+    """The largest gradient the library takes (2^32 - 1024 elements, 17 GB of values, no key array) and one
+    just past 2^31.  The oracle cannot hold such an input in this test's time, so the result is checked by
+    what holds at any size: the header's sum against a binary64 sum, the surviving keys against the
+    threshold of the oracle's table applied to every element on the device, the stream against the
+    oracle's decoder, values against the quantization bound of Eq. 3 (sum / b^c <= |v| < sum / b^(c-1))."""
+    torch, B, G = _gpu()
+    free, _ = torch.cuda.mem_get_info()
+    ws_bytes = B.workspace_size(n, 1, 1024)
+    if free < 4 * n + ws_bytes + (8 << 30):
+        pytest.skip("not enough device memory for the largest gradient")
+    print(f"[fullsize] n={n} workspace={ws_bytes}", flush=True)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(n & 0xFFFF)
+    v = torch.empty(n, dtype=torch.float32, device="cuda")
+    step = 1 << 28
+    total = 0.0
+    for lo in range(0, n, step):
+        part = v[lo:lo + step]
+        part.normal_(0.0, 1e-4, generator=gen)
+    planted = sorted({0, 1, 255, 256, n // 3, (1 << 31) - 1, 1 << 31, (1 << 31) + 1, n - 1025, n - 2, n - 1})
+    for i, pos in enumerate(planted):
+        v[pos] = (-1.0) ** i * (3.0 + i)
+    for lo in range(0, n, step):
+        total += float(v[lo:lo + step].abs().sum(dtype=torch.float64))
+    base = (total / 5.5e-4) ** (1.0 / 128.0)              # threshold about 5.5 sigma: a few hundred survivors
+    p = B.params(base)
+    cap = 1 << 20
+    out = torch.empty(cap // 8, dtype=torch.int64, device="cuda")
+    ws = torch.empty(ws_bytes // 8 + 32, dtype=torch.int64, device="cuda")
+    nbytes = torch.full((2,), -1, dtype=torch.int64, device="cuda")
+    status = torch.full((2,), -1, dtype=torch.int32, device="cuda")
+    rc = B.compress(None, v, p, out, nbytes, status, ws, n=n, out_capacity=cap)
+    torch.cuda.synchronize()
+    assert rc == B.OK and int(status[0]) == 0
+    st = out.view(torch.uint8)[:int(nbytes[0])].cpu().numpy().copy()
+    s_hdr = float(st[24:32].view("<f8")[0])
+    assert int(st[32:40].view("<u8")[0]) == n
+    assert abs(s_hdr - total) <= 1e-9 * total
+    Btab, Vtab = ref.tables(s_hdr, base, 128)
+    thr_bits = int(Btab[128])
+    keys = []
+    for lo in range(0, n, step):
+        bits = v[lo:lo + step].view(torch.int32).bitwise_and(0x7FFFFFFF)
+        keys.append(torch.nonzero(bits >= thr_bits).flatten().cpu().numpy() + lo)
+    keys = np.concatenate(keys).astype(np.uint64)
+    assert set(planted) <= set(int(k) for k in keys) and 20 < keys.size < 100_000
+    rc_ref, k_ref, v_ref = ref.decompress(st)
+    assert rc_ref == ref.OK
+    assert np.array_equal(k_ref.astype(np.uint64), keys)
+    orig = v[torch.from_numpy(keys.astype(np.int64)).cuda()].cpu().numpy().astype(np.float64)
+    dec = v_ref.astype(np.float64)
+    assert np.array_equal(np.signbit(dec), np.signbit(orig))
+    assert np.all(np.abs(dec) <= np.abs(orig) * (1 + 1e-6)) and np.all(np.abs(dec) * base * (1 + 1e-6) > np.abs(orig))
+    del v, ws
+    rc, status, k, vals = G.hip_decompress(st, capacity=keys.size)
+    assert rc == B.OK and status == 0
+    assert np.array_equal(k, k_ref) and np.array_equal(vals.view(np.uint32), v_ref.view(np.uint32))
