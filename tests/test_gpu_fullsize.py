@@ -131,3 +131,66 @@ def test_gradients_beyond_2_to_the_31_and_at_the_size_limit(n):
     rc, status, k, vals = G.hip_decompress(st, capacity=keys.size)
     assert rc == B.OK and status == 0
     assert np.array_equal(k, k_ref) and np.array_equal(vals.view(np.uint32), v_ref.view(np.uint32))
+
+
+def test_largest_gradient_with_a_hundred_million_survivors():
+    """2^32 - 1024 elements again, now with about 3 % of them kept: 4 million key blocks, ranks up to 2^27,
+    a stream of about 200 MB.  Keys: the decoder's output against the threshold applied on the device.
+    Stream: the oracle's decoder must read it and agree with the GPU decoder on every pair."""
+    torch, B, G = _gpu()
+    n = (1 << 32) - 1024
+    free, _ = torch.cuda.mem_get_info()
+    ws_bytes = B.workspace_size(n, 1, 1024)
+    if free < 4 * n + ws_bytes + (16 << 30):
+        pytest.skip("not enough device memory for the largest gradient")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    v = torch.empty(n, dtype=torch.float32, device="cuda")
+    step = 1 << 28
+    total = 0.0
+    for lo in range(0, n, step):
+        v[lo:lo + step].normal_(0.0, 1e-4, generator=gen)
+        total += float(v[lo:lo + step].abs().sum(dtype=torch.float64))
+    base = (total / 2.17e-4) ** (1.0 / 128.0)             # threshold about 2.17 sigma: 3 % survive
+    p = B.params(base)
+    cap = 1 << 30
+    out = torch.empty(cap // 8, dtype=torch.int64, device="cuda")
+    ws = torch.empty(ws_bytes // 8 + 32, dtype=torch.int64, device="cuda")
+    nbytes = torch.full((2,), -1, dtype=torch.int64, device="cuda")
+    status = torch.full((2,), -1, dtype=torch.int32, device="cuda")
+    print(f"[fullsize] n={n} dense case: compress", flush=True)
+    rc = B.compress(None, v, p, out, nbytes, status, ws, n=n, out_capacity=cap)
+    torch.cuda.synchronize()
+    assert rc == B.OK and int(status[0]) == 0
+    del ws
+    sb = int(nbytes[0])
+    hdr = out.view(torch.uint8)[:64].cpu().numpy()
+    s_hdr, d = float(hdr[24:32].view("<f8")[0]), int(hdr[40:48].view("<u8")[0])
+    assert abs(s_hdr - total) <= 1e-9 * total and 0.025 * n < d < 0.035 * n
+    thr_bits = int(ref.tables(s_hdr, base, 128)[0][128])
+    print(f"[fullsize] d={d} stream={sb}: decompress", flush=True)
+    k_out = torch.empty(d, dtype=torch.int32, device="cuda")
+    v_out = torch.empty(d, dtype=torch.float32, device="cuda")
+    cnt = torch.full((2,), -1, dtype=torch.int64, device="cuda")
+    dws = torch.empty(B.decompress_workspace_size(1) // 8 + 32, dtype=torch.int64, device="cuda")
+    rc = B.decompress(out, sb, k_out, v_out, cnt, status, dws, capacity=d)
+    torch.cuda.synchronize()
+    assert rc == B.OK and int(status[0]) == 0 and int(cnt[0]) == d
+    got = k_out.to(torch.int64) & 0xFFFFFFFF
+    pos = 0
+    for lo in range(0, n, step):                          # the surviving indices, slice by slice
+        bits = v[lo:lo + step].view(torch.int32).bitwise_and(0x7FFFFFFF)
+        want = torch.nonzero(bits >= thr_bits).flatten() + lo
+        assert torch.equal(got[pos:pos + want.numel()], want)
+        pos += want.numel()
+    assert pos == d
+    orig = v[got]
+    assert torch.equal(torch.signbit(orig), torch.signbit(v_out))
+    assert bool((v_out.abs() <= orig.abs()).all()) and bool((v_out.abs().double() * base * (1 + 1e-6) > orig.abs().double()).all())
+    del v, orig
+    print("[fullsize] oracle decode of the stream", flush=True)
+    st = out.view(torch.uint8)[:sb].cpu().numpy()
+    rc_ref, k_ref, v_ref = ref.decompress(st)
+    assert rc_ref == ref.OK and k_ref.size == d
+    assert np.array_equal(k_ref, k_out.cpu().numpy().view(np.uint32))
+    assert np.array_equal(v_ref.view(np.uint32), v_out.cpu().numpy().view(np.uint32))
