@@ -119,3 +119,19 @@ def test_batch_with_mixed_token_widths():
             seg[::max(s // 7, 1)] *= np.float32(3e3)
         args.append((W.solve_base(seg, 0.4, tau) if s > 20 else 1.3, tau, 1 + i % 4, 256 << (i % 4)))
     check_segmented(keys, vals, offs, [ref.params(*a) for a in args], [B.params(*a) for a in args])
+
+
+def test_batch_of_the_largest_number_of_segments():
+    # 65536 segments (the limit), most of them tiny, some empty, a few that span several key blocks
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(65536)
+    sizes = rng.integers(0, 40, 65536)
+    sizes[rng.integers(0, 65536, 50)] = rng.integers(3000, 9000, 50)
+    sizes[[0, 1, 65535]] = [0, 5000, 0]
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.uint64)
+    n = int(offs[-1])
+    keys = (np.arange(n, dtype=np.uint64) - np.repeat(offs[:-1], sizes)).astype(np.uint32)
+    vals = (rng.standard_normal(n) * np.repeat(10.0 ** rng.uniform(-6, -2, 65536), sizes)).astype(np.float32)
+    check_segmented(keys, vals, offs, ref.params(1.02, 128, 2, 256), B.params(1.02, 128, 2, 256))
+    rc, status, blob, so = G.hip_compress_segmented(keys, vals, np.append(offs, offs[-1]), B.params(1.02, 128, 2, 256))
+    assert rc == B.ERR_INVALID_ARG                         # 65537 segments
