@@ -14,7 +14,7 @@ constexpr u32 kMaxSegments = 65536;
 constexpr u64 kMaxElems = 0xFFFFFFFFull - 1023;   // per gradient: scratch offsets inside a segment stay below 2^32
 constexpr u32 kMaxSumGrid = 2048;      // most workgroups the abs-sum pass of a single gradient is launched with
 static_assert(sizeof(DecSeg) <= kDecSegBytes && sizeof(DecCtrl) <= kDecCtrlBytes, "decoder workspace records");
-static_assert(sizeof(SegInfo) == 48 && sizeof(SegBatch) <= 3072, "segment table travels as a kernel argument");
+static_assert(sizeof(SegInfo) == 48 && sizeof(SegBatch) <= 3900, "segment table travels as a kernel argument");
 
 static bool params_ok(const fastsgd_params* p) {
     if (!p) return false;
@@ -163,16 +163,16 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     const u64 zero_words = ((single ? pl.zero_end : pl.zero_end_batch) - pl.off_ctrl) / 8;
     u64* zero_begin = reinterpret_cast<u64*>(ws + pl.off_ctrl);
     if (!single) {
-        // clear control words, counters and abs-sum records; store the segment table (48 per launch)
-        for (u32 first = 0; first < n_segments; first += 48) {
+        // clear control words, counters and abs-sum records; store the segment table (kSegBatch per launch)
+        for (u32 first = 0; first < n_segments; first += kSegBatch) {
             SegBatch b;
-            const u32 count = (n_segments - first < 48) ? n_segments - first : 48;
+            const u32 count = (n_segments - first < kSegBatch) ? n_segments - first : kSegBatch;
             for (u32 i = 0; i < count; ++i) b.seg[i] = segs[first + i];
             if (first == 0)
                 hipLaunchKernelGGL(k_init, dim3(clamp_grid((zero_words + 1023) / 1024, 2048)), dim3(256), 0, stream,
                                    zero_begin, zero_words, dsegs, b, first, count);
             else
-                hipLaunchKernelGGL(k_store_segments, dim3(1), dim3(64), 0, stream, dsegs, b, first, count);
+                hipLaunchKernelGGL(k_store_segments, dim3(1), dim3(128), 0, stream, dsegs, b, first, count);
         }
     }
 

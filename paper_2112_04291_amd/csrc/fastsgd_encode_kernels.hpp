@@ -13,7 +13,8 @@
 namespace fsgd {
 
 // ---------------------------------------------------------------------------------------------
-struct SegBatch { SegInfo seg[48]; };   // passed by value: the segment table needs no host->device copy
+constexpr u32 kSegBatch = 80;            // segment records per launch: 3840 bytes of the 4 KB a launch can carry
+struct SegBatch { SegInfo seg[kSegBatch]; };   // passed by value: the segment table needs no host->device copy
 
 __global__ void k_init(u64* zero_begin, u64 zero_words, SegInfo* segs, SegBatch batch, u32 first, u32 count) {
     u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
