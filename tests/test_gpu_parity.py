@@ -346,3 +346,37 @@ def test_narrow_value_tokens(tau, n, kb):
     vals[::n // 10] *= np.float32(1e4)           # a few dominant values: something survives even for tau = 1
     st = check_round_trip(keys, vals, W.solve_base(vals, 0.6, tau), tau, 2, kb)
     assert int(st[40:48].view("<u8")[0]) >= 1
+
+
+def test_keys_that_span_the_whole_32_bit_range_and_streams_that_leave_it():
+    """Deltas of 28 to 32 bits (a lane's running sum can wrap) up to the key 2^32 - 1, and corrupted
+    copies whose keys would pass 2^32: same verdict as the oracle."""
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(31)
+    # 15 steps of 2^28 - 1, then small steps, ending exactly at 2^32 - 1
+    big = np.full(15, (1 << 28) - 1, np.uint64)
+    small = rng.integers(1, 50, 1500).astype(np.uint64)
+    keys = np.cumsum(np.concatenate([np.array([7], np.uint64), big, small]))
+    keys = np.concatenate([keys, np.array([(1 << 32) - 1], np.uint64)])
+    assert keys[-2] < keys[-1]
+    vals = rng.laplace(0, 1.0, keys.size).astype(np.float32)
+    st = check_round_trip(keys.astype(np.uint32), vals, 16.0, tau=128, l=2, kb=256)   # everything survives
+    d = int(st[40:48].view("<u8")[0])
+    assert d == keys.size
+    # one key of 2^32 - 1 alone (M = 32), and a first key of 0
+    check_round_trip(np.array([(1 << 32) - 1], np.uint32), np.array([1.0], np.float32), 1.1)
+    check_round_trip(np.array([0, (1 << 32) - 1], np.uint32), np.array([1.0, -2.0], np.float32), 1.1)
+    # flip bits in the key planes of the long stream: most flips push a key past 2^32 or break the chain
+    dir_off = 64 + ((d + 7) & ~7)
+    blocks_off = dir_off + 16 * ((d + 255) // 256)
+    seen = set()
+    for pos in rng.integers(blocks_off * 8, st.size * 8, 60):
+        s = st.copy()
+        s[int(pos) >> 3] ^= np.uint8(1 << (int(pos) & 7))
+        rc_ref, k_ref, v_ref = ref.decompress(s, capacity=d)
+        rc, status, k, v = G.hip_decompress(s, capacity=d)
+        assert rc == B.OK and status == rc_ref, (int(pos), status, rc_ref)
+        seen.add(status)
+        if status == 0:
+            assert np.array_equal(k, k_ref)
+    assert B.ERR_CORRUPT_STREAM in seen
