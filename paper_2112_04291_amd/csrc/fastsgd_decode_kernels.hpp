@@ -333,79 +333,79 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
     u32 vb[kLaneKeys];
 #pragma unroll
     for (u32 k = 0; k < kLaneKeys; ++k) vb[k] = s_V[(cw[k >> 2] >> (8u * (k & 3u))) & 0xFFu];
-    if (MODE != kStore) {
-        // all reads of a lane's sixteen keys are issued before the first write: the keys of a valid
-        // stream are distinct, and a stream that is not valid leaves unspecified arrays anyway
-        bool big = false;
-        float cur[kLaneKeys];
-        bool on[kLaneKeys];
-#pragma unroll
-        for (u32 k = 0; k < kLaneKeys; ++k) {
-            const bool have = FULL || lane * kLaneKeys + k < n;
-            on[k] = have && kp[k] < dense_len;
-            big |= have && !on[k];
-            cur[k] = on[k] ? dense[kp[k]] : 0.0f;
-        }
-        if (MODE == kAccum) {
-#pragma unroll
-            for (u32 k = 0; k < kLaneKeys; ++k)
-                if (on[k]) dense[kp[k]] = cur[k] + __uint_as_float(vb[k]);
-        } else {
-            // m = b1 m + (1 - b1) g;  v = b2 v + (1 - b2) g^2;  theta -= eta m / sqrt(v + eps)
-            float mo[kLaneKeys], vo[kLaneKeys];
-#pragma unroll
-            for (u32 k = 0; k < kLaneKeys; ++k) {
-                mo[k] = on[k] ? adam.m[kp[k]] : 0.0f;
-                vo[k] = on[k] ? adam.v[kp[k]] : 0.0f;
-            }
-#pragma unroll
-            for (u32 k = 0; k < kLaneKeys; ++k) {
-                if (on[k]) {
-                    const float g = __uint_as_float(vb[k]);
-                    const float mt = adam.beta1 * mo[k] + adam.one_minus_beta1 * g;
-                    const float vt = adam.beta2 * vo[k] + adam.one_minus_beta2 * g * g;
-                    adam.m[kp[k]] = mt;
-                    adam.v[kp[k]] = vt;
-                    dense[kp[k]] = cur[k] - adam.eta * mt / __fsqrt_rn(vt + adam.eps);
-                }
-            }
-        }
-        const u32 li = (n - 1u) & (kLaneKeys - 1u);             // the round's last key sits in lane (n-1)/16
-        u32 lastk = kp[kLaneKeys - 1];
-        if (!FULL) {
-#pragma unroll
-            for (u32 k = 0; k < kLaneKeys; ++k) if (k == li) lastk = kp[k];
-        }
-        carry = read_lane(lastk, uniform((n - 1u) / kLaneKeys));
-        wave_lds_sync();
-        pbit += roundbits;
-        too_big |= __any(big);
-        return !(__any(ovf) || __any(badcode));
-    }
-    // through shared memory to the output arrays: lane-major in, row-major out.  A lane's 16 words sit
-    // 20 words apart (word i at i + 4 * (i / 16)), which spreads the 16-byte writes over all banks.
+    // Lane-major -> row-major through shared memory (row q, lane: pair 64 * q + lane), so that stores to
+    // the output arrays are coalesced and updates of the dense arrays touch neighbouring addresses in one
+    // instruction.  A lane's 16 words sit 20 words apart (word i at i + 4 * (i / 16)), which spreads the
+    // 16-byte writes over all banks.
     wave_lds_sync();
     uint4* t4 = reinterpret_cast<uint4*>(s_pay) + lane * 5u;
     const u32 rowpos = lane + 4u * (lane >> 4);            // position of word 64 * q + lane: rowpos + 80 * q
+    u32 kr[kLaneKeys], vr[kLaneKeys];
 #pragma unroll
     for (u32 j = 0; j < 4; ++j) t4[j] = make_uint4(kp[4 * j], kp[4 * j + 1], kp[4 * j + 2], kp[4 * j + 3]);
     wave_lds_sync();
 #pragma unroll
-    for (u32 q = 0; q < kLaneKeys; ++q) {
-        const u32 i = q * 64u + lane;
-        if (FULL || i < n) keys_dst[i] = s_pay[rowpos + 80u * q];
-    }
+    for (u32 q = 0; q < kLaneKeys; ++q) kr[q] = s_pay[rowpos + 80u * q];
     carry = s_pay[(n - 1u) + 4u * ((n - 1u) >> 4)];          // last key of the round (same in all lanes)
+    if (MODE == kStore) {
+#pragma unroll
+        for (u32 q = 0; q < kLaneKeys; ++q) {
+            const u32 i = q * 64u + lane;
+            if (FULL || i < n) keys_dst[i] = kr[q];
+        }
+    }
     wave_lds_sync();
 #pragma unroll
     for (u32 j = 0; j < 4; ++j) t4[j] = make_uint4(vb[4 * j], vb[4 * j + 1], vb[4 * j + 2], vb[4 * j + 3]);
     wave_lds_sync();
 #pragma unroll
-    for (u32 q = 0; q < kLaneKeys; ++q) {
-        const u32 i = q * 64u + lane;
-        if (FULL || i < n) values_dst[i] = __uint_as_float(s_pay[rowpos + 80u * q]);
-    }
+    for (u32 q = 0; q < kLaneKeys; ++q) vr[q] = s_pay[rowpos + 80u * q];
     wave_lds_sync();
+    if (MODE == kStore) {
+#pragma unroll
+        for (u32 q = 0; q < kLaneKeys; ++q) {
+            const u32 i = q * 64u + lane;
+            if (FULL || i < n) values_dst[i] = __uint_as_float(vr[q]);
+        }
+    } else {
+        // all sixteen reads are issued before the first write: the keys of a valid stream are distinct,
+        // and a stream that is not valid leaves unspecified arrays anyway
+        bool big = false;
+        float cur[kLaneKeys];
+        bool on[kLaneKeys];
+#pragma unroll
+        for (u32 q = 0; q < kLaneKeys; ++q) {
+            const bool have = FULL || q * 64u + lane < n;
+            on[q] = have && kr[q] < dense_len;
+            big |= have && !on[q];
+            cur[q] = on[q] ? dense[kr[q]] : 0.0f;
+        }
+        if (MODE == kAccum) {
+#pragma unroll
+            for (u32 q = 0; q < kLaneKeys; ++q)
+                if (on[q]) dense[kr[q]] = cur[q] + __uint_as_float(vr[q]);
+        } else {
+            // m = b1 m + (1 - b1) g;  v = b2 v + (1 - b2) g^2;  theta -= eta m / sqrt(v + eps)
+            float mo[kLaneKeys], vo[kLaneKeys];
+#pragma unroll
+            for (u32 q = 0; q < kLaneKeys; ++q) {
+                mo[q] = on[q] ? adam.m[kr[q]] : 0.0f;
+                vo[q] = on[q] ? adam.v[kr[q]] : 0.0f;
+            }
+#pragma unroll
+            for (u32 q = 0; q < kLaneKeys; ++q) {
+                if (on[q]) {
+                    const float g = __uint_as_float(vr[q]);
+                    const float mt = adam.beta1 * mo[q] + adam.one_minus_beta1 * g;
+                    const float vt = adam.beta2 * vo[q] + adam.one_minus_beta2 * g * g;
+                    adam.m[kr[q]] = mt;
+                    adam.v[kr[q]] = vt;
+                    dense[kr[q]] = cur[q] - adam.eta * mt / __fsqrt_rn(vt + adam.eps);
+                }
+            }
+        }
+        too_big |= __any(big);
+    }
     pbit += roundbits;
     return !(__any(ovf) || __any(badcode));
 }
