@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="elements the oracle is timed on (0 = the whole workload)")
+    ap.add_argument("--widening", action="store_true",
+                    help="also time decode-and-aggregate (4 copies of each stream) and decode-and-update (Adam); "
+                         "reported under \"widening\", outside the timed step")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run, before anything else, one plain elementwise kernel over the value array "
                          "(out = -in: n*4 bytes read, n*4 bytes written), the dispatch of known HBM traffic the "
@@ -218,6 +221,32 @@ def main():
                     avg_launch_ms=kern_time[dominant] / launches,
                     algorithmic_bytes_per_launch=kern_bytes[dominant] / launches)
 
+    widening = None
+    if args.widening:
+        widening = []
+        dense = torch.zeros(n, dtype=torch.float32, device="cuda")
+        theta, m1, v1 = (torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(3))
+        aws = torch.empty(B.decompress_workspace_size(4) // 8 + 32, dtype=torch.int64, device="cuda")
+        for pt in points:
+            sb = pt["bytes"]
+            four = torch.cat([pt["out"].view(torch.uint8)[:sb]] * 4 + [torch.zeros(64, dtype=torch.uint8, device="cuda")])
+            offs = torch.tensor([0, sb, 2 * sb, 3 * sb, 4 * sb], dtype=torch.int64, device="cuda")
+
+            def do_acc(_):
+                assert B.decompress_accumulate(four, 4 * sb, offs, 4, dense, count, status, aws) == B.OK
+
+            def do_adam(_):
+                assert B.decompress_adam(pt["out"], sb, theta, m1, v1, 1e-3, 0.9, 0.999, 1e-8, count, status, aws) == B.OK
+
+            a_ms = timed(do_acc, pt, args.steps)
+            assert int(status[0]) == B.OK and int(count[0]) == 4 * pt["d"]
+            u_ms = timed(do_adam, pt, args.steps)
+            assert int(status[0]) == B.OK and int(count[0]) == pt["d"]
+            widening.append(dict(keep=pt["keep"], d=pt["d"], accumulate_4_streams_ms=a_ms, adam_ms=u_ms,
+                                 accumulate_pairs_per_s=4.0 * pt["d"] / a_ms * 1e3, adam_pairs_per_s=pt["d"] / u_ms * 1e3))
+            del four
+        del dense, theta, m1, v1
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import ref
@@ -245,6 +274,8 @@ def main():
                    "arithmetic": "f32 values and u32 keys compared as IEEE bit patterns; f64 boundary table"},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "detail": detail,
     }
+    if widening is not None:
+        line["widening"] = widening
     print(json.dumps(line))
 
 

@@ -23,8 +23,13 @@ def _rows(d, suffix):
     return list(csv.DictReader(open(files[0])))
 
 
+_DECODE_MODES = {"k_decode<0>": "k_decode", "k_decode<1>": "k_decode (aggregate)", "k_decode<2>": "k_decode (Adam)"}
+
+
 def _short(name):
     name = name.split("(")[0].replace("void ", "").replace("fsgd::", "")
+    if name in _DECODE_MODES:          # what the launch does with the pairs: store / add to a dense vector / Adam step
+        return _DECODE_MODES[name]
     return name.split("<")[0] if name.startswith("k_") else name[:60]
 
 
@@ -39,7 +44,7 @@ def trace(d, out, command):
                    r.get("Workgroup_Size_X", r.get("Workgroup_Size", "")))
     tot = sum(sum(v) for v in st.values())
     with open(out, "w") as f:
-        f.write(f"# rocprofv3 kernel trace of the benchmark (config 4, 124M elements, four keep fractions)\n\n")
+        f.write("# rocprofv3 kernel trace of the benchmark (config 4, 124M elements, four keep fractions)\n\n")
         f.write(f"Command: `{command}`\n\n")
         f.write("Durations in microseconds, begin to end of each dispatch.\n\n")
         f.write("| kernel | calls | avg us | min us | max us | % of GPU time | VGPRs | LDS bytes | grid | workgroup |\n")
