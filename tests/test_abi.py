@@ -53,3 +53,23 @@ def test_params_struct_layout_matches_header():
     from paper_2112_04291_amd import binding as B
     assert ctypes.sizeof(B.Params) == 24
     assert [f[0] for f in B.Params._fields_] == ["base", "tau", "flag_bits", "block_keys", "reserved"]
+    assert ctypes.sizeof(B.Adam) == 32
+    assert [f[0] for f in B.Adam._fields_] == ["eta", "beta1", "beta2", "eps"]
+    text = open(os.path.join(ROOT, "include", "fastsgd.h")).read()
+    for struct, fields in (("fastsgd_params", B.Params._fields_), ("fastsgd_adam", B.Adam._fields_)):
+        body = re.search(r"typedef struct \{([^}]*)\} " + struct + ";", text).group(1)
+        body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+        assert re.findall(r"\b(\w+);", body) == [f[0] for f in fields]
+
+
+def test_host_side_argument_checks_need_no_gpu():
+    # bad arguments are turned down before anything is launched
+    from paper_2112_04291_amd import binding as B
+    L = B.lib()
+    p = B.params(1.1)
+    assert L.fastsgd_compress(None, None, 10, ctypes.byref(p), None, 0, None, None, None, 0, None) == B.ERR_INVALID_ARG
+    assert L.fastsgd_decompress(None, 0, None, None, 0, None, None, None, 0, None) == B.ERR_INVALID_ARG
+    assert L.fastsgd_decompress_accumulate(None, 0, None, 1, None, 0, None, None, None, 0, None) == B.ERR_INVALID_ARG
+    assert L.fastsgd_decompress_adam(None, 0, None, None, None, 0, None, None, None, None, 0, None) == B.ERR_INVALID_ARG
+    assert B.compressed_size(100, B.params(1.1, 129)) == 0 and B.compressed_size(100, B.params(0.9)) == 0
+    assert B.compressed_size(1 << 33, p) == 0
