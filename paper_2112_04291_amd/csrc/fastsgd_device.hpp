@@ -149,21 +149,6 @@ __device__ __forceinline__ u32 block_excl_scan(u32 x, u32* scratch, u32* total) 
     *total = tot;
     return base + incl - x;
 }
-__device__ __forceinline__ u64 block_excl_scan64(u64 x, u64* scratch, u64* total) {
-    u64 incl = wave_incl_scan64(x);
-    if (lane_id() == 63) scratch[wave_id()] = incl;
-    __syncthreads();
-    u64 base = 0, tot = 0;
-#pragma unroll
-    for (u32 w = 0; w < kWaves; ++w) {
-        u64 t = scratch[w];
-        if (w < wave_id()) base += t;
-        tot += t;
-    }
-    __syncthreads();
-    *total = tot;
-    return base + incl - x;
-}
 
 // ---------------------------------------------------------------------------------------------
 // binary64 -> binary32 bit pattern of a positive, finite, normal double, rounding either to
@@ -219,6 +204,13 @@ __device__ __forceinline__ u32 find_tile_segment(const SegInfo* segs, u32 n_segm
 }
 __device__ __forceinline__ u32 find_chunk_segment(const SegInfo* segs, u32 n_segments, u32 chunk) {
     return wave_upper_index(n_segments, chunk, [&](u32 i) { return segs[i].chunk_begin; });
+}
+
+// Orders a wave's shared-memory accesses: what its lanes wrote before is visible to all of them after.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 __device__ __forceinline__ void set_status(Ctrl* ctrl, u32 code) { atomicCAS(&ctrl->status, 0u, code); }

@@ -720,25 +720,10 @@ __device__ __forceinline__ void lds_excl_scan(T* arr, u32 n, T* scratch) {
     __syncthreads();
 }
 
-// Largest j in [0, nch) with P[j] <= r, for a rank r that is the same in all lanes (P[0] = 0 <= r); *pj
-// receives P[j].  `coarse` is the wave's copy of every 64th entry of P in shared memory (load_coarse), so
-// one memory round trip suffices: the wave reads the 64 entries behind the last coarse hit.
-__device__ __forceinline__ u32 find_chunk_wave(const u32* P, const u32* coarse, u32 nch, u32 r, u32 lane, u32* pj) {
-    const u32 c = (u32)__popcll(__ballot(coarse[lane] <= r)) - 1u;
-    const u32 i2 = c * 64u + lane;
-    const u32 v = i2 < nch ? P[i2] : 0xFFFFFFFFu;
-    const u32 c2 = (u32)__popcll(__ballot(v <= r)) - 1u;
-    *pj = read_lane(v, uniform(c2));
-    return c * 64u + c2;
-}
-
-__device__ __forceinline__ void wave_lds_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// The same for three ranks at once (ra <= rb <= rc), with the three fetches in flight together.
+// Chunk search: for a rank r that is the same in all lanes, the largest j in [0, nch) with P[j] <= r
+// (P[0] = 0 <= r), and P[j] with it.  `coarse` is the wave's copy of every 64th entry of P in shared
+// memory (load_coarse), so one memory round trip suffices: the wave reads the 64 entries behind the last
+// coarse hit.  Done for three ranks at once (ra <= rb <= rc), with the three fetches in flight together.
 __device__ __forceinline__ void find_chunks3(const u32* P, const u32* coarse, u32 nch, u32 ra, u32 rb, u32 rc, u32 lane,
                                              u32 (&j)[3], u32 (&pj)[3]) {
     const u32 cv = coarse[lane];
