@@ -195,6 +195,8 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     marks.mark(stream);
     hipLaunchKernelGGL(k_plan_segments, dim3(n_segments), dim3(kThreads), 0, stream, dsegs, dstates, n_segments, R,
                        ccount, ctrl);
+    if (n_segments > 1)
+        hipLaunchKernelGGL(k_number_segments, dim3(1), dim3(kThreads), 0, stream, dstates, n_segments, ctrl);
     const u64 max_units = (max_items + kWaves - 1) / kWaves + n_segments;
     if (max_kb > kSub)
         hipLaunchKernelGGL(k_measure_keys<true>, dim3(clamp_grid(max_units, (u64)cus * 4)), dim3(kThreads), 0, stream,

@@ -61,7 +61,7 @@ struct BlockInfo { u32 preKey, M, payload_bits, span8; };
 
 struct Ctrl {
     u32 status;         // first device-detected fastsgd_status
-    u32 plan_done;      // batch calls: workgroups of k_plan_segments that have finished
+    u32 reserved;
     u64 total_items;    // batch calls: work items / units of the key encoder
     u64 total_units;
     u64 pad[5];

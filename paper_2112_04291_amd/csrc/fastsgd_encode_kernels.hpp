@@ -4,7 +4,8 @@
 //   k_abs_sum        Algorithm 1 line 1: exact sum of |v| per segment (integer accumulation)
 //   k_tables         Algorithm 1 line 2 + Eq. 3 as a boundary table sum / b^c, c = 1..tau
 //   k_encode_values  Algorithm 1 lines 4-10: threshold test, code, sign, compaction of survivors
-//   k_plan_segments  per segment: scan of the chunk counts, survivors d, key blocks; batch calls: work-item numbering
+//   k_plan_segments  per segment: scan of the chunk counts, survivors d, key blocks
+//   k_number_segments  batch calls: work-item numbering over the segments
 //   k_measure_keys   Algorithm 2, first loop, per key block: deltas, maxDelta -> M, size of the block
 //   k_pack_keys      Algorithm 2, second loop: length flags, bit packing; directory, headers, value planes
 #pragma once
@@ -193,21 +194,25 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
         u32 cur_seg = 0xFFFFFFFFu;
         const u64 t_begin = blockIdx.x * per_wg;
         const u64 t_end = (t_begin + per_wg < n_tiles) ? t_begin + per_wg : n_tiles;
+        SegInfo info = single_seg;                            // (overwritten before use)
+        u64 seg_tile_end = 0, seg_rows = 0;                   // first tile behind the segment in hand, its rows
         for (u64 tile = t_begin; tile < t_end; ++tile) {
-            const u32 seg = find_tile_segment(segs, n_segments, (u32)tile);
-            if (seg != cur_seg) {
+            if (tile >= seg_tile_end) {                       // the segment is looked up only when a tile leaves it
+                const u32 seg = find_tile_segment(segs, n_segments, (u32)tile);
                 if (cur_seg != 0xFFFFFFFFu) {
                     flush_bins<false>(bins, gbins + (u64)cur_seg * n_slots * kBinWords + blockIdx.x % n_slots, n_slots, maxa);
                     maxa = 0;
                 }
                 cur_seg = seg;
+                info = segs[seg];
+                seg_rows = segment_rows(info);
+                seg_tile_end = info.tile_begin + (seg_rows * kRow + kTile - 1) / kTile;
             }
-            const SegInfo info = segs[seg];
             const TileGeom g = tile_geom(info, tile);
             u32 bits[4][4];
             load_tile(values, g, bits);
             const u64 trow0 = (tile - info.tile_begin) * (kTile / kRow);
-            accumulate_tile(bits, bins, maxa, rowmax + 4ull * (info.row_begin + trow0), trow0, segment_rows(info));
+            accumulate_tile(bits, bins, maxa, rowmax + 4ull * (info.row_begin + trow0), trow0, seg_rows);
         }
         if (cur_seg != 0xFFFFFFFFu)
             flush_bins<false>(bins, gbins + (u64)cur_seg * n_slots * kBinWords + blockIdx.x % n_slots, n_slots, maxa);
@@ -546,18 +551,14 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
 // One workgroup per segment turns the segment's chunk counts, in place, into their exclusive scan
 // P[j] = survivors of the segment in its chunks before j (the table through which the key encoder
 // finds rank r: chunk j with P[j] <= r < P[j+1]), and notes the segment's survivors d and key blocks.
-// Batch calls then number the key encoder's work: a work item is one key block (a segment without
-// survivors still has one item, which carries its header); a work unit is kWaves consecutive items of
-// one segment, the share of one workgroup iteration; the workgroup that finishes last (a counter in
-// the control block) scans the segments.
+// Batch calls then number the key encoder's work (k_number_segments): a work item is one key block (a
+// segment without survivors still has one item, which carries its header); a work unit is kWaves
+// consecutive items of one segment, the share of one workgroup iteration.
 __global__ void __launch_bounds__(kThreads)
 k_plan_segments(const SegInfo* __restrict__ segs, SegState* __restrict__ states, u32 n_segments, u32 R,
                 u32* __restrict__ ccount, Ctrl* ctrl) {
-    __shared__ u64 s_wave[2][kWaves];
-    __shared__ u64 s_carry[2];
     __shared__ u32 s_scan[kWaves + 1];
-    __shared__ u32 s_last;
-    const u32 t = threadIdx.x, lane = lane_id(), w = wave_id();
+    const u32 t = threadIdx.x;
     {
         constexpr u32 PER = kMaxSegChunks / kThreads;
         const u32 seg = blockIdx.x;
@@ -593,20 +594,22 @@ k_plan_segments(const SegInfo* __restrict__ segs, SegState* __restrict__ states,
             }
         }
     }
-    if (gridDim.x == 1) return;
-    __threadfence();
-    __syncthreads();
-    if (t == 0) s_last = (atomicAdd(&ctrl->plan_done, 1u) == gridDim.x - 1) ? 1u : 0u;
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
+}
+
+// Batch calls: numbers the key encoder's work over the segments (one workgroup; a launch of its own, so
+// that the per-segment workgroups of k_plan_segments need no fence and no counter).
+__global__ void __launch_bounds__(kThreads)
+k_number_segments(SegState* __restrict__ states, u32 n_segments, Ctrl* ctrl) {
+    __shared__ u64 s_wave[2][kWaves];
+    __shared__ u64 s_carry[2];
+    const u32 t = threadIdx.x, lane = lane_id(), w = wave_id();
     if (t < 2) s_carry[t] = 0;
     __syncthreads();
     for (u32 s0 = 0; s0 < n_segments; s0 += kThreads) {
         const u32 s = s0 + t;
         u64 items = 0, units = 0;
         if (s < n_segments) {
-            const u32 nb = __atomic_load_n(&states[s].nb, __ATOMIC_RELAXED);
+            const u32 nb = states[s].nb;
             items = nb ? nb : 1u;
             units = (items + kWaves - 1) / kWaves;
         }
