@@ -25,10 +25,10 @@ def params(base=1.1, tau=128, flag_bits=2, block_keys=1024):
 _lib = None
 
 
-def lib():
-    global _lib
-    if _lib is None:
-        path = _build.build(force=False)
+def load(path):
+    """The oracle library at `path` with its prototypes declared (the tests of the pins load deliberately
+    broken builds of the oracle through this)."""
+    if True:        # (one block: the prototypes below)
         L = C.CDLL(path)
         u64, u32, vp = C.c_uint64, C.c_uint32, C.c_void_p
         L.fastsgd_ref_abs_sum.argtypes = [vp, u64, C.POINTER(C.c_double)]
@@ -52,7 +52,13 @@ def lib():
         L.fastsgd_ref_decompress_adam.restype = C.c_int
         L.fastsgd_ref_key_tokens_text.argtypes = [vp, u32, u32, C.c_char_p, u64]
         L.fastsgd_ref_key_tokens_text.restype = u32
-        _lib = L
+    return L
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = load(_build.build(force=False))
     return _lib
 
 

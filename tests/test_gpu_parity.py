@@ -208,6 +208,11 @@ def test_corrupt_streams_are_rejected_on_device():
                 poke(dir_off + 16 + 4, "<I", 1), poke(dir_off + 8, "<I", 33), poke(dir_off + 12, "<I", 17),
                 poke(dir_off + 12, "<I", 0xFFFFFFFF)]:
         assert run(mut) == B.ERR_CORRUPT_STREAM
+    # a payload length off by one bit that still rounds to the same number of words
+    pbits0 = struct.unpack_from("<I", st, dir_off + 12)[0]
+    assert pbits0 % 64 not in (0, 1)
+    assert run(poke(dir_off + 12, "<I", pbits0 + 1)) == B.ERR_CORRUPT_STREAM
+    assert run(poke(dir_off + 12, "<I", pbits0 - 1)) == B.ERR_CORRUPT_STREAM
     assert run(lambda s: None, cap=1999) == B.ERR_BUFFER_TOO_SMALL
     rc, status, k, v = G.hip_decompress(st[:48], capacity=10)
     assert status == B.ERR_CORRUPT_STREAM

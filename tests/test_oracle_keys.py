@@ -191,6 +191,12 @@ def test_corrupt_streams_are_rejected():
     assert broken(poke32(dir_off + 16 + 4, 1)) == ref.ERR_CORRUPT_STREAM               # preKey chain
     assert broken(poke32(dir_off + 8, 33)) == ref.ERR_CORRUPT_STREAM                   # M
     assert broken(poke32(dir_off + 12, 17)) == ref.ERR_CORRUPT_STREAM                  # payload bits
+    # a payload length one bit too long or too short that still rounds to the same number of words: only
+    # the count of consumed bits can tell
+    pbits0 = struct.unpack_from("<I", st, dir_off + 12)[0]
+    assert pbits0 % 64 not in (0, 1)
+    assert broken(poke32(dir_off + 12, pbits0 + 1)) == ref.ERR_CORRUPT_STREAM
+    assert broken(poke32(dir_off + 12, pbits0 - 1)) == ref.ERR_CORRUPT_STREAM
     assert ref.decompress(st[:63])[0] == ref.ERR_CORRUPT_STREAM
     assert ref.decompress(st[:-8], capacity=4096)[0] == ref.ERR_CORRUPT_STREAM
 

@@ -127,6 +127,10 @@ def test_tables_against_exact_rationals(S, b, tau):
             assert dn <= t * (1 + tol)           # ... and to the very next float32
         assert int(V[c]) in (int(B[c]), int(B[c]) - 1)   # nearest is the boundary or the float below
         assert float(Vc) <= float(Bc)
+        if np.isfinite(Bc) and int(B[c]) > 0:
+            # ... whichever of the two is nearer to the real boundary (up to the recipe's own rounding)
+            other = dn if int(V[c]) == int(B[c]) else up
+            assert abs(Fraction(float(Vc)) - t) <= abs(other - t) + 2 * tol * t
 
 
 def test_tables_monotone_and_tau_e():
