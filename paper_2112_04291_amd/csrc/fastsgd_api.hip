@@ -124,6 +124,9 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     // chunks of R rows, about kChunkTarget of them, never shorter than one tile
     u64 R64 = (total_rows + kChunkTarget - 1) / kChunkTarget;
     if (R64 < 2 * kValRows) R64 = 2 * kValRows;
+    // a batch: whole batches of rows per chunk, so that no chunk ends on a batch of a row or two (a single
+    // gradient's chunks are long enough for that not to matter, and more chunks serve it better)
+    if (n_segments > 1) R64 = (R64 + kValRows - 1) / kValRows * kValRows;
     u64 n_chunks = 0;
     for (u32 s = 0; s < n_segments; ++s) {
         SegInfo& si = segs[s];
