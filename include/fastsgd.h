@@ -60,7 +60,7 @@ typedef enum {
     FASTSGD_ERR_NONFINITE = 3,        /* a NaN or infinity among the values                  */
     FASTSGD_ERR_UNSORTED_KEYS = 4,    /* surviving keys not strictly increasing             */
     FASTSGD_ERR_CORRUPT_STREAM = 5,   /* decoder: header, directory or planes inconsistent  */
-    FASTSGD_ERR_DEVICE = 6            /* HIP launch failure or an internal wait that gave up */
+    FASTSGD_ERR_DEVICE = 6            /* HIP launch failure                                  */
 } fastsgd_status;
 
 /* Host-only, pure.  Worst-case stream size in bytes for a gradient of n elements (all survive,
@@ -183,7 +183,8 @@ fastsgd_status fastsgd_decompress_adam(const void* d_stream, size_t stream_bytes
  * fastsgd_decompress, run `iterations` (1..4096) times back to back with a HIP event recorded on
  * hip_stream before the first and after every kernel; the call then WAITS for the stream and
  * stores the average milliseconds per kernel in kernel_ms (host).  Kernel order, compress:
- * abs-sum, tables, encode-values, measure-keys, pack-keys; decompress: setup, decode.
+ * abs-sum, tables, encode-values, measure-keys (with the scan of the chunk counts in front of it),
+ * pack-keys; decompress: setup, decode.
  * These two calls create and destroy HIP events; they are not meant for production paths. */
 #define FASTSGD_PROFILE_COMPRESS_KERNELS 5
 #define FASTSGD_PROFILE_DECOMPRESS_KERNELS 2
