@@ -34,10 +34,13 @@ static EncodePlan make_plan(u64 total_n, u32 n_segments, u32 min_kb) {
     pl.total_n = total_n;
     pl.n_segments = n_segments;
     pl.n_slots = (n_segments == 1) ? kMaxSumGrid : 4u;           // abs-sum records per segment
-    pl.max_chunks = (u64)kChunkTarget + n_segments;                // a segment adds at most one short chunk
     pl.max_items = total_n / min_kb + n_segments + 1;              // bound on key blocks (+1 per empty segment)
     pl.max_slots = total_n + 4ull * n_segments + 8;                // scratch entries: element index + 4 per segment
     pl.max_rows = total_n / kRow + 2ull * n_segments + 2;           // a segment adds at most two partial rows
+    // about kChunkTarget chunks, more only where that would make a chunk longer than kMaxChunkRows; a
+    // segment adds at most one short chunk
+    const u64 by_length = pl.max_rows / kMaxChunkRows + 1;
+    pl.max_chunks = (by_length > kChunkTarget ? by_length : (u64)kChunkTarget) + n_segments;
     u64 o = 0;
     pl.off_ctrl = o;  o += up(sizeof(Ctrl), 256);
     pl.off_gsum = o;  o += up((u64)(kMaxGroups + 1) * 8, 256);
@@ -127,6 +130,7 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     // a batch: whole batches of rows per chunk, so that no chunk ends on a batch of a row or two (a single
     // gradient's chunks are long enough for that not to matter, and more chunks serve it better)
     if (n_segments > 1) R64 = (R64 + kValRows - 1) / kValRows * kValRows;
+    if (R64 > kMaxChunkRows) R64 = kMaxChunkRows;                  // (a multiple of kValRows)
     u64 n_chunks = 0;
     for (u32 s = 0; s < n_segments; ++s) {
         SegInfo& si = segs[s];
@@ -134,12 +138,12 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
         const u64 rows = (span + kRow - 1) / kRow;
         si.chunk_begin = (u32)n_chunks;
         const u64 c = (rows + R64 - 1) / R64;
-        if (c > kMaxSegChunks) return FASTSGD_ERR_INVALID_ARG;     // cannot happen: R64 >= total_rows / kChunkTarget
+        if (c > kMaxSegChunks) return FASTSGD_ERR_INVALID_ARG;     // cannot happen: a gradient has under 2^24 + 2 rows
         n_chunks += c;
     }
     const EncodePlan pl = make_plan(total_n, n_segments, min_kb);
     if (total_rows > pl.max_rows || total_rows >= 0xFFFFFFFFull) return FASTSGD_ERR_INVALID_ARG;
-    if (n_chunks > pl.max_chunks || max_items > pl.max_items || n_tiles >= 0xFFFFFFFFull || R64 > 0xFFFFFFull)
+    if (n_chunks > pl.max_chunks || max_items > pl.max_items || n_tiles >= 0xFFFFFFFFull)
         return FASTSGD_ERR_INVALID_ARG;
     if (ws_bytes < pl.total) return FASTSGD_ERR_BUFFER_TOO_SMALL;
     if (out_capacity < kHeaderBytes) return FASTSGD_ERR_BUFFER_TOO_SMALL;

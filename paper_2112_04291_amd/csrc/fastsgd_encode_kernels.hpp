@@ -333,22 +333,29 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
 // Second pass over the values (Algorithm 1 lines 4-10).  No wave depends on another.  The elements of
 // a call are cut into chunks of R rows (a row = 256 elements, a float4 per lane); every WAVE owns one
 // chunk:
-//   the row maxima the first pass left behind tell which rows can hold a survivor at all (the
-//   early-stop test of Algorithm 1 line 5 applied to a whole row); only those rows are read, eight at
-//   a time -> per row, keep test |v| >= threshold as four wave-wide masks -> survivors are staged in
-//   the wave's slice of shared memory in element order (mask popcounts + mbcnt) -> once more than
-//   seven hundred wait there, densely over the staged survivors only: code by binary search in the
-//   boundary table, key fetch -> code byte and key appended to the CHUNK'S OWN SLOT of the scratch
-//   arrays (the chunk's first element index + rank in the chunk).  The loads of the next eight rows
-//   are issued before that flush, so its round trip overlaps with them.
+//   the bounds the first pass left behind, one per quarter row (64 elements, the share of 16 lanes),
+//   tell which quarter rows can hold a survivor at all (the early-stop test of Algorithm 1 line 5 applied
+//   to a whole quarter row); only those are read, and they are read as one ascending stream: a batch is
+//   eight rows of 256 elements, each made of the next four quarter rows of the stream wherever they sit,
+//   so that every lane fetches something useful however few quarter rows are in play -> per row, keep
+//   test |v| >= threshold as four wave-wide masks -> survivors are staged in the wave's slice of shared
+//   memory in element order (mask popcounts + mbcnt) -> once more than kFlushLevel wait there, densely
+//   over the staged survivors only and in whole rounds of 256: code by binary search in the boundary
+//   table, key fetch -> code byte and key appended to the CHUNK'S OWN SLOT of the scratch arrays (the
+//   chunk's first element index + rank in the chunk).  The loads of the next batch are issued before
+//   that flush, so its round trip overlaps with them.
 // The chunk's survivor count goes to ccount[chunk].  Global ranks are never materialised: k_plan_segments
 // turns the (at most 4096) chunk counts of a segment into their scan and the key encoder gathers through
 // that scan.
-// Lane `lane` holds elements row*256 + lane*4 + {0..3} of each row in hand.
-constexpr u32 kStage = 1216;             // staged survivors per wave: two full rows on top of the flush level
+constexpr u32 kStage = 1088;             // staged survivors per wave: two full rows on top of the flush level
+constexpr u32 kRing = 512;               // ring of quarter rows per wave: under a batch left over plus 64 rows of four
 constexpr u32 kFlushLevel = kStage - 2 * kRow;
 constexpr u32 kValWaves = 4;             // waves per workgroup of the value encoder (they never synchronise)
 constexpr u32 kGather = 4;               // key fetches a lane keeps in flight
+static_assert((kRing & (kRing - 1)) == 0 && kRing >= 4 * kValRows - 1 + 4 * 64, "ring: a short batch plus 64 rows");
+static_assert(kMaxChunkRows * 4 <= 65536 && kMaxChunkRows % kValRows == 0, "ring entries are 16 bits");
+static_assert(kFlushLevel >= 64 * kGather, "a flush sends at least one whole round");
+static_assert(512 + 8 * kStage + 2 * kRing <= 10240, "shared memory for sixteen waves per compute unit");
 
 // |v| >= threshold as a float compare with the |x| source modifier: for non-negative finite floats
 // (denormals are preserved in this build) it orders exactly like the unsigned compare of the bit
@@ -398,11 +405,13 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
     __shared__ u32 s_Ball[kValWaves][128];
     __shared__ u32 s_valall[kValWaves][kStage];
     __shared__ u32 s_idxall[kValWaves][kStage];
+    __shared__ uint16_t s_ringall[kValWaves][kRing];        // quarter rows still to be read, in ascending order
     const u32 lane = lane_id();
     const u32 w = uniform(wave_id());
     u32* s_B = s_Ball[w];
     u32* s_val = s_valall[w];       // staged survivors: value bits ...
     u32* s_idx = s_idxall[w];       // ... and element offset inside the chunk
+    uint16_t* s_ring = s_ringall[w];
     const u32 chunk = blockIdx.x * kValWaves + w;
     if (chunk >= n_chunks) return;
     const Chunk ck = chunk_geom(segs, n_segments, chunk, R);
@@ -419,21 +428,23 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
     u32 cbase = 0;                           // survivors of the chunk already in the scratch arrays
     u32 staged = 0;                          // survivors waiting in shared memory
 
-    // Staged survivors -> scratch arrays.
-    auto flush = [&]() {
+    // Staged survivors -> scratch arrays, in rounds of 64 * kGather.  While the chunk goes on only whole
+    // rounds leave (every lane of every round has work) and the rest moves to the front of the stage.
+    auto flush = [&](bool last) {
+        const u32 n_out = last ? staged : staged - staged % (64u * kGather);
         const u64 slot = ck.slot0 + cbase;
         __builtin_amdgcn_wave_barrier();
-        for (u32 j0 = 0; j0 < staged; j0 += 64u * kGather) {
+        for (u32 j0 = 0; j0 < n_out; j0 += 64u * kGather) {
             u32 key[kGather];
 #pragma unroll
             for (u32 k = 0; k < kGather; ++k) {               // all key fetches of the round first
                 const u32 j = j0 + k * 64u + lane;
-                key[k] = (j < staged) ? (implicit ? key0 + s_idx[j] : ckeys[s_idx[j]]) : 0u;
+                key[k] = (j < n_out) ? (implicit ? key0 + s_idx[j] : ckeys[s_idx[j]]) : 0u;
             }
 #pragma unroll
             for (u32 k = 0; k < kGather; ++k) {
                 const u32 j = j0 + k * 64u + lane;
-                if (j < staged) {
+                if (j < n_out) {
                     const u32 vb = s_val[j];
                     const u32 a = vb & 0x7FFFFFFFu;
                     // smallest code c in [1, tau] with a >= B[c]  (B non-increasing, a >= B[tau])
@@ -449,31 +460,52 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
             }
         }
         __builtin_amdgcn_wave_barrier();
-        cbase += staged;
-        staged = 0;
+        const u32 rest = staged - n_out;                      // under one round
+        if (rest) {
+            u32 mv[kGather], mi[kGather];
+#pragma unroll
+            for (u32 k = 0; k < kGather; ++k) {
+                const u32 j = k * 64u + lane;
+                mv[k] = j < rest ? s_val[n_out + j] : 0u;
+                mi[k] = j < rest ? s_idx[n_out + j] : 0u;
+            }
+            wave_lds_sync();
+#pragma unroll
+            for (u32 k = 0; k < kGather; ++k) {
+                const u32 j = k * 64u + lane;
+                if (j < rest) { s_val[j] = mv[k]; s_idx[j] = mi[k]; }
+            }
+            wave_lds_sync();
+        }
+        cbase += n_out;
+        staged = rest;
     };
 
-    // Row r of the chunk.  Rows cut by the segment's ends (its first and last row at most) are fetched
-    // element by element and the elements outside [lo, hi) become zero, which never survives.
-    // `quarters`: bit k set = the row's quarter k (lanes 16k .. 16k+15) can hold a survivor; the others
-    // are not read and count as zero.
-    auto load_row = [&](u32 r, u32 quarters, u32 (&row)[4]) {
-        const u64 e = ck.e0 + (u64)r * kRow;
-        if (e >= ck.lo && e + kRow <= ck.hi) {
-            uint4 q = make_uint4(0u, 0u, 0u, 0u);
-            if ((quarters >> (lane >> 4)) & 1u) q = reinterpret_cast<const uint4*>(cvals + (u64)r * kRow)[lane];
+    // The unit of the fetch is the quarter row (64 elements, 16 lanes): a batch is eight "virtual rows" of
+    // four quarter rows that can hold a survivor, taken in ascending order from wherever they sit, so
+    // that every lane fetches something useful however few quarters are in play.
+    // One virtual row: lane group g = lane / 16 fetches quarter `qidx` (index inside the chunk: row * 4 +
+    // quarter); `elem` is the chunk-relative element offset of the lane's first element.  Quarter rows
+    // cut by the segment's ends are fetched element by element; elements outside [lo, hi) become zero,
+    // which never survives.
+    auto load_quarters = [&](bool on, u32 elem, u32 (&row)[4]) {
+        const u64 e = ck.e0 + elem;
+        const bool inside = e >= ck.lo && e + 4u <= ck.hi;
+        uint4 q = make_uint4(0u, 0u, 0u, 0u);
+        if (__all(inside || !on)) {
+            if (on) q = *reinterpret_cast<const uint4*>(cvals + elem);
             row[0] = q.x; row[1] = q.y; row[2] = q.z; row[3] = q.w;
         } else {
 #pragma unroll
             for (u32 c = 0; c < 4; ++c) {
-                const u64 ee = e + lane * 4u + c;
-                row[c] = (ee >= ck.lo && ee < ck.hi) ? __float_as_uint(values[ee]) : 0u;
+                const u64 ee = e + c;
+                row[c] = (on && ee >= ck.lo && ee < ck.hi) ? __float_as_uint(values[ee]) : 0u;
             }
         }
     };
 
-    // one row: masks, and staging if anything survives
-    auto stage_row = [&](const u32 (&row)[4], u32 off) {
+    // one virtual row: masks, and staging if anything survives
+    auto stage_row = [&](const u32 (&row)[4], u32 elem) {
         u64 m[4];
 #pragma unroll
         for (u32 c = 0; c < 4; ++c) m[c] = __ballot(keeps(row[c], thr_f));
@@ -483,67 +515,78 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
         for (u32 c = 0; c < 4; ++c)
             if (keeps(row[c], thr_f)) {
                 s_val[pos] = row[c];
-                s_idx[pos] = off + lane * 4u + c;
+                s_idx[pos] = elem + c;
                 ++pos;
             }
         staged += (u32)__popcll(m[0]) + (u32)__popcll(m[1]) + (u32)__popcll(m[2]) + (u32)__popcll(m[3]);
     };
 
-    for (u32 g0 = 0; g0 < ck.nrows; g0 += 256u) {
-        // which quarters of the next 256 rows can hold a survivor (unsigned compare of bit patterns: the
-        // same order as the float compare, and nothing passes the keep-nothing threshold): lane j keeps
-        // the four bits of rows g0 + 64*k + j, k = 0..3; a row is read if any of its bits is set
-        u64 mask[4];
-        u32 qbits[4];
-#pragma unroll
-        for (u32 k = 0; k < 4; ++k) {
-            const u32 rr = g0 + k * 64u + lane;
-            const uint2 x = crmax[rr < ck.nrows ? rr : ck.nrows - 1u];
-            u32 qb = ((x.x << 16) >= thr ? 1u : 0u) | ((x.x & 0xFFFF0000u) >= thr ? 2u : 0u) |
-                     ((x.y << 16) >= thr ? 4u : 0u) | ((x.y & 0xFFFF0000u) >= thr ? 8u : 0u);
-            if (rr >= ck.nrows) qb = 0;
-            qbits[k] = qb;
-            mask[k] = __ballot(qb != 0);
+    // The quarter rows that can hold a survivor form one ascending stream over the chunk, kept in a ring
+    // in shared memory (entry = row * 4 + quarter, counted inside the chunk).  The ring is topped up 64
+    // rows at a time: lane j compares the four bounds of row scanned + j with the threshold (unsigned
+    // compare of bit patterns: the same order as the float compare, and nothing passes the keep-nothing
+    // threshold).  The bounds of the 64 rows after those are fetched meanwhile.
+    uint2 xnext = crmax[lane < ck.nrows ? lane : ck.nrows - 1u];
+    u32 scanned = 0;                          // rows whose quarters are in the ring or behind it
+    u32 head = 0, tail = 0;                   // quarters taken from / put into the ring since the start
+    auto refill = [&]() {
+        const uint2 x = xnext;
+        const u32 row = scanned + lane;
+        scanned += 64u;
+        if (scanned < ck.nrows) {
+            const u32 rn = scanned + lane;
+            xnext = crmax[rn < ck.nrows ? rn : ck.nrows - 1u];
         }
-        // the next (up to) eight such rows, in ascending order, with their quarter bits
-        auto take = [&](u32 (&rows)[kValRows], u32 (&quarters)[kValRows]) -> u32 {
-            u32 cnt = 0;
+        u32 qb = ((x.x << 16) >= thr ? 1u : 0u) | ((x.x & 0xFFFF0000u) >= thr ? 2u : 0u) |
+                 ((x.y << 16) >= thr ? 4u : 0u) | ((x.y & 0xFFFF0000u) >= thr ? 8u : 0u);
+        if (row >= ck.nrows) qb = 0;
+        const u32 mine = (u32)__popc(qb);
+        const u32 incl = wave_incl_scan(mine);
+        u32 at = tail + incl - mine;
 #pragma unroll
-            for (u32 slot = 0; slot < kValRows; ++slot) {
-                rows[slot] = 0; quarters[slot] = 0;
+        for (u32 q = 0; q < 4; ++q)
+            if ((qb >> q) & 1u) s_ring[(at++) & (kRing - 1u)] = (uint16_t)((row << 2) | q);
+        tail += read_lane(incl, 63);
+    };
+    // A batch is eight rows of 256 elements in flight, each put together from the next four quarters of
+    // the stream (lanes 16k .. 16k+15 take the k-th of them).
+    auto take = [&](u32 (&elem)[kValRows], u32 (&on)[kValRows]) -> u32 {
+        if (tail - head < 4u * kValRows && scanned < ck.nrows) {
+            do refill(); while (tail - head < 4u * kValRows && scanned < ck.nrows);
+            wave_lds_sync();
+        }
+        const u32 left = tail - head;
+        const u32 nq = left < 4u * kValRows ? left : 4u * kValRows;
 #pragma unroll
-                for (u32 k = 0; k < 4; ++k) {
-                    if (cnt == slot && mask[k]) {
-                        const u32 b = (u32)__builtin_ctzll(mask[k]);
-                        rows[slot] = g0 + k * 64u + b;
-                        quarters[slot] = read_lane(qbits[k], b);
-                        mask[k] &= mask[k] - 1ull;
-                        cnt = slot + 1u;
-                    }
-                }
+        for (u32 slot = 0; slot < kValRows; ++slot) {
+            const u32 i = 4u * slot + (lane >> 4);
+            on[slot] = i < nq ? 1u : 0u;
+            const u32 e = on[slot] ? s_ring[(head + i) & (kRing - 1u)] : 0u;
+            elem[slot] = e * 64u + (lane & 15u) * 4u;
+        }
+        head += nq;
+        return (nq + 3u) >> 2;
+    };
+    u32 bits[kValRows][4], elem[kValRows], on[kValRows];
+    u32 nr = take(elem, on);
+#pragma unroll
+    for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_quarters(on[slot] != 0, elem[slot], bits[slot]);
+    while (nr) {
+#pragma unroll
+        for (u32 pair = 0; pair < kValRows / 2; ++pair) {
+#pragma unroll
+            for (u32 slot = 2 * pair; slot < 2 * pair + 2; ++slot) if (slot < nr) stage_row(bits[slot], elem[slot]);
+            if (pair + 1 == kValRows / 2) {
+                // the registers are free: start on the next rows before finishing these
+                nr = take(elem, on);
+#pragma unroll
+                for (u32 slot = 0; slot < kValRows; ++slot)
+                    if (slot < nr) load_quarters(on[slot] != 0, elem[slot], bits[slot]);
             }
-            return cnt;
-        };
-        u32 bits[kValRows][4], rows[kValRows], quarters[kValRows];
-        u32 nr = take(rows, quarters);
-#pragma unroll
-        for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_row(rows[slot], quarters[slot], bits[slot]);
-        while (nr) {
-#pragma unroll
-            for (u32 pair = 0; pair < kValRows / 2; ++pair) {
-#pragma unroll
-                for (u32 slot = 2 * pair; slot < 2 * pair + 2; ++slot) if (slot < nr) stage_row(bits[slot], rows[slot] * kRow);
-                if (pair + 1 == kValRows / 2) {
-                    // the registers are free: start on the next rows before finishing these
-                    nr = take(rows, quarters);
-#pragma unroll
-                    for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_row(rows[slot], quarters[slot], bits[slot]);
-                }
-                if (staged > kFlushLevel) flush();                 // room for two more rows
-            }
+            if (staged > kFlushLevel) flush(false);                 // room for two more rows
         }
     }
-    if (staged) flush();
+    if (staged) flush(true);
     if (lane == 0) ccount[chunk] = cbase;
 }
 

@@ -236,6 +236,44 @@ def test_values_on_bucket_boundaries_and_quarter_row_bounds():
     check_round_trip(np.arange(n, dtype=np.uint32), v, 2.0, tau=10, l=3, kb=1024)
 
 
+def _spikes(n, pos, seed):
+    """Background far below any threshold, survivors of magnitude about one at `pos`."""
+    rng = np.random.default_rng(seed)
+    v = (rng.uniform(1e-9, 1e-8, n) * rng.choice([-1.0, 1.0], n)).astype(np.float32)
+    pos = np.unique(np.asarray(pos, dtype=np.int64))
+    pos = pos[(pos >= 0) & (pos < n)]
+    v[pos] = (rng.uniform(0.5, 2.0, pos.size) * rng.choice([-1.0, 1.0], pos.size)).astype(np.float32)
+    return v, pos
+
+
+@pytest.mark.parametrize("pattern", ["same_quarter_of_every_row", "every_17th_quarter", "ends_only", "one_row_in_300",
+                                     "quarter_edges", "dense_island_in_a_desert", "last_quarter_only"])
+def test_survivors_clustered_in_few_quarter_rows(pattern):
+    """Placements of the survivors chosen against the unit the value pass fetches by (64 elements): the
+    quarter rows it reads are few, far apart, unevenly spread over the rows, or all of them for a stretch;
+    the array is ragged and several chunks long."""
+    n = 1_500_003
+    q = np.arange((n + 63) // 64, dtype=np.int64)
+    if pattern == "same_quarter_of_every_row":
+        pos = (q[q % 4 == 2] * 64)[:, None] + np.array([0, 31, 63])
+    elif pattern == "every_17th_quarter":
+        pos = q[::17] * 64 + (q[::17] * 7) % 64
+    elif pattern == "ends_only":
+        pos = np.array([0, n - 1])
+    elif pattern == "one_row_in_300":
+        pos = (np.arange(0, n // 256, 300)[:, None] * 256 + np.arange(256)[None, :])
+    elif pattern == "quarter_edges":
+        pos = np.concatenate([q * 64 + 63, q * 64])[:: 5]
+    elif pattern == "dense_island_in_a_desert":
+        pos = np.concatenate([np.arange(700_001, 760_007), [5], [n - 2]])
+    else:
+        pos = np.arange(n - (n % 64), n)
+    v, pos = _spikes(n, np.ravel(pos), 31)
+    b = W.solve_base(v, pos.size / n)
+    st = check_round_trip(np.arange(n, dtype=np.uint32), v, b, kb=512)
+    assert int(st[40:48].view("<u8")[0]) == pos.size
+
+
 def test_workspace_and_buffers_reused_across_sizes():
     """The same workspace serves a large call, then a small one, then an empty one, then a large one
     again: nothing of an earlier call may leak into a later one."""

@@ -121,6 +121,30 @@ def test_batch_with_mixed_token_widths():
     check_segmented(keys, vals, offs, [ref.params(*a) for a in args], [B.params(*a) for a in args])
 
 
+def test_batch_whose_survivors_sit_at_the_segment_ends():
+    # segments of odd lengths (so that they start anywhere inside a row); the survivors are the first and
+    # the last elements of each segment and a lone one in the middle of the long ones: the quarter rows the
+    # value pass reads are the ones that segment boundaries cut
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(77)
+    sizes = [1, 2, 63, 64, 65, 255, 257, 1021, 30_011, 3, 100_003, 511, 0, 7, 250_001, 129]
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.uint64)
+    keys = np.concatenate([np.arange(s, dtype=np.uint32) for s in sizes])
+    vals = (rng.uniform(1e-9, 1e-8, int(offs[-1])) * rng.choice([-1.0, 1.0], int(offs[-1]))).astype(np.float32)
+    args = []
+    for i, s in enumerate(sizes):
+        seg = vals[int(offs[i]):int(offs[i + 1])]
+        pos = sorted({0, min(1, s - 1), s - 1, s // 2} & set(range(s))) if s > 1000 else sorted({0, s - 1} & set(range(s)))
+        for j in pos:
+            seg[j] = np.float32(rng.uniform(0.5, 2.0) * rng.choice([-1.0, 1.0]))
+        args.append((W.solve_base(seg, len(pos) / s) if s else 1.1, 128, 1 + i % 3, 256))
+    check_segmented(keys, vals, offs, [ref.params(*a) for a in args], [B.params(*a) for a in args])
+    # the placement did what it was meant to: exactly the planted elements survive
+    rc, blob, so = ref.compress_segmented(keys, vals, offs, [ref.params(*a) for a in args])
+    kept = [int(blob[int(o) + 40:int(o) + 48].view("<u8")[0]) for o in so[:-1]]
+    assert kept == [min(s, 4 if s > 1000 else 2) for s in sizes]
+
+
 def test_batch_of_the_largest_number_of_segments():
     # 65536 segments (the limit), most of them tiny, some empty, a few that span several key blocks
     torch, B, G = _gpu()
