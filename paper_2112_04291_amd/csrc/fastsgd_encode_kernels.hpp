@@ -347,14 +347,16 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
 // The chunk's survivor count goes to ccount[chunk].  Global ranks are never materialised: k_plan_segments
 // turns the (at most 4096) chunk counts of a segment into their scan and the key encoder gathers through
 // that scan.
-constexpr u32 kStage = 1088;             // staged survivors per wave: two full rows on top of the flush level
+constexpr u32 kStage = 1024;             // staged survivors per wave (a ring)
 constexpr u32 kRing = 512;               // ring of quarter rows per wave: under a batch left over plus 64 rows of four
-constexpr u32 kFlushLevel = kStage - 2 * kRow;
 constexpr u32 kValWaves = 4;             // waves per workgroup of the value encoder (they never synchronise)
 constexpr u32 kGather = 4;               // key fetches a lane keeps in flight
 static_assert((kRing & (kRing - 1)) == 0 && kRing >= 4 * kValRows - 1 + 4 * 64, "ring: a short batch plus 64 rows");
 static_assert(kMaxChunkRows * 4 <= 65536 && kMaxChunkRows % kValRows == 0, "ring entries are 16 bits");
-static_assert(kFlushLevel >= 64 * kGather, "a flush sends at least one whole round");
+constexpr u32 kRound = 64 * kGather;     // survivors per round of a flush
+constexpr u32 kMaxRounds = kStage / kRound;
+static_assert((kStage & (kStage - 1)) == 0 && kStage % kRound == 0 && kStage >= 2 * kRow + kRound,
+              "stage: a power of two, whole rounds, a forced flush sends at least one");
 static_assert(512 + 8 * kStage + 2 * kRing <= 10240, "shared memory for sixteen waves per compute unit");
 
 // |v| >= threshold as a float compare with the |x| source modifier: for non-negative finite floats
@@ -428,57 +430,67 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
     u32 cbase = 0;                           // survivors of the chunk already in the scratch arrays
     u32 staged = 0;                          // survivors waiting in shared memory
 
-    // Staged survivors -> scratch arrays, in rounds of 64 * kGather.  While the chunk goes on only whole
-    // rounds leave (every lane of every round has work) and the rest moves to the front of the stage.
-    auto flush = [&](bool last) {
-        const u32 n_out = last ? staged : staged - staged % (64u * kGather);
-        const u64 slot = ck.slot0 + cbase;
+    // Staged survivors -> scratch arrays, in rounds of kRound.  The stage is a ring (entry i of the staged
+    // ones sits at (first + i) mod kStage).  A flush has two halves: begin() issues the key fetches of the
+    // rounds that leave, complete() turns values into codes and stores codes and keys.  Between the two
+    // the wave stages the next two rows, whose loads were issued before the key fetches: the key fetches
+    // arrive right behind them instead of being waited for on their own.  While the chunk goes on only
+    // whole rounds leave (every lane of every round has work).
+    u32 first = 0;                           // ring position of the oldest staged survivor
+    u32 pending = 0;                         // staged survivors whose keys are on their way
+    u32 pkey[kMaxRounds][kGather];
+    auto begin = [&](u32 n_out) {
         __builtin_amdgcn_wave_barrier();
-        for (u32 j0 = 0; j0 < n_out; j0 += 64u * kGather) {
-            u32 key[kGather];
 #pragma unroll
-            for (u32 k = 0; k < kGather; ++k) {               // all key fetches of the round first
-                const u32 j = j0 + k * 64u + lane;
-                key[k] = (j < n_out) ? (implicit ? key0 + s_idx[j] : ckeys[s_idx[j]]) : 0u;
-            }
+        for (u32 r = 0; r < kMaxRounds; ++r)
+            if (r * kRound < n_out) {
 #pragma unroll
-            for (u32 k = 0; k < kGather; ++k) {
-                const u32 j = j0 + k * 64u + lane;
-                if (j < n_out) {
-                    const u32 vb = s_val[j];
-                    const u32 a = vb & 0x7FFFFFFFu;
-                    // smallest code c in [1, tau] with a >= B[c]  (B non-increasing, a >= B[tau])
-                    u32 lo = 1, hi = tau;
-                    while (lo < hi) {
-                        const u32 mid = (lo + hi) >> 1;
-                        if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
-                    }
-                    scodes[slot + j] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
-                    skeys[slot + j] = key[k];
+                for (u32 k = 0; k < kGather; ++k) {
+                    const u32 j = r * kRound + k * 64u + lane;
+                    const u32 e = s_idx[(first + j) & (kStage - 1u)];
+                    pkey[r][k] = (j < n_out) ? (implicit ? key0 + e : ckeys[e]) : 0u;
                 }
-                __builtin_amdgcn_sched_barrier(0);            // one search at a time: keeps registers low
             }
-        }
+        pending = n_out;
+    };
+    auto complete = [&]() {
+        const u64 slot = ck.slot0 + cbase;
+#pragma unroll
+        for (u32 r = 0; r < kMaxRounds; ++r)
+            if (r * kRound < pending) {
+#pragma unroll
+                for (u32 k = 0; k < kGather; ++k) {
+                    const u32 j = r * kRound + k * 64u + lane;
+                    if (j < pending) {
+                        const u32 vb = s_val[(first + j) & (kStage - 1u)];
+                        const u32 a = vb & 0x7FFFFFFFu;
+                        // smallest code c in [1, tau] with a >= B[c]  (B non-increasing, a >= B[tau])
+                        u32 lo = 1, hi = tau;
+                        while (lo < hi) {
+                            const u32 mid = (lo + hi) >> 1;
+                            if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
+                        }
+                        scodes[slot + j] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
+                        skeys[slot + j] = pkey[r][k];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);        // one search at a time: keeps registers low
+                }
+            }
         __builtin_amdgcn_wave_barrier();
-        const u32 rest = staged - n_out;                      // under one round
-        if (rest) {
-            u32 mv[kGather], mi[kGather];
-#pragma unroll
-            for (u32 k = 0; k < kGather; ++k) {
-                const u32 j = k * 64u + lane;
-                mv[k] = j < rest ? s_val[n_out + j] : 0u;
-                mi[k] = j < rest ? s_idx[n_out + j] : 0u;
-            }
-            wave_lds_sync();
-#pragma unroll
-            for (u32 k = 0; k < kGather; ++k) {
-                const u32 j = k * 64u + lane;
-                if (j < rest) { s_val[j] = mv[k]; s_idx[j] = mi[k]; }
-            }
-            wave_lds_sync();
+        cbase += pending;
+        staged -= pending;
+        first = (first + pending) & (kStage - 1u);
+        pending = 0;
+    };
+    // after every two rows; `loads_issued`: the next batch's loads have just been issued
+    auto flush_step = [&](bool loads_issued) {
+        if (pending) complete();
+        if (staged > kStage - 2 * kRow) {                      // no room for two more rows: at once
+            begin(staged - staged % kRound);
+            complete();
+        } else if (loads_issued && staged >= kRound) {
+            begin(staged - staged % kRound);
         }
-        cbase += n_out;
-        staged = rest;
     };
 
     // The unit of the fetch is the quarter row (64 elements, 16 lanes): a batch is eight "virtual rows" of
@@ -510,12 +522,12 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
 #pragma unroll
         for (u32 c = 0; c < 4; ++c) m[c] = __ballot(keeps(row[c], thr_f));
         if ((m[0] | m[1] | m[2] | m[3]) == 0) return;
-        u32 pos = staged + lanes_below(m[0]) + lanes_below(m[1]) + lanes_below(m[2]) + lanes_below(m[3]);
+        u32 pos = first + staged + lanes_below(m[0]) + lanes_below(m[1]) + lanes_below(m[2]) + lanes_below(m[3]);
 #pragma unroll
         for (u32 c = 0; c < 4; ++c)
             if (keeps(row[c], thr_f)) {
-                s_val[pos] = row[c];
-                s_idx[pos] = elem + c;
+                s_val[pos & (kStage - 1u)] = row[c];
+                s_idx[pos & (kStage - 1u)] = elem + c;
                 ++pos;
             }
         staged += (u32)__popcll(m[0]) + (u32)__popcll(m[1]) + (u32)__popcll(m[2]) + (u32)__popcll(m[3]);
@@ -583,10 +595,14 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                 for (u32 slot = 0; slot < kValRows; ++slot)
                     if (slot < nr) load_quarters(on[slot] != 0, elem[slot], bits[slot]);
             }
-            if (staged > kFlushLevel) flush(false);                 // room for two more rows
+            flush_step(pair + 1 == kValRows / 2);
         }
     }
-    if (staged) flush(true);
+    if (pending) complete();
+    if (staged) {
+        begin(staged);
+        complete();
+    }
     if (lane == 0) ccount[chunk] = cbase;
 }
 
