@@ -44,7 +44,7 @@ enum {
 
 typedef struct {
     double base;         /* b  */
-    uint32_t tau;        /* threshold on the integer code, 1..128 */
+    uint32_t tau;        /* threshold on the integer code, 1..256 */
     uint32_t flag_bits;  /* l, 1..5 */
     uint32_t block_keys; /* surviving keys per key block, power of two in [256, 4096] */
     uint32_t reserved;   /* must be 0 */
@@ -53,6 +53,7 @@ typedef struct {
 #define REF_HEADER_BYTES 64u
 #define REF_MAGIC 0x44475346u /* "FSGD" little-endian */
 #define REF_VERSION 1u
+#define REF_MAX_TAU 256u /* Section 3.2 recommends 128; up to 256 a token is 9 bits */
 
 static uint32_t f32_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
 static float bits_f32(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
@@ -62,7 +63,8 @@ static double bits_f64(uint64_t u) { double f; memcpy(&f, &u, 8); return f; }
 static int params_ok(const ref_params *p) {
     if (!p) return 0;
     if (!(p->base >= 1.0 + 1.0 / 1048576.0) || !(p->base <= 16.0)) return 0;
-    if (p->tau < 1 || p->tau > 128) return 0;
+    if (p->tau < 1 || p->tau > REF_MAX_TAU) return 0;
+    if (p->tau > 128 && !(p->base <= 4.0)) return 0; /* b^tau <= 2^512: sum / b^c stays a normal binary64 */
     if (p->flag_bits < 1 || p->flag_bits > 5) return 0;
     if (p->block_keys < 256 || p->block_keys > 4096) return 0;
     if (p->block_keys & (p->block_keys - 1)) return 0;
@@ -137,7 +139,7 @@ int fastsgd_ref_abs_sum(const float *v, uint64_t n, double *sum_out) {
  * is unused and set to 0.
  * ------------------------------------------------------------------------- */
 void fastsgd_ref_tables(double sum, double base, uint32_t tau,
-                        uint32_t *B_bits /* [129] */, uint32_t *V_bits /* [129] */) {
+                        uint32_t *B_bits /* [tau + 1] */, uint32_t *V_bits /* [tau + 1] */) {
     double P = 1.0;
     B_bits[0] = 0; V_bits[0] = 0;
     for (uint32_t c = 1; c <= tau; ++c) {
@@ -153,7 +155,7 @@ void fastsgd_ref_tables(double sum, double base, uint32_t tau,
 
 /* Phase 1-3 for one value that passed the early-stop test: the integer code.
  * Reading: L = 0 is only possible when one element carries the whole sum; it is
- * stored as 1, so codes are 1..tau and code-1 fits seven bits next to the sign. */
+ * stored as 1, so codes are 1..tau and code-1 takes ceil(log2 tau) bits. */
 static uint32_t code_of(uint32_t abs_bits, const uint32_t *B_bits, uint32_t tau) {
     uint32_t c = 1;
     for (uint32_t cp = 1; cp < tau; ++cp)
@@ -197,7 +199,7 @@ static uint64_t get_u64(const uint8_t *p) { uint64_t x = 0; for (int k = 0; k < 
 static uint64_t words64(uint64_t bits) { return (bits + 63) / 64; }
 
 /* Section 3.2, after the threshold filter: the codes 1..tau need ceil(log2 tau) bits (stored as
- * code-1), one more bit carries the sign: 8 bits for the recommended tau = 128. */
+ * code-1), one more bit carries the sign: 8 bits for the recommended tau = 128, 9 above it. */
 static uint32_t code_width(uint32_t tau) {
     uint32_t q = 0;
     while (((uint32_t)1 << q) < tau) ++q;
@@ -218,11 +220,11 @@ uint64_t fastsgd_ref_compressed_size(uint64_t n, const ref_params *p) {
  * Encoder = Algorithm 1 followed by Algorithm 2 on the surviving keys.
  *
  * Container (the paper fixes none; Reading): little-endian,
- *   [0,64)   header: magic, version u8, l u8, tau u8, 0 u8, block_keys u32,
+ *   [0,64)   header: magic, version u8, l u8, tau u16, block_keys u32,
  *            n_blocks u32, b f64, sum f64, n u64, d u64, total_bytes u64, 0 u64
  *   value plane: one token of w = 1 + ceil(log2 tau) bits per survivor (Section 3.2), token j at
  *            bit j*w counted LSB first: low w-1 bits = code-1, top bit = sign; for tau in 65..128
- *            that is one byte per survivor, bit7 = sign, bits0-6 = code-1
+ *            that is one byte per survivor, bit7 = sign, bits0-6 = code-1; for tau in 129..256 nine bits
  *   zero padding to a multiple of 8 bytes
  *   block directory: n_blocks x {off8 u32, preKey u32, M u32, payload_bits u32}
  *   key blocks, back to back, each a flags plane (cnt*l bits) and a payload
@@ -248,7 +250,7 @@ int fastsgd_ref_compress(const uint32_t *keys, const float *values, uint64_t n,
     if (fastsgd_ref_abs_sum(values, n, &sum)) return REF_ERR_NONFINITE;
 
     /* line 2 (and the boundaries of all other codes) */
-    uint32_t B_bits[129], V_bits[129];
+    uint32_t B_bits[REF_MAX_TAU + 1], V_bits[REF_MAX_TAU + 1];
     fastsgd_ref_tables(sum, p->base, tau, B_bits, V_bits);
     const uint32_t tau_e = B_bits[tau];
 
@@ -256,7 +258,7 @@ int fastsgd_ref_compress(const uint32_t *keys, const float *values, uint64_t n,
     const uint32_t w = code_width(tau);
     uint64_t d = 0;
     uint32_t *skeys = (uint32_t *)malloc((n ? n : 1) * sizeof(uint32_t));
-    uint8_t *token = (uint8_t *)malloc(n ? n : 1);
+    uint16_t *token = (uint16_t *)malloc((n ? n : 1) * sizeof(uint16_t));
     if (!skeys || !token) { free(skeys); free(token); return REF_ERR_INVALID_ARG; }
     if (sum > 0.0) {
         for (uint64_t j = 0; j < n; ++j) {
@@ -264,7 +266,7 @@ int fastsgd_ref_compress(const uint32_t *keys, const float *values, uint64_t n,
             uint32_t a = bits & 0x7FFFFFFFu;
             if (a >= tau_e) { /* |v_j| >= tau_e */
                 uint32_t c = code_of(a, B_bits, tau);
-                token[d] = (uint8_t)((bits >> 31) << (w - 1) | (c - 1));
+                token[d] = (uint16_t)((bits >> 31) << (w - 1) | (c - 1));
                 skeys[d] = keys[j];
                 ++d;
             }
@@ -320,7 +322,7 @@ int fastsgd_ref_compress(const uint32_t *keys, const float *values, uint64_t n,
     uint8_t *h = out;
     memset(h, 0, REF_HEADER_BYTES);
     put_u32(h, REF_MAGIC);
-    h[4] = REF_VERSION; h[5] = (uint8_t)l; h[6] = (uint8_t)tau; h[7] = 0;
+    h[4] = REF_VERSION; h[5] = (uint8_t)l; h[6] = (uint8_t)(tau & 0xFF); h[7] = (uint8_t)(tau >> 8);
     put_u32(h + 8, KB); put_u32(h + 12, (uint32_t)nb);
     put_u64(h + 16, f64_bits(p->base)); put_u64(h + 24, f64_bits(sum));
     put_u64(h + 32, n); put_u64(h + 40, d); put_u64(h + 48, total);
@@ -342,9 +344,9 @@ int fastsgd_ref_decompress(const uint8_t *stream, uint64_t stream_bytes,
     const uint8_t *h = stream;
     if (get_u32(h) != REF_MAGIC || h[4] != REF_VERSION) return REF_ERR_CORRUPT_STREAM;
     ref_params p;
-    p.flag_bits = h[5]; p.tau = h[6]; p.block_keys = get_u32(h + 8); p.reserved = 0;
+    p.flag_bits = h[5]; p.tau = h[6] | (uint32_t)h[7] << 8; p.block_keys = get_u32(h + 8); p.reserved = 0;
     p.base = bits_f64(get_u64(h + 16));
-    if (!params_ok(&p) || h[7] != 0) return REF_ERR_CORRUPT_STREAM;
+    if (!params_ok(&p)) return REF_ERR_CORRUPT_STREAM;
     uint64_t nb = get_u32(h + 12);
     double sum = bits_f64(get_u64(h + 24));
     uint64_t n = get_u64(h + 32), d = get_u64(h + 40), total = get_u64(h + 48);
@@ -358,7 +360,7 @@ int fastsgd_ref_decompress(const uint8_t *stream, uint64_t stream_bytes,
     if (d > capacity) return REF_ERR_BUFFER_TOO_SMALL;
     if (d && (!keys_out || !values_out)) return REF_ERR_INVALID_ARG;
 
-    uint32_t B_bits[129], V_bits[129];
+    uint32_t B_bits[REF_MAX_TAU + 1], V_bits[REF_MAX_TAU + 1];
     fastsgd_ref_tables(sum, p.base, tau, B_bits, V_bits);
 
     /* phases 3-4 */

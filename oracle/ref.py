@@ -84,8 +84,8 @@ def abs_sum(values):
 
 def tables(s, base, tau):
     """Boundary bit patterns B[0..128] and decoded-magnitude bit patterns V[0..128] (index = code)."""
-    B = np.zeros(129, np.uint32)
-    V = np.zeros(129, np.uint32)
+    B = np.zeros(257, np.uint32)
+    V = np.zeros(257, np.uint32)
     lib().fastsgd_ref_tables(float(s), float(base), int(tau), _ptr(B), _ptr(V))
     return B, V
 

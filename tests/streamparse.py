@@ -26,19 +26,22 @@ def _bits(buf, pos, n):
 def parse(stream):
     s = bytes(stream)
     assert len(s) >= 64
-    magic, version, l, tau, zero, KB, nb = struct.unpack_from("<4sBBBBII", s, 0)
+    magic, version, l, tau, KB, nb = struct.unpack_from("<4sBBHII", s, 0)
     base, S = struct.unpack_from("<dd", s, 16)
     n, d, total, rsv = struct.unpack_from("<QQQQ", s, 32)
-    assert magic == b"FSGD" and version == 1 and zero == 0 and rsv == 0
+    assert magic == b"FSGD" and version == 1 and 1 <= tau <= 256 and rsv == 0
     assert total == len(s), (total, len(s))
     assert nb == -(-d // KB)
     # value plane: d tokens of w = 1 + ceil(log2 tau) bits, low bits code-1, top bit the sign; reported
-    # as sign << 7 | code-1 whatever w is
+    # as sign << 7 | code-1 for every w up to 8 (tau <= 128), and as the 9-bit token itself above that;
+    # "code" (1..tau) and "negative" give the two parts whatever w is
     w = 1 + (tau - 1).bit_length()
     dir_off = 64 + 8 * (-(-(d * w) // 64))
     plane = s[64:dir_off]
     toks = [_bits(plane, j * w, w) for j in range(d)]
-    codes = [((t >> (w - 1)) << 7) | (t & ((1 << (w - 1)) - 1)) for t in toks]
+    codes = [((t >> (w - 1)) << 7) | (t & ((1 << (w - 1)) - 1)) for t in toks] if w <= 8 else toks
+    code = [(t & ((1 << (w - 1)) - 1)) + 1 for t in toks]
+    negative = [bool(t >> (w - 1)) for t in toks]
     assert _bits(plane, d * w, 8 * len(plane) - d * w) == 0, "value-plane padding must be zero"
     blocks_off = dir_off + 16 * nb
     keys, tokens, off_expect = [], [], 0
@@ -69,7 +72,7 @@ def parse(stream):
         off_expect = off8 + fwords + pwords
     assert blocks_off + 8 * off_expect == total
     return dict(l=l, tau=tau, KB=KB, nb=nb, w=w, base=base, S=S, n=n, d=d, total=total,
-                codes=codes, keys=keys, tokens=tokens)
+                codes=codes, code=code, negative=negative, keys=keys, tokens=tokens)
 
 
 def exact_code(abs_v, S, base, limit=4096):

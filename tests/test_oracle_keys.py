@@ -145,7 +145,7 @@ def test_unsorted_or_duplicate_surviving_keys_are_rejected():
 
 def test_invalid_params_and_capacity():
     k, v = np.arange(100), np.full(100, BIG, np.float32)
-    for bad in [ref.params(1.0), ref.params(17.0), ref.params(tau=0), ref.params(tau=129),
+    for bad in [ref.params(1.0), ref.params(17.0), ref.params(tau=0), ref.params(tau=257), ref.params(4.5, 129),
                 ref.params(flag_bits=0), ref.params(flag_bits=6), ref.params(block_keys=128),
                 ref.params(block_keys=1000), ref.params(block_keys=8192), ref.params(base=float("nan"))]:
         assert ref.compress(k, v, bad)[0] == ref.ERR_INVALID_ARG

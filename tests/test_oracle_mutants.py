@@ -26,6 +26,10 @@ VALUE_PINS = [lambda: TV.test_abs_sum_equals_fsum_wide_exponents(0),
               lambda: TV.test_decode_underestimates_within_one_base_step(0, 1.1),
               TV.test_values_exactly_on_below_and_above_bucket_boundaries,
               lambda: TV.test_codes_take_one_plus_ceil_log2_tau_bits(33)]
+WIDE_PINS = [TV.test_tables_for_256_codes_in_closed_form_down_to_the_smallest_binary32,
+             lambda: TV.test_codes_above_128_match_exact_rational_log(20, 1.1, 200, 30, 1.0),
+             lambda: TV.test_a_threshold_above_128_only_adds_survivors(200),
+             TV.test_parameter_limits_above_128]
 KEY_PINS = [TK.test_fig3_worked_example,
             lambda: TK.test_flag_is_smallest_level_that_fits(2, 0),
             lambda: TK.test_flag_is_smallest_level_that_fits(3, 1),
@@ -60,7 +64,14 @@ MUTANTS = [
     ("code: a value on a boundary falls into the next bucket", "if (abs_bits < B_bits[cp]) ++c;", "if (abs_bits <= B_bits[cp]) ++c;", VALUE_PINS),
     ("code: counted from zero", "    uint32_t c = 1;\n    for (uint32_t cp = 1; cp < tau; ++cp)", "    uint32_t c = 0;\n    for (uint32_t cp = 1; cp < tau; ++cp)", VALUE_PINS),
     ("filter: a value on the threshold is dropped", "if (a >= tau_e) { /* |v_j| >= tau_e */", "if (a > tau_e) { /* |v_j| >= tau_e */", VALUE_PINS),
-    ("sign lost", "token[d] = (uint8_t)((bits >> 31) << (w - 1) | (c - 1));", "token[d] = (uint8_t)(c - 1);", VALUE_PINS),
+    ("sign lost", "token[d] = (uint16_t)((bits >> 31) << (w - 1) | (c - 1));", "token[d] = (uint16_t)(c - 1);", VALUE_PINS),
+    ("tau above 128: token cut to a byte", "token[d] = (uint16_t)((bits >> 31) << (w - 1) | (c - 1));",
+     "token[d] = (uint8_t)((bits >> 31) << (w - 1) | (c - 1));", WIDE_PINS),
+    ("tau above 128: high byte of tau left out of the header", "h[7] = (uint8_t)(tau >> 8);", "h[7] = 0;", WIDE_PINS),
+    ("tau above 128: header read as one byte", "p.tau = h[6] | (uint32_t)h[7] << 8;", "p.tau = h[6];", WIDE_PINS),
+    ("tau above 128: any base allowed", "if (p->tau > 128 && !(p->base <= 4.0)) return 0;", ";", WIDE_PINS),
+    ("tau above 128: limit one too low", "if (p->tau < 1 || p->tau > REF_MAX_TAU) return 0;",
+     "if (p->tau < 1 || p->tau >= REF_MAX_TAU) return 0;", WIDE_PINS),
     ("token one bit too wide", "    return 1 + q;", "    return 2 + q;", VALUE_PINS),
     ("level length rounded down", "return (i * M + (1u << l) - 1) >> l;", "return (i * M) >> l;", KEY_PINS),
     ("level chosen one too high", "if (need <= level_len(i, M, l)) return i;", "if (need < level_len(i, M, l)) return i;", KEY_PINS),

@@ -400,3 +400,108 @@ def test_packed_codes_beyond_tau_are_rejected():
     bad[64] = (st[64] & 0xF0) | 0x04           # code-1 = 4 is code 5 = tau: fine
     rc, k, v = ref.decompress(bad)
     assert rc == ref.OK
+
+
+# ----------------------------------------------------------------------------- tau above 128 (9-bit tokens)
+def test_tables_for_256_codes_in_closed_form_down_to_the_smallest_binary32():
+    """b = 2 and sum = 2^100: the boundary of code c is 2^(100-c) exactly while that is a binary32 number
+    (normal to 2^-126, denormal to 2^-149).  Below it the two roundings part: the boundary rounds UP to the
+    smallest positive binary32, the decoded magnitude rounds to NEAREST, which is zero (2^-150 is a tie
+    between 0 and 2^-149 and goes to the even one)."""
+    B, V = ref.tables(2.0 ** 100, 2.0, 256)
+    for c in range(1, 250):
+        x = np.float32(2.0 ** (100 - c))
+        assert float(x) == 2.0 ** (100 - c)
+        assert B[c] == x.view(np.uint32) and V[c] == x.view(np.uint32), c
+    assert list(B[250:257]) == [1] * 7                      # bit pattern 1 = 2^-149
+    assert list(V[250:257]) == [0] * 7
+    # the tables of a smaller tau are a prefix of these (the chain does not depend on tau)
+    B2, V2 = ref.tables(2.0 ** 100, 2.0, 128)
+    assert np.array_equal(B2[:129], B[:129]) and np.array_equal(V2[:129], V[:129])
+    assert not B2[129:].any()
+
+
+@pytest.mark.parametrize("seed,b,tau,spread,top", [(20, 1.1, 200, 30, 1.0), (21, 1.05, 256, 30, 1.0),
+                                                   (22, 1.3, 129, 45, 1.0), (23, 4.0, 130, 185, 1e37)])
+def test_codes_above_128_match_exact_rational_log(seed, b, tau, spread, top):
+    """Brute force as above for thresholds past 128: the code is the least c with |v| b^c >= sum, the token
+    is nine bits wide (eight for the code-1, one for the sign)."""
+    rng = np.random.default_rng(seed)
+    n = 400
+    v = (np.clip(rng.laplace(0, 1, n), -3, 3) * top * np.exp(rng.uniform(-spread, 0, n))).astype(np.float32)
+    S = ref.abs_sum(v)[1]                 # (with b = 4 the codes past 128 need the whole binary32 range)
+    info = codes_of(v, ref.params(b, tau, 2, 1024))
+    assert info["w"] == 9 and info["tau"] == tau
+    got = {k: (c, neg) for k, c, neg in zip(info["keys"], info["code"], info["negative"])}
+    checked = above = 0
+    for j, x in enumerate(v):
+        if x == 0:
+            assert j not in got
+            continue
+        c, margin = exact_code(abs(float(x)), S, b, limit=tau + 2)
+        if c is not None and margin < 1e-9:
+            continue
+        if c is None or c > tau:
+            assert j not in got, (j, x, c)
+        else:
+            assert got[j] == (max(c, 1), bool(x < 0)), (j, x, c, got[j])
+            checked += 1
+            above += c > 128
+    assert checked > 50 and above > (5 if tau >= 200 else 0)
+
+
+@pytest.mark.parametrize("tau", [129, 200, 256])
+def test_a_threshold_above_128_only_adds_survivors(tau):
+    """The code of a value does not depend on tau: the stream of tau = 128 must be what is left of the
+    stream of a bigger tau once the codes above 128 are struck out, and every survivor it adds has a code
+    in 129..tau; decoded values agree on the common part."""
+    rng = np.random.default_rng(tau)
+    n = 6000
+    keys = np.sort(rng.choice(10 * n, n, replace=False)).astype(np.uint32)
+    vals = (rng.laplace(0.0, 1e-3, n) * np.exp(rng.uniform(-8, 0, n))).astype(np.float32)
+    S = float(np.abs(vals.astype(np.float64)).sum())
+    base = (S / float(np.quantile(np.abs(vals), 0.3))) ** (1.0 / tau)       # about 70 % survive at tau
+    rc, st8 = ref.compress(keys, vals, ref.params(base, 128, 2, 256))
+    rc9, st9 = ref.compress(keys, vals, ref.params(base, tau, 2, 256))
+    assert rc == ref.OK and rc9 == ref.OK
+    a, b = parse(st8), parse(st9)
+    assert a["w"] == 8 and b["w"] == 9 and b["d"] > a["d"] > 100
+    common = [i for i, c in enumerate(b["code"]) if c <= 128]
+    assert [b["code"][i] for i in common] == a["code"] and [b["negative"][i] for i in common] == a["negative"]
+    assert [b["keys"][i] for i in common] == a["keys"]
+    assert max(b["code"]) <= tau and min(c for c in b["code"] if c > 128) == 129
+    # value plane: d tokens of 9 bits, padded to 8 bytes
+    plane = 8 * math.ceil(b["d"] * 9 / 64)
+    assert st9.size >= 64 + plane + 16 * b["nb"]
+    rc, k8, v8 = ref.decompress(st8)
+    rc9, k9, v9 = ref.decompress(st9)
+    assert rc == ref.OK and rc9 == ref.OK
+    assert np.array_equal(k9[common], k8) and np.array_equal(v9[common].view(np.uint32), v8.view(np.uint32))
+    # the under-estimate of Section 3.2 holds for the new codes too: |v|/b < |decoded| <= |v|
+    src = dict(zip(keys.tolist(), vals.tolist()))
+    for k, x in zip(k9.tolist(), v9.tolist()):
+        o = src[k]
+        assert (x < 0) == (o < 0) and abs(x) <= abs(o) and abs(o) / base < abs(x) * (1 + 2.0 ** -22)
+
+
+def test_parameter_limits_above_128():
+    k, v = np.arange(10), np.full(10, 1.0, np.float32)
+    assert ref.compress(k, v, ref.params(1.1, 256))[0] == ref.OK
+    assert ref.compress(k, v, ref.params(1.1, 257))[0] == ref.ERR_INVALID_ARG
+    # past 128 the base stops at 4: b^tau must stay a finite binary64 well inside the normal range
+    assert ref.compress(k, v, ref.params(4.0, 129))[0] == ref.OK
+    assert ref.compress(k, v, ref.params(4.0 + 1e-9, 129))[0] == ref.ERR_INVALID_ARG
+    assert ref.compress(k, v, ref.params(16.0, 128))[0] == ref.OK
+    # header: tau in 16 bits; a stream that claims 257 is corrupt, and so is a 9-bit code beyond tau
+    rc, st = ref.compress(k, v, ref.params(1.1, 200))
+    assert rc == ref.OK and parse(st)["d"] == 10 and int(st[6]) == 200 and int(st[7]) == 0
+    rc, st2 = ref.compress(k, v, ref.params(1.1, 256))
+    assert int(st2[6]) == 0 and int(st2[7]) == 1
+    rc, k2, v2 = ref.decompress(st2)
+    assert rc == ref.OK and k2.tolist() == list(range(10))
+    bad = st2.copy(); bad[6] = 1
+    assert ref.decompress(bad)[0] == ref.ERR_CORRUPT_STREAM
+    bad = st.copy(); bad[64] = 200                                  # token 0: code-1 = 200 -> code 201 > tau
+    assert ref.decompress(bad)[0] == ref.ERR_CORRUPT_STREAM
+    bad[64] = 199
+    assert ref.decompress(bad)[0] == ref.OK
