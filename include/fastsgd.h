@@ -23,10 +23,11 @@
  *   - Keys are uint32 and strictly increasing within one gradient (the first may be 0);
  *     values are IEEE binary32.  n <= 2^32 - 1024 per gradient.
  *
- * Stream layout (little-endian): 64-byte header {"FSGD", version u8, l u8, tau u8, 0 u8,
+ * Stream layout (little-endian): 64-byte header {"FSGD", version u8, l u8, tau u16,
  * block_keys u32, n_blocks u32, b f64, sum f64, n u64, d u64, total_bytes u64, 0 u64}; value
  * plane of d tokens of 1 + ceil(log2 tau) bits (Section 3.2; low bits code-1, top bit sign; token j
- * at bit j * width, LSB first; one byte each for tau in 65..128) zero-padded to 8 bytes; block
+ * at bit j * width, LSB first; one byte each for tau in 65..128, nine bits for tau in 129..256)
+ * zero-padded to 8 bytes; block
  * directory of n_blocks x {off8 u32, preKey u32, M u32, payload_bits u32}; key blocks back to
  * back, each a flags plane
  * (cnt*l bits) and a payload plane (payload_bits bits), LSB first, zero-padded to 64-bit words.
@@ -45,9 +46,11 @@ extern "C" {
  * quantization, threshold tau of the filter, size l of the length flag; block_keys is how many
  * surviving keys share one M (Algorithm 2 is applied per block, preKey carried across). */
 typedef struct {
-    double   base;       /* b: 1 + 2^-20 <= b <= 16 (paper: about 1.1)            */
-    uint32_t tau;        /* 1..128 (paper: 128, so a code fits one byte with sign;
-                            smaller tau gives narrower codes, see the stream layout) */
+    double   base;       /* b: 1 + 2^-20 <= b <= 16 (paper: about 1.1); <= 4 when tau > 128,
+                            so that b^tau stays finite                             */
+    uint32_t tau;        /* 1..256 (paper: 128, so a code fits one byte with sign;
+                            smaller tau gives narrower codes, larger tau nine-bit
+                            ones, see the stream layout)                            */
     uint32_t flag_bits;  /* l: 1..5 (paper: 2)                                     */
     uint32_t block_keys; /* power of two, 256..4096 (default 1024)                 */
     uint32_t reserved;   /* must be 0                                              */

@@ -9,7 +9,7 @@
 
 namespace fsgd {
 
-constexpr u64 kDecSegBytes = 640, kDecCtrlBytes = 64;   // >= sizeof(DecSeg), sizeof(DecCtrl)
+constexpr u64 kDecSegBytes = 1152, kDecCtrlBytes = 64;   // >= sizeof(DecSeg), sizeof(DecCtrl)
 constexpr u32 kMaxSegments = 65536;
 constexpr u64 kMaxElems = 0xFFFFFFFFull - 1023;   // per gradient: scratch offsets inside a segment stay below 2^32
 constexpr u32 kMaxSumGrid = 2048;      // most workgroups the abs-sum pass of a single gradient is launched with
@@ -19,7 +19,8 @@ static_assert(sizeof(SegInfo) == 48 && sizeof(SegBatch) <= 3900, "segment table 
 static bool params_ok(const fastsgd_params* p) {
     if (!p) return false;
     if (!(p->base >= 1.0 + 1.0 / 1048576.0) || !(p->base <= 16.0)) return false;
-    if (p->tau < 1 || p->tau > 128) return false;
+    if (p->tau < 1 || p->tau > kMaxTau) return false;
+    if (p->tau > 128 && !(p->base <= 4.0)) return false;       // b^tau stays finite (and sum / b^c a normal binary64)
     if (p->flag_bits < 1 || p->flag_bits > 5) return false;
     if (p->block_keys < 256 || p->block_keys > kMaxKB || (p->block_keys & (p->block_keys - 1))) return false;
     return p->reserved == 0;
@@ -53,7 +54,7 @@ static EncodePlan make_plan(u64 total_n, u32 n_segments, u32 min_kb) {
     pl.off_seginfo = o;  o += up((u64)n_segments * sizeof(SegInfo), 256);
     pl.off_segstate = o; o += up((u64)n_segments * sizeof(SegState), 256);
     pl.off_skeys = o;    o += up(pl.max_slots * 4, 256);
-    pl.off_scodes = o;   o += up(pl.max_slots, 256);
+    pl.off_scodes = o;   o += up(pl.max_slots * 2, 256);          // 16 bits per code when some tau is above 128
     pl.total = o;
     return pl;
 }
@@ -102,6 +103,7 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
 
     std::vector<SegInfo> segs(n_segments);
     u32 min_kb = kMaxKB, max_kb = 0;
+    bool wide = false;                                             // some segment's codes need more than a byte
     u64 n_tiles = 0, max_items = 0, total_rows = 0;
     for (u32 s = 0; s < n_segments; ++s) {
         const fastsgd_params* p = &params[params_stride ? s : 0];
@@ -123,6 +125,7 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
         max_items += blocks ? blocks : 1;
         if (p->block_keys < min_kb) min_kb = p->block_keys;
         if (p->block_keys > max_kb) max_kb = p->block_keys;
+        if (p->tau > 128) wide = true;
     }
     // chunks of R rows, about kChunkTarget of them, never shorter than one tile
     u64 R64 = (total_rows + kChunkTarget - 1) / kChunkTarget;
@@ -195,10 +198,15 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     hipLaunchKernelGGL(k_tables, dim3(n_segments), dim3(kTableThreads), 0, stream, dsegs, dstates, gbins,
                        single ? sum_grid : pl.n_slots, ctrl);
     marks.mark(stream);
-    if (n_chunks)
-        hipLaunchKernelGGL(k_encode_values, dim3((u32)((n_chunks + kValWaves - 1) / kValWaves)),
-                           dim3(kValWaves * kWave), 0, stream, kbase, vbase, dsegs, dstates, n_segments, (u32)n_chunks,
-                           R, rowmax, ccount, skeys, scodes);
+    if (n_chunks) {
+        const dim3 grid((u32)((n_chunks + kValWaves - 1) / kValWaves)), block(kValWaves * kWave);
+        if (wide)
+            hipLaunchKernelGGL(k_encode_values<true>, grid, block, 0, stream, kbase, vbase, dsegs, dstates, n_segments,
+                               (u32)n_chunks, R, rowmax, ccount, skeys, (void*)scodes);
+        else
+            hipLaunchKernelGGL(k_encode_values<false>, grid, block, 0, stream, kbase, vbase, dsegs, dstates, n_segments,
+                               (u32)n_chunks, R, rowmax, ccount, skeys, (void*)scodes);
+    }
     marks.mark(stream);
     hipLaunchKernelGGL(k_plan_segments, dim3(n_segments), dim3(kThreads), 0, stream, dsegs, dstates, n_segments, R,
                        ccount, ctrl);
@@ -212,9 +220,14 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
         hipLaunchKernelGGL(k_measure_keys<false>, dim3(clamp_grid(max_units, (u64)cus * 8)), dim3(kThreads), 0, stream,
                            segs[0], dsegs, dstates, n_segments, R, ccount, skeys, binfo, gsum, g_shift, ctrl);
     marks.mark(stream);
-    hipLaunchKernelGGL(k_pack_keys, dim3(clamp_grid(max_units, (u64)cus * 4)), dim3(kThreads), 0, stream, segs[0], dsegs,
-                       dstates, n_segments, R, ccount, skeys, scodes, binfo, gsum, g_shift, out,
-                       (u64)out_capacity, d_out_offsets, single ? 1u : 0u, d_status, ctrl);
+    if (wide)
+        hipLaunchKernelGGL(k_pack_keys<true>, dim3(clamp_grid(max_units, (u64)cus * 4)), dim3(kThreads), 0, stream, segs[0],
+                           dsegs, dstates, n_segments, R, ccount, skeys, (const void*)scodes, binfo, gsum, g_shift, out,
+                           (u64)out_capacity, d_out_offsets, single ? 1u : 0u, d_status, ctrl);
+    else
+        hipLaunchKernelGGL(k_pack_keys<false>, dim3(clamp_grid(max_units, (u64)cus * 4)), dim3(kThreads), 0, stream, segs[0],
+                           dsegs, dstates, n_segments, R, ccount, skeys, (const void*)scodes, binfo, gsum, g_shift, out,
+                           (u64)out_capacity, d_out_offsets, single ? 1u : 0u, d_status, ctrl);
     marks.mark(stream);
     return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
 }
@@ -239,11 +252,11 @@ static fastsgd_status decompress_impl(const void* d_streams, size_t total_bytes,
 
     marks.mark(stream);
     if (single) {
-        hipLaunchKernelGGL(k_decode_setup, dim3(1), dim3(128), 0, stream, streams, (u64)total_bytes,
+        hipLaunchKernelGGL(k_decode_setup, dim3(1), dim3(kMaxTau), 0, stream, streams, (u64)total_bytes,
                            (const u64*)nullptr, 1u, segs, ctrl, capacity, d_counts, d_status);
     } else {
         hipLaunchKernelGGL(k_decode_clear, dim3(1), dim3(64), 0, stream, ctrl);
-        hipLaunchKernelGGL(k_decode_setup, dim3(n_segments), dim3(128), 0, stream, streams, (u64)total_bytes,
+        hipLaunchKernelGGL(k_decode_setup, dim3(n_segments), dim3(kMaxTau), 0, stream, streams, (u64)total_bytes,
                            d_stream_offsets, n_segments == 1 ? 1u : 0u, segs, ctrl, capacity, d_counts, d_status);
         if (n_segments > 1)
             hipLaunchKernelGGL(k_decode_plan, dim3(1), dim3(kThreads), 0, stream, segs, n_segments, capacity, ctrl,
@@ -277,7 +290,7 @@ static fastsgd_status accumulate_impl(const void* d_streams, size_t total_bytes,
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const u32 cus = cu_count();
     hipLaunchKernelGGL(k_decode_clear, dim3(1), dim3(64), 0, stream, ctrl);
-    hipLaunchKernelGGL(k_decode_setup, dim3(n_streams), dim3(128), 0, stream, streams, (u64)total_bytes,
+    hipLaunchKernelGGL(k_decode_setup, dim3(n_streams), dim3(kMaxTau), 0, stream, streams, (u64)total_bytes,
                        d_stream_offsets, 0u, segs, ctrl, ~0ull, counts, d_status);
     hipLaunchKernelGGL(k_decode_plan, dim3(1), dim3(kThreads), 0, stream, segs, n_streams, ~0ull, ctrl, counts, d_status,
                        d_count);
@@ -314,7 +327,7 @@ static fastsgd_status adam_impl(const void* d_stream, size_t stream_bytes, float
     a.beta2 = (float)h->beta2;
     a.one_minus_beta2 = (float)(1.0 - h->beta2);
     a.eps = (float)h->eps;
-    hipLaunchKernelGGL(k_decode_setup, dim3(1), dim3(128), 0, stream, streams, (u64)stream_bytes, (const u64*)nullptr, 1u,
+    hipLaunchKernelGGL(k_decode_setup, dim3(1), dim3(kMaxTau), 0, stream, streams, (u64)stream_bytes, (const u64*)nullptr, 1u,
                        segs, ctrl, ~0ull, d_count, d_status);
     const u32 grid = clamp_grid(((u64)stream_bytes / 96 + 1 + kWaves - 1) / kWaves, (u64)cu_count() * 7);
     hipLaunchKernelGGL(k_decode<kAdam>, dim3(grid), dim3(kThreads), 0, stream, streams, segs, 1u, ctrl, (u32*)nullptr,

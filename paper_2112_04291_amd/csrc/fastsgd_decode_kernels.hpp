@@ -16,7 +16,7 @@ struct DecSeg {
     u64 dir_off, blocks_off, total_words;   // absolute byte offsets; words of all key blocks
     u32 nb, l, tau, KB;
     u32 ok, pad[3];
-    u32 V[128];         // V[c-1] = bit pattern of the decoded magnitude of code c
+    u32 V[kMaxTau];     // V[c-1] = bit pattern of the decoded magnitude of code c
 };
 
 struct DecCtrl {
@@ -52,11 +52,11 @@ __device__ __forceinline__ void plan_streams(DecSeg* segs, u32 n_segments, u64 c
     *out_status = status;
 }
 
-__global__ void __launch_bounds__(128)
+__global__ void __launch_bounds__(kMaxTau)
 k_decode_setup(const uint8_t* __restrict__ streams, u64 total_bytes, const u64* __restrict__ stream_offsets,
                u32 plan_inline, DecSeg* segs, DecCtrl* ctrl, u64 capacity, u64* out_counts, u32* out_status) {
     // launched with one workgroup per stream; for a batch k_decode_clear has reset ctrl beforehand
-    __shared__ double s_P[129];
+    __shared__ double s_P[kMaxTau + 1];
     __shared__ double s_sum;
     __shared__ u32 s_ok, s_tau;
     const u32 seg = blockIdx.x, t = threadIdx.x;
@@ -72,15 +72,15 @@ k_decode_setup(const uint8_t* __restrict__ streams, u64 total_bytes, const u64* 
         if (ok) {
             const u64* h = reinterpret_cast<const u64*>(streams + begin);
             const u64 h0 = h[0], h1 = h[1];
-            l = (u32)(h0 >> 40) & 0xFF; tau = (u32)(h0 >> 48) & 0xFF; KB = (u32)h1; nb = (u32)(h1 >> 32);
+            l = (u32)(h0 >> 40) & 0xFF; tau = (u32)(h0 >> 48); KB = (u32)h1; nb = (u32)(h1 >> 32);
             base = __longlong_as_double((long long)h[2]);
             sum = __longlong_as_double((long long)h[3]);
             const u64 n = h[4], total = h[6];
             d = h[5];
-            ok = ((u32)h0 == kMagic) && (((h0 >> 32) & 0xFF) == kVersion) && ((h0 >> 56) == 0);
-            ok = ok && l >= 1 && l <= 5 && tau >= 1 && tau <= 128;
+            ok = ((u32)h0 == kMagic) && (((h0 >> 32) & 0xFF) == kVersion);
+            ok = ok && l >= 1 && l <= 5 && tau >= 1 && tau <= kMaxTau;
             ok = ok && KB >= 256 && KB <= kMaxKB && (KB & (KB - 1)) == 0;
-            ok = ok && (base >= 1.0 + 1.0 / 1048576.0) && (base <= 16.0);
+            ok = ok && (base >= 1.0 + 1.0 / 1048576.0) && (base <= (tau > 128 ? 4.0 : 16.0));
             ok = ok && (sum >= 0.0) && (sum < __longlong_as_double(0x7FF0000000000000ll));
             ok = ok && n <= 4294967296ull && d <= n;
             if (ok) {
@@ -250,27 +250,30 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         if (k * 64u < npw) s_pay[k * 64u + lane] = pwd[k];                         // (zeros behind the payload)
     wave_lds_sync();
     if (cwid != 8) {
-        // token i of the round sits at bit i * cwid of the round's words; each is widened to the byte
-        // form (sign in bit 7, code-1 below) through shared memory
+        // token i of the round sits at bit i * cwid of the round's words; narrow ones are widened to the
+        // byte form (sign in bit 7, code-1 below) through shared memory
         const u32* cwords = reinterpret_cast<const u32*>(codes_round);
         uint8_t* s_codb = reinterpret_cast<uint8_t*>(s_cod + kCodeWords);
         const u32 ncw = (n * cwid + 31u) >> 5;
         for (u32 i = lane; i < ncw + 1u; i += 64) s_cod[i] = (i < ncw) ? cwords[i] : 0u;
         wave_lds_sync();
-        const u32 tmask = (1u << cwid) - 1u, cmask = tmask >> 1;
+        if (cwid < 8) {
+            const u32 tmask = (1u << cwid) - 1u, cmask = tmask >> 1;
 #pragma unroll 1
-        for (u32 i = lane; i < kSub; i += 64) {
-            u32 byte = 0;
-            if (i < n) {
-                const u32 pos = i * cwid, wa = pos >> 5;
-                const u32 tok = __builtin_amdgcn_alignbit(s_cod[wa + 1u], s_cod[wa], pos & 31u) & tmask;
-                byte = ((tok >> (cwid - 1u)) << 7) | (tok & cmask);
+            for (u32 i = lane; i < kSub; i += 64) {
+                u32 byte = 0;
+                if (i < n) {
+                    const u32 pos = i * cwid, wa = pos >> 5;
+                    const u32 tok = __builtin_amdgcn_alignbit(s_cod[wa + 1u], s_cod[wa], pos & 31u) & tmask;
+                    byte = ((tok >> (cwid - 1u)) << 7) | (tok & cmask);
+                }
+                s_codb[i] = (uint8_t)byte;
             }
-            s_codb[i] = (uint8_t)byte;
+            wave_lds_sync();
+            const uint4 q = reinterpret_cast<const uint4*>(s_codb)[lane];
+            cw[0] = q.x; cw[1] = q.y; cw[2] = q.z; cw[3] = q.w;
         }
-        wave_lds_sync();
-        const uint4 q = reinterpret_cast<const uint4*>(s_codb)[lane];
-        cw[0] = q.x; cw[1] = q.y; cw[2] = q.z; cw[3] = q.w;
+        // (nine-bit tokens stay where they are until the values are looked up)
     }
 
     // flags -> lengths: 8 flags at a time out of a 64-bit window of the lane's flag bits
@@ -325,14 +328,17 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
     for (u32 k = 0; k < kLaneKeys; ++k) kp[k] = (u32)kbase + kp[k];
     // values: the code byte (sign in bit 7) indexes a table of signed values; a code >= tau shows as a
     // carry into bit 7 of (code-1) + (128 - tau), tested four bytes at a time
-    const u32 over = (128u - tau) * 0x01010101u;
-    u32 badbits = 0;
-#pragma unroll
-    for (u32 j = 0; j < 4; ++j) badbits |= ((cw[j] & 0x7F7F7F7Fu) + over) & 0x80808080u;
-    const bool badcode = badbits != 0;                      // (bytes beyond n are 0: code 1, never beyond tau)
+    bool badcode = false;
     u32 vb[kLaneKeys];
+    if (cwid <= 8) {
+        const u32 over = (128u - tau) * 0x01010101u;
+        u32 badbits = 0;
 #pragma unroll
-    for (u32 k = 0; k < kLaneKeys; ++k) vb[k] = s_V[(cw[k >> 2] >> (8u * (k & 3u))) & 0xFFu];
+        for (u32 j = 0; j < 4; ++j) badbits |= ((cw[j] & 0x7F7F7F7Fu) + over) & 0x80808080u;
+        badcode = badbits != 0;                             // (bytes beyond n are 0: code 1, never beyond tau)
+#pragma unroll
+        for (u32 k = 0; k < kLaneKeys; ++k) vb[k] = s_V[(cw[k >> 2] >> (8u * (k & 3u))) & 0xFFu];
+    }
     // Lane-major -> row-major through shared memory (row q, lane: pair 64 * q + lane), so that stores to
     // the output arrays are coalesced and updates of the dense arrays touch neighbouring addresses in one
     // instruction.  A lane's 16 words sit 20 words apart (word i at i + 4 * (i / 16)), which spreads the
@@ -355,12 +361,37 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         }
     }
     wave_lds_sync();
+    // nine-bit tokens (tau in 129..256) are taken row-wise straight from the round's token words: token i
+    // at bit 9 i; code-1 in the low eight bits indexes the 256 magnitudes, bit 8 is the sign
+    auto wide_value = [&](u32 i) -> u32 {
+        const u32 pos = i * 9u, wa = pos >> 5;
+        u32 tok = __builtin_amdgcn_alignbit(s_cod[wa + 1u], s_cod[wa], pos & 31u) & 0x1FFu;
+        if (!FULL && i >= n) tok = 0;
+        badcode |= (tok & 0xFFu) >= tau;
+        return s_V[tok & 0xFFu] | ((tok >> 8) << 31);
+    };
+    if (MODE == kStore && cwid > 8) {
+        // (a loop that stays a loop: the common case keeps its registers)
+#pragma unroll 1
+        for (u32 q = 0; q < kLaneKeys; ++q) {
+            const u32 i = q * 64u + lane;
+            const u32 x = wide_value(i);
+            if (FULL || i < n) values_dst[i] = __uint_as_float(x);
+        }
+        pbit += roundbits;
+        return !(__any(ovf) || __any(badcode));
+    }
+    if (cwid <= 8) {
 #pragma unroll
-    for (u32 j = 0; j < 4; ++j) t4[j] = make_uint4(vb[4 * j], vb[4 * j + 1], vb[4 * j + 2], vb[4 * j + 3]);
-    wave_lds_sync();
+        for (u32 j = 0; j < 4; ++j) t4[j] = make_uint4(vb[4 * j], vb[4 * j + 1], vb[4 * j + 2], vb[4 * j + 3]);
+        wave_lds_sync();
 #pragma unroll
-    for (u32 q = 0; q < kLaneKeys; ++q) vr[q] = s_pay[rowpos + 80u * q];
-    wave_lds_sync();
+        for (u32 q = 0; q < kLaneKeys; ++q) vr[q] = s_pay[rowpos + 80u * q];
+        wave_lds_sync();
+    } else if (MODE != kStore) {
+#pragma unroll
+        for (u32 q = 0; q < kLaneKeys; ++q) vr[q] = wide_value(q * 64u + lane);
+    }
     if (MODE == kStore) {
 #pragma unroll
         for (u32 q = 0; q < kLaneKeys; ++q) {
@@ -441,11 +472,15 @@ k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u
         const u32 nsub = (cnt + kSub - 1) / kSub;
         if (seg != cur_seg) {
             wave_lds_sync();
-            const u32 m0 = ds->V[lane], m1 = ds->V[lane + 64];      // magnitudes; the upper half of the table: negative
+            // tau <= 128: indexed by the code byte, magnitudes below, the same with the sign set above;
+            // beyond that: the 256 magnitudes, the sign is added from the token's top bit
+            const bool wide = tau > 128u;
+            const u32 m0 = ds->V[lane], m1 = ds->V[lane + 64];
+            const u32 m2 = ds->V[lane + (wide ? 128u : 0u)], m3 = ds->V[lane + (wide ? 192u : 64u)];
             s_V[lane] = m0;
             s_V[lane + 64] = m1;
-            s_V[lane + 128] = m0 | 0x80000000u;
-            s_V[lane + 192] = m1 | 0x80000000u;
+            s_V[lane + 128] = wide ? m2 : m2 | 0x80000000u;
+            s_V[lane + 192] = wide ? m3 : m3 | 0x80000000u;
             cur_seg = seg;
             wave_lds_sync();
         }

@@ -24,6 +24,7 @@ constexpr u32 kMagic = 0x44475346u;           // "FSGD"
 constexpr u32 kVersion = 1;
 constexpr u32 kBins = 16;                     // exponent bins of the exact abs-sum (16 exponents each)
 constexpr u32 kMaxKB = 4096;
+constexpr u32 kMaxTau = 256;                  // Section 3.2 recommends 128 (a token of one byte); above it a token takes 9 bits
 constexpr u32 kChunkTarget = 4096;            // chunks a call's elements are cut into (one per wave of the value pass)
 constexpr u32 kMaxSegChunks = kChunkTarget;   // no segment has more chunks than this
 constexpr u32 kMaxChunkRows = 16376;          // rows of a chunk: a quarter row's index inside its chunk fits 16 bits
@@ -52,8 +53,13 @@ struct SegState {
     u64 item_begin;     // first work item (key block) of the segment
     u64 unit_begin;     // first work unit (kWaves key blocks of one segment) of the segment
     u64 pad;
-    u32 B[128];         // B[c-1] = bit pattern of the boundary of code c
+    u32 B[kMaxTau];     // B[c-1] = bit pattern of the boundary of code c
 };
+
+// A survivor's code in the scratch array between the value pass and the key encoder: code-1 with the sign
+// on top, in a byte while every tau of the call is at most 128, in 16 bits otherwise.
+template <bool WIDE> struct ScratchCode { typedef uint8_t type; };
+template <> struct ScratchCode<true> { typedef uint16_t type; };
 
 // Per key block (work item), filled by k_measure_keys, consumed by k_pack_keys.
 //   span8: 8-byte words the item adds to the output: its two planes and, for the first item of a
@@ -174,7 +180,7 @@ __device__ __forceinline__ u32 f64_to_f32_bits(double t, bool round_up) {
 }
 
 // P[c] = fl64(P[c-1] * b), t_c = fl64(sum / P[c]): the real boundary sum / b^c of Eq. 3 in binary64.
-// One thread walks the chain into `P` (129 doubles, shared memory); callers then divide in parallel.
+// One thread walks the chain into `P` (kMaxTau + 1 doubles, shared memory); callers then divide in parallel.
 __device__ __forceinline__ void power_chain(double base, u32 tau, double* P) {
     double p = 1.0;
     P[0] = 1.0;
@@ -224,7 +230,7 @@ __device__ __forceinline__ u32 code_width(u32 tau) { return 1u + (32u - (u32)__c
 // Bytes of the value plane: d tokens of `width` bits, zero-padded to 64-bit words.
 __device__ __forceinline__ u64 value_plane_bytes(u64 d, u32 width) { return 8ull * ((d * width + 63ull) >> 6); }
 constexpr int kBufferWord3 = 0x00020000;   // fourth word of a gfx9 raw buffer descriptor: 32-bit data format
-constexpr u32 kCodeWords = 32u * 8u;   // 32-bit words of 1024 tokens of at most 8 bits
+constexpr u32 kCodeWords = 32u * 8u;   // 32-bit words of 1024 tokens of at most 8 bits (nine-bit tokens take 288 of the 512)
 
 // Level lengths of Algorithm 2's length flag for a block with maximal length M and l flag bits:
 // level i (1..2^l) holds ceil(i*M / 2^l) bits; a delta of `need` significant bits takes the

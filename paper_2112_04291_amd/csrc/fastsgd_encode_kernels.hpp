@@ -233,7 +233,7 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
          u32 n_slots, Ctrl* ctrl) {
     __shared__ u64 s_tot[kBinWords];
     __shared__ unsigned long long s_dig[kDigits];
-    __shared__ double s_P[129];
+    __shared__ double s_P[kMaxTau + 1];
     __shared__ double s_sum;
     __shared__ u32 s_bad;
     const u32 seg = blockIdx.x, t = threadIdx.x;
@@ -357,7 +357,7 @@ constexpr u32 kRound = 64 * kGather;     // survivors per round of a flush
 constexpr u32 kMaxRounds = kStage / kRound;
 static_assert((kStage & (kStage - 1)) == 0 && kStage % kRound == 0 && kStage >= 2 * kRow + kRound,
               "stage: a power of two, whole rounds, a forced flush sends at least one");
-static_assert(512 + 8 * kStage + 2 * kRing <= 10240, "shared memory for sixteen waves per compute unit");
+static_assert(4 * kMaxTau + 8 * kStage + 2 * kRing <= 10240, "shared memory for sixteen waves per compute unit");
 
 // |v| >= threshold as a float compare with the |x| source modifier: for non-negative finite floats
 // (denormals are preserved in this build) it orders exactly like the unsigned compare of the bit
@@ -399,12 +399,17 @@ __device__ __forceinline__ Chunk chunk_geom(const SegInfo* __restrict__ segs, u3
     return c;
 }
 
+// WIDE: some segment of the call has tau > 128; then every survivor's scratch code takes 16 bits (sign
+// in bit 15) instead of 8 (sign in bit 7), and the boundary table has up to 256 entries.
+template <bool WIDE>
 __global__ void __launch_bounds__(kValWaves * kWave) __attribute__((amdgpu_waves_per_eu(4, 8)))
 k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                 const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
                 u32 n_chunks, u32 R, const uint16_t* __restrict__ rowmax, u32* __restrict__ ccount,
-                u32* __restrict__ skeys, uint8_t* __restrict__ scodes) {
-    __shared__ u32 s_Ball[kValWaves][128];
+                u32* __restrict__ skeys, void* __restrict__ scodes_any) {
+    typedef typename ScratchCode<WIDE>::type CodeT;
+    CodeT* __restrict__ scodes = static_cast<CodeT*>(scodes_any);
+    __shared__ u32 s_Ball[kValWaves][WIDE ? kMaxTau : 128];
     __shared__ u32 s_valall[kValWaves][kStage];
     __shared__ u32 s_idxall[kValWaves][kStage];
     __shared__ uint16_t s_ringall[kValWaves][kRing];        // quarter rows still to be read, in ascending order
@@ -419,8 +424,8 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
     const Chunk ck = chunk_geom(segs, n_segments, chunk, R);
     const u32 thr = uniform(states[ck.seg].thr_bits);
     const u32 tau = segs[ck.seg].tau;
-    s_B[lane] = states[ck.seg].B[lane];
-    s_B[lane + 64] = states[ck.seg].B[lane + 64];
+#pragma unroll
+    for (u32 k = 0; k < (WIDE ? kMaxTau : 128u) / 64u; ++k) s_B[lane + 64u * k] = states[ck.seg].B[lane + 64u * k];
     const float thr_f = __uint_as_float(thr);
     const u32* ckeys = keys + ck.e0;
     const bool implicit = keys == nullptr;                 // dense gradient: the key is the index in the segment
@@ -470,7 +475,7 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                             const u32 mid = (lo + hi) >> 1;
                             if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
                         }
-                        scodes[slot + j] = (uint8_t)(((vb >> 31) << 7) | (lo - 1));
+                        scodes[slot + j] = (CodeT)(((vb >> 31) << (WIDE ? 15 : 7)) | (lo - 1));
                         skeys[slot + j] = pkey[r][k];
                     }
                     __builtin_amdgcn_sched_barrier(0);        // one search at a time: keeps registers low
@@ -1029,12 +1034,15 @@ __device__ __forceinline__ u64 item_offset8(const u64* s_G, const BlockInfo* __r
     return s_G[g] + wave_sum64(acc);
 }
 
+template <bool WIDE>
 __global__ void __launch_bounds__(kThreads)
 k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
             u32 R, const u32* __restrict__ ccount, const u32* __restrict__ skeys,
-            const uint8_t* __restrict__ scodes, const BlockInfo* __restrict__ binfo,
+            const void* __restrict__ scodes_any, const BlockInfo* __restrict__ binfo,
             const unsigned long long* __restrict__ gsum, u32 g_shift, uint8_t* __restrict__ out, u64 out_capacity,
             u64* out_offsets, u32 single, u32* out_status, const Ctrl* ctrl) {
+    typedef typename ScratchCode<WIDE>::type CodeT;
+    const CodeT* __restrict__ scodes = static_cast<const CodeT*>(scodes_any);
     __shared__ u64 s_G[kMaxGroups + 1];
     __shared__ u64 s_scan64[kWaves + 1];
     __shared__ __attribute__((aligned(16))) u32 s_payall[kWaves][kSub + 4];
@@ -1136,7 +1144,7 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
         const u32 stride = R * kRow;
         const u64 seg_slot0 = chunk_slot0(info, ku.seg, 0, R);
         const u32* seg_keys = skeys + seg_slot0;
-        const uint8_t* seg_codes = scodes + seg_slot0;
+        const CodeT* seg_codes = scodes + seg_slot0;
         // level and length by significant bits of the delta: lut[need] = (level - 1) | length << 8
         if (lane <= 32) {
             const u32 level = level_of(lane, l, magic);
@@ -1160,22 +1168,23 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
 #pragma unroll
                 for (u32 q = 0; q < kKeyRows; ++q) {
                     const u32 i = q * 64u + lane;
-                    if (i < n) vdst[sub * kSub + i] = (uint8_t)code[q];
+                    const u32 byte = WIDE ? ((code[q] >> 8) & 0x80u) | (code[q] & 0x7Fu) : code[q];
+                    if (i < n) vdst[sub * kSub + i] = (uint8_t)byte;
                 }
             } else {
                 // tokens of cwid bits (sign on top of code-1), token i of the round at bit i * cwid:
                 // assembled in the (still unused) payload window, stored as whole words
-                uint8_t* s_b = reinterpret_cast<uint8_t*>(s_pay);        // the round's code bytes
-                u32* s_t = s_pay + kSub / 4;                             // the token words
+                CodeT* s_c = reinterpret_cast<CodeT*>(s_pay);            // the round's scratch codes
+                u32* s_t = s_pay + kSub * sizeof(CodeT) / 4;             // the token words
                 const u32 nw = (n * cwid + 31u) >> 5;
 #pragma unroll
-                for (u32 q = 0; q < kKeyRows; ++q) s_b[q * 64u + lane] = (uint8_t)code[q];
+                for (u32 q = 0; q < kKeyRows; ++q) s_c[q * 64u + lane] = (CodeT)code[q];
                 for (u32 i = lane; i < nw + 1u; i += 64) s_t[i] = 0;
                 wave_lds_sync();
 #pragma unroll 1
                 for (u32 i = lane; i < n; i += 64) {
-                    const u32 b = s_b[i];
-                    const u32 tok = ((b >> 7) << (cwid - 1u)) | (b & 0x7Fu);
+                    const u32 b = s_c[i];
+                    const u32 tok = ((b >> (WIDE ? 15 : 7)) << (cwid - 1u)) | (b & (WIDE ? 0xFFu : 0x7Fu));
                     const u32 bit = i * cwid;
                     const u64 pv = (u64)tok << (bit & 31u);
                     atomicOr(&s_t[bit >> 5], (u32)pv);

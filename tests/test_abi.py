@@ -71,5 +71,6 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.fastsgd_decompress(None, 0, None, None, 0, None, None, None, 0, None) == B.ERR_INVALID_ARG
     assert L.fastsgd_decompress_accumulate(None, 0, None, 1, None, 0, None, None, None, 0, None) == B.ERR_INVALID_ARG
     assert L.fastsgd_decompress_adam(None, 0, None, None, None, 0, None, None, None, None, 0, None) == B.ERR_INVALID_ARG
-    assert B.compressed_size(100, B.params(1.1, 129)) == 0 and B.compressed_size(100, B.params(0.9)) == 0
+    assert B.compressed_size(100, B.params(1.1, 257)) == 0 and B.compressed_size(100, B.params(0.9)) == 0
+    assert B.compressed_size(100, B.params(4.5, 129)) == 0 and B.compressed_size(100, B.params(4.0, 129)) > 0
     assert B.compressed_size(1 << 33, p) == 0

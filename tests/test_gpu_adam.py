@@ -29,11 +29,11 @@ def hip_adam(st, theta, m, v, eta, b1=0.9, b2=0.999, eps=1e-8):
     return rc, int(status[0]), int(count[0]), t.cpu().numpy(), mm.cpu().numpy(), vv.cpu().numpy()
 
 
-@pytest.mark.parametrize("dim,nnz,keep,seed", [(50_000, 8_000, 0.5, 1), (3_000_000, 600_000, 0.3, 2),
-                                               (4_000, 4_000, 1.0, 3)])
-def test_adam_matches_oracle(dim, nnz, keep, seed):
+@pytest.mark.parametrize("dim,nnz,keep,seed,tau", [(50_000, 8_000, 0.5, 1, 128), (3_000_000, 600_000, 0.3, 2, 128),
+                                                   (4_000, 4_000, 1.0, 3, 128), (300_000, 70_000, 0.6, 4, 200)])
+def test_adam_matches_oracle(dim, nnz, keep, seed, tau):
     from paper_2112_04291_amd import binding as B
-    st, k, g = one_stream(dim, nnz, keep, seed)
+    st, k, g = one_stream(dim, nnz, keep, seed, tau)
     rng = np.random.default_rng(seed)
     theta0 = rng.standard_normal(dim).astype(np.float32)
     m0 = (rng.standard_normal(dim) * 1e-3).astype(np.float32)

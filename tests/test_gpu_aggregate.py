@@ -55,14 +55,14 @@ def test_aggregate_errors_match_oracle():
     assert rc == B.OK and status == B.ERR_CORRUPT_STREAM and cnt == 0
 
 
-def test_aggregate_of_streams_with_narrow_tokens():
+def test_aggregate_of_streams_with_narrow_and_nine_bit_tokens():
     from paper_2112_04291_amd import binding as B
     from paper_2112_04291_amd import workloads as W
     rng = np.random.default_rng(8)
     dim, blobs, offs = 300_000, [], [0]
-    for tau in (16, 128, 5):
+    for tau in (16, 128, 5, 200, 256):
         keys = np.sort(rng.choice(dim, 60_000, replace=False)).astype(np.uint32)
-        vals = rng.laplace(0.0, 1e-3, keys.size).astype(np.float32)
+        vals = (rng.laplace(0.0, 1e-3, keys.size) * np.exp(rng.uniform(-8, 0, keys.size))).astype(np.float32)
         vals[::5000] *= np.float32(1e3)
         rc, st = ref.compress(keys, vals, ref.params(W.solve_base(vals, 0.4, tau), tau, 2, 512))
         assert rc == ref.OK

@@ -391,6 +391,86 @@ def test_narrow_value_tokens(tau, n, kb):
     assert int(st[40:48].view("<u8")[0]) >= 1
 
 
+def _wide_range_values(rng, n):
+    """Magnitudes over five orders of magnitude, so that codes far beyond 128 are in use."""
+    return (rng.laplace(0.0, 1e-2, n) * np.exp(rng.uniform(-12.0, 0.0, n))).astype(np.float32)
+
+
+@pytest.mark.parametrize("tau", [129, 200, 256])
+@pytest.mark.parametrize("n,kb", [(700, 256), (150_001, 1024), (400_003, 4096)])
+def test_thresholds_above_128_take_nine_bit_tokens(tau, n, kb):
+    # tau in 129..256 (Section 3.2: ceil(log2 tau) bits for the code, one for the sign): several blocks,
+    # several rounds of 1024 per block, ragged tails
+    from tests.streamparse import parse
+    rng = np.random.default_rng(tau * 1000 + kb)
+    keys = np.sort(rng.choice(4 * n, n, replace=False)).astype(np.uint32)
+    vals = _wide_range_values(rng, n)
+    st = check_round_trip(keys, vals, W.solve_base(vals, 0.7, tau), tau, 2, kb)
+    info = parse(st) if n < 1000 else None
+    assert int(st[6]) | int(st[7]) << 8 == tau
+    if info:
+        assert info["w"] == 9 and max(info["code"]) > 128
+
+
+def test_thresholds_above_128_without_key_array_and_with_the_papers_base():
+    # the paper's b = 1.1 keeps 10 % of a large dense gradient only with tau near 160
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(200)
+    n = 3_000_017
+    vals = (rng.standard_normal(n) * np.where(rng.random(n) < 0.1, 1e-3, 1e-5)).astype(np.float32)
+    rc_ref, want = ref.compress(np.arange(n, dtype=np.uint32), vals, ref.params(1.1, 162, 2, 1024))
+    assert rc_ref == ref.OK
+    d = int(want[40:48].view("<u8")[0])
+    assert 0.05 * n < d < 0.15 * n
+    rc, status, got, _ = G.hip_compress(None, vals, B.params(1.1, 162, 2, 1024))
+    assert rc == B.OK and status == 0
+    assert np.array_equal(got, want)
+    rc_ref, k_ref, v_ref = ref.decompress(want)
+    rc, status, k, v = G.hip_decompress(want, capacity=d)
+    assert rc == B.OK and status == 0
+    assert np.array_equal(k, k_ref) and np.array_equal(v.view(np.uint32), v_ref.view(np.uint32))
+
+
+def test_nine_bit_codes_beyond_tau_and_bad_limits_are_rejected():
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(9)
+    n = 5000
+    keys = np.arange(n, dtype=np.uint32) * 3
+    vals = _wide_range_values(rng, n)
+    rc, st = ref.compress(keys, vals, ref.params(W.solve_base(vals, 0.9, 200), 200, 2, 256))
+    assert rc == ref.OK
+    d = int(st[40:48].view("<u8")[0])
+    assert d > 3000
+
+    def both(s):
+        rc_ref, k_ref, v_ref = ref.decompress(s, capacity=d)
+        rc, status, k, v = G.hip_decompress(s, capacity=d)
+        assert rc == B.OK and status == rc_ref, (status, rc_ref)
+        return status
+
+    # token j sits at bit 9 j: set the code-1 field of a token in the first round, in a later round of the
+    # first block... to 200 (code 201 > tau) and to 199 (code 200 = tau: fine)
+    for j in (0, 7, 1023, 1024, 2500, d - 1):
+        for field, expect in ((200, B.ERR_CORRUPT_STREAM), (199, B.OK), (255, B.ERR_CORRUPT_STREAM)):
+            s = st.copy()
+            bit = 9 * j
+            word = int.from_bytes(s[64 + (bit >> 3):64 + (bit >> 3) + 4].tobytes(), "little")
+            word = (word & ~(0xFF << (bit & 7))) | (field << (bit & 7))
+            s[64 + (bit >> 3):64 + (bit >> 3) + 4] = np.frombuffer(word.to_bytes(4, "little"), np.uint8)
+            assert both(s) == expect, (j, field)
+    # header: tau = 257, tau = 0, and a base above 4 with tau above 128
+    for lo, hi in ((1, 1), (0, 0)):
+        s = st.copy(); s[6], s[7] = lo, hi
+        assert both(s) == B.ERR_CORRUPT_STREAM
+    s = st.copy(); s[16:24] = np.frombuffer(np.float64(4.5).tobytes(), np.uint8)
+    assert both(s) == B.ERR_CORRUPT_STREAM
+    # host side: the same limits
+    rc, status, got, _ = G.hip_compress(keys, vals, B.params(1.1, 257))
+    assert rc == B.ERR_INVALID_ARG
+    rc, status, got, _ = G.hip_compress(keys, vals, B.params(4.5, 129))
+    assert rc == B.ERR_INVALID_ARG
+
+
 def test_keys_that_span_the_whole_32_bit_range_and_streams_that_leave_it():
     """Deltas of 28 to 32 bits (a lane's running sum can wrap) up to the key 2^32 - 1, and corrupted
     copies whose keys would pass 2^32: same verdict as the oracle."""

@@ -145,6 +145,30 @@ def test_batch_whose_survivors_sit_at_the_segment_ends():
     assert kept == [min(s, 4 if s > 1000 else 2) for s in sizes]
 
 
+def test_batch_with_thresholds_on_both_sides_of_128():
+    # one segment with tau > 128 makes the whole call keep 16-bit scratch codes: the byte-token and the
+    # narrow-token segments next to it must come out unchanged
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(45)
+    taus = [128, 200, 5, 256, 64, 129, 100, 33]
+    sizes = [5000, 70_001, 4097, 30_000, 12289, 250_003, 1, 9000]
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.uint64)
+    keys = np.concatenate([np.arange(s, dtype=np.uint32) for s in sizes])
+    vals = np.concatenate([rng.laplace(0, 1e-3, s) * np.exp(rng.uniform(-10, 0, s)) for s in sizes]).astype(np.float32)
+    args = []
+    for i, (tau, s) in enumerate(zip(taus, sizes)):
+        seg = vals[int(offs[i]):int(offs[i + 1])]
+        args.append((W.solve_base(seg, 0.5, tau) if s > 20 else 1.3, tau, 1 + i % 4, 256 << (i % 4)))
+    blob = check_segmented(keys, vals, offs, [ref.params(*a) for a in args], [B.params(*a) for a in args])
+    # the tau <= 128 segments alone, in a call of their own (byte scratch codes): the same streams
+    rc_ref, blob_all, so = ref.compress_segmented(keys, vals, offs, [ref.params(*a) for a in args])
+    for i in (0, 2, 4):
+        a, b = int(offs[i]), int(offs[i + 1])
+        rc, status, st, _ = G.hip_compress(keys[a:b], vals[a:b], B.params(*args[i]))
+        assert rc == B.OK and status == 0
+        assert np.array_equal(st, blob_all[int(so[i]):int(so[i + 1])])
+
+
 def test_batch_of_the_largest_number_of_segments():
     # 65536 segments (the limit), most of them tiny, some empty, a few that span several key blocks
     torch, B, G = _gpu()

@@ -10,11 +10,13 @@ from oracle import ref
 from paper_2112_04291_amd import workloads as W
 
 
-def one_stream(dim, nnz, keep, seed):
+def one_stream(dim, nnz, keep, seed, tau=128):
     rng = np.random.default_rng(seed)
     keys = np.sort(rng.choice(dim, nnz, replace=False)).astype(np.uint32)
     vals = rng.laplace(0.0, 1e-3, nnz).astype(np.float32)
-    rc, st = ref.compress(keys, vals, ref.params(W.solve_base(vals, keep), 128, 2, 256))
+    if tau > 128:                          # a wider range of magnitudes, so that the codes past 128 are in use
+        vals = (vals * np.exp(rng.uniform(-10, 0, nnz))).astype(np.float32)
+    rc, st = ref.compress(keys, vals, ref.params(W.solve_base(vals, keep, tau), tau, 2, 256))
     assert rc == ref.OK
     rc, k, g = ref.decompress(st)
     assert rc == ref.OK and k.size > 0
