@@ -8,6 +8,7 @@ resident in HBM.  Prints ONE JSON line (metric = input GB/s of the round trip, 8
 """
 import argparse
 import json
+import math
 import os
 import re
 import sys
@@ -246,6 +247,38 @@ def main():
                                  accumulate_pairs_per_s=4.0 * pt["d"] / a_ms * 1e3, adam_pairs_per_s=pt["d"] / u_ms * 1e3))
             del four
         del dense, theta, m1, v1
+        # variants of the encoder: no key array (keys are the indices), and the paper's base b = 1.1 with
+        # the threshold that keeps about the same fraction (b^tau = base^128; above 128 a token is 9 bits)
+        cap_all = max(B.compressed_size(n, B.params(1.1, 256)), B.compressed_size(n, plist[0]))
+        vout = torch.empty(cap_all // 8 + 8, dtype=torch.int64, device="cuda")
+        for pt, wd in zip(points, widening):
+            def do_implicit(_):
+                assert B.compress(None, values, pt["p"], vout, obytes, status, ws, n=n, out_capacity=cap_all) == B.OK
+
+            i_ms = timed(do_implicit, pt, args.steps)
+            assert int(status[0]) == B.OK and int(obytes[0]) == pt["bytes"]
+            tau11 = min(256, max(1, int(math.ceil(128.0 * math.log(pt["p"].base) / math.log(1.1)))))
+            p11 = B.params(1.1, tau11)
+
+            def do_b11(_):
+                assert B.compress(keys, values, p11, vout, obytes, status, ws, n=n, out_capacity=cap_all) == B.OK
+
+            b_ms = timed(do_b11, pt, args.steps)
+            assert int(status[0]) == B.OK
+            sb11 = int(obytes[0])
+            d11 = int(vout.view(torch.uint8)[40:48].cpu().numpy().view("<u8")[0])
+            k11 = torch.empty(max(d11, 1), dtype=torch.int32, device="cuda")
+            v11 = torch.empty(max(d11, 1), dtype=torch.float32, device="cuda")
+
+            def do_b11_dec(_):
+                assert B.decompress(vout, sb11, k11, v11, count, status, dws, capacity=d11) == B.OK
+
+            bd_ms = timed(do_b11_dec, pt, args.steps)
+            assert int(status[0]) == B.OK and int(count[0]) == d11
+            wd.update(no_key_array_compress_ms=i_ms, base_1p1=dict(tau=tau11, d=d11, stream_bytes=sb11,
+                                                                    compress_ms=b_ms, decompress_ms=bd_ms))
+            del k11, v11
+        del vout
 
     cpu = None
     if not args.no_cpu_baseline:

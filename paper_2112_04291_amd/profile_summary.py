@@ -30,6 +30,9 @@ def _short(name):
     name = name.split("(")[0].replace("void ", "").replace("fsgd::", "")
     if name in _DECODE_MODES:          # what the launch does with the pairs: store / add to a dense vector / Adam step
         return _DECODE_MODES[name]
+    if name.startswith(("k_encode_values<", "k_pack_keys<")):     # the instantiation for calls with a tau above 128
+        arg = name.split("<", 1)[1].rstrip(">").replace("(bool)", "").strip()
+        return name.split("<")[0] + (" (16-bit codes)" if arg in ("true", "1") else "")
     return name.split("<")[0] if name.startswith("k_") else name[:60]
 
 
