@@ -339,11 +339,11 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
 //   eight rows of 256 elements, each made of the next four quarter rows of the stream wherever they sit,
 //   so that every lane fetches something useful however few quarter rows are in play -> per row, keep
 //   test |v| >= threshold as four wave-wide masks -> survivors are staged in the wave's slice of shared
-//   memory in element order (mask popcounts + mbcnt) -> once more than kFlushLevel wait there, densely
-//   over the staged survivors only and in whole rounds of 256: code by binary search in the boundary
-//   table, key fetch -> code byte and key appended to the CHUNK'S OWN SLOT of the scratch arrays (the
-//   chunk's first element index + rank in the chunk).  The loads of the next batch are issued before
-//   that flush, so its round trip overlaps with them.
+//   memory in element order (mask popcounts + mbcnt) -> once a round of 256 waits there, densely over
+//   the staged survivors only and in whole rounds: key fetch, code by binary search in the boundary
+//   table -> code and key appended to the CHUNK'S OWN SLOT of the scratch arrays (the chunk's first
+//   element index + rank in the chunk).  The key fetches are issued right behind the loads of the next
+//   batch and used two rows later, so the two round trips overlap.
 // The chunk's survivor count goes to ccount[chunk].  Global ranks are never materialised: k_plan_segments
 // turns the (at most 4096) chunk counts of a segment into their scan and the key encoder gathers through
 // that scan.

@@ -303,11 +303,20 @@ def test_many_rounds_per_block_and_mixed_block_sizes():
 def test_random_shapes_and_parameters(seed):
     """Seeded sweep over sizes (ragged tails of every kind), survival fractions, key gap structures and
     codec parameters: stream bytes, keys and decoded values against the oracle."""
+    _random_case(seed, [1, 2, 7, 64, 100, 127, 128])
+
+
+@pytest.mark.parametrize("seed", range(100, 120))
+def test_random_shapes_and_parameters_with_thresholds_above_128(seed):
+    _random_case(seed, [129, 130, 160, 200, 255, 256])
+
+
+def _random_case(seed, taus):
     rng = np.random.default_rng(1000 + seed)
     n = int(rng.choice([0, 1, 2, 63, 64, 65, 1023, 1025, 5000, 65_537, 200_003, 300_000]))
     if seed % 3 == 0:
         n = int(rng.integers(1, 400_000))
-    tau = int(rng.choice([1, 2, 7, 64, 100, 127, 128]))
+    tau = int(rng.choice(taus))
     l = int(rng.integers(1, 6))
     kb = int(rng.choice([256, 512, 1024, 2048, 4096]))
     keep = float(rng.choice([1.0, 0.9, 0.5, 0.1, 0.02, 0.001]))
@@ -335,6 +344,8 @@ def test_random_shapes_and_parameters(seed):
         keys = np.cumsum(2 ** rng.integers(0, 12, n)).astype(np.uint64)               # powers of two
     assert n == 0 or keys[-1] < 2 ** 32
     b = W.solve_base(vals, keep, tau) if n and np.any(vals != 0) else 1.1
+    if tau > 128:
+        b = min(b, 4.0)
     check_round_trip(keys.astype(np.uint32), vals, b, tau, l, kb)
 
 
