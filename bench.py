@@ -124,16 +124,16 @@ def main():
     status = torch.zeros(2, dtype=torch.int32, device="cuda")
     del probe.out
 
-    # quarter rows (64 elements) whose bound reaches the threshold: what the value pass has to read.
-    # The bound is the largest |v| of the quarter as a bit pattern, upper 16 bits, rounded up.
+    # granules (32 elements, 128 bytes) whose bound reaches the threshold: what the value pass has to read.
+    # The bound is the largest |v| of the granule as a bit pattern, upper 16 bits, rounded up.
     rows = (n + 255) // 256
     pad = rows * 256 - n
     absbits = values.abs().view(torch.int32)
     if pad:
         absbits = torch.cat([absbits, torch.zeros(pad, dtype=torch.int32, device="cuda")])
-    qbound = ((absbits.view(rows * 4, 64).max(dim=1).values.to(torch.int64) + 0xFFFF) >> 16) << 16
+    qbound = ((absbits.view(rows * 8, 32).max(dim=1).values.to(torch.int64) + 0xFFFF) >> 16) << 16
     for pt in points:
-        pt["quarters_active"] = int((qbound >= threshold_bits(pt["sum"], pt["p"].base, pt["p"].tau)).sum())
+        pt["granules_active"] = int((qbound >= threshold_bits(pt["sum"], pt["p"].base, pt["p"].tau)).sum())
     del absbits, qbound
 
     def do_compress(pt):
@@ -185,11 +185,11 @@ def main():
         rc, kd = B.profile_decompress(pt["out"], pt["bytes"], pt["keys_out"], pt["vals_out"], count, status, dws,
                                       args.steps, capacity=pt["d"])
         assert rc == B.OK
-        d, sb, qa = pt["d"], pt["bytes"], pt["quarters_active"]
+        d, sb, qa = pt["d"], pt["bytes"], pt["granules_active"]
         # algorithmic bytes per launch: what each kernel's method has to move
         alg = {
-            "abs_sum": 4.0 * n + 8.0 * rows,                     # every value once; four 16-bit bounds per row out
-            "encode_values": 8.0 * rows + 256.0 * qa + 4.0 * d + 5.0 * d,    # bounds; quarter rows that can hold a
+            "abs_sum": 4.0 * n + 16.0 * rows,                    # every value once; eight 16-bit bounds per row out
+            "encode_values": 16.0 * rows + 128.0 * qa + 4.0 * d + 5.0 * d,   # bounds; granules that can hold a
                                                                  # survivor; keys of survivors; key + code byte to scratch
             "measure_keys": 4.0 * d,                             # surviving keys
             "pack_keys": 5.0 * d + (sb - 64),                    # surviving keys and code bytes in, stream out
@@ -201,7 +201,7 @@ def main():
             kern_bytes[k] = kern_bytes.get(k, 0.0) + v
         comp_alg = 8.0 * n + 18.0 * d + sb                       # two value passes + survivor traffic + stream
         detail.append(dict(keep=pt["keep"], base=pt["p"].base, d=d, stream_bytes=sb, ratio=8.0 * n / sb,
-                           bits_per_key=8.0 * (sb - 64 - d) / max(d, 1), quarter_rows_read=qa, quarter_rows=4 * rows,
+                           bits_per_key=8.0 * (sb - 64 - d) / max(d, 1), granules_read=qa, granules=8 * rows,
                            compress_ms=c_ms, decompress_ms=d_ms,
                            compress_input_GBps=8.0 * n / c_ms / 1e6, decompress_input_GBps=8.0 * n / d_ms / 1e6,
                            compress_elements_per_s=n / c_ms * 1e3,

@@ -48,7 +48,7 @@ static EncodePlan make_plan(u64 total_n, u32 n_segments, u32 min_kb) {
     pl.zero_end = o;                                               // a single-gradient call clears up to here
     pl.off_gbins = o; o += up((u64)n_segments * pl.n_slots * kBinWords * 8, 256);
     pl.zero_end_batch = o;                                         // a batch also clears the abs-sum records
-    pl.off_rowmax = o;   o += up(pl.max_rows * 8, 256);               // four 16-bit quarter-row bounds per row
+    pl.off_rowmax = o;   o += up((pl.max_rows + kTile / kRow) * 2 * kRowGranules, 256);   // a 16-bit bound per granule (+ a tile)
     pl.off_ccount = o;   o += up(pl.max_chunks * 4, 256);
     pl.off_binfo = o;    o += up(pl.max_items * sizeof(BlockInfo), 256);
     pl.off_seginfo = o;  o += up((u64)n_segments * sizeof(SegInfo), 256);

@@ -27,7 +27,10 @@ constexpr u32 kMaxKB = 4096;
 constexpr u32 kMaxTau = 256;                  // Section 3.2 recommends 128 (a token of one byte); above it a token takes 9 bits
 constexpr u32 kChunkTarget = 4096;            // chunks a call's elements are cut into (one per wave of the value pass)
 constexpr u32 kMaxSegChunks = kChunkTarget;   // no segment has more chunks than this
-constexpr u32 kMaxChunkRows = 16376;          // rows of a chunk: a quarter row's index inside its chunk fits 16 bits
+constexpr u32 kGranule = 32;                  // values that share one bound of the first pass: the unit the second pass fetches by
+constexpr u32 kGranLanes = kGranule / 4;      // lanes (a float4 each) that hold one granule of a row
+constexpr u32 kRowGranules = kRow / kGranule; // bounds per row
+constexpr u32 kMaxChunkRows = (65536 / kRowGranules - 1) / kValRows * kValRows;   // a granule's index inside its chunk fits 16 bits
 constexpr u32 kMaxGroups = 2048;              // groups of key blocks whose sizes are added up by atomics
 constexpr u32 kSub = 1024;                    // keys of a key block a wave handles at a time (16 rows of 64)
 constexpr u32 kLaneKeys = kSub / 64;          // ... 16 consecutive keys per lane

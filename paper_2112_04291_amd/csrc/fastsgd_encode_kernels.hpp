@@ -123,12 +123,15 @@ __device__ __forceinline__ void flush_bins(u64 (*bins)[kThreads], u64* rec, u32 
 }
 
 // Also stores, for each of the wave's four rows of the tile that exist (row index below row_end), the
-// largest |v| of each quarter row (64 values: the float4s of 16 neighbouring lanes): the upper 16 bits
-// of its bit pattern, rounded up, so that the stored bound is never below the true maximum.  The
-// second pass skips every quarter row whose bound is below the threshold.  rowmax points at the four
-// entries of the tile's first row; trow0 is that row's index.
+// largest |v| of each granule of the row (kGranule values: the float4s of kGranLanes neighbouring lanes):
+// the upper 16 bits of its bit pattern, rounded up, so that the stored bound is never below the true
+// maximum.  The second pass skips every granule whose bound is below the threshold.  rowmax points at
+// the bounds of the tile's first row; trow0 is that row's index.
+// With `stage` set the bounds of the wave's four rows (16 words) go there, in shared memory, instead of
+// to rowmax (the caller writes them out many tiles at a time).
 __device__ __forceinline__ void accumulate_tile(const u32 bits[4][4], u64 (*bins)[kThreads], u32& maxa,
-                                                uint16_t* __restrict__ rowmax, u64 trow0, u64 row_end) {
+                                                uint16_t* __restrict__ rowmax, u64 trow0, u64 row_end,
+                                                u32* stage = nullptr) {
     const u32 t = threadIdx.x;
 #pragma unroll
     for (u32 r = 0; r < 4; ++r) {
@@ -136,14 +139,25 @@ __device__ __forceinline__ void accumulate_tile(const u32 bits[4][4], u64 (*bins
 #pragma unroll
         for (u32 c = 1; c < 4; ++c) { const u32 a = bits[r][c] & 0x7FFFFFFFu; m = a > m ? a : m; }
         maxa = m > maxa ? m : maxa;
-        u32 y;                                              // maximum over the 16 lanes up to this one
+        u32 y;                                              // maximum over the kGranLanes lanes up to this one
         y = dpp_mov<kDppRowShr1>(0u, m); m = m > y ? m : y;
         y = dpp_mov<kDppRowShr2>(0u, m); m = m > y ? m : y;
         y = dpp_mov<kDppRowShr4>(0u, m); m = m > y ? m : y;
-        y = dpp_mov<kDppRowShr8>(0u, m); m = m > y ? m : y;
         const u32 wr = wave_id() * 4u + r;
-        if ((lane_id() & 15u) == 15u && trow0 + wr < row_end)
-            rowmax[wr * 4u + (lane_id() >> 4)] = (uint16_t)((m + 0xFFFFu) >> 16);   // m < 2^31: no overflow
+        if (kGranLanes == 16) {
+            y = dpp_mov<kDppRowShr8>(0u, m); m = m > y ? m : y;
+            if ((lane_id() & 15u) == 15u && trow0 + wr < row_end)
+                rowmax[wr * kRowGranules + (lane_id() >> 4)] = (uint16_t)((m + 0xFFFFu) >> 16);   // m < 2^31: no overflow
+        } else {
+            // lanes 7 and 15 of every 16 hold a bound each: lane 15 stores the pair as one word
+            const u32 b16 = (m + 0xFFFFu) >> 16;
+            y = dpp_mov<kDppRowShr8>(0u, b16);
+            if (stage) {
+                if ((lane_id() & 15u) == 15u) stage[r * (kRowGranules / 2u) + (lane_id() >> 4)] = y | (b16 << 16);
+            } else if ((lane_id() & 15u) == 15u && trow0 + wr < row_end) {
+                reinterpret_cast<u32*>(rowmax)[wr * (kRowGranules / 2u) + (lane_id() >> 4)] = y | (b16 << 16);
+            }
+        }
     }
 #pragma unroll
     for (u32 r = 0; r < 4; ++r)
@@ -159,12 +173,17 @@ __device__ __forceinline__ void accumulate_tile(const u32 bits[4][4], u64 (*bins
         }
 }
 
+constexpr u32 kWaveTileWords = 4 * kRowGranules / 2;   // 32-bit words of bounds a wave produces per tile (four rows)
+constexpr u32 kBoundStage = 16;                         // tiles whose bounds a workgroup collects before writing them
+static_assert(kWaves * kWaveTileWords * 4 == 256 && kBoundStage * 16 == kThreads, "one 16-byte part per thread when the bounds leave");
+
 template <bool SINGLE>
 __global__ void __launch_bounds__(kThreads)
 k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u32 n_segments, u64 n_tiles,
           u64* gbins, u32 n_slots, u64* zero_begin, u64 zero_words, SegInfo single_seg, SegInfo* seg_store,
           uint16_t* __restrict__ rowmax) {
     __shared__ u64 bins[kBins][kThreads];
+    __shared__ __attribute__((aligned(16))) u32 s_bounds[SINGLE ? kBoundStage : 1][kWaves * kWaveTileWords];
     const u32 t = threadIdx.x;
 #pragma unroll
     for (u32 b = 0; b < kBins; ++b) bins[b][t] = 0;
@@ -177,8 +196,26 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
     const u64 G = gridDim.x;
     const u64 per_wg = (n_tiles + G - 1) / G;
     if (SINGLE) {
+        // The bounds of the workgroup's tiles (256 bytes a tile) wait in shared memory and leave
+        // kBoundStage tiles at a time, in one store instruction: single words written between the loads
+        // of a streaming read cost far more than their bytes.  (Rows behind the last row of the array get
+        // bounds too, of zero; the bounds array has room for a whole last tile.)
         const TileGeom g0 = tile_geom(single_seg, 0);
         const u64 row_end = segment_rows(single_seg);
+        u64 it0 = 0;                                          // iteration of the first tile waiting
+        u32 waiting = 0;
+        auto write_bounds = [&]() {
+            __syncthreads();
+            const u32 piece = t >> 4, part = t & 15u;         // a tile's bounds: sixteen 16-byte parts
+            if (piece < waiting) {
+                const u64 tile = (it0 + piece) * G + blockIdx.x;
+                uint4* dst = reinterpret_cast<uint4*>(rowmax + tile * (kRowGranules * kTile / kRow));
+                dst[part] = reinterpret_cast<const uint4*>(s_bounds[piece])[part];
+            }
+            __syncthreads();
+            it0 += waiting;
+            waiting = 0;
+        };
         for (u64 it = 0; it < per_wg; ++it) {
             const u64 tile = it * G + blockIdx.x;             // neighbours in time are neighbours in memory
             if (tile >= n_tiles) break;
@@ -187,8 +224,10 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
             g.full = (g.tile0 >= g.lo) && (g.tile0 + kTile <= g.hi);
             u32 bits[4][4];
             load_tile(values, g, bits);
-            accumulate_tile(bits, bins, maxa, rowmax + tile * (4u * kTile / kRow), tile * (kTile / kRow), row_end);
+            accumulate_tile(bits, bins, maxa, rowmax, tile * (kTile / kRow), row_end, s_bounds[waiting] + wave_id() * kWaveTileWords);
+            if (++waiting == kBoundStage) write_bounds();
         }
+        if (waiting) write_bounds();
         flush_bins<true>(bins, gbins + blockIdx.x, n_slots, maxa);
     } else {
         u32 cur_seg = 0xFFFFFFFFu;
@@ -212,7 +251,7 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
             u32 bits[4][4];
             load_tile(values, g, bits);
             const u64 trow0 = (tile - info.tile_begin) * (kTile / kRow);
-            accumulate_tile(bits, bins, maxa, rowmax + 4ull * (info.row_begin + trow0), trow0, seg_rows);
+            accumulate_tile(bits, bins, maxa, rowmax + (u64)kRowGranules * (info.row_begin + trow0), trow0, seg_rows);
         }
         if (cur_seg != 0xFFFFFFFFu)
             flush_bins<false>(bins, gbins + (u64)cur_seg * n_slots * kBinWords + blockIdx.x % n_slots, n_slots, maxa);
@@ -333,11 +372,11 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
 // Second pass over the values (Algorithm 1 lines 4-10).  No wave depends on another.  The elements of
 // a call are cut into chunks of R rows (a row = 256 elements, a float4 per lane); every WAVE owns one
 // chunk:
-//   the bounds the first pass left behind, one per quarter row (64 elements, the share of 16 lanes),
-//   tell which quarter rows can hold a survivor at all (the early-stop test of Algorithm 1 line 5 applied
-//   to a whole quarter row); only those are read, and they are read as one ascending stream: a batch is
-//   eight rows of 256 elements, each made of the next four quarter rows of the stream wherever they sit,
-//   so that every lane fetches something useful however few quarter rows are in play -> per row, keep
+//   the bounds the first pass left behind, one per granule (32 elements = 128 bytes, the share of 8
+//   lanes), tell which granules can hold a survivor at all (the early-stop test of Algorithm 1 line 5
+//   applied to a whole granule); only those are read, and they are read as one ascending stream: a batch
+//   is eight rows of 256 elements, each made of the next eight granules of the stream wherever they sit,
+//   so that every lane fetches something useful however few granules are in play -> per row, keep
 //   test |v| >= threshold as four wave-wide masks -> survivors are staged in the wave's slice of shared
 //   memory in element order (mask popcounts + mbcnt) -> once a round of 256 waits there, densely over
 //   the staged survivors only and in whole rounds: key fetch, code by binary search in the boundary
@@ -348,11 +387,12 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
 // turns the (at most 4096) chunk counts of a segment into their scan and the key encoder gathers through
 // that scan.
 constexpr u32 kStage = 1024;             // staged survivors per wave (a ring)
-constexpr u32 kRing = 512;               // ring of quarter rows per wave: under a batch left over plus 64 rows of four
+constexpr u32 kRing = 512;               // ring of granules per wave: under a batch left over plus 256 from a top-up
 constexpr u32 kValWaves = 4;             // waves per workgroup of the value encoder (they never synchronise)
 constexpr u32 kGather = 4;               // key fetches a lane keeps in flight
-static_assert((kRing & (kRing - 1)) == 0 && kRing >= 4 * kValRows - 1 + 4 * 64, "ring: a short batch plus 64 rows");
-static_assert(kMaxChunkRows * 4 <= 65536 && kMaxChunkRows % kValRows == 0, "ring entries are 16 bits");
+static_assert((kRing & (kRing - 1)) == 0 && kRing >= kRowGranules * kValRows - 1 + 4 * 64, "ring: a short batch plus 256 granules");
+static_assert(kMaxChunkRows * kRowGranules <= 65536 && kMaxChunkRows % kValRows == 0 && kRowGranules % 4 == 0,
+              "ring entries are 16 bits; bounds come in groups of four");
 constexpr u32 kRound = 64 * kGather;     // survivors per round of a flush
 constexpr u32 kMaxRounds = kStage / kRound;
 static_assert((kStage & (kStage - 1)) == 0 && kStage % kRound == 0 && kStage >= 2 * kRow + kRound,
@@ -412,7 +452,7 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
     __shared__ u32 s_Ball[kValWaves][WIDE ? kMaxTau : 128];
     __shared__ u32 s_valall[kValWaves][kStage];
     __shared__ u32 s_idxall[kValWaves][kStage];
-    __shared__ uint16_t s_ringall[kValWaves][kRing];        // quarter rows still to be read, in ascending order
+    __shared__ uint16_t s_ringall[kValWaves][kRing];        // granules still to be read, in ascending order
     const u32 lane = lane_id();
     const u32 w = uniform(wave_id());
     u32* s_B = s_Ball[w];
@@ -431,7 +471,10 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
     const bool implicit = keys == nullptr;                 // dense gradient: the key is the index in the segment
     const u32 key0 = (u32)(ck.e0 - ck.lo);                 // (wraps for the up to three slots before the segment)
     const float* cvals = values + ck.e0;
-    const uint2* crmax = reinterpret_cast<const uint2*>(rowmax) + ck.row0;     // four quarter-row bounds per row, 16 bits each
+    // bounds in groups of four (16 bits each): kBoundWords such groups per row
+    constexpr u32 kBoundWords = kRowGranules / 4u;
+    const uint2* crmax = reinterpret_cast<const uint2*>(rowmax) + (u64)ck.row0 * kBoundWords;
+    const u32 nwords = ck.nrows * kBoundWords;
     u32 cbase = 0;                           // survivors of the chunk already in the scratch arrays
     u32 staged = 0;                          // survivors waiting in shared memory
 
@@ -498,14 +541,13 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
         }
     };
 
-    // The unit of the fetch is the quarter row (64 elements, 16 lanes): a batch is eight "virtual rows" of
-    // four quarter rows that can hold a survivor, taken in ascending order from wherever they sit, so
-    // that every lane fetches something useful however few quarters are in play.
-    // One virtual row: lane group g = lane / 16 fetches quarter `qidx` (index inside the chunk: row * 4 +
-    // quarter); `elem` is the chunk-relative element offset of the lane's first element.  Quarter rows
-    // cut by the segment's ends are fetched element by element; elements outside [lo, hi) become zero,
-    // which never survives.
-    auto load_quarters = [&](bool on, u32 elem, u32 (&row)[4]) {
+    // The unit of the fetch is the granule: a batch is eight "virtual rows" of kRowGranules granules that
+    // can hold a survivor, taken in ascending order from wherever they sit, so that every lane fetches
+    // something useful however few granules are in play.
+    // One virtual row: lanes kGranLanes g .. kGranLanes (g + 1) - 1 fetch the g-th of its granules; `elem` is
+    // the chunk-relative element offset of the lane's first element.  Granules cut by the segment's ends
+    // are fetched element by element; elements outside [lo, hi) become zero, which never survives.
+    auto load_granules = [&](bool on, u32 elem, u32 (&row)[4]) {
         const u64 e = ck.e0 + elem;
         const bool inside = e >= ck.lo && e + 4u <= ck.hi;
         uint4 q = make_uint4(0u, 0u, 0u, 0u);
@@ -538,56 +580,58 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
         staged += (u32)__popcll(m[0]) + (u32)__popcll(m[1]) + (u32)__popcll(m[2]) + (u32)__popcll(m[3]);
     };
 
-    // The quarter rows that can hold a survivor form one ascending stream over the chunk, kept in a ring
-    // in shared memory (entry = row * 4 + quarter, counted inside the chunk).  The ring is topped up 64
-    // rows at a time: lane j compares the four bounds of row scanned + j with the threshold (unsigned
-    // compare of bit patterns: the same order as the float compare, and nothing passes the keep-nothing
-    // threshold).  The bounds of the 64 rows after those are fetched meanwhile.
-    uint2 xnext = crmax[lane < ck.nrows ? lane : ck.nrows - 1u];
-    u32 scanned = 0;                          // rows whose quarters are in the ring or behind it
-    u32 head = 0, tail = 0;                   // quarters taken from / put into the ring since the start
+    // The granules (kGranule values, the share of kGranLanes lanes) that can hold a survivor form one
+    // ascending stream over the chunk, kept in a ring in shared memory (entry = index of the granule inside
+    // the chunk).  The ring is topped up 256 granules at a time: lane j compares four bounds, those of the
+    // granules 4 (scanned + j) .. + 3, with the threshold (unsigned compare of bit patterns: the same order
+    // as the float compare, and nothing passes the keep-nothing threshold).  The bounds of the 256 granules
+    // after those are fetched meanwhile.
+    uint2 xnext = crmax[lane < nwords ? lane : nwords - 1u];
+    u32 scanned = 0;                          // groups of four bounds whose granules are in the ring or behind it
+    u32 head = 0, tail = 0;                   // granules taken from / put into the ring since the start
     auto refill = [&]() {
         const uint2 x = xnext;
-        const u32 row = scanned + lane;
+        const u32 word = scanned + lane;
         scanned += 64u;
-        if (scanned < ck.nrows) {
-            const u32 rn = scanned + lane;
-            xnext = crmax[rn < ck.nrows ? rn : ck.nrows - 1u];
+        if (scanned < nwords) {
+            const u32 wn = scanned + lane;
+            xnext = crmax[wn < nwords ? wn : nwords - 1u];
         }
         u32 qb = ((x.x << 16) >= thr ? 1u : 0u) | ((x.x & 0xFFFF0000u) >= thr ? 2u : 0u) |
                  ((x.y << 16) >= thr ? 4u : 0u) | ((x.y & 0xFFFF0000u) >= thr ? 8u : 0u);
-        if (row >= ck.nrows) qb = 0;
+        if (word >= nwords) qb = 0;
         const u32 mine = (u32)__popc(qb);
         const u32 incl = wave_incl_scan(mine);
         u32 at = tail + incl - mine;
 #pragma unroll
         for (u32 q = 0; q < 4; ++q)
-            if ((qb >> q) & 1u) s_ring[(at++) & (kRing - 1u)] = (uint16_t)((row << 2) | q);
+            if ((qb >> q) & 1u) s_ring[(at++) & (kRing - 1u)] = (uint16_t)((word << 2) | q);
         tail += read_lane(incl, 63);
     };
-    // A batch is eight rows of 256 elements in flight, each put together from the next four quarters of
-    // the stream (lanes 16k .. 16k+15 take the k-th of them).
+    // A batch is eight rows of 256 elements in flight, each put together from the next kRowGranules
+    // granules of the stream (lanes kGranLanes k .. kGranLanes (k + 1) - 1 take the k-th of them).
+    constexpr u32 kBatch = kRowGranules * kValRows;
     auto take = [&](u32 (&elem)[kValRows], u32 (&on)[kValRows]) -> u32 {
-        if (tail - head < 4u * kValRows && scanned < ck.nrows) {
-            do refill(); while (tail - head < 4u * kValRows && scanned < ck.nrows);
+        if (tail - head < kBatch && scanned < nwords) {
+            do refill(); while (tail - head < kBatch && scanned < nwords);
             wave_lds_sync();
         }
         const u32 left = tail - head;
-        const u32 nq = left < 4u * kValRows ? left : 4u * kValRows;
+        const u32 nq = left < kBatch ? left : kBatch;
 #pragma unroll
         for (u32 slot = 0; slot < kValRows; ++slot) {
-            const u32 i = 4u * slot + (lane >> 4);
+            const u32 i = kRowGranules * slot + lane / kGranLanes;
             on[slot] = i < nq ? 1u : 0u;
             const u32 e = on[slot] ? s_ring[(head + i) & (kRing - 1u)] : 0u;
-            elem[slot] = e * 64u + (lane & 15u) * 4u;
+            elem[slot] = e * kGranule + (lane & (kGranLanes - 1u)) * 4u;
         }
         head += nq;
-        return (nq + 3u) >> 2;
+        return (nq + kRowGranules - 1u) / kRowGranules;
     };
     u32 bits[kValRows][4], elem[kValRows], on[kValRows];
     u32 nr = take(elem, on);
 #pragma unroll
-    for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_quarters(on[slot] != 0, elem[slot], bits[slot]);
+    for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_granules(on[slot] != 0, elem[slot], bits[slot]);
     while (nr) {
 #pragma unroll
         for (u32 pair = 0; pair < kValRows / 2; ++pair) {
@@ -598,7 +642,7 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                 nr = take(elem, on);
 #pragma unroll
                 for (u32 slot = 0; slot < kValRows; ++slot)
-                    if (slot < nr) load_quarters(on[slot] != 0, elem[slot], bits[slot]);
+                    if (slot < nr) load_granules(on[slot] != 0, elem[slot], bits[slot]);
             }
             flush_step(pair + 1 == kValRows / 2);
         }

@@ -218,9 +218,9 @@ def test_corrupt_streams_are_rejected_on_device():
     assert status == B.ERR_CORRUPT_STREAM
 
 
-def test_values_on_bucket_boundaries_and_quarter_row_bounds():
+def test_values_on_bucket_boundaries_and_granule_bounds():
     """Elements exactly on, one ulp below and one ulp above every boundary (exact powers of two by
-    construction), scattered so that many quarter rows hold a single borderline element: the row-skip
+    construction), scattered so that many granules (32 values, the unit the value pass skips by) hold a single borderline element: the row-skip
     bounds and the boundary table must agree with the oracle to the last bit."""
     from tests.test_oracle_values import boundary_gradient
     keys, vals, codes, kept = boundary_gradient(10)
@@ -247,10 +247,11 @@ def _spikes(n, pos, seed):
 
 
 @pytest.mark.parametrize("pattern", ["same_quarter_of_every_row", "every_17th_quarter", "ends_only", "one_row_in_300",
-                                     "quarter_edges", "dense_island_in_a_desert", "last_quarter_only"])
-def test_survivors_clustered_in_few_quarter_rows(pattern):
-    """Placements of the survivors chosen against the unit the value pass fetches by (64 elements): the
-    quarter rows it reads are few, far apart, unevenly spread over the rows, or all of them for a stretch;
+                                     "quarter_edges", "dense_island_in_a_desert", "last_quarter_only",
+                                     "same_eighth_of_every_row", "eighth_edges", "every_other_eighth"])
+def test_survivors_clustered_in_few_fetch_units(pattern):
+    """Placements of the survivors chosen against the units the value pass fetches by (32 and 64 elements): the
+    units it reads are few, far apart, unevenly spread over the rows, or all of them for a stretch;
     the array is ragged and several chunks long."""
     n = 1_500_003
     q = np.arange((n + 63) // 64, dtype=np.int64)
@@ -266,6 +267,15 @@ def test_survivors_clustered_in_few_quarter_rows(pattern):
         pos = np.concatenate([q * 64 + 63, q * 64])[:: 5]
     elif pattern == "dense_island_in_a_desert":
         pos = np.concatenate([np.arange(700_001, 760_007), [5], [n - 2]])
+    elif pattern == "same_eighth_of_every_row":
+        e = np.arange((n + 31) // 32, dtype=np.int64)
+        pos = (e[e % 8 == 5] * 32)[:, None] + np.array([0, 17, 31])
+    elif pattern == "eighth_edges":
+        e = np.arange((n + 31) // 32, dtype=np.int64)
+        pos = np.concatenate([e * 32 + 31, e * 32])[:: 7]
+    elif pattern == "every_other_eighth":
+        e = np.arange(0, (n + 31) // 32, 2, dtype=np.int64)
+        pos = e * 32 + (e * 5) % 32
     else:
         pos = np.arange(n - (n % 64), n)
     v, pos = _spikes(n, np.ravel(pos), 31)

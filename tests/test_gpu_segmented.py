@@ -123,7 +123,7 @@ def test_batch_with_mixed_token_widths():
 
 def test_batch_whose_survivors_sit_at_the_segment_ends():
     # segments of odd lengths (so that they start anywhere inside a row); the survivors are the first and
-    # the last elements of each segment and a lone one in the middle of the long ones: the quarter rows the
+    # the last elements of each segment and a lone one in the middle of the long ones: the units (32 values) the
     # value pass reads are the ones that segment boundaries cut
     torch, B, G = _gpu()
     rng = np.random.default_rng(77)
