@@ -169,6 +169,50 @@ def test_batch_with_thresholds_on_both_sides_of_128():
         assert np.array_equal(st, blob_all[int(so[i]):int(so[i + 1])])
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_batches(seed):
+    """Seeded sweep over batches: number and sizes of the segments (empty, tiny, ragged, several chunks long),
+    survival fractions, per-segment parameters on both sides of tau = 128, with and without a key array."""
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(7000 + seed)
+    nseg = int(rng.choice([1, 2, 3, 17, 80, 81, 200]))
+    kinds = rng.integers(0, 5, nseg)
+    sizes = np.where(kinds == 0, 0, np.where(kinds == 1, rng.integers(1, 70, nseg),
+                     np.where(kinds == 2, rng.integers(200, 5000, nseg), rng.integers(5000, 120_000, nseg))))
+    if seed % 4 == 0:
+        sizes[int(rng.integers(0, nseg))] = int(rng.integers(600_000, 1_500_000))
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.uint64)
+    n = int(offs[-1])
+    implicit = seed % 3 == 0
+    gaps = rng.integers(1, 40, n).astype(np.uint64)
+    keys = np.empty(n, np.uint32)
+    scales = 10.0 ** rng.uniform(-8, 2, nseg)
+    vals = np.empty(n, np.float32)
+    wide = seed % 2 == 1
+    args = []
+    for i in range(nseg):
+        a, b = int(offs[i]), int(offs[i + 1])
+        keys[a:b] = np.arange(b - a) if implicit else np.cumsum(gaps[a:b]) - 1
+        v = rng.laplace(0.0, scales[i], b - a) * np.exp(rng.uniform(-6, 0, b - a))
+        if b - a > 10 and rng.random() < 0.3:
+            v[rng.random(b - a) < 0.5] = 0.0
+        vals[a:b] = v.astype(np.float32)
+        tau = int(rng.choice([129, 160, 256, 128, 64, 5] if wide else [128, 128, 100, 64, 7, 1]))
+        keep = float(rng.choice([1.0, 0.5, 0.1, 0.01]))
+        seg = vals[a:b]
+        base = W.solve_base(seg, keep, tau) if b > a and np.any(seg != 0) else 1.1
+        args.append((min(base, 4.0) if tau > 128 else base, tau, int(rng.integers(1, 6)), int(rng.choice([256, 1024, 4096]))))
+    rp, hp = [ref.params(*a) for a in args], [B.params(*a) for a in args]
+    if implicit:
+        rc_ref, blob_ref, so_ref = ref.compress_segmented(keys, vals, offs, rp)
+        assert rc_ref == ref.OK
+        rc, status, blob, so = G.hip_compress_segmented(None, vals, offs, hp)
+        assert rc == B.OK and status == 0
+        assert np.array_equal(so, so_ref) and np.array_equal(blob, blob_ref)
+    else:
+        check_segmented(keys, vals, offs, rp, hp)
+
+
 def test_batch_of_the_largest_number_of_segments():
     # 65536 segments (the limit), most of them tiny, some empty, a few that span several key blocks
     torch, B, G = _gpu()
