@@ -194,3 +194,57 @@ def test_largest_gradient_with_a_hundred_million_survivors():
     assert rc_ref == ref.OK and k_ref.size == d
     assert np.array_equal(k_ref, k_out.cpu().numpy().view(np.uint32))
     assert np.array_equal(v_ref.view(np.uint32), v_out.cpu().numpy().view(np.uint32))
+
+
+def test_batch_of_three_largest_gradients_takes_more_than_4096_chunks():
+    """Three gradients of 2^32 - 1024 elements in one call (52 GB of values, no key array): a chunk of the
+    value pass may not be longer than 8184 rows, so this call is cut into 6150 chunks instead of the usual
+    4096 or fewer.  Every stream of the batch must be, byte for byte, what a call on that gradient alone
+    gives (2050 chunks of 8184 rows there against 4096 of 4096 rows here: the stream does not depend on the
+    cut), and that call is checked against the oracle's decoder and the threshold in the test above."""
+    torch, B, G = _gpu()
+    n, nseg = (1 << 32) - 1024, 3
+    ws_bytes = B.workspace_size(nseg * n, nseg, 256)
+    free, _ = torch.cuda.mem_get_info()
+    if free < 4 * nseg * n + ws_bytes + (8 << 30):
+        pytest.skip("not enough device memory for three of the largest gradients")
+    print(f"[fullsize] batch of {nseg} x {n} workspace={ws_bytes}", flush=True)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4096)
+    v = torch.empty(nseg * n, dtype=torch.float32, device="cuda")
+    step = 1 << 28
+    plist = []
+    for s in range(nseg):
+        seg = v[s * n:(s + 1) * n]
+        for lo in range(0, n, step):
+            seg[lo:lo + step].normal_(0.0, 1e-4 * (s + 1), generator=gen)
+        for i, pos in enumerate((0, 1, 255, n // 2 + s, n - 1025, n - 1)):
+            seg[pos] = (-1.0) ** i * (3.0 + i + s)
+        total = 0.0
+        for lo in range(0, n, step):
+            total += float(seg[lo:lo + step].abs().sum(dtype=torch.float64))
+        plist.append(B.params((total / (5.5e-4 * (s + 1))) ** (1.0 / 128.0), 128, 1 + s, 256 << s))
+    cap = 8 << 20
+    out = torch.empty(cap // 8, dtype=torch.int64, device="cuda")
+    ws = torch.empty(ws_bytes // 8 + 32, dtype=torch.int64, device="cuda")
+    so = torch.full((nseg + 1,), -1, dtype=torch.int64, device="cuda")
+    status = torch.full((2,), -1, dtype=torch.int32, device="cuda")
+    rc = B.compress_segmented(None, v, [s * n for s in range(nseg + 1)], plist, out, so, status, ws)
+    torch.cuda.synchronize()
+    assert rc == B.OK and int(status[0]) == 0
+    offs = [int(x) for x in so.cpu()]
+    blob = out.view(torch.uint8)[:offs[-1]].cpu().numpy().copy()
+    one = torch.empty(cap // 8, dtype=torch.int64, device="cuda")
+    nb = torch.full((2,), -1, dtype=torch.int64, device="cuda")
+    for s in range(nseg):
+        print(f"[fullsize] gradient {s} alone", flush=True)
+        rc = B.compress(None, v[s * n:(s + 1) * n], plist[s], one, nb, status, ws, n=n, out_capacity=cap)
+        torch.cuda.synchronize()
+        assert rc == B.OK and int(status[0]) == 0
+        alone = one.view(torch.uint8)[:int(nb[0])].cpu().numpy()
+        part = blob[offs[s]:offs[s + 1]]
+        d = int(part[40:48].view("<u8")[0])
+        assert 20 < d < 200_000 and int(part[32:40].view("<u8")[0]) == n
+        assert part.size == alone.size and np.array_equal(part, alone), f"gradient {s}: batch and single call differ"
+        rc_ref, k_ref, v_ref = ref.decompress(part)
+        assert rc_ref == ref.OK and k_ref.size == d and int(k_ref[0]) == 0 and int(k_ref[-1]) == n - 1
