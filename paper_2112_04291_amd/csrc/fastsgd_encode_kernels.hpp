@@ -982,6 +982,7 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
     __shared__ __attribute__((aligned(16))) uint8_t s_needall[kWaves][BIG ? kMaxKB : 16];   // bit lengths of a big block's deltas
     __shared__ u32 s_lutall[kWaves][33];
     __shared__ u32 s_coarseall[kWaves][64];
+    __shared__ u32 s_span[2][kWaves];                        // sizes of the unit's blocks, by parity of the round
     const u32 lane = lane_id(), w = uniform(wave_id());
     uint8_t* s_need = s_needall[w];
     u32* s_buf = s_bufall[w];
@@ -991,12 +992,17 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
     u32 coarse_seg = 0xFFFFFFFFu;                           // segment whose scan s_coarse samples
     const u64 d0 = states[0].d;
     const u32 nb0 = states[0].nb;
-    for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x) {
+    // The sizes of a unit's (up to) kWaves blocks are added to the group sums by one thread of the
+    // workgroup: an atomic per block would queue 64 deep on every sum (each takes a trip to the L2).
+    u32 round = 0;
+    for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x, ++round) {
         SegInfo info;
         const KeyUnit ku = key_unit(seg0, segs, states, n_segments, R, unit, d0, nb0, &info);
         const u32* P = ccount + ku.cb;                      // the segment's chunk scan
         const u32 blk = ku.blk0 + w;
-        if (blk >= (ku.nb ? ku.nb : 1u)) continue;
+        // the wave's block: its record, and the words it adds to the output (0: no block for this wave)
+        auto measure_block = [&]() -> u32 {
+        if (blk >= (ku.nb ? ku.nb : 1u)) return 0u;
         if (ku.seg != coarse_seg && ku.nb) { load_coarse(P, ku.nch, lane, s_coarse); coarse_seg = ku.seg; }
         const u64 item = ku.item_begin + blk;
         const u32 head8 = (u32)((kHeaderBytes + value_plane_bytes(ku.d, code_width(info.tau)) + 16ull * ku.nb) >> 3);   // first item of a segment
@@ -1004,9 +1010,8 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
             if (lane == 0) {
                 BlockInfo bi; bi.preKey = 0; bi.M = 0; bi.payload_bits = 0; bi.span8 = head8;
                 binfo[item] = bi;
-                atomicAdd(&gsum[item >> g_shift], (unsigned long long)head8);
             }
-            continue;
+            return head8;
         }
         const u32 first = uniform(blk * ku.KB);
         const u32 cnt = uniform((u32)((ku.d - first < ku.KB) ? ku.d - first : ku.KB));
@@ -1057,15 +1062,32 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
         }
         bits = wave_sum(bits);
         wave_lds_sync();
+        const u32 span8 = ((cnt * l + 63u) >> 6) + ((bits + 63u) >> 6) + (blk == 0 ? head8 : 0u);
         if (lane == 0) {
             BlockInfo bi;
-            bi.preKey = preKey; bi.M = M; bi.payload_bits = bits;
-            bi.span8 = ((cnt * l + 63u) >> 6) + ((bits + 63u) >> 6) + (blk == 0 ? head8 : 0u);
+            bi.preKey = preKey; bi.M = M; bi.payload_bits = bits; bi.span8 = span8;
             binfo[item] = bi;
-            atomicAdd(&gsum[item >> g_shift], (unsigned long long)bi.span8);
+        }
+        return span8;
+        };
+        const u32 span8 = measure_block();
+        if (lane == 0) s_span[round & 1u][w] = span8;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            // the unit's items are consecutive: they fall into one group of sums or two
+            const u64 item0 = ku.item_begin + ku.blk0, g0 = item0 >> g_shift;
+            unsigned long long a = 0, b = 0;
+#pragma unroll
+            for (u32 k = 0; k < kWaves; ++k) {
+                const u32 x = s_span[round & 1u][k];
+                if (((item0 + k) >> g_shift) == g0) a += x; else b += x;
+            }
+            if (a) atomicAdd(&gsum[g0], a);
+            if (b) atomicAdd(&gsum[g0 + 1], b);
         }
     }
 }
+
 
 // Offset (in 8-byte words) at which work item `item` starts adding to the output: the groups before
 // its group (s_G, scanned) plus the items before it inside the group.  All lanes of the wave call it
