@@ -26,7 +26,8 @@ def hip_accumulate(blob, offs, dense):
 
 
 @pytest.mark.parametrize("n_workers,dim,nnz,keep", [(1, 100_000, 20_000, 0.5), (3, 400_000, 150_000, 0.3),
-                                                    (8, 2_000_000, 300_000, 0.05), (2, 5_000, 5_000, 1.0)])
+                                                    (8, 2_000_000, 300_000, 0.05), (2, 5_000, 5_000, 1.0),
+                                                    (48, 500_000, 40_000, 0.2)])
 def test_aggregate_matches_oracle_bit_for_bit(n_workers, dim, nnz, keep):
     from paper_2112_04291_amd import binding as B
     blob, offs, pairs = worker_streams(n_workers, dim, nnz, keep, 300 + n_workers)
