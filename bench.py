@@ -57,6 +57,7 @@ def main():
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replays of the per-point timings")
     ap.add_argument("--cpu-sample", type=int, default=0, help="elements the oracle is timed on (0 = the whole workload)")
     ap.add_argument("--widening", action="store_true",
                     help="also time decode-and-aggregate (4 copies of each stream) and decode-and-update (Adam); "
@@ -173,12 +174,40 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters
 
+    # the same calls replayed from a HIP graph (a call is kernel launches only, so it can be captured):
+    # what the kernels take once the launch gaps between them are gone
+    def graph_timed(fn, pt, iters):
+        if args.no_graph:
+            return None
+        cur = torch.cuda.current_stream()
+        side = torch.cuda.Stream()
+        side.wait_stream(cur)
+        with torch.cuda.stream(side):
+            fn(pt)                                           # warm-up outside the capture
+        cur.wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(iters):
+                fn(pt)
+        graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
     detail = []
     kern_time = {}
     kern_bytes = {}
     for pt in points:
         c_ms = timed(do_compress, pt, args.steps)
         d_ms = timed(do_decompress, pt, args.steps)
+        cg_ms = graph_timed(do_compress, pt, args.steps)
+        dg_ms = graph_timed(do_decompress, pt, args.steps)
+        assert int(status[0]) == B.OK and int(count[0]) == pt["d"] and int(obytes[0]) == pt["bytes"]
         rc, kc = B.profile_compress(keys, values, pt["p"], pt["out"], obytes, status, ws, args.steps, n=n,
                                     out_capacity=pt["cap"])
         assert rc == B.OK
@@ -203,6 +232,9 @@ def main():
         detail.append(dict(keep=pt["keep"], base=pt["p"].base, d=d, stream_bytes=sb, ratio=8.0 * n / sb,
                            bits_per_key=8.0 * (sb - 64 - d) / max(d, 1), granules_read=qa, granules=8 * rows,
                            compress_ms=c_ms, decompress_ms=d_ms,
+                           compress_graph_ms=cg_ms, decompress_graph_ms=dg_ms,
+                           compress_graph_hbm_frac=None if cg_ms is None else comp_alg / cg_ms / 1e6 / HBM_PEAK_GBPS,
+                           decompress_graph_hbm_frac=None if dg_ms is None else (sb + 8.0 * d) / dg_ms / 1e6 / HBM_PEAK_GBPS,
                            compress_input_GBps=8.0 * n / c_ms / 1e6, decompress_input_GBps=8.0 * n / d_ms / 1e6,
                            compress_elements_per_s=n / c_ms * 1e3,
                            compress_hbm_frac=comp_alg / c_ms / 1e6 / HBM_PEAK_GBPS,
