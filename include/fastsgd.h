@@ -73,7 +73,8 @@ size_t fastsgd_compressed_size(uint64_t n, const fastsgd_params* p);
 
 /* Host-only, pure.  Bytes of device workspace fastsgd_compress (n_segments = 1) or
  * fastsgd_compress_segmented needs for total_n elements in n_segments gradients whose smallest
- * block_keys is min_block_keys.  Returns 0 on invalid arguments. */
+ * block_keys is min_block_keys (about 6 bytes per element: the scratch keys and codes of the
+ * survivors, whose number is not known beforehand).  Returns 0 on invalid arguments. */
 size_t fastsgd_workspace_size(uint64_t total_n, uint32_t n_segments, uint32_t min_block_keys);
 
 /* Host-only, pure.  Bytes of device workspace the decoders need for n_segments streams. */
