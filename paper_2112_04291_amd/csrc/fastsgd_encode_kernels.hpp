@@ -1230,13 +1230,27 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
 #pragma unroll
             for (u32 q = 0; q < kKeyRows; ++q) code[q] = (q * 64u + lane < n) ? seg_codes[ent[q]] : 0u;
             if (cwid == 8) {
-                // the survivors' code bytes go straight into the value plane
+                // the survivors' code bytes go into the value plane 16 to a lane (single bytes cost several
+                // times their share of a store): turned round in the (still unused) payload window
+                uint8_t* s_b = reinterpret_cast<uint8_t*>(s_pay);
 #pragma unroll
                 for (u32 q = 0; q < kKeyRows; ++q) {
-                    const u32 i = q * 64u + lane;
                     const u32 byte = WIDE ? ((code[q] >> 8) & 0x80u) | (code[q] & 0x7Fu) : code[q];
-                    if (i < n) vdst[sub * kSub + i] = (uint8_t)byte;
+                    s_b[q * 64u + lane] = (uint8_t)byte;
                 }
+                wave_lds_sync();
+                const uint4 c16 = reinterpret_cast<const uint4*>(s_pay)[lane];
+                uint8_t* vrow = vdst + sub * kSub + 16u * lane;          // (8-byte aligned: streams and blocks are)
+                if (16u * lane + 16u <= n) {
+                    reinterpret_cast<uint2*>(vrow)[0] = make_uint2(c16.x, c16.y);
+                    reinterpret_cast<uint2*>(vrow)[1] = make_uint2(c16.z, c16.w);
+                } else if (16u * lane < n) {                             // the round's last, partial sixteen
+                    const u32 cw4[4] = {c16.x, c16.y, c16.z, c16.w};
+#pragma unroll
+                    for (u32 k = 0; k < 16; ++k)
+                        if (16u * lane + k < n) vrow[k] = (uint8_t)(cw4[k >> 2] >> (8u * (k & 3u)));
+                }
+                wave_lds_sync();
             } else {
                 // tokens of cwid bits (sign on top of code-1), token i of the round at bit i * cwid:
                 // assembled in the (still unused) payload window, stored as whole words
