@@ -40,8 +40,12 @@ def trace(d, out, command):
     rows = _rows(d, "kernel_trace.csv")
     st = collections.defaultdict(list)
     meta = {}
-    for r in rows:
+    seen = set()
+    for r in sorted(rows, key=lambda r: int(r["Start_Timestamp"])):
         k = _short(r["Kernel_Name"])
+        if k.startswith("k_") and k not in seen:   # a kernel's first launch in the process can include loading its code
+            seen.add(k)
+            continue
         st[k].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
         meta[k] = (r.get("VGPR_Count", ""), r.get("LDS_Block_Size", ""), r.get("Grid_Size_X", r.get("Grid_Size", "")),
                    r.get("Workgroup_Size_X", r.get("Workgroup_Size", "")))
@@ -49,7 +53,8 @@ def trace(d, out, command):
     with open(out, "w") as f:
         f.write("# rocprofv3 kernel trace of the benchmark (config 4, 124M elements, four keep fractions)\n\n")
         f.write(f"Command: `{command}`\n\n")
-        f.write("Durations in microseconds, begin to end of each dispatch.\n\n")
+        f.write("Durations in microseconds, begin to end of each dispatch; the first launch of each of the library's "
+                "kernels in the process is left out (it can include loading the kernel's code).\n\n")
         f.write("| kernel | calls | avg us | min us | max us | % of GPU time | VGPRs | LDS bytes | grid | workgroup |\n")
         f.write("|---|---|---|---|---|---|---|---|---|---|\n")
         for k, v in sorted(st.items(), key=lambda kv: -sum(kv[1])):
