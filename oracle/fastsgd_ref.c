@@ -391,7 +391,10 @@ int fastsgd_ref_decompress(const uint8_t *stream, uint64_t stream_bytes,
             uint32_t level = get_bits(fl, (uint64_t)i * l, l) + 1;
             uint32_t len = level_len(level, M, l);
             if (pbit + len > payload_bits) return REF_ERR_CORRUPT_STREAM;
-            key += get_bits(pl, pbit, len);
+            uint32_t delta = get_bits(pl, pbit, len);
+            /* Eq. 4 is taken over distinct ascending keys: only the very first delta of a gradient can be 0 */
+            if (delta == 0 && first + i != 0) return REF_ERR_CORRUPT_STREAM;
+            key += delta;
             pbit += len;
             if (key > 0xFFFFFFFFull) return REF_ERR_CORRUPT_STREAM;
             keys_out[first + i] = (uint32_t)key;

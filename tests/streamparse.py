@@ -45,6 +45,7 @@ def parse(stream):
     assert _bits(plane, d * w, 8 * len(plane) - d * w) == 0, "value-plane padding must be zero"
     blocks_off = dir_off + 16 * nb
     keys, tokens, off_expect = [], [], 0
+    payload_at = []          # absolute bit position in the stream of every key's binary delta
     last = 0
     for blk in range(nb):
         off8, pre, M, pbits = struct.unpack_from("<IIII", s, dir_off + 16 * blk)
@@ -59,6 +60,7 @@ def parse(stream):
             level = _bits(fl, i * l, l) + 1
             ln = level_len(level, M, l)
             delta = _bits(pl, pos, ln)
+            payload_at.append(8 * (blocks_off + 8 * (off8 + fwords)) + pos)
             pos += ln
             key += delta
             maxd = max(maxd, delta)
@@ -72,7 +74,7 @@ def parse(stream):
         off_expect = off8 + fwords + pwords
     assert blocks_off + 8 * off_expect == total
     return dict(l=l, tau=tau, KB=KB, nb=nb, w=w, base=base, S=S, n=n, d=d, total=total,
-                codes=codes, code=code, negative=negative, keys=keys, tokens=tokens)
+                codes=codes, code=code, negative=negative, keys=keys, tokens=tokens, payload_at=payload_at)
 
 
 def exact_code(abs_v, S, base, limit=4096):
@@ -90,3 +92,14 @@ def exact_code(abs_v, S, base, limit=4096):
     hi = float(a * p / s) - 1.0                      # >= 0: how far past the boundary it passed
     lo = 1.0 - float(a * p / b / s) if c > 0 else 1.0  # > 0: how far short of the previous one
     return c, min(abs(hi), abs(lo))
+
+
+def with_zero_delta(stream, rank):
+    """A copy of `stream` (a uint8 array) in which the binary delta of key number `rank` is all zeros, so
+    that the key repeats its predecessor: a stream no encoder writes (Eq. 4 is taken over distinct keys)."""
+    info = parse(stream)
+    out = stream.copy()
+    pos, ln = info["payload_at"][rank], info["tokens"][rank][1]
+    for k in range(ln):
+        out[(pos + k) >> 3] &= ~(1 << ((pos + k) & 7)) & 0xFF
+    return out

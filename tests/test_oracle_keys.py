@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 from oracle import ref
-from tests.streamparse import bitlen, level_len, parse
+from tests.streamparse import bitlen, level_len, parse, with_zero_delta
 from tests.test_oracle_values import golden
 
 BIG = np.float32(1.0)   # with b = 1.1, tau = 128 every equal-magnitude value survives while n < ~2e5
@@ -118,6 +118,53 @@ def test_size_uniform_gaps_close_to_paper_model():
     assert info["total"] <= ref.compressed_size(d, ref.params(1.1, 128, l, 1024))
 
 
+# ----------------------------------------------------------------------------- the size bound
+def worst_case_bytes(n, tau, l, KB):
+    """The bound of the container description, term by term: header, n value tokens of 1 + ceil(log2 tau)
+    bits padded to 64-bit words, one 16-byte directory entry per block, and per block a flags plane of
+    KB*l bits and a payload plane of KB*32 bits, each padded to 64-bit words."""
+    w = 1 + (tau - 1).bit_length()
+    nb = -(-n // KB)
+    return 64 + 8 * (-(-(n * w) // 64)) + 16 * nb + nb * 8 * (-(-(KB * l) // 64) + -(-(KB * 32) // 64))
+
+
+@pytest.mark.parametrize("KB", [256, 1024, 4096])
+def test_size_bound_is_reached_by_a_block_of_longest_tokens(KB):
+    """One full block, every element kept, l = 1: the first delta is 2^31 (M = 32, levels of 16 and 32 bits),
+    every other delta is 2^16 and so takes the 32-bit level: every token costs l + 32 bits, which is the
+    worst case the bound is made of.  The stream the encoder writes must fill the bound to the byte."""
+    keys = (1 << 31) + (np.arange(KB, dtype=np.uint64) << 16)
+    p = ref.params(1.1, 128, 1, KB)
+    st, info = all_survive(keys, p)
+    assert info["d"] == KB and info["nb"] == 1
+    assert all(t[1] == 32 and t[3] == 32 for t in info["tokens"])
+    assert info["total"] == len(st) == ref.compressed_size(KB, p) == worst_case_bytes(KB, 128, 1, KB)
+    # one element more opens a second block: the bound grows by a whole worst-case block
+    assert ref.compressed_size(KB + 1, p) == worst_case_bytes(KB + 1, 128, 1, KB) > info["total"] + 16 + 4 * KB
+
+
+def test_size_bound_term_by_term_over_a_grid():
+    for tau in (1, 2, 3, 64, 65, 128, 129, 200, 256):
+        for l in (1, 2, 3, 4, 5):
+            for KB in (256, 512, 1024, 2048, 4096):
+                for n in (0, 1, 7, 8, 9, KB - 1, KB, KB + 1, 3 * KB, 3 * KB + 5, 1_000_003):
+                    base = 1.1 if tau <= 128 else 1.05
+                    assert ref.compressed_size(n, ref.params(base, tau, l, KB)) == worst_case_bytes(n, tau, l, KB), \
+                        (n, tau, l, KB)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_no_stream_exceeds_the_size_bound(seed):
+    """Keys drawn to make long tokens (large, uneven gaps), small blocks, every l."""
+    rng = np.random.default_rng(seed)
+    for l in (1, 2, 3, 4, 5):
+        d = int(rng.integers(1, 2000))
+        keys = np.sort(rng.choice(2 ** 32 - 1, d, replace=False))
+        p = ref.params(1.1, 128, l, 256)
+        st, info = all_survive(keys, p)
+        assert info["d"] == d and len(st) <= ref.compressed_size(d, p)
+
+
 # ----------------------------------------------------------------------------- round trip + errors
 @pytest.mark.parametrize("seed,kb,l", [(0, 256, 2), (1, 1024, 1), (2, 4096, 5), (3, 512, 3)])
 def test_round_trip_keys_lossless(seed, kb, l):
@@ -199,6 +246,24 @@ def test_corrupt_streams_are_rejected():
     assert broken(poke32(dir_off + 12, pbits0 - 1)) == ref.ERR_CORRUPT_STREAM
     assert ref.decompress(st[:63])[0] == ref.ERR_CORRUPT_STREAM
     assert ref.decompress(st[:-8], capacity=4096)[0] == ref.ERR_CORRUPT_STREAM
+
+
+def test_a_stream_that_repeats_a_key_is_rejected():
+    """Eq. 4 is taken over the distinct, ascending keys of one gradient: a delta of 0 can only be the very first
+    (key 0).  A stream whose tokens say otherwise is not one an encoder wrote."""
+    keys = np.array([0, 3, 7, 20, 21, 300, 301, 5000], np.uint32)
+    st, info = all_survive(keys, ref.params(1.1, 128, 2, 256))
+    assert info["tokens"][0][2] == 0 and ref.decompress(st)[0] == ref.OK          # key 0: delta 0 at rank 0 is fine
+    for rank in (1, 2, 4, 7):
+        bad = with_zero_delta(st, rank)
+        assert not np.array_equal(bad, st)
+        assert ref.decompress(bad)[0] == ref.ERR_CORRUPT_STREAM, rank
+    # across a block boundary: first key of the second block equal to the last of the first
+    keys = np.cumsum(np.full(300, 5)).astype(np.uint32)
+    st, info = all_survive(keys, ref.params(1.1, 128, 2, 256))
+    bad = with_zero_delta(st, 256)
+    assert ref.decompress(bad)[0] == ref.ERR_CORRUPT_STREAM      # (here the preKey chain notices as well)
+    assert ref.decompress(with_zero_delta(st, 255))[0] == ref.ERR_CORRUPT_STREAM
 
 
 # ----------------------------------------------------------------------------- segmented batch

@@ -43,7 +43,11 @@ DECODE_PINS = [lambda: TV.test_decode_underestimates_within_one_base_step(0, 1.1
                lambda: TK.test_round_trip_keys_lossless(0, 256, 2),
                lambda: TK.test_block_boundaries_carry_prekey(257),
                TK.test_corrupt_streams_are_rejected,
+               TK.test_a_stream_that_repeats_a_key_is_rejected,
                TK.test_segmented_equals_independent_streams]
+SIZE_PINS = [lambda: TK.test_size_bound_is_reached_by_a_block_of_longest_tokens(256),
+             lambda: TK.test_size_bound_is_reached_by_a_block_of_longest_tokens(1024),
+             TK.test_size_bound_term_by_term_over_a_grid]
 AFTER_PINS = [lambda: TG.test_aggregate_equals_scatter_adds_in_stream_order(2),
               lambda: TG.test_aggregate_equals_scatter_adds_in_stream_order(5),
               TA.test_first_step_from_zero_state_closed_form,
@@ -83,10 +87,18 @@ MUTANTS = [
      "values_out[j] = bits_f32(V_bits[c]);", DECODE_PINS),
     ("decoder: magnitude of the neighbouring code", "uint32_t c = (token & (((uint32_t)1 << (w - 1)) - 1)) + 1;",
      "uint32_t c = (token & (((uint32_t)1 << (w - 1)) - 1)) + 2;", DECODE_PINS),
-    ("decoder: deltas not summed up", "key += get_bits(pl, pbit, len);", "key = get_bits(pl, pbit, len);", DECODE_PINS),
+    ("decoder: deltas not summed up", "key += delta;", "key = delta;", DECODE_PINS),
+    ("decoder: a repeated key tolerated", "if (delta == 0 && first + i != 0) return REF_ERR_CORRUPT_STREAM;", ";", DECODE_PINS),
     ("decoder: block does not start from its preKey", "uint64_t pbit = 0, key = preKey;", "uint64_t pbit = 0, key = 0;", DECODE_PINS),
     ("decoder: directory chain not checked", "if (preKey != prev_last) return REF_ERR_CORRUPT_STREAM;", ";", DECODE_PINS),
     ("decoder: unused payload bits tolerated", "if (pbit != payload_bits) return REF_ERR_CORRUPT_STREAM;", ";", DECODE_PINS),
+    ("size bound: directory entries left out", "return REF_HEADER_BYTES + value_plane_bytes(n, p->tau) + 16 * nb + nb * per_block;",
+     "return REF_HEADER_BYTES + value_plane_bytes(n, p->tau) + nb * per_block;", SIZE_PINS),
+    ("size bound: longest binary delta taken as 31 bits", "words64(KB * 32));", "words64(KB * 31));", SIZE_PINS),
+    ("size bound: flags plane left out", "uint64_t per_block = 8 * (words64(KB * p->flag_bits) + words64(KB * 32));",
+     "uint64_t per_block = 8 * words64(KB * 32);", SIZE_PINS),
+    ("size bound: value tokens counted as bytes whatever tau is", "static uint64_t value_plane_bytes(uint64_t d, uint32_t tau) { return 8 * words64(d * code_width(tau)); }",
+     "static uint64_t value_plane_bytes(uint64_t d, uint32_t tau) { (void)tau; return 8 * words64(d * 8); }", WIDE_PINS + SIZE_PINS),
     ("aggregate: streams taken from the last to the first", "const uint8_t *st = streams + stream_offsets[s];\n        uint64_t bytes = stream_offsets[s + 1] - stream_offsets[s];\n        uint64_t d = bytes >= REF_HEADER_BYTES ? get_u64(st + 40) : 0;\n        if (d > 8 * bytes) return REF_ERR_CORRUPT_STREAM;      /* every pair costs more than one bit */\n        uint32_t *k",
      "const uint32_t sr = n_streams - 1 - s;\n        const uint8_t *st = streams + stream_offsets[sr];\n        uint64_t bytes = stream_offsets[sr + 1] - stream_offsets[sr];\n        uint64_t d = bytes >= REF_HEADER_BYTES ? get_u64(st + 40) : 0;\n        if (d > 8 * bytes) return REF_ERR_CORRUPT_STREAM;\n        uint32_t *k", AFTER_PINS),
     ("aggregate overwrites instead of adding", "else dense[k[j]] = dense[k[j]] + v[j];", "else dense[k[j]] = v[j];", AFTER_PINS),
@@ -130,5 +142,5 @@ def test_a_planted_mistake_fails_a_pin(broken_oracle, name, old, new, pins):
 
 
 def test_the_sound_oracle_passes_the_same_pins():
-    for pin in VALUE_PINS + KEY_PINS + DECODE_PINS + AFTER_PINS:
+    for pin in VALUE_PINS + WIDE_PINS + KEY_PINS + DECODE_PINS + SIZE_PINS + AFTER_PINS:
         pin()
