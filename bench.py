@@ -2,9 +2,19 @@
 """Benchmark of the FastSGD codec on one MI355X.
 
 A "step" is one pass of the whole hot path over one batch of synthetic input: for every keep fraction
-of the workload's sweep, fastsgd_compress followed by fastsgd_decompress of that stream, inputs
-resident in HBM.  Prints ONE JSON line (metric = input GB/s of the round trip, 8 bytes per element:
-4-byte key + 4-byte value, the paper's 64 bits per original pair, Section 3.4).
+of the workload's sweep, fastsgd_compress followed by fastsgd_decompress of that stream (config 5: one
+fastsgd_compress_segmented + fastsgd_decompress_segmented over the 160 tensors), inputs resident in HBM.
+Prints ONE JSON line (metric = input GB/s of the round trip, 8 bytes per element: 4-byte key + 4-byte
+value, the paper's 64 bits per original pair, Section 3.4).
+
+Byte counts used below, per call (N elements, d survivors, sb stream bytes, rows = N/256):
+  compress, "algorithmic"  8N + 18d + sb : both value passes in full, key + scratch traffic of the survivors
+                                           (4d key fetch, 5d scratch out, 5d + 4d scratch back in), stream out
+  compress, "moved"        what the kernels are built to move: the second pass reads only the 128-byte
+                           granules whose bound reaches the threshold (q of them), and a key fetch pulls in
+                           the whole 128-byte line around each surviving key of an explicit key array
+                           (key_lines of them): 4N + 32 rows + 128 q + 128 key_lines + 14d + sb
+  decompress               sb + 8d
 """
 import argparse
 import json
@@ -25,7 +35,7 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bench_c4_hbm_traffic.md")
 def threshold_bits(total, base, tau):
     """Bit pattern of the early-stop threshold sum / b^tau (Algorithm 1 line 2) the way the codec
     evaluates it: the power by repeated float64 multiplication, the quotient rounded up to float32.
-    Only used to count, for the byte accounting, the rows the value pass has to read."""
+    Only used to count, for the byte accounting, the granules the value pass has to read."""
     import numpy as np
     p = 1.0
     for _ in range(tau):
@@ -49,18 +59,299 @@ def committed_traffic(kernel):
     return None
 
 
+def host_cpu():
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count()
+    return model, os.cpu_count(), usable
+
+
+class Timer:
+    """Event timing on torch's current stream, which is the stream the binding launches on."""
+
+    def __init__(self, torch, use_graph):
+        self.torch = torch
+        self.use_graph = use_graph
+
+    def eager(self, fn, iters):
+        torch = self.torch
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn(0)
+        e0.record()
+        for i in range(iters):
+            fn(i + 1)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    def graph(self, fn, iters):
+        """The same calls replayed from a HIP graph (a call is kernel launches only, so it can be
+        captured): what the kernels take once the launch gaps between them are gone."""
+        if not self.use_graph:
+            return None
+        torch = self.torch
+        cur = torch.cuda.current_stream()
+        side = torch.cuda.Stream()
+        side.wait_stream(cur)
+        with torch.cuda.stream(side):
+            fn(0)                                            # warm-up outside the capture
+        cur.wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(iters):
+                fn(i)
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+
+class SingleCase:
+    """One gradient (configs 1-4): a sweep of keep fractions, one stream per point."""
+
+    def __init__(self, w, keeps, copies=1):
+        import numpy as np
+        import torch
+        from paper_2112_04291_amd import binding as B
+        from paper_2112_04291_amd import workloads as W
+        self.w, self.B, self.torch = w, B, torch
+        self.n = n = int(w.values.size)
+        self.keeps = list(keeps)
+        self.bases = W.solve_bases(w.values, self.keeps)
+        # `copies` copies of the input, used in turn, so that a small input is not served from the caches
+        self.keys = [torch.from_numpy(w.keys.view(np.int32)).cuda() for _ in range(copies)]
+        self.values = [torch.from_numpy(w.values).cuda() for _ in range(copies)]
+        self.dense = bool(n and w.keys[0] == 0 and w.keys[-1] == n - 1)       # keys are the indices
+        plist = [B.params(b) for b in self.bases]
+        probe = B.Buffers(n, plist[0])
+        self.points = []
+        for keep, p in zip(self.keeps, plist):
+            rc = B.compress(self.keys[0], self.values[0], p, probe.out, probe.out_offsets, probe.status, probe.workspace,
+                            n=n, out_capacity=probe.out_capacity)
+            torch.cuda.synchronize()
+            assert rc == B.OK and int(probe.status[0]) == B.OK, (rc, int(probe.status[0]))
+            nbytes = int(probe.out_offsets[0])
+            hdr = probe.out_bytes_view()[:64].cpu().numpy()
+            d = int(hdr[40:48].view("<u8")[0])
+            total = float(hdr[24:32].view("<f8")[0])
+            out = torch.empty(nbytes // 8 + 8, dtype=torch.int64, device="cuda")
+            self.points.append(dict(keep=keep, p=p, out=out, cap=nbytes, bytes=nbytes, d=d, sum=total,
+                                    keys_out=torch.empty(max(d, 1), dtype=torch.int32, device="cuda"),
+                                    vals_out=torch.empty(max(d, 1), dtype=torch.float32, device="cuda")))
+        self.ws, self.dws = probe.workspace, probe.dec_workspace
+        self.obytes = torch.zeros(2, dtype=torch.int64, device="cuda")
+        self.count = torch.zeros(2, dtype=torch.int64, device="cuda")
+        self.status = torch.zeros(2, dtype=torch.int32, device="cuda")
+        del probe.out
+
+    def count_fetch_units(self):
+        """Per point: granules (32 values, 128 bytes) whose bound reaches the threshold -- what the value pass
+        has to read -- and, for a dense gradient with an explicit key array, the 128-byte lines of that array
+        that hold a surviving key.  The bound is the largest |v| of the granule as a bit pattern, upper 16
+        bits, rounded up."""
+        torch, n = self.torch, self.n
+        rows = (n + 255) // 256
+        pad = rows * 256 - n
+        absbits = self.values[0].abs().view(torch.int32)
+        if pad:
+            absbits = torch.cat([absbits, torch.zeros(pad, dtype=torch.int32, device="cuda")])
+        qbound = ((absbits.view(rows * 8, 32).max(dim=1).values.to(torch.int64) + 0xFFFF) >> 16) << 16
+        for pt in self.points:
+            pt["granules_active"] = int((qbound >= threshold_bits(pt["sum"], pt["p"].base, pt["p"].tau)).sum())
+            pt["key_lines"] = None
+        del absbits, qbound
+        if self.dense:
+            for pt in self.points:
+                self.compress(pt)
+                self.decompress(pt)
+                torch.cuda.synchronize()
+                lines = torch.unique_consecutive(pt["keys_out"][:pt["d"]] >> 5)
+                pt["key_lines"] = int(lines.numel())
+
+    def compress(self, pt, i=0, keys=True):
+        k = self.keys[i % len(self.keys)] if keys else None
+        rc = self.B.compress(k, self.values[i % len(self.values)], pt["p"], pt["out"], self.obytes, self.status, self.ws,
+                             n=self.n, out_capacity=pt["cap"])
+        assert rc == self.B.OK
+
+    def decompress(self, pt, i=0):
+        rc = self.B.decompress(pt["out"], pt["bytes"], pt["keys_out"], pt["vals_out"], self.count, self.status, self.dws,
+                               capacity=pt["d"])
+        assert rc == self.B.OK
+
+    def check(self, pt):
+        assert int(self.status[0]) == self.B.OK and int(self.count[0]) == pt["d"] and int(self.obytes[0]) == pt["bytes"]
+
+    def stream_bytes_host(self, pt):
+        return pt["out"].view(self.torch.uint8)[:pt["bytes"]].cpu().numpy()
+
+    def oracle_streams(self, ref):
+        """The oracle over the whole workload, every point: (seconds, [stream per point])."""
+        t0 = time.perf_counter()
+        streams = []
+        for b in self.bases:
+            rc, st = ref.compress(self.w.keys, self.w.values, ref.params(b))
+            assert rc == ref.OK
+            rc, k2, v2 = ref.decompress(st)
+            assert rc == ref.OK
+            streams.append(st)
+        return time.perf_counter() - t0, streams
+
+
+class BatchCase:
+    """Config 5: 160 tensors in one segmented call, every tensor with its own base (1 % kept)."""
+
+    def __init__(self, w, keep, copies=1):
+        import numpy as np
+        import torch
+        from paper_2112_04291_amd import binding as B
+        from paper_2112_04291_amd import workloads as W
+        self.w, self.B, self.torch = w, B, torch
+        self.n = n = int(w.values.size)
+        self.keeps = [keep]
+        offs = [int(x) for x in w.seg_offsets]
+        self.offs = offs
+        self.nseg = nseg = len(offs) - 1
+        self.bases = [W.solve_bases(w.values[offs[i]:offs[i + 1]], [keep])[0] for i in range(nseg)]
+        self.plist = [B.params(b) for b in self.bases]
+        self.keys = [torch.from_numpy(w.keys.view(np.int32)).cuda() for _ in range(copies)]
+        self.values = [torch.from_numpy(w.values).cuda() for _ in range(copies)]
+        self.dense = False
+        cap = B.compressed_size(max(n, 1), B.params(1.1, 128, 2, 1024)) + (64 + 4096) * nseg
+        out = torch.empty(cap // 8 + 8, dtype=torch.int64, device="cuda")
+        self.ws = torch.empty(B.workspace_size(n, nseg, 1024) // 8 + 32, dtype=torch.int64, device="cuda")
+        self.dws = B.decoder_workspace(nseg)
+        self.out_offs = torch.zeros(nseg + 1, dtype=torch.int64, device="cuda")
+        self.pair_offs = torch.zeros(nseg + 1, dtype=torch.int64, device="cuda")
+        self.status = torch.zeros(2, dtype=torch.int32, device="cuda")
+        pt = dict(keep=keep, out=out, p=self.plist[0])
+        self.points = [pt]
+        self.compress(pt)
+        torch.cuda.synchronize()
+        assert int(self.status[0]) == B.OK
+        so = self.out_offs.cpu().numpy()
+        pt["bytes"] = int(so[-1])
+        blob = out.view(torch.uint8)[:pt["bytes"]].cpu().numpy()
+        pt["d"] = int(sum(int(blob[int(o) + 40:int(o) + 48].view("<u8")[0]) for o in so[:-1]))
+        pt["keys_out"] = torch.empty(max(pt["d"], 1), dtype=torch.int32, device="cuda")
+        pt["vals_out"] = torch.empty(max(pt["d"], 1), dtype=torch.float32, device="cuda")
+        pt["granules_active"] = None
+        pt["key_lines"] = None
+
+    def count_fetch_units(self):
+        pass
+
+    def compress(self, pt, i=0, keys=True):
+        k = self.keys[i % len(self.keys)] if keys else None
+        rc = self.B.compress_segmented(k, self.values[i % len(self.values)], self.offs, self.plist, pt["out"], self.out_offs,
+                                       self.status, self.ws)
+        assert rc == self.B.OK
+
+    def decompress(self, pt, i=0):
+        rc = self.B.decompress_segmented(pt["out"], pt["bytes"], self.out_offs, self.nseg, pt["keys_out"], pt["vals_out"],
+                                         self.pair_offs, self.status, self.dws)
+        assert rc == self.B.OK
+
+    def check(self, pt):
+        assert int(self.status[0]) == self.B.OK and int(self.pair_offs[self.nseg]) == pt["d"]
+        assert int(self.out_offs[self.nseg]) == pt["bytes"]
+
+    def stream_bytes_host(self, pt):
+        return pt["out"].view(self.torch.uint8)[:pt["bytes"]].cpu().numpy()
+
+    def oracle_streams(self, ref):
+        t0 = time.perf_counter()
+        rc, blob, so = ref.compress_segmented(self.w.keys, self.w.values, self.w.seg_offsets,
+                                              [ref.params(b) for b in self.bases])
+        assert rc == ref.OK
+        rc, k2, v2, po = ref.decompress_segmented(blob, so, self.points[0]["d"])
+        assert rc == ref.OK
+        return time.perf_counter() - t0, [blob]
+
+
+WORKLOAD_NAMES = {"c1": "c1_tiny_sparse", "c2": "c2_dense_25m", "c3": "c3_sparse_zipf", "c4": "c4_dense_124m",
+                  "c5": "c5_segmented"}
+
+
+def make_case(name, scale=1.0, keeps=None):
+    from paper_2112_04291_amd import workloads as W
+    t0 = time.time()
+    if name == "c5":
+        w = W.config5()
+        case = BatchCase(w, 0.01, copies=2)
+    else:
+        gen = {"c1": W.config1, "c2": W.config2, "c3": W.config3, "c4": W.config4}[name]
+        if scale != 1.0 and name in ("c2", "c4"):
+            w = gen(n=int({"c2": 25_600_000, "c4": 124_000_000}[name] * scale))
+        else:
+            w = gen()
+        in_bytes = 8 * int(w.values.size)
+        copies = 1 if in_bytes >= (512 << 20) else min(8, -(-(1 << 30) // max(in_bytes, 1)))
+        case = SingleCase(w, keeps or w.meta["keep"], copies=copies)
+    print(f"[bench] workload {w.name}: n={case.n} keeps={case.keeps} (ready in {time.time() - t0:.1f}s)",
+          file=sys.stderr, flush=True)
+    return case
+
+
+def point_record(case, pt, timer, iters):
+    """Timings and rates of one point of a case (compress and decompress each timed on their own)."""
+    n, d, sb = case.n, pt["d"], pt["bytes"]
+    rows = (n + 255) // 256
+    c_ms = timer.eager(lambda i: case.compress(pt, i), iters)
+    d_ms = timer.eager(lambda i: case.decompress(pt, i), iters)
+    cg_ms = timer.graph(lambda i: case.compress(pt, i), iters)
+    dg_ms = timer.graph(lambda i: case.decompress(pt, i), iters)
+    case.check(pt)
+    comp_alg = 8.0 * n + 18.0 * d + sb                         # two value passes + survivor traffic + stream
+    dec_alg = sb + 8.0 * d
+    rec = dict(keep=pt["keep"], d=d, stream_bytes=sb, ratio=8.0 * n / sb,
+               compress_ms=c_ms, decompress_ms=d_ms, compress_graph_ms=cg_ms, decompress_graph_ms=dg_ms,
+               compress_input_GBps=8.0 * n / c_ms / 1e6, decompress_input_GBps=8.0 * n / d_ms / 1e6,
+               compress_elements_per_s=n / c_ms * 1e3,
+               compress_algorithmic_bytes=comp_alg, decompress_algorithmic_bytes=dec_alg,
+               compress_hbm_frac=comp_alg / c_ms / 1e6 / HBM_PEAK_GBPS,
+               decompress_hbm_frac=dec_alg / d_ms / 1e6 / HBM_PEAK_GBPS,
+               compress_graph_hbm_frac=None if cg_ms is None else comp_alg / cg_ms / 1e6 / HBM_PEAK_GBPS,
+               decompress_graph_hbm_frac=None if dg_ms is None else dec_alg / dg_ms / 1e6 / HBM_PEAK_GBPS)
+    if pt.get("granules_active") is not None:
+        qa = pt["granules_active"]
+        kl = pt["key_lines"]
+        moved = 4.0 * n + 32.0 * rows + 128.0 * qa + (128.0 * kl if kl is not None else 4.0 * d) + 14.0 * d + sb
+        rec.update(base=pt["p"].base, bits_per_key=8.0 * (sb - 64 - d) / max(d, 1), granules_read=qa, granules=8 * rows,
+                   key_lines_read=kl, compress_moved_bytes=moved,
+                   compress_moved_frac=moved / c_ms / 1e6 / HBM_PEAK_GBPS)
+    return rec
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--keeps", default="", help="comma-separated keep fractions instead of the workload's sweep "
+                                                  "(profiling one point on its own)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replays of the per-point timings")
-    ap.add_argument("--cpu-sample", type=int, default=0, help="elements the oracle is timed on (0 = the whole workload)")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the per-config records of the configurations that are not the timed workload")
     ap.add_argument("--widening", action="store_true",
-                    help="also time decode-and-aggregate (4 copies of each stream) and decode-and-update (Adam); "
+                    help="also time decode-and-aggregate (8 streams into one dense vector) and decode-and-update (Adam); "
                          "reported under \"widening\", outside the timed step")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run, before anything else, one plain elementwise kernel over the value array "
@@ -75,27 +366,16 @@ def main():
     import numpy as np
     import torch
     from paper_2112_04291_amd import binding as B
-    from paper_2112_04291_amd import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     B.lib()
+    timer = Timer(torch, not args.no_graph)
 
-    gen = {"c1": W.config1, "c2": W.config2, "c3": W.config3, "c4": W.config4}[args.workload]
-    t0 = time.time()
-    if args.scale != 1.0 and args.workload in ("c2", "c4"):
-        w = gen(n=int({"c2": 25_600_000, "c4": 124_000_000}[args.workload] * args.scale))
-    else:
-        w = gen()
-    keeps = w.meta["keep"]
-    bases = W.solve_bases(w.values, keeps)
-    n = int(w.values.size)
-    print(f"[bench] workload {w.name}: n={n} keeps={keeps} bases={bases} (generated in {time.time() - t0:.1f}s)",
-          file=sys.stderr, flush=True)
-
-    keys = torch.from_numpy(w.keys.view(np.int32)).cuda()
-    values = torch.from_numpy(w.values).cuda()
-    plist = [B.params(b) for b in bases]
+    keeps = [float(x) for x in args.keeps.split(",") if x] or None
+    case = make_case(args.workload, args.scale, keeps)
+    n, points = case.n, case.points
+    values = case.values[0]
 
     if args.calibrate:
         ref_copy = torch.empty_like(values)
@@ -103,199 +383,152 @@ def main():
         torch.cuda.synchronize()
         del ref_copy
 
-    # one output buffer per sweep point (sized from a first, untimed pass), shared workspace
-    probe = B.Buffers(n, plist[0])
-    points = []
-    for keep, p in zip(keeps, plist):
-        rc = B.compress(keys, values, p, probe.out, probe.out_offsets, probe.status, probe.workspace, n=n,
-                        out_capacity=probe.out_capacity)
-        torch.cuda.synchronize()
-        assert rc == B.OK and int(probe.status[0]) == B.OK, (rc, int(probe.status[0]))
-        nbytes = int(probe.out_offsets[0])
-        hdr = probe.out_bytes_view()[:64].cpu().numpy()
-        d = int(hdr[40:48].view("<u8")[0])
-        total = float(hdr[24:32].view("<f8")[0])
-        out = torch.empty(nbytes // 8 + 8, dtype=torch.int64, device="cuda")
-        points.append(dict(keep=keep, p=p, out=out, cap=nbytes, bytes=nbytes, d=d, sum=total,
-                           keys_out=torch.empty(max(d, 1), dtype=torch.int32, device="cuda"),
-                           vals_out=torch.empty(max(d, 1), dtype=torch.float32, device="cuda")))
-    ws, dws = probe.workspace, probe.dec_workspace
-    obytes = torch.zeros(2, dtype=torch.int64, device="cuda")
-    count = torch.zeros(2, dtype=torch.int64, device="cuda")
-    status = torch.zeros(2, dtype=torch.int32, device="cuda")
-    del probe.out
+    case.count_fetch_units()
 
-    # granules (32 elements, 128 bytes) whose bound reaches the threshold: what the value pass has to read.
-    # The bound is the largest |v| of the granule as a bit pattern, upper 16 bits, rounded up.
-    rows = (n + 255) // 256
-    pad = rows * 256 - n
-    absbits = values.abs().view(torch.int32)
-    if pad:
-        absbits = torch.cat([absbits, torch.zeros(pad, dtype=torch.int32, device="cuda")])
-    qbound = ((absbits.view(rows * 8, 32).max(dim=1).values.to(torch.int64) + 0xFFFF) >> 16) << 16
-    for pt in points:
-        pt["granules_active"] = int((qbound >= threshold_bits(pt["sum"], pt["p"].base, pt["p"].tau)).sum())
-    del absbits, qbound
-
-    def do_compress(pt):
-        rc = B.compress(keys, values, pt["p"], pt["out"], obytes, status, ws, n=n, out_capacity=pt["cap"])
-        assert rc == B.OK
-
-    def do_decompress(pt):
-        rc = B.decompress(pt["out"], pt["bytes"], pt["keys_out"], pt["vals_out"], count, status, dws, capacity=pt["d"])
-        assert rc == B.OK
-
-    def step():
+    # ---- the timed step: the whole hot path over the whole sweep
+    def step(i):
         for pt in points:
-            do_compress(pt)
-            do_decompress(pt)
+            case.compress(pt, i)
+            case.decompress(pt, i)
 
-    for _ in range(args.warmup):
-        step()
+    for i in range(args.warmup):
+        step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
+    for i in range(args.steps):
+        step(i)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    assert int(status[0]) == B.OK and int(count[0]) == points[-1]["d"]
+    case.check(points[-1])
     ms_per_step = 1e3 * elapsed / args.steps
-    in_bytes_step = 8.0 * n * len(points)
-    value = in_bytes_step / (elapsed / args.steps) / 1e9
+    value = 8.0 * n * len(points) / (elapsed / args.steps) / 1e9
 
-    # per direction and per sweep point, event-timed on the launch stream
-    def timed(fn, pt, iters):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        fn(pt)
-        e0.record()
-        for _ in range(iters):
-            fn(pt)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters
+    # ---- what this GPU sustains on a plain streaming read and a plain copy of the value array
+    sink = torch.zeros(2, dtype=torch.int64, device="cuda")
+    probe_src = values if values.numel() >= (32 << 20) else torch.zeros(124_000_000, dtype=torch.float32, device="cuda")
+    probe_bytes = probe_src.numel() * 4
+    read_ms = timer.eager(lambda i: B.probe_read(probe_src, sink), args.steps)
+    copy_dst = torch.empty_like(probe_src)
+    copy_ms = timer.eager(lambda i: copy_dst.copy_(probe_src), args.steps)
+    del copy_dst
+    peak_measured = dict(read_GBps=probe_bytes / read_ms / 1e6, copy_GBps=2.0 * probe_bytes / copy_ms / 1e6,
+                         bytes=probe_bytes, note="fastsgd_probe_read (plain streaming read) and a device-to-device copy "
+                                                 "of the same array, timed in this run")
 
-    # the same calls replayed from a HIP graph (a call is kernel launches only, so it can be captured):
-    # what the kernels take once the launch gaps between them are gone
-    def graph_timed(fn, pt, iters):
-        if args.no_graph:
-            return None
-        cur = torch.cuda.current_stream()
-        side = torch.cuda.Stream()
-        side.wait_stream(cur)
-        with torch.cuda.stream(side):
-            fn(pt)                                           # warm-up outside the capture
-        cur.wait_stream(side)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for _ in range(iters):
-                fn(pt)
-        graph.replay()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        graph.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters
-
+    # ---- per direction and per sweep point, event-timed on the launch stream; per kernel for one gradient
     detail = []
-    kern_time = {}
-    kern_bytes = {}
+    kern_time, kern_bytes = {}, {}
+    rows = (n + 255) // 256
     for pt in points:
-        c_ms = timed(do_compress, pt, args.steps)
-        d_ms = timed(do_decompress, pt, args.steps)
-        cg_ms = graph_timed(do_compress, pt, args.steps)
-        dg_ms = graph_timed(do_decompress, pt, args.steps)
-        assert int(status[0]) == B.OK and int(count[0]) == pt["d"] and int(obytes[0]) == pt["bytes"]
-        rc, kc = B.profile_compress(keys, values, pt["p"], pt["out"], obytes, status, ws, args.steps, n=n,
-                                    out_capacity=pt["cap"])
-        assert rc == B.OK
-        rc, kd = B.profile_decompress(pt["out"], pt["bytes"], pt["keys_out"], pt["vals_out"], count, status, dws,
-                                      args.steps, capacity=pt["d"])
-        assert rc == B.OK
-        d, sb, qa = pt["d"], pt["bytes"], pt["granules_active"]
-        # algorithmic bytes per launch: what each kernel's method has to move
-        alg = {
-            "abs_sum": 4.0 * n + 16.0 * rows,                    # every value once; eight 16-bit bounds per row out
-            "encode_values": 16.0 * rows + 128.0 * qa + 4.0 * d + 5.0 * d,   # bounds; granules that can hold a
-                                                                 # survivor; keys of survivors; key + code byte to scratch
-            "measure_keys": 4.0 * d,                             # surviving keys
-            "pack_keys": 5.0 * d + (sb - 64),                    # surviving keys and code bytes in, stream out
-            "decode": sb + 8.0 * d,                              # stream in, (key, value) pairs out
-        }
-        for k, v in {**kc, **{"decode": kd["decode"], "decode_setup": kd["setup"]}}.items():
-            kern_time[k] = kern_time.get(k, 0.0) + v
-        for k, v in alg.items():
-            kern_bytes[k] = kern_bytes.get(k, 0.0) + v
-        comp_alg = 8.0 * n + 18.0 * d + sb                       # two value passes + survivor traffic + stream
-        detail.append(dict(keep=pt["keep"], base=pt["p"].base, d=d, stream_bytes=sb, ratio=8.0 * n / sb,
-                           bits_per_key=8.0 * (sb - 64 - d) / max(d, 1), granules_read=qa, granules=8 * rows,
-                           compress_ms=c_ms, decompress_ms=d_ms,
-                           compress_graph_ms=cg_ms, decompress_graph_ms=dg_ms,
-                           compress_graph_hbm_frac=None if cg_ms is None else comp_alg / cg_ms / 1e6 / HBM_PEAK_GBPS,
-                           decompress_graph_hbm_frac=None if dg_ms is None else (sb + 8.0 * d) / dg_ms / 1e6 / HBM_PEAK_GBPS,
-                           compress_input_GBps=8.0 * n / c_ms / 1e6, decompress_input_GBps=8.0 * n / d_ms / 1e6,
-                           compress_elements_per_s=n / c_ms * 1e3,
-                           compress_hbm_frac=comp_alg / c_ms / 1e6 / HBM_PEAK_GBPS,
-                           decompress_hbm_frac=(sb + 8.0 * d) / d_ms / 1e6 / HBM_PEAK_GBPS,
-                           kernels_ms={**kc, **{"decode_" + k: v for k, v in kd.items()}}))
+        rec = point_record(case, pt, timer, args.steps)
+        if isinstance(case, SingleCase):
+            rc, kc = B.profile_compress(case.keys[0], values, pt["p"], pt["out"], case.obytes, case.status, case.ws,
+                                        args.steps, n=n, out_capacity=pt["cap"])
+            assert rc == B.OK
+            rc, kd = B.profile_decompress(pt["out"], pt["bytes"], pt["keys_out"], pt["vals_out"], case.count, case.status,
+                                          case.dws, args.steps, capacity=pt["d"])
+            assert rc == B.OK
+            d, sb, qa, kl = pt["d"], pt["bytes"], pt["granules_active"], pt["key_lines"]
+            # bytes each kernel is built to move, per launch: every value once and eight 16-bit bounds per row out;
+            # bounds, granules that can hold a survivor, key lines of survivors, key + code byte to scratch;
+            # surviving keys; surviving keys and code bytes in, stream out; stream in, (key, value) pairs out
+            alg = {
+                "abs_sum": 4.0 * n + 16.0 * rows,
+                "encode_values": 16.0 * rows + 128.0 * qa + (128.0 * kl if kl is not None else 4.0 * d) + 5.0 * d,
+                "measure_keys": 4.0 * d,
+                "pack_keys": 5.0 * d + (sb - 64),
+                "decode": sb + 8.0 * d,
+            }
+            for k, v in {**kc, **{"decode": kd["decode"]}}.items():
+                kern_time[k] = kern_time.get(k, 0.0) + v
+            for k, v in alg.items():
+                kern_bytes[k] = kern_bytes.get(k, 0.0) + v
+            rec["kernels_ms"] = {**kc, **{"decode_" + k: v for k, v in kd.items()}}
+            rec["kernels_moved_bytes"] = alg
+            # the same call without a key array (keys are the indices): what a dense gradient needs
+            if case.dense:
+                i_ms = timer.eager(lambda i: case.compress(pt, i, keys=False), args.steps)
+                assert int(case.status[0]) == B.OK and int(case.obytes[0]) == pt["bytes"]
+                ialg = 8.0 * n + 14.0 * d + sb
+                rec.update(compress_no_key_array_ms=i_ms,
+                           compress_no_key_array_hbm_frac=ialg / i_ms / 1e6 / HBM_PEAK_GBPS)
+        detail.append(rec)
 
-    dominant = max(("abs_sum", "encode_values"), key=lambda k: kern_time[k])
-    kernels = {k: dict(ms_total=kern_time[k], achieved_GBps=kern_bytes[k] / kern_time[k] / 1e6,
-                       frac=kern_bytes[k] / kern_time[k] / 1e6 / HBM_PEAK_GBPS) for k in kern_bytes}
-    launches = len(points)
-    roofline = dict(bound="hbm", kernel="k_" + dominant,
-                    achieved=kern_bytes[dominant] / kern_time[dominant] / 1e6, peak=HBM_PEAK_GBPS, unit="GB/s",
-                    frac=kern_bytes[dominant] / kern_time[dominant] / 1e6 / HBM_PEAK_GBPS,
-                    traffic=committed_traffic("k_" + dominant),
-                    traffic_source="profiles/bench_c4_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
-                                   "separate runs of this command, scaled by a plain elementwise kernel of known size; bytes per launch)",
-                    avg_launch_ms=kern_time[dominant] / launches,
-                    algorithmic_bytes_per_launch=kern_bytes[dominant] / launches)
+    kernels = None
+    big = max(detail, key=lambda r: r["d"])                          # the point with the most survivors
+    calls = dict(point=dict(keep=big["keep"], d=big["d"], stream_bytes=big["stream_bytes"]),
+                 compress=dict(ms=big["compress_ms"], algorithmic_bytes=big["compress_algorithmic_bytes"],
+                               frac=big["compress_hbm_frac"], moved_bytes=big.get("compress_moved_bytes"),
+                               moved_frac=big.get("compress_moved_frac"),
+                               no_key_array_ms=big.get("compress_no_key_array_ms"),
+                               no_key_array_frac=big.get("compress_no_key_array_hbm_frac")),
+                 decompress=dict(ms=big["decompress_ms"], algorithmic_bytes=big["decompress_algorithmic_bytes"],
+                                 frac=big["decompress_hbm_frac"]),
+                 note="whole calls at the sweep point with the most survivors; frac = algorithmic bytes / time / peak "
+                      "(compress 8N+18d+sb, decompress sb+8d); moved_* counts the granules actually read and the "
+                      "128-byte key lines actually fetched instead; no_key_array_*: the same gradient passed without "
+                      "its key array (8N+14d+sb)")
+    if kern_time:
+        dominant = max(("abs_sum", "encode_values"), key=lambda k: kern_time[k])
+        kernels = {k: dict(ms_total=kern_time[k], achieved_GBps=kern_bytes[k] / kern_time[k] / 1e6,
+                           frac=kern_bytes[k] / kern_time[k] / 1e6 / HBM_PEAK_GBPS) for k in kern_bytes}
+        launches = len(points)
+        roofline = dict(bound="hbm", kernel="k_" + dominant,
+                        achieved=kern_bytes[dominant] / kern_time[dominant] / 1e6, peak=HBM_PEAK_GBPS, unit="GB/s",
+                        frac=kern_bytes[dominant] / kern_time[dominant] / 1e6 / HBM_PEAK_GBPS,
+                        traffic=committed_traffic("k_" + dominant) if args.workload == "c4" and not keeps else None,
+                        traffic_source="profiles/bench_c4_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
+                                       "separate runs of this command, scaled by a plain elementwise kernel of known size; "
+                                       "bytes per launch)",
+                        avg_launch_ms=kern_time[dominant] / launches,
+                        algorithmic_bytes_per_launch=kern_bytes[dominant] / launches,
+                        peak_measured=peak_measured, calls=calls)
+    else:
+        comp = sum(r["compress_algorithmic_bytes"] for r in detail) / sum(r["compress_ms"] for r in detail) / 1e6
+        roofline = dict(bound="hbm", kernel="fastsgd_compress_segmented (whole call)", achieved=comp, peak=HBM_PEAK_GBPS,
+                        unit="GB/s", frac=comp / HBM_PEAK_GBPS, traffic=None, peak_measured=peak_measured, calls=calls)
 
     widening = None
-    if args.widening:
+    if args.widening and isinstance(case, SingleCase):
         widening = []
+        n_streams = 8
         dense = torch.zeros(n, dtype=torch.float32, device="cuda")
         theta, m1, v1 = (torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(3))
-        aws = torch.empty(B.decompress_workspace_size(4) // 8 + 32, dtype=torch.int64, device="cuda")
+        aws = B.decoder_workspace(n_streams)
+        count, status, obytes, ws, dws = case.count, case.status, case.obytes, case.ws, case.dws
+        keys = case.keys[0]
         for pt in points:
             sb = pt["bytes"]
-            four = torch.cat([pt["out"].view(torch.uint8)[:sb]] * 4 + [torch.zeros(64, dtype=torch.uint8, device="cuda")])
-            offs = torch.tensor([0, sb, 2 * sb, 3 * sb, 4 * sb], dtype=torch.int64, device="cuda")
+            many = torch.cat([pt["out"].view(torch.uint8)[:sb]] * n_streams + [torch.zeros(64, dtype=torch.uint8, device="cuda")])
+            offs = torch.tensor([i * sb for i in range(n_streams + 1)], dtype=torch.int64, device="cuda")
 
             def do_acc(_):
-                assert B.decompress_accumulate(four, 4 * sb, offs, 4, dense, count, status, aws) == B.OK
+                assert B.decompress_accumulate(many, n_streams * sb, offs, n_streams, dense, count, status, aws) == B.OK
 
             def do_adam(_):
                 assert B.decompress_adam(pt["out"], sb, theta, m1, v1, 1e-3, 0.9, 0.999, 1e-8, count, status, aws) == B.OK
 
-            a_ms = timed(do_acc, pt, args.steps)
-            assert int(status[0]) == B.OK and int(count[0]) == 4 * pt["d"]
-            u_ms = timed(do_adam, pt, args.steps)
+            a_ms = timer.eager(do_acc, args.steps)
+            assert int(status[0]) == B.OK and int(count[0]) == n_streams * pt["d"]
+            u_ms = timer.eager(do_adam, args.steps)
             assert int(status[0]) == B.OK and int(count[0]) == pt["d"]
-            widening.append(dict(keep=pt["keep"], d=pt["d"], accumulate_4_streams_ms=a_ms, adam_ms=u_ms,
-                                 accumulate_pairs_per_s=4.0 * pt["d"] / a_ms * 1e3, adam_pairs_per_s=pt["d"] / u_ms * 1e3))
-            del four
+            widening.append(dict(keep=pt["keep"], d=pt["d"], accumulate_streams=n_streams, accumulate_ms=a_ms, adam_ms=u_ms,
+                                 accumulate_pairs_per_s=float(n_streams) * pt["d"] / a_ms * 1e3,
+                                 adam_pairs_per_s=pt["d"] / u_ms * 1e3))
+            del many
         del dense, theta, m1, v1
-        # variants of the encoder: no key array (keys are the indices), and the paper's base b = 1.1 with
-        # the threshold that keeps about the same fraction (b^tau = base^128; above 128 a token is 9 bits)
-        cap_all = max(B.compressed_size(n, B.params(1.1, 256)), B.compressed_size(n, plist[0]))
+        # the paper's base b = 1.1 with the threshold that keeps about the same fraction (b^tau = base^128;
+        # above 128 a token is 9 bits)
+        cap_all = max(B.compressed_size(n, B.params(1.1, 256)), B.compressed_size(n, points[0]["p"]))
         vout = torch.empty(cap_all // 8 + 8, dtype=torch.int64, device="cuda")
         for pt, wd in zip(points, widening):
-            def do_implicit(_):
-                assert B.compress(None, values, pt["p"], vout, obytes, status, ws, n=n, out_capacity=cap_all) == B.OK
-
-            i_ms = timed(do_implicit, pt, args.steps)
-            assert int(status[0]) == B.OK and int(obytes[0]) == pt["bytes"]
             tau11 = min(256, max(1, int(math.ceil(128.0 * math.log(pt["p"].base) / math.log(1.1)))))
             p11 = B.params(1.1, tau11)
 
             def do_b11(_):
                 assert B.compress(keys, values, p11, vout, obytes, status, ws, n=n, out_capacity=cap_all) == B.OK
 
-            b_ms = timed(do_b11, pt, args.steps)
+            b_ms = timer.eager(do_b11, args.steps)
             assert int(status[0]) == B.OK
             sb11 = int(obytes[0])
             d11 = int(vout.view(torch.uint8)[40:48].cpu().numpy().view("<u8")[0])
@@ -305,40 +538,64 @@ def main():
             def do_b11_dec(_):
                 assert B.decompress(vout, sb11, k11, v11, count, status, dws, capacity=d11) == B.OK
 
-            bd_ms = timed(do_b11_dec, pt, args.steps)
+            bd_ms = timer.eager(do_b11_dec, args.steps)
             assert int(status[0]) == B.OK and int(count[0]) == d11
-            wd.update(no_key_array_compress_ms=i_ms, base_1p1=dict(tau=tau11, d=d11, stream_bytes=sb11,
-                                                                    compress_ms=b_ms, decompress_ms=bd_ms))
+            wd.update(base_1p1=dict(tau=tau11, d=d11, stream_bytes=sb11, compress_ms=b_ms, decompress_ms=bd_ms))
             del k11, v11
         del vout
 
+    # ---- the CPU oracle on the same workload: a baseline, and the check that the timed streams are the oracle's
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import ref
-        m = n if args.cpu_sample <= 0 else min(args.cpu_sample, n)
-        sk, sv = w.keys[:m], w.values[:m]
-        sbases = bases if m == n else W.solve_bases(sv, keeps)
-        t0 = time.perf_counter()
-        for b in sbases:
-            rc, st = ref.compress(sk, sv, ref.params(b))
-            assert rc == ref.OK
-            rc, k2, v2 = ref.decompress(st)
-            assert rc == ref.OK
-        cpu_s = time.perf_counter() - t0
-        cpu = dict(value=8.0 * m * len(sbases) / cpu_s / 1e9, unit="GB/s", cores=1, kind="oracle",
-                   sample=f"{'all' if m == n else 'first'} {m} elements of {w.name}, all {len(sbases)} keep "
-                          f"fractions, compress+decompress once, {cpu_s:.1f} s on one host core")
+        cpu_s, ref_streams = case.oracle_streams(ref)
+        same = True
+        for pt, st_ref in zip(points, ref_streams):
+            case.compress(pt)
+            torch.cuda.synchronize()
+            got = case.stream_bytes_host(pt)
+            same = same and got.size == st_ref.size and bool(np.array_equal(got, st_ref))
+        model, nproc, usable = host_cpu()
+        cpu = dict(value=8.0 * n * len(points) / cpu_s / 1e9, unit="GB/s", cores=1, kind="oracle",
+                   cpu_model=model, nproc=nproc, usable_cores=usable, parity_checked=same,
+                   sample=f"all {n} elements of {case.w.name}, all {len(points)} keep fraction(s), compress+decompress "
+                          f"once, {cpu_s:.1f} s on one host core; every GPU stream of the timed step compared byte for "
+                          f"byte with the oracle's")
+        assert same, "a stream of the timed step differs from the oracle's"
+        del ref_streams
+
+    # ---- one record per other configuration (one call each, inputs used in turn where they are small)
+    configs = None
+    keep_fractions = [r["keep"] for r in detail]
+    if args.workload == "c4" and not args.no_other_configs and not keeps and args.scale == 1.0:
+        del case, values, points, probe_src
+        torch.cuda.empty_cache()
+        configs = []
+        for name in ("c1", "c2", "c3", "c5"):
+            c = make_case(name)
+            for pt in c.points:
+                rec = point_record(c, pt, timer, args.steps)
+                in_bytes = 8 * c.n
+                rec.update(workload=c.w.name, n=c.n, segments=getattr(c, "nseg", 1), input_copies=len(c.values),
+                           residency="cache-resident (inputs under 512 MB in all: rates may exceed HBM peak)"
+                           if in_bytes * len(c.values) < (512 << 20) else "HBM (the inputs used in turn exceed the caches)")
+                configs.append(rec)
+            del c
+            torch.cuda.empty_cache()
 
     line = {
         "metric": "compress & decompress input GB/s (% of HBM peak) on 1 MI355X; compression ratio",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "n": n, "keep_fractions": keeps, "tau": 128, "flag_bits": 2,
+        "config": {"workload": WORKLOAD_NAMES[args.workload], "n": n,
+                   "keep_fractions": keep_fractions, "tau": 128, "flag_bits": 2,
                    "block_keys": 1024, "step": "compress+decompress at every keep fraction",
                    "arithmetic": "f32 values and u32 keys compared as IEEE bit patterns; f64 boundary table"},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "detail": detail,
     }
+    if configs is not None:
+        line["configs"] = configs
     if widening is not None:
         line["widening"] = widening
     print(json.dumps(line))

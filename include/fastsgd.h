@@ -14,6 +14,7 @@
  *     device); everything else is host memory read during the call only.
  *   - The caller owns every buffer.  The library allocates no device memory and keeps no state
  *     between calls; two calls may run concurrently if they use different workspaces.
+ *     (include/fastsgd_profile.h declares two measurement aids that do not follow these rules.)
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default
  *     stream).  No entry point synchronises with the host.  Values only the device knows are
  *     reported through the d_* result words, valid once the stream has been synchronised.
@@ -77,7 +78,10 @@ size_t fastsgd_compressed_size(uint64_t n, const fastsgd_params* p);
  * survivors, whose number is not known beforehand).  Returns 0 on invalid arguments. */
 size_t fastsgd_workspace_size(uint64_t total_n, uint32_t n_segments, uint32_t min_block_keys);
 
-/* Host-only, pure.  Bytes of device workspace the decoders need for n_segments streams. */
+/* Host-only, pure.  Bytes of device workspace the decoders need for n_segments streams.
+ * The first 4096 bytes of a decoder workspace hold control words that must be ZERO before the workspace's
+ * first use (clear them once after allocating it); every decoder call leaves them zero again, so the
+ * workspace can be reused call after call without further clearing.  The rest needs no initialisation. */
 size_t fastsgd_decompress_workspace_size(uint32_t n_segments);
 
 /* Encoder (Algorithms 1 and 2) for one worker's gradient {(k_j, v_j)}, j = 1..n.
@@ -100,7 +104,10 @@ fastsgd_status fastsgd_compress(const uint32_t* d_keys, const float* d_values, u
  *   d_stream           device, stream_bytes bytes, 8-byte aligned
  *   d_keys_out, d_values_out   device, `capacity` entries each; receive the d surviving pairs
  *   d_count            device u64: d, or 0 if *d_status != FASTSGD_OK
- *   d_workspace        device, >= fastsgd_decompress_workspace_size(1) bytes, 256-byte aligned */
+ *   d_workspace        device, >= fastsgd_decompress_workspace_size(1) bytes, 256-byte aligned, control
+ *                      words zero (see fastsgd_decompress_workspace_size)
+ * One kernel launch: the header is checked and the table of decoded magnitudes rebuilt inside it.  A stream
+ * in which a key repeats its predecessor (a delta of 0 anywhere but at the first key) is corrupt. */
 fastsgd_status fastsgd_decompress(const void* d_stream, size_t stream_bytes,
                                   uint32_t* d_keys_out, float* d_values_out, uint64_t capacity,
                                   uint64_t* d_count, uint32_t* d_status,
@@ -181,28 +188,6 @@ fastsgd_status fastsgd_decompress_adam(const void* d_stream, size_t stream_bytes
                                        const fastsgd_adam* h,
                                        uint64_t* d_count, uint32_t* d_status,
                                        void* d_workspace, size_t workspace_bytes, void* hip_stream);
-
-/* Measurement aids (Section 4.2 of the paper reports encoder and decoder time separately; these
- * split each further, per kernel).  Same arguments and results as fastsgd_compress /
- * fastsgd_decompress, run `iterations` (1..4096) times back to back with a HIP event recorded on
- * hip_stream before the first and after every kernel; the call then WAITS for the stream and
- * stores the average milliseconds per kernel in kernel_ms (host).  Kernel order, compress:
- * abs-sum, tables, encode-values, measure-keys (with the scan of the chunk counts in front of it),
- * pack-keys; decompress: setup, decode.
- * These two calls create and destroy HIP events; they are not meant for production paths. */
-#define FASTSGD_PROFILE_COMPRESS_KERNELS 5
-#define FASTSGD_PROFILE_DECOMPRESS_KERNELS 2
-fastsgd_status fastsgd_profile_compress(const uint32_t* d_keys, const float* d_values, uint64_t n,
-                                        const fastsgd_params* p,
-                                        void* d_out, size_t out_capacity,
-                                        uint64_t* d_out_bytes, uint32_t* d_status,
-                                        void* d_workspace, size_t workspace_bytes, void* hip_stream,
-                                        uint32_t iterations, float* kernel_ms);
-fastsgd_status fastsgd_profile_decompress(const void* d_stream, size_t stream_bytes,
-                                          uint32_t* d_keys_out, float* d_values_out, uint64_t capacity,
-                                          uint64_t* d_count, uint32_t* d_status,
-                                          void* d_workspace, size_t workspace_bytes, void* hip_stream,
-                                          uint32_t iterations, float* kernel_ms);
 
 #ifdef __cplusplus
 }

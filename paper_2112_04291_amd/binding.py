@@ -1,4 +1,4 @@
-"""Thin ctypes binding over libfastsgd.so (declared in include/fastsgd.h).
+"""Thin ctypes binding over libfastsgd.so (declared in include/fastsgd.h and include/fastsgd_profile.h).
 
 Argument marshalling only: every step of the codec runs in the library's HIP kernels.  PyTorch is
 used for device memory and for the current stream handle.  There is no CPU fallback: if the library
@@ -18,9 +18,9 @@ STATUS_NAMES = ["OK", "INVALID_ARG", "BUFFER_TOO_SMALL", "NONFINITE", "UNSORTED_
 EXPORTS = ["fastsgd_compressed_size", "fastsgd_workspace_size", "fastsgd_decompress_workspace_size",
            "fastsgd_compress", "fastsgd_decompress", "fastsgd_compress_segmented", "fastsgd_decompress_segmented",
            "fastsgd_decompress_accumulate", "fastsgd_decompress_adam",
-           "fastsgd_profile_compress", "fastsgd_profile_decompress"]
+           "fastsgd_profile_compress", "fastsgd_profile_decompress", "fastsgd_probe_read"]
 COMPRESS_KERNELS = ["abs_sum", "tables", "encode_values", "measure_keys", "pack_keys"]
-DECOMPRESS_KERNELS = ["setup", "decode"]
+DECOMPRESS_KERNELS = ["decode"]
 
 
 class Params(C.Structure):
@@ -74,6 +74,8 @@ def lib():
         L.fastsgd_profile_compress.restype = C.c_int
         L.fastsgd_profile_decompress.argtypes = [vp, sz, vp, vp, u64, vp, vp, vp, sz, vp, u32, fp]
         L.fastsgd_profile_decompress.restype = C.c_int
+        L.fastsgd_probe_read.argtypes = [vp, sz, vp, vp]
+        L.fastsgd_probe_read.restype = C.c_int
         _lib = L
     return _lib
 
@@ -134,6 +136,11 @@ def profile_decompress(stream, stream_bytes, keys_out, values_out, count, status
     return rc, dict(zip(DECOMPRESS_KERNELS, [float(x) for x in ms]))
 
 
+def probe_read(src, sink):
+    """fastsgd_probe_read over the whole device tensor `src`: a plain streaming read, to be timed by the caller."""
+    return lib().fastsgd_probe_read(_p(src), src.numel() * src.element_size(), _p(sink), _stream())
+
+
 def _params_array(plist, n_segments):
     if isinstance(plist, Params):
         return (Params * 1)(plist), 0
@@ -175,6 +182,12 @@ def decompress_accumulate(streams, total_bytes, stream_offsets, n_streams, dense
                                                workspace.numel() * workspace.element_size(), _stream())
 
 
+def decoder_workspace(n_segments=1, device="cuda"):
+    """A decoder workspace for n_segments streams, its control words cleared (the library asks for that
+    once, before the first use, and leaves them clear after every call)."""
+    return torch.zeros(decompress_workspace_size(n_segments) // 8 + 32, dtype=torch.int64, device=device)
+
+
 # ----------------------------------------------------------------------------------------------------
 # Buffer plumbing for callers that do not manage their own device memory (tests, benchmark, smoke).
 class Buffers:
@@ -189,8 +202,7 @@ class Buffers:
         self.out = torch.empty((cap + 7) // 8, dtype=torch.int64, device=self.device)
         self.out_capacity = cap
         self.workspace = torch.empty(workspace_size(n, n_segments, kb) // 8 + 32, dtype=torch.int64, device=self.device)
-        self.dec_workspace = torch.empty(decompress_workspace_size(n_segments) // 8 + 32, dtype=torch.int64,
-                                         device=self.device)
+        self.dec_workspace = decoder_workspace(n_segments, self.device)
         self.out_offsets = torch.zeros(n_segments + 1, dtype=torch.int64, device=self.device)
         self.pair_offsets = torch.zeros(n_segments + 1, dtype=torch.int64, device=self.device)
         self.status = torch.zeros(2, dtype=torch.int32, device=self.device)

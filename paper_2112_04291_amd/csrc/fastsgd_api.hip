@@ -9,11 +9,13 @@
 
 namespace fsgd {
 
-constexpr u64 kDecSegBytes = 1152, kDecCtrlBytes = 64;   // >= sizeof(DecSeg), sizeof(DecCtrl)
+constexpr u64 kDecSegBytes = 1152;   // >= sizeof(DecSeg)
 constexpr u32 kMaxSegments = 65536;
+constexpr u32 kInlineWaves = 16;       // waves per workgroup of a single-stream decode launch over a long stream ...
+constexpr u64 kInlineLargeBytes = 6u << 20;   // ... which is one of at least this many bytes (some 3000 key blocks)
 constexpr u64 kMaxElems = 0xFFFFFFFFull - 1023;   // per gradient: scratch offsets inside a segment stay below 2^32
 constexpr u32 kMaxSumGrid = 2048;      // most workgroups the abs-sum pass of a single gradient is launched with
-static_assert(sizeof(DecSeg) <= kDecSegBytes && sizeof(DecCtrl) <= kDecCtrlBytes, "decoder workspace records");
+static_assert(sizeof(DecSeg) <= kDecSegBytes, "decoder workspace records");
 static_assert(sizeof(SegInfo) == 48 && sizeof(SegBatch) <= 3900, "segment table travels as a kernel argument");
 
 static bool params_ok(const fastsgd_params* p) {
@@ -101,7 +103,10 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     const float* vbase = d_values + first_elem - mis;
     const u32* kbase = d_keys ? d_keys + first_elem - mis : nullptr;     // no key array: keys are 0..n-1
 
-    std::vector<SegInfo> segs(n_segments);
+    SegInfo one_seg;                                               // a single gradient needs no heap
+    std::vector<SegInfo> seg_table;
+    if (n_segments > 1) seg_table.resize(n_segments);
+    SegInfo* segs = n_segments > 1 ? seg_table.data() : &one_seg;
     u32 min_kb = kMaxKB, max_kb = 0;
     bool wide = false;                                             // some segment's codes need more than a byte
     u64 n_tiles = 0, max_items = 0, total_rows = 0;
@@ -242,18 +247,32 @@ static fastsgd_status decompress_impl(const void* d_streams, size_t total_bytes,
     if (((uintptr_t)d_streams & 7) || ((uintptr_t)d_ws & 255)) return FASTSGD_ERR_INVALID_ARG;
     if (capacity && (!d_keys_out || !d_values_out)) return FASTSGD_ERR_INVALID_ARG;
     if (((uintptr_t)d_keys_out & 3) || ((uintptr_t)d_values_out & 3)) return FASTSGD_ERR_INVALID_ARG;
-    if (ws_bytes < kDecCtrlBytes + 192 + (u64)n_segments * kDecSegBytes) return FASTSGD_ERR_BUFFER_TOO_SMALL;
+    if (ws_bytes < kDecSegOffset + (u64)n_segments * kDecSegBytes) return FASTSGD_ERR_BUFFER_TOO_SMALL;
     uint8_t* ws = static_cast<uint8_t*>(d_ws);
     DecCtrl* ctrl = reinterpret_cast<DecCtrl*>(ws);
-    DecSeg* segs = reinterpret_cast<DecSeg*>(ws + 256);
+    DecSeg* segs = reinterpret_cast<DecSeg*>(ws + kDecSegOffset);
     const uint8_t* streams = static_cast<const uint8_t*>(d_streams);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const u32 cus = cu_count();
 
     marks.mark(stream);
+    // every key costs at least three bits, so bytes/96 bounds the number of key blocks
+    const u64 max_blocks = (u64)total_bytes / 96 + n_segments;
+    const u32 grid = clamp_grid((max_blocks + kWaves - 1) / kWaves, (u64)cus * 7);
     if (single) {
-        hipLaunchKernelGGL(k_decode_setup, dim3(1), dim3(kMaxTau), 0, stream, streams, (u64)total_bytes,
-                           (const u64*)nullptr, 1u, segs, ctrl, capacity, d_counts, d_status);
+        // One launch: every workgroup checks the header and rebuilds the magnitude table itself.  A long
+        // stream (thousands of key blocks: every wave slot of the GPU busy) is decoded by one large workgroup
+        // per compute unit, so that one walk of b^c serves sixteen waves; a short one by small workgroups,
+        // which spread its few blocks over more compute units.
+        DecDone* done = reinterpret_cast<DecDone*>(ws + kDecDoneOffset);
+        if (total_bytes >= kInlineLargeBytes)
+            hipLaunchKernelGGL((k_decode<kStore, true, kInlineWaves>), dim3(clamp_grid((max_blocks + kInlineWaves - 1) / kInlineWaves, cus)),
+                               dim3(kInlineWaves * kWave), 0, stream, streams, (u64)total_bytes, capacity, (const DecSeg*)nullptr, 1u,
+                               ctrl, done, d_keys_out, d_values_out, d_counts, 1u, d_status, (float*)nullptr, (u64)0, 0u, AdamArgs());
+        else
+            hipLaunchKernelGGL((k_decode<kStore, true, kWaves>), dim3(clamp_grid((max_blocks + kWaves - 1) / kWaves, (u64)cus * 4)),
+                               dim3(kThreads), 0, stream, streams, (u64)total_bytes, capacity, (const DecSeg*)nullptr, 1u,
+                               ctrl, done, d_keys_out, d_values_out, d_counts, 1u, d_status, (float*)nullptr, (u64)0, 0u, AdamArgs());
     } else {
         hipLaunchKernelGGL(k_decode_clear, dim3(1), dim3(64), 0, stream, ctrl);
         hipLaunchKernelGGL(k_decode_setup, dim3(n_segments), dim3(kMaxTau), 0, stream, streams, (u64)total_bytes,
@@ -261,12 +280,10 @@ static fastsgd_status decompress_impl(const void* d_streams, size_t total_bytes,
         if (n_segments > 1)
             hipLaunchKernelGGL(k_decode_plan, dim3(1), dim3(kThreads), 0, stream, segs, n_segments, capacity, ctrl,
                                d_counts, d_status, (u64*)nullptr);
+        hipLaunchKernelGGL((k_decode<kStore, false, kWaves>), dim3(grid), dim3(kThreads), 0, stream, streams, (u64)total_bytes, capacity,
+                           segs, n_segments, ctrl, (DecDone*)nullptr, d_keys_out, d_values_out, d_counts, n_segments + 1u, d_status,
+                           (float*)nullptr, (u64)0, 0u, AdamArgs());
     }
-    marks.mark(stream);
-    // every key costs at least three bits, so bytes/96 bounds the number of key blocks
-    hipLaunchKernelGGL(k_decode<kStore>, dim3(clamp_grid(((u64)total_bytes / 96 + n_segments + kWaves - 1) / kWaves, (u64)cus * 7)),
-                       dim3(kThreads), 0, stream, streams, segs, n_segments, ctrl, d_keys_out, d_values_out, d_counts,
-                       single ? 1u : n_segments + 1u, d_status, (float*)nullptr, (u64)0, 0u, AdamArgs());
     marks.mark(stream);
     return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
 }
@@ -280,11 +297,11 @@ static fastsgd_status accumulate_impl(const void* d_streams, size_t total_bytes,
     if (n_streams < 1 || n_streams > kMaxSegments) return FASTSGD_ERR_INVALID_ARG;
     if (((uintptr_t)d_streams & 7) || ((uintptr_t)d_ws & 255) || ((uintptr_t)d_dense & 3)) return FASTSGD_ERR_INVALID_ARG;
     if (dense_len && !d_dense) return FASTSGD_ERR_INVALID_ARG;
-    const u64 off_counts = 256 + up((u64)n_streams * kDecSegBytes, 256);
+    const u64 off_counts = kDecSegOffset + up((u64)n_streams * kDecSegBytes, 256);
     if (ws_bytes < off_counts + ((u64)n_streams + 1) * 8) return FASTSGD_ERR_BUFFER_TOO_SMALL;
     uint8_t* ws = static_cast<uint8_t*>(d_ws);
     DecCtrl* ctrl = reinterpret_cast<DecCtrl*>(ws);
-    DecSeg* segs = reinterpret_cast<DecSeg*>(ws + 256);
+    DecSeg* segs = reinterpret_cast<DecSeg*>(ws + kDecSegOffset);
     u64* counts = reinterpret_cast<u64*>(ws + off_counts);
     const uint8_t* streams = static_cast<const uint8_t*>(d_streams);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -296,8 +313,9 @@ static fastsgd_status accumulate_impl(const void* d_streams, size_t total_bytes,
                        d_count);
     const u32 grid = clamp_grid(((u64)total_bytes / 96 + 1 + kWaves - 1) / kWaves, (u64)cus * 7);
     for (u32 s = 0; s < n_streams; ++s)
-        hipLaunchKernelGGL(k_decode<kAccum>, dim3(grid), dim3(kThreads), 0, stream, streams, segs, n_streams, ctrl,
-                           (u32*)nullptr, (float*)nullptr, d_count, 1u, d_status, d_dense, dense_len, s, AdamArgs());
+        hipLaunchKernelGGL((k_decode<kAccum, false, kWaves>), dim3(grid), dim3(kThreads), 0, stream, streams, (u64)total_bytes, ~0ull,
+                           segs, n_streams, ctrl, (DecDone*)nullptr, (u32*)nullptr, (float*)nullptr, d_count, 1u, d_status, d_dense, dense_len, s,
+                           AdamArgs());
     return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
 }
 
@@ -312,10 +330,10 @@ static fastsgd_status adam_impl(const void* d_stream, size_t stream_bytes, float
     if (!(h->eta == h->eta) || !(h->beta1 >= 0.0 && h->beta1 <= 1.0) || !(h->beta2 >= 0.0 && h->beta2 <= 1.0) ||
         !(h->eps >= 0.0))
         return FASTSGD_ERR_INVALID_ARG;
-    if (ws_bytes < kDecCtrlBytes + 192 + kDecSegBytes) return FASTSGD_ERR_BUFFER_TOO_SMALL;
+    if (ws_bytes < kDecSegOffset + kDecSegBytes) return FASTSGD_ERR_BUFFER_TOO_SMALL;
     uint8_t* ws = static_cast<uint8_t*>(d_ws);
     DecCtrl* ctrl = reinterpret_cast<DecCtrl*>(ws);
-    DecSeg* segs = reinterpret_cast<DecSeg*>(ws + 256);
+    DecSeg* segs = reinterpret_cast<DecSeg*>(ws + kDecSegOffset);
     const uint8_t* streams = static_cast<const uint8_t*>(d_stream);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     AdamArgs a;
@@ -327,12 +345,34 @@ static fastsgd_status adam_impl(const void* d_stream, size_t stream_bytes, float
     a.beta2 = (float)h->beta2;
     a.one_minus_beta2 = (float)(1.0 - h->beta2);
     a.eps = (float)h->eps;
+    // (two launches: with the header work inside it this variant of the decode kernel runs out of registers)
     hipLaunchKernelGGL(k_decode_setup, dim3(1), dim3(kMaxTau), 0, stream, streams, (u64)stream_bytes, (const u64*)nullptr, 1u,
                        segs, ctrl, ~0ull, d_count, d_status);
     const u32 grid = clamp_grid(((u64)stream_bytes / 96 + 1 + kWaves - 1) / kWaves, (u64)cu_count() * 7);
-    hipLaunchKernelGGL(k_decode<kAdam>, dim3(grid), dim3(kThreads), 0, stream, streams, segs, 1u, ctrl, (u32*)nullptr,
-                       (float*)nullptr, d_count, 1u, d_status, d_theta, dim, 0u, a);
+    hipLaunchKernelGGL((k_decode<kAdam, false, kWaves>), dim3(grid), dim3(kThreads), 0, stream, streams, (u64)stream_bytes, ~0ull,
+                       segs, 1u, ctrl, (DecDone*)nullptr, (u32*)nullptr, (float*)nullptr, d_count, 1u, d_status, d_theta, dim, 0u, a);
     return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
+}
+
+// Streaming read probe: 16 bytes per lane (non-temporal loads); a workgroup takes 16 KB at a time (four loads
+// per lane in flight),
+// consecutive workgroups take consecutive pieces; the data only feeds a hash that decides a store that
+// (practically) never happens.
+__global__ void __launch_bounds__(kThreads) k_probe_read(const uint4* __restrict__ src, u64 n16, u64* sink) {
+    constexpr u32 U = 4;
+    const u64 stride = (u64)gridDim.x * kThreads * U;
+    u32 h = 0;
+    for (u64 base = (u64)blockIdx.x * kThreads * U + threadIdx.x; base < n16; base += stride) {
+        uint4 q[U];
+#pragma unroll
+        for (u32 r = 0; r < U; ++r) {
+            const u64 i = base + r * kThreads;
+            q[r] = i < n16 ? load_stream16(src + i) : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (u32 r = 0; r < U; ++r) h ^= q[r].x ^ q[r].y ^ q[r].z ^ q[r].w;
+    }
+    if (h == 0x9E3779B9u && __popcll(__ballot(true)) == 1) sink[0] = h;
 }
 
 // Runs `call` `iterations` times with an event after every kernel and averages the gaps.
@@ -387,7 +427,7 @@ size_t fastsgd_workspace_size(uint64_t total_n, uint32_t n_segments, uint32_t mi
 
 size_t fastsgd_decompress_workspace_size(uint32_t n_segments) {
     if (n_segments < 1 || n_segments > kMaxSegments) return 0;
-    return (size_t)(256 + up((u64)n_segments * kDecSegBytes, 256) + ((u64)n_segments + 1) * 8);
+    return (size_t)(kDecSegOffset + up((u64)n_segments * kDecSegBytes, 256) + ((u64)n_segments + 1) * 8);
 }
 
 fastsgd_status fastsgd_decompress_accumulate(const void* d_streams, size_t total_bytes,
@@ -426,6 +466,15 @@ fastsgd_status fastsgd_profile_compress(const uint32_t* d_keys, const float* d_v
                             return compress_impl(d_keys, d_values, offs, 1, p, 0, d_out, out_capacity, d_out_bytes,
                                                  d_status, d_workspace, workspace_bytes, hip_stream, true, m);
                         });
+}
+
+fastsgd_status fastsgd_probe_read(const void* d_src, size_t bytes, uint64_t* d_sink, void* hip_stream) {
+    if (!d_src || !d_sink || ((uintptr_t)d_src & 15)) return FASTSGD_ERR_INVALID_ARG;
+    const u64 n16 = bytes / 16;
+    const u32 grid = clamp_grid((n16 + kThreads - 1) / kThreads, (u64)cu_count() * 8);
+    hipLaunchKernelGGL(k_probe_read, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<const uint4*>(d_src), n16, (u64*)d_sink);
+    return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
 }
 
 fastsgd_status fastsgd_profile_decompress(const void* d_stream, size_t stream_bytes, uint32_t* d_keys_out,

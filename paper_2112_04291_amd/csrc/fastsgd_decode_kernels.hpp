@@ -1,10 +1,12 @@
 // Decoder kernels of the gfx950 FastSGD codec (Section 3.1 of arXiv 2112.04291, decoder phases 1-4).
 //
-//   k_decode_setup   per stream: validate the header, rebuild the table of decoded magnitudes
+//   k_decode_setup   batches, per stream: validate the header, rebuild the table of decoded magnitudes
 //                    sum / b^c (phases 3-4 evaluated once per code)
 //   k_decode_plan    pair offsets and work-item numbering over the streams of a batch
 //   k_decode         per key block: flags -> lengths -> bit offsets -> deltas (phase 1),
-//                    prefix sum + preKey -> keys (phase 2), code byte -> value (phases 3-4)
+//                    prefix sum + preKey -> keys (phase 2), code byte -> value (phases 3-4).
+//                    A single stream needs no other launch: every wave checks the header and rebuilds
+//                    the magnitude table itself, and the last workgroup to finish reports the outcome.
 #pragma once
 #include "fastsgd_device.hpp"
 
@@ -23,6 +25,58 @@ struct DecCtrl {
     u32 status, pad;
     u64 total_items, total_pairs;
 };
+
+// Completion count of a single-stream launch (which has no setup kernel and no kernel after it): the
+// workgroups that have key blocks to decode count themselves in when their waves are through, and the one
+// that completes the count reports the launch's outcome.  Atomics on one address are served one after the
+// other, a few nanoseconds each, so the count is kept in kDoneGroups words on cache lines of their own
+// (workgroup b counts in group b mod kDoneGroups) and one word on top that counts the completed groups.
+// All words must be zero when a launch begins and are zero again when it ends: the counters wrap (atomicInc)
+// and the last workgroup takes the failure word away, so they need clearing only once, before the
+// workspace's first use.  Batch launches never touch them.
+constexpr u32 kDoneGroups = 16;
+struct DecDone {
+    u32 fail;                    // first failure a wave of the launch found (a fastsgd_status), 0 = none
+    u32 top;                     // groups that have completed
+    u32 pad[30];
+    u32 group[kDoneGroups][32];  // [g][0]: workgroups of group g that have finished
+};
+constexpr u64 kDecDoneOffset = 128;       // in the decoder workspace
+constexpr u64 kDecSegOffset = 4096;       // the per-stream records of a batch start here
+static_assert(kDecDoneOffset + sizeof(DecDone) <= kDecSegOffset && sizeof(DecCtrl) <= kDecDoneOffset, "decoder workspace layout");
+
+// What a stream's header says, checked; byte offsets are relative to the start of the stream.
+struct DecHead {
+    u64 d, dir_off, blocks_off, total_words;
+    u32 nb, l, tau, KB;
+    double base, sum;
+};
+
+// Parses and checks the 64-byte header at `h` of a stream that may use up to `avail` bytes.
+__device__ __forceinline__ bool parse_header(const u64* __restrict__ h, u64 avail, DecHead& hd) {
+    const u64 h0 = h[0], h1 = h[1];
+    hd.l = (u32)(h0 >> 40) & 0xFF; hd.tau = (u32)(h0 >> 48); hd.KB = (u32)h1; hd.nb = (u32)(h1 >> 32);
+    hd.base = __longlong_as_double((long long)h[2]);
+    hd.sum = __longlong_as_double((long long)h[3]);
+    const u64 n = h[4], total = h[6];
+    hd.d = h[5];
+    const u32 l = hd.l, tau = hd.tau, KB = hd.KB;
+    bool ok = ((u32)h0 == kMagic) && (((h0 >> 32) & 0xFF) == kVersion);
+    ok = ok && l >= 1 && l <= 5 && tau >= 1 && tau <= kMaxTau;
+    ok = ok && KB >= 256 && KB <= kMaxKB && (KB & (KB - 1)) == 0;
+    ok = ok && (hd.base >= 1.0 + 1.0 / 1048576.0) && (hd.base <= (tau > 128 ? 4.0 : 16.0));
+    ok = ok && (hd.sum >= 0.0) && (hd.sum < __longlong_as_double(0x7FF0000000000000ll));
+    ok = ok && n <= 4294967296ull && hd.d <= n;
+    hd.dir_off = 0; hd.blocks_off = 0; hd.total_words = 0;
+    if (ok) {
+        ok = (u64)hd.nb == (hd.d + KB - 1) / KB;
+        hd.dir_off = kHeaderBytes + value_plane_bytes(hd.d, code_width(tau));
+        hd.blocks_off = hd.dir_off + 16ull * hd.nb;
+        ok = ok && total <= avail && total >= hd.blocks_off && (total & 7) == 0;
+        hd.total_words = ok ? (total - hd.blocks_off) >> 3 : 0;
+    }
+    return ok;
+}
 
 __device__ __forceinline__ void dec_fail(DecCtrl* ctrl, u32 code, u32* out_status, u64* out_counts, u32 n_counts) {
     if (atomicCAS(&ctrl->status, 0u, code) == 0u) *out_status = code;
@@ -70,27 +124,10 @@ k_decode_setup(const uint8_t* __restrict__ streams, u64 total_bytes, const u64* 
         u64 d = 0, dir_off = 0, blocks_off = 0, total_words = 0;
         double base = 2.0, sum = 0.0;
         if (ok) {
-            const u64* h = reinterpret_cast<const u64*>(streams + begin);
-            const u64 h0 = h[0], h1 = h[1];
-            l = (u32)(h0 >> 40) & 0xFF; tau = (u32)(h0 >> 48); KB = (u32)h1; nb = (u32)(h1 >> 32);
-            base = __longlong_as_double((long long)h[2]);
-            sum = __longlong_as_double((long long)h[3]);
-            const u64 n = h[4], total = h[6];
-            d = h[5];
-            ok = ((u32)h0 == kMagic) && (((h0 >> 32) & 0xFF) == kVersion);
-            ok = ok && l >= 1 && l <= 5 && tau >= 1 && tau <= kMaxTau;
-            ok = ok && KB >= 256 && KB <= kMaxKB && (KB & (KB - 1)) == 0;
-            ok = ok && (base >= 1.0 + 1.0 / 1048576.0) && (base <= (tau > 128 ? 4.0 : 16.0));
-            ok = ok && (sum >= 0.0) && (sum < __longlong_as_double(0x7FF0000000000000ll));
-            ok = ok && n <= 4294967296ull && d <= n;
-            if (ok) {
-                ok = (u64)nb == (d + KB - 1) / KB;
-                dir_off = kHeaderBytes + value_plane_bytes(d, code_width(tau));
-                blocks_off = dir_off + 16ull * nb;
-                ok = ok && total <= end - begin && total >= blocks_off && (total & 7) == 0;
-                total_words = ok ? (total - blocks_off) >> 3 : 0;
-                dir_off += begin; blocks_off += begin;
-            }
+            DecHead hd;
+            ok = parse_header(reinterpret_cast<const u64*>(streams + begin), end - begin, hd);
+            l = hd.l; tau = hd.tau; KB = hd.KB; nb = hd.nb; d = hd.d; base = hd.base; sum = hd.sum;
+            dir_off = hd.dir_off + begin; blocks_off = hd.blocks_off + begin; total_words = hd.total_words;
         }
         if (!ok) { d = 0; nb = 0; tau = 1; }
         ds->stream_begin = begin; ds->d = d; ds->nb = nb; ds->l = l; ds->tau = tau; ds->KB = KB;
@@ -199,14 +236,16 @@ struct AdamArgs {
 
 // FULL: the round has all 1024 keys (no key-index tests).  MODE kAccum / kAdam: instead of storing the
 // pairs, update the dense arrays at every key (keys are unique inside a stream, so plain
-// read-modify-write is enough); a key >= dense_len sets too_big.  Returns false if the stream is corrupt.
+// read-modify-write is enough); a key >= dense_len sets too_big.  stream_start: the round begins with the
+// stream's first key, the only one whose delta may be 0 (Eq. 4 is taken over distinct ascending keys).
+// Returns false if the stream is corrupt.
 template <bool FULL, int MODE>
 __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round, const u32* __restrict__ psrc,
                                              u32 pw_total, const uint8_t* __restrict__ codes_round, u32 n, u32 l,
                                              u32 M, u32 tau, u32 cwid, u32 pbits, u32& pbit, u32& carry, u32 lane,
                                              u32* s_pay, u32* s_flg, u32* s_cod, const u32* s_V, u32* __restrict__ keys_dst,
                                              float* __restrict__ values_dst, float* __restrict__ dense, u64 dense_len,
-                                             const AdamArgs& adam, bool& too_big) {
+                                             const AdamArgs& adam, bool& too_big, bool stream_start) {
     const u32 nfw = (n * l + 31u) >> 5;
     const u32 pw0 = pbit >> 5, wbits = pbit & 31u;
     u32 npw = ((wbits + n * M + 31u) >> 5) + 1u;           // words this round can reach (+1: windows)
@@ -305,9 +344,7 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
     u32 bp = wbits + incl - lanebits;
     u32 kp[kLaneKeys];
     u32 acc = 0;
-    bool ovf = false;
-    // (sixteen deltas of at most 27 bits cannot wrap a lane's running sum)
-    const bool wrap_possible = M > 27u;
+    bool ovf = false;                                       // a key beyond 32 bits, or one that repeats its predecessor
 #pragma unroll
     for (u32 k = 0; k < kLaneKeys; ++k) {
         const u32 wa = bp >> 5;
@@ -316,7 +353,11 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         if (!FULL && len[k] == 0) dl = 0;                   // (a real key has a length of at least 1)
         bp += len[k];
         const u32 nx = acc + dl;
-        if (wrap_possible) ovf |= nx < acc;
+        // the running sum must grow: it does not if it wraps (only a long delta can do that) or if the delta
+        // is 0, i.e. the key repeats its predecessor -- which only the stream's very first key may do
+        // (keys beyond n have no length and no delta)
+        if (k == 0) ovf |= dl == 0 && (FULL || len[k] != 0) && !(stream_start && lane == 0);
+        else ovf |= nx <= acc && (FULL || len[k] != 0);
         acc = nx;
         kp[k] = acc;
     }
@@ -357,7 +398,7 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
 #pragma unroll
         for (u32 q = 0; q < kLaneKeys; ++q) {
             const u32 i = q * 64u + lane;
-            if (FULL || i < n) keys_dst[i] = kr[q];
+            if (FULL || i < n) __builtin_nontemporal_store(kr[q], &keys_dst[i]);    // written once, not read again here
         }
     }
     wave_lds_sync();
@@ -376,7 +417,7 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         for (u32 q = 0; q < kLaneKeys; ++q) {
             const u32 i = q * 64u + lane;
             const u32 x = wide_value(i);
-            if (FULL || i < n) values_dst[i] = __uint_as_float(x);
+            if (FULL || i < n) __builtin_nontemporal_store(__uint_as_float(x), &values_dst[i]);
         }
         pbit += roundbits;
         return !(__any(ovf) || __any(badcode));
@@ -396,7 +437,7 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
 #pragma unroll
         for (u32 q = 0; q < kLaneKeys; ++q) {
             const u32 i = q * 64u + lane;
-            if (FULL || i < n) values_dst[i] = __uint_as_float(vr[q]);
+            if (FULL || i < n) __builtin_nontemporal_store(__uint_as_float(vr[q]), &values_dst[i]);
         }
     } else {
         // all sixteen reads are issued before the first write: the keys of a valid stream are distinct,
@@ -441,40 +482,95 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
     return !(__any(ovf) || __any(badcode));
 }
 
-// MODE kAccum / kAdam: the launch handles the key blocks of stream `only` alone and updates the dense
-// arrays (one launch per stream, so that the updates happen stream after stream).
-template <int MODE>
-__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(MODE == kStore ? 4 : 2, 8)))
-k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u32 n_segments, DecCtrl* ctrl,
-         u32* __restrict__ keys_out, float* __restrict__ values_out, u64* out_counts, u32 n_counts,
-         u32* out_status, float* __restrict__ dense, u64 dense_len, u32 only, AdamArgs adam) {
-    __shared__ __attribute__((aligned(16))) u32 s_payall[kWaves][20 * 64];     // payload window (17 rows of 64 words); output staging (1280 words)
-    __shared__ u32 s_flgall[kWaves][3 * 64];                                    // flags of a round (160 words at most)
-    __shared__ u32 s_Vall[kWaves][256];                                         // value by code byte (bit 7: sign)
-    __shared__ __attribute__((aligned(16))) u32 s_codall[kWaves][2 * kCodeWords];   // token words, then widened bytes
+// MODE kAccum: the launch handles the key blocks of stream `only` alone and updates the dense array (one
+// launch per stream, so that the updates happen stream after stream).
+// INLINE: one stream and no other launch.  Every wave reads the 64-byte header and reaches the same verdict
+// on it; the workgroup rebuilds the table of decoded magnitudes sum / b^c (phases 3-4 evaluated once per
+// code): one thread walks the tau multiplications of b^c -- a chain of dependent binary64 operations that
+// takes microseconds, which is why such a launch uses few, large workgroups (WAVES = 16: one chain per
+// compute unit) -- then 256 threads divide, one code each.  A wave that finds its block corrupt leaves the
+// code in done->fail (first one wins); every workgroup that has key blocks counts itself in `done` when its
+// waves are through, and the one that completes the count writes *out_status and out_counts[0] and leaves
+// the control words zero for the next launch (workgroups without key blocks leave at once; a launch with
+// nothing to decode is reported by workgroup 0 alone).
+template <int MODE, bool INLINE, u32 WAVES>
+__global__ void __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu(MODE == kStore ? 4 : 2, 8)))
+k_decode(const uint8_t* __restrict__ streams, u64 stream_bytes, u64 capacity, const DecSeg* __restrict__ segs,
+         u32 n_segments, DecCtrl* ctrl, DecDone* done, u32* __restrict__ keys_out, float* __restrict__ values_out, u64* out_counts,
+         u32 n_counts, u32* out_status, float* __restrict__ dense, u64 dense_len, u32 only, AdamArgs adam) {
+    static_assert(!INLINE || WAVES >= 4, "256 threads divide for the 256 codes");
+    __shared__ __attribute__((aligned(16))) u32 s_payall[WAVES][20 * 64];     // payload window (17 rows of 64 words); output staging (1280 words)
+    __shared__ u32 s_flgall[WAVES][3 * 64];                                    // flags of a round (160 words at most)
+    __shared__ u32 s_Vall[INLINE ? 1 : WAVES][256];                            // value by code byte (bit 7: sign); one stream: one table
+    __shared__ __attribute__((aligned(16))) u32 s_codall[WAVES][2 * kCodeWords];   // token words, then widened bytes
     const u32 lane = lane_id(), w = uniform(wave_id());
     u32* s_pay = s_payall[w];
     u32* s_flg = s_flgall[w];
-    u32* s_V = s_Vall[w];
+    u32* s_V = s_Vall[INLINE ? 0 : w];
     u32* s_cod = s_codall[w];
-    u64 item_lo = 0, item_hi = ctrl->total_items;
-    if (MODE != kStore && item_hi) { item_lo = segs[only].item_begin; item_hi = item_lo + segs[only].nb; }
+    u64 item_lo = 0, item_hi = 0;
     u32 cur_seg = 0xFFFFFFFFu;
+    DecHead hd = {};                // the stream in hand (wave-uniform)
+    u64 stream_begin = 0, pair_begin = 0, seg_item_begin = 0;
+    u32 head_status = 0;            // INLINE: what the header alone says
+    u32 n_work = 1;                 // INLINE: workgroups that have key blocks (and report through the count)
+    u32 dir_first = 0;              // INLINE: the wave's first directory entry, fetched before the table is built
+    if (INLINE) {
+        bool ok = stream_bytes >= kHeaderBytes;
+        if (ok) ok = parse_header(reinterpret_cast<const u64*>(streams), stream_bytes, hd);
+        if (!ok) head_status = FASTSGD_ERR_CORRUPT_STREAM;
+        else if (hd.d > capacity) head_status = FASTSGD_ERR_BUFFER_TOO_SMALL;
+        head_status = uniform(head_status);
+        if (head_status == 0 && hd.nb) {
+            const u32 units = (hd.nb + WAVES - 1u) / WAVES;
+            n_work = units < gridDim.x ? units : gridDim.x;
+        }
+        if (blockIdx.x >= n_work) return;                    // nothing to decode and nothing to report
+        if (head_status == 0 && hd.nb) {
+            item_hi = hd.nb;
+            const u32 blk0 = blockIdx.x * WAVES + w;
+            if (blk0 < hd.nb && (lane < 4 || (lane < 8 && blk0 + 1 < hd.nb)))
+                dir_first = reinterpret_cast<const u32*>(streams + hd.dir_off + 16ull * blk0)[lane];
+            // magnitudes of the codes: P[c] = fl64(P[c-1] * b) walked by one thread into wave 0's (still
+            // unused) payload window, then thread t divides for code t + 1
+            double* P = reinterpret_cast<double*>(s_payall[0]);
+            if (threadIdx.x == 0) power_chain(hd.base, hd.tau, P);
+            __syncthreads();
+            const u32 t = threadIdx.x;
+            u32 m = 0;
+            if (t < hd.tau && hd.sum > 0.0) m = f64_to_f32_bits(hd.sum / P[t + 1u], false);
+            __syncthreads();
+            // tau <= 128: indexed by the code byte, magnitudes below, the same with the sign set above;
+            // beyond that: the 256 magnitudes, the sign is added from the token's top bit
+            if (hd.tau > 128u) {
+                if (t < 256u) s_V[t] = m;
+            } else if (t < 128u) {
+                s_V[t] = m;
+                s_V[t + 128u] = m | 0x80000000u;
+            }
+            cur_seg = 0;
+            __syncthreads();
+        }
+    } else {
+        item_hi = ctrl->total_items;
+        if (MODE != kStore && item_hi) { item_lo = segs[only].item_begin; item_hi = item_lo + segs[only].nb; }
+    }
 
-    for (u64 item = item_lo + (u64)blockIdx.x * kWaves + w; item < item_hi; item += (u64)gridDim.x * kWaves) {
-        const u32 seg = MODE != kStore ? only : ((n_segments == 1) ? 0u : uniform(find_dec_segment(segs, n_segments, item)));
-        const DecSeg* ds = &segs[seg];
-        const u32 KB = uniform(ds->KB), l = uniform(ds->l), tau = uniform(ds->tau), nb = uniform(ds->nb);
-        const u64 d = ds->d;
-        const u32 blk = uniform((u32)(item - ds->item_begin));
-        const u32 first = blk * KB;
-        const u32 cnt = uniform((u32)((d - first < KB) ? d - first : KB));
-        const u32 nsub = (cnt + kSub - 1) / kSub;
-        if (seg != cur_seg) {
+    const u64 item_first = item_lo + (u64)blockIdx.x * WAVES + w;
+    for (u64 item = item_first; item < item_hi; item += (u64)gridDim.x * WAVES) {
+        const u32 seg = (INLINE || n_segments == 1) ? 0u : (MODE != kStore ? only : uniform(find_dec_segment(segs, n_segments, item)));
+        if (!INLINE && seg != cur_seg) {
+            const DecSeg* ds = &segs[seg];
+            hd.KB = uniform(ds->KB); hd.l = uniform(ds->l); hd.tau = uniform(ds->tau); hd.nb = uniform(ds->nb);
+            hd.d = uniform64(ds->d);
+            hd.dir_off = uniform64(ds->dir_off); hd.blocks_off = uniform64(ds->blocks_off);   // (absolute in a batch)
+            hd.total_words = uniform64(ds->total_words);
+            stream_begin = uniform64(ds->stream_begin); pair_begin = uniform64(ds->pair_begin);
+            seg_item_begin = uniform64(ds->item_begin);
             wave_lds_sync();
             // tau <= 128: indexed by the code byte, magnitudes below, the same with the sign set above;
             // beyond that: the 256 magnitudes, the sign is added from the token's top bit
-            const bool wide = tau > 128u;
+            const bool wide = hd.tau > 128u;
             const u32 m0 = ds->V[lane], m1 = ds->V[lane + 64];
             const u32 m2 = ds->V[lane + (wide ? 128u : 0u)], m3 = ds->V[lane + (wide ? 192u : 64u)];
             s_V[lane] = m0;
@@ -484,45 +580,78 @@ k_decode(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u
             cur_seg = seg;
             wave_lds_sync();
         }
+        const u32 KB = hd.KB, l = hd.l, tau = hd.tau, nb = hd.nb;
+        const u64 d = hd.d;
+        const u32 blk = uniform((u32)(item - seg_item_begin));
+        const u32 first = blk * KB;
+        const u32 cnt = uniform((u32)((d - first < KB) ? d - first : KB));
+        const u32 nsub = (cnt + kSub - 1) / kSub;
         // directory entry of the block and of the next one, checked against each other
-        const u32* dir = reinterpret_cast<const u32*>(streams + ds->dir_off + 16ull * blk);
+        const u32* dir = reinterpret_cast<const u32*>(streams + hd.dir_off + 16ull * blk);
         const bool has_next = blk + 1 < nb;
-        const u32 dword = (lane < 4 || (lane < 8 && has_next)) ? dir[lane] : 0u;
+        u32 dword;
+        if (INLINE && item == item_first) dword = dir_first;
+        else dword = (lane < 4 || (lane < 8 && has_next)) ? dir[lane] : 0u;
         const u32 off8 = read_lane(dword, 0), preKey = read_lane(dword, 1), M = read_lane(dword, 2);
         const u32 pbits = read_lane(dword, 3), next_off8_dir = read_lane(dword, 4), next_pre = read_lane(dword, 5);
-        const u64 total_words = ds->total_words;
+        const u64 total_words = hd.total_words;
         const u64 next_off8 = has_next ? (u64)next_off8_dir : total_words;
         const u32 fwords = (cnt * l + 63u) >> 6, pwords = (pbits + 63u) >> 6;
         bool bad = (M < 1 || M > 32) || (pbits > cnt * 32u) || ((u64)off8 + fwords + pwords != next_off8) ||
                    ((u64)off8 + fwords + pwords > total_words) || (blk == 0 && (off8 != 0 || preKey != 0));
+        bool too_big = false;
         if (!bad) {
-            const u32* fsrc = reinterpret_cast<const u32*>(streams + uniform64(ds->blocks_off + 8ull * off8));   // flags plane
+            const u32* fsrc = reinterpret_cast<const u32*>(streams + uniform64(hd.blocks_off + 8ull * off8));   // flags plane
             const u32* psrc = fsrc + 2u * fwords;                                                              // payload plane
             const u32 pw_total = 2u * pwords;
             const u32 cwid = uniform(code_width(tau));                 // bits of a value token
-            const uint8_t* codes = streams + uniform64(ds->stream_begin + kHeaderBytes + (u64)(first >> 3) * cwid);
-            const u64 out0 = uniform64(ds->pair_begin + first);
+            const uint8_t* codes = streams + uniform64(stream_begin + kHeaderBytes + (u64)(first >> 3) * cwid);
+            const u64 out0 = uniform64(pair_begin + first);
             u32 pbit = 0;                  // payload bits consumed by the rounds before
             u32 carry = preKey;            // key before the round in hand
-            bool ok = true, too_big = false;
+            bool ok = true;
             for (u32 sub = 0; sub < nsub && ok; ++sub) {
                 const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
+                // the lane number as a value of this round: keeps the dozens of shared-memory addresses derived
+                // from it from being computed once and held in registers across the whole kernel
+                u32 lane_r = lane;
+                asm volatile("" : "+v"(lane_r));
                 u32* kd = MODE != kStore ? nullptr : keys_out + out0 + sub * kSub;
                 float* vd = MODE != kStore ? nullptr : values_out + out0 + sub * kSub;
+                const bool stream_start = (blk == 0 && sub == 0);       // the round holds the stream's first key
                 if (n == kSub)
                     ok = decode_round<true, MODE>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * (kSub / 8u) * cwid, n, l, M,
-                                                   tau, cwid, pbits, pbit, carry, lane, s_pay, s_flg, s_cod, s_V, kd, vd, dense, dense_len,
-                                                   adam, too_big);
+                                                   tau, cwid, pbits, pbit, carry, lane_r, s_pay, s_flg, s_cod, s_V, kd, vd, dense, dense_len,
+                                                   adam, too_big, stream_start);
                 else
                     ok = decode_round<false, MODE>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * (kSub / 8u) * cwid, n, l, M,
-                                                    tau, cwid, pbits, pbit, carry, lane, s_pay, s_flg, s_cod, s_V, kd, vd, dense, dense_len,
-                                                    adam, too_big);
+                                                    tau, cwid, pbits, pbit, carry, lane_r, s_pay, s_flg, s_cod, s_V, kd, vd, dense, dense_len,
+                                                    adam, too_big, stream_start);
             }
             bad = !ok || (pbit != pbits) || (has_next && carry != next_pre);
-            if (!bad && too_big && lane == 0)
-                dec_fail(ctrl, FASTSGD_ERR_BUFFER_TOO_SMALL, out_status, out_counts, n_counts);
         }
-        if (bad && lane == 0) dec_fail(ctrl, FASTSGD_ERR_CORRUPT_STREAM, out_status, out_counts, n_counts);
+        if ((bad || too_big) && lane == 0) {
+            const u32 code = bad ? FASTSGD_ERR_CORRUPT_STREAM : FASTSGD_ERR_BUFFER_TOO_SMALL;
+            if (INLINE) atomicCAS(&done->fail, 0u, code);
+            else dec_fail(ctrl, code, out_status, out_counts, n_counts);
+        }
+    }
+    if (INLINE) {
+        // (the barrier also waits for the memory operations of every wave of the workgroup, so a failure
+        // word is in place before the workgroup counts itself)
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const u32 n_groups = n_work < kDoneGroups ? n_work : kDoneGroups;
+            const u32 g = blockIdx.x % kDoneGroups;
+            const u32 members = (n_work - g + kDoneGroups - 1u) / kDoneGroups;        // workgroups b < n_work with b mod 16 = g
+            if (atomicInc(&done->group[g][0], members - 1u) == members - 1u &&        // (wraps to 0 with the last one)
+                atomicInc(&done->top, n_groups - 1u) == n_groups - 1u) {
+                const u32 fail = atomicExch(&done->fail, 0u);
+                const u32 status = head_status ? head_status : fail;
+                *out_status = status;
+                out_counts[0] = status ? 0ull : hd.d;
+            }
+        }
     }
 }
 

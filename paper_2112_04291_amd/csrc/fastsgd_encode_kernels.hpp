@@ -55,7 +55,7 @@ __device__ __forceinline__ void load_tile(const float* __restrict__ values, cons
     if (g.full) {
 #pragma unroll
         for (u32 r = 0; r < 4; ++r) {
-            const uint4 q = *reinterpret_cast<const uint4*>(values + g.tile0 + slot0 + r * 256u);
+            const uint4 q = load_stream16(values + g.tile0 + slot0 + r * 256u);
             bits[r][0] = q.x; bits[r][1] = q.y; bits[r][2] = q.z; bits[r][3] = q.w;
         }
     } else {

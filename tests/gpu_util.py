@@ -40,7 +40,7 @@ def hip_decompress(stream, capacity, bufs=None, p=None):
     vals_out = torch.empty(max(capacity, 1), dtype=torch.float32, device="cuda")
     count = torch.full((2,), -1, dtype=torch.int64, device="cuda")
     status = torch.full((2,), -1, dtype=torch.int32, device="cuda")
-    ws = torch.empty(B.decompress_workspace_size(1) // 8 + 32, dtype=torch.int64, device="cuda")
+    ws = B.decoder_workspace(1)
     rc = B.decompress(dev, s.size, keys_out, vals_out, count, status, ws, capacity=capacity)
     torch.cuda.synchronize()
     if rc != B.OK:
@@ -80,7 +80,7 @@ def hip_decompress_segmented(blob, stream_offsets, capacity):
     vals_out = torch.empty(max(capacity, 1), dtype=torch.float32, device="cuda")
     po = torch.full((nseg + 1,), -1, dtype=torch.int64, device="cuda")
     status = torch.full((2,), -1, dtype=torch.int32, device="cuda")
-    ws = torch.empty(B.decompress_workspace_size(nseg) // 8 + 32, dtype=torch.int64, device="cuda")
+    ws = B.decoder_workspace(nseg)
     rc = B.lib().fastsgd_decompress_segmented(B._p(dev), s.size, B._p(so), nseg, B._p(keys_out), B._p(vals_out),
                                               int(capacity), B._p(po), B._p(status), B._p(ws),
                                               ws.numel() * 8, B._stream())

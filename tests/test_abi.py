@@ -1,4 +1,4 @@
-"""The C-ABI library loads and exports every symbol include/fastsgd.h declares; host-only entry
+"""The C-ABI library loads and exports every symbol include/*.h declares; host-only entry
 points agree with the oracle's closed forms.  No GPU needed (no compute call is made)."""
 import ctypes
 import os
@@ -12,9 +12,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "fastsgd.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(fastsgd_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names.update(re.findall(r"\b(fastsgd_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_expected_entry_points():

@@ -23,7 +23,7 @@ def hip_adam(st, theta, m, v, eta, b1=0.9, b2=0.999, eps=1e-8):
     t, mm, vv = (torch.from_numpy(a.copy()).cuda() for a in (theta, m, v))
     count = torch.full((2,), -1, dtype=torch.int64, device="cuda")
     status = torch.full((2,), -1, dtype=torch.int32, device="cuda")
-    ws = torch.empty(B.decompress_workspace_size(1) // 8 + 32, dtype=torch.int64, device="cuda")
+    ws = B.decoder_workspace(1)
     rc = B.decompress_adam(dev, s.size, t, mm, vv, eta, b1, b2, eps, count, status, ws)
     torch.cuda.synchronize()
     return rc, int(status[0]), int(count[0]), t.cpu().numpy(), mm.cpu().numpy(), vv.cpu().numpy()
@@ -75,3 +75,10 @@ def test_adam_errors_match_oracle():
     assert not t.any() and not m.any() and not v.any()
     rc, *_ = hip_adam(st, *z, 0.1, b1=1.5)
     assert rc == B.ERR_INVALID_ARG
+    # a stream in which a key repeats its predecessor would make the update depend on the order of the lanes
+    from tests.streamparse import with_zero_delta
+    for rank in (1, 500, k.size - 1):
+        bad = with_zero_delta(st, rank)
+        assert ref.decompress_adam(bad, *[a.copy() for a in z], 0.1)[0] == ref.ERR_CORRUPT_STREAM
+        rc, status, cnt, *_ = hip_adam(bad, *z, 0.1)
+        assert rc == B.OK and status == B.ERR_CORRUPT_STREAM and cnt == 0, rank

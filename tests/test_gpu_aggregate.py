@@ -19,7 +19,7 @@ def hip_accumulate(blob, offs, dense):
     dd = torch.from_numpy(dense.copy()).cuda()
     count = torch.full((2,), -1, dtype=torch.int64, device="cuda")
     status = torch.full((2,), -1, dtype=torch.int32, device="cuda")
-    ws = torch.empty(B.decompress_workspace_size(n) // 8 + 32, dtype=torch.int64, device="cuda")
+    ws = B.decoder_workspace(n)
     rc = B.decompress_accumulate(dev, s.size, so, n, dd, count, status, ws)
     torch.cuda.synchronize()
     return rc, int(status[0]), int(count[0]), dd.cpu().numpy()
@@ -54,6 +54,20 @@ def test_aggregate_errors_match_oracle():
     assert ref.decompress_accumulate(bad, offs, np.zeros(top + 1, np.float32))[0] == ref.ERR_CORRUPT_STREAM
     rc, status, cnt, _ = hip_accumulate(bad, offs, np.zeros(top + 1, np.float32))
     assert rc == B.OK and status == B.ERR_CORRUPT_STREAM and cnt == 0
+
+
+def test_aggregate_rejects_a_stream_that_repeats_a_key():
+    from paper_2112_04291_amd import binding as B
+    from tests.streamparse import with_zero_delta
+    blob, offs, pairs = worker_streams(3, 50_000, 10_000, 0.5, 12)
+    top = max(int(k.max()) for k, _ in pairs)
+    second = blob[int(offs[1]):int(offs[2])]
+    for rank in (1, 700, pairs[1][0].size - 1):
+        bad = blob.copy()
+        bad[int(offs[1]):int(offs[2])] = with_zero_delta(second, rank)
+        assert ref.decompress_accumulate(bad, offs, np.zeros(top + 1, np.float32))[0] == ref.ERR_CORRUPT_STREAM
+        rc, status, cnt, _ = hip_accumulate(bad, offs, np.zeros(top + 1, np.float32))
+        assert rc == B.OK and status == B.ERR_CORRUPT_STREAM and cnt == 0, rank
 
 
 def test_aggregate_of_streams_with_narrow_and_nine_bit_tokens():

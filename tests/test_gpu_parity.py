@@ -218,6 +218,65 @@ def test_corrupt_streams_are_rejected_on_device():
     assert status == B.ERR_CORRUPT_STREAM
 
 
+def test_a_stream_that_repeats_a_key_is_rejected_on_device():
+    """A delta of 0 anywhere but at the stream's first key (Eq. 4 is over distinct keys): same verdict as
+    the oracle, at the first key of a lane, inside a lane, at a round's and a block's first key."""
+    torch, B, G = _gpu()
+    from tests.streamparse import with_zero_delta
+    rng = np.random.default_rng(77)
+    keys = np.concatenate([[0], np.cumsum(rng.integers(1, 60, 5000))]).astype(np.uint32)
+    rc, st = ref.compress(keys, np.full(keys.size, 1.0, np.float32), ref.params(1.1, 128, 2, 2048))
+    assert rc == 0 and ref.decompress(st)[0] == ref.OK
+    rc, status, k, v = G.hip_decompress(st, capacity=keys.size)
+    assert status == 0 and np.array_equal(k, keys)          # key 0 first: a delta of 0 at rank 0 is fine
+    for rank in (1, 15, 16, 17, 1023, 1024, 2047, 2048, 2049, 4999, 5000):
+        bad = with_zero_delta(st, rank)
+        assert ref.decompress(bad)[0] == ref.ERR_CORRUPT_STREAM
+        rc, status, k, v = G.hip_decompress(bad, capacity=keys.size)
+        assert rc == B.OK and status == B.ERR_CORRUPT_STREAM and k.size == 0, rank
+
+
+def test_decoder_workspace_is_left_clear_after_every_call():
+    """The decoder's control words are cleared once and must come back clear from every call, also from one
+    that fails: good, corrupt, too small, good again on ONE workspace, every verdict the oracle's."""
+    torch, B, G = _gpu()
+    from tests.streamparse import with_zero_delta
+    rng = np.random.default_rng(5)
+    n = 300_000
+    keys = np.cumsum(rng.integers(1, 9, n)).astype(np.uint32)
+    vals = rng.laplace(0, 1e-3, n).astype(np.float32)
+    rc, st = ref.compress(keys, vals, ref.params(W.solve_base(vals, 0.3, 100), 100))
+    assert rc == 0
+    rc_ref, k_ref, v_ref = ref.decompress(st)
+    d = k_ref.size
+    bad = st.copy()
+    bad[64 + 16 * (d // 32)] |= 0x7F                          # code 128 > tau = 100 in the middle of the value plane
+    assert ref.decompress(bad)[0] == ref.ERR_CORRUPT_STREAM
+    ws = B.decoder_workspace(1)
+    keys_out = torch.empty(d, dtype=torch.int32, device="cuda")
+    vals_out = torch.empty(d, dtype=torch.float32, device="cuda")
+    count = torch.zeros(2, dtype=torch.int64, device="cuda")
+    status = torch.zeros(2, dtype=torch.int32, device="cuda")
+
+    def run(stream, cap):
+        dev = torch.from_numpy(np.concatenate([stream, np.zeros((-stream.size) % 8 + 8, np.uint8)])).cuda()
+        count.fill_(-1)
+        status.fill_(-1)
+        assert B.decompress(dev, stream.size, keys_out, vals_out, count, status, ws, capacity=cap) == B.OK
+        torch.cuda.synchronize()
+        return int(status[0]), int(count[0])
+
+    for _ in range(2):
+        assert run(st, d) == (0, d)
+        assert np.array_equal(keys_out.cpu().numpy().view(np.uint32), k_ref)
+        assert run(bad, d) == (B.ERR_CORRUPT_STREAM, 0)
+        assert run(st, d - 1) == (B.ERR_BUFFER_TOO_SMALL, 0)
+        assert run(st[:40], d) == (B.ERR_CORRUPT_STREAM, 0)
+        assert run(with_zero_delta(st, d - 1), d) == (B.ERR_CORRUPT_STREAM, 0)
+    assert run(st, d) == (0, d)
+    assert not ws[:512].any()                                 # the 4096 bytes of control words
+
+
 def test_values_on_bucket_boundaries_and_granule_bounds():
     """Elements exactly on, one ulp below and one ulp above every boundary (exact powers of two by
     construction), scattered so that many granules (32 values, the unit the value pass skips by) hold a single borderline element: the row-skip
