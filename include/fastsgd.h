@@ -100,6 +100,24 @@ fastsgd_status fastsgd_compress(const uint32_t* d_keys, const float* d_values, u
                                 uint64_t* d_out_bytes, uint32_t* d_status,
                                 void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* fastsgd_compress for callers that cannot allocate or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same stream byte for
+ * byte, but the workspace is a fixed array of FASTSGD_STATIC_SCRATCH_BYTES inside the library (one per
+ * GPU, held until the process ends).  The call allocates nothing on host or device.
+ *   n                  at most FASTSGD_STATIC_MAX_ELEMS, else FASTSGD_ERR_BUFFER_TOO_SMALL is returned
+ *                      and nothing is enqueued
+ * Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU (different streams,
+ * or graph launches in flight together) race and give undefined streams; calls on one stream, or otherwise
+ * ordered, are fine -- each call clears the control words it relies on.  The first call on a device looks
+ * the array's address up (no stream work); make it outside any graph capture.
+ * Returns FASTSGD_ERR_DEVICE if that lookup fails. */
+#define FASTSGD_STATIC_MAX_ELEMS 1048576ull
+#define FASTSGD_STATIC_SCRATCH_BYTES (8u << 20)
+fastsgd_status fastsgd_compress_static(const uint32_t* d_keys, const float* d_values, uint64_t n,
+                                       const fastsgd_params* p,
+                                       void* d_out, size_t out_capacity,
+                                       uint64_t* d_out_bytes, uint32_t* d_status, void* hip_stream);
+
 /* Decoder (Section 3.1, phases 1-4) of one stream.
  *   d_stream           device, stream_bytes bytes, 8-byte aligned
  *   d_keys_out, d_values_out   device, `capacity` entries each; receive the d surviving pairs

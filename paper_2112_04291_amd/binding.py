@@ -16,7 +16,7 @@ OK, ERR_INVALID_ARG, ERR_BUFFER_TOO_SMALL, ERR_NONFINITE, ERR_UNSORTED_KEYS, ERR
 STATUS_NAMES = ["OK", "INVALID_ARG", "BUFFER_TOO_SMALL", "NONFINITE", "UNSORTED_KEYS", "CORRUPT_STREAM", "DEVICE"]
 
 EXPORTS = ["fastsgd_compressed_size", "fastsgd_workspace_size", "fastsgd_decompress_workspace_size",
-           "fastsgd_compress", "fastsgd_decompress", "fastsgd_compress_segmented", "fastsgd_decompress_segmented",
+           "fastsgd_compress", "fastsgd_compress_static", "fastsgd_decompress", "fastsgd_compress_segmented", "fastsgd_decompress_segmented",
            "fastsgd_decompress_accumulate", "fastsgd_decompress_adam",
            "fastsgd_profile_compress", "fastsgd_profile_decompress", "fastsgd_probe_read"]
 COMPRESS_KERNELS = ["abs_sum", "tables", "encode_values", "measure_keys", "pack_keys"]
@@ -59,6 +59,8 @@ def lib():
         L.fastsgd_decompress_workspace_size.restype = sz
         L.fastsgd_compress.argtypes = [vp, vp, u64, PP, vp, sz, vp, vp, vp, sz, vp]
         L.fastsgd_compress.restype = C.c_int
+        L.fastsgd_compress_static.argtypes = [vp, vp, u64, PP, vp, sz, vp, vp, vp]
+        L.fastsgd_compress_static.restype = C.c_int
         L.fastsgd_decompress.argtypes = [vp, sz, vp, vp, u64, vp, vp, vp, sz, vp]
         L.fastsgd_decompress.restype = C.c_int
         L.fastsgd_compress_segmented.argtypes = [vp, vp, C.POINTER(u64), u32, PP, u32, vp, sz, vp, vp, vp, sz, vp]
@@ -106,6 +108,17 @@ def compress(keys, values, p, out, out_bytes, status, workspace, n=None, out_cap
     cap = out.numel() * out.element_size() if out_capacity is None else int(out_capacity)
     return lib().fastsgd_compress(_p(keys), _p(values), n, C.byref(p), _p(out), cap, _p(out_bytes), _p(status),
                                   _p(workspace), workspace.numel() * workspace.element_size(), _stream())
+
+
+STATIC_MAX_ELEMS = 1 << 20
+
+
+def compress_static(keys, values, p, out, out_bytes, status, n=None, out_capacity=None):
+    """fastsgd_compress_static: fastsgd_compress on the library's own fixed workspace (n <= STATIC_MAX_ELEMS)."""
+    n = values.numel() if n is None else int(n)
+    cap = out.numel() * out.element_size() if out_capacity is None else int(out_capacity)
+    return lib().fastsgd_compress_static(_p(keys), _p(values), n, C.byref(p), _p(out), cap, _p(out_bytes), _p(status),
+                                         _stream())
 
 
 def decompress(stream, stream_bytes, keys_out, values_out, count, status, workspace, capacity=None):

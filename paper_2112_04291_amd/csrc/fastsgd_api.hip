@@ -1,6 +1,7 @@
 // C ABI of the gfx950 FastSGD codec: argument checks, workspace carve-up, kernel launches.
 // Every entry point only enqueues work on the caller's stream.
 #include <atomic>
+#include <mutex>
 #include <vector>
 
 #include "fastsgd_device.hpp"
@@ -405,6 +406,34 @@ static fastsgd_status profile_loop(u32 n_kernels, u32 iterations, float* kernel_
 
 }  // namespace fsgd
 
+// Workspace of fastsgd_compress_static: one array per GPU the library runs on, held until the process
+// ends.  Host code never uses the array's name as an address: the device address is looked up once per
+// device (static_scratch) and passed to the kernels like any caller's workspace.
+static __device__ __align__(256) unsigned char scratch[FASTSGD_STATIC_SCRATCH_BYTES];
+
+namespace fsgd {
+
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[64];                                    // per device, nullptr until looked up
+
+// Device address of `scratch` on the current device, or nullptr (unknown device, lookup failed).
+static void* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+}  // namespace fsgd
+
 using namespace fsgd;
 
 extern "C" {
@@ -452,6 +481,19 @@ fastsgd_status fastsgd_compress(const uint32_t* d_keys, const float* d_values, u
     const u64 offs[2] = {0, n};
     return compress_impl(d_keys, d_values, offs, 1, p, 0, d_out, out_capacity, d_out_bytes, d_status, d_workspace,
                          workspace_bytes, hip_stream, true);
+}
+
+fastsgd_status fastsgd_compress_static(const uint32_t* d_keys, const float* d_values, uint64_t n,
+                                       const fastsgd_params* p, void* d_out, size_t out_capacity,
+                                       uint64_t* d_out_bytes, uint32_t* d_status, void* hip_stream) {
+    if (n > FASTSGD_STATIC_MAX_ELEMS) return FASTSGD_ERR_BUFFER_TOO_SMALL;      // beyond what the fixed workspace holds
+    if (!params_ok(p)) return FASTSGD_ERR_INVALID_ARG;
+    if (make_plan(FASTSGD_STATIC_MAX_ELEMS, 1, 256).total > FASTSGD_STATIC_SCRATCH_BYTES) return FASTSGD_ERR_DEVICE;
+    void* ws = static_scratch();
+    if (!ws) return FASTSGD_ERR_DEVICE;
+    const u64 offs[2] = {0, n};
+    return compress_impl(d_keys, d_values, offs, 1, p, 0, d_out, out_capacity, d_out_bytes, d_status, ws,
+                         FASTSGD_STATIC_SCRATCH_BYTES, hip_stream, true);
 }
 
 fastsgd_status fastsgd_profile_compress(const uint32_t* d_keys, const float* d_values, uint64_t n,
