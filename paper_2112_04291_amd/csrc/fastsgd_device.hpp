@@ -56,7 +56,8 @@ struct SegState {
     u64 d;              // survivors
     u64 item_begin;     // first work item (key block) of the segment
     u64 unit_begin;     // first work unit (kWaves key blocks of one segment) of the segment
-    u64 pad;
+    float lg_sum;       // log2(sum) and 1 / log2(b) in binary32: the value pass's first guess of a code,
+    float inv_lg_base;  //   (lg_sum - log2|v|) * inv_lg_base ~ log_b(sum / |v|)
     u32 B[kMaxTau];     // B[c-1] = bit pattern of the boundary of code c
 };
 

@@ -357,6 +357,9 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
         if (bad) set_status(ctrl, FASTSGD_ERR_NONFINITE);
         st->sum = bad ? 0.0 : sum;
         s_sum = bad ? 0.0 : sum;
+        // for the value pass's first guess of a code, ceil(log_b(sum / |v|)) in binary32
+        st->lg_sum = (sum > 0.0 && !bad) ? (float)log2(sum) : 0.0f;
+        st->inv_lg_base = (float)(1.0 / log2(info.base));
     }
     __syncthreads();
     const double sum = s_sum;
@@ -386,18 +389,22 @@ k_tables(const SegInfo* __restrict__ segs, SegState* __restrict__ states, const 
 // The chunk's survivor count goes to ccount[chunk].  Global ranks are never materialised: k_plan_segments
 // turns the (at most 4096) chunk counts of a segment into their scan and the key encoder gathers through
 // that scan.
-constexpr u32 kStage = 1024;             // staged survivors per wave (a ring)
+constexpr u32 kStage = 1024;             // staged survivors per wave (a ring of 8-byte entries)
 constexpr u32 kRing = 512;               // ring of granules per wave: under a batch left over plus 256 from a top-up
 constexpr u32 kValWaves = 4;             // waves per workgroup of the value encoder (they never synchronise)
-constexpr u32 kGather = 4;               // key fetches a lane keeps in flight
+constexpr u32 kGather = 4;               // survivors a lane handles per round of a flush: four CONSECUTIVE ones
 static_assert((kRing & (kRing - 1)) == 0 && kRing >= kRowGranules * kValRows - 1 + 4 * 64, "ring: a short batch plus 256 granules");
 static_assert(kMaxChunkRows * kRowGranules <= 65536 && kMaxChunkRows % kValRows == 0 && kRowGranules % 4 == 0,
               "ring entries are 16 bits; bounds come in groups of four");
 constexpr u32 kRound = 64 * kGather;     // survivors per round of a flush
-constexpr u32 kMaxRounds = kStage / kRound;
 static_assert((kStage & (kStage - 1)) == 0 && kStage % kRound == 0 && kStage >= 2 * kRow + kRound,
               "stage: a power of two, whole rounds, a forced flush sends at least one");
 static_assert(4 * kMaxTau + 8 * kStage + 2 * kRing <= 10240, "shared memory for sixteen waves per compute unit");
+#ifndef FSGD_DENSE_ROWS
+#define FSGD_DENSE_ROWS 2
+#endif
+static_assert(FSGD_DENSE_ROWS * kRow + kRound <= kStage, "a batch of rows on top of what a flush leaves");
+constexpr u32 kDenseNum = 3, kDenseDen = 4;   // a chunk is walked row by row if this share of its granules can hold a survivor
 
 // |v| >= threshold as a float compare with the |x| source modifier: for non-negative finite floats
 // (denormals are preserved in this build) it orders exactly like the unsigned compare of the bit
@@ -406,8 +413,8 @@ __device__ __forceinline__ bool keeps(u32 value_bits, float threshold) {
     return __builtin_fabsf(__uint_as_float(value_bits)) >= threshold;
 }
 
-__device__ __forceinline__ u32 lanes_below(u64 mask) {
-    return __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
+__device__ __forceinline__ u32 lanes_below(u64 mask, u32 add) {
+    return __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, add));
 }
 
 struct Chunk {           // wave-uniform description of the chunk a wave owns
@@ -439,220 +446,451 @@ __device__ __forceinline__ Chunk chunk_geom(const SegInfo* __restrict__ segs, u3
     return c;
 }
 
+// What a wave of the value pass knows about its chunk and its call (wave-uniform unless said otherwise).
+struct ValueCtx {
+    Chunk ck;
+    u32 lane;                          // (per lane)
+    const u32* s_B;                    // shared memory: [c - 1] = boundary of code c
+    uint2* s_ent;                      // shared memory: staged survivors (value bits, tag), a ring of kStage
+    uint16_t* s_ring;                  // shared memory: granules still to be read
+    u32 thr, tau;
+    float thr_f, lg_sum, inv_lg_base;
+    const u32* keys;                   // the call's key array (nullptr: keys are the indices) ...
+    const float* values;               // ... and value array, both counted from the aligned base
+    const u32* ckeys;                  // the chunk's first key / value
+    const float* cvals;
+    u32 key0;                          // key of the chunk's first element where keys are the indices
+    const uint2* crmax;                // the chunk's granule bounds, in groups of four
+    u32 nwords;                        // ... and how many groups
+    u32* skeys;
+    void* scodes;
+};
+
+// which of the four bounds of a group reach the threshold (unsigned compare of bit patterns: the same
+// order as the float compare, and nothing passes the keep-nothing threshold)
+__device__ __forceinline__ u32 live_bits(uint2 x, u32 thr) {
+    return ((x.x << 16) >= thr ? 1u : 0u) | ((x.x & 0xFFFF0000u) >= thr ? 2u : 0u) |
+           ((x.y << 16) >= thr ? 4u : 0u) | ((x.y & 0xFFFF0000u) >= thr ? 8u : 0u);
+}
+
+// One chunk of the second value pass; returns the number of its survivors (in the scratch arrays when the
+// function returns).
+//
+// Survivors wait in a ring of (value bits, tag) entries in the wave's shared memory, in element order; the
+// tag is the survivor's key where that is known when it is staged (BY_ROWS, or IMPLICIT: no key array) and
+// its element offset in the chunk otherwise (its key is then fetched when it leaves).  They leave in rounds
+// of 256, four consecutive ones to a lane: code by a first guess from the binary logarithm of |v| checked
+// against the boundary table (two probes; a binary search over the table where the probes do not bracket the
+// value), the lane's four codes in one store, its four keys in another.
+//
+// BY_ROWS: most granules of the chunk can hold a survivor, so the chunk is read row by row, keys alongside the
+// values, everything coalesced.  Otherwise granule by granule: only the granules that can hold a survivor, as
+// one ascending stream.
 // WIDE: some segment of the call has tau > 128; then every survivor's scratch code takes 16 bits (sign
 // in bit 15) instead of 8 (sign in bit 7), and the boundary table has up to 256 entries.
+template <bool WIDE, bool BY_ROWS, bool IMPLICIT>
+__device__ __forceinline__ u32 encode_chunk(const ValueCtx& cx) {
+    typedef typename ScratchCode<WIDE>::type CodeT;
+    constexpr bool TAG_IS_KEY = BY_ROWS || IMPLICIT;
+    CodeT* __restrict__ scodes = static_cast<CodeT*>(cx.scodes);
+    u32* __restrict__ skeys = cx.skeys;
+    const Chunk& ck = cx.ck;
+    const u32 lane = cx.lane, thr = cx.thr, tau = cx.tau;
+    const float thr_f = cx.thr_f, lg_sum = cx.lg_sum, inv_lg_base = cx.inv_lg_base;
+    const u32* s_B = cx.s_B;
+    uint2* s_ent = cx.s_ent;
+    const u32* ckeys = cx.ckeys;
+    const float* cvals = cx.cvals;
+    const u32 key0 = cx.key0;
+    u32 cbase = 0;                           // survivors of the chunk already in the scratch arrays
+    u32 staged = 0;                          // survivors waiting in shared memory
+    u32 first = 0;                           // ring position of the oldest staged survivor (a multiple of kRound)
+
+    // A round of (up to) kRound staged survivors -> scratch arrays.  begin() issues the key fetches of the round
+    // that leaves (only where the tags are element offsets), complete() turns values into codes and stores
+    // codes and keys.  Where keys have to be fetched the wave stages the next two rows between the two, whose
+    // loads were issued before the key fetches: the key fetches arrive right behind them instead of being
+    // waited for on their own.  While the chunk goes on only whole rounds leave.
+    u32 pending = 0;                         // staged survivors that are leaving (at most kRound)
+    u32 pk0 = 0, pk1 = 0, pk2 = 0, pk3 = 0;  // its keys, where they had to be fetched
+    auto begin = [&](u32 n_out) {
+        wave_lds_sync();
+        if (!TAG_IS_KEY) {
+            const uint4* e4 = reinterpret_cast<const uint4*>(s_ent + first) + 2u * lane;
+            const uint4 x = e4[0], y = e4[1];
+            const u32 j = kGather * lane;
+            pk0 = (j + 0u < n_out) ? ckeys[x.y] : 0u;
+            pk1 = (j + 1u < n_out) ? ckeys[x.w] : 0u;
+            pk2 = (j + 2u < n_out) ? ckeys[y.y] : 0u;
+            pk3 = (j + 3u < n_out) ? ckeys[y.w] : 0u;
+        }
+        pending = n_out;
+    };
+    // the lane's four survivors of the round that leaves: how many of them exist, their codes (sign on top of
+    // code - 1, as the scratch array holds them) and keys
+    auto round_codes = [&](u32 n_out, u32& have, u32 (&cd)[kGather], u32 (&key)[kGather]) {
+        const uint4* e4 = reinterpret_cast<const uint4*>(s_ent + first) + 2u * lane;
+        const uint4 x = e4[0], y = e4[1];
+        const u32 vb[kGather] = {x.x, x.z, y.x, y.z};
+        key[0] = TAG_IS_KEY ? x.y : pk0; key[1] = TAG_IS_KEY ? x.w : pk1;
+        key[2] = TAG_IS_KEY ? y.y : pk2; key[3] = TAG_IS_KEY ? y.w : pk3;
+        const u32 j = kGather * lane;
+        have = j >= n_out ? 0u : (n_out - j < kGather ? n_out - j : kGather);
+        // codes: a first guess ceil(log_b(sum / |v|)) in binary32, good to a small fraction of a code, checked
+        // against the table (B[c-1] > a >= B[c] settles it); entries beyond the staged ones hold stale bits,
+        // they get the threshold's code and are not stored
+        bool settled = true;
+#pragma unroll
+        for (u32 k = 0; k < kGather; ++k) {
+            const u32 a = k < have ? (vb[k] & 0x7FFFFFFFu) : thr;
+            const float g = (lg_sum - __log2f(__uint_as_float(a))) * inv_lg_base;
+            int ci = (int)__builtin_ceilf(g);
+            ci = ci < 1 ? 1 : (ci > (int)tau ? (int)tau : ci);
+            const u32 c = (u32)ci;
+            const u32 below = s_B[c - 1u], above = s_B[c >= 2u ? c - 2u : 0u];
+            settled = settled & (a >= below) & (c == 1u || a < above);
+            cd[k] = c;
+        }
+        if (__builtin_expect(__any(!settled), 0)) {
+            // somewhere the guess was off (a value next to a boundary, a base next to 1, a denormal): the
+            // smallest code c in [1, tau] with a >= B[c] by binary search (B non-increasing, a >= B[tau])
+#pragma unroll
+            for (u32 k = 0; k < kGather; ++k) {
+                const u32 a = k < have ? (vb[k] & 0x7FFFFFFFu) : thr;
+                u32 lo = 1, hi = tau;
+                while (lo < hi) {
+                    const u32 mid = (lo + hi) >> 1;
+                    if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
+                }
+                cd[k] = lo;
+                __builtin_amdgcn_sched_barrier(0);        // one search at a time
+            }
+        }
+#pragma unroll
+        for (u32 k = 0; k < kGather; ++k) cd[k] = ((vb[k] >> 31) << (WIDE ? 15 : 7)) | (cd[k] - 1u);
+    };
+    auto round_done = [&](u32 n_out) {
+        wave_lds_sync();
+        cbase += n_out;
+        staged -= n_out;
+        first = (first + n_out) & (kStage - 1u);
+    };
+    auto complete = [&]() {
+        const u64 slot = ck.slot0 + cbase;
+        u32 have, cd[kGather], key[kGather];
+        round_codes(pending, have, cd, key);
+        const u32 j = kGather * lane;
+        CodeT* cdst = scodes + slot + j;
+        u32* kdst = skeys + slot + j;
+        if (have == kGather) {
+            if (WIDE) *reinterpret_cast<uint2*>(cdst) = make_uint2(cd[0] | (cd[1] << 16), cd[2] | (cd[3] << 16));
+            else *reinterpret_cast<u32*>(cdst) = cd[0] | (cd[1] << 8) | (cd[2] << 16) | (cd[3] << 24);
+            *reinterpret_cast<uint4*>(kdst) = make_uint4(key[0], key[1], key[2], key[3]);
+        } else {
+#pragma unroll
+            for (u32 k = 0; k < kGather; ++k)
+                if (k < have) { cdst[k] = (CodeT)cd[k]; kdst[k] = key[k]; }
+        }
+        round_done(pending);
+        pending = 0;
+    };
+
+    // one row of four values per lane: masks, and staging if anything survives
+    auto stage_row = [&](const u32 (&row)[4], const u32 (&tag)[4]) {
+        u64 m[4];
+#pragma unroll
+        for (u32 c = 0; c < 4; ++c) m[c] = __ballot(keeps(row[c], thr_f));
+        if ((m[0] | m[1] | m[2] | m[3]) == 0) return;
+        u32 pos = lanes_below(m[3], lanes_below(m[2], lanes_below(m[1], lanes_below(m[0], first + staged))));
+#pragma unroll
+        for (u32 c = 0; c < 4; ++c)
+            if (keeps(row[c], thr_f)) {
+                s_ent[pos & (kStage - 1u)] = make_uint2(row[c], tag[c]);
+                ++pos;
+            }
+        staged += (u32)__popcll(m[0]) + (u32)__popcll(m[1]) + (u32)__popcll(m[2]) + (u32)__popcll(m[3]);
+    };
+    // whole rounds leave at once: under a round stays, so two more rows always fit (kStage = 4 rows)
+    auto flush_rounds = [&]() {
+        while (staged >= kRound) {
+            begin(kRound);
+            complete();
+        }
+    };
+
+    if constexpr (BY_ROWS) {
+        // ---- row by row: row r = elements 256 r + 4 lane .. + 3 of the chunk.  Rows that lie wholly inside
+        // the segment (all but, at most, the chunk's first and last) are fetched through buffer descriptors
+        // that end with the last of them, so that a batch reaching beyond reads zeros -- which never survive --
+        // without a branch; kDenseRows rows are staged while the next kDenseRows are on their way.
+        constexpr u32 kDenseRows = FSGD_DENSE_ROWS;
+        const u32 nrows = ck.nrows;
+        auto row_inside = [&](u32 r) { const u64 e = ck.e0 + (u64)r * kRow; return e >= ck.lo && e + kRow <= ck.hi; };
+        // a row cut by the segment's ends: element by element
+        auto cut_row = [&](u32 r) {
+            u32 vrow[4], tag[4];
+#pragma unroll
+            for (u32 c = 0; c < 4; ++c) {
+                const u32 elem = r * kRow + lane * 4u + c;
+                const u64 ee = ck.e0 + elem;
+                const bool in = ee >= ck.lo && ee < ck.hi;
+                vrow[c] = in ? __float_as_uint(cx.values[ee]) : 0u;       // zero never survives
+                tag[c] = IMPLICIT ? key0 + elem : (in ? cx.keys[ee] : 0u);
+            }
+            stage_row(vrow, tag);
+            flush_rounds();
+        };
+        const u32 rb = row_inside(0) ? 0u : 1u;                               // first and ...
+        const u32 re = (nrows > rb && !row_inside(nrows - 1u)) ? nrows - 1u : nrows;   // ... one past the last whole row
+        if (rb) cut_row(0);
+        if (re > rb) {
+            const u32 nfull = re - rb;
+            const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<float*>(cvals + rb * kRow), 0, (int)(nfull * kRow * 4u), kBufferWord3);
+            const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<u32*>(IMPLICIT ? reinterpret_cast<const u32*>(cvals) : ckeys + rb * kRow), 0, (int)(nfull * kRow * 4u), kBufferWord3);
+            constexpr int kNt = 2;                                             // non-temporal: read once
+            u32 va[kDenseRows][4], ka[kDenseRows][4], vb2[kDenseRows][4], kb2[kDenseRows][4];
+            auto load_batch = [&](u32 (&v)[kDenseRows][4], u32 (&k)[kDenseRows][4], u32 r) {      // rows rb + r ..
+#pragma unroll
+                for (u32 s = 0; s < kDenseRows; ++s) {
+                    const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(lane * 16u), (int)((r + s) * kRow * 4u), kNt);
+                    v[s][0] = q.x; v[s][1] = q.y; v[s][2] = q.z; v[s][3] = q.w;
+                    if (!IMPLICIT) {
+                        const u32x4 kq = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(lane * 16u), (int)((r + s) * kRow * 4u), kNt);
+                        k[s][0] = kq.x; k[s][1] = kq.y; k[s][2] = kq.z; k[s][3] = kq.w;
+                    }
+                }
+            };
+            auto stage_batch = [&](const u32 (&v)[kDenseRows][4], const u32 (&k)[kDenseRows][4], u32 r) {
+#pragma unroll
+                for (u32 s = 0; s < kDenseRows; ++s) {
+                    if (IMPLICIT) {
+                        const u32 t0 = key0 + (rb + r + s) * kRow + lane * 4u;
+                        const u32 tag[4] = {t0, t0 + 1u, t0 + 2u, t0 + 3u};
+                        stage_row(v[s], tag);
+                    } else {
+                        stage_row(v[s], k[s]);
+                    }
+                }
+            };
+            // A whole round leaves, if one is waiting, between the request for the next rows and the wait for
+            // the rows in hand.  Its two stores are issued in any case, through buffer descriptors over the
+            // chunk's scratch entries, with an offset beyond the descriptor's end when no round leaves (the
+            // hardware drops such a store): a wave's loads and stores complete in the order issued, and the
+            // compiler counts how many may still be out when it waits for a load; stores that exist on one
+            // path only would make every such wait also wait for loads that were only just issued.
+            const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(
+                scodes + ck.slot0, 0, (int)(nrows * kRow * (u32)sizeof(CodeT)), kBufferWord3);
+            const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(
+                skeys + ck.slot0, 0, (int)(nrows * kRow * 4u), kBufferWord3);
+            constexpr int kDropped = 0x40000000;                       // an offset no chunk reaches
+            auto round_leaves = [&]() {
+                const bool go = staged >= kRound;
+                const u32 at = cbase;
+                u32 cd[kGather] = {0u, 0u, 0u, 0u}, key[kGather] = {0u, 0u, 0u, 0u};
+                if (go) {
+                    u32 have;
+                    wave_lds_sync();
+                    round_codes(kRound, have, cd, key);
+                    round_done(kRound);
+                }
+                u32x4 kq;
+                kq.x = key[0]; kq.y = key[1]; kq.z = key[2]; kq.w = key[3];
+                if (WIDE) {
+                    typedef u32 u32x2 __attribute__((ext_vector_type(2)));
+                    u32x2 cq;
+                    cq.x = cd[0] | (cd[1] << 16); cq.y = cd[2] | (cd[3] << 16);
+                    __builtin_amdgcn_raw_buffer_store_b64(cq, crs, (int)(lane * 8u), go ? (int)(at * 2u) : kDropped, 0);
+                } else {
+                    __builtin_amdgcn_raw_buffer_store_b32(cd[0] | (cd[1] << 8) | (cd[2] << 16) | (cd[3] << 24), crs,
+                                                          (int)(lane * 4u), go ? (int)at : kDropped, 0);
+                }
+                __builtin_amdgcn_raw_buffer_store_b128(kq, srs, (int)(lane * 16u), go ? (int)(at * 4u) : kDropped, 0);
+            };
+            load_batch(va, ka, 0);
+            for (u32 r = 0; r < nfull; r += 2u * kDenseRows) {
+                load_batch(vb2, kb2, r + kDenseRows);
+                round_leaves();
+                while (staged >= kRound) round_leaves();               // (more than half of the values survive)
+                stage_batch(va, ka, r);
+                load_batch(va, ka, r + 2u * kDenseRows);
+                round_leaves();
+                while (staged >= kRound) round_leaves();
+                stage_batch(vb2, kb2, r + kDenseRows);
+            }
+            flush_rounds();
+        }
+        if (re < nrows) cut_row(nrows - 1u);
+    } else {
+        // ---- granule by granule.  The unit of the fetch is the granule: a batch is eight "virtual rows" of
+        // kRowGranules granules that can hold a survivor, taken in ascending order from wherever they sit, so
+        // that every lane fetches something useful however few granules are in play.
+        // One virtual row: lanes kGranLanes g .. kGranLanes (g + 1) - 1 fetch the g-th of its granules; `elem`
+        // is the chunk-relative element offset of the lane's first element.  Granules cut by the segment's ends
+        // are fetched element by element; elements outside [lo, hi) become zero, which never survives.
+        uint16_t* s_ring = cx.s_ring;
+        const uint2* crmax = cx.crmax;
+        const u32 nwords = cx.nwords;
+        auto load_granules = [&](bool on, u32 elem, u32 (&row)[4]) {
+            const u64 e = ck.e0 + elem;
+            const bool inside = e >= ck.lo && e + 4u <= ck.hi;
+            uint4 q = make_uint4(0u, 0u, 0u, 0u);
+            if (__all(inside || !on)) {
+                if (on) q = *reinterpret_cast<const uint4*>(cvals + elem);
+                row[0] = q.x; row[1] = q.y; row[2] = q.z; row[3] = q.w;
+            } else {
+#pragma unroll
+                for (u32 c = 0; c < 4; ++c) {
+                    const u64 ee = e + c;
+                    row[c] = (on && ee >= ck.lo && ee < ck.hi) ? __float_as_uint(cx.values[ee]) : 0u;
+                }
+            }
+        };
+        auto stage_granules = [&](const u32 (&row)[4], u32 elem) {
+            const u32 t0 = IMPLICIT ? key0 + elem : elem;
+            const u32 tag[4] = {t0, t0 + 1u, t0 + 2u, t0 + 3u};
+            stage_row(row, tag);
+        };
+        // after every two rows of the granule stream; `loads_issued`: the next batch's loads have just been issued
+        auto flush_step = [&](bool loads_issued) {
+            if (pending) complete();
+            while (staged > kStage - 2 * kRow) {                   // no room for two more rows: at once
+                begin(kRound);
+                complete();
+            }
+            if (loads_issued && staged >= kRound) begin(kRound);
+        };
+
+        // The granules (kGranule values, the share of kGranLanes lanes) that can hold a survivor form one
+        // ascending stream over the chunk, kept in a ring in shared memory (entry = index of the granule inside
+        // the chunk).  The ring is topped up 256 granules at a time: lane j compares four bounds, those of the
+        // granules 4 (scanned + j) .. + 3, with the threshold.  The bounds of the 256 granules after those are
+        // fetched meanwhile.
+        uint2 xnext = crmax[lane < nwords ? lane : nwords - 1u];
+        u32 scanned = 0;                          // groups of four bounds whose granules are in the ring or behind it
+        u32 head = 0, tail = 0;                   // granules taken from / put into the ring since the start
+        auto refill = [&]() {
+            const uint2 x = xnext;
+            const u32 word = scanned + lane;
+            scanned += 64u;
+            if (scanned < nwords) {
+                const u32 wn = scanned + lane;
+                xnext = crmax[wn < nwords ? wn : nwords - 1u];
+            }
+            u32 qb = live_bits(x, thr);
+            if (word >= nwords) qb = 0;
+            const u32 mine = (u32)__popc(qb);
+            const u32 incl = wave_incl_scan(mine);
+            u32 at = tail + incl - mine;
+#pragma unroll
+            for (u32 q = 0; q < 4; ++q)
+                if ((qb >> q) & 1u) s_ring[(at++) & (kRing - 1u)] = (uint16_t)((word << 2) | q);
+            tail += read_lane(incl, 63);
+        };
+        // A batch is eight rows of 256 elements in flight, each put together from the next kRowGranules
+        // granules of the stream (lanes kGranLanes k .. kGranLanes (k + 1) - 1 take the k-th of them).
+        constexpr u32 kBatch = kRowGranules * kValRows;
+        auto take = [&](u32 (&elem)[kValRows], u32 (&on)[kValRows]) -> u32 {
+            if (tail - head < kBatch && scanned < nwords) {
+                do refill(); while (tail - head < kBatch && scanned < nwords);
+                wave_lds_sync();
+            }
+            const u32 left = tail - head;
+            const u32 nq = left < kBatch ? left : kBatch;
+#pragma unroll
+            for (u32 slot = 0; slot < kValRows; ++slot) {
+                const u32 i = kRowGranules * slot + lane / kGranLanes;
+                on[slot] = i < nq ? 1u : 0u;
+                const u32 e = on[slot] ? s_ring[(head + i) & (kRing - 1u)] : 0u;
+                elem[slot] = e * kGranule + (lane & (kGranLanes - 1u)) * 4u;
+            }
+            head += nq;
+            return (nq + kRowGranules - 1u) / kRowGranules;
+        };
+        u32 bits[kValRows][4], elem[kValRows], on[kValRows];
+        u32 nr = take(elem, on);
+#pragma unroll
+        for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_granules(on[slot] != 0, elem[slot], bits[slot]);
+        while (nr) {
+#pragma unroll
+            for (u32 pair = 0; pair < kValRows / 2; ++pair) {
+#pragma unroll
+                for (u32 slot = 2 * pair; slot < 2 * pair + 2; ++slot) if (slot < nr) stage_granules(bits[slot], elem[slot]);
+                if (pair + 1 == kValRows / 2) {
+                    // the registers are free: start on the next rows before finishing these
+                    nr = take(elem, on);
+#pragma unroll
+                    for (u32 slot = 0; slot < kValRows; ++slot)
+                        if (slot < nr) load_granules(on[slot] != 0, elem[slot], bits[slot]);
+                }
+                flush_step(pair + 1 == kValRows / 2);
+            }
+        }
+    }
+    if (pending) complete();
+    while (staged) {
+        begin(staged < kRound ? staged : kRound);
+        complete();
+    }
+    return cbase;
+}
+
+// Second pass over the values, one wave per chunk (see encode_chunk).
 template <bool WIDE>
 __global__ void __launch_bounds__(kValWaves * kWave) __attribute__((amdgpu_waves_per_eu(4, 8)))
 k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
                 const SegInfo* __restrict__ segs, const SegState* __restrict__ states, u32 n_segments,
                 u32 n_chunks, u32 R, const uint16_t* __restrict__ rowmax, u32* __restrict__ ccount,
                 u32* __restrict__ skeys, void* __restrict__ scodes_any) {
-    typedef typename ScratchCode<WIDE>::type CodeT;
-    CodeT* __restrict__ scodes = static_cast<CodeT*>(scodes_any);
-    __shared__ u32 s_Ball[kValWaves][WIDE ? kMaxTau : 128];
-    __shared__ u32 s_valall[kValWaves][kStage];
-    __shared__ u32 s_idxall[kValWaves][kStage];
+    constexpr u32 kTable = WIDE ? kMaxTau : 128u;
+    __shared__ u32 s_Ball[kValWaves][kTable];               // [c - 1] = boundary of code c
+    __shared__ __attribute__((aligned(16))) uint2 s_entall[kValWaves][kStage];
     __shared__ uint16_t s_ringall[kValWaves][kRing];        // granules still to be read, in ascending order
     const u32 lane = lane_id();
     const u32 w = uniform(wave_id());
     u32* s_B = s_Ball[w];
-    u32* s_val = s_valall[w];       // staged survivors: value bits ...
-    u32* s_idx = s_idxall[w];       // ... and element offset inside the chunk
-    uint16_t* s_ring = s_ringall[w];
     const u32 chunk = blockIdx.x * kValWaves + w;
     if (chunk >= n_chunks) return;
-    const Chunk ck = chunk_geom(segs, n_segments, chunk, R);
-    const u32 thr = uniform(states[ck.seg].thr_bits);
-    const u32 tau = segs[ck.seg].tau;
+    ValueCtx cx;
+    cx.ck = chunk_geom(segs, n_segments, chunk, R);
+    const SegState* st = &states[cx.ck.seg];
+    cx.lane = lane;
+    cx.s_B = s_B;
+    cx.s_ent = s_entall[w];
+    cx.s_ring = s_ringall[w];
+    cx.thr = uniform(st->thr_bits);
+    cx.tau = segs[cx.ck.seg].tau;
+    cx.thr_f = __uint_as_float(cx.thr);
+    cx.lg_sum = st->lg_sum;
+    cx.inv_lg_base = st->inv_lg_base;
 #pragma unroll
-    for (u32 k = 0; k < (WIDE ? kMaxTau : 128u) / 64u; ++k) s_B[lane + 64u * k] = states[ck.seg].B[lane + 64u * k];
-    const float thr_f = __uint_as_float(thr);
-    const u32* ckeys = keys + ck.e0;
-    const bool implicit = keys == nullptr;                 // dense gradient: the key is the index in the segment
-    const u32 key0 = (u32)(ck.e0 - ck.lo);                 // (wraps for the up to three slots before the segment)
-    const float* cvals = values + ck.e0;
-    // bounds in groups of four (16 bits each): kBoundWords such groups per row
-    constexpr u32 kBoundWords = kRowGranules / 4u;
-    const uint2* crmax = reinterpret_cast<const uint2*>(rowmax) + (u64)ck.row0 * kBoundWords;
-    const u32 nwords = ck.nrows * kBoundWords;
-    u32 cbase = 0;                           // survivors of the chunk already in the scratch arrays
-    u32 staged = 0;                          // survivors waiting in shared memory
-
-    // Staged survivors -> scratch arrays, in rounds of kRound.  The stage is a ring (entry i of the staged
-    // ones sits at (first + i) mod kStage).  A flush has two halves: begin() issues the key fetches of the
-    // rounds that leave, complete() turns values into codes and stores codes and keys.  Between the two
-    // the wave stages the next two rows, whose loads were issued before the key fetches: the key fetches
-    // arrive right behind them instead of being waited for on their own.  While the chunk goes on only
-    // whole rounds leave (every lane of every round has work).
-    u32 first = 0;                           // ring position of the oldest staged survivor
-    u32 pending = 0;                         // staged survivors whose keys are on their way
-    u32 pkey[kMaxRounds][kGather];
-    auto begin = [&](u32 n_out) {
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (u32 r = 0; r < kMaxRounds; ++r)
-            if (r * kRound < n_out) {
-#pragma unroll
-                for (u32 k = 0; k < kGather; ++k) {
-                    const u32 j = r * kRound + k * 64u + lane;
-                    const u32 e = s_idx[(first + j) & (kStage - 1u)];
-                    pkey[r][k] = (j < n_out) ? (implicit ? key0 + e : ckeys[e]) : 0u;
-                }
-            }
-        pending = n_out;
-    };
-    auto complete = [&]() {
-        const u64 slot = ck.slot0 + cbase;
-#pragma unroll
-        for (u32 r = 0; r < kMaxRounds; ++r)
-            if (r * kRound < pending) {
-#pragma unroll
-                for (u32 k = 0; k < kGather; ++k) {
-                    const u32 j = r * kRound + k * 64u + lane;
-                    if (j < pending) {
-                        const u32 vb = s_val[(first + j) & (kStage - 1u)];
-                        const u32 a = vb & 0x7FFFFFFFu;
-                        // smallest code c in [1, tau] with a >= B[c]  (B non-increasing, a >= B[tau])
-                        u32 lo = 1, hi = tau;
-                        while (lo < hi) {
-                            const u32 mid = (lo + hi) >> 1;
-                            if (a >= s_B[mid - 1]) hi = mid; else lo = mid + 1;
-                        }
-                        scodes[slot + j] = (CodeT)(((vb >> 31) << (WIDE ? 15 : 7)) | (lo - 1));
-                        skeys[slot + j] = pkey[r][k];
-                    }
-                    __builtin_amdgcn_sched_barrier(0);        // one search at a time: keeps registers low
-                }
-            }
-        __builtin_amdgcn_wave_barrier();
-        cbase += pending;
-        staged -= pending;
-        first = (first + pending) & (kStage - 1u);
-        pending = 0;
-    };
-    // after every two rows; `loads_issued`: the next batch's loads have just been issued
-    auto flush_step = [&](bool loads_issued) {
-        if (pending) complete();
-        if (staged > kStage - 2 * kRow) {                      // no room for two more rows: at once
-            begin(staged - staged % kRound);
-            complete();
-        } else if (loads_issued && staged >= kRound) {
-            begin(staged - staged % kRound);
-        }
-    };
-
-    // The unit of the fetch is the granule: a batch is eight "virtual rows" of kRowGranules granules that
-    // can hold a survivor, taken in ascending order from wherever they sit, so that every lane fetches
-    // something useful however few granules are in play.
-    // One virtual row: lanes kGranLanes g .. kGranLanes (g + 1) - 1 fetch the g-th of its granules; `elem` is
-    // the chunk-relative element offset of the lane's first element.  Granules cut by the segment's ends
-    // are fetched element by element; elements outside [lo, hi) become zero, which never survives.
-    auto load_granules = [&](bool on, u32 elem, u32 (&row)[4]) {
-        const u64 e = ck.e0 + elem;
-        const bool inside = e >= ck.lo && e + 4u <= ck.hi;
-        uint4 q = make_uint4(0u, 0u, 0u, 0u);
-        if (__all(inside || !on)) {
-            if (on) q = *reinterpret_cast<const uint4*>(cvals + elem);
-            row[0] = q.x; row[1] = q.y; row[2] = q.z; row[3] = q.w;
-        } else {
-#pragma unroll
-            for (u32 c = 0; c < 4; ++c) {
-                const u64 ee = e + c;
-                row[c] = (on && ee >= ck.lo && ee < ck.hi) ? __float_as_uint(values[ee]) : 0u;
-            }
-        }
-    };
-
-    // one virtual row: masks, and staging if anything survives
-    auto stage_row = [&](const u32 (&row)[4], u32 elem) {
-        u64 m[4];
-#pragma unroll
-        for (u32 c = 0; c < 4; ++c) m[c] = __ballot(keeps(row[c], thr_f));
-        if ((m[0] | m[1] | m[2] | m[3]) == 0) return;
-        u32 pos = first + staged + lanes_below(m[0]) + lanes_below(m[1]) + lanes_below(m[2]) + lanes_below(m[3]);
-#pragma unroll
-        for (u32 c = 0; c < 4; ++c)
-            if (keeps(row[c], thr_f)) {
-                s_val[pos & (kStage - 1u)] = row[c];
-                s_idx[pos & (kStage - 1u)] = elem + c;
-                ++pos;
-            }
-        staged += (u32)__popcll(m[0]) + (u32)__popcll(m[1]) + (u32)__popcll(m[2]) + (u32)__popcll(m[3]);
-    };
-
-    // The granules (kGranule values, the share of kGranLanes lanes) that can hold a survivor form one
-    // ascending stream over the chunk, kept in a ring in shared memory (entry = index of the granule inside
-    // the chunk).  The ring is topped up 256 granules at a time: lane j compares four bounds, those of the
-    // granules 4 (scanned + j) .. + 3, with the threshold (unsigned compare of bit patterns: the same order
-    // as the float compare, and nothing passes the keep-nothing threshold).  The bounds of the 256 granules
-    // after those are fetched meanwhile.
-    uint2 xnext = crmax[lane < nwords ? lane : nwords - 1u];
-    u32 scanned = 0;                          // groups of four bounds whose granules are in the ring or behind it
-    u32 head = 0, tail = 0;                   // granules taken from / put into the ring since the start
-    auto refill = [&]() {
-        const uint2 x = xnext;
-        const u32 word = scanned + lane;
-        scanned += 64u;
-        if (scanned < nwords) {
-            const u32 wn = scanned + lane;
-            xnext = crmax[wn < nwords ? wn : nwords - 1u];
-        }
-        u32 qb = ((x.x << 16) >= thr ? 1u : 0u) | ((x.x & 0xFFFF0000u) >= thr ? 2u : 0u) |
-                 ((x.y << 16) >= thr ? 4u : 0u) | ((x.y & 0xFFFF0000u) >= thr ? 8u : 0u);
-        if (word >= nwords) qb = 0;
-        const u32 mine = (u32)__popc(qb);
-        const u32 incl = wave_incl_scan(mine);
-        u32 at = tail + incl - mine;
-#pragma unroll
-        for (u32 q = 0; q < 4; ++q)
-            if ((qb >> q) & 1u) s_ring[(at++) & (kRing - 1u)] = (uint16_t)((word << 2) | q);
-        tail += read_lane(incl, 63);
-    };
-    // A batch is eight rows of 256 elements in flight, each put together from the next kRowGranules
-    // granules of the stream (lanes kGranLanes k .. kGranLanes (k + 1) - 1 take the k-th of them).
-    constexpr u32 kBatch = kRowGranules * kValRows;
-    auto take = [&](u32 (&elem)[kValRows], u32 (&on)[kValRows]) -> u32 {
-        if (tail - head < kBatch && scanned < nwords) {
-            do refill(); while (tail - head < kBatch && scanned < nwords);
-            wave_lds_sync();
-        }
-        const u32 left = tail - head;
-        const u32 nq = left < kBatch ? left : kBatch;
-#pragma unroll
-        for (u32 slot = 0; slot < kValRows; ++slot) {
-            const u32 i = kRowGranules * slot + lane / kGranLanes;
-            on[slot] = i < nq ? 1u : 0u;
-            const u32 e = on[slot] ? s_ring[(head + i) & (kRing - 1u)] : 0u;
-            elem[slot] = e * kGranule + (lane & (kGranLanes - 1u)) * 4u;
-        }
-        head += nq;
-        return (nq + kRowGranules - 1u) / kRowGranules;
-    };
-    u32 bits[kValRows][4], elem[kValRows], on[kValRows];
-    u32 nr = take(elem, on);
-#pragma unroll
-    for (u32 slot = 0; slot < kValRows; ++slot) if (slot < nr) load_granules(on[slot] != 0, elem[slot], bits[slot]);
-    while (nr) {
-#pragma unroll
-        for (u32 pair = 0; pair < kValRows / 2; ++pair) {
-#pragma unroll
-            for (u32 slot = 2 * pair; slot < 2 * pair + 2; ++slot) if (slot < nr) stage_row(bits[slot], elem[slot]);
-            if (pair + 1 == kValRows / 2) {
-                // the registers are free: start on the next rows before finishing these
-                nr = take(elem, on);
-#pragma unroll
-                for (u32 slot = 0; slot < kValRows; ++slot)
-                    if (slot < nr) load_granules(on[slot] != 0, elem[slot], bits[slot]);
-            }
-            flush_step(pair + 1 == kValRows / 2);
-        }
+    for (u32 k = 0; k < kTable / 64u; ++k) s_B[lane + 64u * k] = st->B[lane + 64u * k];
+    cx.keys = keys;
+    cx.values = values;
+    cx.ckeys = keys + cx.ck.e0;
+    cx.cvals = values + cx.ck.e0;
+    cx.key0 = (u32)(cx.ck.e0 - cx.ck.lo);                   // (wraps for the up to three slots before the segment)
+    // bounds in groups of four (16 bits each): kRowGranules / 4 such groups per row
+    cx.crmax = reinterpret_cast<const uint2*>(rowmax) + (u64)cx.ck.row0 * (kRowGranules / 4u);
+    cx.nwords = cx.ck.nrows * (kRowGranules / 4u);
+    cx.skeys = skeys;
+    cx.scodes = scodes_any;
+    const bool implicit = keys == nullptr;                  // dense gradient: the key is the index in the segment
+    // How the chunk is read: row by row if at least kDenseNum / kDenseDen of its granules can hold a
+    // survivor (that needs the keys 16-byte aligned like the values, or no key array at all).
+    bool by_rows = false;
+    if (implicit || (((uintptr_t)cx.ckeys & 15u) == 0)) {
+        u32 live = 0;
+        for (u32 i = lane; i < cx.nwords; i += 64u) live += (u32)__popc(live_bits(cx.crmax[i], cx.thr));
+        live = wave_sum(live);
+        by_rows = live * kDenseDen >= cx.nwords * 4u * kDenseNum;
     }
-    if (pending) complete();
-    if (staged) {
-        begin(staged);
-        complete();
-    }
-    if (lane == 0) ccount[chunk] = cbase;
+    wave_lds_sync();
+    u32 count;
+    if (by_rows) count = implicit ? encode_chunk<WIDE, true, true>(cx) : encode_chunk<WIDE, true, false>(cx);
+    else count = implicit ? encode_chunk<WIDE, false, true>(cx) : encode_chunk<WIDE, false, false>(cx);
+    if (lane == 0) ccount[chunk] = count;
 }
 
 // ---------------------------------------------------------------------------------------------
