@@ -7,13 +7,18 @@ fastsgd_compress_segmented + fastsgd_decompress_segmented over the 160 tensors),
 Prints ONE JSON line (metric = input GB/s of the round trip, 8 bytes per element: 4-byte key + 4-byte
 value, the paper's 64 bits per original pair, Section 3.4).
 
+A dense gradient (configs 2, 4, 5: keys 0..n-1) is passed the way a caller holding one passes it, without a
+key array (d_keys = NULL: the keys are the indices); the same call WITH the explicit key array 0..n-1 is timed
+beside it and reported as `compress_explicit_keys_*`.  Sparse gradients (configs 1, 3) have their key arrays.
+
 Byte counts used below, per call (N elements, d survivors, sb stream bytes, rows = N/256):
-  compress, "algorithmic"  8N + 18d + sb : both value passes in full, key + scratch traffic of the survivors
-                                           (4d key fetch, 5d scratch out, 5d + 4d scratch back in), stream out
+  compress, "algorithmic"  no key array: 8N + 14d + sb; key array: 8N + 18d + sb : both value passes in full, key
+                           (4d, where there is a key array) + scratch traffic of the survivors (5d scratch out,
+                           5d + 4d scratch back in), stream out
   compress, "moved"        what the kernels are built to move: the second pass reads only the 128-byte
-                           granules whose bound reaches the threshold (q of them), and a key fetch pulls in
-                           the whole 128-byte line around each surviving key of an explicit key array
-                           (key_lines of them): 4N + 32 rows + 128 q + 128 key_lines + 14d + sb
+                           granules whose bound reaches the threshold (q of them), and with an explicit key array
+                           whole 128-byte lines around the surviving keys (key_lines of them):
+                           4N + 32 rows + 128 q [+ 128 key_lines] + 14d + sb
   decompress               sb + 8d
 """
 import argparse
@@ -182,7 +187,8 @@ class SingleCase:
                 lines = torch.unique_consecutive(pt["keys_out"][:pt["d"]] >> 5)
                 pt["key_lines"] = int(lines.numel())
 
-    def compress(self, pt, i=0, keys=True):
+    def compress(self, pt, i=0, keys=None):
+        keys = (not self.dense) if keys is None else keys       # a dense gradient goes without its key array
         k = self.keys[i % len(self.keys)] if keys else None
         rc = self.B.compress(k, self.values[i % len(self.values)], pt["p"], pt["out"], self.obytes, self.status, self.ws,
                              n=self.n, out_capacity=pt["cap"])
@@ -230,7 +236,7 @@ class BatchCase:
         self.plist = [B.params(b) for b in self.bases]
         self.keys = [torch.from_numpy(w.keys.view(np.int32)).cuda() for _ in range(copies)]
         self.values = [torch.from_numpy(w.values).cuda() for _ in range(copies)]
-        self.dense = False
+        self.dense = True                                        # every tensor has the keys 0..n_i-1
         cap = B.compressed_size(max(n, 1), B.params(1.1, 128, 2, 1024)) + (64 + 4096) * nseg
         out = torch.empty(cap // 8 + 8, dtype=torch.int64, device="cuda")
         self.ws = torch.empty(B.workspace_size(n, nseg, 1024) // 8 + 32, dtype=torch.int64, device="cuda")
@@ -255,7 +261,8 @@ class BatchCase:
     def count_fetch_units(self):
         pass
 
-    def compress(self, pt, i=0, keys=True):
+    def compress(self, pt, i=0, keys=None):
+        keys = (not self.dense) if keys is None else keys
         k = self.keys[i % len(self.keys)] if keys else None
         rc = self.B.compress_segmented(k, self.values[i % len(self.values)], self.offs, self.plist, pt["out"], self.out_offs,
                                        self.status, self.ws)
@@ -316,9 +323,11 @@ def point_record(case, pt, timer, iters):
     cg_ms = timer.graph(lambda i: case.compress(pt, i), iters)
     dg_ms = timer.graph(lambda i: case.decompress(pt, i), iters)
     case.check(pt)
-    comp_alg = 8.0 * n + 18.0 * d + sb                         # two value passes + survivor traffic + stream
+    key_bytes = 0.0 if case.dense else 4.0 * d                 # key fetch of the survivors, where there is a key array
+    comp_alg = 8.0 * n + 14.0 * d + key_bytes + sb             # two value passes + survivor traffic + stream
     dec_alg = sb + 8.0 * d
     rec = dict(keep=pt["keep"], d=d, stream_bytes=sb, ratio=8.0 * n / sb,
+               key_array="none (dense gradient: the keys are the indices)" if case.dense else "explicit",
                compress_ms=c_ms, decompress_ms=d_ms, compress_graph_ms=cg_ms, decompress_graph_ms=dg_ms,
                compress_input_GBps=8.0 * n / c_ms / 1e6, decompress_input_GBps=8.0 * n / d_ms / 1e6,
                compress_elements_per_s=n / c_ms * 1e3,
@@ -329,11 +338,21 @@ def point_record(case, pt, timer, iters):
                decompress_graph_hbm_frac=None if dg_ms is None else dec_alg / dg_ms / 1e6 / HBM_PEAK_GBPS)
     if pt.get("granules_active") is not None:
         qa = pt["granules_active"]
-        kl = pt["key_lines"]
-        moved = 4.0 * n + 32.0 * rows + 128.0 * qa + (128.0 * kl if kl is not None else 4.0 * d) + 14.0 * d + sb
+        moved = 4.0 * n + 32.0 * rows + 128.0 * qa + key_bytes + 14.0 * d + sb
         rec.update(base=pt["p"].base, bits_per_key=8.0 * (sb - 64 - d) / max(d, 1), granules_read=qa, granules=8 * rows,
-                   key_lines_read=kl, compress_moved_bytes=moved,
-                   compress_moved_frac=moved / c_ms / 1e6 / HBM_PEAK_GBPS)
+                   compress_moved_bytes=moved, compress_moved_frac=moved / c_ms / 1e6 / HBM_PEAK_GBPS)
+    if case.dense:
+        # the same call with the explicit key array 0..n-1
+        e_ms = timer.eager(lambda i: case.compress(pt, i, keys=True), iters)
+        case.check(pt)
+        ealg = 8.0 * n + 18.0 * d + sb
+        rec.update(compress_explicit_keys_ms=e_ms, compress_explicit_keys_algorithmic_bytes=ealg,
+                   compress_explicit_keys_hbm_frac=ealg / e_ms / 1e6 / HBM_PEAK_GBPS)
+        kl = pt.get("key_lines")
+        if kl is not None and pt.get("granules_active") is not None:
+            emoved = 4.0 * n + 32.0 * rows + 128.0 * pt["granules_active"] + 128.0 * kl + 14.0 * d + sb
+            rec.update(key_lines_read=kl, compress_explicit_keys_moved_bytes=emoved,
+                       compress_explicit_keys_moved_frac=emoved / e_ms / 1e6 / HBM_PEAK_GBPS)
     return rec
 
 
@@ -422,19 +441,19 @@ def main():
     for pt in points:
         rec = point_record(case, pt, timer, args.steps)
         if isinstance(case, SingleCase):
-            rc, kc = B.profile_compress(case.keys[0], values, pt["p"], pt["out"], case.obytes, case.status, case.ws,
-                                        args.steps, n=n, out_capacity=pt["cap"])
+            rc, kc = B.profile_compress(None if case.dense else case.keys[0], values, pt["p"], pt["out"], case.obytes,
+                                        case.status, case.ws, args.steps, n=n, out_capacity=pt["cap"])
             assert rc == B.OK
             rc, kd = B.profile_decompress(pt["out"], pt["bytes"], pt["keys_out"], pt["vals_out"], case.count, case.status,
                                           case.dws, args.steps, capacity=pt["d"])
             assert rc == B.OK
-            d, sb, qa, kl = pt["d"], pt["bytes"], pt["granules_active"], pt["key_lines"]
+            d, sb, qa = pt["d"], pt["bytes"], pt["granules_active"]
             # bytes each kernel is built to move, per launch: every value once and eight 16-bit bounds per row out;
-            # bounds, granules that can hold a survivor, key lines of survivors, key + code byte to scratch;
-            # surviving keys; surviving keys and code bytes in, stream out; stream in, (key, value) pairs out
+            # bounds, granules that can hold a survivor, keys of survivors (where there is a key array), key + code
+            # byte to scratch; surviving keys; surviving keys and code bytes in, stream out; stream in, pairs out
             alg = {
                 "abs_sum": 4.0 * n + 16.0 * rows,
-                "encode_values": 16.0 * rows + 128.0 * qa + (128.0 * kl if kl is not None else 4.0 * d) + 5.0 * d,
+                "encode_values": 16.0 * rows + 128.0 * qa + (0.0 if case.dense else 4.0 * d) + 5.0 * d,
                 "measure_keys": 4.0 * d,
                 "pack_keys": 5.0 * d + (sb - 64),
                 "decode": sb + 8.0 * d,
@@ -445,29 +464,24 @@ def main():
                 kern_bytes[k] = kern_bytes.get(k, 0.0) + v
             rec["kernels_ms"] = {**kc, **{"decode_" + k: v for k, v in kd.items()}}
             rec["kernels_moved_bytes"] = alg
-            # the same call without a key array (keys are the indices): what a dense gradient needs
-            if case.dense:
-                i_ms = timer.eager(lambda i: case.compress(pt, i, keys=False), args.steps)
-                assert int(case.status[0]) == B.OK and int(case.obytes[0]) == pt["bytes"]
-                ialg = 8.0 * n + 14.0 * d + sb
-                rec.update(compress_no_key_array_ms=i_ms,
-                           compress_no_key_array_hbm_frac=ialg / i_ms / 1e6 / HBM_PEAK_GBPS)
         detail.append(rec)
 
     kernels = None
     big = max(detail, key=lambda r: r["d"])                          # the point with the most survivors
     calls = dict(point=dict(keep=big["keep"], d=big["d"], stream_bytes=big["stream_bytes"]),
-                 compress=dict(ms=big["compress_ms"], algorithmic_bytes=big["compress_algorithmic_bytes"],
+                 compress=dict(key_array=big["key_array"], ms=big["compress_ms"],
+                               algorithmic_bytes=big["compress_algorithmic_bytes"],
                                frac=big["compress_hbm_frac"], moved_bytes=big.get("compress_moved_bytes"),
                                moved_frac=big.get("compress_moved_frac"),
-                               no_key_array_ms=big.get("compress_no_key_array_ms"),
-                               no_key_array_frac=big.get("compress_no_key_array_hbm_frac")),
+                               explicit_keys_ms=big.get("compress_explicit_keys_ms"),
+                               explicit_keys_frac=big.get("compress_explicit_keys_hbm_frac"),
+                               explicit_keys_moved_frac=big.get("compress_explicit_keys_moved_frac")),
                  decompress=dict(ms=big["decompress_ms"], algorithmic_bytes=big["decompress_algorithmic_bytes"],
                                  frac=big["decompress_hbm_frac"]),
                  note="whole calls at the sweep point with the most survivors; frac = algorithmic bytes / time / peak "
-                      "(compress 8N+18d+sb, decompress sb+8d); moved_* counts the granules actually read and the "
-                      "128-byte key lines actually fetched instead; no_key_array_*: the same gradient passed without "
-                      "its key array (8N+14d+sb)")
+                      "(compress 8N+14d+sb without a key array, 8N+18d+sb with one; decompress sb+8d); moved_* counts the "
+                      "granules actually read (and the 128-byte key lines actually fetched) instead; explicit_keys_*: "
+                      "the same dense gradient passed WITH the key array 0..n-1")
     if kern_time:
         dominant = max(("abs_sum", "encode_values"), key=lambda k: kern_time[k])
         kernels = {k: dict(ms_total=kern_time[k], achieved_GBps=kern_bytes[k] / kern_time[k] / 1e6,
@@ -496,7 +510,7 @@ def main():
         theta, m1, v1 = (torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(3))
         aws = B.decoder_workspace(n_streams)
         count, status, obytes, ws, dws = case.count, case.status, case.obytes, case.ws, case.dws
-        keys = case.keys[0]
+        keys = None if case.dense else case.keys[0]
         for pt in points:
             sb = pt["bytes"]
             many = torch.cat([pt["out"].view(torch.uint8)[:sb]] * n_streams + [torch.zeros(64, dtype=torch.uint8, device="cuda")])
@@ -591,6 +605,7 @@ def main():
         "config": {"workload": WORKLOAD_NAMES[args.workload], "n": n,
                    "keep_fractions": keep_fractions, "tau": 128, "flag_bits": 2,
                    "block_keys": 1024, "step": "compress+decompress at every keep fraction",
+                   "key_array": detail[0]["key_array"],
                    "arithmetic": "f32 values and u32 keys compared as IEEE bit patterns; f64 boundary table"},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "detail": detail,
     }

@@ -21,6 +21,9 @@
  *   - The return value covers what the host can see (bad arguments, workspace too small, launch
  *     failure).  Conditions detected on the device set *d_status to a fastsgd_status value and
  *     the reported length (bytes / pairs) to 0; nothing is ever written past a stated capacity.
+ *   - Where several device-detected conditions hold at once the encoder reports, in this order, a
+ *     non-finite value, keys out of order, an output buffer too small.  (A sequential encoder would
+ *     report whichever of the last two it meets first; both verdicts describe the same refused input.)
  *   - Keys are uint32 and strictly increasing within one gradient (the first may be 0);
  *     values are IEEE binary32.  n <= 2^32 - 1024 per gradient.
  *

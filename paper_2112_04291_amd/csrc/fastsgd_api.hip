@@ -450,7 +450,8 @@ size_t fastsgd_compressed_size(uint64_t n, const fastsgd_params* p) {
 size_t fastsgd_workspace_size(uint64_t total_n, uint32_t n_segments, uint32_t min_block_keys) {
     if (n_segments < 1 || n_segments > kMaxSegments || total_n >= (1ull << 40)) return 0;
     if (min_block_keys < 256 || min_block_keys > kMaxKB || (min_block_keys & (min_block_keys - 1))) return 0;
-    // + 4 elements: the call may shift its base down to a 16-byte boundary
+    // (the plan's bounds leave room for the call shifting its base down to a 16-byte boundary: 8 scratch entries
+    // and two rows beyond the elements)
     return (size_t)make_plan(total_n, n_segments, min_block_keys).total;
 }
 

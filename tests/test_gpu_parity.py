@@ -122,6 +122,31 @@ def test_unsorted_surviving_keys_are_reported():
     check_round_trip(keys, np.full(n, 1.0, np.float32), 1.1, expect_status=ref.ERR_UNSORTED_KEYS)
 
 
+def test_which_status_wins_when_several_conditions_hold():
+    """Non-finite input before keys out of order before a buffer too small; the sequential oracle reports
+    whichever of the last two it meets first, so its verdict is only required to be one of them."""
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(3)
+    n = 20_000
+    keys = np.cumsum(rng.integers(1, 9, n)).astype(np.uint32)
+    vals = rng.laplace(0, 1e-3, n).astype(np.float32)
+    p, rp = B.params(16.0), ref.params(16.0)                    # b^tau is huge: everything survives
+    swapped = keys.copy()
+    swapped[[15_000, 15_001]] = swapped[[15_001, 15_000]]
+    small = 64 + 4096                                           # holds the header, not the stream
+    rc, status, st, _ = G.hip_compress(swapped, vals, p, out_capacity=small)
+    assert rc == B.OK and status == B.ERR_UNSORTED_KEYS and st.size == 0
+    assert ref.compress(swapped, vals, rp, capacity=small)[0] in (ref.ERR_UNSORTED_KEYS, ref.ERR_BUFFER_TOO_SMALL)
+    bad = vals.copy()
+    bad[7] = np.inf
+    rc, status, st, _ = G.hip_compress(swapped, bad, p, out_capacity=small)
+    assert rc == B.OK and status == B.ERR_NONFINITE and st.size == 0
+    assert ref.compress(swapped, bad, rp, capacity=small)[0] == ref.ERR_NONFINITE
+    rc, status, st, _ = G.hip_compress(keys, vals, p, out_capacity=small)
+    assert rc == B.OK and status == B.ERR_BUFFER_TOO_SMALL and st.size == 0
+    assert ref.compress(keys, vals, rp, capacity=small)[0] == ref.ERR_BUFFER_TOO_SMALL
+
+
 def test_output_capacity_is_respected():
     torch, B, G = _gpu()
     w = W.small_mixture(21, 100_000)
