@@ -145,8 +145,8 @@ class SingleCase:
         probe = B.Buffers(n, plist[0])
         self.points = []
         for keep, p in zip(self.keeps, plist):
-            rc = B.compress(self.keys[0], self.values[0], p, probe.out, probe.out_offsets, probe.status, probe.workspace,
-                            n=n, out_capacity=probe.out_capacity)
+            rc = B.compress(None if self.dense else self.keys[0], self.values[0], p, probe.out, probe.out_offsets,
+                            probe.status, probe.workspace, n=n, out_capacity=probe.out_capacity)
             torch.cuda.synchronize()
             assert rc == B.OK and int(probe.status[0]) == B.OK, (rc, int(probe.status[0]))
             nbytes = int(probe.out_offsets[0])
@@ -314,7 +314,7 @@ def make_case(name, scale=1.0, keeps=None):
     return case
 
 
-def point_record(case, pt, timer, iters):
+def point_record(case, pt, timer, iters, explicit_keys=True):
     """Timings and rates of one point of a case (compress and decompress each timed on their own)."""
     n, d, sb = case.n, pt["d"], pt["bytes"]
     rows = (n + 255) // 256
@@ -341,7 +341,7 @@ def point_record(case, pt, timer, iters):
         moved = 4.0 * n + 32.0 * rows + 128.0 * qa + key_bytes + 14.0 * d + sb
         rec.update(base=pt["p"].base, bits_per_key=8.0 * (sb - 64 - d) / max(d, 1), granules_read=qa, granules=8 * rows,
                    compress_moved_bytes=moved, compress_moved_frac=moved / c_ms / 1e6 / HBM_PEAK_GBPS)
-    if case.dense:
+    if case.dense and explicit_keys:
         # the same call with the explicit key array 0..n-1
         e_ms = timer.eager(lambda i: case.compress(pt, i, keys=True), iters)
         case.check(pt)
@@ -367,6 +367,9 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replays of the per-point timings")
+    ap.add_argument("--no-explicit-keys", action="store_true",
+                    help="do not also time a dense gradient WITH its explicit key array (profiling runs: every "
+                         "launch in the trace then belongs to the timed call)")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the per-config records of the configurations that are not the timed workload")
     ap.add_argument("--widening", action="store_true",
@@ -439,7 +442,7 @@ def main():
     kern_time, kern_bytes = {}, {}
     rows = (n + 255) // 256
     for pt in points:
-        rec = point_record(case, pt, timer, args.steps)
+        rec = point_record(case, pt, timer, args.steps, not args.no_explicit_keys)
         if isinstance(case, SingleCase):
             rc, kc = B.profile_compress(None if case.dense else case.keys[0], values, pt["p"], pt["out"], case.obytes,
                                         case.status, case.ws, args.steps, n=n, out_capacity=pt["cap"])

@@ -1221,7 +1221,8 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
     __shared__ u32 s_lutall[kWaves][33];
     __shared__ u32 s_coarseall[kWaves][64];
     __shared__ u32 s_span[2][kWaves];                        // sizes of the unit's blocks, by parity of the round
-    const u32 lane = lane_id(), w = uniform(wave_id());
+    u32 lane = lane_id();
+    const u32 w = uniform(wave_id());
     uint8_t* s_need = s_needall[w];
     u32* s_buf = s_bufall[w];
     u32* s_lut = s_lutall[w];
@@ -1234,6 +1235,9 @@ k_measure_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* _
     // workgroup: an atomic per block would queue 64 deep on every sum (each takes a trip to the L2).
     u32 round = 0;
     for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x, ++round) {
+        // the lane number as a value of this unit: keeps the many addresses derived from it from being computed
+        // once and held in registers across the whole kernel
+        asm volatile("" : "+v"(lane));
         SegInfo info;
         const KeyUnit ku = key_unit(seg0, segs, states, n_segments, R, unit, d0, nb0, &info);
         const u32* P = ccount + ku.cb;                      // the segment's chunk scan
@@ -1353,7 +1357,8 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
     __shared__ u32 s_flgall[kWaves][kSub * 5 / 32 + 2];
     __shared__ u32 s_lutall[kWaves][33];
     __shared__ u32 s_coarseall[kWaves][64];
-    const u32 t = threadIdx.x, lane = lane_id(), w = uniform(wave_id());
+    const u32 t = threadIdx.x, w = uniform(wave_id());
+    u32 lane = lane_id();
     u32* s_pay = s_payall[w];
     u32* s_flg = s_flgall[w];
     u32* s_lut = s_lutall[w];
@@ -1387,6 +1392,7 @@ k_pack_keys(SegInfo seg0, const SegInfo* __restrict__ segs, const SegState* __re
     const u64 d0 = states[0].d;
     const u32 nb0 = states[0].nb;
     for (u64 unit = blockIdx.x; unit < total_units; unit += gridDim.x) {
+        asm volatile("" : "+v"(lane));      // (as in k_measure_keys: nothing derived from the lane number is kept across units)
         SegInfo info;
         const KeyUnit ku = key_unit(seg0, segs, states, n_segments, R, unit, d0, nb0, &info);
         const u32* P = ccount + ku.cb;                      // the segment's chunk scan
