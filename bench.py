@@ -34,7 +34,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bench_c4_hbm_traffic.md")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bench_c4_all_hbm_traffic.md")
 
 
 def threshold_bits(total, base, tau):
@@ -494,7 +494,7 @@ def main():
                         achieved=kern_bytes[dominant] / kern_time[dominant] / 1e6, peak=HBM_PEAK_GBPS, unit="GB/s",
                         frac=kern_bytes[dominant] / kern_time[dominant] / 1e6 / HBM_PEAK_GBPS,
                         traffic=committed_traffic("k_" + dominant) if args.workload == "c4" and not keeps else None,
-                        traffic_source="profiles/bench_c4_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
+                        traffic_source="profiles/bench_c4_all_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
                                        "separate runs of this command, scaled by a plain elementwise kernel of known size; "
                                        "bytes per launch)",
                         avg_launch_ms=kern_time[dominant] / launches,
