@@ -312,6 +312,28 @@ static fastsgd_status accumulate_impl(const void* d_streams, size_t total_bytes,
                        d_stream_offsets, 0u, segs, ctrl, ~0ull, counts, d_status);
     hipLaunchKernelGGL(k_decode_plan, dim3(1), dim3(kThreads), 0, stream, segs, n_streams, ~0ull, ctrl, counts, d_status,
                        d_count);
+    // Gradients that keep a large share of their entries: one pass over the dense vector per group of streams
+    // instead of one per stream.  A pair of the other form moves two 64-byte lines of the dense vector through
+    // the memory system (read and write back) for some two bytes of stream; the pass moves eight bytes per entry of the
+    // vector for each group.  (The streams' pair counts are on the device only; their bytes are what the host
+    // can go by.)
+    const u64 n_groups = ((u64)n_streams + kTileStreams - 1) / kTileStreams;
+    const bool by_tiles = n_streams >= 2 && dense_len >= 1 && ((uintptr_t)d_dense & 15) == 0 &&
+                          (u64)total_bytes * 4 >= dense_len * n_groups;
+    if (by_tiles) {
+        const u64 n_tiles = (dense_len + kTileKeys - 1) / kTileKeys;
+        // a workgroup per compute unit, each with a run of tiles of its own (short vectors: runs of three, so
+        // that few tiles do not mean as many workgroups that each start every stream afresh)
+        u64 per = (n_tiles + cus - 1) / cus;
+        if (per < 3) per = n_tiles < 3 ? n_tiles : 3;
+        const u32 grid = (u32)((n_tiles + per - 1) / per);
+        for (u32 s0 = 0; s0 < n_streams; s0 += kTileStreams) {
+            const u32 n_here = n_streams - s0 < kTileStreams ? n_streams - s0 : kTileStreams;
+            hipLaunchKernelGGL(k_accumulate_tiles, dim3(grid), dim3(kTileStreams * kWave), 0, stream, streams, segs, s0, n_here,
+                               ctrl, d_count, d_status, d_dense, dense_len, (u32)per);
+        }
+        return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
+    }
     const u32 grid = clamp_grid(((u64)total_bytes / 96 + 1 + kWaves - 1) / kWaves, (u64)cus * 7);
     for (u32 s = 0; s < n_streams; ++s)
         hipLaunchKernelGGL((k_decode<kAccum, false, kWaves>), dim3(grid), dim3(kThreads), 0, stream, streams, (u64)total_bytes, ~0ull,

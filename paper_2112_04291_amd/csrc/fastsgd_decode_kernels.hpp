@@ -36,7 +36,7 @@ struct DecCtrl {
 // workspace's first use.  Batch launches never touch them.
 constexpr u32 kDoneGroups = 16;
 struct DecDone {
-    u32 fail;                    // first failure a wave of the launch found (a fastsgd_status), 0 = none
+    u32 fail;                    // the gravest failure the waves of the launch found (a fastsgd_status), 0 = none
     u32 top;                     // groups that have completed
     u32 pad[30];
     u32 group[kDoneGroups][32];  // [g][0]: workgroups of group g that have finished
@@ -78,8 +78,11 @@ __device__ __forceinline__ bool parse_header(const u64* __restrict__ h, u64 avai
     return ok;
 }
 
+// A failure found while decoding.  If waves find different ones, the larger code stays: a corrupt stream
+// outranks a buffer that is too small.
 __device__ __forceinline__ void dec_fail(DecCtrl* ctrl, u32 code, u32* out_status, u64* out_counts, u32 n_counts) {
-    if (atomicCAS(&ctrl->status, 0u, code) == 0u) *out_status = code;
+    atomicMax(&ctrl->status, code);
+    atomicMax(out_status, code);
     for (u32 i = 0; i < n_counts; ++i) out_counts[i] = 0;
 }
 
@@ -225,7 +228,7 @@ __device__ __forceinline__ u32 mad24(u32 a, u32 b, u32 c) {
 
 // What a decode launch does with the pairs: store them, add every value to dense[key] (Section 2.1,
 // aggregation), or apply the Adam step of Section 4.1 at every key.
-enum : int { kStore = 0, kAccum = 1, kAdam = 2 };
+enum : int { kStore = 0, kAccum = 1, kAdam = 2, kHand = 3 };   // kHand: hand the pairs back to the caller, 16 consecutive ones per lane
 
 // Adam state and hyper-parameters (Section 4.1); theta is passed as the dense array.
 struct AdamArgs {
@@ -245,7 +248,8 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
                                              u32 M, u32 tau, u32 cwid, u32 pbits, u32& pbit, u32& carry, u32 lane,
                                              u32* s_pay, u32* s_flg, u32* s_cod, const u32* s_V, u32* __restrict__ keys_dst,
                                              float* __restrict__ values_dst, float* __restrict__ dense, u64 dense_len,
-                                             const AdamArgs& adam, bool& too_big, bool stream_start) {
+                                             const AdamArgs& adam, bool& too_big, bool stream_start,
+                                             u32 (&out_keys)[kLaneKeys], u32 (&out_vals)[kLaneKeys]) {
     const u32 nfw = (n * l + 31u) >> 5;
     const u32 pw0 = pbit >> 5, wbits = pbit & 31u;
     u32 npw = ((wbits + n * M + 31u) >> 5) + 1u;           // words this round can reach (+1: windows)
@@ -380,6 +384,26 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
 #pragma unroll
         for (u32 k = 0; k < kLaneKeys; ++k) vb[k] = s_V[(cw[k >> 2] >> (8u * (k & 3u))) & 0xFFu];
     }
+    if (MODE == kHand) {
+        // the caller takes the pairs as they are, 16 consecutive ones per lane (keys beyond n repeat the last key,
+        // their values are the first code's: the caller knows n)
+        if (cwid > 8) {
+#pragma unroll
+            for (u32 k = 0; k < kLaneKeys; ++k) {
+                const u32 i = lane * kLaneKeys + k, pos = i * 9u, wa = pos >> 5;
+                u32 tok = __builtin_amdgcn_alignbit(s_cod[wa + 1u], s_cod[wa], pos & 31u) & 0x1FFu;
+                if (!FULL && i >= n) tok = 0;
+                badcode |= (tok & 0xFFu) >= tau;
+                vb[k] = s_V[tok & 0xFFu] | ((tok >> 8) << 31);
+            }
+        }
+#pragma unroll
+        for (u32 k = 0; k < kLaneKeys; ++k) { out_keys[k] = kp[k]; out_vals[k] = vb[k]; }
+        carry = read_lane(kp[kLaneKeys - 1], 63);           // (keys beyond n add nothing: the last lane ends on the round's last key)
+        pbit += roundbits;
+        wave_lds_sync();
+        return !(__any(ovf) || __any(badcode));
+    }
     // Lane-major -> row-major through shared memory (row q, lane: pair 64 * q + lane), so that stores to
     // the output arrays are coalesced and updates of the dense arrays touch neighbouring addresses in one
     // instruction.  A lane's 16 words sit 20 words apart (word i at i + 4 * (i / 16)), which spreads the
@@ -489,7 +513,7 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
 // code): one thread walks the tau multiplications of b^c -- a chain of dependent binary64 operations that
 // takes microseconds, which is why such a launch uses few, large workgroups (WAVES = 16: one chain per
 // compute unit) -- then 256 threads divide, one code each.  A wave that finds its block corrupt leaves the
-// code in done->fail (first one wins); every workgroup that has key blocks counts itself in `done` when its
+// code in done->fail (the larger code stays); every workgroup that has key blocks counts itself in `done` when its
 // waves are through, and the one that completes the count writes *out_status and out_counts[0] and leaves
 // the control words zero for the next launch (workgroups without key blocks leave at once; a launch with
 // nothing to decode is reported by workgroup 0 alone).
@@ -619,20 +643,21 @@ k_decode(const uint8_t* __restrict__ streams, u64 stream_bytes, u64 capacity, co
                 u32* kd = MODE != kStore ? nullptr : keys_out + out0 + sub * kSub;
                 float* vd = MODE != kStore ? nullptr : values_out + out0 + sub * kSub;
                 const bool stream_start = (blk == 0 && sub == 0);       // the round holds the stream's first key
+                u32 unused_k[kLaneKeys], unused_v[kLaneKeys];
                 if (n == kSub)
                     ok = decode_round<true, MODE>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * (kSub / 8u) * cwid, n, l, M,
                                                    tau, cwid, pbits, pbit, carry, lane_r, s_pay, s_flg, s_cod, s_V, kd, vd, dense, dense_len,
-                                                   adam, too_big, stream_start);
+                                                   adam, too_big, stream_start, unused_k, unused_v);
                 else
                     ok = decode_round<false, MODE>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * (kSub / 8u) * cwid, n, l, M,
                                                     tau, cwid, pbits, pbit, carry, lane_r, s_pay, s_flg, s_cod, s_V, kd, vd, dense, dense_len,
-                                                    adam, too_big, stream_start);
+                                                    adam, too_big, stream_start, unused_k, unused_v);
             }
             bad = !ok || (pbit != pbits) || (has_next && carry != next_pre);
         }
         if ((bad || too_big) && lane == 0) {
             const u32 code = bad ? FASTSGD_ERR_CORRUPT_STREAM : FASTSGD_ERR_BUFFER_TOO_SMALL;
-            if (INLINE) atomicCAS(&done->fail, 0u, code);
+            if (INLINE) atomicMax(&done->fail, code);
             else dec_fail(ctrl, code, out_status, out_counts, n_counts);
         }
     }
@@ -653,6 +678,280 @@ k_decode(const uint8_t* __restrict__ streams, u64 stream_bytes, u64 capacity, co
             }
         }
     }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Decode-and-aggregate in one pass over the dense vector (Section 2.1: the workers' gradients are decoded
+// and added up).  For gradients that keep a large share of their entries, adding stream after stream moves
+// the whole dense vector through the memory system once per stream; here it moves once per group of
+// kTileStreams streams.
+//
+// A workgroup owns a run of consecutive tiles of kTileKeys keys and holds one tile at a time in shared
+// memory.  Wave w walks the key blocks of the group's w-th stream in order, one round of up to 1024 pairs
+// at a time, and keeps the round in registers (16 consecutive pairs per lane) until the tile that holds its
+// last key has come -- so a round that straddles tiles is decoded once.  Binary32 addition is not
+// associative, so for every key the streams are added in the given order: the waves take turns, stream
+// after stream, with a barrier between turns (keys are distinct inside a stream, so a turn is a plain
+// read-add-write of shared memory), and decode their next rounds all at the same time between the turns.
+// A workgroup starts each stream at the block that holds the first key of its run (found by a search of the
+// block directory's preKeys, which the launch checks to be strictly increasing so that every block is met
+// by some workgroup) and decodes that block from its beginning, keys below the run being skipped.
+// The workgroup that owns the last tile goes on to the end of every stream: what is left there has keys
+// beyond the dense vector (FASTSGD_ERR_BUFFER_TOO_SMALL) unless it is corrupt, which is reported first.
+constexpr u32 kTileKeys = 16384;
+constexpr u32 kTileStreams = 8;
+constexpr u32 kFrontSpins = 1u << 22;     // polls of the other streams' fronts before a wait is given up (seconds)
+
+// Largest index i in [0, n) with pre(i) <= x, or 0 (the wave probes 64 entries per round trip).  Stays inside
+// [0, n) whatever the entries hold.
+template <class Value>
+__device__ __forceinline__ u32 dir_upper_index(u32 n, u32 x, Value pre) {
+    u32 lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const u32 step = (hi - lo + 63u) / 64u;
+        const u32 idx = lo + lane_id() * step;
+        const bool p = idx < hi && pre(idx) <= x;
+        const u32 c = (u32)__popcll(__ballot(p));
+        lo = uniform(lo + (c ? c - 1u : 0u) * step);           // (c <= lanes with idx < hi, so lo stays below hi)
+        hi = lo + step < hi ? lo + step : hi;
+    }
+    return lo;
+}
+
+__global__ void __launch_bounds__(kTileStreams * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
+k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u32 seg0, u32 n_here,
+                   DecCtrl* ctrl, u64* out_count, u32* out_status, float* __restrict__ dense, u64 dense_len,
+                   u32 tiles_per_group) {
+    __shared__ __attribute__((aligned(16))) float s_tile[kTileKeys];
+    __shared__ __attribute__((aligned(16))) u32 s_payall[kTileStreams][17 * 64];      // payload window of a round
+    __shared__ u32 s_flgall[kTileStreams][3 * 64];
+    __shared__ u32 s_Vall[kTileStreams][256];
+    __shared__ __attribute__((aligned(16))) u32 s_codall[kTileStreams][2 * kCodeWords];
+    __shared__ u32 s_front[kTileStreams];
+    __shared__ u32 s_go;
+    const u32 lane = lane_id(), w = uniform(wave_id()), t = threadIdx.x;
+    if (t == 0) s_go = (ctrl->status == 0);          // (one reading for the whole workgroup: others may fail meanwhile)
+    __syncthreads();
+    if (!s_go) return;
+
+    // the block directories must rise: preKey of a block is the last key of the one before
+    for (u32 s = 0; s < n_here; ++s) {
+        const DecSeg* ds = &segs[seg0 + s];
+        const u32 nb = ds->nb;
+        const u32* dir = reinterpret_cast<const u32*>(streams + ds->dir_off);
+        bool falls = false;
+        for (u64 b = (u64)blockIdx.x * blockDim.x + t; b + 1 < nb; b += (u64)gridDim.x * blockDim.x)
+            falls |= dir[4 * (b + 1) + 1] <= dir[4 * b + 1];
+        if (falls) dec_fail(ctrl, FASTSGD_ERR_CORRUPT_STREAM, out_status, out_count, 1);
+    }
+
+    const u64 n_tiles = (dense_len + kTileKeys - 1) / kTileKeys;
+    const u64 t_begin = (u64)blockIdx.x * tiles_per_group;
+    u64 t_end = t_begin + tiles_per_group;
+    if (t_end > n_tiles) t_end = n_tiles;
+    if (t_begin >= n_tiles) return;
+
+    u32* s_pay = s_payall[w];
+    u32* s_flg = s_flgall[w];
+    u32* s_V = s_Vall[w];
+    u32* s_cod = s_codall[w];
+    const bool mine = w < n_here;
+    DecHead hd = {};
+    u64 stream_begin = 0;
+    if (mine) {
+        const DecSeg* ds = &segs[seg0 + w];
+        hd.KB = uniform(ds->KB); hd.l = uniform(ds->l); hd.tau = uniform(ds->tau); hd.nb = uniform(ds->nb);
+        hd.d = uniform64(ds->d);
+        hd.dir_off = uniform64(ds->dir_off); hd.blocks_off = uniform64(ds->blocks_off);
+        hd.total_words = uniform64(ds->total_words);
+        stream_begin = uniform64(ds->stream_begin);
+        const bool wide = hd.tau > 128u;
+        const u32 m0 = ds->V[lane], m1 = ds->V[lane + 64];
+        const u32 m2 = ds->V[lane + (wide ? 128u : 0u)], m3 = ds->V[lane + (wide ? 192u : 64u)];
+        s_V[lane] = m0;
+        s_V[lane + 64] = m1;
+        s_V[lane + 128] = wide ? m2 : m2 | 0x80000000u;
+        s_V[lane + 192] = wide ? m3 : m3 | 0x80000000u;
+        wave_lds_sync();
+    }
+    const u32 KB = hd.KB, l = hd.l, tau = hd.tau, nb = hd.nb;
+    const u32 cwid = uniform(code_width(tau ? tau : 1u));
+    const u32* dirs = reinterpret_cast<const u32*>(streams + hd.dir_off);
+
+    // the wave's place in its stream
+    bool ended = !mine || nb == 0;       // no round left to decode
+    bool have = false;                   // a round is in the registers (it may hold keys of tiles to come)
+    u32 kp[kLaneKeys], vb[kLaneKeys];
+#pragma unroll
+    for (u32 k = 0; k < kLaneKeys; ++k) { kp[k] = 0; vb[k] = 0; }
+    u32 n_cur = 0, last = 0;             // pairs of the round in the registers, its last key
+    u32 blk = 0, sub = 0, nsub = 0, cnt = 0;
+    u32 M = 1, pbits = 0, pbit = 0, carry = 0, next_pre = 0, pw_total = 0;
+    bool has_next = false;
+    const u32* fsrc = nullptr;
+    const u32* psrc = nullptr;
+    const uint8_t* codes = nullptr;
+    if (!ended && t_begin) {
+        const u32 r0 = (u32)(t_begin * kTileKeys) - 1u;       // the block whose preKey is the last one below the run
+        blk = uniform(dir_upper_index(nb, r0, [&](u32 i) { return dirs[4 * i + 1]; }));
+    }
+    auto stop = [&](u32 code) {
+        if (lane == 0) dec_fail(ctrl, code, out_status, out_count, 1);
+        ended = true;
+        have = false;
+    };
+    auto decode_next = [&]() {
+        if (sub == nsub) {               // open block blk
+            const u32* dir = dirs + 4ull * blk;
+            has_next = blk + 1 < nb;
+            const u32 dword = (lane < 4 || (lane < 8 && has_next)) ? dir[lane] : 0u;
+            const u32 off8 = read_lane(dword, 0), preKey = read_lane(dword, 1);
+            M = read_lane(dword, 2); pbits = read_lane(dword, 3);
+            const u32 next_off8_dir = read_lane(dword, 4);
+            next_pre = read_lane(dword, 5);
+            const u32 first = blk * KB;
+            cnt = uniform((u32)((hd.d - first < KB) ? hd.d - first : KB));
+            const u64 next_off8 = has_next ? (u64)next_off8_dir : hd.total_words;
+            const u32 fwords = (cnt * l + 63u) >> 6, pwords = (pbits + 63u) >> 6;
+            const bool bad = (M < 1 || M > 32) || (pbits > cnt * 32u) || ((u64)off8 + fwords + pwords != next_off8) ||
+                             ((u64)off8 + fwords + pwords > hd.total_words) || (blk == 0 && (off8 != 0 || preKey != 0));
+            if (bad) { stop(FASTSGD_ERR_CORRUPT_STREAM); return; }
+            fsrc = reinterpret_cast<const u32*>(streams + uniform64(hd.blocks_off + 8ull * off8));
+            psrc = fsrc + 2u * fwords;
+            pw_total = 2u * pwords;
+            codes = streams + uniform64(stream_begin + kHeaderBytes + (u64)(first >> 3) * cwid);
+            pbit = 0;
+            carry = preKey;
+            sub = 0;
+            nsub = (cnt + kSub - 1) / kSub;
+        }
+        const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
+        u32 lane_r = lane;
+        asm volatile("" : "+v"(lane_r));
+        const bool stream_start = (blk == 0 && sub == 0);
+        bool unused = false;
+        bool ok;
+        if (n == kSub)
+            ok = decode_round<true, kHand>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * (kSub / 8u) * cwid, n, l, M, tau,
+                                           cwid, pbits, pbit, carry, lane_r, s_pay, s_flg, s_cod, s_V, nullptr, nullptr, nullptr,
+                                           0, AdamArgs(), unused, stream_start, kp, vb);
+        else
+            ok = decode_round<false, kHand>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * (kSub / 8u) * cwid, n, l, M, tau,
+                                            cwid, pbits, pbit, carry, lane_r, s_pay, s_flg, s_cod, s_V, nullptr, nullptr, nullptr,
+                                            0, AdamArgs(), unused, stream_start, kp, vb);
+        if (!ok) { stop(FASTSGD_ERR_CORRUPT_STREAM); return; }
+        ++sub;
+        have = true;
+        n_cur = n;
+        last = carry;
+        if (sub == nsub) {
+            if (pbit != pbits || (has_next && carry != next_pre)) { stop(FASTSGD_ERR_CORRUPT_STREAM); return; }
+            ++blk;
+            if (blk == nb) ended = true;
+        }
+    };
+
+    for (u64 tile = t_begin; tile < t_end; ++tile) {
+        const u64 k0 = tile * kTileKeys;
+        const u32 klen = (u32)(dense_len - k0 < kTileKeys ? dense_len - k0 : kTileKeys);
+        const u64 k_end = k0 + klen;
+        float* dtile = dense + k0;
+        // tile in: 16 bytes per lane where the tile has them (the launch requires a 16-byte aligned vector)
+        for (u32 i = t * 4u; i < kTileKeys; i += kTileStreams * kWave * 4u) {
+            float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i + 4u <= klen) q = *reinterpret_cast<const float4*>(dtile + i);
+            else {
+                if (i < klen) q.x = dtile[i];
+                if (i + 1u < klen) q.y = dtile[i + 1u];
+                if (i + 2u < klen) q.z = dtile[i + 2u];
+            }
+            *reinterpret_cast<float4*>(&s_tile[i]) = q;
+        }
+        if (lane == 0) s_front[w] = mine ? 0u : klen;
+        __syncthreads();
+        // s_front[s]: stream s has added all its keys below k0 + s_front[s].  A wave adds a key only once
+        // the fronts of all streams before its own have passed it; the first stream never waits, so the
+        // waits end.
+        u32 my_front = 0;
+        while (mine) {
+            if (have) {
+                const u64 past = (u64)last + 1u;                       // first key the round does not hold
+                const u32 hi = past > k0 ? (u32)(past - k0 < klen ? past - k0 : klen) : 0u;
+                u32 spins = 0;
+                while (my_front < hi) {
+                    u32 lim = hi;
+                    if (w) {
+                        // the fronts of the streams before this one (lanes 0..w-1 read one each)
+                        u32 f = klen;
+                        if (lane < w) f = __hip_atomic_load(&s_front[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+#pragma unroll
+                        for (u32 j = 0; j < kTileStreams - 1; ++j) {
+                            const u32 fj = read_lane(f, j);
+                            lim = fj < lim ? fj : lim;
+                        }
+                        if (lim <= my_front) {
+                            // nothing to do yet.  The count only ends a wait that cannot end by itself (it never
+                            // has): the launch then reports a device failure instead of hanging
+                            if (++spins > kFrontSpins) {
+                                if (lane == 0) dec_fail(ctrl, FASTSGD_ERR_DEVICE, out_status, out_count, 1);
+                                lim = hi;
+                            } else {
+                                __builtin_amdgcn_s_sleep(2);
+                                continue;
+                            }
+                        }
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                    }
+                    // the round's keys in [my_front, lim) of the tile
+                    const u32 base = (u32)k0 + my_front, width = lim - my_front;
+                    float cur[kLaneKeys];
+                    bool on[kLaneKeys];
+#pragma unroll
+                    for (u32 k = 0; k < kLaneKeys; ++k) {
+                        const u32 idx = kp[k] - base;                 // (keys below wrap to far beyond)
+                        on[k] = idx < width && lane * kLaneKeys + k < n_cur;
+                        cur[k] = on[k] ? s_tile[idx + my_front] : 0.0f;
+                    }
+#pragma unroll
+                    for (u32 k = 0; k < kLaneKeys; ++k)
+                        if (on[k]) s_tile[kp[k] - (u32)k0] = cur[k] + __uint_as_float(vb[k]);
+                    my_front = lim;
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                    if (lane == 0) __hip_atomic_store(&s_front[w], my_front, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+                if (past >= k_end) break;                             // the rest of the round belongs to tiles to come
+            }
+            if (ended) break;
+            decode_next();
+            if (!have) break;                                         // (the stream is corrupt: reported, nothing more to add)
+        }
+        if (mine) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            if (lane == 0) __hip_atomic_store(&s_front[w], klen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        __syncthreads();
+        // tile out
+        for (u32 i = t * 4u; i < kTileKeys; i += kTileStreams * kWave * 4u) {
+            const float4 q = *reinterpret_cast<const float4*>(&s_tile[i]);
+            if (i + 4u <= klen) *reinterpret_cast<float4*>(dtile + i) = q;
+            else {
+                if (i < klen) dtile[i] = q.x;
+                if (i + 1u < klen) dtile[i + 1u] = q.y;
+                if (i + 2u < klen) dtile[i + 2u] = q.z;
+            }
+        }
+        __syncthreads();
+    }
+    // A block the wave has opened is decoded to its end (its last round carries the checks of the whole block,
+    // and the next workgroup may start behind it).  Behind the last tile the same goes for the rest of every
+    // stream: what is left there lies beyond the dense vector, unless it is corrupt, which outranks that.
+    const bool last_group = t_end == n_tiles;
+    bool big = have && (u64)last >= dense_len;
+    while (!ended && (last_group || sub != nsub)) {
+        decode_next();
+        big = big || have;
+    }
+    if (last_group && big && lane == 0) dec_fail(ctrl, FASTSGD_ERR_BUFFER_TOO_SMALL, out_status, out_count, 1);
 }
 
 }  // namespace fsgd

@@ -90,3 +90,98 @@ def test_aggregate_of_streams_with_narrow_and_nine_bit_tokens():
     rc, status, cnt, got = hip_accumulate(blob, offs, np.zeros(dim, np.float32))
     assert rc == B.OK and status == 0 and cnt == cnt_ref
     assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+# --- dense gradients: the library adds them in one pass over the dense vector (groups of eight streams, a
+# tile of 16384 keys at a time, runs of tiles per workgroup); the cases below are sized so that this form is
+# the one that runs (the streams' bytes, times four, reach the vector's length per group of eight), with
+# vectors that end inside a tile and inside a 16-byte piece, blocks of one to four rounds, partial groups
+
+def dense_streams(n_workers, dim, nnz, keep, kb, seed, taus=(128,)):
+    from paper_2112_04291_amd import workloads as W
+    rng = np.random.default_rng(seed)
+    blobs, offs = [], [0]
+    for wkr in range(n_workers):
+        keys = np.sort(rng.choice(dim, nnz, replace=False)).astype(np.uint32)
+        vals = rng.laplace(0.0, 1e-3 * (wkr + 1), nnz).astype(np.float32)
+        tau = taus[wkr % len(taus)]
+        rc, st = ref.compress(keys, vals, ref.params(W.solve_base(vals, keep, tau), tau, 1 + wkr % 4, kb))
+        assert rc == ref.OK
+        blobs.append(st)
+        offs.append(offs[-1] + st.size)
+    blob, offs = np.concatenate(blobs), np.array(offs, np.uint64)
+    assert 4 * blob.size >= dim * (-(-n_workers // 8)) and n_workers >= 2       # (the library's own test for this form)
+    return blob, offs
+
+
+def check_against_oracle(blob, offs, dense0):
+    from paper_2112_04291_amd import binding as B
+    want = dense0.copy()
+    rc_ref, cnt_ref = ref.decompress_accumulate(blob, offs, want)
+    rc, status, cnt, got = hip_accumulate(blob, offs, dense0)
+    assert rc == B.OK and status == rc_ref
+    if rc_ref == ref.OK:
+        assert cnt == cnt_ref
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    else:
+        assert cnt == 0
+    return rc_ref
+
+
+@pytest.mark.parametrize("n_workers,dim,nnz,keep,kb", [(9, 200_003, 120_000, 0.5, 1024), (4, 150_001, 100_000, 0.9, 4096),
+                                                       (8, 70_000, 60_000, 1.0, 1024), (3, 3 * 16384, 30_000, 0.6, 2048),
+                                                       (2, 16_385, 9_000, 0.7, 1024), (17, 1_000_000, 400_000, 0.25, 1024),
+                                                       (5, 2_000_002, 1_500_000, 0.8, 1024)])
+def test_aggregate_in_one_pass_matches_oracle_bit_for_bit(n_workers, dim, nnz, keep, kb):
+    blob, offs = dense_streams(n_workers, dim, nnz, keep, kb, 900 + n_workers, taus=(128, 16, 200))
+    rng = np.random.default_rng(6)
+    dense0 = rng.standard_normal(dim).astype(np.float32) * np.float32(1e-3)
+    assert check_against_oracle(blob, offs, dense0) == ref.OK
+
+
+def test_aggregate_in_one_pass_reports_keys_beyond_the_vector():
+    blob, offs = dense_streams(3, 300_000, 200_000, 0.8, 1024, 21)
+    for short in (299_000, 150_000, 20_000, 1):            # the last: every key but key 0 lies beyond
+        assert check_against_oracle(blob, offs, np.zeros(short, np.float32)) == ref.ERR_BUFFER_TOO_SMALL
+
+
+def test_aggregate_in_one_pass_rejects_damaged_streams():
+    import struct
+    from tests.streamparse import parse
+    blob, offs = dense_streams(3, 120_000, 60_000, 0.9, 2048, 22)
+    a, b = int(offs[1]), int(offs[2])
+    info = parse(blob[a:b])
+    dir_off = 64 + 8 * (-(-(info["d"] * info["w"]) // 64))
+    assert info["nb"] >= 8
+    cases = []
+    for blk in (1, info["nb"] // 2, info["nb"] - 1):
+        bad = blob.copy()                                  # a directory whose preKeys do not rise
+        pre = struct.unpack_from("<I", bad, a + dir_off + 16 * blk + 4)[0]
+        struct.pack_into("<I", bad, a + dir_off + 16 * blk + 4, struct.unpack_from("<I", bad, a + dir_off + 16 * (blk - 1) + 4)[0])
+        cases.append(bad)
+        bad = blob.copy()                                  # a preKey that is off by one
+        struct.pack_into("<I", bad, a + dir_off + 16 * blk + 4, pre + 1)
+        cases.append(bad)
+        bad = blob.copy()                                  # payload bits of the block one short
+        pb = struct.unpack_from("<I", bad, a + dir_off + 16 * blk + 12)[0]
+        struct.pack_into("<I", bad, a + dir_off + 16 * blk + 12, pb - 1)
+        cases.append(bad)
+    bad = blob.copy()
+    bad[a + 64] |= 0x7F                                    # a code beyond tau... or not: the oracle says which
+    cases.append(bad)
+    for rank in (1, 3000, info["d"] - 1):
+        from tests.streamparse import with_zero_delta
+        bad = blob.copy()
+        bad[a:b] = with_zero_delta(blob[a:b], rank)
+        cases.append(bad)
+    n_bad = 0
+    for bad in cases:
+        n_bad += check_against_oracle(bad, offs, np.zeros(120_000, np.float32)) == ref.ERR_CORRUPT_STREAM
+    assert n_bad >= len(cases) - 1
+    # damaged behind the end of a vector that is too short as well: corrupt is what is reported (the first
+    # stream here: the oracle stops at the first stream that fails, the library reports the gravest failure)
+    first = parse(blob[:int(offs[1])])
+    dir0 = 64 + 8 * (-(-(first["d"] * first["w"]) // 64))
+    bad = blob.copy()
+    struct.pack_into("<I", bad, dir0 + 16 * (first["nb"] - 1) + 12, 0)
+    assert check_against_oracle(bad, offs, np.zeros(60_000, np.float32)) == ref.ERR_CORRUPT_STREAM
