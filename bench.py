@@ -514,26 +514,42 @@ def main():
         aws = B.decoder_workspace(n_streams)
         count, status, obytes, ws, dws = case.count, case.status, case.obytes, case.ws, case.dws
         keys = None if case.dense else case.keys[0]
+        cap_w = max(B.compressed_size(n, pt["p"]) for pt in points)
+        wout = torch.empty(cap_w // 8 + 8, dtype=torch.int64, device="cuda")
         for pt in points:
             sb = pt["bytes"]
-            many = torch.cat([pt["out"].view(torch.uint8)[:sb]] * n_streams + [torch.zeros(64, dtype=torch.uint8, device="cuda")])
-            offs = torch.tensor([i * sb for i in range(n_streams + 1)], dtype=torch.int64, device="cuda")
+            # the workers' gradients: the same values, rotated by a different amount for every worker, so that
+            # the streams hold different keys (same keep fraction, same base)
+            parts, sizes = [], []
+            for wkr in range(n_streams):
+                vals_w = torch.roll(case.values[0], wkr * 15485863) if wkr else case.values[0]
+                rc = B.compress(keys, vals_w, pt["p"], wout, obytes, status, ws, n=n, out_capacity=cap_w)
+                torch.cuda.synchronize()
+                assert rc == B.OK and int(status[0]) == B.OK
+                sizes.append(int(obytes[0]))
+                parts.append(wout.view(torch.uint8)[:sizes[-1]].clone())
+                del vals_w
+            d_all = sum(int(x[40:48].cpu().numpy().view("<u8")[0]) for x in parts)
+            many = torch.cat(parts + [torch.zeros(64, dtype=torch.uint8, device="cuda")])
+            offs = torch.tensor([sum(sizes[:i]) for i in range(n_streams + 1)], dtype=torch.int64, device="cuda")
+            total_w = sum(sizes)
+            del parts
 
             def do_acc(_):
-                assert B.decompress_accumulate(many, n_streams * sb, offs, n_streams, dense, count, status, aws) == B.OK
+                assert B.decompress_accumulate(many, total_w, offs, n_streams, dense, count, status, aws) == B.OK
 
             def do_adam(_):
                 assert B.decompress_adam(pt["out"], sb, theta, m1, v1, 1e-3, 0.9, 0.999, 1e-8, count, status, aws) == B.OK
 
             a_ms = timer.eager(do_acc, args.steps)
-            assert int(status[0]) == B.OK and int(count[0]) == n_streams * pt["d"]
+            assert int(status[0]) == B.OK and int(count[0]) == d_all
             u_ms = timer.eager(do_adam, args.steps)
             assert int(status[0]) == B.OK and int(count[0]) == pt["d"]
             widening.append(dict(keep=pt["keep"], d=pt["d"], accumulate_streams=n_streams, accumulate_ms=a_ms, adam_ms=u_ms,
-                                 accumulate_pairs_per_s=float(n_streams) * pt["d"] / a_ms * 1e3,
+                                 accumulate_pairs=d_all, accumulate_pairs_per_s=float(d_all) / a_ms * 1e3,
                                  adam_pairs_per_s=pt["d"] / u_ms * 1e3))
             del many
-        del dense, theta, m1, v1
+        del dense, theta, m1, v1, wout
         # the paper's base b = 1.1 with the threshold that keeps about the same fraction (b^tau = base^128;
         # above 128 a token is 9 bits)
         cap_all = max(B.compressed_size(n, B.params(1.1, 256)), B.compressed_size(n, points[0]["p"]))

@@ -292,7 +292,7 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
     for (u32 k = 0; k < 17; ++k)
         if (k * 64u < npw) s_pay[k * 64u + lane] = pwd[k];                         // (zeros behind the payload)
     wave_lds_sync();
-    if (cwid != 8) {
+    if (MODE != kHand && cwid != 8) {
         // token i of the round sits at bit i * cwid of the round's words; narrow ones are widened to the
         // byte form (sign in bit 7, code-1 below) through shared memory
         const u32* cwords = reinterpret_cast<const u32*>(codes_round);
@@ -375,7 +375,22 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
     // carry into bit 7 of (code-1) + (128 - tau), tested four bytes at a time
     bool badcode = false;
     u32 vb[kLaneKeys];
-    if (cwid <= 8) {
+    if (MODE == kHand && cwid != 8) {
+        // (this form keeps its shared memory small: the lane's tokens come straight from the token words, two
+        // cached loads a token)
+        const u32* cwords = reinterpret_cast<const u32*>(codes_round);
+        const u32 ncw = (n * cwid + 31u) >> 5, tmask = (1u << cwid) - 1u, cmask = tmask >> 1;
+#pragma unroll
+        for (u32 k = 0; k < kLaneKeys; ++k) {
+            const u32 i = lane * kLaneKeys + k, pos = i * cwid, wa = pos >> 5;
+            const u32 w0 = wa < ncw ? cwords[wa] : 0u, w1 = wa + 1u < ncw ? cwords[wa + 1u] : 0u;
+            u32 tok = __builtin_amdgcn_alignbit(w1, w0, pos & 31u) & tmask;
+            if (!FULL && i >= n) tok = 0;
+            const u32 c1 = tok & cmask, sign = tok >> (cwid - 1u);
+            badcode |= c1 >= tau;
+            vb[k] = cwid < 8 ? s_V[(sign << 7) | c1] : (s_V[c1 & 0xFFu] | (sign << 31));
+        }
+    } else if (cwid <= 8) {
         const u32 over = (128u - tau) * 0x01010101u;
         u32 badbits = 0;
 #pragma unroll
@@ -385,18 +400,8 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         for (u32 k = 0; k < kLaneKeys; ++k) vb[k] = s_V[(cw[k >> 2] >> (8u * (k & 3u))) & 0xFFu];
     }
     if (MODE == kHand) {
-        // the caller takes the pairs as they are, 16 consecutive ones per lane (keys beyond n repeat the last key,
-        // their values are the first code's: the caller knows n)
-        if (cwid > 8) {
-#pragma unroll
-            for (u32 k = 0; k < kLaneKeys; ++k) {
-                const u32 i = lane * kLaneKeys + k, pos = i * 9u, wa = pos >> 5;
-                u32 tok = __builtin_amdgcn_alignbit(s_cod[wa + 1u], s_cod[wa], pos & 31u) & 0x1FFu;
-                if (!FULL && i >= n) tok = 0;
-                badcode |= (tok & 0xFFu) >= tau;
-                vb[k] = s_V[tok & 0xFFu] | ((tok >> 8) << 31);
-            }
-        }
+        // the caller takes the pairs as they are, 16 consecutive ones per lane (those beyond n repeat the last key,
+        // their values mean nothing: the caller knows n)
 #pragma unroll
         for (u32 k = 0; k < kLaneKeys; ++k) { out_keys[k] = kp[k]; out_vals[k] = vb[k]; }
         carry = read_lane(kp[kLaneKeys - 1], 63);           // (keys beyond n add nothing: the last lane ends on the round's last key)
@@ -718,15 +723,17 @@ __device__ __forceinline__ u32 dir_upper_index(u32 n, u32 x, Value pre) {
     return lo;
 }
 
-__global__ void __launch_bounds__(kTileStreams * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
+template <bool AHEAD, u32 TILE>
+__global__ void __launch_bounds__(kTileStreams * kWave) __attribute__((amdgpu_waves_per_eu(AHEAD ? 2 : 4, AHEAD ? 2 : 4)))
 k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u32 seg0, u32 n_here,
                    DecCtrl* ctrl, u64* out_count, u32* out_status, float* __restrict__ dense, u64 dense_len,
                    u32 tiles_per_group) {
-    __shared__ __attribute__((aligned(16))) float s_tile[kTileKeys];
+    static_assert(TILE % (kTileStreams * kWave * 4) == 0, "whole 16-byte pieces for every thread");
+    constexpr u32 kPieces = TILE / (kTileStreams * kWave * 4);
+    __shared__ __attribute__((aligned(16))) float s_tile[TILE + kWave];      // (the last 64: a place to write for lanes with nothing to add)
     __shared__ __attribute__((aligned(16))) u32 s_payall[kTileStreams][17 * 64];      // payload window of a round
     __shared__ u32 s_flgall[kTileStreams][3 * 64];
     __shared__ u32 s_Vall[kTileStreams][256];
-    __shared__ __attribute__((aligned(16))) u32 s_codall[kTileStreams][2 * kCodeWords];
     __shared__ u32 s_front[kTileStreams];
     __shared__ u32 s_go;
     const u32 lane = lane_id(), w = uniform(wave_id()), t = threadIdx.x;
@@ -745,7 +752,7 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
         if (falls) dec_fail(ctrl, FASTSGD_ERR_CORRUPT_STREAM, out_status, out_count, 1);
     }
 
-    const u64 n_tiles = (dense_len + kTileKeys - 1) / kTileKeys;
+    const u64 n_tiles = (dense_len + TILE - 1) / TILE;
     const u64 t_begin = (u64)blockIdx.x * tiles_per_group;
     u64 t_end = t_begin + tiles_per_group;
     if (t_end > n_tiles) t_end = n_tiles;
@@ -754,7 +761,7 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
     u32* s_pay = s_payall[w];
     u32* s_flg = s_flgall[w];
     u32* s_V = s_Vall[w];
-    u32* s_cod = s_codall[w];
+    u32* s_cod = nullptr;                // (rounds handed back never stage their tokens)
     const bool mine = w < n_here;
     DecHead hd = {};
     u64 stream_begin = 0;
@@ -781,10 +788,12 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
     // the wave's place in its stream
     bool ended = !mine || nb == 0;       // no round left to decode
     bool have = false;                   // a round is in the registers (it may hold keys of tiles to come)
-    u32 kp[kLaneKeys], vb[kLaneKeys];
+    bool ahead = false;                  // ... and the one after it as well, decoded while the wave had to wait
+    u32 kp[kLaneKeys], vb[kLaneKeys], kq[kLaneKeys], vq[kLaneKeys];
 #pragma unroll
-    for (u32 k = 0; k < kLaneKeys; ++k) { kp[k] = 0; vb[k] = 0; }
+    for (u32 k = 0; k < kLaneKeys; ++k) { kp[k] = 0; vb[k] = 0; kq[k] = 0; vq[k] = 0; }
     u32 n_cur = 0, last = 0;             // pairs of the round in the registers, its last key
+    u32 n_ahead = 0, last_ahead = 0;     // the same of the round decoded ahead
     u32 blk = 0, sub = 0, nsub = 0, cnt = 0;
     u32 M = 1, pbits = 0, pbit = 0, carry = 0, next_pre = 0, pw_total = 0;
     bool has_next = false;
@@ -792,14 +801,16 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
     const u32* psrc = nullptr;
     const uint8_t* codes = nullptr;
     if (!ended && t_begin) {
-        const u32 r0 = (u32)(t_begin * kTileKeys) - 1u;       // the block whose preKey is the last one below the run
+        const u32 r0 = (u32)(t_begin * TILE) - 1u;       // the block whose preKey is the last one below the run
         blk = uniform(dir_upper_index(nb, r0, [&](u32 i) { return dirs[4 * i + 1]; }));
     }
     auto stop = [&](u32 code) {
         if (lane == 0) dec_fail(ctrl, code, out_status, out_count, 1);
         ended = true;
         have = false;
+        ahead = false;
     };
+    // decodes the stream's next round into the registers of the round ahead
     auto decode_next = [&]() {
         if (sub == nsub) {               // open block blk
             const u32* dir = dirs + 4ull * blk;
@@ -834,51 +845,120 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
         if (n == kSub)
             ok = decode_round<true, kHand>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * (kSub / 8u) * cwid, n, l, M, tau,
                                            cwid, pbits, pbit, carry, lane_r, s_pay, s_flg, s_cod, s_V, nullptr, nullptr, nullptr,
-                                           0, AdamArgs(), unused, stream_start, kp, vb);
+                                           0, AdamArgs(), unused, stream_start, kq, vq);
         else
             ok = decode_round<false, kHand>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * (kSub / 8u) * cwid, n, l, M, tau,
                                             cwid, pbits, pbit, carry, lane_r, s_pay, s_flg, s_cod, s_V, nullptr, nullptr, nullptr,
-                                            0, AdamArgs(), unused, stream_start, kp, vb);
+                                            0, AdamArgs(), unused, stream_start, kq, vq);
         if (!ok) { stop(FASTSGD_ERR_CORRUPT_STREAM); return; }
         ++sub;
-        have = true;
-        n_cur = n;
-        last = carry;
+        ahead = true;
+        n_ahead = n;
+        last_ahead = carry;
         if (sub == nsub) {
             if (pbit != pbits || (has_next && carry != next_pre)) { stop(FASTSGD_ERR_CORRUPT_STREAM); return; }
             ++blk;
             if (blk == nb) ended = true;
         }
     };
+    // the round ahead becomes the round in hand
+    auto step = [&]() {
+#pragma unroll
+        for (u32 k = 0; k < kLaneKeys; ++k) { kp[k] = kq[k]; vb[k] = vq[k]; }
+        n_cur = n_ahead;
+        last = last_ahead;
+        have = true;
+        ahead = false;
+    };
 
-    for (u64 tile = t_begin; tile < t_end; ++tile) {
-        const u64 k0 = tile * kTileKeys;
-        const u32 klen = (u32)(dense_len - k0 < kTileKeys ? dense_len - k0 : kTileKeys);
+    // One loop over the tiles of the run and a last turn without a tile, written so that the round decoder
+    // appears once in the code: it is long, the waves of a workgroup are all at different places of the kernel
+    // and share one instruction cache.
+    const bool last_group = t_end == n_tiles;
+    bool big = false;                    // the stream holds keys beyond the dense vector
+    float4 q[kPieces];                   // a whole tile on its way from memory, a 16-byte piece per thread and step
+    bool fetched = false;
+#pragma unroll
+    for (u32 j = 0; j < kPieces; ++j) q[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (u64 tile = t_begin;; ++tile) {
+        const bool tail = tile >= t_end;
+        const u64 k0 = tile * TILE;
+        const u32 klen = tail ? 0u : (u32)(dense_len - k0 < TILE ? dense_len - k0 : TILE);
         const u64 k_end = k0 + klen;
-        float* dtile = dense + k0;
-        // tile in: 16 bytes per lane where the tile has them (the launch requires a 16-byte aligned vector)
-        for (u32 i = t * 4u; i < kTileKeys; i += kTileStreams * kWave * 4u) {
-            float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (i + 4u <= klen) q = *reinterpret_cast<const float4*>(dtile + i);
-            else {
-                if (i < klen) q.x = dtile[i];
-                if (i + 1u < klen) q.y = dtile[i + 1u];
-                if (i + 2u < klen) q.z = dtile[i + 2u];
+        float* dtile = dense + (tail ? 0 : k0);
+        if (!tail) {
+            // tile in: 16 bytes per lane (the launch requires a 16-byte aligned vector).  A whole tile was fetched
+            // into registers while the tile before it was at work (the run's first one: just now)
+            if (klen == TILE) {
+                if (!fetched) {
+#pragma unroll
+                    for (u32 j = 0; j < kPieces; ++j) q[j] = reinterpret_cast<const float4*>(dtile)[t + j * kTileStreams * kWave];
+                    // (all of them under way before the first one is used: otherwise the compiler waits for each)
+#pragma unroll
+                    for (u32 j = 0; j + 1 < kPieces; j += 2)
+                        asm volatile("" : "+v"(q[j].x), "+v"(q[j].y), "+v"(q[j].z), "+v"(q[j].w), "+v"(q[j + 1].x), "+v"(q[j + 1].y),
+                                          "+v"(q[j + 1].z), "+v"(q[j + 1].w));
+                }
+#pragma unroll
+                for (u32 j = 0; j < kPieces; ++j) reinterpret_cast<float4*>(s_tile)[t + j * kTileStreams * kWave] = q[j];
+            } else {
+                for (u32 i = t * 4u; i < TILE; i += kTileStreams * kWave * 4u) {
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (i + 4u <= klen) v = *reinterpret_cast<const float4*>(dtile + i);
+                    else {
+                        if (i < klen) v.x = dtile[i];
+                        if (i + 1u < klen) v.y = dtile[i + 1u];
+                        if (i + 2u < klen) v.z = dtile[i + 2u];
+                    }
+                    *reinterpret_cast<float4*>(&s_tile[i]) = v;
+                }
             }
-            *reinterpret_cast<float4*>(&s_tile[i]) = q;
+            // the next tile, if it is a whole one: on its way while this one is at work
+            fetched = tile + 1 < t_end && dense_len - (k0 + TILE) >= TILE;
+            if (fetched) {
+#pragma unroll
+                for (u32 j = 0; j < kPieces; ++j) q[j] = reinterpret_cast<const float4*>(dtile + TILE)[t + j * kTileStreams * kWave];
+            }
+            if (lane == 0) s_front[w] = mine ? 0u : klen;
+            __syncthreads();
+        } else {
+            big = (have && (u64)last >= dense_len) || ahead;      // (the round ahead lies behind the one in hand)
         }
-        if (lane == 0) s_front[w] = mine ? 0u : klen;
-        __syncthreads();
         // s_front[s]: stream s has added all its keys below k0 + s_front[s].  A wave adds a key only once
         // the fronts of all streams before its own have passed it; the first stream never waits, so the
         // waits end.
-        u32 my_front = 0;
-        while (mine) {
-            if (have) {
+        u32 my_front = 0, spins = 0;
+        u32 phase = mine ? 0u : 2u;          // 0: at work on the tile, 1: through with it, 2: leave
+        while (phase < 2u) {
+            bool fetch = false;              // decode the stream's next round
+            if (tail) {
+                // A block the wave has opened is decoded to its end (its last round carries the checks of the
+                // whole block, and the next workgroup may start behind it).  Behind the last tile the same goes
+                // for the rest of every stream: what is left there lies beyond the dense vector, unless it is
+                // corrupt, which outranks that.
+                big = big || ahead;
+                fetch = !ended && (last_group || sub != nsub);
+                if (!fetch) phase = 2u;
+            } else if (phase == 1u) {
+                // while other streams are still at work on the tile: the round after the one in hand
+                if (AHEAD && !ahead && !ended) {
+                    u32 f = klen;
+                    if (lane < n_here) f = __hip_atomic_load(&s_front[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    fetch = __any(f < klen);
+                }
+                phase = 2u;
+            } else if (!have) {
+                if (ahead) step();
+                else if (ended) phase = 1u;
+                else fetch = true;
+            } else {
                 const u64 past = (u64)last + 1u;                       // first key the round does not hold
                 const u32 hi = past > k0 ? (u32)(past - k0 < klen ? past - k0 : klen) : 0u;
-                u32 spins = 0;
-                while (my_front < hi) {
+                if (my_front >= hi) {
+                    // the round has nothing more for this tile
+                    if (past >= k_end) phase = 1u;                     // ... but for tiles to come
+                    else have = false;
+                } else {
                     u32 lim = hi;
                     if (w) {
                         // the fronts of the streams before this one (lanes 0..w-1 read one each)
@@ -889,67 +969,67 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
                             const u32 fj = read_lane(f, j);
                             lim = fj < lim ? fj : lim;
                         }
-                        if (lim <= my_front) {
-                            // nothing to do yet.  The count only ends a wait that cannot end by itself (it never
-                            // has): the launch then reports a device failure instead of hanging
-                            if (++spins > kFrontSpins) {
-                                if (lane == 0) dec_fail(ctrl, FASTSGD_ERR_DEVICE, out_status, out_count, 1);
-                                lim = hi;
-                            } else {
-                                __builtin_amdgcn_s_sleep(2);
-                                continue;
-                            }
-                        }
+                    }
+                    if (lim <= my_front) {
+                        // nothing to add yet: time to decode the round after this one
+                        if (AHEAD && !ahead && !ended) fetch = true;
+                        else if (++spins > kFrontSpins) {
+                            // (only ends a wait that cannot end by itself, which has never been seen: the launch
+                            // then reports a device failure instead of hanging)
+                            if (lane == 0) dec_fail(ctrl, FASTSGD_ERR_DEVICE, out_status, out_count, 1);
+                            have = false; ahead = false; ended = true;
+                        } else __builtin_amdgcn_s_sleep(2);
+                    } else {
                         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                    }
-                    // the round's keys in [my_front, lim) of the tile
-                    const u32 base = (u32)k0 + my_front, width = lim - my_front;
-                    float cur[kLaneKeys];
-                    bool on[kLaneKeys];
+                        // The round's keys in [my_front, lim) of the tile: sixteen reads, sixteen additions, sixteen
+                        // writes, without a branch -- a key outside the range takes the lane's own entry behind the
+                        // tile instead, which nobody reads.
+                        const u32 base = (u32)k0, width = lim - my_front;
+                        const u32 mine_n = n_cur > lane * kLaneKeys ? n_cur - lane * kLaneKeys : 0u;   // the lane's pairs
+                        u32 at[kLaneKeys];
+                        float cur[kLaneKeys];
 #pragma unroll
-                    for (u32 k = 0; k < kLaneKeys; ++k) {
-                        const u32 idx = kp[k] - base;                 // (keys below wrap to far beyond)
-                        on[k] = idx < width && lane * kLaneKeys + k < n_cur;
-                        cur[k] = on[k] ? s_tile[idx + my_front] : 0.0f;
-                    }
+                        for (u32 k = 0; k < kLaneKeys; ++k) {
+                            const u32 idx = kp[k] - base;                 // (keys below the tile wrap to far beyond it)
+                            at[k] = (idx - my_front < width && k < mine_n) ? idx : TILE + lane;
+                            cur[k] = s_tile[at[k]];
+                        }
 #pragma unroll
-                    for (u32 k = 0; k < kLaneKeys; ++k)
-                        if (on[k]) s_tile[kp[k] - (u32)k0] = cur[k] + __uint_as_float(vb[k]);
-                    my_front = lim;
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-                    if (lane == 0) __hip_atomic_store(&s_front[w], my_front, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        for (u32 k = 0; k < kLaneKeys; ++k) s_tile[at[k]] = cur[k] + __uint_as_float(vb[k]);
+                        my_front = lim;
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                        if (lane == 0) __hip_atomic_store(&s_front[w], my_front, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    }
                 }
-                if (past >= k_end) break;                             // the rest of the round belongs to tiles to come
             }
-            if (ended) break;
-            decode_next();
-            if (!have) break;                                         // (the stream is corrupt: reported, nothing more to add)
+            if (phase == 1u && !tail) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                if (lane == 0) __hip_atomic_store(&s_front[w], klen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+            if (fetch) {
+                decode_next();
+                if (!AHEAD && ahead && !tail) step();      // (without the second set of registers the round is taken up at once)
+            }
         }
-        if (mine) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            if (lane == 0) __hip_atomic_store(&s_front[w], klen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        }
+        if (tail) break;
         __syncthreads();
         // tile out
-        for (u32 i = t * 4u; i < kTileKeys; i += kTileStreams * kWave * 4u) {
-            const float4 q = *reinterpret_cast<const float4*>(&s_tile[i]);
-            if (i + 4u <= klen) *reinterpret_cast<float4*>(dtile + i) = q;
-            else {
-                if (i < klen) dtile[i] = q.x;
-                if (i + 1u < klen) dtile[i + 1u] = q.y;
-                if (i + 2u < klen) dtile[i + 2u] = q.z;
+        if (klen == TILE) {
+#pragma unroll
+            for (u32 j = 0; j < kPieces; ++j)
+                reinterpret_cast<float4*>(dtile)[t + j * kTileStreams * kWave] = reinterpret_cast<const float4*>(s_tile)[t + j * kTileStreams * kWave];
+        } else {
+            for (u32 i = t * 4u; i < TILE; i += kTileStreams * kWave * 4u) {
+                const float4 q = *reinterpret_cast<const float4*>(&s_tile[i]);
+                if (i + 4u <= klen) *reinterpret_cast<float4*>(dtile + i) = q;
+                else {
+                    if (i < klen) dtile[i] = q.x;
+                    if (i + 1u < klen) dtile[i + 1u] = q.y;
+                    if (i + 2u < klen) dtile[i + 2u] = q.z;
+                }
             }
         }
         __syncthreads();
-    }
-    // A block the wave has opened is decoded to its end (its last round carries the checks of the whole block,
-    // and the next workgroup may start behind it).  Behind the last tile the same goes for the rest of every
-    // stream: what is left there lies beyond the dense vector, unless it is corrupt, which outranks that.
-    const bool last_group = t_end == n_tiles;
-    bool big = have && (u64)last >= dense_len;
-    while (!ended && (last_group || sub != nsub)) {
-        decode_next();
-        big = big || have;
     }
     if (last_group && big && lane == 0) dec_fail(ctrl, FASTSGD_ERR_BUFFER_TOO_SMALL, out_status, out_count, 1);
 }
