@@ -10,8 +10,7 @@
 
 namespace fsgd {
 
-#ifndef FSGD_AGG_AHEAD
-#define FSGD_AGG_AHEAD true
+#ifndef FSGD_AGG_TILE
 #define FSGD_AGG_TILE 24576
 #endif
 constexpr u64 kDecSegBytes = 1152;   // >= sizeof(DecSeg)
@@ -325,18 +324,17 @@ static fastsgd_status accumulate_impl(const void* d_streams, size_t total_bytes,
     const bool by_tiles = n_streams >= 2 && dense_len >= 1 && ((uintptr_t)d_dense & 15) == 0 &&
                           (u64)total_bytes * 4 >= dense_len * n_groups;
     if (by_tiles) {
-        // two workgroups per compute unit, each with a run of tiles of its own (short vectors: runs of three, so
+        // a workgroup per compute unit, each with a run of tiles of its own (short vectors: runs of three, so
         // that few tiles do not mean as many workgroups that each start every stream afresh)
-        constexpr bool kAhead = FSGD_AGG_AHEAD;
         constexpr u32 kTile = FSGD_AGG_TILE;
         const u64 n_tiles = (dense_len + kTile - 1) / kTile;
-        const u64 groups = (u64)cus * (kAhead ? 1 : 2);
+        const u64 groups = cus;
         u64 per = (n_tiles + groups - 1) / groups;
         if (per < 3) per = n_tiles < 3 ? n_tiles : 3;
         const u32 grid = (u32)((n_tiles + per - 1) / per);
         for (u32 s0 = 0; s0 < n_streams; s0 += kTileStreams) {
             const u32 n_here = n_streams - s0 < kTileStreams ? n_streams - s0 : kTileStreams;
-            hipLaunchKernelGGL((k_accumulate_tiles<kAhead, kTile>), dim3(grid), dim3(kTileStreams * kWave), 0, stream, streams, segs,
+            hipLaunchKernelGGL((k_accumulate_tiles<kTile>), dim3(grid), dim3(kTileStreams * kWave), 0, stream, streams, segs,
                                s0, n_here, ctrl, d_count, d_status, d_dense, dense_len, (u32)per);
         }
         return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;

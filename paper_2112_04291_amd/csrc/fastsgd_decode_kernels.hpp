@@ -723,8 +723,8 @@ __device__ __forceinline__ u32 dir_upper_index(u32 n, u32 x, Value pre) {
     return lo;
 }
 
-template <bool AHEAD, u32 TILE>
-__global__ void __launch_bounds__(kTileStreams * kWave) __attribute__((amdgpu_waves_per_eu(AHEAD ? 2 : 4, AHEAD ? 2 : 4)))
+template <u32 TILE>
+__global__ void __launch_bounds__(kTileStreams * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict__ segs, u32 seg0, u32 n_here,
                    DecCtrl* ctrl, u64* out_count, u32* out_status, float* __restrict__ dense, u64 dense_len,
                    u32 tiles_per_group) {
@@ -787,13 +787,14 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
 
     // the wave's place in its stream
     bool ended = !mine || nb == 0;       // no round left to decode
-    bool have = false;                   // a round is in the registers (it may hold keys of tiles to come)
-    bool ahead = false;                  // ... and the one after it as well, decoded while the wave had to wait
-    u32 kp[kLaneKeys], vb[kLaneKeys], kq[kLaneKeys], vq[kLaneKeys];
+    bool have = false;                   // the registers hold a round (it may reach into tiles to come)
+    bool ahead = false;                  // ... and the one after it, decoded while the wave had to wait
+    u32 kp[kLaneKeys], vb[kLaneKeys];    // the round in hand, 16 consecutive pairs per lane
+    u32 kq[kLaneKeys], vq[kLaneKeys];    // the round ahead
 #pragma unroll
     for (u32 k = 0; k < kLaneKeys; ++k) { kp[k] = 0; vb[k] = 0; kq[k] = 0; vq[k] = 0; }
-    u32 n_cur = 0, last = 0;             // pairs of the round in the registers, its last key
-    u32 n_ahead = 0, last_ahead = 0;     // the same of the round decoded ahead
+    u32 n_cur = 0, last = 0;             // pairs of the round in hand, its last key
+    u32 n_ahead = 0, last_ahead = 0;
     u32 blk = 0, sub = 0, nsub = 0, cnt = 0;
     u32 M = 1, pbits = 0, pbit = 0, carry = 0, next_pre = 0, pw_total = 0;
     bool has_next = false;
@@ -801,7 +802,7 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
     const u32* psrc = nullptr;
     const uint8_t* codes = nullptr;
     if (!ended && t_begin) {
-        const u32 r0 = (u32)(t_begin * TILE) - 1u;       // the block whose preKey is the last one below the run
+        const u32 r0 = (u32)(t_begin * TILE) - 1u;            // the block whose preKey is the last one below the run
         blk = uniform(dir_upper_index(nb, r0, [&](u32 i) { return dirs[4 * i + 1]; }));
     }
     auto stop = [&](u32 code) {
@@ -861,104 +862,122 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
             if (blk == nb) ended = true;
         }
     };
-    // the round ahead becomes the round in hand
-    auto step = [&]() {
-#pragma unroll
-        for (u32 k = 0; k < kLaneKeys; ++k) { kp[k] = kq[k]; vb[k] = vq[k]; }
-        n_cur = n_ahead;
-        last = last_ahead;
-        have = true;
-        ahead = false;
-    };
 
-    // One loop over the tiles of the run and a last turn without a tile, written so that the round decoder
-    // appears once in the code: it is long, the waves of a workgroup are all at different places of the kernel
-    // and share one instruction cache.
     const bool last_group = t_end == n_tiles;
     bool big = false;                    // the stream holds keys beyond the dense vector
     float4 q[kPieces];                   // a whole tile on its way from memory, a 16-byte piece per thread and step
     bool fetched = false;
 #pragma unroll
     for (u32 j = 0; j < kPieces; ++j) q[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (u64 tile = t_begin;; ++tile) {
-        const bool tail = tile >= t_end;
-        const u64 k0 = tile * TILE;
-        const u32 klen = tail ? 0u : (u32)(dense_len - k0 < TILE ? dense_len - k0 : TILE);
-        const u64 k_end = k0 + klen;
-        float* dtile = dense + (tail ? 0 : k0);
-        if (!tail) {
-            // tile in: 16 bytes per lane (the launch requires a 16-byte aligned vector).  A whole tile was fetched
-            // into registers while the tile before it was at work (the run's first one: just now)
-            if (klen == TILE) {
-                if (!fetched) {
+    u64 tile = t_begin;
+    u64 k0 = 0;                          // first key of the tile in shared memory
+    u32 klen = 0;                        // its keys
+    u32 my_front = 0;                    // the stream has added its keys below k0 + my_front
+    // Tile in: 16 bytes per lane (the launch requires a 16-byte aligned vector).  A whole tile was fetched into
+    // registers while the tile before it was at work (the run's first one: just now).
+    auto enter = [&]() {
+        k0 = tile * TILE;
+        klen = (u32)(dense_len - k0 < TILE ? dense_len - k0 : TILE);
+        float* dtile = dense + k0;
+        if (klen == TILE) {
+            if (!fetched) {
 #pragma unroll
-                    for (u32 j = 0; j < kPieces; ++j) q[j] = reinterpret_cast<const float4*>(dtile)[t + j * kTileStreams * kWave];
-                    // (all of them under way before the first one is used: otherwise the compiler waits for each)
+                for (u32 j = 0; j < kPieces; ++j) q[j] = reinterpret_cast<const float4*>(dtile)[t + j * kTileStreams * kWave];
+                // (all of them under way before the first one is used: otherwise the compiler waits for each)
 #pragma unroll
-                    for (u32 j = 0; j + 1 < kPieces; j += 2)
-                        asm volatile("" : "+v"(q[j].x), "+v"(q[j].y), "+v"(q[j].z), "+v"(q[j].w), "+v"(q[j + 1].x), "+v"(q[j + 1].y),
-                                          "+v"(q[j + 1].z), "+v"(q[j + 1].w));
-                }
-#pragma unroll
-                for (u32 j = 0; j < kPieces; ++j) reinterpret_cast<float4*>(s_tile)[t + j * kTileStreams * kWave] = q[j];
-            } else {
-                for (u32 i = t * 4u; i < TILE; i += kTileStreams * kWave * 4u) {
-                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (i + 4u <= klen) v = *reinterpret_cast<const float4*>(dtile + i);
-                    else {
-                        if (i < klen) v.x = dtile[i];
-                        if (i + 1u < klen) v.y = dtile[i + 1u];
-                        if (i + 2u < klen) v.z = dtile[i + 2u];
-                    }
-                    *reinterpret_cast<float4*>(&s_tile[i]) = v;
-                }
+                for (u32 j = 0; j + 1 < kPieces; j += 2)
+                    asm volatile("" : "+v"(q[j].x), "+v"(q[j].y), "+v"(q[j].z), "+v"(q[j].w), "+v"(q[j + 1].x), "+v"(q[j + 1].y),
+                                      "+v"(q[j + 1].z), "+v"(q[j + 1].w));
             }
-            // the next tile, if it is a whole one: on its way while this one is at work
-            fetched = tile + 1 < t_end && dense_len - (k0 + TILE) >= TILE;
-            if (fetched) {
 #pragma unroll
-                for (u32 j = 0; j < kPieces; ++j) q[j] = reinterpret_cast<const float4*>(dtile + TILE)[t + j * kTileStreams * kWave];
-            }
-            if (lane == 0) s_front[w] = mine ? 0u : klen;
-            __syncthreads();
+            for (u32 j = 0; j < kPieces; ++j) reinterpret_cast<float4*>(s_tile)[t + j * kTileStreams * kWave] = q[j];
         } else {
-            big = (have && (u64)last >= dense_len) || ahead;      // (the round ahead lies behind the one in hand)
-        }
-        // s_front[s]: stream s has added all its keys below k0 + s_front[s].  A wave adds a key only once
-        // the fronts of all streams before its own have passed it; the first stream never waits, so the
-        // waits end.
-        u32 my_front = 0, spins = 0;
-        u32 phase = mine ? 0u : 2u;          // 0: at work on the tile, 1: through with it, 2: leave
-        while (phase < 2u) {
-            bool fetch = false;              // decode the stream's next round
-            if (tail) {
-                // A block the wave has opened is decoded to its end (its last round carries the checks of the
-                // whole block, and the next workgroup may start behind it).  Behind the last tile the same goes
-                // for the rest of every stream: what is left there lies beyond the dense vector, unless it is
-                // corrupt, which outranks that.
-                big = big || ahead;
-                fetch = !ended && (last_group || sub != nsub);
-                if (!fetch) phase = 2u;
-            } else if (phase == 1u) {
-                // while other streams are still at work on the tile: the round after the one in hand
-                if (AHEAD && !ahead && !ended) {
-                    u32 f = klen;
-                    if (lane < n_here) f = __hip_atomic_load(&s_front[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    fetch = __any(f < klen);
+            for (u32 i = t * 4u; i < TILE; i += kTileStreams * kWave * 4u) {
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (i + 4u <= klen) v = *reinterpret_cast<const float4*>(dtile + i);
+                else {
+                    if (i < klen) v.x = dtile[i];
+                    if (i + 1u < klen) v.y = dtile[i + 1u];
+                    if (i + 2u < klen) v.z = dtile[i + 2u];
                 }
-                phase = 2u;
-            } else if (!have) {
-                if (ahead) step();
-                else if (ended) phase = 1u;
-                else fetch = true;
-            } else {
-                const u64 past = (u64)last + 1u;                       // first key the round does not hold
+                *reinterpret_cast<float4*>(&s_tile[i]) = v;
+            }
+        }
+        // the next tile, if it is a whole one: on its way while this one is at work
+        fetched = tile + 1 < t_end && dense_len - (k0 + TILE) >= TILE;
+        if (fetched) {
+#pragma unroll
+            for (u32 j = 0; j < kPieces; ++j) q[j] = reinterpret_cast<const float4*>(dtile + TILE)[t + j * kTileStreams * kWave];
+        }
+        my_front = 0;
+        if (lane == 0) s_front[w] = mine ? 0u : klen;
+        __syncthreads();
+    };
+    // Tile out, once every stream is through with it.
+    auto leave = [&]() {
+        if (mine) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            if (lane == 0) __hip_atomic_store(&s_front[w], klen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            // while other streams are still at work on the tile: the round after the one in hand
+            if (!ahead && !ended) {
+                u32 f = klen;
+                if (lane < n_here) f = __hip_atomic_load(&s_front[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (__any(f < klen)) decode_next();
+            }
+        }
+        __syncthreads();
+        float* dtile = dense + k0;
+        if (klen == TILE) {
+#pragma unroll
+            for (u32 j = 0; j < kPieces; ++j)
+                reinterpret_cast<float4*>(dtile)[t + j * kTileStreams * kWave] = reinterpret_cast<const float4*>(s_tile)[t + j * kTileStreams * kWave];
+        } else {
+            for (u32 i = t * 4u; i < TILE; i += kTileStreams * kWave * 4u) {
+                const float4 v = *reinterpret_cast<const float4*>(&s_tile[i]);
+                if (i + 4u <= klen) *reinterpret_cast<float4*>(dtile + i) = v;
+                else {
+                    if (i < klen) dtile[i] = v.x;
+                    if (i + 1u < klen) dtile[i + 1u] = v.y;
+                    if (i + 2u < klen) dtile[i + 2u] = v.z;
+                }
+            }
+        }
+        __syncthreads();
+        ++tile;
+    };
+
+    // Round after round (the round decoder appears once in the code: it is long, and the waves of a workgroup
+    // are all at different places of the kernel and share one instruction cache); inside, the tiles the
+    // round reaches.  Every wave passes the same barriers, two per tile, whatever its stream holds.
+    // s_front[s]: stream s has added all its keys below k0 + s_front[s].  A wave adds a key only once the
+    // fronts of all streams before its own have passed it; the first stream never waits, so the waits end.
+    enter();
+    bool tiles_left = true;
+    u32 spins = 0;
+    for (;;) {
+        // A block the wave has opened is decoded to its end even behind the run's last tile (its last round
+        // carries the checks of the whole block, and the next workgroup may start behind it).  Behind the
+        // vector's last tile the same goes for the rest of every stream: what is left there lies beyond the dense
+        // vector, unless it is corrupt, which outranks that.
+        if (!ahead && !ended && (tiles_left || last_group || sub != nsub)) decode_next();
+        have = ahead;
+        if (ahead) {
+#pragma unroll
+            for (u32 k = 0; k < kLaneKeys; ++k) { kp[k] = kq[k]; vb[k] = vq[k]; }
+            n_cur = n_ahead;
+            last = last_ahead;
+            ahead = false;
+        }
+        if (!tiles_left) {
+            if (!have) break;
+            big = big || last_group;
+            continue;
+        }
+        for (;;) {
+            if (have) {
+                const u64 past = (u64)last + 1u;                           // first key the round does not hold
                 const u32 hi = past > k0 ? (u32)(past - k0 < klen ? past - k0 : klen) : 0u;
-                if (my_front >= hi) {
-                    // the round has nothing more for this tile
-                    if (past >= k_end) phase = 1u;                     // ... but for tiles to come
-                    else have = false;
-                } else {
+                while (my_front < hi) {
                     u32 lim = hi;
                     if (w) {
                         // the fronts of the streams before this one (lanes 0..w-1 read one each)
@@ -969,67 +988,55 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
                             const u32 fj = read_lane(f, j);
                             lim = fj < lim ? fj : lim;
                         }
-                    }
-                    if (lim <= my_front) {
-                        // nothing to add yet: time to decode the round after this one
-                        if (AHEAD && !ahead && !ended) fetch = true;
-                        else if (++spins > kFrontSpins) {
-                            // (only ends a wait that cannot end by itself, which has never been seen: the launch
-                            // then reports a device failure instead of hanging)
-                            if (lane == 0) dec_fail(ctrl, FASTSGD_ERR_DEVICE, out_status, out_count, 1);
-                            have = false; ahead = false; ended = true;
-                        } else __builtin_amdgcn_s_sleep(2);
-                    } else {
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                        // The round's keys in [my_front, lim) of the tile: sixteen reads, sixteen additions, sixteen
-                        // writes, without a branch -- a key outside the range takes the lane's own entry behind the
-                        // tile instead, which nobody reads.
-                        const u32 base = (u32)k0, width = lim - my_front;
-                        const u32 mine_n = n_cur > lane * kLaneKeys ? n_cur - lane * kLaneKeys : 0u;   // the lane's pairs
-                        u32 at[kLaneKeys];
-                        float cur[kLaneKeys];
-#pragma unroll
-                        for (u32 k = 0; k < kLaneKeys; ++k) {
-                            const u32 idx = kp[k] - base;                 // (keys below the tile wrap to far beyond it)
-                            at[k] = (idx - my_front < width && k < mine_n) ? idx : TILE + lane;
-                            cur[k] = s_tile[at[k]];
+                        if (lim <= my_front) {
+                            // nothing to add yet: time to decode the round after this one
+                            if (!ahead && !ended) {
+                                decode_next();
+                                if (ended && !ahead) { have = false; break; }     // (corrupt: reported, nothing more to add)
+                                continue;
+                            }
+                            // (The count only ends a wait that cannot end by itself, which has never been seen: the
+                            // launch then reports a device failure instead of hanging.)
+                            if (++spins > kFrontSpins) {
+                                if (lane == 0) dec_fail(ctrl, FASTSGD_ERR_DEVICE, out_status, out_count, 1);
+                                lim = hi;
+                            } else {
+                                __builtin_amdgcn_s_sleep(2);
+                                continue;
+                            }
                         }
-#pragma unroll
-                        for (u32 k = 0; k < kLaneKeys; ++k) s_tile[at[k]] = cur[k] + __uint_as_float(vb[k]);
-                        my_front = lim;
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-                        if (lane == 0) __hip_atomic_store(&s_front[w], my_front, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     }
-                }
-            }
-            if (phase == 1u && !tail) {
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-                if (lane == 0) __hip_atomic_store(&s_front[w], klen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            }
-            if (fetch) {
-                decode_next();
-                if (!AHEAD && ahead && !tail) step();      // (without the second set of registers the round is taken up at once)
-            }
-        }
-        if (tail) break;
-        __syncthreads();
-        // tile out
-        if (klen == TILE) {
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                    // The round's keys in [my_front, lim) of the tile: sixteen reads, sixteen additions, sixteen
+                    // writes, without a branch -- a key outside the range takes the lane's own entry behind the
+                    // tile instead, which nobody reads.
+                    const u32 base = (u32)k0, width = lim - my_front;
+                    const u32 mine_n = n_cur > lane * kLaneKeys ? n_cur - lane * kLaneKeys : 0u;   // the lane's pairs
+                    u32 at[kLaneKeys];
+                    float cur[kLaneKeys];
 #pragma unroll
-            for (u32 j = 0; j < kPieces; ++j)
-                reinterpret_cast<float4*>(dtile)[t + j * kTileStreams * kWave] = reinterpret_cast<const float4*>(s_tile)[t + j * kTileStreams * kWave];
-        } else {
-            for (u32 i = t * 4u; i < TILE; i += kTileStreams * kWave * 4u) {
-                const float4 q = *reinterpret_cast<const float4*>(&s_tile[i]);
-                if (i + 4u <= klen) *reinterpret_cast<float4*>(dtile + i) = q;
-                else {
-                    if (i < klen) dtile[i] = q.x;
-                    if (i + 1u < klen) dtile[i + 1u] = q.y;
-                    if (i + 2u < klen) dtile[i + 2u] = q.z;
+                    for (u32 k = 0; k < kLaneKeys; ++k) {
+                        const u32 idx = kp[k] - base;                     // (keys below the tile wrap to far beyond it)
+                        at[k] = (idx - my_front < width && k < mine_n) ? idx : TILE + lane;
+                        cur[k] = s_tile[at[k]];
+                    }
+#pragma unroll
+                    for (u32 k = 0; k < kLaneKeys; ++k) s_tile[at[k]] = cur[k] + __uint_as_float(vb[k]);
+                    my_front = lim;
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                    if (lane == 0) __hip_atomic_store(&s_front[w], my_front, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
+                if (have && past < k0 + klen) break;                       // nothing of the round lies behind this tile
             }
+            // the stream is through with this tile
+            leave();
+            if (tile == t_end) { tiles_left = false; break; }
+            enter();
         }
-        __syncthreads();
+        if (!tiles_left) {
+            big = have && (u64)last >= dense_len;
+            if (!have) break;
+        }
     }
     if (last_group && big && lane == 0) dec_fail(ctrl, FASTSGD_ERR_BUFFER_TOO_SMALL, out_status, out_count, 1);
 }
