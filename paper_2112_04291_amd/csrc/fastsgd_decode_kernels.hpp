@@ -805,18 +805,23 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
         const u32 r0 = (u32)(t_begin * TILE) - 1u;            // the block whose preKey is the last one below the run
         blk = uniform(dir_upper_index(nb, r0, [&](u32 i) { return dirs[4 * i + 1]; }));
     }
+    // (What one lane could do alone -- report a failure, publish a front -- is done by all lanes alike: a branch
+    // on the lane number in the middle of these loops makes the compiler treat the loops' own, wave-wide
+    // conditions as if they differed between lanes, and it then runs them under lane masks.)
     auto stop = [&](u32 code) {
-        if (lane == 0) dec_fail(ctrl, code, out_status, out_count, 1);
+        dec_fail(ctrl, code, out_status, out_count, 1);
         ended = true;
         have = false;
         ahead = false;
     };
-    // decodes the stream's next round into the registers of the round ahead
+    // decodes the stream's next round into the registers of the round ahead (written without early ways out:
+    // the loops around it keep a single exit each, which the compiler turns into plain branches)
     auto decode_next = [&]() {
+        bool good = true;
         if (sub == nsub) {               // open block blk
             const u32* dir = dirs + 4ull * blk;
             has_next = blk + 1 < nb;
-            const u32 dword = (lane < 4 || (lane < 8 && has_next)) ? dir[lane] : 0u;
+            const u32 dword = dir[has_next ? (lane & 7u) : (lane & 3u)];
             const u32 off8 = read_lane(dword, 0), preKey = read_lane(dword, 1);
             M = read_lane(dword, 2); pbits = read_lane(dword, 3);
             const u32 next_off8_dir = read_lane(dword, 4);
@@ -825,42 +830,54 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
             cnt = uniform((u32)((hd.d - first < KB) ? hd.d - first : KB));
             const u64 next_off8 = has_next ? (u64)next_off8_dir : hd.total_words;
             const u32 fwords = (cnt * l + 63u) >> 6, pwords = (pbits + 63u) >> 6;
-            const bool bad = (M < 1 || M > 32) || (pbits > cnt * 32u) || ((u64)off8 + fwords + pwords != next_off8) ||
-                             ((u64)off8 + fwords + pwords > hd.total_words) || (blk == 0 && (off8 != 0 || preKey != 0));
-            if (bad) { stop(FASTSGD_ERR_CORRUPT_STREAM); return; }
-            fsrc = reinterpret_cast<const u32*>(streams + uniform64(hd.blocks_off + 8ull * off8));
-            psrc = fsrc + 2u * fwords;
-            pw_total = 2u * pwords;
-            codes = streams + uniform64(stream_begin + kHeaderBytes + (u64)(first >> 3) * cwid);
-            pbit = 0;
-            carry = preKey;
-            sub = 0;
-            nsub = (cnt + kSub - 1) / kSub;
+            good = !((M < 1 || M > 32) || (pbits > cnt * 32u) || ((u64)off8 + fwords + pwords != next_off8) ||
+                     ((u64)off8 + fwords + pwords > hd.total_words) || (blk == 0 && (off8 != 0 || preKey != 0)));
+            if (good) {
+                fsrc = reinterpret_cast<const u32*>(streams + uniform64(hd.blocks_off + 8ull * off8));
+                psrc = fsrc + 2u * fwords;
+                pw_total = 2u * pwords;
+                codes = streams + uniform64(stream_begin + kHeaderBytes + (u64)(first >> 3) * cwid);
+                pbit = 0;
+                carry = preKey;
+                sub = 0;
+                nsub = (cnt + kSub - 1) / kSub;
+            }
         }
-        const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
-        u32 lane_r = lane;
-        asm volatile("" : "+v"(lane_r));
-        const bool stream_start = (blk == 0 && sub == 0);
-        bool unused = false;
-        bool ok;
-        if (n == kSub)
-            ok = decode_round<true, kHand>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * (kSub / 8u) * cwid, n, l, M, tau,
-                                           cwid, pbits, pbit, carry, lane_r, s_pay, s_flg, s_cod, s_V, nullptr, nullptr, nullptr,
-                                           0, AdamArgs(), unused, stream_start, kq, vq);
-        else
-            ok = decode_round<false, kHand>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * (kSub / 8u) * cwid, n, l, M, tau,
-                                            cwid, pbits, pbit, carry, lane_r, s_pay, s_flg, s_cod, s_V, nullptr, nullptr, nullptr,
-                                            0, AdamArgs(), unused, stream_start, kq, vq);
-        if (!ok) { stop(FASTSGD_ERR_CORRUPT_STREAM); return; }
-        ++sub;
-        ahead = true;
-        n_ahead = n;
-        last_ahead = carry;
-        if (sub == nsub) {
-            if (pbit != pbits || (has_next && carry != next_pre)) { stop(FASTSGD_ERR_CORRUPT_STREAM); return; }
-            ++blk;
-            if (blk == nb) ended = true;
+        if (good) {
+            const u32 n = cnt - sub * kSub < kSub ? cnt - sub * kSub : kSub;
+            u32 lane_r = lane;
+            asm volatile("" : "+v"(lane_r));
+            const bool stream_start = (blk == 0 && sub == 0);
+            bool unused = false;
+            if (n == kSub)
+                good = decode_round<true, kHand>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * (kSub / 8u) * cwid, n, l, M, tau,
+                                                 cwid, pbits, pbit, carry, lane_r, s_pay, s_flg, s_cod, s_V, nullptr, nullptr, nullptr,
+                                                 0, AdamArgs(), unused, stream_start, kq, vq);
+            else
+                good = decode_round<false, kHand>(fsrc + sub * 32u * l, psrc, pw_total, codes + sub * (kSub / 8u) * cwid, n, l, M, tau,
+                                                  cwid, pbits, pbit, carry, lane_r, s_pay, s_flg, s_cod, s_V, nullptr, nullptr, nullptr,
+                                                  0, AdamArgs(), unused, stream_start, kq, vq);
+            if (good) {
+                ++sub;
+                ahead = true;
+                n_ahead = n;
+                last_ahead = carry;
+                if (sub == nsub) {
+                    good = pbit == pbits && (!has_next || carry == next_pre);
+                    ++blk;
+                    if (blk == nb) ended = true;
+                }
+            }
         }
+        if (!good) stop(FASTSGD_ERR_CORRUPT_STREAM);
+        // (everything the loops branch on is the same in all lanes; said again, so that the branches are scalar)
+        ahead = uniform((u32)ahead) != 0u;
+        ended = uniform((u32)ended) != 0u;
+        have = uniform((u32)have) != 0u;
+        n_ahead = uniform(n_ahead);
+        last_ahead = uniform(last_ahead);
+        sub = uniform(sub); nsub = uniform(nsub); blk = uniform(blk);
+        pbit = uniform(pbit); carry = uniform(carry);
     };
 
     const bool last_group = t_end == n_tiles;
@@ -910,19 +927,18 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
             for (u32 j = 0; j < kPieces; ++j) q[j] = reinterpret_cast<const float4*>(dtile + TILE)[t + j * kTileStreams * kWave];
         }
         my_front = 0;
-        if (lane == 0) s_front[w] = mine ? 0u : klen;
+        s_front[w] = mine ? 0u : klen;
         __syncthreads();
     };
     // Tile out, once every stream is through with it.
     auto leave = [&]() {
         if (mine) {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            if (lane == 0) __hip_atomic_store(&s_front[w], klen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            __hip_atomic_store(&s_front[w], klen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             // while other streams are still at work on the tile: the round after the one in hand
             if (!ahead && !ended) {
-                u32 f = klen;
-                if (lane < n_here) f = __hip_atomic_load(&s_front[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                if (__any(f < klen)) decode_next();
+                const u32 f = __hip_atomic_load(&s_front[lane & (kTileStreams - 1u)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (__any(lane < n_here && f < klen)) decode_next();
             }
         }
         __syncthreads();
@@ -952,9 +968,9 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
     // s_front[s]: stream s has added all its keys below k0 + s_front[s].  A wave adds a key only once the
     // fronts of all streams before its own have passed it; the first stream never waits, so the waits end.
     enter();
-    bool tiles_left = true;
+    bool tiles_left = true, run = true;
     u32 spins = 0;
-    for (;;) {
+    while (run) {
         // A block the wave has opened is decoded to its end even behind the run's last tile (its last round
         // carries the checks of the whole block, and the next workgroup may start behind it).  Behind the
         // vector's last tile the same goes for the rest of every stream: what is left there lies beyond the dense
@@ -969,73 +985,73 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
             ahead = false;
         }
         if (!tiles_left) {
-            if (!have) break;
-            big = big || last_group;
-            continue;
-        }
-        for (;;) {
-            if (have) {
+            run = have;
+            big = big || (have && last_group);
+        } else {
+            bool more = true;            // the round (or the end of the stream) still has tiles to go through
+            while (more) {
                 const u64 past = (u64)last + 1u;                           // first key the round does not hold
-                const u32 hi = past > k0 ? (u32)(past - k0 < klen ? past - k0 : klen) : 0u;
-                while (my_front < hi) {
+                const u32 hi = uniform((have && past > k0) ? (u32)(past - k0 < klen ? past - k0 : klen) : 0u);
+                while (have && my_front < hi) {
                     u32 lim = hi;
                     if (w) {
                         // the fronts of the streams before this one (lanes 0..w-1 read one each)
-                        u32 f = klen;
-                        if (lane < w) f = __hip_atomic_load(&s_front[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        u32 f = __hip_atomic_load(&s_front[lane & (kTileStreams - 1u)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        f = lane < w ? f : klen;
 #pragma unroll
                         for (u32 j = 0; j < kTileStreams - 1; ++j) {
                             const u32 fj = read_lane(f, j);
                             lim = fj < lim ? fj : lim;
                         }
-                        if (lim <= my_front) {
-                            // nothing to add yet: time to decode the round after this one
-                            if (!ahead && !ended) {
-                                decode_next();
-                                if (ended && !ahead) { have = false; break; }     // (corrupt: reported, nothing more to add)
-                                continue;
-                            }
-                            // (The count only ends a wait that cannot end by itself, which has never been seen: the
-                            // launch then reports a device failure instead of hanging.)
-                            if (++spins > kFrontSpins) {
-                                if (lane == 0) dec_fail(ctrl, FASTSGD_ERR_DEVICE, out_status, out_count, 1);
-                                lim = hi;
-                            } else {
-                                __builtin_amdgcn_s_sleep(2);
-                                continue;
-                            }
+                    }
+                    lim = uniform(lim);
+                    if (lim <= my_front && spins > kFrontSpins) {
+                        // (only ends a wait that cannot end by itself, which has never been seen: the launch then
+                        // reports a device failure instead of hanging)
+                        dec_fail(ctrl, FASTSGD_ERR_DEVICE, out_status, out_count, 1);
+                        lim = hi;
+                    }
+                    if (lim > my_front) {
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                        // The round's keys in [my_front, lim) of the tile: sixteen reads, sixteen additions, sixteen
+                        // writes, without a branch -- a key outside the range takes the lane's own entry behind the
+                        // tile instead, which nobody reads.
+                        const u32 base = (u32)k0, width = lim - my_front;
+                        const u32 mine_n = n_cur > lane * kLaneKeys ? n_cur - lane * kLaneKeys : 0u;   // the lane's pairs
+                        u32 at[kLaneKeys];
+                        float cur[kLaneKeys];
+#pragma unroll
+                        for (u32 k = 0; k < kLaneKeys; ++k) {
+                            const u32 idx = kp[k] - base;                     // (keys below the tile wrap to far beyond it)
+                            at[k] = (idx - my_front < width && k < mine_n) ? idx : TILE + lane;
+                            cur[k] = s_tile[at[k]];
                         }
-                    }
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                    // The round's keys in [my_front, lim) of the tile: sixteen reads, sixteen additions, sixteen
-                    // writes, without a branch -- a key outside the range takes the lane's own entry behind the
-                    // tile instead, which nobody reads.
-                    const u32 base = (u32)k0, width = lim - my_front;
-                    const u32 mine_n = n_cur > lane * kLaneKeys ? n_cur - lane * kLaneKeys : 0u;   // the lane's pairs
-                    u32 at[kLaneKeys];
-                    float cur[kLaneKeys];
 #pragma unroll
-                    for (u32 k = 0; k < kLaneKeys; ++k) {
-                        const u32 idx = kp[k] - base;                     // (keys below the tile wrap to far beyond it)
-                        at[k] = (idx - my_front < width && k < mine_n) ? idx : TILE + lane;
-                        cur[k] = s_tile[at[k]];
+                        for (u32 k = 0; k < kLaneKeys; ++k) s_tile[at[k]] = cur[k] + __uint_as_float(vb[k]);
+                        my_front = lim;
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                        __hip_atomic_store(&s_front[w], my_front, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    } else if (!ahead && !ended) {
+                        // nothing to add yet: time to decode the round after this one
+                        decode_next();
+                        have = ahead || !ended;                                // (corrupt: reported, nothing more to add)
+                    } else {
+                        ++spins;
+                        __builtin_amdgcn_s_sleep(2);
                     }
-#pragma unroll
-                    for (u32 k = 0; k < kLaneKeys; ++k) s_tile[at[k]] = cur[k] + __uint_as_float(vb[k]);
-                    my_front = lim;
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-                    if (lane == 0) __hip_atomic_store(&s_front[w], my_front, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
-                if (have && past < k0 + klen) break;                       // nothing of the round lies behind this tile
+                if (have && past < k0 + klen) more = false;                    // nothing of the round lies behind this tile
+                else {
+                    // the stream is through with this tile
+                    leave();
+                    if (tile == t_end) { tiles_left = false; more = false; }
+                    else enter();
+                }
             }
-            // the stream is through with this tile
-            leave();
-            if (tile == t_end) { tiles_left = false; break; }
-            enter();
-        }
-        if (!tiles_left) {
-            big = have && (u64)last >= dense_len;
-            if (!have) break;
+            if (!tiles_left) {
+                big = have && (u64)last >= dense_len;
+                run = have;
+            }
         }
     }
     if (last_group && big && lane == 0) dec_fail(ctrl, FASTSGD_ERR_BUFFER_TOO_SMALL, out_status, out_count, 1);
