@@ -9,14 +9,15 @@ from tests.test_oracle_aggregate import worker_streams
 pytestmark = pytest.mark.gpu
 
 
-def hip_accumulate(blob, offs, dense):
+def hip_accumulate(blob, offs, dense, shift=0):
+    """`shift`: the dense vector starts that many elements into its allocation (1: not 16-byte aligned)."""
     import torch
     from paper_2112_04291_amd import binding as B
     n = len(offs) - 1
     s = np.ascontiguousarray(blob, dtype=np.uint8)
     dev = torch.from_numpy(np.concatenate([s, np.zeros((-s.size) % 8 + 8, np.uint8)])).cuda()
     so = torch.from_numpy(np.ascontiguousarray(offs, dtype=np.uint64).view(np.int64)).cuda()
-    dd = torch.from_numpy(dense.copy()).cuda()
+    dd = torch.from_numpy(np.concatenate([np.zeros(shift, np.float32), dense])).cuda()[shift:]
     count = torch.full((2,), -1, dtype=torch.int64, device="cuda")
     status = torch.full((2,), -1, dtype=torch.int32, device="cuda")
     ws = B.decoder_workspace(n)
@@ -27,7 +28,7 @@ def hip_accumulate(blob, offs, dense):
 
 @pytest.mark.parametrize("n_workers,dim,nnz,keep", [(1, 100_000, 20_000, 0.5), (3, 400_000, 150_000, 0.3),
                                                     (8, 2_000_000, 300_000, 0.05), (2, 5_000, 5_000, 1.0),
-                                                    (48, 500_000, 40_000, 0.2)])
+                                                    (48, 500_000, 40_000, 0.2), (4, 4_000_000, 20_000, 0.5)])
 def test_aggregate_matches_oracle_bit_for_bit(n_workers, dim, nnz, keep):
     from paper_2112_04291_amd import binding as B
     blob, offs, pairs = worker_streams(n_workers, dim, nnz, keep, 300 + n_workers)
@@ -39,6 +40,22 @@ def test_aggregate_matches_oracle_bit_for_bit(n_workers, dim, nnz, keep):
     rc, status, cnt, got = hip_accumulate(blob, offs, dense0)
     assert rc == B.OK and status == 0 and cnt == cnt_ref
     assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+def test_aggregate_into_a_vector_that_is_not_16_byte_aligned():
+    """Such a vector is added to stream after stream, whatever the streams hold (the one-pass form moves 16-byte
+    pieces of it)."""
+    from paper_2112_04291_amd import binding as B
+    blob, offs, pairs = worker_streams(3, 300_001, 120_000, 0.6, 17)
+    rng = np.random.default_rng(9)
+    dense0 = rng.standard_normal(300_001).astype(np.float32) * np.float32(1e-3)
+    want = dense0.copy()
+    rc_ref, cnt_ref = ref.decompress_accumulate(blob, offs, want)
+    assert rc_ref == ref.OK
+    for shift in (1, 2, 3):
+        rc, status, cnt, got = hip_accumulate(blob, offs, dense0, shift=shift)
+        assert rc == B.OK and status == 0 and cnt == cnt_ref
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
 
 
 def test_aggregate_errors_match_oracle():
@@ -94,7 +111,7 @@ def test_aggregate_of_streams_with_narrow_and_nine_bit_tokens():
 
 # --- dense gradients: the library adds them in one pass over the dense vector (groups of eight streams, a
 # tile of 16384 keys at a time, runs of tiles per workgroup); the cases below are sized so that this form is
-# the one that runs (the streams' bytes, times four, reach the vector's length per group of eight), with
+# the one that runs (the streams' bytes, times ten, reach the vector's length per group of eight), with
 # vectors that end inside a tile and inside a 16-byte piece, blocks of one to four rounds, partial groups
 
 def dense_streams(n_workers, dim, nnz, keep, kb, seed, taus=(128,)):
@@ -110,7 +127,7 @@ def dense_streams(n_workers, dim, nnz, keep, kb, seed, taus=(128,)):
         blobs.append(st)
         offs.append(offs[-1] + st.size)
     blob, offs = np.concatenate(blobs), np.array(offs, np.uint64)
-    assert 4 * blob.size >= dim * (-(-n_workers // 8)) and n_workers >= 2       # (the library's own test for this form)
+    assert 10 * blob.size >= dim * (-(-n_workers // 8)) and n_workers >= 2      # (the library's own test for this form)
     return blob, offs
 
 
