@@ -24,6 +24,8 @@
  *   - Where several device-detected conditions hold at once the encoder reports, in this order, a
  *     non-finite value, keys out of order, an output buffer too small.  (A sequential encoder would
  *     report whichever of the last two it meets first; both verdicts describe the same refused input.)
+ *     The decoders report a corrupt stream in preference to a capacity or dense vector that is
+ *     too small for what the stream holds.
  *   - Keys are uint32 and strictly increasing within one gradient (the first may be 0);
  *     values are IEEE binary32.  n <= 2^32 - 1024 per gradient.
  *
@@ -166,9 +168,13 @@ fastsgd_status fastsgd_decompress_segmented(const void* d_streams, size_t total_
 
 /* Decoder followed by the aggregation the decoded gradients are for (Section 2.1, Fig. 1: the
  * workers' gradients are decoded and added up before the model update): for every pair (k, v)
- * of every stream, d_dense[k] += v, a binary32 addition.  The streams are added one after the
- * other in the given order (one decode launch per stream), keys are unique inside a stream, so
- * the result does not depend on how the work is spread over the GPU.
+ * of every stream, d_dense[k] += v, a binary32 addition.  At every key the streams are added in
+ * the given order and keys are unique inside a stream, so the result does not depend on how the
+ * work is spread over the GPU: sparse streams are added by one decode launch per stream, dense
+ * ones (from about one kept entry in two hundred on, if d_dense is 16-byte aligned) in one pass
+ * over d_dense per group of eight streams, with the same sums.
+ * If several streams fail, or one fails in several ways, *d_status holds the gravest failure:
+ * a corrupt stream outranks a key beyond the dense vector.
  *   d_streams, total_bytes   device, the concatenated streams of the workers, 8-byte aligned
  *   d_stream_offsets   device u64[n_streams + 1]: byte offset of each stream, each a multiple of 8
  *   d_dense, dense_len device float[dense_len], updated in place; a decoded key >= dense_len

@@ -275,14 +275,16 @@ __device__ __forceinline__ bool decode_round(const u32* __restrict__ fsrc_round,
         const uint2 a = c2[0], b = c2[1];
         cw[0] = a.x; cw[1] = a.y; cw[2] = b.x; cw[3] = b.y;
     } else {
+        // through a descriptor that ends with the round's last word of bytes (the plane is padded to 64 bits):
+        // words beyond it read 0, the bytes of the last word beyond n are masked away
+        const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint8_t*>(codes_round), 0, (int)uniform((n + 3u) & ~3u), kBufferWord3);
 #pragma unroll
         for (u32 j = 0; j < 4; ++j) {
-            u32 x = 0;
-#pragma unroll
-            for (u32 bb = 0; bb < 4; ++bb) {
-                const u32 i = lane * kLaneKeys + j * 4u + bb;
-                if (i < n) x |= (u32)codes_round[i] << (8u * bb);
-            }
+            const u32 i0 = lane * kLaneKeys + j * 4u;
+            u32 x = __builtin_amdgcn_raw_buffer_load_b32(crs, (int)i0, 0, 0);
+            const u32 left = n > i0 ? n - i0 : 0u;          // bytes of the round from here on
+            if (left < 4u) x &= (1u << (8u * left)) - 1u;
             cw[j] = x;
         }
     }
@@ -687,23 +689,26 @@ k_decode(const uint8_t* __restrict__ streams, u64 stream_bytes, u64 capacity, co
 
 // ---------------------------------------------------------------------------------------------------
 // Decode-and-aggregate in one pass over the dense vector (Section 2.1: the workers' gradients are decoded
-// and added up).  For gradients that keep a large share of their entries, adding stream after stream moves
-// the whole dense vector through the memory system once per stream; here it moves once per group of
-// kTileStreams streams.
+// and added up).  For gradients that keep more than a few in a thousand of their entries, adding stream after
+// stream moves the whole dense vector through the memory system once per stream; here it moves once per
+// group of kTileStreams streams.
 //
-// A workgroup owns a run of consecutive tiles of kTileKeys keys and holds one tile at a time in shared
-// memory.  Wave w walks the key blocks of the group's w-th stream in order, one round of up to 1024 pairs
-// at a time, and keeps the round in registers (16 consecutive pairs per lane) until the tile that holds its
-// last key has come -- so a round that straddles tiles is decoded once.  Binary32 addition is not
-// associative, so for every key the streams are added in the given order: the waves take turns, stream
-// after stream, with a barrier between turns (keys are distinct inside a stream, so a turn is a plain
-// read-add-write of shared memory), and decode their next rounds all at the same time between the turns.
+// A workgroup owns a run of consecutive tiles of TILE keys and holds one tile at a time in shared memory
+// (the next one is on its way into registers meanwhile).  Wave w walks the key blocks of the group's w-th
+// stream in order, one round of up to 1024 pairs at a time, and keeps the round in registers (16 consecutive
+// pairs per lane) until the tile that holds its last key has come -- so a round that straddles tiles is
+// decoded once.  Binary32 addition is not associative, so for every key the streams are added in the given
+// order: every stream publishes a front, the key below which it has added everything it holds for the tile,
+// and a wave adds a key only once the fronts of all streams before its own have passed it (keys are
+// distinct inside a stream, so an addition is a plain read-add-write of shared memory).  A wave that has to
+// wait decodes its stream's next round meanwhile, into a second set of registers, so that the streams
+// decode side by side although they add one after the other.  The waves meet at a barrier only where a
+// tile is written back and the next one comes in.
 // A workgroup starts each stream at the block that holds the first key of its run (found by a search of the
 // block directory's preKeys, which the launch checks to be strictly increasing so that every block is met
 // by some workgroup) and decodes that block from its beginning, keys below the run being skipped.
 // The workgroup that owns the last tile goes on to the end of every stream: what is left there has keys
 // beyond the dense vector (FASTSGD_ERR_BUFFER_TOO_SMALL) unless it is corrupt, which is reported first.
-constexpr u32 kTileKeys = 16384;
 constexpr u32 kTileStreams = 8;
 constexpr u32 kFrontSpins = 1u << 22;     // polls of the other streams' fronts before a wait is given up (seconds)
 
