@@ -24,8 +24,9 @@
  *   - Where several device-detected conditions hold at once the encoder reports, in this order, a
  *     non-finite value, keys out of order, an output buffer too small.  (A sequential encoder would
  *     report whichever of the last two it meets first; both verdicts describe the same refused input.)
- *     The decoders report a corrupt stream in preference to a capacity or dense vector that is
- *     too small for what the stream holds.
+ *     The decoders check the header and the pair capacity before anything else (a header that is
+ *     corrupt, then a capacity that is too small); the decoders that update dense arrays meet keys
+ *     beyond those arrays while they decode, and report a corrupt stream in preference to such a key.
  *   - Keys are uint32 and strictly increasing within one gradient (the first may be 0);
  *     values are IEEE binary32.  n <= 2^32 - 1024 per gradient.
  *
