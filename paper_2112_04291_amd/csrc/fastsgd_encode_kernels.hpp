@@ -50,9 +50,17 @@ __device__ __forceinline__ TileGeom tile_geom(const SegInfo& s, u64 tile) {
     g.full = (g.tile0 >= g.lo) && (g.tile0 + kTile <= g.hi);
     return g;
 }
-__device__ __forceinline__ void load_tile(const float* __restrict__ values, const TileGeom& g, u32 bits[4][4]) {
+// keep: the tile is among the last ones the pass reads, which the second value pass reads first (it walks
+// the array from its end): an ordinary load, so that the caches hold on to it; everything else streams.
+__device__ __forceinline__ void load_tile(const float* __restrict__ values, const TileGeom& g, u32 bits[4][4], bool keep = false) {
     const u32 slot0 = wave_id() * 1024u + lane_id() * 4u;
-    if (g.full) {
+    if (g.full && keep) {
+#pragma unroll
+        for (u32 r = 0; r < 4; ++r) {
+            const uint4 q = *reinterpret_cast<const uint4*>(values + g.tile0 + slot0 + r * 256u);
+            bits[r][0] = q.x; bits[r][1] = q.y; bits[r][2] = q.z; bits[r][3] = q.w;
+        }
+    } else if (g.full) {
 #pragma unroll
         for (u32 r = 0; r < 4; ++r) {
             const uint4 q = load_stream16(values + g.tile0 + slot0 + r * 256u);
@@ -87,6 +95,10 @@ __device__ __forceinline__ void load_tile(const float* __restrict__ values, cons
 //                     copies of the segment's record each time it leaves a segment (atomics on
 //                     memory k_init cleared).
 constexpr u32 kBinWords = 2 * kBins + 2;
+#ifndef FSGD_KEEP_MB
+#define FSGD_KEEP_MB 160
+#endif
+constexpr u64 kKeepTiles = (u64)FSGD_KEEP_MB * 64;     // 16 KB a tile: what the first value pass leaves in the caches
 
 template <bool SINGLE>
 __device__ __forceinline__ void flush_bins(u64 (*bins)[kThreads], u64* rec, u32 n_slots, u32 maxa) {
@@ -223,7 +235,7 @@ k_abs_sum(const float* __restrict__ values, const SegInfo* __restrict__ segs, u3
             g.tile0 += tile * kTile;
             g.full = (g.tile0 >= g.lo) && (g.tile0 + kTile <= g.hi);
             u32 bits[4][4];
-            load_tile(values, g, bits);
+            load_tile(values, g, bits, tile + kKeepTiles >= n_tiles);
             accumulate_tile(bits, bins, maxa, rowmax, tile * (kTile / kRow), row_end, s_bounds[waiting] + wave_id() * kWaveTileWords);
             if (++waiting == kBoundStage) write_bounds();
         }
@@ -850,8 +862,10 @@ k_encode_values(const u32* __restrict__ keys, const float* __restrict__ values,
     const u32 lane = lane_id();
     const u32 w = uniform(wave_id());
     u32* s_B = s_Ball[w];
-    const u32 chunk = blockIdx.x * kValWaves + w;
-    if (chunk >= n_chunks) return;
+    // (chunks from the array's end to its beginning: the end is what the first pass read last)
+    const u32 chunk_raw = blockIdx.x * kValWaves + w;
+    if (chunk_raw >= n_chunks) return;
+    const u32 chunk = n_chunks - 1u - chunk_raw;
     ValueCtx cx;
     cx.ck = chunk_geom(segs, n_segments, chunk, R);
     const SegState* st = &states[cx.ck.seg];
