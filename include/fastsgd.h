@@ -84,6 +84,13 @@ size_t fastsgd_compressed_size(uint64_t n, const fastsgd_params* p);
  * survivors, whose number is not known beforehand).  Returns 0 on invalid arguments. */
 size_t fastsgd_workspace_size(uint64_t total_n, uint32_t n_segments, uint32_t min_block_keys);
 
+/* The same for a caller that knows the largest threshold tau it will pass: up to 128 a code takes
+ * one byte of scratch instead of two (about 5 bytes per element instead of 6).  A call whose tau
+ * needs more than its workspace has returns FASTSGD_ERR_BUFFER_TOO_SMALL.  Returns 0 on invalid
+ * arguments (max_tau 1..256). */
+size_t fastsgd_workspace_size_tau(uint64_t total_n, uint32_t n_segments, uint32_t min_block_keys,
+                                  uint32_t max_tau);
+
 /* Host-only, pure.  Bytes of device workspace the decoders need for n_segments streams.
  * The first 4096 bytes of a decoder workspace hold control words that must be ZERO before the workspace's
  * first use (clear them once after allocating it); every decoder call leaves them zero again, so the

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libfastsgd.so")
 OK, ERR_INVALID_ARG, ERR_BUFFER_TOO_SMALL, ERR_NONFINITE, ERR_UNSORTED_KEYS, ERR_CORRUPT_STREAM, ERR_DEVICE = range(7)
 STATUS_NAMES = ["OK", "INVALID_ARG", "BUFFER_TOO_SMALL", "NONFINITE", "UNSORTED_KEYS", "CORRUPT_STREAM", "DEVICE"]
 
-EXPORTS = ["fastsgd_compressed_size", "fastsgd_workspace_size", "fastsgd_decompress_workspace_size",
+EXPORTS = ["fastsgd_compressed_size", "fastsgd_workspace_size", "fastsgd_workspace_size_tau", "fastsgd_decompress_workspace_size",
            "fastsgd_compress", "fastsgd_compress_static", "fastsgd_decompress", "fastsgd_compress_segmented", "fastsgd_decompress_segmented",
            "fastsgd_decompress_accumulate", "fastsgd_decompress_adam",
            "fastsgd_profile_compress", "fastsgd_profile_decompress", "fastsgd_probe_read"]
@@ -55,6 +55,8 @@ def lib():
         L.fastsgd_compressed_size.restype = sz
         L.fastsgd_workspace_size.argtypes = [u64, u32, u32]
         L.fastsgd_workspace_size.restype = sz
+        L.fastsgd_workspace_size_tau.argtypes = [u64, u32, u32, u32]
+        L.fastsgd_workspace_size_tau.restype = sz
         L.fastsgd_decompress_workspace_size.argtypes = [u32]
         L.fastsgd_decompress_workspace_size.restype = sz
         L.fastsgd_compress.argtypes = [vp, vp, u64, PP, vp, sz, vp, vp, vp, sz, vp]
@@ -94,8 +96,12 @@ def compressed_size(n, p):
     return int(lib().fastsgd_compressed_size(int(n), C.byref(p)))
 
 
-def workspace_size(total_n, n_segments=1, min_block_keys=1024):
-    return int(lib().fastsgd_workspace_size(int(total_n), int(n_segments), int(min_block_keys)))
+def workspace_size(total_n, n_segments=1, min_block_keys=1024, max_tau=None):
+    """Bytes of encoder workspace; with max_tau (the largest threshold the caller will pass) the smaller amount
+    that thresholds up to 128 get by with."""
+    if max_tau is None:
+        return int(lib().fastsgd_workspace_size(int(total_n), int(n_segments), int(min_block_keys)))
+    return int(lib().fastsgd_workspace_size_tau(int(total_n), int(n_segments), int(min_block_keys), int(max_tau)))
 
 
 def decompress_workspace_size(n_segments=1):

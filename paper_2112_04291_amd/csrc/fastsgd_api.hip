@@ -60,8 +60,9 @@ static EncodePlan make_plan(u64 total_n, u32 n_segments, u32 min_kb) {
     pl.off_seginfo = o;  o += up((u64)n_segments * sizeof(SegInfo), 256);
     pl.off_segstate = o; o += up((u64)n_segments * sizeof(SegState), 256);
     pl.off_skeys = o;    o += up(pl.max_slots * 4, 256);
-    pl.off_scodes = o;   o += up(pl.max_slots * 2, 256);          // 16 bits per code when some tau is above 128
-    pl.total = o;
+    pl.off_scodes = o;                                             // last: a byte per code, ...
+    pl.total_narrow = o + up(pl.max_slots, 256);
+    pl.total = o + up(pl.max_slots * 2, 256);                      // ... 16 bits when some tau is above 128
     return pl;
 }
 
@@ -157,7 +158,7 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
     if (total_rows > pl.max_rows || total_rows >= 0xFFFFFFFFull) return FASTSGD_ERR_INVALID_ARG;
     if (n_chunks > pl.max_chunks || max_items > pl.max_items || n_tiles >= 0xFFFFFFFFull)
         return FASTSGD_ERR_INVALID_ARG;
-    if (ws_bytes < pl.total) return FASTSGD_ERR_BUFFER_TOO_SMALL;
+    if (ws_bytes < (wide ? pl.total : pl.total_narrow)) return FASTSGD_ERR_BUFFER_TOO_SMALL;
     if (out_capacity < kHeaderBytes) return FASTSGD_ERR_BUFFER_TOO_SMALL;
     const u32 R = (u32)R64;
     u32 g_shift = 6;                                               // key blocks per group of the size sums
@@ -481,6 +482,14 @@ size_t fastsgd_workspace_size(uint64_t total_n, uint32_t n_segments, uint32_t mi
     // (the plan's bounds leave room for the call shifting its base down to a 16-byte boundary: 8 scratch entries
     // and two rows beyond the elements)
     return (size_t)make_plan(total_n, n_segments, min_block_keys).total;
+}
+
+size_t fastsgd_workspace_size_tau(uint64_t total_n, uint32_t n_segments, uint32_t min_block_keys, uint32_t max_tau) {
+    if (n_segments < 1 || n_segments > kMaxSegments || total_n >= (1ull << 40)) return 0;
+    if (min_block_keys < 256 || min_block_keys > kMaxKB || (min_block_keys & (min_block_keys - 1))) return 0;
+    if (max_tau < 1 || max_tau > kMaxTau) return 0;
+    const EncodePlan pl = make_plan(total_n, n_segments, min_block_keys);
+    return (size_t)(max_tau > 128 ? pl.total : pl.total_narrow);
 }
 
 size_t fastsgd_decompress_workspace_size(uint32_t n_segments) {

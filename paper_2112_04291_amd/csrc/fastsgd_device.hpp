@@ -84,7 +84,8 @@ struct EncodePlan {     // host-computed carve-up of the workspace
     u64 max_chunks, max_items, total_n, max_slots, max_rows;
     u32 n_segments, n_slots;
     u64 off_ctrl, off_gsum, zero_end, off_gbins, zero_end_batch;   // [off_ctrl, zero_end*) is cleared per call
-    u64 off_rowmax, off_ccount, off_binfo, off_seginfo, off_segstate, off_skeys, off_scodes, total;
+    u64 off_rowmax, off_ccount, off_binfo, off_seginfo, off_segstate, off_skeys, off_scodes;
+    u64 total_narrow, total;      // bytes needed if every tau is at most 128 (a byte per code) / in any case
 };
 
 // ---------------------------------------------------------------------------------------------

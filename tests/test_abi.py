@@ -50,6 +50,12 @@ def test_workspace_size_is_monotone_and_rejects_bad_arguments():
     assert 0 < a < b and c > B.workspace_size(10 ** 6, 160, 1024) > a
     assert B.workspace_size(10, 0, 1024) == 0 and B.workspace_size(10, 1, 100) == 0
     assert B.decompress_workspace_size(1) > 0 and B.decompress_workspace_size(0) == 0
+    # a caller that announces thresholds of at most 128 gets by with a byte per code instead of two
+    n = 10 ** 6
+    narrow, wide = B.workspace_size(n, 1, 1024, max_tau=128), B.workspace_size(n, 1, 1024, max_tau=129)
+    assert wide == B.workspace_size(n, 1, 1024) and wide == B.workspace_size(n, 1, 1024, max_tau=256)
+    assert n - 512 <= wide - narrow <= n + 1024 and narrow == B.workspace_size(n, 1, 1024, max_tau=1)
+    assert B.workspace_size(n, 1, 1024, max_tau=0) == 0 and B.workspace_size(n, 1, 1024, max_tau=257) == 0
 
 
 def test_params_struct_layout_matches_header():

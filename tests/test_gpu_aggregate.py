@@ -202,3 +202,49 @@ def test_aggregate_in_one_pass_rejects_damaged_streams():
     bad = blob.copy()
     struct.pack_into("<I", bad, dir0 + 16 * (first["nb"] - 1) + 12, 0)
     assert check_against_oracle(bad, offs, np.zeros(60_000, np.float32)) == ref.ERR_CORRUPT_STREAM
+
+
+def test_aggregate_in_one_pass_of_uneven_streams():
+    """Streams that are empty, that end early, that start late, that hold a single pair: every wave still passes
+    every tile."""
+    from paper_2112_04291_amd import workloads as W
+    rng = np.random.default_rng(31)
+    dim = 200_000
+    spans = [(0, dim), (0, 0), (150_000, dim), (0, 30_000), (99_999, 100_000), (0, dim), (60_000, 61_000)]
+    blobs, offs = [], [0]
+    for lo, hi in spans:
+        keys = np.arange(lo, hi, dtype=np.uint32)
+        keys = keys[rng.random(keys.size) < 0.7]
+        vals = rng.laplace(0.0, 1e-3, keys.size).astype(np.float32)
+        base = W.solve_base(vals, 0.9) if keys.size else 1.5
+        rc, st = ref.compress(keys, vals, ref.params(base, 128, 2, 1024))
+        assert rc == ref.OK
+        blobs.append(st)
+        offs.append(offs[-1] + st.size)
+    blob, offs = np.concatenate(blobs), np.array(offs, np.uint64)
+    assert 10 * blob.size >= dim
+    dense0 = rng.standard_normal(dim).astype(np.float32)
+    assert check_against_oracle(blob, offs, dense0) == ref.OK
+
+
+def test_aggregate_in_one_pass_keeps_denormal_sums():
+    """Gradients so small that the sums are denormal: added as binary32 denormals, not flushed."""
+    from paper_2112_04291_amd import workloads as W
+    rng = np.random.default_rng(32)
+    dim = 100_000
+    blobs, offs = [], [0]
+    for wkr in range(4):
+        keys = np.sort(rng.choice(dim, 60_000, replace=False)).astype(np.uint32)
+        vals = (rng.laplace(0.0, 1.0, keys.size) * 1e-41).astype(np.float32)
+        assert np.count_nonzero(vals) > 50_000 and np.abs(vals).max() < 1.2e-38
+        rc, st = ref.compress(keys, vals, ref.params(W.solve_base(vals, 0.9), 128, 2, 1024))
+        assert rc == ref.OK
+        blobs.append(st)
+        offs.append(offs[-1] + st.size)
+    blob, offs = np.concatenate(blobs), np.array(offs, np.uint64)
+    assert 10 * blob.size >= dim
+    want = np.zeros(dim, np.float32)
+    assert ref.decompress_accumulate(blob, offs, want)[0] == ref.OK
+    tiny = np.abs(want[want != 0])
+    assert tiny.size > 50_000 and tiny.max() < 1.2e-38           # the sums are denormal
+    assert check_against_oracle(blob, offs, np.zeros(dim, np.float32)) == ref.OK

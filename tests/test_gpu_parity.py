@@ -384,6 +384,33 @@ def test_workspace_and_buffers_reused_across_sizes():
         assert np.array_equal(st, st_ref)
 
 
+def test_workspace_sized_for_one_byte_codes():
+    """A caller that announces thresholds of at most 128 passes a workspace with a byte of scratch per code: every
+    element may survive, nothing is written behind the workspace, and a call with a larger threshold is refused."""
+    torch, B, G = _gpu()
+    rng = np.random.default_rng(61)
+    n = 300_000
+    vals = rng.laplace(0.0, 1e-3, n).astype(np.float32)
+    vals[np.abs(vals) < 1e-7] = np.float32(1e-7)
+    w = W.Workload("all_survive", np.arange(n, dtype=np.uint32), vals, n)
+    for tau, fits in ((128, True), (40, True), (129, False), (256, False)):
+        b = min(W.solve_base(w.values, 1.0, tau), 4.0 if tau > 128 else 16.0)
+        p = B.params(b, tau)
+        bufs = B.Buffers(n, p)
+        words = B.workspace_size(n, 1, p.block_keys, max_tau=128) // 8
+        assert B.workspace_size(n, 1, p.block_keys, max_tau=128) % 8 == 0
+        whole = torch.full((words + 512,), 0x5A5A5A5A5A5A5A5A, dtype=torch.int64, device="cuda")
+        bufs.workspace = whole[:words]
+        rc, status, st, _ = G.hip_compress(w.keys, w.values, p, bufs=bufs)
+        if fits:
+            rc_ref, st_ref = ref.compress(w.keys, w.values, ref.params(b, tau))
+            assert rc == B.OK and status == rc_ref == 0 and np.array_equal(st, st_ref)
+            assert int(st[40:48].view("<u8")[0]) > 0.9 * n            # (nearly) every element survived
+        else:
+            assert rc == B.ERR_BUFFER_TOO_SMALL
+        assert bool((whole[words:] == 0x5A5A5A5A5A5A5A5A).all())
+
+
 def test_many_rounds_per_block_and_mixed_block_sizes():
     """Blocks of 2048 and 4096 keys take several rounds of 1024 per wave; dense keys, all survive."""
     n = 50_000
