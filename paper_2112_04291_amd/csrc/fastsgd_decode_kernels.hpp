@@ -710,6 +710,7 @@ k_decode(const uint8_t* __restrict__ streams, u64 stream_bytes, u64 capacity, co
 // The workgroup that owns the last tile goes on to the end of every stream: what is left there has keys
 // beyond the dense vector (FASTSGD_ERR_BUFFER_TOO_SMALL) unless it is corrupt, which is reported first.
 constexpr u32 kTileStreams = 8;
+constexpr u32 kMinAdd = 2048;             // keys of a tile a wave waits for before it adds a part of its round
 constexpr u32 kFrontSpins = 1u << 22;     // polls of the other streams' fronts before a wait is given up (seconds)
 
 // Largest index i in [0, n) with pre(i) <= x, or 0 (the wave probes 64 entries per round trip).  Stays inside
@@ -1016,7 +1017,9 @@ k_accumulate_tiles(const uint8_t* __restrict__ streams, const DecSeg* __restrict
                         dec_fail(ctrl, FASTSGD_ERR_DEVICE, out_status, out_count, 1);
                         lim = hi;
                     }
-                    if (lim > my_front) {
+                    // (a pass over the wave's pairs costs the same for one key as for a thousand: short ranges wait
+                    // until they have grown or the streams before have passed the round's end)
+                    if (lim >= hi || lim >= my_front + kMinAdd) {
                         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
                         // The round's keys in [my_front, lim) of the tile: sixteen reads, sixteen additions, sixteen
                         // writes, without a branch -- a key outside the range takes the lane's own entry behind the
