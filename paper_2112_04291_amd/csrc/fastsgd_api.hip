@@ -293,8 +293,10 @@ static fastsgd_status decompress_impl(const void* d_streams, size_t total_bytes,
     return hipGetLastError() == hipSuccess ? FASTSGD_OK : FASTSGD_ERR_DEVICE;
 }
 
-// Decode-and-aggregate: the streams are checked and planned like a batch, then one launch per stream
-// adds that stream's values into the dense array, so the additions happen stream after stream.
+// Decode-and-aggregate: the streams are checked and planned like a batch; then either one launch per stream
+// adds that stream's values into the dense array (sparse streams), or one launch per group of eight streams
+// takes the dense array through shared memory once (dense streams).  Either way the additions at a key
+// happen stream after stream.
 static fastsgd_status accumulate_impl(const void* d_streams, size_t total_bytes, const u64* d_stream_offsets,
                                       u32 n_streams, float* d_dense, u64 dense_len, u64* d_count, u32* d_status,
                                       void* d_ws, size_t ws_bytes, void* hip_stream) {
