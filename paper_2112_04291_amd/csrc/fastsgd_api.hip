@@ -196,7 +196,8 @@ static fastsgd_status compress_impl(const u32* d_keys, const float* d_values, co
         }
     }
 
-    u32 sum_grid = cus * 4 < kMaxSumGrid ? cus * 4 : kMaxSumGrid;
+    // (three workgroups per compute unit: four fit and run 2 % slower, two 17 %, six to eight with shared accumulators 6 %)
+    u32 sum_grid = cus * 3 < kMaxSumGrid ? cus * 3 : kMaxSumGrid;
     sum_grid = clamp_grid(n_tiles, sum_grid);
     if (single)
         hipLaunchKernelGGL(k_abs_sum<true>, dim3(sum_grid), dim3(kThreads), 0, stream, vbase, dsegs, 1u, n_tiles,
