@@ -248,3 +248,33 @@ def test_batch_of_three_largest_gradients_takes_more_than_4096_chunks():
         assert part.size == alone.size and np.array_equal(part, alone), f"gradient {s}: batch and single call differ"
         rc_ref, k_ref, v_ref = ref.decompress(part)
         assert rc_ref == ref.OK and k_ref.size == d and int(k_ref[0]) == 0 and int(k_ref[-1]) == n - 1
+
+
+def test_config4_aggregation_of_four_workers_in_one_pass():
+    """Decode-and-aggregate at the benchmark's size: four workers' streams of the 124M-element gradient (rotated by
+    a different amount per worker) at 10 % kept, added into a 124M vector -- the one-pass form with runs of twenty
+    tiles per workgroup -- compared bit for bit with the oracle's sums."""
+    torch, B, G = _gpu()
+    from tests.test_gpu_aggregate import hip_accumulate
+    w = W.config4()
+    n = w.values.size
+    base = W.solve_bases(w.values, [0.10])[0]
+    blobs, offs = [], [0]
+    for wkr in range(4):
+        vals = np.roll(w.values, wkr * 15485863)
+        rc, st = ref.compress(w.keys, vals, ref.params(base))
+        assert rc == ref.OK
+        blobs.append(st)
+        offs.append(offs[-1] + st.size)
+        print(f"[fullsize] worker {wkr}: {st.size} bytes", flush=True)
+    blob, offs = np.concatenate(blobs), np.array(offs, np.uint64)
+    assert 10 * blob.size >= n
+    rng = np.random.default_rng(77)
+    dense0 = rng.standard_normal(n, dtype=np.float32) * np.float32(1e-3)
+    want = dense0.copy()
+    rc_ref, cnt_ref = ref.decompress_accumulate(blob, offs, want)
+    assert rc_ref == ref.OK
+    print("[fullsize] oracle sums done", flush=True)
+    rc, status, cnt, got = hip_accumulate(blob, offs, dense0)
+    assert rc == B.OK and status == 0 and cnt == cnt_ref
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
